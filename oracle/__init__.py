@@ -1,0 +1,132 @@
+"""fp64 CPU oracle for the HGRN2 recurrence (paper Section 3.2, Eq. 3).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package imports this; only the tests,
+the smoke check and the CPU-baseline leg of the benchmark do.  The arithmetic lives in
+``hgrn2_oracle.c`` (plain C, one token at a time); this module only compiles it with gcc,
+marshals numpy arrays through ctypes and returns numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hgrn2_oracle.c")
+_LIB = os.path.join(_HERE, "libhgrn2_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle into a shared library next to its source."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-ffp-contract=off", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+_D = ctypes.POINTER(ctypes.c_double)
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_D)
+
+
+def _c(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float64)
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle will use."""
+    return int(_load().hgrn2_oracle_threads())
+
+
+def _check(rc):
+    if rc != 0:
+        raise RuntimeError("hgrn2 oracle returned status %d" % rc)
+
+
+def fwd(q, f, v, h0=None, want_hT=True):
+    """Eq. 3 over a whole sequence.  q, f: [B,H,N,dk]; v: [B,H,N,dv]; h0: [B,H,dk,dv] or None.
+
+    Returns (o [B,H,N,dv], hT [B,H,dk,dv]); the input gate is tied, k = 1 - f.
+    """
+    q, f, v, h0 = _c(q), _c(f), _c(v), _c(h0)
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    assert f.shape == q.shape and v.shape == (B, H, N, dv)
+    assert h0 is None or h0.shape == (B, H, dk, dv)
+    o = np.empty((B, H, N, dv), np.float64)
+    hT = np.empty((B, H, dk, dv), np.float64) if want_hT else None
+    _check(_load().hgrn2_oracle_fwd(B, H, N, dk, dv, _p(q), _p(f), _p(v), _p(h0), _p(o), _p(hT)))
+    return o, hT
+
+
+def fwd_untied(q, k, f, v, h0=None):
+    """The same loop with a free key vector (GLA column of Table 4); for the f == 1 pin."""
+    q, k, f, v, h0 = _c(q), _c(k), _c(f), _c(v), _c(h0)
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == q.shape and f.shape == q.shape
+    o = np.empty((B, H, N, dv), np.float64)
+    hT = np.empty((B, H, dk, dv), np.float64)
+    _check(_load().hgrn2_oracle_fwd_untied(B, H, N, dk, dv, _p(q), _p(k), _p(f), _p(v), _p(h0),
+                                           _p(o), _p(hT)))
+    return o, hT
+
+
+def step(q, f, v, state):
+    """One token of Eq. 3.  q, f: [B,H,dk]; v: [B,H,dv]; state [B,H,dk,dv] is updated IN PLACE
+    (must be a C-contiguous float64 array).  Returns o [B,H,dv]."""
+    assert state.dtype == np.float64 and state.flags["C_CONTIGUOUS"]
+    q, f, v = _c(q), _c(f), _c(v)
+    B, H, dk = q.shape
+    dv = v.shape[-1]
+    assert state.shape == (B, H, dk, dv)
+    o = np.empty((B, H, dv), np.float64)
+    _check(_load().hgrn2_oracle_step(B, H, dk, dv, _p(q), _p(f), _p(v), _p(state), _p(o)))
+    return o
+
+
+def steps(q, f, v, state):
+    """T consecutive single-token steps.  q, f: [T,B,H,dk]; v: [T,B,H,dv]; state updated in place.
+    Returns o [T,B,H,dv]."""
+    assert state.dtype == np.float64 and state.flags["C_CONTIGUOUS"]
+    q, f, v = _c(q), _c(f), _c(v)
+    T, B, H, dk = q.shape
+    dv = v.shape[-1]
+    assert state.shape == (B, H, dk, dv)
+    o = np.empty((T, B, H, dv), np.float64)
+    _check(_load().hgrn2_oracle_steps(T, B, H, dk, dv, _p(q), _p(f), _p(v), _p(state), _p(o)))
+    return o
+
+
+def bwd(q, f, v, dO, h0=None, dhT=None, want_dh0=True):
+    """Reverse-mode gradients of L = sum(o * dO) + sum(hT * dhT).
+
+    Returns (dq, df, dv, dh0); df already contains the tied path k = 1 - f.
+    """
+    q, f, v, dO, h0, dhT = _c(q), _c(f), _c(v), _c(dO), _c(h0), _c(dhT)
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    assert dO.shape == v.shape
+    dq = np.empty_like(q)
+    df = np.empty_like(f)
+    dvv = np.empty_like(v)
+    dh0 = np.empty((B, H, dk, dv), np.float64) if want_dh0 else None
+    _check(_load().hgrn2_oracle_bwd(B, H, N, dk, dv, _p(q), _p(f), _p(v), _p(h0), _p(dO), _p(dhT),
+                                    _p(dq), _p(df), _p(dvv), _p(dh0)))
+    return dq, df, dvv, dh0

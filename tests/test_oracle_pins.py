@@ -1,0 +1,354 @@
+"""Pins for the fp64 CPU oracle: every check compares it with something OTHER than its own loop.
+
+P1  brute-force quadratic ("attention") form with the per-channel decay mask
+P2  f == 1: tied gate -> state frozen at h0; untied key -> cumulative linear attention
+P3  f == 0: o_t = (sum_a q_t[a]) v_t
+P4  constant gate closed form 1 - c^t
+P5  split / hand-off (hT -> h0), N x step == fwd, and the backward hand-off (dh0 -> dhT)
+P6  convexity invariant of the tied gate (key and forget gate sum to one)
+P7  chunkwise regrouping (the algebra the GPU kernels use), any chunk length
+P8  linearity in v (+h0) and in q
+P9  fp64 central finite differences, torch autograd, and the gate-gradient suffix identity
+A two-token example in exact rational arithmetic closes the list (the paper prints no numeric
+values of Eq. 3, so tests/golden/ holds no fixture for it).
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+RNG = np.random.default_rng(12345)
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def rand_inputs(B, H, N, dk, dv, lo=0.05, hi=1.0, rng=RNG, h0=True):
+    q = rng.standard_normal((B, H, N, dk))
+    f = rng.uniform(lo, hi, size=(B, H, N, dk))
+    v = rng.standard_normal((B, H, N, dv))
+    h = 0.3 * rng.standard_normal((B, H, dk, dv)) if h0 else None
+    return q, f, v, h
+
+
+# ----------------------------------------------------------------------------- P1
+def quadratic_form(q, f, v, h0):
+    """O = A V + (Q * prod_{s<=i} f_s) h0, A_ij = sum_a q_i[a] k_j[a] prod_{s=j+1..i} f_s[a], j<=i.
+
+    Written with explicit products over the gate (no recurrence, no logs): O(N^2 dk)."""
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    o = np.zeros((B, H, N, dv))
+    k = 1.0 - f
+    for b in range(B):
+        for h in range(H):
+            for i in range(N):
+                acc = np.zeros(dv)
+                for j in range(i + 1):
+                    decay = np.prod(f[b, h, j + 1:i + 1, :], axis=0)        # empty product = 1
+                    acc += np.sum(q[b, h, i] * k[b, h, j] * decay) * v[b, h, j]
+                if h0 is not None:
+                    acc += (q[b, h, i] * np.prod(f[b, h, :i + 1, :], axis=0)) @ h0[b, h]
+                o[b, h, i] = acc
+    return o
+
+
+@pytest.mark.parametrize("N,dk,dv,use_h0", [(1, 3, 2, True), (7, 4, 5, True), (48, 8, 6, False),
+                                            (96, 16, 16, True)])
+def test_p1_bruteforce_quadratic_form(N, dk, dv, use_h0):
+    q, f, v, h0 = rand_inputs(2, 2, N, dk, dv, h0=use_h0)
+    o, hT = oracle.fwd(q, f, v, h0)
+    ref = quadratic_form(q, f, v, h0)
+    assert np.max(np.abs(o - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+    # final state from the unrolled sum: S_N = sum_j Diag(prod_{s>j} f) k_j^T v_j + Diag(prod f) h0
+    k = 1.0 - f
+    S = np.zeros_like(hT)
+    for j in range(N):
+        decay = np.prod(f[:, :, j + 1:, :], axis=2)
+        S += (decay * k[:, :, j])[..., None] * v[:, :, j][..., None, :]
+    if h0 is not None:
+        S += np.prod(f, axis=2)[..., None] * h0
+    assert np.max(np.abs(hT - S)) <= 1e-12
+
+
+# ----------------------------------------------------------------------------- P2
+def test_p2_f_one_tied_freezes_state():
+    q, f, v, h0 = rand_inputs(2, 3, 20, 5, 4)
+    f = np.ones_like(f)
+    o, hT = oracle.fwd(q, f, v, h0)
+    assert np.array_equal(hT, h0)
+    assert np.allclose(o, np.einsum("bhna,bhac->bhnc", q, h0), rtol=0, atol=1e-13)
+    o0, hT0 = oracle.fwd(q, f, v, None)
+    assert np.all(o0 == 0) and np.all(hT0 == 0)
+
+
+def test_p2_f_one_untied_is_cumulative_linear_attention():
+    q, f, v, _ = rand_inputs(2, 2, 33, 6, 7, h0=False)
+    k = RNG.standard_normal(q.shape)
+    f = np.ones_like(f)
+    o, hT = oracle.fwd_untied(q, k, f, v)
+    A = np.tril(np.einsum("bhia,bhja->bhij", q, k))          # causal mask, diagonal kept
+    assert np.allclose(o, A @ v, rtol=0, atol=1e-12)
+    assert np.allclose(hT, np.einsum("bhna,bhnc->bhac", k, v), rtol=0, atol=1e-12)
+
+
+def test_untied_with_tied_key_equals_tied():
+    q, f, v, h0 = rand_inputs(1, 2, 17, 4, 3)
+    o1, h1 = oracle.fwd(q, f, v, h0)
+    o2, h2 = oracle.fwd_untied(q, 1.0 - f, f, v, h0)
+    assert np.array_equal(o1, o2) and np.array_equal(h1, h2)
+
+
+# ----------------------------------------------------------------------------- P3
+def test_p3_f_zero():
+    q, f, v, h0 = rand_inputs(2, 2, 11, 5, 6)
+    f = np.zeros_like(f)
+    o, hT = oracle.fwd(q, f, v, h0)
+    assert np.allclose(o, q.sum(-1, keepdims=True) * v, rtol=0, atol=1e-13)
+    assert np.allclose(hT, np.broadcast_to(v[:, :, -1][:, :, None, :], hT.shape))
+
+
+# ----------------------------------------------------------------------------- P4
+@pytest.mark.parametrize("c", [0.0, 0.3, 0.9, 0.999, 1.0])
+def test_p4_constant_gate_closed_form(c):
+    B, H, N, dk, dv = 1, 2, 200, 6, 5
+    q = np.ones((B, H, N, dk))
+    v = np.ones((B, H, N, dv))
+    f = np.full((B, H, N, dk), c)
+    o, hT = oracle.fwd(q, f, v, None)
+    t = np.arange(1, N + 1, dtype=np.float64)
+    want = dk * (1.0 - c ** t)
+    assert np.allclose(o, want[None, None, :, None], rtol=1e-12, atol=1e-13)
+    assert np.allclose(hT, 1.0 - c ** N, rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- P5
+def test_p5_split_handoff_forward_and_steps():
+    q, f, v, h0 = rand_inputs(2, 2, 70, 6, 5)
+    o, hT = oracle.fwd(q, f, v, h0)
+    m = 29
+    o1, h1 = oracle.fwd(q[:, :, :m], f[:, :, :m], v[:, :, :m], h0)
+    o2, h2 = oracle.fwd(q[:, :, m:], f[:, :, m:], v[:, :, m:], h1)
+    assert np.array_equal(np.concatenate([o1, o2], 2), o) and np.array_equal(h2, hT)
+    st = h0.copy()
+    for t in range(q.shape[2]):
+        ot = oracle.step(q[:, :, t], f[:, :, t], v[:, :, t], st)
+        assert np.array_equal(ot, o[:, :, t])
+    assert np.array_equal(st, hT)
+    st2 = h0.copy()
+    tok = lambda x: np.ascontiguousarray(np.moveaxis(x, 2, 0))
+    o_s = oracle.steps(tok(q), tok(f), tok(v), st2)
+    assert np.array_equal(np.moveaxis(o_s, 0, 2), o) and np.array_equal(st2, hT)
+
+
+def test_p5_split_handoff_backward():
+    q, f, v, h0 = rand_inputs(1, 2, 50, 5, 4)
+    dO = RNG.standard_normal(v.shape)
+    dhT = RNG.standard_normal(h0.shape)
+    dq, df, dv, dh0 = oracle.bwd(q, f, v, dO, h0, dhT)
+    m = 21
+    _, h1 = oracle.fwd(q[:, :, :m], f[:, :, :m], v[:, :, :m], h0)
+    dq2, df2, dv2, dh1 = oracle.bwd(q[:, :, m:], f[:, :, m:], v[:, :, m:], dO[:, :, m:], h1, dhT)
+    dq1, df1, dv1, dh0b = oracle.bwd(q[:, :, :m], f[:, :, :m], v[:, :, :m], dO[:, :, :m], h0, dh1)
+    for whole, a, b in ((dq, dq1, dq2), (df, df1, df2), (dv, dv1, dv2)):
+        assert np.allclose(whole, np.concatenate([a, b], 2), rtol=1e-12, atol=1e-12)
+    assert np.allclose(dh0, dh0b, rtol=1e-12, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- P6
+def test_p6_convexity_invariant():
+    B, H, N, dk, dv = 2, 2, 40, 5, 4
+    q, f, v, _ = rand_inputs(B, H, N, dk, dv, lo=0.0, hi=1.0, h0=False)
+    vbar = RNG.standard_normal((B, H, 1, dv))
+    v_const = np.broadcast_to(vbar, v.shape).copy()
+    h0 = np.broadcast_to(vbar, (B, H, dk, dv)).copy()
+    _, hT = oracle.fwd(q, f, v_const, h0)
+    assert np.allclose(hT, h0, rtol=0, atol=1e-13)        # convex combination of equal rows
+    h0r = RNG.standard_normal((B, H, dk, dv))
+    st = h0r.copy()
+    lo = h0r.copy()                                  # running per-entry bounds
+    hi = h0r.copy()
+    for t in range(N):
+        oracle.step(q[:, :, t], f[:, :, t], v[:, :, t], st)
+        lo = np.minimum(lo, v[:, :, t][:, :, None, :])
+        hi = np.maximum(hi, v[:, :, t][:, :, None, :])
+        assert np.all(st >= lo - 1e-13) and np.all(st <= hi + 1e-13)
+
+
+# ----------------------------------------------------------------------------- P7
+def chunkwise_fwd(q, f, v, h0, C):
+    """fp64 regrouping into chunks of C: O = tril(Q~ K~^T) V + Q~ S_n, S_{n+1} = Diag(g) S_n + K^^T V,
+    with chunk-local cumulative gate products (no logs, so f = 0 inside a chunk is avoided by
+    the caller)."""
+    B, H, N, dk = q.shape
+    dv = v.shape[-1]
+    S = np.zeros((B, H, dk, dv)) if h0 is None else h0.copy()
+    o = np.zeros((B, H, N, dv))
+    for s in range(0, N, C):
+        e = min(N, s + C)
+        Q, F, V = q[:, :, s:e], f[:, :, s:e], v[:, :, s:e]
+        K = 1.0 - F
+        G = np.cumprod(F, axis=2)                     # Gamma_r, inclusive
+        g = G[:, :, -1]                               # whole-chunk decay
+        Qs, Ks, Kh = Q * G, K / G, K * (g[:, :, None] / G)
+        P = np.tril(np.einsum("bhia,bhja->bhij", Qs, Ks))
+        o[:, :, s:e] = P @ V + np.einsum("bhia,bhac->bhic", Qs, S)
+        S = g[..., None] * S + np.einsum("bhja,bhjc->bhac", Kh, V)
+    return o, S
+
+
+@pytest.mark.parametrize("C", [1, 16, 64, 100])
+def test_p7_chunk_invariance(C):
+    q, f, v, h0 = rand_inputs(1, 2, 100, 8, 6, lo=0.4)
+    o, hT = oracle.fwd(q, f, v, h0)
+    oc, hc = chunkwise_fwd(q, f, v, h0, C)
+    assert np.allclose(o, oc, rtol=1e-9, atol=1e-9) and np.allclose(hT, hc, rtol=1e-9, atol=1e-9)
+
+
+# ----------------------------------------------------------------------------- P8
+def test_p8_linearity():
+    q, f, v, h0 = rand_inputs(1, 2, 25, 5, 4)
+    q2, _, v2, h02 = rand_inputs(1, 2, 25, 5, 4)
+    a, b = 0.7, -1.9
+    o1, h1 = oracle.fwd(q, f, v, h0)
+    o2, h2 = oracle.fwd(q, f, v2, h02)
+    o12, h12 = oracle.fwd(q, f, a * v + b * v2, a * h0 + b * h02)
+    assert np.allclose(o12, a * o1 + b * o2, atol=1e-12) and np.allclose(h12, a * h1 + b * h2, atol=1e-12)
+    o3, _ = oracle.fwd(q2, f, v, h0)
+    o13, _ = oracle.fwd(a * q + b * q2, f, v, h0)
+    assert np.allclose(o13, a * o1 + b * o3, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- P9
+def loss(q, f, v, h0, dO, dhT):
+    o, hT = oracle.fwd(q, f, v, h0)
+    return float(np.sum(o * dO) + np.sum(hT * dhT))
+
+
+@pytest.mark.parametrize("N", [1, 5, 70])      # 70 crosses the oracle's checkpoint interval of 64
+def test_p9_finite_differences(N):
+    rng = np.random.default_rng(99 + N)
+    B, H, dk, dv = 1, 2, 4, 3
+    q, f, v, h0 = rand_inputs(B, H, N, dk, dv, lo=0.2, hi=0.95, rng=rng)
+    dO = rng.standard_normal(v.shape)
+    dhT = rng.standard_normal(h0.shape)
+    grads = oracle.bwd(q, f, v, dO, h0, dhT)
+    eps = 1e-6
+    args = [q, f, v, h0]
+    for which, g in zip(range(4), grads):
+        x = args[which]
+        flat = x.reshape(-1)
+        idx = rng.choice(flat.size, size=min(flat.size, 60), replace=False)
+        for i in idx:
+            old = flat[i]
+            flat[i] = old + eps
+            lp = loss(q, f, v, h0, dO, dhT)
+            flat[i] = old - eps
+            lm = loss(q, f, v, h0, dO, dhT)
+            flat[i] = old
+            fd = (lp - lm) / (2 * eps)
+            assert abs(fd - g.reshape(-1)[i]) <= 1e-7 * max(1.0, abs(fd)), (which, i, fd, g.reshape(-1)[i])
+
+
+def test_p9_torch_autograd():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(7)
+    B, H, N, dk, dv = 2, 2, 37, 5, 6
+    q, f, v, h0 = rand_inputs(B, H, N, dk, dv, lo=0.1, hi=1.0, rng=rng)
+    dO = rng.standard_normal(v.shape)
+    dhT = rng.standard_normal(h0.shape)
+    tq, tf, tv, th = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, f, v, h0))
+    S = th
+    outs = []
+    for t in range(N):
+        S = tf[:, :, t, :, None] * S + (1 - tf[:, :, t, :, None]) * tv[:, :, t, None, :]
+        outs.append(torch.einsum("bha,bhac->bhc", tq[:, :, t], S))
+    L = (torch.stack(outs, 2) * torch.tensor(dO)).sum() + (S * torch.tensor(dhT)).sum()
+    L.backward()
+    dq, df, dv_, dh0 = oracle.bwd(q, f, v, dO, h0, dhT)
+    for mine, ref in ((dq, tq.grad), (df, tf.grad), (dv_, tv.grad), (dh0, th.grad)):
+        assert np.allclose(mine, ref.numpy(), rtol=1e-11, atol=1e-11)
+
+
+def test_p9_gate_gradient_suffix_identity():
+    """f * (decay-path gradient) at step s equals sum_{t>=s}(q_t dq_t - k_t dk_t) + rowsum(dhT * hT);
+    dk is recovered from the untied split: df = dd - dk and dk_t = sum_b dS_t[a,b] v_t[b]."""
+    rng = np.random.default_rng(3)
+    B, H, N, dk, dv = 1, 2, 45, 4, 5
+    q, f, v, h0 = rand_inputs(B, H, N, dk, dv, lo=0.2, rng=rng)
+    dO = rng.standard_normal(v.shape)
+    dhT = rng.standard_normal(h0.shape)
+    dq, df, dv_, _ = oracle.bwd(q, f, v, dO, h0, dhT)
+    _, hT = oracle.fwd(q, f, v, h0)
+    # dk via finite differences of the untied loop (independent of oracle.bwd)
+    k = 1.0 - f
+    eps = 1e-6
+    dk_fd = np.zeros_like(k)
+    for idx in np.ndindex(*k.shape):
+        old = k[idx]
+        k[idx] = old + eps
+        op, hp = oracle.fwd_untied(q, k, f, v, h0)
+        k[idx] = old - eps
+        om, hm = oracle.fwd_untied(q, k, f, v, h0)
+        k[idx] = old
+        dk_fd[idx] = (np.sum((op - om) * dO) + np.sum((hp - hm) * dhT)) / (2 * eps)
+    dd = df + dk_fd                                   # decay-path gradient
+    terms = q * dq - (1.0 - f) * dk_fd
+    suffix = np.flip(np.cumsum(np.flip(terms, 2), 2), 2) + np.sum(dhT * hT, -1)[:, :, None, :]
+    assert np.allclose(f * dd, suffix, rtol=1e-6, atol=1e-6)
+
+
+# ----------------------------------------------------------------------------- two-token closed form
+def test_two_token_closed_form_exact():
+    """N = 2, dk = 2, dv = 1 written out term by term in exact rational arithmetic (all inputs
+    dyadic, so the fp64 oracle must reproduce every value exactly)."""
+    from fractions import Fraction as Fr
+    q1, q2 = (Fr(1), Fr(2)), (Fr(-1), Fr(1))
+    f1, f2 = (Fr(1, 2), Fr(1, 4)), (Fr(3, 4), Fr(1, 2))
+    v1, v2 = Fr(2), Fr(-4)
+    h0 = (Fr(1), Fr(-2))
+    g1, g2 = Fr(1), Fr(3)                                    # upstream gradients of o_1, o_2
+    S1 = tuple(f1[a] * h0[a] + (1 - f1[a]) * v1 for a in range(2))
+    S2 = tuple(f2[a] * S1[a] + (1 - f2[a]) * v2 for a in range(2))
+    o1 = q1[0] * S1[0] + q1[1] * S1[1]
+    o2 = q2[0] * S2[0] + q2[1] * S2[1]
+    # L = g1 o1 + g2 o2, differentiated by hand
+    dS2 = tuple(q2[a] * g2 for a in range(2))
+    dS1 = tuple(q1[a] * g1 + f2[a] * dS2[a] for a in range(2))
+    want = {
+        "o": [o1, o2], "hT": list(S2),
+        "dq": [g1 * S1[0], g1 * S1[1], g2 * S2[0], g2 * S2[1]],
+        "df": [dS1[0] * (h0[0] - v1), dS1[1] * (h0[1] - v1), dS2[0] * (S1[0] - v2), dS2[1] * (S1[1] - v2)],
+        "dv": [sum((1 - f1[a]) * dS1[a] for a in range(2)), sum((1 - f2[a]) * dS2[a] for a in range(2))],
+        "dh0": [f1[0] * dS1[0], f1[1] * dS1[1]],
+    }
+    assert (o1, o2) == (Fr(7, 2), Fr(-13, 8)) and want["dv"] == [Fr(2), Fr(3, 4)]   # by hand
+    arr = lambda xs, shape: np.array([float(x) for x in xs], dtype=np.float64).reshape(shape)
+    q = arr(q1 + q2, (1, 1, 2, 2)); f = arr(f1 + f2, (1, 1, 2, 2)); v = arr([v1, v2], (1, 1, 2, 1))
+    h = arr(h0, (1, 1, 2, 1)); dO = arr([g1, g2], (1, 1, 2, 1))
+    o, hT = oracle.fwd(q, f, v, h)
+    dq, df, dv, dh0 = oracle.bwd(q, f, v, dO, h, None)
+    assert np.array_equal(o.reshape(-1), arr(want["o"], -1))
+    assert np.array_equal(hT.reshape(-1), arr(want["hT"], -1))
+    assert np.array_equal(dq.reshape(-1), arr(want["dq"], -1))
+    assert np.array_equal(df.reshape(-1), arr(want["df"], -1))
+    assert np.array_equal(dv.reshape(-1), arr(want["dv"], -1))
+    assert np.array_equal(dh0.reshape(-1), arr(want["dh0"], -1))
+
+
+# ----------------------------------------------------------------------------- planted mistakes
+def test_pins_detect_planted_mistakes():
+    """A dropped tie, a stale-state read-out or a transposed state would each break a pin."""
+    q, f, v, h0 = rand_inputs(1, 1, 12, 4, 4)
+    o, _ = oracle.fwd(q, f, v, h0)
+    ref = quadratic_form(q, f, v, h0)
+    # read-out from S_{t-1} instead of S_t
+    stale = np.zeros_like(o)
+    S = h0[0, 0].copy()
+    for t in range(12):
+        stale[0, 0, t] = q[0, 0, t] @ S
+        S = f[0, 0, t][:, None] * S + (1 - f[0, 0, t])[:, None] * v[0, 0, t][None, :]
+    assert np.max(np.abs(stale - ref)) > 1e-3 and np.max(np.abs(o - ref)) < 1e-12
+    # untied key k = 1 would violate the convexity pin
+    o_bad, h_bad = oracle.fwd_untied(q, np.ones_like(q), f, np.ones_like(v), np.ones_like(h0))
+    assert np.max(np.abs(h_bad - 1.0)) > 1e-3
