@@ -1,0 +1,116 @@
+/*
+ * hgrn2.h -- C ABI of the MI355X (gfx950) HGRN2 recurrence library.
+ *
+ * The operation is the multi-head HGRN2 recurrence of the paper (Section 3.2, Eq. 3, and the
+ * "Multihead Variant" paragraph), in the query/key/value naming of its Table 4:
+ *
+ *     S_t = Diag(f_t) S_{t-1} + k_t^T v_t ,   k_t = 1 - f_t ,        S_t in R^{dk x dv}
+ *     o_t = q_t S_t                                                   (reads the UPDATED state)
+ *
+ * where q is the paper's output gate, f the (lower-bounded) forget gate, v the input vector and
+ * the input gate (key) is tied to the forget gate.  S is the transpose of the paper's h.  No
+ * scaling of q, no output gate and no normalisation are applied (Table 4 omits GLA's output gate).
+ * Every (batch, head) pair is an independent recurrence.
+ *
+ * Conventions common to all entry points
+ *   - All tensor pointers are DEVICE pointers to dense row-major arrays, last index fastest:
+ *         q, f, grad_q, grad_f : [B][H][N][dk]
+ *         v, o, grad_o, grad_v : [B][H][N][dv]
+ *         h0, hT, grad_h0, grad_hT, state : [B][H][dk][dv], always fp32
+ *     q, v, o and all grad_* sequence tensors have element type `io_dtype`; f has `gate_dtype`.
+ *   - The caller owns every buffer, including the workspace.  The library never allocates,
+ *     frees or retains device memory and keeps no state between calls.
+ *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL = the
+ *     default stream).  No entry point synchronises with the host.
+ *   - Return value: an hgrn2_status.  Argument errors are detected on the host before anything
+ *     is launched; on error nothing has been enqueued.  Nothing throws or aborts across the ABI.
+ *   - Gate domain: f in [0, 1].  Results are exact (up to rounding) while the product of the
+ *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
+ *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
+ *     intra-chunk terms degrade smoothly (they stay finite) instead of failing.
+ *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}; any B, H, N >= 0.
+ *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
+ *     io_dtype F32 is supported by hgrn2_fwd and hgrn2_step (hgrn2_bwd: BF16 only).
+ */
+#ifndef HGRN2_H
+#define HGRN2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HGRN2_OK = 0,
+    HGRN2_ERR_NULL = 1,        /* a required pointer is NULL */
+    HGRN2_ERR_SHAPE = 2,       /* negative or zero size, or a size product that overflows */
+    HGRN2_ERR_UNSUPPORTED = 3, /* well-formed but outside the supported set listed above */
+    HGRN2_ERR_WORKSPACE = 4,   /* workspace missing, too small or not 256-byte aligned */
+    HGRN2_ERR_HIP = 5          /* a HIP call or kernel launch reported an error */
+} hgrn2_status;
+
+typedef enum { HGRN2_F32 = 0, HGRN2_BF16 = 1 } hgrn2_dtype;
+
+typedef struct {
+    int32_t B, H, N, dk, dv;
+    int32_t chunk;      /* chunk length of the chunkwise algorithm; 0 selects the default (64) */
+    int32_t io_dtype;   /* hgrn2_dtype of q, v, o and of every grad_* sequence tensor */
+    int32_t gate_dtype; /* hgrn2_dtype of f (grad_f follows io_dtype) */
+} hgrn2_shape;
+
+/* Bytes of device workspace hgrn2_fwd / hgrn2_bwd need for this shape (0 if the shape is
+ * invalid or unsupported; the corresponding call then reports the precise error). */
+size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape);
+size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape);
+
+/*
+ * Chunkwise-parallel forward pass of Eq. 3 over whole sequences (the "hardware-efficient
+ * training" form the paper refers to in Section 3.2: an exact regrouping of the recurrence
+ * into per-chunk matrix products plus a chunk-to-chunk state recurrence).
+ *   q, f, v   in   device, read-only
+ *   h0        in   device fp32 [B][H][dk][dv], or NULL for a zero initial state
+ *   o         out  device [B][H][N][dv], io_dtype
+ *   hT        out  device fp32 [B][H][dk][dv] final state S_N, or NULL if not wanted
+ *   workspace      device scratch of at least hgrn2_fwd_workspace_bytes(shape) bytes, 256-byte
+ *                  aligned; contents on entry are ignored, contents on return are unspecified
+ */
+int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+              const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+              void* hip_stream);
+
+/*
+ * Backward pass of hgrn2_fwd: gradients of L = sum(o * grad_o) + sum(hT * grad_hT).
+ * Stateless: everything needed is recomputed from q, f, v, h0.  The paper gives no backward
+ * algorithm; this is reverse-mode differentiation of Eq. 3 in chunkwise form.
+ *   grad_o    in   device [B][H][N][dv], io_dtype
+ *   grad_hT   in   device fp32 [B][H][dk][dv], or NULL for zero
+ *   grad_q, grad_f, grad_v   out  device, io_dtype.  grad_f is the gradient w.r.t. the gate f
+ *             INCLUDING the tied path k = 1 - f, so callers never see k or its gradient.
+ *   grad_h0   out  device fp32 [B][H][dk][dv], or NULL if not wanted
+ *   workspace as for hgrn2_fwd, sized by hgrn2_bwd_workspace_bytes(shape)
+ */
+int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+              const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+              void* grad_f, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+              void* hip_stream);
+
+/*
+ * Single-token recurrent (decode) step: one application of Eq. 3 per (batch, head).
+ *   q_t, f_t  in   device [B][H][dk]        v_t  in   device [B][H][dv]
+ *   state     in/out device fp32 [B][H][dk][dv], updated IN PLACE to S_t
+ *   o_t       out  device [B][H][dv], io_dtype; computed from the updated state
+ * Needs no workspace.
+ */
+int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+               const void* q_t, const void* f_t, const void* v_t, float* state, void* o_t,
+               void* hip_stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* hgrn2_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HGRN2_H */

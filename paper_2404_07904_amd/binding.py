@@ -1,0 +1,153 @@
+"""Thin ctypes binding of libhgrn2.so: same entry-point names as include/hgrn2.h, argument
+marshalling only.  PyTorch is used for device memory and the current stream, nothing else; every
+step of the computation runs in the HIP kernels.  There is no fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhgrn2.so")
+
+HGRN2_F32, HGRN2_BF16 = 0, 1
+STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
+          4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
+EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
+           "hgrn2_step", "hgrn2_status_string"]
+
+
+class hgrn2_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("io_dtype", ctypes.c_int32), ("gate_dtype", ctypes.c_int32)]
+
+
+class Hgrn2Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (%s)" % (where, STATUS.get(status, status), status_string(status)))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the native library (built in-tree by paper_2404_07904_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("native library %s is missing: run `python -m paper_2404_07904_amd.build`"
+                               % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+        sp = ctypes.POINTER(hgrn2_shape)
+        L.hgrn2_fwd_workspace_bytes.restype = sz
+        L.hgrn2_fwd_workspace_bytes.argtypes = [sp]
+        L.hgrn2_bwd_workspace_bytes.restype = sz
+        L.hgrn2_bwd_workspace_bytes.argtypes = [sp]
+        L.hgrn2_fwd.restype = ctypes.c_int
+        L.hgrn2_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_bwd.restype = ctypes.c_int
+        L.hgrn2_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_step.restype = ctypes.c_int
+        L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_status_string.restype = ctypes.c_char_p
+        L.hgrn2_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().hgrn2_status_string(int(status)).decode()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return HGRN2_BF16
+    if t.dtype == torch.float32:
+        return HGRN2_F32
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous device tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_shape(q, v, f, chunk=0) -> hgrn2_shape:
+    B, H, N, dk = q.shape
+    return hgrn2_shape(B, H, N, dk, v.shape[-1], chunk, _dt(q), _dt(f))
+
+
+def hgrn2_fwd_workspace_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_fwd_workspace_bytes(ctypes.byref(shape)))
+
+
+def hgrn2_bwd_workspace_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_bwd_workspace_bytes(ctypes.byref(shape)))
+
+
+def _workspace(nbytes, device, workspace):
+    if workspace is not None:
+        return workspace
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, workspace=None):
+    """o, hT = chunkwise forward of the recurrence.  q, f: [B,H,N,dk]; v: [B,H,N,dv]; h0 fp32."""
+    shape = make_shape(q, v, f, chunk)
+    assert v.dtype == q.dtype and f.shape == q.shape
+    if o is None:
+        o = torch.empty_like(v)
+    if hT is None and want_hT:
+        hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    nbytes = hgrn2_fwd_workspace_bytes(shape)
+    ws = _workspace(nbytes, q.device, workspace)
+    rc = lib().hgrn2_fwd(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(o), _ptr(hT),
+                         _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_fwd")
+    return o, hT
+
+
+def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chunk=0, workspace=None,
+              grad_q=None, grad_f=None, grad_v=None, grad_h0=None):
+    """grad_q, grad_f, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
+    shape = make_shape(q, v, f, chunk)
+    grad_q = torch.empty_like(q) if grad_q is None else grad_q
+    grad_f = torch.empty_like(q) if grad_f is None else grad_f
+    grad_v = torch.empty_like(v) if grad_v is None else grad_v
+    if grad_h0 is None and want_grad_h0:
+        grad_h0 = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    nbytes = hgrn2_bwd_workspace_bytes(shape)
+    ws = _workspace(nbytes, q.device, workspace)
+    rc = lib().hgrn2_bwd(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(grad_o),
+                         _ptr(grad_hT), _ptr(grad_q), _ptr(grad_f), _ptr(grad_v), _ptr(grad_h0),
+                         _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd")
+    return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgrn2_step(q_t, f_t, v_t, state, o_t=None):
+    """One decode step; `state` [B,H,dk,dv] fp32 is updated in place.  Returns o_t [B,H,dv]."""
+    B, H, dk = q_t.shape
+    dv = v_t.shape[-1]
+    assert state.dtype == torch.float32 and tuple(state.shape) == (B, H, dk, dv)
+    if o_t is None:
+        o_t = torch.empty_like(v_t)
+    rc = lib().hgrn2_step(B, H, dk, dv, _dt(q_t), _dt(f_t), _ptr(q_t), _ptr(f_t), _ptr(v_t), _ptr(state),
+                          _ptr(o_t), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_step")
+    return o_t

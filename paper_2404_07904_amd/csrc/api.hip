@@ -1,0 +1,127 @@
+// C-ABI layer of the HGRN2 library: argument validation on the host, workspace carving and the
+// sequence of kernel launches.  See include/hgrn2.h for the contract of every entry point.
+#include "../../include/hgrn2.h"
+#include "kernels.hpp"
+
+#include <limits.h>
+
+using namespace hgrn2;
+
+namespace {
+
+bool dtype_ok(int32_t t) { return t == HGRN2_F32 || t == HGRN2_BF16; }
+bool dim_ok(int32_t d) { return d == 64 || d == 128; }
+
+// Validates a shape; on success fills `d`.
+int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
+{
+    if (!s) return HGRN2_ERR_NULL;
+    if (s->B < 0 || s->H < 0 || s->N < 0 || s->dk <= 0 || s->dv <= 0 || s->chunk < 0) return HGRN2_ERR_SHAPE;
+    if (!dtype_ok(s->io_dtype) || !dtype_ok(s->gate_dtype)) return HGRN2_ERR_SHAPE;
+    const long long bh = (long long)s->B * s->H;
+    if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
+    const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
+    if (bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk
+    if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
+    if (s->chunk != 0 && s->chunk != kChunk) return HGRN2_ERR_UNSUPPORTED;
+    if (backward && s->io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
+    d->BH = (int)bh;
+    d->N = s->N;
+    d->NC = (int)nc;
+    d->dk = s->dk;
+    d->dv = s->dv;
+    d->io_bf16 = s->io_dtype == HGRN2_BF16;
+    d->gate_bf16 = s->gate_dtype == HGRN2_BF16;
+    return HGRN2_OK;
+}
+
+size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}   // namespace
+
+extern "C" {
+
+size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape(shape, false, &d) != HGRN2_OK) return 0;
+    return round256(state_ws_bytes(d));
+}
+
+size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    return 2 * round256(state_ws_bytes(d));
+}
+
+int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+              void* o, float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, false, &d);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)d.BH * d.N > 0;
+    if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (d.BH == 0) return HGRN2_OK;
+    if (!has_tokens && !hT) return HGRN2_OK;
+    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, workspace, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+              const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v,
+              float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)d.BH * d.N > 0;
+    if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
+    const size_t one = round256(state_ws_bytes(d));
+    if (one > 0 && (!workspace || workspace_bytes < 2 * one || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (d.BH == 0) return HGRN2_OK;
+    if (!has_tokens && !grad_h0) return HGRN2_OK;
+    void* ws_s = workspace;
+    void* ws_ds = static_cast<char*>(workspace) + one;
+    if (has_tokens && launch_sweep(d, kSweepStateBwd, q, f, v, h0, nullptr, ws_s, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_sweep(d, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (has_tokens &&
+        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+               const void* q_t, const void* f_t, const void* v_t, float* state, void* o_t, void* hip_stream)
+{
+    if (B < 0 || H < 0 || dk <= 0 || dv <= 0) return HGRN2_ERR_SHAPE;
+    if (!dtype_ok(io_dtype) || !dtype_ok(gate_dtype)) return HGRN2_ERR_SHAPE;
+    const long long bh = (long long)B * H;
+    if (bh > INT_MAX / 2) return HGRN2_ERR_SHAPE;
+    if (!dim_ok(dk) || !dim_ok(dv)) return HGRN2_ERR_UNSUPPORTED;
+    if (bh > 0 && (!q_t || !f_t || !v_t || !state || !o_t)) return HGRN2_ERR_NULL;
+    if (launch_step((int)bh, dk, dv, io_dtype == HGRN2_BF16, gate_dtype == HGRN2_BF16, q_t, f_t, v_t, state, o_t,
+                    static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+const char* hgrn2_status_string(int status)
+{
+    switch (status) {
+    case HGRN2_OK: return "ok";
+    case HGRN2_ERR_NULL: return "a required pointer is NULL";
+    case HGRN2_ERR_SHAPE: return "invalid shape or dtype";
+    case HGRN2_ERR_UNSUPPORTED: return "shape, chunk or dtype outside the supported set";
+    case HGRN2_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case HGRN2_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+    }
+}
+
+}   // extern "C"

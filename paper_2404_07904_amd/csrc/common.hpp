@@ -1,0 +1,236 @@
+// Shared device-side building blocks for the gfx950 HGRN2 kernels.
+//
+// Notation (paper Section 3.2, Eq. 3 and Table 4): q = output gate (query), f = forget gate,
+// k = 1 - f = input gate (key), v = input vector (value), S = dk x dv state.  Within one chunk
+// of C tokens, G_r = prod_{s<=r} f_s is the cumulative gate product from the chunk start and
+// g = G_C the whole-chunk decay.
+//
+// Thread layout used for all element-wise ("prep") work on a [C x D] tile: a workgroup has four
+// wave64s; wave w owns the RW = C/4 consecutive rows (tokens) RW*w .. RW*w+RW-1 and lane l owns the
+// channel pair (2l, 2l+1).  A global row is then one fully coalesced wave-wide load, the
+// cumulative products along time run serially in registers, and because a thread holds RW
+// consecutive tokens of a channel it can also write the tile TRANSPOSED (token-contiguous) to
+// LDS with 16-byte vectors, which is the layout an MFMA operand needs when the contraction runs
+// over time.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hgrn2 {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr float kTinyProduct = 7.888609052210118e-31f;   // 2^-100: floor under a reciprocal
+
+// LDS row padding (in elements) that keeps rows 16-byte aligned and staggers banks.
+template <typename T> __host__ __device__ constexpr int pad_elems() { return 16 / (int)sizeof(T); }
+
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// ---- global memory access of element pairs, storage type chosen at run time -------------------
+__device__ __forceinline__ f32x2 load_pair(const void* base, size_t idx, bool is_bf16)
+{
+    if (is_bf16) {
+        const uint32_t u = *reinterpret_cast<const uint32_t*>(static_cast<const char*>(base) + idx * 2);
+        f32x2 r;
+        r.x = __uint_as_float(u << 16);
+        r.y = __uint_as_float(u & 0xffff0000u);
+        return r;
+    }
+    return *reinterpret_cast<const f32x2*>(static_cast<const char*>(base) + idx * 4);
+}
+
+template <typename T> __device__ __forceinline__ f32x2 load_pair_t(const T* base, size_t idx);
+template <> __device__ __forceinline__ f32x2 load_pair_t<__bf16>(const __bf16* base, size_t idx)
+{
+    return load_pair(base, idx, true);
+}
+template <> __device__ __forceinline__ f32x2 load_pair_t<float>(const float* base, size_t idx)
+{
+    return load_pair(base, idx, false);
+}
+
+template <typename T> __device__ __forceinline__ void store_pair_t(T* base, size_t idx, float a, float b);
+template <> __device__ __forceinline__ void store_pair_t<__bf16>(__bf16* base, size_t idx, float a, float b)
+{
+    bf16x2 h;
+    h.x = (__bf16)a;
+    h.y = (__bf16)b;
+    *reinterpret_cast<bf16x2*>(base + idx) = h;
+}
+template <> __device__ __forceinline__ void store_pair_t<float>(float* base, size_t idx, float a, float b)
+{
+    f32x2 h;
+    h.x = a;
+    h.y = b;
+    *reinterpret_cast<f32x2*>(base + idx) = h;
+}
+
+// ---- matrix-core policy -------------------------------------------------------------------------
+// One "k-step" contracts 16 values.  A fragment holds the 8 values one lane contributes to it:
+// lane (r = lane % 32, g = lane / 32) supplies row r of A (or column r of B) at k-slots 8g..8g+7.
+// Which physical k index a slot denotes is the caller's choice as long as A and B agree.
+// Accumulator layout of a 32x32 tile (both MFMA flavours): register v of lane (c = lane % 32,
+// g = lane / 32) is element [row 8*(v/4) + 4*g + v%4][column c].
+template <typename T> struct Mma;
+
+template <> struct Mma<__bf16> {
+    typedef bf16x8 frag;
+    static __device__ __forceinline__ frag load(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+    // two separate runs of 4 consecutive values
+    static __device__ __forceinline__ frag load2(const __bf16* p0, const __bf16* p1)
+    {
+        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(p0);
+        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(p1);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    // 8 values `stride` elements apart (an operand whose k index is the slow axis of the tile)
+    static __device__ __forceinline__ frag gather(const __bf16* p, int stride)
+    {
+        frag r;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) r[s] = p[s * stride];
+        return r;
+    }
+    static __device__ __forceinline__ frag pack(const float* x)
+    {
+        frag r;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) r[s] = (__bf16)x[s];
+        return r;
+    }
+    static __device__ __forceinline__ float get(const frag& a, int s) { return (float)a[s]; }
+    static __device__ __forceinline__ void mma(f32x16& acc, const frag& a, const frag& b)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+    }
+};
+
+template <> struct Mma<float> {
+    struct frag { float v[8]; };
+    static __device__ __forceinline__ frag load(const float* p)
+    {
+        frag r;
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(p);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(p + 4);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) { r.v[s] = lo[s]; r.v[4 + s] = hi[s]; }
+        return r;
+    }
+    static __device__ __forceinline__ frag load2(const float* p0, const float* p1)
+    {
+        frag r;
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(p0);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(p1);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) { r.v[s] = lo[s]; r.v[4 + s] = hi[s]; }
+        return r;
+    }
+    static __device__ __forceinline__ frag gather(const float* p, int stride)
+    {
+        frag r;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) r.v[s] = p[s * stride];
+        return r;
+    }
+    static __device__ __forceinline__ frag pack(const float* x)
+    {
+        frag r;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) r.v[s] = x[s];
+        return r;
+    }
+    static __device__ __forceinline__ float get(const frag& a, int s) { return a.v[s]; }
+    // the fp32 MFMA contracts 2 values per instruction: lane group g supplies k = g
+    static __device__ __forceinline__ void mma(f32x16& acc, const frag& a, const frag& b)
+    {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[s], b.v[s], acc, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// Fragment order of a dk x dv state tile in the workspace: the 32x32 accumulator tile (ta, tb)
+// is stored as two k-step fragments; fragment `half` of lane `lane` holds accumulator registers
+// 8*half .. 8*half+7, i.e. rows 16*half + 8*(s/4) + 4*(lane/32) + s%4 (s = 0..7) of column
+// lane%32.  A consumer reads the same 8 values back as one MFMA operand fragment.
+__device__ __forceinline__ size_t state_frag_offset(int ta, int tb, int n_tb, int half, int lane)
+{
+    return ((size_t)((ta * n_tb + tb) * 2 + half) * 64 + lane) * 8;
+}
+
+// ---- per-thread gate products of one RW-token block ---------------------------------------------
+template <int RW> struct GateBlock {
+    float f[RW][2];   // gate values, channel pair
+    float a[RW][2];   // inclusive product from the block start:  prod_{s<=i} f_s
+    float z[RW][2];   // exclusive product to the block end:      prod_{s>i}  f_s
+};
+
+template <int RW> __device__ __forceinline__ void gate_products(GateBlock<RW>& gb)
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        float run = 1.0f;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) { run *= gb.f[i][c]; gb.a[i][c] = run; }
+        run = 1.0f;
+#pragma unroll
+        for (int i = RW - 1; i >= 0; --i) { gb.z[i][c] = run; run *= gb.f[i][c]; }
+    }
+}
+
+// Block totals of the four waves -> decay from the chunk start to this block's start (pre),
+// from this block's end to the chunk end (post), and the extra factor that links this block to
+// the mid-chunk reference row C/2 (mid): for the two blocks after the reference it is the
+// product of the blocks between the reference and this block, likewise before it.
+struct BlockDecay { float pre, post, mid, all; };
+
+__device__ __forceinline__ BlockDecay block_decay(const float* tot, int D, int w, int ch)
+{
+    const float t0 = tot[0 * D + ch], t1 = tot[1 * D + ch], t2 = tot[2 * D + ch], t3 = tot[3 * D + ch];
+    BlockDecay r;
+    r.pre = (w == 0) ? 1.0f : (w == 1) ? t0 : (w == 2) ? t0 * t1 : t0 * t1 * t2;
+    r.post = (w == 3) ? 1.0f : (w == 2) ? t3 : (w == 1) ? t2 * t3 : t1 * t2 * t3;
+    r.mid = (w == 0) ? t1 : (w == 3) ? t2 : 1.0f;
+    r.all = (t0 * t1) * (t2 * t3);
+    return r;
+}
+
+// Write RW consecutive values (one channel, tokens RW*w..) as 16-byte vectors to a transposed tile.
+template <typename T, int RW> __device__ __forceinline__ void store_run(T* dst, const float* x);
+template <> __device__ __forceinline__ void store_run<__bf16, 16>(__bf16* dst, const float* x)
+{
+    *reinterpret_cast<bf16x8*>(dst) = Mma<__bf16>::pack(x);
+    *reinterpret_cast<bf16x8*>(dst + 8) = Mma<__bf16>::pack(x + 8);
+}
+template <> __device__ __forceinline__ void store_run<float, 16>(float* dst, const float* x)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f32x4 t;
+        t.x = x[4 * j]; t.y = x[4 * j + 1]; t.z = x[4 * j + 2]; t.w = x[4 * j + 3];
+        *reinterpret_cast<f32x4*>(dst + 4 * j) = t;
+    }
+}
+
+// XCD-aware decomposition of a linear workgroup id into (sequence, tile): consecutive ids are
+// dealt round-robin to the 8 XCDs, so all tiles of one sequence (which read the same q/f rows)
+// are placed on the same XCD and share its L2.  The grid must be seq_padded * n_tile with
+// seq_padded a multiple of 8; ids whose sequence is out of range exit.
+__device__ __forceinline__ void xcd_map(int id, int n_tile, int& seq, int& tile)
+{
+    const int x = id & 7;
+    const int r = id >> 3;
+    tile = r % n_tile;
+    seq = (r / n_tile) * 8 + x;
+}
+
+}   // namespace hgrn2

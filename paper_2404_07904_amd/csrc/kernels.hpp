@@ -1,0 +1,53 @@
+// Host-visible launch interface between the C-ABI translation unit and the kernel translation
+// units.  Every launcher validates nothing (the C-ABI layer has done that), enqueues on the given
+// stream and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hgrn2 {
+
+// Compile-time chunk length of the chunkwise kernels.
+constexpr int kChunk = 64;
+
+struct SeqDims {
+    int BH;          // B * H independent sequences
+    int N;           // tokens per sequence
+    int NC;          // chunks per sequence = ceil(N / kChunk)
+    int dk, dv;
+    bool io_bf16;    // q, v, o, grad_* storage: bf16 (else fp32)
+    bool gate_bf16;  // f storage
+};
+
+// What a state sweep accumulates.
+enum SweepMode {
+    kSweepStateFwd = 0,   // S_n for the forward read-out   (fragments contract over dk)
+    kSweepStateBwd = 1,   // S_n for the backward pass      (fragments contract over dv)
+    kSweepGrad = 2        // dS_{n+1}, reverse order        (fragments contract over dv)
+};
+
+// Chunk-to-chunk recurrence.  Writes, for every chunk n, the state entering it (modes 0/1) or
+// the state gradient leaving it (mode 2) into `ws` as MFMA fragments, and the final state
+// (`final_state`, may be null) in plain fp32 [dk][dv].  `a_src` is f (modes 0/1) or q (mode 2);
+// `b_src` is v (modes 0/1) or grad_o (mode 2).
+hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
+                        const float* init_state, float* final_state, void* ws, hipStream_t stream);
+
+// Per-chunk forward read-out  O = tril(Q~ K~^T) V + (Q G) S_n.
+hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,
+                          void* o, hipStream_t stream);
+
+// Per-chunk gradients dq, df, dv from the two state sweeps.
+hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                           const void* ws_state, const void* ws_dstate, void* grad_q, void* grad_f,
+                           void* grad_v, hipStream_t stream);
+
+// Decode step.
+hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, const void* q, const void* f,
+                       const void* v, float* state, void* o, hipStream_t stream);
+
+// Bytes of one per-chunk state set in the workspace.
+size_t state_ws_bytes(const SeqDims& d);
+
+}   // namespace hgrn2

@@ -1,0 +1,259 @@
+// Chunk-to-chunk state recurrence of the chunkwise HGRN2 algorithm (paper Section 3.2, Eq. 3,
+// regrouped per chunk of C tokens):
+//
+//   forward state     S_{n+1} = Diag(g_n) S_n + K^_n^T V_n ,       K^_j = k_j * prod_{s>j in chunk} f_s
+//   state gradient    dS_n    = Diag(g_n) dS_{n+1} + Q^_n^T dO_n , Q^_i = q_i * prod_{s<=i in chunk} f_s
+//
+// with g_n the product of all gates of chunk n.  One workgroup owns a [dk x TV] column slab of
+// the state of one (batch, head) and walks the chunks in order (reverse order for the gradient),
+// keeping the slab in fp32 MFMA accumulators.  Before each update it writes the slab, rounded to
+// the operand type, to the workspace in MFMA-fragment order so that the per-chunk kernels can
+// load it straight into operand registers.  The contraction runs over time, so both operands are
+// staged in LDS token-contiguous (see common.hpp for the thread layout that makes this free).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace hgrn2 {
+
+struct SweepParams {
+    const void* q;
+    const void* f;
+    const void* bsrc;
+    const float* init;
+    float* fin;
+    void* ws;
+    int BH, N, NC, n_tile, gate_bf16;
+};
+
+template <typename T, int DK, int DV, int TV, int MODE>
+__global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
+{
+    constexpr int C = kChunk, RW = C / kWaves;
+    constexpr int PC = C + pad_elems<T>();
+    constexpr int NAT = DK / 32, NBT = TV / 32, NT = NAT * NBT, TPW = NT / kWaves;
+    static_assert(NT % kWaves == 0 && TPW >= 1, "tile count must be a multiple of the wave count");
+    constexpr bool TRANS = MODE != kSweepStateFwd;
+    constexpr bool REVERSE = MODE == kSweepGrad;
+    typedef Mma<T> M;
+
+    extern __shared__ __align__(16) char smem[];
+    T* AT = reinterpret_cast<T*>(smem);          // [DK][PC]  a-side operand, token-contiguous
+    T* BT = AT + DK * PC;                        // [TV][PC]  b-side operand, token-contiguous
+    float* gam = reinterpret_cast<float*>(BT + TV * PC);   // [DK] whole-chunk decay
+    float* tot = gam + DK;                       // [4][DK] per-wave block products
+
+    int bh, tile;
+    xcd_map(blockIdx.x, p.n_tile, bh, tile);
+    if (bh >= p.BH) return;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int col0 = tile * TV;
+    const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;
+    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    const bool gate_bf16 = p.gate_bf16 != 0;
+    const T* qsrc = static_cast<const T*>(p.q);
+    const T* bsrc = static_cast<const T*>(p.bsrc);
+    T* ws = static_cast<T*>(p.ws) + (size_t)bh * p.NC * DK * DV;
+
+    f32x2 rf[RW], rq[RW], rb[RW];
+    auto load_chunk = [&](int n) {
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const int row = n * C + RW * w + i;
+            const bool ok = row < p.N;
+            f32x2 one; one.x = 1.0f; one.y = 1.0f;
+            f32x2 zero; zero.x = 0.0f; zero.y = 0.0f;
+            rf[i] = (ok && a_act) ? load_pair(p.f, seq_k + (size_t)row * DK + 2 * lane, gate_bf16) : one;
+            if (MODE == kSweepGrad)
+                rq[i] = (ok && a_act) ? load_pair_t<T>(qsrc, seq_k + (size_t)row * DK + 2 * lane) : zero;
+            rb[i] = (ok && b_act) ? load_pair_t<T>(bsrc, seq_v + (size_t)row * DV + col0 + 2 * lane) : zero;
+        }
+    };
+
+    // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
+    f32x16 acc[TPW];
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float x = 0.0f;
+            if (p.init) {
+                const float* s0 = p.init + (size_t)bh * DK * DV;
+                x = TRANS ? s0[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)]
+                          : s0[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32];
+            }
+            acc[j][v] = x;
+        }
+    }
+
+    if (p.NC > 0) load_chunk(REVERSE ? p.NC - 1 : 0);
+
+    for (int it = 0; it < p.NC; ++it) {
+        const int n = REVERSE ? p.NC - 1 - it : it;
+
+        // ---- gate products of this thread's RW tokens, channel pair (2*lane, 2*lane+1) ----
+        float a0[RW], a1[RW], z0[RW], z1[RW];
+        {
+            float run0 = 1.0f, run1 = 1.0f;
+#pragma unroll
+            for (int i = 0; i < RW; ++i) { run0 *= rf[i].x; run1 *= rf[i].y; a0[i] = run0; a1[i] = run1; }
+            run0 = 1.0f; run1 = 1.0f;
+#pragma unroll
+            for (int i = RW - 1; i >= 0; --i) { z0[i] = run0; z1[i] = run1; run0 *= rf[i].x; run1 *= rf[i].y; }
+        }
+        if (a_act) {
+            tot[w * DK + 2 * lane] = a0[RW - 1];
+            tot[w * DK + 2 * lane + 1] = a1[RW - 1];
+        }
+        __syncthreads();
+        if (a_act) {
+            const BlockDecay d0 = block_decay(tot, DK, w, 2 * lane);
+            const BlockDecay d1 = block_decay(tot, DK, w, 2 * lane + 1);
+            float x0[RW], x1[RW];
+#pragma unroll
+            for (int i = 0; i < RW; ++i) {
+                if (MODE == kSweepGrad) {
+                    x0[i] = rq[i].x * (d0.pre * a0[i]);
+                    x1[i] = rq[i].y * (d1.pre * a1[i]);
+                } else {
+                    x0[i] = (1.0f - rf[i].x) * (z0[i] * d0.post);
+                    x1[i] = (1.0f - rf[i].y) * (z1[i] * d1.post);
+                }
+            }
+            store_run<T, RW>(AT + (2 * lane) * PC + RW * w, x0);
+            store_run<T, RW>(AT + (2 * lane + 1) * PC + RW * w, x1);
+            if (w == 0) { gam[2 * lane] = d0.all; gam[2 * lane + 1] = d1.all; }
+        }
+        if (b_act) {
+            float x0[RW], x1[RW];
+#pragma unroll
+            for (int i = 0; i < RW; ++i) { x0[i] = rb[i].x; x1[i] = rb[i].y; }
+            store_run<T, RW>(BT + (2 * lane) * PC + RW * w, x0);
+            store_run<T, RW>(BT + (2 * lane + 1) * PC + RW * w, x1);
+        }
+        if (it + 1 < p.NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
+        __syncthreads();
+
+        // ---- hand the slab as it stands (state entering / gradient leaving chunk n) to the workspace
+        T* wsn = ws + (size_t)n * DK * DV;
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float x[8];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) x[s] = acc[j][8 * half + s];
+                *reinterpret_cast<typename M::frag*>(
+                    wsn + state_frag_offset(at, col0 / 32 + bt, DV / 32, half, lane)) = M::pack(x);
+            }
+        }
+
+        // ---- slab = Diag(g) slab + A^T B over the chunk ----
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int id = w + kWaves * j, at = id % NAT;
+            if (TRANS) {
+                const float gm = gam[32 * at + r32];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] *= gm;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const f32x4 gm = *reinterpret_cast<const f32x4*>(gam + 32 * at + 8 * c + 4 * g);
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) acc[j][4 * c + jj] *= gm[jj];
+                }
+            }
+        }
+#pragma unroll
+        for (int ks = 0; ks < C / 16; ++ks) {
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+                const typename M::frag fa = M::load(AT + (32 * at + r32) * PC + 16 * ks + 8 * g);
+                const typename M::frag fb = M::load(BT + (32 * bt + r32) * PC + 16 * ks + 8 * g);
+                if (TRANS) M::mma(acc[j], fb, fa);
+                else       M::mma(acc[j], fa, fb);
+            }
+        }
+    }
+
+    if (p.fin) {
+        float* s1 = p.fin + (size_t)bh * DK * DV;
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                if (TRANS) s1[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)] = acc[j][v];
+                else       s1[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32] = acc[j][v];
+            }
+        }
+    }
+}
+
+template <typename T, int DK, int DV, int TV, int MODE>
+static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_t stream)
+{
+    SweepParams p = p0;
+    p.n_tile = DV / TV;
+    constexpr int PC = kChunk + pad_elems<T>();
+    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(1 + kWaves) * DK * sizeof(float);
+    auto kern = sweep_kernel<T, DK, DV, TV, MODE>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const int seq_pad = (d.BH + 7) / 8 * 8;
+    hipLaunchKernelGGL(kern, dim3(seq_pad * p.n_tile), dim3(kThreads), lds, stream, p);
+    return hipGetLastError();
+}
+
+template <typename T, int DK, int DV, int MODE>
+static hipError_t launch_tv(const SeqDims& d, const SweepParams& p, hipStream_t stream)
+{
+    // Narrow slabs when there are few sequences, so that the sweep still covers the 256 CUs.
+    if constexpr (DV == 128 && DK == 128) {
+        if (d.BH < 96) return launch_one<T, DK, DV, 32, MODE>(d, p, stream);
+    }
+    if constexpr (DV == 128) {
+        if (d.BH < 256) return launch_one<T, DK, DV, 64, MODE>(d, p, stream);
+    }
+    return launch_one<T, DK, DV, DV, MODE>(d, p, stream);
+}
+
+template <typename T, int MODE>
+static hipError_t launch_dims(const SeqDims& d, const SweepParams& p, hipStream_t stream)
+{
+    if (d.dk == 128 && d.dv == 128) return launch_tv<T, 128, 128, MODE>(d, p, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_tv<T, 64, 64, MODE>(d, p, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_tv<T, 128, 64, MODE>(d, p, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_tv<T, 64, 128, MODE>(d, p, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
+                        const float* init_state, float* final_state, void* ws, hipStream_t stream)
+{
+    if (d.BH == 0) return hipSuccess;
+    SweepParams p;
+    p.q = q; p.f = f; p.bsrc = b_src; p.init = init_state; p.fin = final_state; p.ws = ws;
+    p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.n_tile = 1; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    if (d.io_bf16) {
+        switch (mode) {
+        case kSweepStateFwd: return launch_dims<__bf16, kSweepStateFwd>(d, p, stream);
+        case kSweepStateBwd: return launch_dims<__bf16, kSweepStateBwd>(d, p, stream);
+        case kSweepGrad:     return launch_dims<__bf16, kSweepGrad>(d, p, stream);
+        }
+    } else {
+        if (mode == kSweepStateFwd) return launch_dims<float, kSweepStateFwd>(d, p, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+size_t state_ws_bytes(const SeqDims& d)
+{
+    return (size_t)d.BH * d.NC * d.dk * d.dv * (d.io_bf16 ? 2 : 4);
+}
+
+}   // namespace hgrn2
