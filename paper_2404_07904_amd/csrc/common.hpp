@@ -99,6 +99,20 @@ template <> struct Mma<__bf16> {
         for (int s = 0; s < 8; ++s) r[s] = p[s * stride];
         return r;
     }
+    // Operand whose k index is the SLOW axis of a row-major LDS tile (element (k, x) at
+    // tile[k * pitch + x]): lane (x0 + lane % 32, g) receives k = k0 + 8g .. k0 + 8g + 7 through
+    // two LDS transpose reads.  In a transpose read the 16 lanes of a group each fetch 4
+    // consecutive 16-bit values (4 lanes per k row, 16 columns) and lane i gets back column i
+    // of the 4 x 16 block, i.e. 4 consecutive k of one x.
+    static __device__ __forceinline__ frag load_kmajor(const __bf16* tile, int pitch, int k0, int x0, int lane)
+    {
+        typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+        const int i16 = lane & 15;
+        const __bf16* p = tile + (k0 + 8 * (lane >> 5) + (i16 >> 2)) * pitch + x0 + (lane & 16) + 4 * (i16 & 3);
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * pitch));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
     static __device__ __forceinline__ frag pack(const float* x)
     {
         frag r;
@@ -139,6 +153,10 @@ template <> struct Mma<float> {
 #pragma unroll
         for (int s = 0; s < 8; ++s) r.v[s] = p[s * stride];
         return r;
+    }
+    static __device__ __forceinline__ frag load_kmajor(const float* tile, int pitch, int k0, int x0, int lane)
+    {
+        return gather(tile + (k0 + 8 * (lane >> 5)) * pitch + x0 + (lane & 31), pitch);
     }
     static __device__ __forceinline__ frag pack(const float* x)
     {
