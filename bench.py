@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the HGRN2 hot path on one MI355X.
+
+One "step" is one pass of the whole training path over one batch of seeded synthetic input at
+the layer shape B=8, H=16, N=2048, dk=dv=128 (bf16 storage, fp32 accumulation): hgrn2_fwd
+followed by hgrn2_bwd.  value = B*N / (time per step) in tokens/s.  The decode path
+(hgrn2_step at B=256, H=16, d=128, 512 consecutive in-place steps) is timed in the same run and
+reported under "decode" in GB/s of algorithmic bytes.
+
+Also reported on the same JSON line:
+  roofline      the dominant kernel of the step against the HBM roofline (8 TB/s), from HIP-event
+                timings of the individual stages taken in this run
+  mfma          algorithmic flops of fwd+bwd against the dense bf16 MFMA peak (2.5 PFLOP/s)
+  cpu_baseline  the fp64 CPU oracle on the same inputs, all host cores, same run
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+CHUNK = 64
+
+# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each
+# scaled by what the same counter reads for a plain copy kernel of known size; bytes per launch at
+# the benchmark workload.  None until measured; see profiles/.
+MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": None}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layer", type=int, default=12, help="gate statistics: layer of the 24-layer stack (0, 12, 23)")
+    ap.add_argument("--decode-steps", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; every (batch, head) pair is an independent "
+              "recurrence, so more GPUs would only split the batch. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2404_07904_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.lib()          # fail loudly if the native library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    B, H, N, D = 8, 16, 2048, 128
+    tokens = B * N
+    token_heads = B * H * N
+
+    def to_dev(x, dt=torch.bfloat16):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(dev).to(dt).contiguous()
+
+    # two seeded input sets, used alternately so that no step finds its inputs in cache
+    sets = []
+    hosts = []
+    for i in range(2):
+        w = synth.config2(args.layer if i == 0 else (args.layer + 1) % 24)
+        hosts.append(w)
+        sets.append(tuple(to_dev(x) for x in (w.q, w.f, w.v, w.dO)))
+    shape = binding.make_shape(sets[0][0], sets[0][2], sets[0][1])
+    ws = torch.empty(binding.hgrn2_bwd_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    o = torch.empty_like(sets[0][2])
+    hT = torch.empty((B, H, D, D), dtype=torch.float32, device=dev)
+    gq, gf, gv = (torch.empty_like(sets[0][0]) for _ in range(3))
+
+    def step(i):
+        q, f, v, dO = sets[i % 2]
+        binding.hgrn2_fwd(q, f, v, None, o=o, hT=hT, workspace=ws)
+        binding.hgrn2_bwd(q, f, v, dO, None, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = tokens / (ms_per_step * 1e-3)
+
+    # ---- per-stage durations with HIP events on the stream the kernels run on ----
+    half = ws.numel() // 2
+    ws_a, ws_b = ws[:half], ws[half:]
+
+    def timed(fn, reps=10):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i, (a, b) in enumerate(ev):
+            a.record()
+            fn(i)
+            b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in ev) / reps * 1e-3   # seconds
+
+    def s_fwd(i):
+        q, f, v, _ = sets[i % 2]
+        binding.hgrn2_state_sweep(shape, binding.SWEEP_STATE_FWD, None, f, v, ws_a, None, hT)
+
+    def s_out(i):
+        q, f, v, _ = sets[i % 2]
+        binding.hgrn2_fwd_readout(shape, q, f, v, ws_a, o)
+
+    def s_bst(i):
+        q, f, v, _ = sets[i % 2]
+        binding.hgrn2_state_sweep(shape, binding.SWEEP_STATE_BWD, None, f, v, ws_a)
+
+    def s_grad(i):
+        q, f, v, dO = sets[i % 2]
+        binding.hgrn2_state_sweep(shape, binding.SWEEP_STATE_GRAD, q, f, dO, ws_b)
+
+    def s_chunk(i):
+        q, f, v, dO = sets[i % 2]
+        binding.hgrn2_bwd_chunk_grads(shape, q, f, v, dO, ws_a, ws_b, gq, gf, gv)
+
+    el = 2  # bytes per bf16 element
+    state_bytes = B * H * (N // CHUNK) * D * D * el
+    seq_k = token_heads * D * el
+    # algorithmic bytes: the operation's own inputs/outputs each stage has to touch (workspace
+    # traffic is overhead of the implementation and is not counted)
+    stages = [
+        ("state_sweep_fwd", s_fwd, 2 * seq_k),            # f, v
+        ("fwd_readout", s_out, 4 * seq_k),                 # q, f, v -> o           (1024 B / token-head)
+        ("state_sweep_bwd", s_bst, 2 * seq_k),             # f, v
+        ("state_sweep_grad", s_grad, 3 * seq_k),           # q, f, dO
+        ("bwd_chunk_grads", s_chunk, 7 * seq_k),           # q, f, v, dO -> dq, df, dv (1792 B / token-head)
+    ]
+    stage_out = {}
+    for name, fn, abytes in stages:
+        for i in range(2):
+            fn(i)
+        dt = timed(fn)
+        stage_out[name] = {"us": round(dt * 1e6, 2), "algorithmic_GB": round(abytes / 1e9, 4),
+                           "GBps": round(abytes / dt / 1e9, 1)}
+    dom = max(stage_out, key=lambda k: stage_out[k]["us"])
+    dom_bytes = dict((n, b) for n, _, b in stages)[dom]
+    achieved = dom_bytes / (stage_out[dom]["us"] * 1e-6) / 1e9
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
+
+    flops = token_heads * ((4 * D * D + CHUNK * 2 * D) + (8 * D * D + CHUNK * 5 * D))   # fwd + bwd, algorithmic
+    mfma_tflops = flops / (ms_per_step * 1e-3) / 1e12
+    io_bytes = token_heads * (1024 + 1792)
+    result = {
+        "metric": "tokens/s fwd+bwd (H=16,dk=dv=128,N=2048) + % MFMA peak; step GB/s",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[2]: layer-shaped fwd+bwd, B=8 H=16 N=2048 dk=dv=128 bf16, gates of layer %d of 24"
+                               % args.layer, "global_batch": B, "seq_len": N, "heads": H, "chunk": CHUNK},
+        "roofline": roofline,
+        "mfma": {"achieved_TFLOPs": round(mfma_tflops, 2), "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                 "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 5)},
+        "hbm_step": {"algorithmic_GBps": round(io_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+                     "frac": round(io_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "stages": stage_out,
+    }
+
+    # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----
+    if not args.no_decode:
+        Bd, Hd, T_distinct = 256, 16, 64
+        wd = synth.config4(T=T_distinct, B=Bd, H=Hd, d=D)
+        qd, fd, vd = (to_dev(x) for x in (wd.q, wd.f, wd.v))
+        st = to_dev(wd.state, torch.float32)
+        od = torch.empty((Bd, Hd, D), dtype=torch.bfloat16, device=dev)
+        for t in range(8):
+            binding.hgrn2_step(qd[t], fd[t], vd[t], st, od)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for t in range(args.decode_steps):
+            k = t % T_distinct
+            binding.hgrn2_step(qd[k], fd[k], vd[k], st, od)
+        b.record()
+        torch.cuda.synchronize()
+        dt = a.elapsed_time(b) * 1e-3 / args.decode_steps
+        step_bytes = 2 * Bd * Hd * D * D * 4 + 4 * Bd * Hd * D * el
+        result["decode"] = {"workload": "configs[4]: B=256 H=16 dk=dv=128, %d in-place steps, %d distinct tokens cycled"
+                                        % (args.decode_steps, T_distinct),
+                            "us_per_step": round(dt * 1e6, 2), "GBps": round(step_bytes / dt / 1e9, 1),
+                            "roofline": {"bound": "hbm", "achieved": round(step_bytes / dt / 1e9, 1),
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": round(step_bytes / dt / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}}
+
+    # ---- CPU baseline: the fp64 oracle as it stands, on the same seeded inputs ----
+    if not args.no_cpu_baseline:
+        import oracle
+        w = hosts[0]
+        binding.hgrn2_fwd(*sets[0][:3], None, o=o, hT=hT, workspace=ws)
+        binding.hgrn2_bwd(*sets[0], None, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv)
+        torch.cuda.synchronize()
+        gpu_out = [x.float().cpu().numpy() for x in (o, gq, gf, gv)]
+        reps, t_cpu = 0, 0.0
+        while t_cpu < 10.0 and reps < 4:
+            c0 = time.perf_counter()
+            o_ref, _ = oracle.fwd(w.q, w.f, w.v, None, want_hT=False)
+            g_ref = oracle.bwd(w.q, w.f, w.v, w.dO, None, None, want_dh0=False)
+            t_cpu += time.perf_counter() - c0
+            reps += 1
+        refs = [o_ref, g_ref[0], g_ref[1], g_ref[2]]
+        errs = {}
+        for name, x, r in zip(("o", "dq", "df", "dv"), gpu_out, refs):
+            errs[name] = float("%.3e" % (np.max(np.abs(x - r)) / np.max(np.abs(r))))
+        result["cpu_baseline"] = {"value": round(tokens * reps / t_cpu, 1), "unit": "tokens/s",
+                                  "cores": oracle.threads(), "kind": "oracle",
+                                  "sample": "the full benchmark workload (B=8,H=16,N=2048,d=128), fwd+bwd in fp64, "
+                                            "%d repetition(s), %.1f s" % (reps, t_cpu)}
+        result["parity_vs_oracle_full_size"] = errs
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -107,6 +107,35 @@ int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, i
                const void* q_t, const void* f_t, const void* v_t, float* state, void* o_t,
                void* hip_stream);
 
+/*
+ * Stage entry points.  hgrn2_fwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_FWD) followed by
+ * hgrn2_fwd_readout; hgrn2_bwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_BWD), then
+ * hgrn2_state_sweep(HGRN2_SWEEP_STATE_GRAD), then hgrn2_bwd_chunk_grads.  They exist for callers
+ * that time or schedule the stages themselves (e.g. overlap the two backward sweeps on two
+ * streams).  All follow from regrouping Eq. 3 (Section 3.2) into chunks of 64 tokens:
+ *   state sweep      S_{n+1} = Diag(g_n) S_n + K^_n^T V_n   (or its transpose-gradient
+ *                    dS_n = Diag(g_n) dS_{n+1} + Q^_n^T dO_n, walking the chunks backwards);
+ *   forward read-out o = tril(Q~ K~^T) V + (q G) S_n per chunk;
+ *   chunk gradients  grad_q, grad_f, grad_v per chunk from S_n and dS_{n+1}.
+ * `chunk_states` buffers are device memory of hgrn2_fwd_workspace_bytes(shape) bytes, 256-byte
+ * aligned, in a private MFMA-fragment order that depends on the sweep mode: a buffer written
+ * in one mode may only be consumed by the stage that expects that mode.
+ *   hgrn2_state_sweep: b_src is v (STATE_FWD, STATE_BWD) or grad_o (STATE_GRAD); q is read only
+ *     in STATE_GRAD; init_state is h0 (or grad_hT), may be NULL = 0; final_state receives hT
+ *     (or grad_h0), may be NULL.
+ */
+typedef enum { HGRN2_SWEEP_STATE_FWD = 0, HGRN2_SWEEP_STATE_BWD = 1, HGRN2_SWEEP_STATE_GRAD = 2 } hgrn2_sweep_mode;
+
+int hgrn2_state_sweep(const hgrn2_shape* shape, int32_t mode, const void* q, const void* f, const void* b_src,
+                      const float* init_state, float* final_state, void* chunk_states,
+                      size_t chunk_states_bytes, void* hip_stream);
+int hgrn2_fwd_readout(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+                      const void* chunk_states /* STATE_FWD */, void* o, void* hip_stream);
+int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+                          const void* grad_o, const void* chunk_states /* STATE_BWD */,
+                          const void* chunk_state_grads /* STATE_GRAD */, void* grad_q, void* grad_f,
+                          void* grad_v, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* hgrn2_status_string(int status);
 

@@ -17,7 +17,9 @@ HGRN2_F32, HGRN2_BF16 = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn2_status_string"]
+           "hgrn2_step", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
+           "hgrn2_status_string"]
+SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
 class hgrn2_shape(ctypes.Structure):
@@ -55,6 +57,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_state_sweep.restype = ctypes.c_int
+        L.hgrn2_state_sweep.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_fwd_readout.restype = ctypes.c_int
+        L.hgrn2_fwd_readout.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_bwd_chunk_grads.restype = ctypes.c_int
+        L.hgrn2_bwd_chunk_grads.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_status_string.restype = ctypes.c_char_p
         L.hgrn2_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -151,3 +159,26 @@ def hgrn2_step(q_t, f_t, v_t, state, o_t=None):
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_step")
     return o_t
+
+
+def hgrn2_state_sweep(shape, mode, q, f, b_src, chunk_states, init_state=None, final_state=None):
+    """Stage entry point: chunk-to-chunk recurrence; fills `chunk_states` (uint8 device buffer)."""
+    rc = lib().hgrn2_state_sweep(ctypes.byref(shape), mode, _ptr(q), _ptr(f), _ptr(b_src), _ptr(init_state),
+                                 _ptr(final_state), _ptr(chunk_states), chunk_states.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_state_sweep")
+
+
+def hgrn2_fwd_readout(shape, q, f, v, chunk_states, o):
+    rc = lib().hgrn2_fwd_readout(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(chunk_states), _ptr(o),
+                                 _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_fwd_readout")
+
+
+def hgrn2_bwd_chunk_grads(shape, q, f, v, grad_o, chunk_states, chunk_state_grads, grad_q, grad_f, grad_v):
+    rc = lib().hgrn2_bwd_chunk_grads(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(grad_o),
+                                     _ptr(chunk_states), _ptr(chunk_state_grads), _ptr(grad_q), _ptr(grad_f),
+                                     _ptr(grad_v), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd_chunk_grads")

@@ -111,6 +111,57 @@ int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, i
     return HGRN2_OK;
 }
 
+int hgrn2_state_sweep(const hgrn2_shape* shape, int32_t mode, const void* q, const void* f, const void* b_src,
+                      const float* init_state, float* final_state, void* chunk_states,
+                      size_t chunk_states_bytes, void* hip_stream)
+{
+    if (mode < 0 || mode > 2) return HGRN2_ERR_SHAPE;
+    SeqDims d;
+    const int rc = check_shape(shape, mode != HGRN2_SWEEP_STATE_FWD, &d);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)d.BH * d.N > 0;
+    if (has_tokens && (!f || !b_src || (mode == HGRN2_SWEEP_STATE_GRAD && !q))) return HGRN2_ERR_NULL;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need > 0 && (!chunk_states || chunk_states_bytes < need || ((uintptr_t)chunk_states & 255)))
+        return HGRN2_ERR_WORKSPACE;
+    if (d.BH == 0) return HGRN2_OK;
+    if (launch_sweep(d, static_cast<SweepMode>(mode), q, f, b_src, init_state, final_state, chunk_states,
+                     static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_fwd_readout(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+                      const void* chunk_states, void* o, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, false, &d);
+    if (rc != HGRN2_OK) return rc;
+    if ((size_t)d.BH * d.N == 0) return HGRN2_OK;
+    if (!q || !f || !v || !chunk_states || !o) return HGRN2_ERR_NULL;
+    if ((uintptr_t)chunk_states & 255) return HGRN2_ERR_WORKSPACE;
+    if (launch_fwd_out(d, q, f, v, chunk_states, o, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+                          const void* grad_o, const void* chunk_states, const void* chunk_state_grads,
+                          void* grad_q, void* grad_f, void* grad_v, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d);
+    if (rc != HGRN2_OK) return rc;
+    if ((size_t)d.BH * d.N == 0) return HGRN2_OK;
+    if (!q || !f || !v || !grad_o || !chunk_states || !chunk_state_grads || !grad_q || !grad_f || !grad_v)
+        return HGRN2_ERR_NULL;
+    if (((uintptr_t)chunk_states & 255) || ((uintptr_t)chunk_state_grads & 255)) return HGRN2_ERR_WORKSPACE;
+    if (launch_bwd_grad(d, q, f, v, grad_o, chunk_states, chunk_state_grads, grad_q, grad_f, grad_v,
+                        static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
 const char* hgrn2_status_string(int status)
 {
     switch (status) {

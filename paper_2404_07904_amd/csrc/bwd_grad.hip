@@ -128,17 +128,17 @@ __global__ __launch_bounds__(kThreads) void bwd_grad_kernel(BwdGradParams p)
     f32x2 rf[RW], rq[RW];
     {
         f32x2 rv[RW], rd[RW];
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const int row = n * C + RW * w + i;
-            const bool ok = row < p.N;
-            f32x2 one; one.x = 1.0f; one.y = 1.0f;
-            f32x2 zero; zero.x = 0.0f; zero.y = 0.0f;
-            rf[i] = (ok && k_act) ? load_pair(p.f, seq_k + (size_t)row * DK + 2 * lane, gate_bf16) : one;
-            rq[i] = (ok && k_act) ? load_pair_t<T>(qg, seq_k + (size_t)row * DK + 2 * lane) : zero;
-            rv[i] = (ok && v_act) ? load_pair_t<T>(vg, seq_v + (size_t)row * DV + 2 * lane) : zero;
-            rd[i] = (ok && v_act) ? load_pair_t<T>(dog, seq_v + (size_t)row * DV + 2 * lane) : zero;
-        }
+        RawRows<RW> raw_f, raw_q, raw_v, raw_d;
+        const int row0 = n * C + RW * w;
+        const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
+        load_rows<RW>(raw_f, p.f, seq_k, DK, col_k, row0, p.N, gate_bf16);
+        load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_v, vg, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_d, dog, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
+        convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
+        convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
+        convert_rows<RW>(rv, raw_v, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
+        convert_rows<RW>(rd, raw_d, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
         if (v_act) {
 #pragma unroll
             for (int i = 0; i < RW; ++i) {

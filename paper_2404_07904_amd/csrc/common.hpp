@@ -73,6 +73,55 @@ template <> __device__ __forceinline__ void store_pair_t<float>(float* base, siz
     *reinterpret_cast<f32x2*>(base + idx) = h;
 }
 
+// ---- batched row loads ---------------------------------------------------------------------------
+// RW consecutive rows of one channel pair, kept RAW (bf16 pairs as a 32-bit pattern in .x) so
+// that all loads of a batch are issued back to back and converted only when first used.  Row
+// indices are clamped into [0, n_rows) and the column is the caller's (already valid) one, so
+// every address is in bounds and no load sits behind a branch; out-of-range rows are replaced
+// by `fill` at conversion time.
+template <int RW> struct RawRows { f32x2 r[RW]; };
+
+template <int RW>
+__device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, size_t seq_off, int row_stride,
+                                          int col, int row0, int n_rows, bool is_bf16)
+{
+    if (is_bf16) {
+        const char* b = static_cast<const char*>(base) + (seq_off + col) * 2;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const int rc = min(row0 + i, n_rows - 1);
+            out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(b + (size_t)rc * row_stride * 2));
+        }
+    } else {
+        const char* b = static_cast<const char*>(base) + (seq_off + col) * 4;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const int rc = min(row0 + i, n_rows - 1);
+            out.r[i] = *reinterpret_cast<const f32x2*>(b + (size_t)rc * row_stride * 4);
+        }
+    }
+}
+
+template <int RW>
+__device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>& raw, int row0, int n_rows,
+                                             bool lane_active, bool is_bf16, float fill)
+{
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+        f32x2 x = raw.r[i];
+        if (is_bf16) {
+            const uint32_t u = __float_as_uint(raw.r[i].x);
+            x.x = __uint_as_float(u << 16);
+            x.y = __uint_as_float(u & 0xffff0000u);
+        }
+        const bool ok = lane_active && (row0 + i < n_rows);
+        dst[i].x = ok ? x.x : fill;
+        dst[i].y = ok ? x.y : fill;
+    }
+}
+
+template <typename T> __host__ __device__ constexpr bool is_bf16_type() { return sizeof(T) == 2; }
+
 // ---- matrix-core policy -------------------------------------------------------------------------
 // One "k-step" contracts 16 values.  A fragment holds the 8 values one lane contributes to it:
 // lane (r = lane % 32, g = lane / 32) supplies row r of A (or column r of B) at k-slots 8g..8g+7.

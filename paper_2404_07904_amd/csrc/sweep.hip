@@ -54,19 +54,14 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
     const T* bsrc = static_cast<const T*>(p.bsrc);
     T* ws = static_cast<T*>(p.ws) + (size_t)bh * p.NC * DK * DV;
 
-    f32x2 rf[RW], rq[RW], rb[RW];
+    // raw rows of the chunk being prefetched; inactive lanes read column 0 and are ignored
+    RawRows<RW> raw_f, raw_q, raw_b;
+    const int col_a = a_act ? 2 * lane : 0, col_b = col0 + (b_act ? 2 * lane : 0);
     auto load_chunk = [&](int n) {
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const int row = n * C + RW * w + i;
-            const bool ok = row < p.N;
-            f32x2 one; one.x = 1.0f; one.y = 1.0f;
-            f32x2 zero; zero.x = 0.0f; zero.y = 0.0f;
-            rf[i] = (ok && a_act) ? load_pair(p.f, seq_k + (size_t)row * DK + 2 * lane, gate_bf16) : one;
-            if (MODE == kSweepGrad)
-                rq[i] = (ok && a_act) ? load_pair_t<T>(qsrc, seq_k + (size_t)row * DK + 2 * lane) : zero;
-            rb[i] = (ok && b_act) ? load_pair_t<T>(bsrc, seq_v + (size_t)row * DV + col0 + 2 * lane) : zero;
-        }
+        const int row0 = n * C + RW * w;
+        load_rows<RW>(raw_f, p.f, seq_k, DK, col_a, row0, p.N, gate_bf16);
+        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, DK, col_a, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_b, bsrc, seq_v, DV, col_b, row0, p.N, is_bf16_type<T>());
     };
 
     // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
@@ -90,6 +85,13 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
 
     for (int it = 0; it < p.NC; ++it) {
         const int n = REVERSE ? p.NC - 1 - it : it;
+        f32x2 rf[RW], rq[RW], rb[RW];
+        {
+            const int row0 = n * C + RW * w;
+            convert_rows<RW>(rf, raw_f, row0, p.N, a_act, gate_bf16, 1.0f);
+            if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, p.N, a_act, is_bf16_type<T>(), 0.0f);
+            convert_rows<RW>(rb, raw_b, row0, p.N, b_act, is_bf16_type<T>(), 0.0f);
+        }
 
         // ---- gate products of this thread's RW tokens, channel pair (2*lane, 2*lane+1) ----
         float a0[RW], a1[RW], z0[RW], z1[RW];

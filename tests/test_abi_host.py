@@ -1,0 +1,122 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every function the
+header declares, sizes workspaces, and turns bad arguments into status codes before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2404_07904_amd import binding
+from paper_2404_07904_amd.binding import hgrn2_shape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, E_NULL, E_SHAPE, E_UNSUP, E_WS, E_HIP = range(6)
+FAKE = ctypes.c_void_p(0x10000)          # never dereferenced: every call below fails validation first
+FAKE_WS = ctypes.c_void_p(0x100000)      # 256-byte aligned
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hgrn2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hgrn2_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.lib()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS), (names, binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    for code in range(6):
+        s = binding.status_string(code)
+        assert isinstance(s, str) and s
+    assert binding.status_string(0) == "ok"
+    assert "unknown" in binding.status_string(99)
+
+
+def shape(B=2, H=3, N=100, dk=64, dv=64, chunk=0, io=1, gate=1):
+    return hgrn2_shape(B, H, N, dk, dv, chunk, io, gate)
+
+
+def test_workspace_sizes():
+    s = shape(B=8, H=16, N=2048, dk=128, dv=128)
+    one = 8 * 16 * 32 * 128 * 128 * 2
+    assert binding.hgrn2_fwd_workspace_bytes(s) == one
+    assert binding.hgrn2_bwd_workspace_bytes(s) == 2 * one
+    s32 = shape(B=1, H=1, N=256, io=0, gate=0)
+    assert binding.hgrn2_fwd_workspace_bytes(s32) == 4 * 64 * 64 * 4
+    assert binding.hgrn2_bwd_workspace_bytes(s32) == 0           # fp32 backward is unsupported
+    assert binding.hgrn2_fwd_workspace_bytes(shape(N=65)) == 2 * 3 * 2 * 64 * 64 * 2   # ragged: 2 chunks
+    assert binding.hgrn2_fwd_workspace_bytes(shape(N=0)) == 0
+    assert binding.hgrn2_fwd_workspace_bytes(shape(dk=96)) == 0
+
+
+def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):
+    return binding.lib().hgrn2_fwd(ctypes.byref(s) if s is not None else None, q, f, v, h0, o, hT, ws, ws_bytes, None)
+
+
+def call_bwd(s, q=FAKE, f=FAKE, v=FAKE, go=FAKE, gq=FAKE, gf=FAKE, gv=FAKE, ws=FAKE_WS, ws_bytes=1 << 40):
+    return binding.lib().hgrn2_bwd(ctypes.byref(s) if s is not None else None, q, f, v, None, go, None, gq, gf, gv,
+                                   None, ws, ws_bytes, None)
+
+
+def test_fwd_argument_errors():
+    assert call_fwd(None) == E_NULL
+    assert call_fwd(shape(B=-1)) == E_SHAPE
+    assert call_fwd(shape(N=-5)) == E_SHAPE
+    assert call_fwd(shape(dk=0)) == E_SHAPE
+    assert call_fwd(shape(io=7)) == E_SHAPE
+    assert call_fwd(shape(B=1 << 20, H=1 << 20)) == E_SHAPE
+    assert call_fwd(shape(dk=96)) == E_UNSUP
+    assert call_fwd(shape(dv=256)) == E_UNSUP
+    assert call_fwd(shape(chunk=32)) == E_UNSUP
+    assert call_fwd(shape(), q=None) == E_NULL
+    assert call_fwd(shape(), o=None) == E_NULL
+    assert call_fwd(shape(), ws=None) == E_WS
+    assert call_fwd(shape(), ws_bytes=1000) == E_WS
+    assert call_fwd(shape(), ws=ctypes.c_void_p(0x100010)) == E_WS
+    # nothing to do: no sequences at all
+    assert call_fwd(shape(B=0), q=None, f=None, v=None, o=None, ws=None, ws_bytes=0) == OK
+
+
+def test_bwd_argument_errors():
+    assert call_bwd(None) == E_NULL
+    assert call_bwd(shape(io=0)) == E_UNSUP          # fp32 storage: forward and step only
+    assert call_bwd(shape(dk=32)) == E_UNSUP
+    assert call_bwd(shape(), go=None) == E_NULL
+    assert call_bwd(shape(), gf=None) == E_NULL
+    one = binding.hgrn2_fwd_workspace_bytes(shape())
+    assert call_bwd(shape(), ws_bytes=2 * one - 1) == E_WS
+    assert call_bwd(shape(B=0), q=None, f=None, v=None, go=None, gq=None, gf=None, gv=None, ws=None, ws_bytes=0) == OK
+
+
+def test_step_argument_errors():
+    step = binding.lib().hgrn2_step
+    assert step(-1, 1, 64, 64, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
+    assert step(1, 1, 64, 64, 3, 1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_SHAPE
+    assert step(1, 1, 48, 64, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_UNSUP
+    assert step(1, 1, 64, 64, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None) == E_NULL
+    assert step(0, 4, 64, 64, 1, 1, None, None, None, None, None, None) == OK
+
+
+def test_stage_entry_point_errors():
+    lib = binding.lib()
+    s = shape()
+    assert lib.hgrn2_state_sweep(ctypes.byref(s), 5, FAKE, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_SHAPE
+    assert lib.hgrn2_state_sweep(ctypes.byref(s), 2, None, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_NULL
+    assert lib.hgrn2_state_sweep(ctypes.byref(s), 0, None, FAKE, FAKE, None, None, FAKE_WS, 10, None) == E_WS
+    s32 = shape(io=0, gate=0)
+    assert lib.hgrn2_state_sweep(ctypes.byref(s32), 1, None, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_UNSUP
+    assert lib.hgrn2_fwd_readout(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, None) == E_NULL
+    assert lib.hgrn2_bwd_chunk_grads(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE_WS, ctypes.c_void_p(0x100008),
+                                     FAKE, FAKE, FAKE, None) == E_WS
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError):
+        binding.lib()
