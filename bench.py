@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--decode-steps", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
 
@@ -98,6 +101,14 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = tokens / (ms_per_step * 1e-3)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- per-stage durations with HIP events on the stream the kernels run on ----
     half = ws.numel() // 2
