@@ -143,6 +143,14 @@ def main():
         q, f, v, dO = sets[i % 2]
         binding.hgrn2_bwd_chunk_grads(shape, q, f, v, dO, ws_a, ws_b, gq, gf, gv)
 
+    def s_whole_fwd(i):
+        q, f, v, _ = sets[i % 2]
+        binding.hgrn2_fwd(q, f, v, None, o=o, hT=hT, workspace=ws)
+
+    def s_whole_bwd(i):
+        q, f, v, dO = sets[i % 2]
+        binding.hgrn2_bwd(q, f, v, dO, None, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv)
+
     el = 2  # bytes per bf16 element
     state_bytes = B * H * (N // CHUNK) * D * D * el
     seq_k = token_heads * D * el
@@ -155,7 +163,15 @@ def main():
         ("state_sweep_grad", s_grad, 3 * seq_k),           # q, f, dO
         ("bwd_chunk_grads", s_chunk, 7 * seq_k),           # q, f, v, dO -> dq, df, dv (1792 B / token-head)
     ]
+    calls = [("hgrn2_fwd", s_whole_fwd, 4 * seq_k), ("hgrn2_bwd", s_whole_bwd, 7 * seq_k)]
     stage_out = {}
+    call_out = {}
+    for name, fn, abytes in calls:
+        for i in range(2):
+            fn(i)
+        dt = timed(fn)
+        call_out[name] = {"us": round(dt * 1e6, 2), "algorithmic_GB": round(abytes / 1e9, 4),
+                          "GBps": round(abytes / dt / 1e9, 1)}
     for name, fn, abytes in stages:
         for i in range(2):
             fn(i)
@@ -184,6 +200,7 @@ def main():
                  "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 5)},
         "hbm_step": {"algorithmic_GBps": round(io_bytes / (ms_per_step * 1e-3) / 1e9, 1),
                      "frac": round(io_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+        "calls": call_out,
         "stages": stage_out,
     }
 

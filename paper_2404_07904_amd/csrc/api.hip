@@ -68,6 +68,8 @@ int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (d.BH == 0) return HGRN2_OK;
     if (!has_tokens && !hT) return HGRN2_OK;
+    if (fwd_fused_supported(d))
+        return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
     if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, workspace, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
@@ -89,8 +91,7 @@ int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void
     if (!has_tokens && !grad_h0) return HGRN2_OK;
     void* ws_s = workspace;
     void* ws_ds = static_cast<char*>(workspace) + one;
-    if (has_tokens && launch_sweep(d, kSweepStateBwd, q, f, v, h0, nullptr, ws_s, stream) != hipSuccess) return HGRN2_ERR_HIP;
-    if (launch_sweep(d, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (has_tokens &&
         launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;

@@ -85,19 +85,35 @@ template <int RW>
 __device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, size_t seq_off, int row_stride,
                                           int col, int row0, int n_rows, bool is_bf16)
 {
+    // A block that lies fully inside the sequence (every block but possibly the last) needs one
+    // address; its rows are compile-time offsets from it.  Only a ragged block clamps per row.
+    const bool full = row0 + RW <= n_rows;
     if (is_bf16) {
         const char* b = static_cast<const char*>(base) + (seq_off + col) * 2;
+        if (full) {
+            const char* b0 = b + (size_t)row0 * row_stride * 2;
 #pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const int rc = min(row0 + i, n_rows - 1);
-            out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(b + (size_t)rc * row_stride * 2));
+            for (int i = 0; i < RW; ++i)
+                out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(b0 + i * row_stride * 2));
+        } else {
+#pragma unroll
+            for (int i = 0; i < RW; ++i) {
+                const int rc = min(row0 + i, n_rows - 1);
+                out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(b + (size_t)rc * row_stride * 2));
+            }
         }
     } else {
         const char* b = static_cast<const char*>(base) + (seq_off + col) * 4;
+        if (full) {
+            const char* b0 = b + (size_t)row0 * row_stride * 4;
 #pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const int rc = min(row0 + i, n_rows - 1);
-            out.r[i] = *reinterpret_cast<const f32x2*>(b + (size_t)rc * row_stride * 4);
+            for (int i = 0; i < RW; ++i) out.r[i] = *reinterpret_cast<const f32x2*>(b0 + i * row_stride * 4);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RW; ++i) {
+                const int rc = min(row0 + i, n_rows - 1);
+                out.r[i] = *reinterpret_cast<const f32x2*>(b + (size_t)rc * row_stride * 4);
+            }
         }
     }
 }
@@ -106,6 +122,7 @@ template <int RW>
 __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>& raw, int row0, int n_rows,
                                              bool lane_active, bool is_bf16, float fill)
 {
+    const bool all_rows = row0 + RW <= n_rows;      // wave-uniform: only the last chunk can be ragged
 #pragma unroll
     for (int i = 0; i < RW; ++i) {
         f32x2 x = raw.r[i];
@@ -114,9 +131,15 @@ __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>
             x.x = __uint_as_float(u << 16);
             x.y = __uint_as_float(u & 0xffff0000u);
         }
-        const bool ok = lane_active && (row0 + i < n_rows);
-        dst[i].x = ok ? x.x : fill;
-        dst[i].y = ok ? x.y : fill;
+        dst[i] = x;
+    }
+    if (!all_rows || !lane_active) {
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const bool ok = lane_active && (row0 + i < n_rows);
+            dst[i].x = ok ? dst[i].x : fill;
+            dst[i].y = ok ? dst[i].y : fill;
+        }
     }
 }
 
@@ -268,6 +291,24 @@ __device__ __forceinline__ BlockDecay block_decay(const float* tot, int D, int w
     r.post = (w == 3) ? 1.0f : (w == 2) ? t3 : (w == 1) ? t2 * t3 : t1 * t2 * t3;
     r.mid = (w == 0) ? t1 : (w == 3) ? t2 : 1.0f;
     r.all = (t0 * t1) * (t2 * t3);
+    return r;
+}
+
+// The same for NW row blocks (one per wave): products of the block totals before / after block w,
+// between block w and the mid-chunk reference row, and over the whole chunk.
+template <int NW> __device__ __forceinline__ BlockDecay block_decay_n(const float* tot, int D, int w, int ch)
+{
+    BlockDecay r;
+    r.pre = 1.0f; r.post = 1.0f; r.mid = 1.0f; r.all = 1.0f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        const float t = tot[i * D + ch];
+        r.all *= t;
+        r.pre *= (i < w) ? t : 1.0f;
+        r.post *= (i > w) ? t : 1.0f;
+        const bool between = (w >= NW / 2) ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
+        r.mid *= between ? t : 1.0f;
+    }
     return r;
 }
 

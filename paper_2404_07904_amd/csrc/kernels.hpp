@@ -34,9 +34,21 @@ enum SweepMode {
 hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
                         const float* init_state, float* final_state, void* ws, hipStream_t stream);
 
+// Both sweeps of the backward pass (kSweepStateBwd into ws_state, kSweepGrad into ws_dstate) in
+// one launch.
+hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                             const float* h0, const float* grad_hT, float* grad_h0, void* ws_state,
+                             void* ws_dstate, hipStream_t stream);
+
 // Per-chunk forward read-out  O = tril(Q~ K~^T) V + (Q G) S_n.
 hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,
                           void* o, hipStream_t stream);
+
+// Fused forward (state recurrence + read-out in one pass, states never leave the chip); only for
+// the shapes fwd_fused_supported() accepts.
+bool fwd_fused_supported(const SeqDims& d);
+hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, const void* v, const float* h0,
+                            void* o, float* hT, hipStream_t stream);
 
 // Per-chunk gradients dq, df, dv from the two state sweeps.
 hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,

@@ -23,10 +23,19 @@ struct SweepParams {
     float* fin;
     void* ws;
     int BH, N, NC, n_tile, gate_bf16;
+#ifdef HGRN2_PHASE_TIMING
+    long long* dbg;      // [workgroup][wave][8] accumulated clock ticks per phase (diagnostic builds only)
+#endif
 };
 
+#ifdef HGRN2_PHASE_TIMING
+#define HGRN2_STAMP(k) do { const long long t_now = wall_clock64(); ph[k] += t_now - t_prev; t_prev = t_now; } while (0)
+#else
+#define HGRN2_STAMP(k) do { } while (0)
+#endif
+
 template <typename T, int DK, int DV, int TV, int MODE>
-__global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
+__device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 {
     constexpr int C = kChunk, RW = C / kWaves;
     constexpr int PC = C + pad_elems<T>();
@@ -43,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
     float* tot = gam + DK;                       // [4][DK] per-wave block products
 
     int bh, tile;
-    xcd_map(blockIdx.x, p.n_tile, bh, tile);
+    xcd_map(block_id, p.n_tile, bh, tile);
     if (bh >= p.BH) return;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
@@ -83,6 +92,10 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
 
     if (p.NC > 0) load_chunk(REVERSE ? p.NC - 1 : 0);
 
+#ifdef HGRN2_PHASE_TIMING
+    long long ph[8] = {0};
+    long long t_prev = wall_clock64();
+#endif
     for (int it = 0; it < p.NC; ++it) {
         const int n = REVERSE ? p.NC - 1 - it : it;
         f32x2 rf[RW], rq[RW], rb[RW];
@@ -107,7 +120,9 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
             tot[w * DK + 2 * lane] = a0[RW - 1];
             tot[w * DK + 2 * lane + 1] = a1[RW - 1];
         }
+        HGRN2_STAMP(0);
         __syncthreads();
+        HGRN2_STAMP(1);
         if (a_act) {
             const BlockDecay d0 = block_decay(tot, DK, w, 2 * lane);
             const BlockDecay d1 = block_decay(tot, DK, w, 2 * lane + 1);
@@ -133,8 +148,11 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
             store_run<T, RW>(BT + (2 * lane) * PC + RW * w, x0);
             store_run<T, RW>(BT + (2 * lane + 1) * PC + RW * w, x1);
         }
+        HGRN2_STAMP(2);
         if (it + 1 < p.NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
+        HGRN2_STAMP(3);
         __syncthreads();
+        HGRN2_STAMP(4);
 
         // ---- hand the slab as it stands (state entering / gradient leaving chunk n) to the workspace
         T* wsn = ws + (size_t)n * DK * DV;
@@ -151,6 +169,7 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
             }
         }
 
+        HGRN2_STAMP(5);
         // ---- slab = Diag(g) slab + A^T B over the chunk ----
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
@@ -179,8 +198,13 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
                 else       M::mma(acc[j], fa, fb);
             }
         }
+        HGRN2_STAMP(6);
     }
 
+#ifdef HGRN2_PHASE_TIMING
+    if (lane == 0 && p.dbg)
+        for (int k = 0; k < 8; ++k) p.dbg[((size_t)block_id * kWaves + w) * 8 + k] = ph[k];
+#endif
     if (p.fin) {
         float* s1 = p.fin + (size_t)bh * DK * DV;
 #pragma unroll
@@ -193,6 +217,50 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
             }
         }
     }
+}
+
+template <typename T, int DK, int DV, int TV, int MODE>
+__global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
+{
+    sweep_body<T, DK, DV, TV, MODE>(p, blockIdx.x);
+}
+
+// The two sweeps of the backward pass (forward states, reverse state gradients) are independent;
+// one launch runs both, the first half of the grid walking forwards and the second backwards, so
+// that two latency-bound sequential kernels share the chip instead of running one after the other.
+template <typename T, int DK, int DV, int TV>
+__global__ __launch_bounds__(kThreads) void sweep_pair_kernel(SweepParams ps, SweepParams pg, int half)
+{
+    if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd>(ps, blockIdx.x);
+    else                        sweep_body<T, DK, DV, TV, kSweepGrad>(pg, blockIdx.x - half);
+}
+
+template <typename T, int DK, int DV, int TV>
+static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, const SweepParams& pg0, hipStream_t stream)
+{
+    SweepParams ps = ps0, pg = pg0;
+    ps.n_tile = pg.n_tile = DV / TV;
+    constexpr int PC = kChunk + pad_elems<T>();
+    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(1 + kWaves) * DK * sizeof(float);
+    auto kern = sweep_pair_kernel<T, DK, DV, TV>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const int half = (d.BH + 7) / 8 * 8 * ps.n_tile;
+    hipLaunchKernelGGL(kern, dim3(2 * half), dim3(kThreads), lds, stream, ps, pg, half);
+    return hipGetLastError();
+}
+
+template <typename T, int DK, int DV>
+static hipError_t launch_pair_tv(const SeqDims& d, const SweepParams& ps, const SweepParams& pg, hipStream_t stream)
+{
+    if constexpr (DV == 128 && DK == 128) {
+        if (d.BH < 96) return launch_pair_one<T, DK, DV, 32>(d, ps, pg, stream);
+    }
+    if constexpr (DV == 128) {
+        if (d.BH < 256) return launch_pair_one<T, DK, DV, 64>(d, ps, pg, stream);
+    }
+    return launch_pair_one<T, DK, DV, DV>(d, ps, pg, stream);
 }
 
 template <typename T, int DK, int DV, int TV, int MODE>
@@ -250,6 +318,24 @@ hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const v
     } else {
         if (mode == kSweepStateFwd) return launch_dims<float, kSweepStateFwd>(d, p, stream);
     }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                             const float* h0, const float* grad_hT, float* grad_h0, void* ws_state,
+                             void* ws_dstate, hipStream_t stream)
+{
+    if (d.BH == 0) return hipSuccess;
+    if (!d.io_bf16) return hipErrorInvalidValue;
+    SweepParams ps, pg;
+    ps.q = nullptr; ps.f = f; ps.bsrc = v; ps.init = h0; ps.fin = nullptr; ps.ws = ws_state;
+    pg.q = q; pg.f = f; pg.bsrc = grad_o; pg.init = grad_hT; pg.fin = grad_h0; pg.ws = ws_dstate;
+    ps.BH = pg.BH = d.BH; ps.N = pg.N = d.N; ps.NC = pg.NC = d.NC; ps.n_tile = pg.n_tile = 1;
+    ps.gate_bf16 = pg.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64>(d, ps, pg, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_pair_tv<__bf16, 64, 128>(d, ps, pg, stream);
     return hipErrorInvalidValue;
 }
 

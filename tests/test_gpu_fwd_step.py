@@ -97,6 +97,30 @@ def test_fwd_split_handoff():
     check("hT", host(h2), host(hT), 1e-5)
 
 
+@pytest.mark.parametrize("N", [1, 64, 203, 448])
+@pytest.mark.parametrize("gate", ["bf16", "f32"])
+def test_fwd_fused_path(N, gate):
+    """B*H >= 64 at d = 128 takes the single-pass kernel (state kept on chip)."""
+    print("\n[fwd fused] B*H=72 N=%d gate=%s" % (N, gate), flush=True)
+    w = synth.make_sequence(500 + N, 8, 9, N, 128, 128, io_dtype="bf16", gate_dtype=gate, lb=0.1, with_h0=True)
+    run_fwd(w)
+
+
+def test_fwd_fused_matches_two_kernel_path():
+    """The single-pass kernel and sweep + read-out agree to bf16 rounding on the same inputs."""
+    w = synth.make_sequence(77, 8, 8, 300, 128, 128, io_dtype="bf16", lb=0.3, with_h0=True)
+    q, f, v, h0 = dev(w.q, "bf16"), dev(w.f, "bf16"), dev(w.v, "bf16"), dev(w.h0)
+    o1, hT1 = binding.hgrn2_fwd(q, f, v, h0)
+    shape = binding.make_shape(q, v, f)
+    ws = torch.empty(binding.hgrn2_fwd_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    o2, hT2 = torch.empty_like(o1), torch.empty_like(hT1)
+    binding.hgrn2_state_sweep(shape, binding.SWEEP_STATE_FWD, None, f, v, ws, h0, hT2)
+    binding.hgrn2_fwd_readout(shape, q, f, v, ws, o2)
+    torch.cuda.synchronize()
+    check("o", host(o1), host(o2), 8e-3)
+    check("hT", host(hT1), host(hT2), 1e-5)
+
+
 # ------------------------------------------------------------------------------------ step
 @pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (64, 128), (128, 64)])
 @pytest.mark.parametrize("io", ["bf16", "f32"])
