@@ -76,10 +76,11 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     static constexpr size_t dpt = pt + (size_t)C * PC * sizeof(T);          // dP^T [C][PC]
     static constexpr size_t tot = dpt + (size_t)C * PC * sizeof(T);         // [8][DK] fp32 block products
     static constexpr size_t rp = tot + (size_t)kBwdWaves * DK * sizeof(float);   // [DK] fp32  g * rowsum(dS * S_n)
-    static constexpr size_t blk = rp + (size_t)DK * sizeof(float);               // [2][8][DK] fp32 block sums
-    static constexpr size_t dvs = blk + (size_t)2 * kBwdWaves * DK * sizeof(float);   // dv staging [C][PV]
+    static constexpr size_t blk = rp + (size_t)DK * sizeof(float);               // [8][DK] fp32 block sums of e
+    static constexpr size_t ys = blk + (size_t)kBwdWaves * DK * sizeof(float);   // [2][DK] fp32 column sums per row tile
+    static constexpr size_t dvs = ys + (size_t)2 * DK * sizeof(float);           // dv staging [C][PV]
     static constexpr size_t total = dvs + (size_t)C * PV * sizeof(T);
-    // phase 2 (aliases the operand tiles): fp32 staging of two accumulator sets at a time
+    // phase 2 (aliases the operand tiles): fp32 staging of X and Y
     static constexpr size_t cq = 0;                                         // [C][PF] fp32
     static constexpr size_t ck = cq + (size_t)C * PF * sizeof(float);       // [C][PF] fp32
     static_assert(ck + (size_t)C * PF * sizeof(float) <= tot, "staging must fit in the operand and P tiles");
@@ -107,52 +108,75 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     float* Rp = reinterpret_cast<float*>(smem + L::rp);
     float* blkE = reinterpret_cast<float*>(smem + L::blk);     // [8][DK] block sums of e
-    float* blkY = blkE + NW * DK;                               // [8][DK] block sums of y
+    float* Ys = reinterpret_cast<float*>(smem + L::ys);       // [2][DK]
     float* cQ = reinterpret_cast<float*>(smem + L::cq);
     float* cK = reinterpret_cast<float*>(smem + L::ck);
     T* dVs = reinterpret_cast<T*>(smem + L::dvs);
 
-    const int n = blockIdx.x % p.NC, bh = blockIdx.x / p.NC;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK, v_act = 2 * lane < DV;
-    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     const T* dog = static_cast<const T*>(p.dO);
-    const size_t slot = ((size_t)bh * p.NC + n) * DK * DV;
-    const T* wsS = static_cast<const T*>(p.ws_s) + slot;
-    const T* wsD = static_cast<const T*>(p.ws_ds) + slot;
+    const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
 
     // tile ownership (a wave without a tile of a kind skips that work)
     const bool has_a = w < NRT * NAT, has_b = w < NRT * NBT;
     const int rt_a = has_a ? w / NAT : 0, at = w % NAT;     // (row tile, channel tile) of dq / dk
     const int rt_b = has_b ? w / NBT : 0, bt = w % NBT;     // (row tile, column tile) of dv
 
+    // Everything one chunk needs from global memory: the raw rows of f, q, v, dO of this wave's row
+    // block and the state fragments of channel tile `at` (operand B[k = dv index][n = channel]).
+    // The workgroup is persistent: it walks the chunks blockIdx.x, blockIdx.x + gridDim.x, ... and
+    // issues the row loads of its next chunk as soon as the matrix stage of the current one is
+    // done, so that they fly during the element-wise epilogue; the state fragments are requested
+    // at the top of a chunk and are not needed before its own element-wise stage is over.
+    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, RawRows<RW>& cv, RawRows<RW>& cdo, int chunk) {
+        const int cn = chunk % p.NC, cbh = chunk / p.NC;
+        const size_t sk_ = (size_t)cbh * p.N * DK, sv_ = (size_t)cbh * p.N * DV;
+        const int r0 = cn * C + RW * w;
+        load_rows<RW>(cf, p.f, sk_, DK, col_k, r0, p.N, gate_bf16);
+        load_rows<RW>(cq, qg, sk_, DK, col_k, r0, p.N, is_bf16_type<T>());
+        load_rows<RW>(cv, vg, sv_, DV, col_v, r0, p.N, is_bf16_type<T>());
+        load_rows<RW>(cdo, dog, sv_, DV, col_v, r0, p.N, is_bf16_type<T>());
+    };
+    auto load_chunk_states = [&](frag (&cS)[2 * NBT], frag (&cD)[2 * NBT], int chunk) {
+        const size_t slot = (size_t)chunk * DK * DV;
+        const T* wsS = static_cast<const T*>(p.ws_s) + slot;
+        const T* wsD = static_cast<const T*>(p.ws_ds) + slot;
+#pragma unroll
+        for (int kk = 0; kk < 2 * NBT; ++kk) {
+            cS[kk] = *reinterpret_cast<const frag*>(wsS + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
+            cD[kk] = *reinterpret_cast<const frag*>(wsD + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
+        }
+    };
+
+    const int n_chunks = p.BH * p.NC;
+    RawRows<RW> raw_f, raw_q, raw_v, raw_d;
+    frag sS[2 * NBT], sD[2 * NBT];
+    if ((int)blockIdx.x < n_chunks) load_chunk_rows(raw_f, raw_q, raw_v, raw_d, blockIdx.x);
+
+  for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+    // Re-derive the lane-dependent indices inside the loop from a value the compiler cannot see
+    // through: otherwise it hoists dozens of loop-invariant LDS addresses out of the loop, keeps
+    // them in registers across the whole body and spills.
+    int lane_opaque = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane_opaque));
+    const int lane = lane_opaque, r32 = lane & 31, g = lane >> 5;
+    const int n = chunk % p.NC, bh = chunk / p.NC;
+    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    load_chunk_states(sS, sD, chunk);      // first needed two barriers from here; covered by the element-wise stage
+
 #ifdef HGRN2_PHASE_TIMING
     long long ph[24] = {0};
     long long t_prev = wall_clock64();
 #endif
-    // ---------------- loads ----------------
-    // state fragments of channel tile `at`: operand B[k = dv index][n = channel], 2*NBT k-steps
-    frag sS[2 * NBT], sD[2 * NBT];
-#pragma unroll
-    for (int kk = 0; kk < 2 * NBT; ++kk) {
-        sS[kk] = *reinterpret_cast<const frag*>(wsS + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
-        sD[kk] = *reinterpret_cast<const frag*>(wsD + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
-    }
     // rf/rq are re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
-    RawRows<RW> raw_f, raw_q;
     const int row0 = n * C + RW * w;
     f32x2 rf[RW], rq[RW];
     {
         f32x2 rv[RW], rd[RW];
-        RawRows<RW> raw_v, raw_d;
-        const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
-        load_rows<RW>(raw_f, p.f, seq_k, DK, col_k, row0, p.N, gate_bf16);
-        load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_v, vg, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_d, dog, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
         convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
         convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
         convert_rows<RW>(rv, raw_v, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
@@ -177,7 +201,6 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
         if (w >= NW / 2) { sq0 = m0; sq1 = m1; sk0 = i0; sk1 = i1; }
         else             { sk0 = m0; sk1 = m1; sq0 = i0; sq1 = i1; }
     };
-    float hp0 = 0.0f, hp1 = 0.0f, hq0 = 0.0f, hq1 = 0.0f;     // G_m and g / G_m of this lane's channel pair
     {
         float pr0[RW], pr1[RW], t0 = 1.0f, t1 = 1.0f;
         if (w >= NW / 2) {
@@ -195,18 +218,18 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
         __syncthreads();
         HGRN2_STAMP(1);
         if (k_act) {
-            const BlockDecay d0 = block_decay_n<NW>(tot, DK, w, 2 * lane);
-            const BlockDecay d1 = block_decay_n<NW>(tot, DK, w, 2 * lane + 1);
-            hp0 = 1.0f; hp1 = 1.0f;
+            // product of the block totals between this block and the reference row
+            float mid0 = 1.0f, mid1 = 1.0f;
 #pragma unroll
-            for (int i = 0; i < NW / 2; ++i) { hp0 *= tot[i * DK + 2 * lane]; hp1 *= tot[i * DK + 2 * lane + 1]; }
-            hq0 = 1.0f; hq1 = 1.0f;
-#pragma unroll
-            for (int i = NW / 2; i < NW; ++i) { hq0 *= tot[i * DK + 2 * lane]; hq1 *= tot[i * DK + 2 * lane + 1]; }
+            for (int i = 0; i < NW; ++i) {
+                const bool between = (w >= NW / 2) ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
+                mid0 *= between ? tot[i * DK + 2 * lane] : 1.0f;
+                mid1 *= between ? tot[i * DK + 2 * lane + 1] : 1.0f;
+            }
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
                 const int row = RW * w + i;
-                mm0[i] = d0.mid * pr0[i]; mm1[i] = d1.mid * pr1[i];
+                mm0[i] = mid0 * pr0[i]; mm1[i] = mid1 * pr1[i];
                 float sq0, sq1, sk0, sk1;
                 scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
                 store_pair_t<T>(Qm, (size_t)row * PK + 2 * lane, rq[i].x * sq0, rq[i].y * sq1);
@@ -217,31 +240,27 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             for (int i = 0; i < RW; ++i) { mm0[i] = 1.0f; mm1[i] = 1.0f; }
         }
     }
-    // outgoing state gradient of channel tile `at`, scaled by H_m, -> LDS, row-major [channel][dv index];
-    // and g * rowsum(dS * S_n).  Done once per channel tile, by the waves of row tile 0.
+    // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv index] (the fragments hold
+    // it already scaled and rounded: their bits go to LDS as they are), and
+    // R = rowsum((H_m dS) * (G_m S_n)) = g * rowsum(dS * S_n).  Once per channel tile (row tile 0).
     if (w < NAT) {
         const int ch = 32 * at + r32;
-        float hq = 1.0f, hp = 1.0f;
-#pragma unroll
-        for (int i = 0; i < NW / 2; ++i) { hp *= tot[i * DK + ch]; hq *= tot[(NW / 2 + i) * DK + ch]; }
         float rs = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
             T* row = dSm + (size_t)ch * PV + 16 * kk + 4 * g;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) rs += M::get(sS[kk], s) * M::get(sD[kk], s);
             float x[8];
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const float d = M::get(sD[kk], s);
-                rs += M::get(sS[kk], s) * d;
-                x[s] = d * hq;
-            }
+            for (int s = 0; s < 8; ++s) x[s] = M::get(sD[kk], s);
             store_pair_t<T>(row, 0, x[0], x[1]);
             store_pair_t<T>(row, 2, x[2], x[3]);
             store_pair_t<T>(row, 8, x[4], x[5]);
             store_pair_t<T>(row, 10, x[6], x[7]);
         }
         rs += __shfl_xor(rs, 32);
-        if (g == 0) Rp[ch] = (hp * hq) * rs;
+        if (g == 0) Rp[ch] = rs;
     }
     HGRN2_STAMP(2);
     __syncthreads();
@@ -315,35 +334,56 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
         for (int v = 0; v < 16; ++v)
             dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PV + 32 * bt + r32] = (T)(aV[v] + aV2[v]);
     }
-    // aQ = dP K~, aQs = dO S_n^T, aK = dP^T Q~, aKs = V dS^T for the tile (rt_a, at)
-    f32x16 aQ, aQs, aK, aKs;
+    // tile (rt_a, at):  X = dP K~ + dO (G_m S_n)^T,  Y = dP^T Q~ + V (H_m dS)^T.  The second part of Y
+    // is accumulated on its own first, because sum_j K~_j * (V (H_m dS)^T)_j over ALL rows of the chunk
+    // (the R-like term of the gate gradient, see the epilogue) is taken from it.
+    f32x16 aX, aY;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { aQ[v] = 0.0f; aQs[v] = 0.0f; aK[v] = 0.0f; aKs[v] = 0.0f; }
+    for (int v = 0; v < 16; ++v) { aX[v] = 0.0f; aY[v] = 0.0f; }
     if (has_a) {
+        f32x16 aKs;
 #pragma unroll
-        for (int ks = 0; ks < 2 * NRT; ++ks) {
-            M::mma(aQ, M::load_kmajor(dPt, PC, 16 * ks, 32 * rt_a, lane), M::load_kmajor(Km, PK, 16 * ks, 32 * at, lane));
-            M::mma(aK, M::load(dPt + (32 * rt_a + r32) * PC + 16 * ks + 8 * g), M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane));
-        }
+        for (int v = 0; v < 16; ++v) aKs[v] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
             const T* drow = dOm + (32 * rt_a + r32) * PV + 16 * kk + 4 * g;
             const T* vrow = Vm + (32 * rt_a + r32) * PV + 16 * kk + 4 * g;
-            M::mma(aQs, M::load2(drow, drow + 8), sS[kk]);
+            M::mma(aX, M::load2(drow, drow + 8), sS[kk]);
             M::mma(aKs, M::load2(vrow, vrow + 8), sD[kk]);
         }
+        float ys = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            ys += (float)Km[(size_t)(32 * rt_a + acc_row(v, lane)) * PK + 32 * at + r32] * aKs[v];
+        ys += __shfl_xor(ys, 32);
+        if (g == 0) Ys[rt_a * DK + 32 * at + r32] = ys;
+#pragma unroll
+        for (int ks = 0; ks < 2 * NRT; ++ks) {
+            M::mma(aX, M::load_kmajor(dPt, PC, 16 * ks, 32 * rt_a, lane), M::load_kmajor(Km, PK, 16 * ks, 32 * at, lane));
+            M::mma(aY, M::load(dPt + (32 * rt_a + r32) * PC + 16 * ks + 8 * g), M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) aY[v] += aKs[v];
     }
+    // next chunk of this workgroup: its row loads are in flight during the staging / epilogue below
+    // (and this chunk's own f, q rows again, for the epilogue: re-reading 8 cached rows is cheaper
+    // than holding them in registers across the matrix stage)
+    RawRows<RW> nxt_f, nxt_q;
+    const bool has_next = chunk + (int)gridDim.x < n_chunks;
+    load_rows<RW>(raw_f, p.f, seq_k, DK, col_k, row0, p.N, gate_bf16);
+    load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
+    if (has_next) load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, chunk + gridDim.x);   // v, dO of this chunk are dead
     HGRN2_STAMP(6);
     __syncthreads();     // every wave is done with the operand tiles
     HGRN2_STAMP(7);
 
-    // ---------------- round 1 staging: aQ, aQs as [row][channel] fp32 ----------------
+    // ---------------- staging: X, Y as [row][channel] fp32 ----------------
     if (has_a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const size_t o = (size_t)(32 * rt_a + acc_row(v, lane)) * PF + 32 * at + r32;
-            cQ[o] = aQ[v];
-            cK[o] = aQs[v];
+            cQ[o] = aX[v];
+            cK[o] = aY[v];
         }
     }
     HGRN2_STAMP(8);
@@ -351,30 +391,37 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     HGRN2_STAMP(9);
 
     // ---------------- element-wise epilogue in the row-block / channel-pair layout ----------------
-    // e = pair terms + incoming-state term of dL (summed as a suffix), y = outgoing-state term
-    // (summed as an exclusive prefix); see the header comment.
+    //   dq = sq X,  dk = sk Y,  e = bf16(Q~) X - bf16(K~) Y   (with the values the MFMAs consumed)
+    //   dg_s = sum_{i >= s in chunk} e_i + sum_{all j in chunk} K~_j (V (H_m dS)^T)_j + R
+    // In e the pair terms of X and Y cancel to fp32 accuracy; the outgoing-state part of Y that e
+    // subtracts for rows >= s is added back for ALL rows from the very same products, so what remains
+    // of it is the exact prefix over j < s (see the header comment).
     float e0[RW], e1[RW], dk0[RW], dk1[RW];
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
     convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
     convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
     if (k_act) {
+        float se0 = 0.0f, se1 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < RW; ++i) {
+        for (int i = RW - 1; i >= 0; --i) {
             const int row = RW * w + i;
             const f32x2 xq = *reinterpret_cast<const f32x2*>(cQ + (size_t)row * PF + 2 * lane);
-            const f32x2 xs = *reinterpret_cast<const f32x2*>(cK + (size_t)row * PF + 2 * lane);
+            const f32x2 xk = *reinterpret_cast<const f32x2*>(cK + (size_t)row * PF + 2 * lane);
             float sq0, sq1, sk0, sk1;
             scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
-            const float qs0 = rq[i].x * sq0, qs1 = rq[i].y * sq1;   // exactly what went into Q~
-            const float dq0 = sq0 * (xq.x + hp0 * xs.x), dq1 = sq1 * (xq.y + hp1 * xs.y);
-            e0[i] = (float)(T)qs0 * xq.x + qs0 * (hp0 * xs.x);
-            e1[i] = (float)(T)qs1 * xq.y + qs1 * (hp1 * xs.y);
+            const float qs0 = rq[i].x * sq0, qs1 = rq[i].y * sq1;                       // exactly what went into Q~
+            const float ks0 = (1.0f - rf[i].x) * sk0, ks1 = (1.0f - rf[i].y) * sk1;     // ... and into K~
+            dk0[i] = sk0 * xk.x; dk1[i] = sk1 * xk.y;
+            se0 += (float)(T)qs0 * xq.x - (float)(T)ks0 * xk.x;
+            se1 += (float)(T)qs1 * xq.y - (float)(T)ks1 * xk.y;
+            e0[i] = se0; e1[i] = se1;                                                   // inclusive suffix inside the block
             const int grow = n * C + row;
-            if (grow < p.N) store_pair_t<T>(dqg, seq_k + (size_t)grow * DK + 2 * lane, dq0, dq1);
+            if (grow < p.N) store_pair_t<T>(dqg, seq_k + (size_t)grow * DK + 2 * lane, sq0 * xq.x, sq1 * xq.y);
         }
+        blkE[w * DK + 2 * lane] = se0; blkE[w * DK + 2 * lane + 1] = se1;
     }
-    // coalesced store of dv (staged in round 1)
+    // coalesced store of dv
     {
         constexpr int VEC = 16 / (int)sizeof(T);
         constexpr int VPR = DV / VEC;
@@ -389,62 +436,22 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
         }
     }
     HGRN2_STAMP(10);
-    __syncthreads();     // everyone has read round 1
+    __syncthreads();
     HGRN2_STAMP(12);
-
-    // ---------------- round 2 staging: aK, aKs ----------------
-    if (has_a) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const size_t o = (size_t)(32 * rt_a + acc_row(v, lane)) * PF + 32 * at + r32;
-            cQ[o] = aK[v];
-            cK[o] = aKs[v];
-        }
-    }
-    HGRN2_STAMP(13);
-    __syncthreads();
-    HGRN2_STAMP(14);
-    float y0[RW], y1[RW];
-    if (k_act) {
-        float se0 = 0.0f, se1 = 0.0f, sy0 = 0.0f, sy1 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const int row = RW * w + i;
-            const f32x2 xk = *reinterpret_cast<const f32x2*>(cQ + (size_t)row * PF + 2 * lane);
-            const f32x2 xs = *reinterpret_cast<const f32x2*>(cK + (size_t)row * PF + 2 * lane);
-            float sq0, sq1, sk0, sk1;
-            scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
-            const float ks0 = (1.0f - rf[i].x) * sk0, ks1 = (1.0f - rf[i].y) * sk1;   // what went into K~
-            dk0[i] = sk0 * (xk.x + hq0 * xs.x);
-            dk1[i] = sk1 * (xk.y + hq1 * xs.y);
-            e0[i] -= (float)(T)ks0 * xk.x;
-            e1[i] -= (float)(T)ks1 * xk.y;
-            y0[i] = sy0; y1[i] = sy1;                         // exclusive prefix inside the block
-            sy0 += ks0 * (hq0 * xs.x);
-            sy1 += ks1 * (hq1 * xs.y);
-        }
-#pragma unroll
-        for (int i = RW - 1; i >= 0; --i) { se0 += e0[i]; se1 += e1[i]; e0[i] = se0; e1[i] = se1; }   // inclusive suffix
-        blkE[w * DK + 2 * lane] = se0; blkE[w * DK + 2 * lane + 1] = se1;
-        blkY[w * DK + 2 * lane] = sy0; blkY[w * DK + 2 * lane + 1] = sy1;
-    }
-    HGRN2_STAMP(15);
-    __syncthreads();
-    HGRN2_STAMP(16);
     if (k_act) {
         const int c0 = 2 * lane, c1 = 2 * lane + 1;
-        float add0 = Rp[c0], add1 = Rp[c1];
+        float add0 = Rp[c0] + Ys[c0] + Ys[DK + c0], add1 = Rp[c1] + Ys[c1] + Ys[DK + c1];
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
-            add0 += (ww > w) ? blkE[ww * DK + c0] : (ww < w) ? blkY[ww * DK + c0] : 0.0f;
-            add1 += (ww > w) ? blkE[ww * DK + c1] : (ww < w) ? blkY[ww * DK + c1] : 0.0f;
+            add0 += (ww > w) ? blkE[ww * DK + c0] : 0.0f;
+            add1 += (ww > w) ? blkE[ww * DK + c1] : 0.0f;
         }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
             const int grow = n * C + RW * w + i;
             if (grow < p.N) {
-                const float df0 = (e0[i] + y0[i] + add0) * fast_rcp(fmaxf(rf[i].x, 1e-30f)) - dk0[i];
-                const float df1 = (e1[i] + y1[i] + add1) * fast_rcp(fmaxf(rf[i].y, 1e-30f)) - dk1[i];
+                const float df0 = (e0[i] + add0) * fast_rcp(fmaxf(rf[i].x, 1e-30f)) - dk0[i];
+                const float df1 = (e1[i] + add1) * fast_rcp(fmaxf(rf[i].y, 1e-30f)) - dk1[i];
                 store_pair_t<T>(dfg, seq_k + (size_t)grow * DK + 2 * lane, df0, df1);
             }
         }
@@ -452,8 +459,12 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #ifdef HGRN2_PHASE_TIMING
     HGRN2_STAMP(17);
     if (lane == 0 && p.dbg)
-        for (int k = 0; k < 24; ++k) p.dbg[((size_t)blockIdx.x * NW + w) * 24 + k] = ph[k];
+        for (int k = 0; k < 24; ++k) p.dbg[((size_t)chunk * NW + w) * 24 + k] = ph[k];
 #endif
+    raw_f = nxt_f;
+    raw_q = nxt_q;
+    __syncthreads();     // the staging areas alias the operand tiles the next chunk is about to write
+  }
 }
 
 template <typename T, int DK, int DV>
@@ -464,7 +475,10 @@ static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)d.BH * d.NC)), dim3(kBwdThreads), L::total, stream, p);
+    // one persistent workgroup per CU (the LDS footprint admits no more), each walking its share of chunks
+    const size_t n_chunks = (size_t)d.BH * d.NC;
+    const unsigned grid = (unsigned)(n_chunks < 256 ? n_chunks : 256);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBwdThreads), L::total, stream, p);
     return hipGetLastError();
 }
 

@@ -3,6 +3,8 @@
 //
 //     o_i = sum_{j<=i} ( sum_a q_i[a] k_j[a] prod_{j<s<=i} f_s[a] ) v_j  +  (q_i * G_i) S_n
 //
+// (q_i * G_i) S_n is evaluated as Q~_i (G_m * S_n): the state sweep stores G_m * S_n.
+//
 // The decay between two tokens is factored around the reference row m = C/2:
 //     prod_{j<s<=i} f_s = (G_i / G_m) (G_m / G_j)  ->  P = tril(Q~ K~^T),  Q~ = q G/G_m,  K~ = k G_m/G
 // so every cumulative product spans at most C/2 tokens, and the one that appears as a divisor is
@@ -30,13 +32,12 @@ template <typename T, int DK, int DV> struct FwdOutLds {
     static constexpr int PC = C + pad_elems<T>();
     static constexpr int PO = DV + pad_elems<T>();
     static constexpr size_t qm = 0;                                   // [C][PK]  Q~
-    static constexpr size_t km = qm + (size_t)C * PK * sizeof(T);     // [C][PK]  K~
-    static constexpr size_t qf = km + (size_t)C * PK * sizeof(T);     // [C][PK]  q * G
-    static constexpr size_t vt = qf + (size_t)C * PK * sizeof(T);     // [DV][PC] V transposed
+    static constexpr size_t km = qm + (size_t)C * PK * sizeof(T);     // [C][PK]  K~, later [C][PO] output staging
+    static constexpr size_t ost = km;
+    static constexpr size_t vt = km + (size_t)C * (PK > PO ? PK : PO) * sizeof(T);   // [DV][PC] V transposed
     static constexpr size_t pm = vt + (size_t)DV * PC * sizeof(T);    // [C][PC]  P
     static constexpr size_t tot = pm + (size_t)C * PC * sizeof(T);    // [4][DK] fp32
     static constexpr size_t total = tot + (size_t)kWaves * DK * sizeof(float);
-    static_assert(2 * C * PK >= C * PO, "output staging must fit in the Q~/K~ tiles");
 };
 
 template <typename T, int DK, int DV>
@@ -51,11 +52,10 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
     extern __shared__ __align__(16) char smem[];
     T* Qm = reinterpret_cast<T*>(smem + L::qm);
     T* Km = reinterpret_cast<T*>(smem + L::km);
-    T* Qf = reinterpret_cast<T*>(smem + L::qf);
     T* Vt = reinterpret_cast<T*>(smem + L::vt);
     T* Pm = reinterpret_cast<T*>(smem + L::pm);
     float* tot = reinterpret_cast<float*>(smem + L::tot);
-    T* Ost = Qm;   // output staging aliases Q~/K~ once P has been formed
+    T* Ost = reinterpret_cast<T*>(smem + L::ost);   // output staging aliases K~ once P has been formed
 
     const int n = blockIdx.x % p.NC, bh = blockIdx.x / p.NC;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
@@ -124,7 +124,6 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
             }
             store_pair_t<T>(Qm, (size_t)row * PK + 2 * lane, qs0, qs1);
             store_pair_t<T>(Km, (size_t)row * PK + 2 * lane, ks0, ks1);
-            store_pair_t<T>(Qf, (size_t)row * PK + 2 * lane, rq[i].x * (d0.pre * a0[i]), rq[i].y * (d1.pre * a1[i]));
         }
     }
     if (v_act) {
@@ -183,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
             // k-slot order of the state fragments: rows 16ks + {4g..4g+3, 8+4g..8+4g+3}
-            const T* qrow = Qf + (32 * rt + r32) * PK + 16 * ks + 4 * g;
+            const T* qrow = Qm + (32 * rt + r32) * PK + 16 * ks + 4 * g;
             const typename M::frag fa = M::load2(qrow, qrow + 8);
             M::mma(acc, fa, sfrag[ks]);
         }

@@ -6,9 +6,10 @@
 //
 // with g_n the product of all gates of chunk n.  One workgroup owns a [dk x TV] column slab of
 // the state of one (batch, head) and walks the chunks in order (reverse order for the gradient),
-// keeping the slab in fp32 MFMA accumulators.  Before each update it writes the slab, rounded to
-// the operand type, to the workspace in MFMA-fragment order so that the per-chunk kernels can
-// load it straight into operand registers.  The contraction runs over time, so both operands are
+// keeping the slab in fp32 MFMA accumulators.  Before each update it writes the slab, scaled by
+// the half-chunk gate product its consumer would apply anyway (G_m of chunk n for S_n, g/G_m for
+// dS_{n+1}) and rounded to the operand type, to the workspace in MFMA-fragment order so that the
+// per-chunk kernels can load it straight into operand registers.  The contraction runs over time, so both operands are
 // staged in LDS token-contiguous (see common.hpp for the thread layout that makes this free).
 #include "common.hpp"
 #include "kernels.hpp"
@@ -50,6 +51,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     T* BT = AT + DK * PC;                        // [TV][PC]  b-side operand, token-contiguous
     float* gam = reinterpret_cast<float*>(BT + TV * PC);   // [DK] whole-chunk decay
     float* tot = gam + DK;                       // [4][DK] per-wave block products
+    float* hsc = tot + kWaves * DK;              // [DK] half-chunk decay folded into the stored fragments
 
     int bh, tile;
     xcd_map(block_id, p.n_tile, bh, tile);
@@ -139,7 +141,14 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             }
             store_run<T, RW>(AT + (2 * lane) * PC + RW * w, x0);
             store_run<T, RW>(AT + (2 * lane + 1) * PC + RW * w, x1);
-            if (w == 0) { gam[2 * lane] = d0.all; gam[2 * lane + 1] = d1.all; }
+            if (w == 0) {
+                gam[2 * lane] = d0.all; gam[2 * lane + 1] = d1.all;
+                // what the consumers multiply the state with anyway: the gate product of the first
+                // half of the chunk for S_n (read-out side), of the second half for dS_{n+1}
+                constexpr int h0 = REVERSE ? 2 : 0;
+                hsc[2 * lane] = tot[h0 * DK + 2 * lane] * tot[(h0 + 1) * DK + 2 * lane];
+                hsc[2 * lane + 1] = tot[h0 * DK + 2 * lane + 1] * tot[(h0 + 1) * DK + 2 * lane + 1];
+            }
         }
         if (b_act) {
             float x0[RW], x1[RW];
@@ -162,8 +171,16 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 float x[8];
+                if (TRANS) {
+                    const float sc = hsc[32 * at + r32];
 #pragma unroll
-                for (int s = 0; s < 8; ++s) x[s] = acc[j][8 * half + s];
+                    for (int s = 0; s < 8; ++s) x[s] = acc[j][8 * half + s] * sc;
+                } else {
+                    const f32x4 sc0 = *reinterpret_cast<const f32x4*>(hsc + 32 * at + 16 * half + 4 * g);
+                    const f32x4 sc1 = *reinterpret_cast<const f32x4*>(hsc + 32 * at + 16 * half + 8 + 4 * g);
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) { x[s] = acc[j][8 * half + s] * sc0[s]; x[4 + s] = acc[j][8 * half + 4 + s] * sc1[s]; }
+                }
                 *reinterpret_cast<typename M::frag*>(
                     wsn + state_frag_offset(at, col0 / 32 + bt, DV / 32, half, lane)) = M::pack(x);
             }
@@ -241,7 +258,7 @@ static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, cons
     SweepParams ps = ps0, pg = pg0;
     ps.n_tile = pg.n_tile = DV / TV;
     constexpr int PC = kChunk + pad_elems<T>();
-    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(1 + kWaves) * DK * sizeof(float);
+    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
     auto kern = sweep_pair_kernel<T, DK, DV, TV>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -254,11 +271,14 @@ static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, cons
 template <typename T, int DK, int DV>
 static hipError_t launch_pair_tv(const SeqDims& d, const SweepParams& ps, const SweepParams& pg, hipStream_t stream)
 {
+    // The sweeps are bound by the element-wise work on the gates, which every column slab of a
+    // sequence repeats: use the widest slab that still gives each of the 256 CUs a workgroup
+    // (two sweeps share the grid).
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH < 96) return launch_pair_one<T, DK, DV, 32>(d, ps, pg, stream);
+        if (d.BH < 48) return launch_pair_one<T, DK, DV, 32>(d, ps, pg, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH < 256) return launch_pair_one<T, DK, DV, 64>(d, ps, pg, stream);
+        if (d.BH < 128) return launch_pair_one<T, DK, DV, 64>(d, ps, pg, stream);
     }
     return launch_pair_one<T, DK, DV, DV>(d, ps, pg, stream);
 }
@@ -269,7 +289,7 @@ static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_
     SweepParams p = p0;
     p.n_tile = DV / TV;
     constexpr int PC = kChunk + pad_elems<T>();
-    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(1 + kWaves) * DK * sizeof(float);
+    const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
     auto kern = sweep_kernel<T, DK, DV, TV, MODE>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
