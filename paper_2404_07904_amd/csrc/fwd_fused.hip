@@ -1,22 +1,35 @@
 // Fused forward pass of the chunkwise HGRN2 algorithm (paper Section 3.2, Eq. 3): the
 // chunk-to-chunk state recurrence and the per-chunk read-out in ONE pass over q, f, v,
 //
-//     O_n     = tril(Q~ K~^T) V + (q G) S_n
-//     S_{n+1} = Diag(g) S_n + K^^T V
+//     O_n     = tril(Q~ K~^T) V + Q~ (G_m S_n)
+//     S_{n+1} = h (G_m S_n + K~^T V)
 //
-// so that the per-chunk states never travel through HBM (the two-kernel path writes and re-reads
-// 2*dk*dv bytes per chunk, as much again as the chunk's own q, f, v, o).  One workgroup of eight
-// wave64s owns a whole (batch, head) and walks its chunks in order:
-//   * the dk x dv state lives in fp32 MFMA accumulators, two 32x32 tiles per wave; after every
-//     update each wave drops a bf16 copy of its tiles into LDS in MFMA-fragment order, from where
-//     all waves read the operand of (q G) S_n;
+// with Q~ = q G/G_m, K~ = k G_m/G (k = 1 - f, G the cumulative gate product inside the chunk, G_m
+// its value after the first half of the chunk, h the product over the second half), so that the
+// per-chunk states never travel through HBM (the two-kernel path writes and re-reads 2*dk*dv
+// bytes per chunk, as much again as the chunk's own q, f, v, o).  One workgroup of eight wave64s
+// owns a whole (batch, head) and walks its chunks in order, software-pipelined in two stages
+// per chunk with one barrier after each:
+//
+//   stage A(n):  store O(n-1) from its LDS staging tile; copy V(n) into LDS; rescale the state
+//                to G_m(n) S_n and publish it (bf16, MFMA-fragment order) to LDS; first half of
+//                the element-wise work of chunk n+1 (gate products, per-wave block totals);
+//                P(n) = tril(Q~ K~^T) on three waves
+//   stage B(n):  all remaining contractions of chunk n (Q~ (G_m S_n), P V, K~^T V) while the
+//                second half of the element-wise work of chunk n+1 (Q~, K~ tiles) fills the
+//                other tile buffer; O(n) into its staging tile
+//
+//   * the dk x dv state lives in fp32 MFMA accumulators, two 32x32 tiles per wave;
 //   * wave w owns rows 8w..8w+7 of the chunk for the element-wise work (gate products along time
-//     serially in registers, channel pair per lane), and the 32x32 output tile (w/4, w%4);
-//   * the next chunk's rows are loaded into registers while the current chunk is computed.
+//     serially in registers, channel pair per lane) and the 32x32 output tile (w/4, w%4);
+//   * every LDS tile is row-major [token][channel]; operands whose contraction index is the
+//     token are read with LDS transpose loads, so V needs no arithmetic at all on its way in;
+//   * rows are fetched two chunks ahead into two alternating register sets.
 // Used for bf16 storage with dk = dv = 128 when there are enough sequences to fill the chip;
 // other cases take the sweep + read-out path.
 #include "common.hpp"
 #include "kernels.hpp"
+#include <type_traits>
 
 namespace hgrn2 {
 
@@ -30,7 +43,7 @@ struct FwdFusedParams {
     const float* h0;
     void* o;
     float* hT;
-    int N, NC, gate_bf16;
+    int N, NC;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][16] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -42,59 +55,67 @@ struct FwdFusedParams {
 #define HGRN2_STAMP(k) do { } while (0)
 #endif
 
-template <int DK, int DV> struct FwdFusedLds {
-    typedef __bf16 T;
-    static constexpr int C = kChunk;
-    static constexpr int PK = DK + 8, PC = C + 8, PO = DV + 8;
-    static constexpr size_t qm = 0;                                     // Q~   [C][PK]
-    static constexpr size_t km = qm + (size_t)C * PK * 2;               // K~   [C][PK]
-    static constexpr size_t qf = km + (size_t)C * PK * 2;               // q G  [C][PK]
-    static constexpr size_t vt = qf + (size_t)C * PK * 2;               // V^T  [DV][PC]
-    static constexpr size_t kt = vt + (size_t)DV * PC * 2;              // K^^T [DK][PC]
-    static constexpr size_t pm = kt + (size_t)DK * PC * 2;              // P    [C][PC]
-    static constexpr size_t sb = pm + (size_t)C * PC * 2;               // state, bf16, fragment order
-    static constexpr size_t gam = sb + (size_t)DK * DV * 2;             // [DK] fp32
-    static constexpr size_t tot = gam + (size_t)DK * 4;                 // [8][DK] fp32
-    static constexpr size_t total = tot + (size_t)kFusedWaves * DK * 4;
-    static_assert(2 * C * PK >= C * PO, "output staging must fit in the Q~/K~ tiles");
+struct FwdFusedLds {
+    static constexpr int DK = 128, DV = 128, C = kChunk;
+    // Row pitches in elements.  Tiles read row-major with 16-byte vectors want consecutive rows
+    // 4 banks apart (+8 elements); tiles read with transpose loads (4 rows x 64 bytes per half
+    // wave) want them 16 banks apart (+32 elements); K~ is read both ways and takes +40.
+    static constexpr int PQ = DK + 8, PKK = DK + 40, PV = DV + 32, PC = C + 8, PO = DV + 8;
+    static constexpr size_t qm = 0;                                     // Q~  [2][C][PQ]
+    static constexpr size_t km = qm + (size_t)2 * C * PQ * 2;           // K~  [2][C][PKK]
+    static constexpr size_t vm = km + (size_t)2 * C * PKK * 2;          // V   [C][PV]
+    static constexpr size_t pm = vm + (size_t)C * PV * 2;               // P   [C][PC]
+    static constexpr size_t sb = pm + (size_t)C * PC * 2;               // G_m S_n, bf16, fragment order
+    static constexpr size_t ost = sb + (size_t)DK * DV * 2;             // O   [C][PO]
+    static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals
+    static constexpr size_t ca = tot + (size_t)kFusedWaves * DK * 4;    // [DK] fp32 state rescale
+    static constexpr size_t total = ca + (size_t)DK * 4;
+    static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <int DK, int DV>
+template <bool GATE_BF16>
 __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams p)
 {
     typedef __bf16 T;
     typedef Mma<T> M;
     typedef typename M::frag frag;
-    typedef FwdFusedLds<DK, DV> L;
-    constexpr int C = kChunk, NW = kFusedWaves, RW = C / NW;
-    constexpr int PK = L::PK, PC = L::PC, PO = L::PO;
-    constexpr int NRT = C / 32, NAT = DK / 32, NBT = DV / 32, NKS = DK / 16;
-    static_assert(DK == 128 && DV == 128 && NRT * NBT == NW && NAT * NBT == 2 * NW, "tile/wave mapping");
+    typedef FwdFusedLds L;
+    constexpr int DK = L::DK, DV = L::DV, C = L::C, NW = kFusedWaves, RW = C / NW;
+    constexpr int PQ = L::PQ, PKK = L::PKK, PV = L::PV, PC = L::PC, PO = L::PO;
+    constexpr int NBT = DV / 32, NKS = DK / 16;
+    static_assert(RW == 8 && (C / 32) * NBT == NW && (DK / 32) * NBT == 2 * NW, "tile/wave mapping");
 
     extern __shared__ __align__(16) char smem[];
     T* Qm = reinterpret_cast<T*>(smem + L::qm);
     T* Km = reinterpret_cast<T*>(smem + L::km);
-    T* Qf = reinterpret_cast<T*>(smem + L::qf);
-    T* Vt = reinterpret_cast<T*>(smem + L::vt);
-    T* Kt = reinterpret_cast<T*>(smem + L::kt);
+    T* Vm = reinterpret_cast<T*>(smem + L::vm);
     T* Pm = reinterpret_cast<T*>(smem + L::pm);
     T* Sb = reinterpret_cast<T*>(smem + L::sb);
-    float* gam = reinterpret_cast<float*>(smem + L::gam);
+    T* Ost = reinterpret_cast<T*>(smem + L::ost);
     float* tot = reinterpret_cast<float*>(smem + L::tot);
-    T* Ost = Qm;
+    float* cA = reinterpret_cast<float*>(smem + L::ca);
 
     const int bh = blockIdx.x;
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
     const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
-    const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     T* og = static_cast<T*>(p.o);
+    const int NC = p.NC;
 
     const int rt = w / NBT, bt = w % NBT;    // output tile of this wave
     const int at0 = 2 * rt;                  // its two state tiles: (at0, bt), (at0 + 1, bt)
+    const bool after = w >= NW / 2;          // rows of this wave lie after the mid-chunk reference
 
-    // ---- state: fp32 accumulators + bf16 fragment copy in LDS ----
+    if (NC == 0) {                           // empty sequence: hT = h0 (uniform early exit, before any barrier)
+        if (p.hT)
+            for (int idx = tid; idx < DK * DV; idx += kFusedThreads)
+                p.hT[(size_t)bh * DK * DV + idx] = p.h0 ? p.h0[(size_t)bh * DK * DV + idx] : 0.0f;
+        return;
+    }
+
+    // ---- state: fp32 accumulators.  Between chunks they hold S_n / h(n-1); see stage A. ----
     f32x16 accS[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -102,9 +123,166 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         for (int v = 0; v < 16; ++v)
             accS[j][v] = p.h0 ? p.h0[(size_t)bh * DK * DV + (size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + 32 * bt + r32]
                               : 0.0f;
-    auto publish_state = [&]() {
+    float hprev0 = 1.0f, hprev1 = 1.0f;      // h of the previous chunk, channels 2*lane, 2*lane+1
+
+    // ---- row fetch, two chunks ahead, two register sets ----
+    RawRows<RW> rawf[2], rawq[2];
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 rawv[2];                   // V is fetched one chunk ahead only
+    const int vrow = RW * w + (lane >> 4), vcol = 8 * (lane & 15);      // V copy: 16 bytes per lane, rows vrow, vrow+4
+    // Every load is issued unconditionally (a row past the end of the sequence re-reads the last
+    // row), and the chunk loop always runs an even number of passes, so that its body is
+    // straight-line code: the compiler can then count outstanding loads exactly and the two
+    // register sets never have to be copied.  A pass over a chunk index >= NC sees gates equal
+    // to one on every row and is an exact no-op on the state.  Row addresses are wave-uniform.
+    const char* fbase = static_cast<const char*>(p.f) + seq_k * (GATE_BF16 ? 2 : 4);
+    const char* qbase = reinterpret_cast<const char*>(qg + seq_k);
+    const char* vbase = reinterpret_cast<const char*>(vg + seq_v);
+    const int last_row = p.N - 1;
+    auto load_f = [&](RawRows<RW>& d, int c) {
+        const int row0 = c * C + RW * w;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int i = 0; i < RW; ++i) {
+            const char* rp = fbase + (size_t)min(row0 + i, last_row) * (DK * (GATE_BF16 ? 2 : 4));
+            if (GATE_BF16) d.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + 4 * lane));
+            else d.r[i] = *reinterpret_cast<const f32x2*>(rp + 8 * lane);
+        }
+    };
+    auto load_q = [&](RawRows<RW>& d, int c) {
+        const int row0 = c * C + RW * w;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const char* rp = qbase + (size_t)min(row0 + i, last_row) * (DK * 2);
+            d.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + 4 * lane));
+        }
+    };
+    auto load_v = [&](u32x4 (&d)[2], int c) {
+        const int row0 = c * C + RW * w;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int rc = min(row0 + (lane >> 4) + 4 * j, last_row);
+            d[j] = *reinterpret_cast<const u32x4*>(vbase + (size_t)rc * (DV * 2) + 2 * vcol);
+        }
+    };
+    // Rows past the end of the sequence need no masking here: their K~ is zero (f = 1 there), so
+    // whatever finite values stand in for them never reach a stored output or the state.
+    auto store_v = [&](const u32x4 (&s)[2]) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4*>(Vm + (vrow + 4 * j) * PV + vcol) = s[j];
+    };
+
+    // ---- element-wise work of one chunk, split around the exchange of the block totals ----
+    // With a = inclusive gate product from the start of this wave's 8-row block, z = exclusive
+    // product to its end, t = a z the block total, mid = product of the blocks between this block
+    // and the mid-chunk reference row, and m = product of the gates between the reference row and
+    // this row:
+    //   rows after the reference:  Q~ = q m,   K~ = k / m,   m = mid a,  1/m = z / (mid t)
+    //   rows before it:            Q~ = q / m, K~ = k m,     m = mid z,  1/m = a / (mid t)
+    // so Q~ = (q a) s_a and K~ = (k z) s_z with per-channel block factors s_a, s_z in {mid,
+    // 1/(mid t)}: one reciprocal per channel and block, floored so that it stays finite outside
+    // the supported gate range.
+    // First half (before the totals are exchanged): q a, k z, t.
+    float qa0[RW], qa1[RW], kz0[RW], kz1[RW], bt0, bt1;
+    auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
+        f32x2 rf[RW];
+        convert_rows<RW>(rf, rf_raw, c * C + RW * w, p.N, true, GATE_BF16, 1.0f);
+        float run0 = 1.0f, run1 = 1.0f;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const uint32_t u = __float_as_uint(rq_raw.r[i].x);
+            run0 *= rf[i].x; run1 *= rf[i].y;
+            qa0[i] = __uint_as_float(u << 16) * run0;
+            qa1[i] = __uint_as_float(u & 0xffff0000u) * run1;
+        }
+        bt0 = run0; bt1 = run1;
+        run0 = 1.0f; run1 = 1.0f;
+#pragma unroll
+        for (int i = RW - 1; i >= 0; --i) {
+            kz0[i] = (1.0f - rf[i].x) * run0; kz1[i] = (1.0f - rf[i].y) * run1;
+            run0 *= rf[i].x; run1 *= rf[i].y;
+        }
+        *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{bt0, bt1};
+    };
+    // Second half: block factors from the exchanged totals, tiles to LDS.
+    auto prep_tiles = [&](int c) {
+        f32x2 t[NW];
+#pragma unroll
+        for (int i = 0; i < NW; ++i) t[i] = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
+        float mid0 = 1.0f, mid1 = 1.0f;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const bool between = after ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
+            mid0 *= between ? t[i].x : 1.0f;
+            mid1 *= between ? t[i].y : 1.0f;
+        }
+        const float gm0 = (t[0].x * t[1].x) * (t[2].x * t[3].x), gm1 = (t[0].y * t[1].y) * (t[2].y * t[3].y);
+        const float hh0 = (t[4].x * t[5].x) * (t[6].x * t[7].x), hh1 = (t[4].y * t[5].y) * (t[6].y * t[7].y);
+        const float R0 = fast_rcp(fmaxf(mid0 * bt0, kTinyProduct));
+        const float R1 = fast_rcp(fmaxf(mid1 * bt1, kTinyProduct));
+        const float sa0 = after ? mid0 : R0, sa1 = after ? mid1 : R1;       // multiplies q a
+        const float sz0 = after ? R0 : mid0, sz1 = after ? R1 : mid1;       // multiplies k z
+        T* Qd = Qm + (size_t)(c & 1) * C * PQ + (size_t)(RW * w) * PQ + 2 * lane;
+        T* Kd = Km + (size_t)(c & 1) * C * PKK + (size_t)(RW * w) * PKK + 2 * lane;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            store_pair_t<T>(Qd, (size_t)i * PQ, qa0[i] * sa0, qa1[i] * sa1);
+            store_pair_t<T>(Kd, (size_t)i * PKK, kz0[i] * sz0, kz1[i] * sz1);
+        }
+        // state rescale of the chunk: h of the previous chunk times G_m of this one
+        if (w == 0) *reinterpret_cast<f32x2*>(cA + 2 * lane) = f32x2{hprev0 * gm0, hprev1 * gm1};
+        hprev0 = hh0; hprev1 = hh1;
+    };
+
+    // O leaves through registers that stay reserved for the whole pass (see the end of stage B):
+    // a global store reads its data registers late, and overwriting them earlier would make the
+    // wave wait for the store, and with it for every prefetch issued before it, to complete.
+    u32x4 obuf[C * (DV / 8) / kFusedThreads];
+    auto store_o = [&](int c) {
+        constexpr int VPR = DV / 8;
+#pragma unroll
+        for (int k = 0; k < C * VPR / kFusedThreads; ++k) {
+            const int idx = tid + k * kFusedThreads;
+            const int row = idx / VPR, cv = idx % VPR;
+            const int grow = c * C + row;
+            obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
+            if ((unsigned)grow < (unsigned)p.N)      // also false for the chunk "-1" of the first pass
+                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * DV + cv * 8) = obuf[k];
+        }
+    };
+
+#ifdef HGRN2_PHASE_TIMING
+    long long ph[16] = {0};
+    long long t_prev = wall_clock64();
+#endif
+
+    // ---- prologue: rows of chunks 0 and 1 in flight, element-wise work of chunk 0 ----
+    // the never-written block of P (rows 0..31 x columns 32..63) must read as zero
+    for (int idx = tid; idx < 32 * 32; idx += kFusedThreads) Pm[(idx >> 5) * PC + 32 + (idx & 31)] = (T)0.0f;
+    load_f(rawf[0], 0); load_q(rawq[0], 0); load_v(rawv, 0);
+    load_f(rawf[1], 1); load_q(rawq[1], 1);
+    prep_gates(rawf[0], rawq[0], 0);
+    load_f(rawf[0], 2); load_q(rawq[0], 2);
+    __syncthreads();
+    prep_tiles(0);
+    __syncthreads();
+
+    auto chunk = [&](auto PAR, int n) {
+        constexpr int par = decltype(PAR)::value;
+        const T* Qc = Qm + (size_t)par * C * PQ;
+        const T* Kc = Km + (size_t)par * C * PKK;
+        // ======================= stage A =======================
+        store_o(n - 1);
+        store_v(rawv);
+        load_v(rawv, n + 1);
+        // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const f32x4 cm = *reinterpret_cast<const f32x4*>(cA + 32 * (at0 + j) + 8 * c + 4 * g);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) accS[j][4 * c + jj] *= cm[jj];
+            }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 float x[8];
@@ -112,90 +290,20 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
                 for (int s = 0; s < 8; ++s) x[s] = accS[j][8 * half + s];
                 *reinterpret_cast<frag*>(Sb + state_frag_offset(at0 + j, bt, NBT, half, lane)) = M::pack(x);
             }
-    };
-    publish_state();
-
-    RawRows<RW> raw_f, raw_q, raw_v;
-    auto load_chunk = [&](int n) {
-        const int row0 = n * C + RW * w;
-        load_rows<RW>(raw_f, p.f, seq_k, DK, 2 * lane, row0, p.N, gate_bf16);
-        load_rows<RW>(raw_q, qg, seq_k, DK, 2 * lane, row0, p.N, true);
-        load_rows<RW>(raw_v, vg, seq_v, DV, 2 * lane, row0, p.N, true);
-    };
-    if (p.NC > 0) load_chunk(0);
-
-#ifdef HGRN2_PHASE_TIMING
-    long long ph[16] = {0};
-    long long t_prev = wall_clock64();
-#endif
-    for (int n = 0; n < p.NC; ++n) {
-        // ---------------- element-wise stage ----------------
-        f32x2 rf[RW], rq[RW], rv[RW];
-        {
-            const int row0 = n * C + RW * w;
-            convert_rows<RW>(rf, raw_f, row0, p.N, true, gate_bf16, 1.0f);
-            convert_rows<RW>(rq, raw_q, row0, p.N, true, true, 0.0f);
-            convert_rows<RW>(rv, raw_v, row0, p.N, true, true, 0.0f);
         }
-        float a0[RW], a1[RW], z0[RW], z1[RW];
-        {
-            float run0 = 1.0f, run1 = 1.0f;
-#pragma unroll
-            for (int i = 0; i < RW; ++i) { run0 *= rf[i].x; run1 *= rf[i].y; a0[i] = run0; a1[i] = run1; }
-            run0 = 1.0f; run1 = 1.0f;
-#pragma unroll
-            for (int i = RW - 1; i >= 0; --i) { z0[i] = run0; z1[i] = run1; run0 *= rf[i].x; run1 *= rf[i].y; }
-        }
-        tot[w * DK + 2 * lane] = a0[RW - 1];
-        tot[w * DK + 2 * lane + 1] = a1[RW - 1];
+        prep_gates(rawf[1 - par], rawq[1 - par], n + 1);
+        load_f(rawf[1 - par], n + 3); load_q(rawq[1 - par], n + 3);
         HGRN2_STAMP(0);
-        __syncthreads();                                   // B1 (also: previous chunk's staging has been read)
-        HGRN2_STAMP(1);
-        {
-            const BlockDecay d0 = block_decay_n<NW>(tot, DK, w, 2 * lane);
-            const BlockDecay d1 = block_decay_n<NW>(tot, DK, w, 2 * lane + 1);
-            float kh0[RW], kh1[RW], v0[RW], v1[RW];
-#pragma unroll
-            for (int i = 0; i < RW; ++i) {
-                const int row = RW * w + i;
-                float m0, m1, qs0, qs1, ks0, ks1;
-                const float k0 = 1.0f - rf[i].x, k1 = 1.0f - rf[i].y;
-                if (w >= NW / 2) {
-                    m0 = d0.mid * a0[i]; m1 = d1.mid * a1[i];
-                    qs0 = rq[i].x * m0; qs1 = rq[i].y * m1;
-                    ks0 = k0 * fast_rcp(fmaxf(m0, kTinyProduct)); ks1 = k1 * fast_rcp(fmaxf(m1, kTinyProduct));
-                } else {
-                    m0 = d0.mid * z0[i]; m1 = d1.mid * z1[i];
-                    qs0 = rq[i].x * fast_rcp(fmaxf(m0, kTinyProduct)); qs1 = rq[i].y * fast_rcp(fmaxf(m1, kTinyProduct));
-                    ks0 = k0 * m0; ks1 = k1 * m1;
-                }
-                store_pair_t<T>(Qm, (size_t)row * PK + 2 * lane, qs0, qs1);
-                store_pair_t<T>(Km, (size_t)row * PK + 2 * lane, ks0, ks1);
-                store_pair_t<T>(Qf, (size_t)row * PK + 2 * lane, rq[i].x * (d0.pre * a0[i]), rq[i].y * (d1.pre * a1[i]));
-                kh0[i] = k0 * (z0[i] * d0.post); kh1[i] = k1 * (z1[i] * d1.post);
-                v0[i] = rv[i].x; v1[i] = rv[i].y;
-            }
-            *reinterpret_cast<frag*>(Kt + (2 * lane) * PC + RW * w) = M::pack(kh0);
-            *reinterpret_cast<frag*>(Kt + (2 * lane + 1) * PC + RW * w) = M::pack(kh1);
-            *reinterpret_cast<frag*>(Vt + (2 * lane) * PC + RW * w) = M::pack(v0);
-            *reinterpret_cast<frag*>(Vt + (2 * lane + 1) * PC + RW * w) = M::pack(v1);
-            if (w == 0) { gam[2 * lane] = d0.all; gam[2 * lane + 1] = d1.all; }
-        }
-        if (n + 1 < p.NC) load_chunk(n + 1);              // in flight during the matrix stages
-        HGRN2_STAMP(2);
-        __syncthreads();                                   // B2
-        HGRN2_STAMP(3);
-
-        // ---------------- P^T blocks (J <= I), one per wave ----------------
-        if (w < NRT * (NRT + 1) / 2) {
+        // P^T blocks (J <= I), one per wave
+        if (w < 3) {
             const int I = (w == 0) ? 0 : 1, J = (w == 2) ? 1 : 0;     // 0:(0,0) 1:(0,1) 2:(1,1) as (J,I)
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
-                M::mma(acc, M::load(Km + (32 * J + r32) * PK + 16 * ks + 8 * g),
-                       M::load(Qm + (32 * I + r32) * PK + 16 * ks + 8 * g));     // acc[row j][col i]
+                M::mma(acc, M::load(Kc + (32 * J + r32) * PKK + 16 * ks + 8 * g),
+                       M::load(Qc + (32 * I + r32) * PQ + 16 * ks + 8 * g));     // acc[row j][col i]
             const int i_glob = 32 * I + r32;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -203,76 +311,72 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
                 float x[4];
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) x[jj] = (j0 + jj <= i_glob) ? acc[4 * c + jj] : 0.0f;
-                store_pair_t<T>(Pm, (size_t)i_glob * PC + j0, x[0], x[1]);
-                store_pair_t<T>(Pm, (size_t)i_glob * PC + j0 + 2, x[2], x[3]);
+                bf16x4 pk;
+                pk[0] = (T)x[0]; pk[1] = (T)x[1]; pk[2] = (T)x[2]; pk[3] = (T)x[3];
+                *reinterpret_cast<bf16x4*>(Pm + (size_t)i_glob * PC + j0) = pk;
             }
         }
+        HGRN2_STAMP(1);
+        __syncthreads();
+        HGRN2_STAMP(2);
+        // ======================= stage B =======================
+        // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
+        f32x16 accO;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < C / 16; ++ks) {
+            const frag vf = M::load_kmajor(Vm, PV, 16 * ks, 32 * bt, lane);
+            M::mma(accS[0], M::load_kmajor(Kc, PKK, 16 * ks, 32 * at0, lane), vf);
+            M::mma(accS[1], M::load_kmajor(Kc, PKK, 16 * ks, 32 * (at0 + 1), lane), vf);
+            M::mma(accO, vf, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g));   // zero block included
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
+                const int ks2 = 2 * ks + hh;
+                const T* qrow = Qc + (32 * rt + r32) * PQ + 16 * ks2 + 4 * g;
+                M::mma(accO, *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane)),
+                       M::load2(qrow, qrow + 8));
+            }
+        }
+        HGRN2_STAMP(3);
+        prep_tiles(n + 1);
         HGRN2_STAMP(4);
-        __syncthreads();                                   // B3
+        // accO[v] = O[token 32 rt + r32][channel 32 bt + 8 (v/4) + 4 g + v%4]
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            bf16x4 pk;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)accO[4 * c + jj];
+            *reinterpret_cast<bf16x4*>(Ost + (size_t)(32 * rt + r32) * PO + 32 * bt + 8 * c + 4 * g) = pk;
+        }
         HGRN2_STAMP(5);
-
-        // ---------------- output tile (rt, bt): P V + (q G) S_n ----------------
-        {
-            f32x16 acc;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-            for (int ks = 0; ks < 2 * (rt + 1); ++ks)
-                M::mma(acc, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g),
-                       M::load(Vt + (32 * bt + r32) * PC + 16 * ks + 8 * g));
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                const T* qrow = Qf + (32 * rt + r32) * PK + 16 * ks + 4 * g;
-                M::mma(acc, M::load2(qrow, qrow + 8),
-                       *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks >> 1, bt, NBT, ks & 1, lane)));
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                Ost[(size_t)(32 * rt + acc_row(v, lane)) * PO + 32 * bt + r32] = (T)acc[v];
-        }
+        for (int k = 0; k < C * (DV / 8) / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
+        __syncthreads();
         HGRN2_STAMP(6);
-        // ---------------- state tiles (at0, bt), (at0+1, bt): Diag(g) S + K^^T V ----------------
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const f32x4 gm = *reinterpret_cast<const f32x4*>(gam + 32 * (at0 + j) + 8 * c + 4 * g);
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) accS[j][4 * c + jj] *= gm[jj];
-            }
-#pragma unroll
-            for (int ks = 0; ks < C / 16; ++ks)
-                M::mma(accS[j], M::load(Kt + (32 * (at0 + j) + r32) * PC + 16 * ks + 8 * g),
-                       M::load(Vt + (32 * bt + r32) * PC + 16 * ks + 8 * g));
-        }
-        HGRN2_STAMP(7);
-        __syncthreads();                                   // B4: S_n and the operand tiles are no longer read
-        HGRN2_STAMP(8);
+    };
 
-        publish_state();
-        {
-            constexpr int VPR = DV / 8;
-            for (int idx = tid; idx < C * VPR; idx += kFusedThreads) {
-                const int row = idx / VPR, cv = idx % VPR;
-                const int grow = n * C + row;
-                if (grow < p.N)
-                    *reinterpret_cast<uint4*>(og + seq_v + (size_t)grow * DV + cv * 8) =
-                        *reinterpret_cast<const uint4*>(Ost + (size_t)row * PO + cv * 8);
-            }
-        }
+    int n_end = 0;
+    for (; n_end < NC; n_end += 2) {
+        chunk(std::integral_constant<int, 0>(), n_end);
+        chunk(std::integral_constant<int, 1>(), n_end + 1);
     }
+    store_o(n_end - 1);
 
 #ifdef HGRN2_PHASE_TIMING
-    HGRN2_STAMP(9);
     if (lane == 0 && p.dbg)
         for (int k = 0; k < 16; ++k) p.dbg[((size_t)bh * NW + w) * 16 + k] = ph[k];
 #endif
     if (p.hT) {
+        // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1)
         float* s1 = p.hT + (size_t)bh * DK * DV;
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                s1[(size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + 32 * bt + r32] = accS[j][v];
+            for (int v = 0; v < 16; ++v) {
+                const int a = 32 * (at0 + j) + acc_row(v, lane);
+                s1[(size_t)a * DV + 32 * bt + r32] = cA[a] * accS[j][v];
+            }
     }
 }
 
@@ -285,11 +389,11 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
                             void* o, float* hT, hipStream_t stream)
 {
     if (d.BH == 0) return hipSuccess;
-    typedef FwdFusedLds<128, 128> L;
+    typedef FwdFusedLds L;
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
-    p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
-    auto kern = fwd_fused_kernel<128, 128>;
+    p.N = d.N; p.NC = d.NC;
+    auto kern = d.gate_bf16 ? fwd_fused_kernel<true> : fwd_fused_kernel<false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
     if (e != hipSuccess) return e;
