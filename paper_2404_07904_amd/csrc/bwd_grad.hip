@@ -62,15 +62,19 @@ struct BwdGradParams {
 
 template <typename T, int DK, int DV> struct BwdGradLds {
     static constexpr int C = kChunk;
-    static constexpr int PK = DK + pad_elems<T>();      // pitch of [C][DK] tiles
-    static constexpr int PV = DV + pad_elems<T>();      // pitch of [C][DV] tiles and of dS [DK][DV]
+    // Tiles that are also read with LDS transpose loads (Q~, K~, dO, dS) take a pitch of D + 24
+    // elements: row-major 16-byte reads stay conflict-free and the transpose reads run at twice
+    // the rate they reach at D + 8.  V and the dv staging tile are only read row-major.
+    static constexpr int PK = DK + 3 * pad_elems<T>();  // pitch of the Q~, K~ tiles [C][DK]
+    static constexpr int PV = DV + 3 * pad_elems<T>();  // pitch of the dO tile [C][DV] and of dS [DK][DV]
+    static constexpr int PVR = DV + pad_elems<T>();     // pitch of the V tile and of the dv staging tile
     static constexpr int PC = C + pad_elems<T>();       // pitch of [C][C] tiles
     static constexpr int PF = DK + 4;                   // pitch of fp32 staging [C][DK]
     // phase 1: operand tiles
     static constexpr size_t qm = 0;                                         // Q~   [C][PK]
     static constexpr size_t km = qm + (size_t)C * PK * sizeof(T);           // K~   [C][PK]
-    static constexpr size_t vm = km + (size_t)C * PK * sizeof(T);           // V    [C][PV]
-    static constexpr size_t dom = vm + (size_t)C * PV * sizeof(T);          // dO   [C][PV]
+    static constexpr size_t vm = km + (size_t)C * PK * sizeof(T);           // V    [C][PVR]
+    static constexpr size_t dom = vm + (size_t)C * PVR * sizeof(T);         // dO   [C][PV]
     static constexpr size_t dsm = dom + (size_t)C * PV * sizeof(T);         // H_m * dS  [DK][PV]
     static constexpr size_t pt = dsm + (size_t)DK * PV * sizeof(T);         // P^T  [C][PC]  ([j][i])
     static constexpr size_t dpt = pt + (size_t)C * PC * sizeof(T);          // dP^T [C][PC]
@@ -79,7 +83,8 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     static constexpr size_t blk = rp + (size_t)DK * sizeof(float);               // [8][DK] fp32 block sums of e
     static constexpr size_t ys = blk + (size_t)kBwdWaves * DK * sizeof(float);   // [2][DK] fp32 column sums per row tile
     static constexpr size_t dvs = ys + (size_t)2 * DK * sizeof(float);           // dv staging [C][PV]
-    static constexpr size_t total = dvs + (size_t)C * PV * sizeof(T);
+    static constexpr size_t total = dvs + (size_t)C * PVR * sizeof(T);
+    static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
     // phase 2 (aliases the operand tiles): fp32 staging of X and Y
     static constexpr size_t cq = 0;                                         // [C][PF] fp32
     static constexpr size_t ck = cq + (size_t)C * PF * sizeof(float);       // [C][PF] fp32
@@ -91,7 +96,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 {
     constexpr int C = kChunk, NW = kBwdWaves, RW = C / NW;
     typedef BwdGradLds<T, DK, DV> L;
-    constexpr int PK = L::PK, PV = L::PV, PC = L::PC, PF = L::PF;
+    constexpr int PK = L::PK, PV = L::PV, PVR = L::PVR, PC = L::PC, PF = L::PF;
     constexpr int NRT = C / 32, NAT = DK / 32, NBT = DV / 32;
     static_assert(NRT == 2 && NRT * NAT <= NW && NRT * NBT <= NW, "one tile per wave");
     typedef Mma<T> M;
@@ -184,7 +189,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
         if (v_act) {
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
-                store_pair_t<T>(Vm, (size_t)(RW * w + i) * PV + 2 * lane, rv[i].x, rv[i].y);
+                store_pair_t<T>(Vm, (size_t)(RW * w + i) * PVR + 2 * lane, rv[i].x, rv[i].y);
                 store_pair_t<T>(dOm, (size_t)(RW * w + i) * PV + 2 * lane, rd[i].x, rd[i].y);
             }
         }
@@ -281,9 +286,9 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
             for (int ks = 0; ks < DV / 16; ks += 2) {
                 M::mma(acc0, M::load(dOm + (32 * I + r32) * PV + 16 * ks + 8 * g),
-                       M::load(Vm + (32 * J + r32) * PV + 16 * ks + 8 * g));
+                       M::load(Vm + (32 * J + r32) * PVR + 16 * ks + 8 * g));
                 M::mma(acc1, M::load(dOm + (32 * I + r32) * PV + 16 * (ks + 1) + 8 * g),
-                       M::load(Vm + (32 * J + r32) * PV + 16 * (ks + 1) + 8 * g));
+                       M::load(Vm + (32 * J + r32) * PVR + 16 * (ks + 1) + 8 * g));
             }
         } else {
 #pragma unroll
@@ -332,7 +337,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             M::mma(aV, M::load(Km + (32 * rt_b + r32) * PK + 16 * ks + 8 * g), M::load_kmajor(dSm, PV, 16 * ks, 32 * bt, lane));
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PV + 32 * bt + r32] = (T)(aV[v] + aV2[v]);
+            dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PVR + 32 * bt + r32] = (T)(aV[v] + aV2[v]);
     }
     // tile (rt_a, at):  X = dP K~ + dO (G_m S_n)^T,  Y = dP^T Q~ + V (H_m dS)^T.  The second part of Y
     // is accumulated on its own first, because sum_j K~_j * (V (H_m dS)^T)_j over ALL rows of the chunk
@@ -347,7 +352,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
             const T* drow = dOm + (32 * rt_a + r32) * PV + 16 * kk + 4 * g;
-            const T* vrow = Vm + (32 * rt_a + r32) * PV + 16 * kk + 4 * g;
+            const T* vrow = Vm + (32 * rt_a + r32) * PVR + 16 * kk + 4 * g;
             M::mma(aX, M::load2(drow, drow + 8), sS[kk]);
             M::mma(aKs, M::load2(vrow, vrow + 8), sD[kk]);
         }
@@ -430,7 +435,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
             if (grow < p.N) {
-                const uint4 val = *reinterpret_cast<const uint4*>(dVs + (size_t)row * PV + cv * VEC);
+                const uint4 val = *reinterpret_cast<const uint4*>(dVs + (size_t)row * PVR + cv * VEC);
                 *reinterpret_cast<uint4*>(dvg + seq_v + (size_t)grow * DV + cv * VEC) = val;
             }
         }
