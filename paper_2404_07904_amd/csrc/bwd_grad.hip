@@ -20,7 +20,16 @@
 //        + sum_{i>=s} q_i G_i (dO S_n^T)_i                        read-out of the incoming state
 //        + sum_{j<s}  k_j (g/G_j) (V dS_{n+1}^T)_j                (R minus the suffix of the same terms)
 //        + g * rowsum(dS_{n+1} * S_n)
-// in which no term cancels against another.
+// in which no term cancels against another.  The first two lines are the suffix sum of
+// e'_i = Q~_i X_i - K~_i Y1_i with X = dP K~ + dO (G_m S_n)^T and Y1 = dP^T Q~, the third the
+// exclusive prefix sum of K~_j Ks_j with Ks = V (H_m dS)^T, the fourth is R.
+//
+// LDS instructions cost about the same whatever their width, so the kernel is laid out to need
+// few of them: V and dO travel from global memory to their LDS tiles as raw 16-byte vectors,
+// with the columns inside every group of 16 stored in the order the state fragments keep their
+// contraction index (bits 2 and 3 of the index swapped), so that the matching MFMA operand is
+// one 16-byte read; the accumulators of the 64 x dk results are kept transposed (channel in the
+// register index), so that they reach their fp32 staging tiles as 16-byte vectors.
 //
 // One workgroup of eight wave64s per chunk (two waves per SIMD, so that LDS and MFMA latencies of
 // one wave are covered by the other).  Wave w owns rows 8w..8w+7 of the chunk for the
@@ -48,7 +57,7 @@ struct BwdGradParams {
     void* dq;
     void* df;
     void* dv;
-    int BH, N, NC, gate_bf16;
+    int BH, N, NC;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][24] clock ticks per phase (diagnostic builds only)
 #endif
@@ -70,28 +79,35 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     static constexpr int PVR = DV + pad_elems<T>();     // pitch of the V tile and of the dv staging tile
     static constexpr int PC = C + pad_elems<T>();       // pitch of [C][C] tiles
     static constexpr int PF = DK + 4;                   // pitch of fp32 staging [C][DK]
+    static constexpr size_t cmax(size_t a, size_t b) { return a > b ? a : b; }
     // phase 1: operand tiles
     static constexpr size_t qm = 0;                                         // Q~   [C][PK]
     static constexpr size_t km = qm + (size_t)C * PK * sizeof(T);           // K~   [C][PK]
-    static constexpr size_t vm = km + (size_t)C * PK * sizeof(T);           // V    [C][PVR]
-    static constexpr size_t dom = vm + (size_t)C * PVR * sizeof(T);         // dO   [C][PV]
-    static constexpr size_t dsm = dom + (size_t)C * PV * sizeof(T);         // H_m * dS  [DK][PV]
+    static constexpr size_t vm = km + (size_t)C * PK * sizeof(T);           // V    [C][PVR]  (columns permuted)
+    static constexpr size_t dom = vm + (size_t)C * PVR * sizeof(T);         // dO   [C][PV]   (columns permuted)
+    static constexpr size_t dsm = dom + (size_t)C * PV * sizeof(T);         // H_m * dS  [DK][PV] (columns permuted)
     static constexpr size_t pt = dsm + (size_t)DK * PV * sizeof(T);         // P^T  [C][PC]  ([j][i])
     static constexpr size_t dpt = pt + (size_t)C * PC * sizeof(T);          // dP^T [C][PC]
     static constexpr size_t tot = dpt + (size_t)C * PC * sizeof(T);         // [8][DK] fp32 block products
-    static constexpr size_t rp = tot + (size_t)kBwdWaves * DK * sizeof(float);   // [DK] fp32  g * rowsum(dS * S_n)
-    static constexpr size_t blk = rp + (size_t)DK * sizeof(float);               // [8][DK] fp32 block sums of e
-    static constexpr size_t ys = blk + (size_t)kBwdWaves * DK * sizeof(float);   // [2][DK] fp32 column sums per row tile
-    static constexpr size_t dvs = ys + (size_t)2 * DK * sizeof(float);           // dv staging [C][PV]
+    static constexpr size_t p1_end = tot + (size_t)kBwdWaves * DK * sizeof(float);
+    // phase 2 (aliases phase 1): fp32 staging of X, Y1, Ks and the block sums of the epilogue
+    static constexpr size_t cx = 0;                                         // [C][PF] fp32
+    static constexpr size_t cy = cx + (size_t)C * PF * sizeof(float);
+    static constexpr size_t cks = cy + (size_t)C * PF * sizeof(float);
+    static constexpr size_t blke = cks + (size_t)C * PF * sizeof(float);    // [8][DK] fp32 block sums of e'
+    static constexpr size_t blkk = blke + (size_t)kBwdWaves * DK * sizeof(float);   // [8][DK] block sums of K~ Ks
+    static constexpr size_t p2_end = blkk + (size_t)kBwdWaves * DK * sizeof(float);
+    // The next chunk's first stage writes the V, dO tiles and the block products while the last
+    // stage of this one may still read the block sums; where those overlap, a barrier ends the chunk.
+    static constexpr bool end_barrier = !(blke >= dsm && p2_end <= tot);
+    // both phases
+    static constexpr size_t rp = cmax(p1_end, p2_end);                      // [DK] fp32  g * rowsum(dS * S_n)
+    static constexpr size_t dvs = rp + (size_t)DK * sizeof(float);          // dv staging [C][PVR]
     static constexpr size_t total = dvs + (size_t)C * PVR * sizeof(T);
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
-    // phase 2 (aliases the operand tiles): fp32 staging of X and Y
-    static constexpr size_t cq = 0;                                         // [C][PF] fp32
-    static constexpr size_t ck = cq + (size_t)C * PF * sizeof(float);       // [C][PF] fp32
-    static_assert(ck + (size_t)C * PF * sizeof(float) <= tot, "staging must fit in the operand and P tiles");
 };
 
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool GATE_BF16>
 __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 {
     constexpr int C = kChunk, NW = kBwdWaves, RW = C / NW;
@@ -99,8 +115,10 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     constexpr int PK = L::PK, PV = L::PV, PVR = L::PVR, PC = L::PC, PF = L::PF;
     constexpr int NRT = C / 32, NAT = DK / 32, NBT = DV / 32;
     static_assert(NRT == 2 && NRT * NAT <= NW && NRT * NBT <= NW, "one tile per wave");
+    static_assert(sizeof(T) == 2, "bf16 storage");
     typedef Mma<T> M;
     typedef typename M::frag frag;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
     extern __shared__ __align__(16) char smem[];
     T* Qm = reinterpret_cast<T*>(smem + L::qm);
@@ -112,41 +130,58 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     T* dPt = reinterpret_cast<T*>(smem + L::dpt);
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     float* Rp = reinterpret_cast<float*>(smem + L::rp);
-    float* blkE = reinterpret_cast<float*>(smem + L::blk);     // [8][DK] block sums of e
-    float* Ys = reinterpret_cast<float*>(smem + L::ys);       // [2][DK]
-    float* cQ = reinterpret_cast<float*>(smem + L::cq);
-    float* cK = reinterpret_cast<float*>(smem + L::ck);
+    float* cX = reinterpret_cast<float*>(smem + L::cx);
+    float* cY = reinterpret_cast<float*>(smem + L::cy);
+    float* cKs = reinterpret_cast<float*>(smem + L::cks);
+    float* blkE = reinterpret_cast<float*>(smem + L::blke);
+    float* blkK = reinterpret_cast<float*>(smem + L::blkk);
     T* dVs = reinterpret_cast<T*>(smem + L::dvs);
 
-    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
-    const bool k_act = 2 * lane < DK, v_act = 2 * lane < DV;
-    const bool gate_bf16 = p.gate_bf16 != 0;
+    const int tid = threadIdx.x;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
+    constexpr bool gate_bf16 = GATE_BF16;
+    constexpr int GES = GATE_BF16 ? 2 : 4;
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     const T* dog = static_cast<const T*>(p.dO);
-    const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
 
     // tile ownership (a wave without a tile of a kind skips that work)
     const bool has_a = w < NRT * NAT, has_b = w < NRT * NBT;
     const int rt_a = has_a ? w / NAT : 0, at = w % NAT;     // (row tile, channel tile) of dq / dk
     const int rt_b = has_b ? w / NBT : 0, bt = w % NBT;     // (row tile, column tile) of dv
 
-    // Everything one chunk needs from global memory: the raw rows of f, q, v, dO of this wave's row
-    // block and the state fragments of channel tile `at` (operand B[k = dv index][n = channel]).
-    // The workgroup is persistent: it walks the chunks blockIdx.x, blockIdx.x + gridDim.x, ... and
-    // issues the row loads of its next chunk as soon as the matrix stage of the current one is
-    // done, so that they fly during the element-wise epilogue; the state fragments are requested
-    // at the top of a chunk and are not needed before its own element-wise stage is over.
-    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, RawRows<RW>& cv, RawRows<RW>& cdo, int chunk) {
+    // V and dO tiles: one (row, 16-column group) per thread, 32 bytes
+    constexpr int GPR = DV / 16;
+    const bool vd_act = tid < C * GPR;
+    const int vd_row = vd_act ? tid / GPR : 0, vd_grp = tid % GPR;
+
+    // Everything one chunk needs from global memory: the raw rows of f, q of this wave's row block,
+    // this thread's 32 bytes of V and dO, and the state fragments of channel tile `at` (operand
+    // B[k = dv index][n = channel]).  The workgroup is persistent: it walks the chunks blockIdx.x,
+    // blockIdx.x + gridDim.x, ... and issues the row loads of its next chunk as soon as the matrix
+    // stage of the current one is done, so that they fly during the element-wise epilogue; the
+    // state fragments are requested at the top of a chunk and are not needed before its own
+    // element-wise stage is over.  Rows past the end of a sequence re-read its last row: their
+    // gates are replaced by one and their q by zero, which makes whatever finite values stand in
+    // for V and dO there drop out of every stored result.
+    auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, int chunk, int lane) {
+        const int col_k = (2 * lane < DK) ? 2 * lane : 0;
         const int cn = chunk % p.NC, cbh = chunk / p.NC;
-        const size_t sk_ = (size_t)cbh * p.N * DK, sv_ = (size_t)cbh * p.N * DV;
+        const size_t sk_ = (size_t)cbh * p.N * DK;
         const int r0 = cn * C + RW * w;
-        load_rows<RW>(cf, p.f, sk_, DK, col_k, r0, p.N, gate_bf16);
-        load_rows<RW>(cq, qg, sk_, DK, col_k, r0, p.N, is_bf16_type<T>());
-        load_rows<RW>(cv, vg, sv_, DV, col_v, r0, p.N, is_bf16_type<T>());
-        load_rows<RW>(cdo, dog, sv_, DV, col_v, r0, p.N, is_bf16_type<T>());
+        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sk_ * GES, r0, p.N - 1, DK, col_k);
+        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sk_), r0, p.N - 1, DK, col_k);
     };
-    auto load_chunk_states = [&](frag (&cS)[2 * NBT], frag (&cD)[2 * NBT], int chunk) {
+    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], int chunk, int lane) {
+        load_fq_rows(cf, cq, chunk, lane);
+        const int cn = chunk % p.NC, cbh = chunk / p.NC;
+        const size_t vo = (size_t)cbh * p.N * DV + (size_t)min(cn * C + vd_row, p.N - 1) * DV + 16 * vd_grp;
+        cv[0] = *reinterpret_cast<const u32x4*>(vg + vo);
+        cv[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
+        cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
+        cd[1] = *reinterpret_cast<const u32x4*>(dog + vo + 8);
+    };
+    auto load_chunk_states = [&](frag (&cS)[2 * NBT], frag (&cD)[2 * NBT], int chunk, int lane) {
         const size_t slot = (size_t)chunk * DK * DV;
         const T* wsS = static_cast<const T*>(p.ws_s) + slot;
         const T* wsD = static_cast<const T*>(p.ws_ds) + slot;
@@ -158,9 +193,11 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     };
 
     const int n_chunks = p.BH * p.NC;
-    RawRows<RW> raw_f, raw_q, raw_v, raw_d;
+    RawRows<RW> raw_f, raw_q;
+    u32x4 raw_v[2], raw_d[2];
     frag sS[2 * NBT], sD[2 * NBT];
-    if ((int)blockIdx.x < n_chunks) load_chunk_rows(raw_f, raw_q, raw_v, raw_d, blockIdx.x);
+    if ((int)blockIdx.x >= n_chunks) return;
+    load_chunk_rows(raw_f, raw_q, raw_v, raw_d, blockIdx.x, tid & 63);
 
   for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
     // Re-derive the lane-dependent indices inside the loop from a value the compiler cannot see
@@ -169,37 +206,37 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     int lane_opaque = threadIdx.x & 63;
     asm volatile("" : "+v"(lane_opaque));
     const int lane = lane_opaque, r32 = lane & 31, g = lane >> 5;
+    const bool k_act = 2 * lane < DK;
     const int n = chunk % p.NC, bh = chunk / p.NC;
     const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
-    load_chunk_states(sS, sD, chunk);      // first needed two barriers from here; covered by the element-wise stage
+    load_chunk_states(sS, sD, chunk, lane);      // first needed two barriers from here; covered by the element-wise stage
 
 #ifdef HGRN2_PHASE_TIMING
     long long ph[24] = {0};
     long long t_prev = wall_clock64();
 #endif
-    // rf/rq are re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
+    // V, dO tiles: raw bits, the four 4-column quads of a 16-column group stored in the order
+    // (0, 2, 1, 3), i.e. column b at position b with bits 2 and 3 swapped
+    if (vd_act) {
+        T* vdst = Vm + (size_t)vd_row * PVR + 16 * vd_grp;
+        T* ddst = dOm + (size_t)vd_row * PV + 16 * vd_grp;
+        *reinterpret_cast<u32x4*>(vdst) = u32x4{raw_v[0][0], raw_v[0][1], raw_v[1][0], raw_v[1][1]};
+        *reinterpret_cast<u32x4*>(vdst + 8) = u32x4{raw_v[0][2], raw_v[0][3], raw_v[1][2], raw_v[1][3]};
+        *reinterpret_cast<u32x4*>(ddst) = u32x4{raw_d[0][0], raw_d[0][1], raw_d[1][0], raw_d[1][1]};
+        *reinterpret_cast<u32x4*>(ddst + 8) = u32x4{raw_d[0][2], raw_d[0][3], raw_d[1][2], raw_d[1][3]};
+    }
+    // rf is re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
     const int row0 = n * C + RW * w;
     f32x2 rf[RW], rq[RW];
-    {
-        f32x2 rv[RW], rd[RW];
-        convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
-        convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
-        convert_rows<RW>(rv, raw_v, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
-        convert_rows<RW>(rd, raw_d, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
-        if (v_act) {
-#pragma unroll
-            for (int i = 0; i < RW; ++i) {
-                store_pair_t<T>(Vm, (size_t)(RW * w + i) * PVR + 2 * lane, rv[i].x, rv[i].y);
-                store_pair_t<T>(dOm, (size_t)(RW * w + i) * PV + 2 * lane, rd[i].x, rd[i].y);
-            }
-        }
-    }
+    convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
+    convert_rows<RW>(rq, raw_q, row0, p.N, k_act, true, 0.0f);
 
     // ---------------- gate products; scaled operand tiles ----------------
     // pr = product of the gates between each row and the block edge that faces the reference row
     // (rows after the reference: from the block start up to the row; rows before: after the row
     // up to the block end); sq/sk are kept for the epilogue: dq = sq * (...), dk = sk * (...)
     float mm0[RW], mm1[RW];
+    bf16x2 qb[RW], kb[RW];      // Q~, K~ of this thread's elements exactly as rounded for the MFMAs (epilogue)
     // sq = Q~/q and sk = K~/k from m: rows after the reference carry m on the q side, rows before on the k side
     auto scales = [&](float m0, float m1, float& sq0, float& sq1, float& sk0, float& sk1) {
         const float i0 = fast_rcp(fmaxf(m0, kTinyProduct)), i1 = fast_rcp(fmaxf(m1, kTinyProduct));
@@ -215,10 +252,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
             for (int i = RW - 1; i >= 0; --i) { pr0[i] = t0; pr1[i] = t1; t0 *= rf[i].x; t1 *= rf[i].y; }
         }
-        if (k_act) {
-            tot[w * DK + 2 * lane] = t0;
-            tot[w * DK + 2 * lane + 1] = t1;
-        }
+        if (k_act) *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{t0, t1};
         HGRN2_STAMP(0);
         __syncthreads();
         HGRN2_STAMP(1);
@@ -228,8 +262,9 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
             for (int i = 0; i < NW; ++i) {
                 const bool between = (w >= NW / 2) ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
-                mid0 *= between ? tot[i * DK + 2 * lane] : 1.0f;
-                mid1 *= between ? tot[i * DK + 2 * lane + 1] : 1.0f;
+                const f32x2 t = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
+                mid0 *= between ? t.x : 1.0f;
+                mid1 *= between ? t.y : 1.0f;
             }
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
@@ -237,35 +272,35 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
                 mm0[i] = mid0 * pr0[i]; mm1[i] = mid1 * pr1[i];
                 float sq0, sq1, sk0, sk1;
                 scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
-                store_pair_t<T>(Qm, (size_t)row * PK + 2 * lane, rq[i].x * sq0, rq[i].y * sq1);
-                store_pair_t<T>(Km, (size_t)row * PK + 2 * lane, (1.0f - rf[i].x) * sk0, (1.0f - rf[i].y) * sk1);
+                qb[i].x = (T)(rq[i].x * sq0); qb[i].y = (T)(rq[i].y * sq1);
+                kb[i].x = (T)((1.0f - rf[i].x) * sk0); kb[i].y = (T)((1.0f - rf[i].y) * sk1);
+                *reinterpret_cast<bf16x2*>(Qm + (size_t)row * PK + 2 * lane) = qb[i];
+                *reinterpret_cast<bf16x2*>(Km + (size_t)row * PK + 2 * lane) = kb[i];
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < RW; ++i) { mm0[i] = 1.0f; mm1[i] = 1.0f; }
+            for (int i = 0; i < RW; ++i) { mm0[i] = 1.0f; mm1[i] = 1.0f; qb[i] = bf16x2{(T)0.0f, (T)0.0f}; kb[i] = qb[i]; }
         }
     }
-    // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv index] (the fragments hold
-    // it already scaled and rounded: their bits go to LDS as they are), and
+    // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv position] (the fragments hold
+    // it already scaled and rounded, and in position order: their bits go to LDS as they are), and
     // R = rowsum((H_m dS) * (G_m S_n)) = g * rowsum(dS * S_n).  Once per channel tile (row tile 0).
     if (w < NAT) {
         const int ch = 32 * at + r32;
-        float rs = 0.0f;
+        f32x16 accR;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accR[v] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
-            T* row = dSm + (size_t)ch * PV + 16 * kk + 4 * g;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) rs += M::get(sS[kk], s) * M::get(sD[kk], s);
-            float x[8];
-#pragma unroll
-            for (int s = 0; s < 8; ++s) x[s] = M::get(sD[kk], s);
-            store_pair_t<T>(row, 0, x[0], x[1]);
-            store_pair_t<T>(row, 2, x[2], x[3]);
-            store_pair_t<T>(row, 8, x[4], x[5]);
-            store_pair_t<T>(row, 10, x[6], x[7]);
+            M::mma(accR, sS[kk], sD[kk]);          // [channel a][channel a'] = sum_b S'[a][b] D'[a'][b]; R is its diagonal
+            *reinterpret_cast<frag*>(dSm + (size_t)ch * PV + 16 * kk + 8 * g) = sD[kk];
         }
-        rs += __shfl_xor(rs, 32);
-        if (g == 0) Rp[ch] = rs;
+        // diagonal element of column r32: accumulator register 4 (r32 / 8) + r32 % 4 of the lane group (r32 / 4) % 2
+        const int vsel = 4 * (r32 >> 3) + (r32 & 3);
+        float rs = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) rs = (v == vsel) ? accR[v] : rs;
+        if (g == ((r32 >> 2) & 1)) Rp[ch] = rs;
     }
     HGRN2_STAMP(2);
     __syncthreads();
@@ -305,17 +340,16 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int i0 = 32 * I + 8 * c + 4 * g;
-            float x[4];
+            bf16x4 pk;
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) x[ii] = (j_glob <= i0 + ii) ? acc0[4 * c + ii] + acc1[4 * c + ii] : 0.0f;
-            store_pair_t<T>(dst, (size_t)j_glob * PC + i0, x[0], x[1]);
-            store_pair_t<T>(dst, (size_t)j_glob * PC + i0 + 2, x[2], x[3]);
+            for (int ii = 0; ii < 4; ++ii) pk[ii] = (T)((j_glob <= i0 + ii) ? acc0[4 * c + ii] + acc1[4 * c + ii] : 0.0f);
+            *reinterpret_cast<bf16x4*>(dst + (size_t)j_glob * PC + i0) = pk;
         }
     } else {
-        T* dst = (w == 6) ? Pt : dPt;
-#pragma unroll
-        for (int c = 0; c < 8; ++c)      // rows 32..63, columns 0..31: 32 x 32 values, 16 per lane
-            store_pair_t<T>(dst, (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1) + 2 * c, 0.0f, 0.0f);
+        T* dst = (w == 6) ? Pt : dPt;    // rows 32..63, columns 0..31: 32 x 32 values, 16 per lane
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1)) = z;
+        *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1) + 8) = z;
     }
     HGRN2_STAMP(4);
     __syncthreads();
@@ -324,7 +358,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     // ---------------- main contractions ----------------
     // dv tile (rt_b, bt) first: P^T dO over the chunk and K~ (H_m dS) over the channels (the masked
     // halves of P^T / dP^T are zero, so every contraction runs over the full chunk with no
-    // branches).  It goes to its staging area at once, which frees its registers.
+    // branches).  It goes to its staging area at once, which frees its registers.  Its columns
+    // come out in the position order of the dO and dS tiles and are put back here.
     if (has_b) {
         f32x16 aV, aV2;
 #pragma unroll
@@ -335,60 +370,45 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #pragma unroll
         for (int ks = 0; ks < DK / 16; ++ks)
             M::mma(aV, M::load(Km + (32 * rt_b + r32) * PK + 16 * ks + 8 * g), M::load_kmajor(dSm, PV, 16 * ks, 32 * bt, lane));
+        const int colv = 32 * bt + ((r32 & 0x13) | ((r32 & 4) << 1) | ((r32 & 8) >> 1));
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PVR + 32 * bt + r32] = (T)(aV[v] + aV2[v]);
+            dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PVR + colv] = (T)(aV[v] + aV2[v]);
     }
-    // tile (rt_a, at):  X = dP K~ + dO (G_m S_n)^T,  Y = dP^T Q~ + V (H_m dS)^T.  The second part of Y
-    // is accumulated on its own first, because sum_j K~_j * (V (H_m dS)^T)_j over ALL rows of the chunk
-    // (the R-like term of the gate gradient, see the epilogue) is taken from it.
-    f32x16 aX, aY;
+    // tile (rt_a, at), transposed (channel = accumulator row):
+    //   X^T = K~^T dP^T + (G_m S_n) dO^T,   Y1^T = Q~^T dP,   Ks^T = (H_m dS) V^T
+    f32x16 aX, aY, aKs;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { aX[v] = 0.0f; aY[v] = 0.0f; }
+    for (int v = 0; v < 16; ++v) { aX[v] = 0.0f; aY[v] = 0.0f; aKs[v] = 0.0f; }
     if (has_a) {
-        f32x16 aKs;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) aKs[v] = 0.0f;
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
-            const T* drow = dOm + (32 * rt_a + r32) * PV + 16 * kk + 4 * g;
-            const T* vrow = Vm + (32 * rt_a + r32) * PVR + 16 * kk + 4 * g;
-            M::mma(aX, M::load2(drow, drow + 8), sS[kk]);
-            M::mma(aKs, M::load2(vrow, vrow + 8), sD[kk]);
+            M::mma(aX, sS[kk], M::load(dOm + (32 * rt_a + r32) * PV + 16 * kk + 8 * g));
+            M::mma(aKs, sD[kk], M::load(Vm + (32 * rt_a + r32) * PVR + 16 * kk + 8 * g));
         }
-        float ys = 0.0f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-            ys += (float)Km[(size_t)(32 * rt_a + acc_row(v, lane)) * PK + 32 * at + r32] * aKs[v];
-        ys += __shfl_xor(ys, 32);
-        if (g == 0) Ys[rt_a * DK + 32 * at + r32] = ys;
 #pragma unroll
         for (int ks = 0; ks < 2 * NRT; ++ks) {
-            M::mma(aX, M::load_kmajor(dPt, PC, 16 * ks, 32 * rt_a, lane), M::load_kmajor(Km, PK, 16 * ks, 32 * at, lane));
-            M::mma(aY, M::load(dPt + (32 * rt_a + r32) * PC + 16 * ks + 8 * g), M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane));
+            M::mma(aX, M::load_kmajor(Km, PK, 16 * ks, 32 * at, lane), M::load_kmajor(dPt, PC, 16 * ks, 32 * rt_a, lane));
+            M::mma(aY, M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane), M::load(dPt + (32 * rt_a + r32) * PC + 16 * ks + 8 * g));
         }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) aY[v] += aKs[v];
     }
     // next chunk of this workgroup: its row loads are in flight during the staging / epilogue below
-    // (and this chunk's own f, q rows again, for the epilogue: re-reading 8 cached rows is cheaper
-    // than holding them in registers across the matrix stage)
+    // Every load is unconditional (the last chunk of a workgroup fetches itself again), which
+    // keeps the count of outstanding loads exact, so that nothing below waits for these.
     RawRows<RW> nxt_f, nxt_q;
-    const bool has_next = chunk + (int)gridDim.x < n_chunks;
-    load_rows<RW>(raw_f, p.f, seq_k, DK, col_k, row0, p.N, gate_bf16);
-    load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
-    if (has_next) load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, chunk + gridDim.x);   // v, dO of this chunk are dead
+    load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, min(chunk + (int)gridDim.x, n_chunks - 1), lane);   // v, dO of this chunk are dead
     HGRN2_STAMP(6);
     __syncthreads();     // every wave is done with the operand tiles
     HGRN2_STAMP(7);
 
-    // ---------------- staging: X, Y as [row][channel] fp32 ----------------
+    // ---------------- staging: X, Y1, Ks as [row][channel] fp32, 16 bytes per store ----------------
     if (has_a) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const size_t o = (size_t)(32 * rt_a + acc_row(v, lane)) * PF + 32 * at + r32;
-            cQ[o] = aX[v];
-            cK[o] = aY[v];
+        for (int c = 0; c < 4; ++c) {
+            const size_t o = (size_t)(32 * rt_a + r32) * PF + 32 * at + 8 * c + 4 * g;
+            *reinterpret_cast<f32x4*>(cX + o) = f32x4{aX[4 * c], aX[4 * c + 1], aX[4 * c + 2], aX[4 * c + 3]};
+            *reinterpret_cast<f32x4*>(cY + o) = f32x4{aY[4 * c], aY[4 * c + 1], aY[4 * c + 2], aY[4 * c + 3]};
+            *reinterpret_cast<f32x4*>(cKs + o) = f32x4{aKs[4 * c], aKs[4 * c + 1], aKs[4 * c + 2], aKs[4 * c + 3]};
         }
     }
     HGRN2_STAMP(8);
@@ -396,70 +416,83 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     HGRN2_STAMP(9);
 
     // ---------------- element-wise epilogue in the row-block / channel-pair layout ----------------
-    //   dq = sq X,  dk = sk Y,  e = bf16(Q~) X - bf16(K~) Y   (with the values the MFMAs consumed)
-    //   dg_s = sum_{i >= s in chunk} e_i + sum_{all j in chunk} K~_j (V (H_m dS)^T)_j + R
-    // In e the pair terms of X and Y cancel to fp32 accuracy; the outgoing-state part of Y that e
-    // subtracts for rows >= s is added back for ALL rows from the very same products, so what remains
-    // of it is the exact prefix over j < s (see the header comment).
-    float e0[RW], e1[RW], dk0[RW], dk1[RW];
+    //   dq = sq X,  dk = sk (Y1 + Ks),  e' = bf16(Q~) X - bf16(K~) Y1,  kk = bf16(K~) Ks
+    //   dg_s = sum_{i >= s in chunk} e'_i + sum_{j < s in chunk} kk_j + R
+    // (bf16(.) are the values the MFMAs consumed, so that the pair terms inside e' cancel to fp32
+    // accuracy).  Here: suffix / prefix inside the wave's row block, and the block sums to LDS.
+    float gs0[RW], gs1[RW], dk0[RW], dk1[RW];
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
     convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
-    convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
+    // rows of this wave's block to global memory: one address and constant offsets when the
+    // whole block lies inside the sequence, row by row otherwise
+    auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
+        T* bp = dst + seq_k + (size_t)row0 * DK + 2 * lane;
+        if (row0 + RW <= p.N) {
+#pragma unroll
+            for (int i = 0; i < RW; ++i) store_pair_t<T>(bp, (size_t)i * DK, x0[i], x1[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < RW; ++i)
+                if (row0 + i < p.N) store_pair_t<T>(bp, (size_t)i * DK, x0[i], x1[i]);
+        }
+    };
     if (k_act) {
+        float kk0[RW], kk1[RW], dq0[RW], dq1[RW];
         float se0 = 0.0f, se1 = 0.0f;
 #pragma unroll
         for (int i = RW - 1; i >= 0; --i) {
             const int row = RW * w + i;
-            const f32x2 xq = *reinterpret_cast<const f32x2*>(cQ + (size_t)row * PF + 2 * lane);
-            const f32x2 xk = *reinterpret_cast<const f32x2*>(cK + (size_t)row * PF + 2 * lane);
+            const f32x2 xq = *reinterpret_cast<const f32x2*>(cX + (size_t)row * PF + 2 * lane);
+            const f32x2 xy = *reinterpret_cast<const f32x2*>(cY + (size_t)row * PF + 2 * lane);
+            const f32x2 xs = *reinterpret_cast<const f32x2*>(cKs + (size_t)row * PF + 2 * lane);
             float sq0, sq1, sk0, sk1;
             scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
-            const float qs0 = rq[i].x * sq0, qs1 = rq[i].y * sq1;                       // exactly what went into Q~
-            const float ks0 = (1.0f - rf[i].x) * sk0, ks1 = (1.0f - rf[i].y) * sk1;     // ... and into K~
-            dk0[i] = sk0 * xk.x; dk1[i] = sk1 * xk.y;
-            se0 += (float)(T)qs0 * xq.x - (float)(T)ks0 * xk.x;
-            se1 += (float)(T)qs1 * xq.y - (float)(T)ks1 * xk.y;
-            e0[i] = se0; e1[i] = se1;                                                   // inclusive suffix inside the block
-            const int grow = n * C + row;
-            if (grow < p.N) store_pair_t<T>(dqg, seq_k + (size_t)grow * DK + 2 * lane, sq0 * xq.x, sq1 * xq.y);
+            const float qb0 = (float)qb[i].x, qb1 = (float)qb[i].y, kb0 = (float)kb[i].x, kb1 = (float)kb[i].y;
+            dk0[i] = sk0 * (xy.x + xs.x); dk1[i] = sk1 * (xy.y + xs.y);
+            se0 += qb0 * xq.x - kb0 * xy.x;
+            se1 += qb1 * xq.y - kb1 * xy.y;
+            gs0[i] = se0; gs1[i] = se1;                                                 // inclusive suffix inside the block
+            kk0[i] = kb0 * xs.x; kk1[i] = kb1 * xs.y;
+            dq0[i] = sq0 * xq.x; dq1[i] = sq1 * xq.y;
         }
-        blkE[w * DK + 2 * lane] = se0; blkE[w * DK + 2 * lane + 1] = se1;
+        store_block(dqg, dq0, dq1);
+        float pk0 = 0.0f, pk1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) { gs0[i] += pk0; gs1[i] += pk1; pk0 += kk0[i]; pk1 += kk1[i]; }   // exclusive prefix inside the block
+        *reinterpret_cast<f32x2*>(blkE + w * DK + 2 * lane) = f32x2{se0, se1};
+        *reinterpret_cast<f32x2*>(blkK + w * DK + 2 * lane) = f32x2{pk0, pk1};
     }
     // coalesced store of dv
     {
-        constexpr int VEC = 16 / (int)sizeof(T);
-        constexpr int VPR = DV / VEC;
+        constexpr int VPR = DV / 8;
         T* dvg = static_cast<T*>(p.dv);
         for (int idx = tid; idx < C * VPR; idx += kBwdThreads) {
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
-            if (grow < p.N) {
-                const uint4 val = *reinterpret_cast<const uint4*>(dVs + (size_t)row * PVR + cv * VEC);
-                *reinterpret_cast<uint4*>(dvg + seq_v + (size_t)grow * DV + cv * VEC) = val;
-            }
+            if (grow < p.N)
+                *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * DV + cv * 8) =
+                    *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * 8);
         }
     }
     HGRN2_STAMP(10);
     __syncthreads();
     HGRN2_STAMP(12);
     if (k_act) {
-        const int c0 = 2 * lane, c1 = 2 * lane + 1;
-        float add0 = Rp[c0] + Ys[c0] + Ys[DK + c0], add1 = Rp[c1] + Ys[c1] + Ys[DK + c1];
+        f32x2 add = *reinterpret_cast<const f32x2*>(Rp + 2 * lane);
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
-            add0 += (ww > w) ? blkE[ww * DK + c0] : 0.0f;
-            add1 += (ww > w) ? blkE[ww * DK + c1] : 0.0f;
+            const f32x2 be = *reinterpret_cast<const f32x2*>(blkE + ww * DK + 2 * lane);
+            const f32x2 bk = *reinterpret_cast<const f32x2*>(blkK + ww * DK + 2 * lane);
+            add.x += (ww > w) ? be.x : (ww < w) ? bk.x : 0.0f;
+            add.y += (ww > w) ? be.y : (ww < w) ? bk.y : 0.0f;
         }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
-            const int grow = n * C + RW * w + i;
-            if (grow < p.N) {
-                const float df0 = (e0[i] + add0) * fast_rcp(fmaxf(rf[i].x, 1e-30f)) - dk0[i];
-                const float df1 = (e1[i] + add1) * fast_rcp(fmaxf(rf[i].y, 1e-30f)) - dk1[i];
-                store_pair_t<T>(dfg, seq_k + (size_t)grow * DK + 2 * lane, df0, df1);
-            }
+            gs0[i] = (gs0[i] + add.x) * fast_rcp(fmaxf(rf[i].x, 1e-30f)) - dk0[i];
+            gs1[i] = (gs1[i] + add.y) * fast_rcp(fmaxf(rf[i].y, 1e-30f)) - dk1[i];
         }
+        store_block(dfg, gs0, gs1);
     }
 #ifdef HGRN2_PHASE_TIMING
     HGRN2_STAMP(17);
@@ -468,7 +501,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #endif
     raw_f = nxt_f;
     raw_q = nxt_q;
-    __syncthreads();     // the staging areas alias the operand tiles the next chunk is about to write
+    if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
 }
 
@@ -476,7 +509,7 @@ template <typename T, int DK, int DV>
 static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream_t stream)
 {
     typedef BwdGradLds<T, DK, DV> L;
-    auto kern = bwd_grad_kernel<T, DK, DV>;
+    auto kern = d.gate_bf16 ? bwd_grad_kernel<T, DK, DV, true> : bwd_grad_kernel<T, DK, DV, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
     if (e != hipSuccess) return e;
@@ -496,7 +529,7 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     BwdGradParams p;
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = ws_dstate;
     p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
-    p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    p.BH = d.BH; p.N = d.N; p.NC = d.NC;
 #ifdef HGRN2_PHASE_TIMING
     p.dbg = nullptr;
 #endif

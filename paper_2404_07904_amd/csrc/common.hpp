@@ -118,6 +118,33 @@ __device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, si
     }
 }
 
+// The same without any branch: rows past `last_row` re-read that row (conversion replaces them
+// by the fill value).  `seq_base` (start of the sequence, in bytes) and `row0` must be
+// wave-uniform, so that the row addresses live in scalar registers and the lane only adds its
+// byte offset; every load is issued unconditionally, which lets the compiler count outstanding
+// loads exactly instead of draining them all.
+template <int RW, bool IS_BF16>
+__device__ __forceinline__ void load_rows_clamped(RawRows<RW>& out, const char* seq_base, int row0, int last_row,
+                                                  int row_elems, int lane_col)
+{
+    constexpr int ES = IS_BF16 ? 2 : 4;
+    if (row0 + RW - 1 <= last_row) {      // whole block inside the sequence: one address, constant offsets
+        const char* rp = seq_base + (size_t)row0 * (row_elems * ES) + lane_col * ES;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            if (IS_BF16) out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + i * row_elems * ES));
+            else out.r[i] = *reinterpret_cast<const f32x2*>(rp + i * row_elems * ES);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const char* rp = seq_base + (size_t)min(row0 + i, last_row) * (row_elems * ES);
+            if (IS_BF16) out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + lane_col * ES));
+            else out.r[i] = *reinterpret_cast<const f32x2*>(rp + lane_col * ES);
+        }
+    }
+}
+
 template <int RW>
 __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>& raw, int row0, int n_rows,
                                              bool lane_active, bool is_bf16, float fill)
