@@ -103,7 +103,9 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     // both phases
     static constexpr size_t rp = cmax(p1_end, p2_end);                      // [DK] fp32  g * rowsum(dS * S_n)
     static constexpr size_t dvs = rp + (size_t)DK * sizeof(float);          // dv staging [C][PVR]
-    static constexpr size_t total = dvs + (size_t)C * PVR * sizeof(T);
+    static constexpr size_t one = dvs + (size_t)C * PVR * sizeof(T);        // [DK] fp32, all 1.0 (neutral factor)
+    static constexpr size_t zero = one + (size_t)DK * sizeof(float);        // [DK] fp32, all 0.0 (neutral term)
+    static constexpr size_t total = zero + (size_t)DK * sizeof(float);
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
@@ -136,6 +138,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     float* blkE = reinterpret_cast<float*>(smem + L::blke);
     float* blkK = reinterpret_cast<float*>(smem + L::blkk);
     T* dVs = reinterpret_cast<T*>(smem + L::dvs);
+    float* ones = reinterpret_cast<float*>(smem + L::one);
+    float* zeros = reinterpret_cast<float*>(smem + L::zero);
 
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
@@ -146,7 +150,8 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     const T* dog = static_cast<const T*>(p.dO);
 
     // tile ownership (a wave without a tile of a kind skips that work)
-    const bool has_a = w < NRT * NAT, has_b = w < NRT * NBT;
+    const bool has_a = (NRT * NAT == NW) || w < NRT * NAT, has_b = (NRT * NBT == NW) || w < NRT * NBT;
+    const bool after = w >= NW / 2;          // rows of this wave lie after the mid-chunk reference
     const int rt_a = has_a ? w / NAT : 0, at = w % NAT;     // (row tile, channel tile) of dq / dk
     const int rt_b = has_b ? w / NBT : 0, bt = w % NBT;     // (row tile, column tile) of dv
 
@@ -197,6 +202,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     u32x4 raw_v[2], raw_d[2];
     frag sS[2 * NBT], sD[2 * NBT];
     if ((int)blockIdx.x >= n_chunks) return;
+    for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
     load_chunk_rows(raw_f, raw_q, raw_v, raw_d, blockIdx.x, tid & 63);
 
   for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
@@ -214,6 +220,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 #ifdef HGRN2_PHASE_TIMING
     long long ph[24] = {0};
     long long t_prev = wall_clock64();
+    ph[20] = t_prev;
 #endif
     // V, dO tiles: raw bits, the four 4-column quads of a 16-column group stored in the order
     // (0, 2, 1, 3), i.e. column b at position b with bits 2 and 3 swapped
@@ -232,54 +239,53 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     convert_rows<RW>(rq, raw_q, row0, p.N, k_act, true, 0.0f);
 
     // ---------------- gate products; scaled operand tiles ----------------
-    // pr = product of the gates between each row and the block edge that faces the reference row
-    // (rows after the reference: from the block start up to the row; rows before: after the row
-    // up to the block end); sq/sk are kept for the epilogue: dq = sq * (...), dk = sk * (...)
-    float mm0[RW], mm1[RW];
+    // With a = inclusive gate product from the start of this wave's 8-row block, z = exclusive
+    // product to its end, t = a z the block total, mid = product of the blocks between this block
+    // and the mid-chunk reference row, and m = product of the gates between the reference row and
+    // this row:
+    //   rows after the reference:  Q~ = q m,   K~ = k / m,   m = mid a,  1/m = z / (mid t)
+    //   rows before it:            Q~ = q / m, K~ = k m,     m = mid z,  1/m = a / (mid t)
+    // so sq = Q~/q = s_a a and sk = K~/k = s_z z with per-channel block factors s_a, s_z in
+    // {mid, 1/(mid t)}: one reciprocal per channel and block, with a floor added under it so that
+    // it stays finite outside the supported gate range.  a, z, s_a, s_z are kept for the
+    // epilogue (dq = sq * (...), dk = sk * (...)).
+    float a0[RW], a1[RW], z0[RW], z1[RW], sa0 = 1.0f, sa1 = 1.0f, sz0 = 1.0f, sz1 = 1.0f;
     bf16x2 qb[RW], kb[RW];      // Q~, K~ of this thread's elements exactly as rounded for the MFMAs (epilogue)
-    // sq = Q~/q and sk = K~/k from m: rows after the reference carry m on the q side, rows before on the k side
-    auto scales = [&](float m0, float m1, float& sq0, float& sq1, float& sk0, float& sk1) {
-        const float i0 = fast_rcp(fmaxf(m0, kTinyProduct)), i1 = fast_rcp(fmaxf(m1, kTinyProduct));
-        if (w >= NW / 2) { sq0 = m0; sq1 = m1; sk0 = i0; sk1 = i1; }
-        else             { sk0 = m0; sk1 = m1; sq0 = i0; sq1 = i1; }
-    };
     {
-        float pr0[RW], pr1[RW], t0 = 1.0f, t1 = 1.0f;
-        if (w >= NW / 2) {
+        float t0 = 1.0f, t1 = 1.0f;
 #pragma unroll
-            for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; pr0[i] = t0; pr1[i] = t1; }
-        } else {
+        for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; a0[i] = t0; a1[i] = t1; }
+        float u0 = 1.0f, u1 = 1.0f;
 #pragma unroll
-            for (int i = RW - 1; i >= 0; --i) { pr0[i] = t0; pr1[i] = t1; t0 *= rf[i].x; t1 *= rf[i].y; }
-        }
+        for (int i = RW - 1; i >= 0; --i) { z0[i] = u0; z1[i] = u1; u0 *= rf[i].x; u1 *= rf[i].y; }
         if (k_act) *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{t0, t1};
         HGRN2_STAMP(0);
         __syncthreads();
         HGRN2_STAMP(1);
         if (k_act) {
-            // product of the block totals between this block and the reference row
-            float mid0 = 1.0f, mid1 = 1.0f;
-#pragma unroll
-            for (int i = 0; i < NW; ++i) {
-                const bool between = (w >= NW / 2) ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
-                const f32x2 t = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
-                mid0 *= between ? t.x : 1.0f;
-                mid1 *= between ? t.y : 1.0f;
-            }
+            // product of the (at most three) block totals between this block and the reference
+            // row; the row addresses are wave-uniform, an absent factor reads the row of ones
+            const float* r1 = after ? (w > 4 ? tot + 4 * DK : ones) : (w < 3 ? tot + 3 * DK : ones);
+            const float* r2 = after ? (w > 5 ? tot + 5 * DK : ones) : (w < 2 ? tot + 2 * DK : ones);
+            const float* r3 = after ? (w > 6 ? tot + 6 * DK : ones) : (w < 1 ? tot + 1 * DK : ones);
+            const f32x2 m1 = *reinterpret_cast<const f32x2*>(r1 + 2 * lane);
+            const f32x2 m2 = *reinterpret_cast<const f32x2*>(r2 + 2 * lane);
+            const f32x2 m3 = *reinterpret_cast<const f32x2*>(r3 + 2 * lane);
+            const float mid0 = m1.x * m2.x * m3.x, mid1 = m1.y * m2.y * m3.y;
+            const float R0 = fast_rcp(mid0 * t0 + kTinyProduct), R1 = fast_rcp(mid1 * t1 + kTinyProduct);
+            sa0 = after ? mid0 : R0; sa1 = after ? mid1 : R1;
+            sz0 = after ? R0 : mid0; sz1 = after ? R1 : mid1;
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
                 const int row = RW * w + i;
-                mm0[i] = mid0 * pr0[i]; mm1[i] = mid1 * pr1[i];
-                float sq0, sq1, sk0, sk1;
-                scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
-                qb[i].x = (T)(rq[i].x * sq0); qb[i].y = (T)(rq[i].y * sq1);
-                kb[i].x = (T)((1.0f - rf[i].x) * sk0); kb[i].y = (T)((1.0f - rf[i].y) * sk1);
+                qb[i].x = (T)(rq[i].x * (sa0 * a0[i])); qb[i].y = (T)(rq[i].y * (sa1 * a1[i]));
+                kb[i].x = (T)((1.0f - rf[i].x) * (sz0 * z0[i])); kb[i].y = (T)((1.0f - rf[i].y) * (sz1 * z1[i]));
                 *reinterpret_cast<bf16x2*>(Qm + (size_t)row * PK + 2 * lane) = qb[i];
                 *reinterpret_cast<bf16x2*>(Km + (size_t)row * PK + 2 * lane) = kb[i];
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < RW; ++i) { mm0[i] = 1.0f; mm1[i] = 1.0f; qb[i] = bf16x2{(T)0.0f, (T)0.0f}; kb[i] = qb[i]; }
+            for (int i = 0; i < RW; ++i) { qb[i] = bf16x2{(T)0.0f, (T)0.0f}; kb[i] = qb[i]; }
         }
     }
     // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv position] (the fragments hold
@@ -446,15 +452,13 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             const f32x2 xq = *reinterpret_cast<const f32x2*>(cX + (size_t)row * PF + 2 * lane);
             const f32x2 xy = *reinterpret_cast<const f32x2*>(cY + (size_t)row * PF + 2 * lane);
             const f32x2 xs = *reinterpret_cast<const f32x2*>(cKs + (size_t)row * PF + 2 * lane);
-            float sq0, sq1, sk0, sk1;
-            scales(mm0[i], mm1[i], sq0, sq1, sk0, sk1);
             const float qb0 = (float)qb[i].x, qb1 = (float)qb[i].y, kb0 = (float)kb[i].x, kb1 = (float)kb[i].y;
-            dk0[i] = sk0 * (xy.x + xs.x); dk1[i] = sk1 * (xy.y + xs.y);
-            se0 += qb0 * xq.x - kb0 * xy.x;
-            se1 += qb1 * xq.y - kb1 * xy.y;
+            dk0[i] = (sz0 * z0[i]) * (xy.x + xs.x); dk1[i] = (sz1 * z1[i]) * (xy.y + xs.y);
+            se0 = fmaf(qb0, xq.x, se0); se0 = fmaf(-kb0, xy.x, se0);
+            se1 = fmaf(qb1, xq.y, se1); se1 = fmaf(-kb1, xy.y, se1);
             gs0[i] = se0; gs1[i] = se1;                                                 // inclusive suffix inside the block
             kk0[i] = kb0 * xs.x; kk1[i] = kb1 * xs.y;
-            dq0[i] = sq0 * xq.x; dq1[i] = sq1 * xq.y;
+            dq0[i] = (sa0 * a0[i]) * xq.x; dq1[i] = (sa1 * a1[i]) * xq.y;
         }
         store_block(dqg, dq0, dq1);
         float pk0 = 0.0f, pk1 = 0.0f;
@@ -479,23 +483,25 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     __syncthreads();
     HGRN2_STAMP(12);
     if (k_act) {
+        // R + block sums of e' of the later blocks + block sums of K~ Ks of the earlier ones (row
+        // addresses are wave-uniform; this block's own slot reads the row of zeros)
         f32x2 add = *reinterpret_cast<const f32x2*>(Rp + 2 * lane);
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
-            const f32x2 be = *reinterpret_cast<const f32x2*>(blkE + ww * DK + 2 * lane);
-            const f32x2 bk = *reinterpret_cast<const f32x2*>(blkK + ww * DK + 2 * lane);
-            add.x += (ww > w) ? be.x : (ww < w) ? bk.x : 0.0f;
-            add.y += (ww > w) ? be.y : (ww < w) ? bk.y : 0.0f;
+            const float* src = (ww > w) ? blkE + ww * DK : (ww < w) ? blkK + ww * DK : zeros;
+            const f32x2 b = *reinterpret_cast<const f32x2*>(src + 2 * lane);
+            add.x += b.x; add.y += b.y;
         }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
-            gs0[i] = (gs0[i] + add.x) * fast_rcp(fmaxf(rf[i].x, 1e-30f)) - dk0[i];
-            gs1[i] = (gs1[i] + add.y) * fast_rcp(fmaxf(rf[i].y, 1e-30f)) - dk1[i];
+            gs0[i] = (gs0[i] + add.x) * fast_rcp(rf[i].x + 1e-30f) - dk0[i];
+            gs1[i] = (gs1[i] + add.y) * fast_rcp(rf[i].y + 1e-30f) - dk1[i];
         }
         store_block(dfg, gs0, gs1);
     }
 #ifdef HGRN2_PHASE_TIMING
     HGRN2_STAMP(17);
+    ph[21] = t_prev;
     if (lane == 0 && p.dbg)
         for (int k = 0; k < 24; ++k) p.dbg[((size_t)chunk * NW + w) * 24 + k] = ph[k];
 #endif
