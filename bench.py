@@ -32,7 +32,7 @@ CHUNK = 64
 # HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for a plain copy kernel of known size; bytes per launch at
 # the benchmark workload.  None until measured; see profiles/.
-MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 738.7e6}    # 537.4 MB read + 201.3 MB written (profiles/pmc_hbm_traffic_config2.md)
+MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 738.9e6}    # 537.6 MB read + 201.3 MB written (profiles/pmc_hbm_traffic_config2.md)
 
 
 def parse():
