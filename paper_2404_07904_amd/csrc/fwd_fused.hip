@@ -22,8 +22,11 @@
 //   * the dk x dv state lives in fp32 MFMA accumulators, two 32x32 tiles per wave;
 //   * wave w owns rows 8w..8w+7 of the chunk for the element-wise work (gate products along time
 //     serially in registers, channel pair per lane) and the 32x32 output tile (w/4, w%4);
-//   * every LDS tile is row-major [token][channel]; operands whose contraction index is the
-//     token are read with LDS transpose loads, so V needs no arithmetic at all on its way in;
+//   * V is a raw row-major [token][channel] copy (no arithmetic on its way in) and is read with LDS
+//     transpose loads; K~ is kept transposed ([channel][token], which the row-block layout writes
+//     as 16-byte vectors), so that the state update reads it with plain 16-byte loads; Q~ keeps
+//     its columns in the order the state fragments hold the contraction index (bits 2 and 3 of
+//     the channel swapped), so that its operand of the read-out is one 16-byte load too;
 //   * rows are fetched two chunks ahead into two alternating register sets.
 // Used for bf16 storage with dk = dv = 128 when there are enough sequences to fill the chip;
 // other cases take the sweep + read-out path.
@@ -59,16 +62,16 @@ struct FwdFusedLds {
     static constexpr int DK = 128, DV = 128, C = kChunk;
     // Row pitches in elements.  Tiles read row-major with 16-byte vectors want consecutive rows
     // 4 banks apart (+8 elements); tiles read with transpose loads (4 rows x 64 bytes per half
-    // wave) want them 16 banks apart (+32 elements); K~ is read both ways and takes +40.
-    static constexpr int PQ = DK + 8, PKK = DK + 40, PV = DV + 32, PC = C + 8, PO = DV + 8;
-    static constexpr size_t qm = 0;                                     // Q~  [2][C][PQ]
-    static constexpr size_t km = qm + (size_t)2 * C * PQ * 2;           // K~  [2][C][PKK]
-    static constexpr size_t vm = km + (size_t)2 * C * PKK * 2;          // V   [C][PV]
+    // wave) want them 16 banks apart (+32 elements).
+    static constexpr int PQ = DK + 8, PT = C + 8, PV = DV + 32, PC = C + 8, PO = DV + 8;
+    static constexpr size_t qm = 0;                                     // Q~    [2][C][PQ], columns in fragment order
+    static constexpr size_t km = qm + (size_t)2 * C * PQ * 2;           // K~^T  [2][DK][PT]
+    static constexpr size_t vm = km + (size_t)2 * DK * PT * 2;          // V     [C][PV]
     static constexpr size_t pm = vm + (size_t)C * PV * 2;               // P   [C][PC]
     static constexpr size_t sb = pm + (size_t)C * PC * 2;               // G_m S_n, bf16, fragment order
     static constexpr size_t ost = sb + (size_t)DK * DV * 2;             // O   [C][PO]
-    static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals
-    static constexpr size_t ca = tot + (size_t)kFusedWaves * DK * 4;    // [DK] fp32 state rescale
+    static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals + one row of ones
+    static constexpr size_t ca = tot + (size_t)(kFusedWaves + 1) * DK * 4;   // [DK] fp32 state rescale
     static constexpr size_t total = ca + (size_t)DK * 4;
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     typedef typename M::frag frag;
     typedef FwdFusedLds L;
     constexpr int DK = L::DK, DV = L::DV, C = L::C, NW = kFusedWaves, RW = C / NW;
-    constexpr int PQ = L::PQ, PKK = L::PKK, PV = L::PV, PC = L::PC, PO = L::PO;
+    constexpr int PQ = L::PQ, PT = L::PT, PV = L::PV, PC = L::PC, PO = L::PO;
     constexpr int NBT = DV / 32, NKS = DK / 16;
     static_assert(RW == 8 && (C / 32) * NBT == NW && (DK / 32) * NBT == 2 * NW, "tile/wave mapping");
 
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         for (int v = 0; v < 16; ++v)
             accS[j][v] = p.h0 ? p.h0[(size_t)bh * DK * DV + (size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + 32 * bt + r32]
                               : 0.0f;
-    float hprev0 = 1.0f, hprev1 = 1.0f;      // h of the previous chunk, channels 2*lane, 2*lane+1
+    float hprev0 = 1.0f, hprev1 = 1.0f;      // h of the previous chunk, channels 2*lane, 2*lane+1 (wave 0 only)
 
     // ---- row fetch, two chunks ahead, two register sets ----
     RawRows<RW> rawf[2], rawq[2];
@@ -197,40 +200,51 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         bt0 = run0; bt1 = run1;
         run0 = 1.0f; run1 = 1.0f;
 #pragma unroll
-        for (int i = RW - 1; i >= 0; --i) {
-            kz0[i] = (1.0f - rf[i].x) * run0; kz1[i] = (1.0f - rf[i].y) * run1;
-            run0 *= rf[i].x; run1 *= rf[i].y;
+        for (int i = RW - 1; i >= 0; --i) {      // k z = (1 - f) z = z_i - z_{i-1}
+            const float n0 = run0 * rf[i].x, n1 = run1 * rf[i].y;
+            kz0[i] = run0 - n0; kz1[i] = run1 - n1;
+            run0 = n0; run1 = n1;
         }
         *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{bt0, bt1};
     };
     // Second half: block factors from the exchanged totals, tiles to LDS.
     auto prep_tiles = [&](int c) {
-        f32x2 t[NW];
-#pragma unroll
-        for (int i = 0; i < NW; ++i) t[i] = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
-        float mid0 = 1.0f, mid1 = 1.0f;
-#pragma unroll
-        for (int i = 0; i < NW; ++i) {
-            const bool between = after ? (i >= NW / 2 && i < w) : (i > w && i < NW / 2);
-            mid0 *= between ? t[i].x : 1.0f;
-            mid1 *= between ? t[i].y : 1.0f;
-        }
-        const float gm0 = (t[0].x * t[1].x) * (t[2].x * t[3].x), gm1 = (t[0].y * t[1].y) * (t[2].y * t[3].y);
-        const float hh0 = (t[4].x * t[5].x) * (t[6].x * t[7].x), hh1 = (t[4].y * t[5].y) * (t[6].y * t[7].y);
-        const float R0 = fast_rcp(fmaxf(mid0 * bt0, kTinyProduct));
-        const float R1 = fast_rcp(fmaxf(mid1 * bt1, kTinyProduct));
+        // product of the (at most three) block totals between this block and the reference row;
+        // the row addresses are wave-uniform, an absent factor reads the row of ones
+        const float* ones = tot + NW * DK;
+        const float* r1 = after ? (w > 4 ? tot + 4 * DK : ones) : (w < 3 ? tot + 3 * DK : ones);
+        const float* r2 = after ? (w > 5 ? tot + 5 * DK : ones) : (w < 2 ? tot + 2 * DK : ones);
+        const float* r3 = after ? (w > 6 ? tot + 6 * DK : ones) : (w < 1 ? tot + 1 * DK : ones);
+        const f32x2 m1 = *reinterpret_cast<const f32x2*>(r1 + 2 * lane);
+        const f32x2 m2 = *reinterpret_cast<const f32x2*>(r2 + 2 * lane);
+        const f32x2 m3 = *reinterpret_cast<const f32x2*>(r3 + 2 * lane);
+        const float mid0 = m1.x * m2.x * m3.x, mid1 = m1.y * m2.y * m3.y;
+        const float R0 = fast_rcp(mid0 * bt0 + kTinyProduct);
+        const float R1 = fast_rcp(mid1 * bt1 + kTinyProduct);
         const float sa0 = after ? mid0 : R0, sa1 = after ? mid1 : R1;       // multiplies q a
         const float sz0 = after ? R0 : mid0, sz1 = after ? R1 : mid1;       // multiplies k z
-        T* Qd = Qm + (size_t)(c & 1) * C * PQ + (size_t)(RW * w) * PQ + 2 * lane;
-        T* Kd = Km + (size_t)(c & 1) * C * PKK + (size_t)(RW * w) * PKK + 2 * lane;
+        // Q~: row-major, channel pair (2l, 2l+1) at column position sigma(2l) (bits 2 and 3 swapped);
+        // K~^T: this thread's 8 tokens of each of its two channels as one 16-byte vector
+        const int qcol = ((2 * lane) & ~12) | (((2 * lane) & 4) << 1) | (((2 * lane) & 8) >> 1);
+        T* Qd = Qm + (size_t)(c & 1) * C * PQ + (size_t)(RW * w) * PQ + qcol;
+        T* Kd = Km + (size_t)(c & 1) * DK * PT + (size_t)(2 * lane) * PT + RW * w;
+        float k0[RW], k1[RW];
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
             store_pair_t<T>(Qd, (size_t)i * PQ, qa0[i] * sa0, qa1[i] * sa1);
-            store_pair_t<T>(Kd, (size_t)i * PKK, kz0[i] * sz0, kz1[i] * sz1);
+            k0[i] = kz0[i] * sz0; k1[i] = kz1[i] * sz1;
         }
-        // state rescale of the chunk: h of the previous chunk times G_m of this one
-        if (w == 0) *reinterpret_cast<f32x2*>(cA + 2 * lane) = f32x2{hprev0 * gm0, hprev1 * gm1};
-        hprev0 = hh0; hprev1 = hh1;
+        *reinterpret_cast<frag*>(Kd) = M::pack(k0);
+        *reinterpret_cast<frag*>(Kd + PT) = M::pack(k1);
+        // state rescale of the chunk, by wave 0: h of the previous chunk times G_m of this one
+        if (w == 0) {
+            f32x2 t[NW];
+#pragma unroll
+            for (int i = 0; i < NW; ++i) t[i] = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
+            const float gm0 = (t[0].x * t[1].x) * (t[2].x * t[3].x), gm1 = (t[0].y * t[1].y) * (t[2].y * t[3].y);
+            *reinterpret_cast<f32x2*>(cA + 2 * lane) = f32x2{hprev0 * gm0, hprev1 * gm1};
+            hprev0 = (t[4].x * t[5].x) * (t[6].x * t[7].x); hprev1 = (t[4].y * t[5].y) * (t[6].y * t[7].y);
+        }
     };
 
     // O leaves through registers that stay reserved for the whole pass (see the end of stage B):
@@ -258,6 +272,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     // ---- prologue: rows of chunks 0 and 1 in flight, element-wise work of chunk 0 ----
     // the never-written block of P (rows 0..31 x columns 32..63) must read as zero
     for (int idx = tid; idx < 32 * 32; idx += kFusedThreads) Pm[(idx >> 5) * PC + 32 + (idx & 31)] = (T)0.0f;
+    if (tid < DK) tot[NW * DK + tid] = 1.0f;
     load_f(rawf[0], 0); load_q(rawq[0], 0); load_v(rawv, 0);
     load_f(rawf[1], 1); load_q(rawq[1], 1);
     prep_gates(rawf[0], rawq[0], 0);
@@ -269,7 +284,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     auto chunk = [&](auto PAR, int n) {
         constexpr int par = decltype(PAR)::value;
         const T* Qc = Qm + (size_t)par * C * PQ;
-        const T* Kc = Km + (size_t)par * C * PKK;
+        const T* Kc = Km + (size_t)par * DK * PT;
         // ======================= stage A =======================
         store_o(n - 1);
         store_v(rawv);
@@ -300,10 +315,18 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+            // K~ operand: lane (token 32 J + r32, g) needs the channels of k-step ks in fragment order,
+            // 16 ks + 4 g + {0..3} and 16 ks + 8 + 4 g + {0..3}: two transpose reads of K~^T rows
+            typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+            const int i16 = lane & 15;
+            const T* kp = Kc + (size_t)(4 * g + (i16 >> 2)) * PT + 32 * J + (lane & 16) + 4 * (i16 & 3);
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
-                M::mma(acc, M::load(Kc + (32 * J + r32) * PKK + 16 * ks + 8 * g),
+            for (int ks = 0; ks < NKS; ++ks) {
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks) * PT));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks + 8) * PT));
+                M::mma(acc, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7),
                        M::load(Qc + (32 * I + r32) * PQ + 16 * ks + 8 * g));     // acc[row j][col i]
+            }
             const int i_glob = 32 * I + r32;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -327,15 +350,14 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
 #pragma unroll
         for (int ks = 0; ks < C / 16; ++ks) {
             const frag vf = M::load_kmajor(Vm, PV, 16 * ks, 32 * bt, lane);
-            M::mma(accS[0], M::load_kmajor(Kc, PKK, 16 * ks, 32 * at0, lane), vf);
-            M::mma(accS[1], M::load_kmajor(Kc, PKK, 16 * ks, 32 * (at0 + 1), lane), vf);
+            M::mma(accS[0], M::load(Kc + (32 * at0 + r32) * PT + 16 * ks + 8 * g), vf);
+            M::mma(accS[1], M::load(Kc + (32 * (at0 + 1) + r32) * PT + 16 * ks + 8 * g), vf);
             M::mma(accO, vf, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g));   // zero block included
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
                 const int ks2 = 2 * ks + hh;
-                const T* qrow = Qc + (32 * rt + r32) * PQ + 16 * ks2 + 4 * g;
                 M::mma(accO, *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane)),
-                       M::load2(qrow, qrow + 8));
+                       M::load(Qc + (32 * rt + r32) * PQ + 16 * ks2 + 8 * g));
             }
         }
         HGRN2_STAMP(3);
