@@ -28,6 +28,9 @@
 //     its columns in the order the state fragments hold the contraction index (bits 2 and 3 of
 //     the channel swapped), so that its operand of the read-out is one 16-byte load too;
 //   * rows are fetched two chunks ahead into two alternating register sets.
+//   * with fewer sequences than compute units, two workgroups share a sequence, each owning one
+//     half of the dv columns (of V, O and the state): the element-wise work on q and f and the
+//     P blocks are done twice, everything that scales with dv is halved, and the whole chip is busy.
 // Used for bf16 storage with dk = dv = 128 when there are enough sequences to fill the chip;
 // other cases take the sweep + read-out path.
 #include "common.hpp"
@@ -46,7 +49,7 @@ struct FwdFusedParams {
     const float* h0;
     void* o;
     float* hT;
-    int N, NC;
+    int N, NC, BH;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][16] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -58,35 +61,38 @@ struct FwdFusedParams {
 #define HGRN2_STAMP(k) do { } while (0)
 #endif
 
-struct FwdFusedLds {
-    static constexpr int DK = 128, DV = 128, C = kChunk;
+template <int NSPLIT> struct FwdFusedLds {
+    static constexpr int DK = 128, DV = 128, DVW = DV / NSPLIT, C = kChunk;   // DVW: dv columns of one workgroup
     // Row pitches in elements.  Tiles read row-major with 16-byte vectors want consecutive rows
     // 4 banks apart (+8 elements); tiles read with transpose loads (4 rows x 64 bytes per half
     // wave) want them 16 banks apart (+32 elements).
-    static constexpr int PQ = DK + 8, PT = C + 8, PV = DV + 32, PC = C + 8, PO = DV + 8;
+    static constexpr int PQ = DK + 8, PT = C + 8, PV = DVW + 32, PC = C + 8, PO = DVW + 8;
     static constexpr size_t qm = 0;                                     // Q~    [2][C][PQ], columns in fragment order
     static constexpr size_t km = qm + (size_t)2 * C * PQ * 2;           // K~^T  [2][DK][PT]
     static constexpr size_t vm = km + (size_t)2 * DK * PT * 2;          // V     [C][PV]
     static constexpr size_t pm = vm + (size_t)C * PV * 2;               // P   [C][PC]
     static constexpr size_t sb = pm + (size_t)C * PC * 2;               // G_m S_n, bf16, fragment order
-    static constexpr size_t ost = sb + (size_t)DK * DV * 2;             // O   [C][PO]
+    static constexpr size_t ost = sb + (size_t)DK * DVW * 2;            // O   [C][PO]
     static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals + one row of ones
     static constexpr size_t ca = tot + (size_t)(kFusedWaves + 1) * DK * 4;   // [DK] fp32 state rescale
     static constexpr size_t total = ca + (size_t)DK * 4;
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <bool GATE_BF16>
+template <bool GATE_BF16, int NSPLIT>
 __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams p)
 {
     typedef __bf16 T;
     typedef Mma<T> M;
     typedef typename M::frag frag;
-    typedef FwdFusedLds L;
-    constexpr int DK = L::DK, DV = L::DV, C = L::C, NW = kFusedWaves, RW = C / NW;
+    typedef FwdFusedLds<NSPLIT> L;
+    constexpr int DK = L::DK, DV = L::DV, DVW = L::DVW, C = L::C, NW = kFusedWaves, RW = C / NW;
     constexpr int PQ = L::PQ, PT = L::PT, PV = L::PV, PC = L::PC, PO = L::PO;
-    constexpr int NBT = DV / 32, NKS = DK / 16;
-    static_assert(RW == 8 && (C / 32) * NBT == NW && (DK / 32) * NBT == 2 * NW, "tile/wave mapping");
+    constexpr int NBT = DVW / 32, NKS = DK / 16;
+    constexpr int NST = (DK / 32) * NBT / NW;        // state tiles per wave: 2 (whole dv) or 1 (half)
+    constexpr int NOT = (C / 32) * NBT;              // output tiles of the workgroup: waves 0 .. NOT-1 own one
+    constexpr int PW0 = (NOT == NW) ? 0 : NOT;       // first of the three waves that compute the P blocks
+    static_assert(RW == 8 && NST * NW == (DK / 32) * NBT && NOT <= NW && PW0 + 3 <= NW, "tile/wave mapping");
 
     extern __shared__ __align__(16) char smem[];
     T* Qm = reinterpret_cast<T*>(smem + L::qm);
@@ -98,7 +104,13 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     float* cA = reinterpret_cast<float*>(smem + L::ca);
 
-    const int bh = blockIdx.x;
+    // workgroup -> (sequence, dv half): ids 8 apart land on the same XCD (ids are dealt to the 8
+    // XCDs round-robin), so the two halves of a sequence share an L2 for the q, f rows both read
+    int bh, split;
+    if (NSPLIT == 1) { bh = blockIdx.x; split = 0; }
+    else { const int x = blockIdx.x & 7, r = blockIdx.x >> 3; split = r % NSPLIT; bh = (r / NSPLIT) * 8 + x; }
+    if (bh >= p.BH) return;                  // padding of the grid (uniform, before any barrier)
+    const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
     const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
@@ -107,32 +119,39 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     T* og = static_cast<T*>(p.o);
     const int NC = p.NC;
 
-    const int rt = w / NBT, bt = w % NBT;    // output tile of this wave
-    const int at0 = 2 * rt;                  // its two state tiles: (at0, bt), (at0 + 1, bt)
+    const int rt = w / NBT, bt = w % NBT;    // output tile (rt, bt) of this wave, if w < NOT
+    const int at0 = NST * (w / NBT);         // its state tiles: (at0 .. at0 + NST - 1, bt)
+    const bool has_o = (NOT == NW) || w < NOT;
+    const bool is_p = w >= PW0 && w < PW0 + 3;
     const bool after = w >= NW / 2;          // rows of this wave lie after the mid-chunk reference
 
     if (NC == 0) {                           // empty sequence: hT = h0 (uniform early exit, before any barrier)
         if (p.hT)
-            for (int idx = tid; idx < DK * DV; idx += kFusedThreads)
-                p.hT[(size_t)bh * DK * DV + idx] = p.h0 ? p.h0[(size_t)bh * DK * DV + idx] : 0.0f;
+            for (int idx = tid; idx < DK * DVW; idx += kFusedThreads) {
+                const size_t e = (size_t)bh * DK * DV + (size_t)(idx / DVW) * DV + dv0 + idx % DVW;
+                p.hT[e] = p.h0 ? p.h0[e] : 0.0f;
+            }
         return;
     }
 
     // ---- state: fp32 accumulators.  Between chunks they hold S_n / h(n-1); see stage A. ----
-    f32x16 accS[2];
+    f32x16 accS[NST];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NST; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            accS[j][v] = p.h0 ? p.h0[(size_t)bh * DK * DV + (size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + 32 * bt + r32]
+            accS[j][v] = p.h0 ? p.h0[(size_t)bh * DK * DV + (size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + dv0 + 32 * bt + r32]
                               : 0.0f;
     float hprev0 = 1.0f, hprev1 = 1.0f;      // h of the previous chunk, channels 2*lane, 2*lane+1 (wave 0 only)
 
     // ---- row fetch, two chunks ahead, two register sets ----
     RawRows<RW> rawf[2], rawq[2];
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    u32x4 rawv[2];                   // V is fetched one chunk ahead only
-    const int vrow = RW * w + (lane >> 4), vcol = 8 * (lane & 15);      // V copy: 16 bytes per lane, rows vrow, vrow+4
+    constexpr int VPR = DVW / 8;             // 16-byte vectors per V / O row
+    constexpr int NVV = VPR / 8;             // vectors per thread
+    constexpr int VRS = 64 / VPR;            // rows one wave covers per vector
+    u32x4 rawv[NVV];                 // V is fetched one chunk ahead only
+    const int vrow = RW * w + lane / VPR, vcol = 8 * (lane % VPR);      // V copy: 16 bytes per lane, rows vrow (+ VRS)
     // Every load is issued unconditionally (a row past the end of the sequence re-reads the last
     // row), and the chunk loop always runs an even number of passes, so that its body is
     // straight-line code: the compiler can then count outstanding loads exactly and the two
@@ -140,7 +159,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     // to one on every row and is an exact no-op on the state.  Row addresses are wave-uniform.
     const char* fbase = static_cast<const char*>(p.f) + seq_k * (GATE_BF16 ? 2 : 4);
     const char* qbase = reinterpret_cast<const char*>(qg + seq_k);
-    const char* vbase = reinterpret_cast<const char*>(vg + seq_v);
+    const char* vbase = reinterpret_cast<const char*>(vg + seq_v + dv0);
     const int last_row = p.N - 1;
     auto load_f = [&](RawRows<RW>& d, int c) {
         const int row0 = c * C + RW * w;
@@ -159,19 +178,19 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
             d.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + 4 * lane));
         }
     };
-    auto load_v = [&](u32x4 (&d)[2], int c) {
+    auto load_v = [&](u32x4 (&d)[NVV], int c) {
         const int row0 = c * C + RW * w;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int rc = min(row0 + (lane >> 4) + 4 * j, last_row);
+        for (int j = 0; j < NVV; ++j) {
+            const int rc = min(row0 + lane / VPR + VRS * j, last_row);
             d[j] = *reinterpret_cast<const u32x4*>(vbase + (size_t)rc * (DV * 2) + 2 * vcol);
         }
     };
     // Rows past the end of the sequence need no masking here: their K~ is zero (f = 1 there), so
     // whatever finite values stand in for them never reach a stored output or the state.
-    auto store_v = [&](const u32x4 (&s)[2]) {
+    auto store_v = [&](const u32x4 (&s)[NVV]) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4*>(Vm + (vrow + 4 * j) * PV + vcol) = s[j];
+        for (int j = 0; j < NVV; ++j) *reinterpret_cast<u32x4*>(Vm + (vrow + VRS * j) * PV + vcol) = s[j];
     };
 
     // ---- element-wise work of one chunk, split around the exchange of the block totals ----
@@ -250,9 +269,8 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     // O leaves through registers that stay reserved for the whole pass (see the end of stage B):
     // a global store reads its data registers late, and overwriting them earlier would make the
     // wave wait for the store, and with it for every prefetch issued before it, to complete.
-    u32x4 obuf[C * (DV / 8) / kFusedThreads];
+    u32x4 obuf[C * VPR / kFusedThreads];
     auto store_o = [&](int c) {
-        constexpr int VPR = DV / 8;
 #pragma unroll
         for (int k = 0; k < C * VPR / kFusedThreads; ++k) {
             const int idx = tid + k * kFusedThreads;
@@ -260,7 +278,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
             const int grow = c * C + row;
             obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
             if ((unsigned)grow < (unsigned)p.N)      // also false for the chunk "-1" of the first pass
-                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * DV + cv * 8) = obuf[k];
+                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * DV + dv0 + cv * 8) = obuf[k];
         }
     };
 
@@ -291,7 +309,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         load_v(rawv, n + 1);
         // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NST; ++j) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const f32x4 cm = *reinterpret_cast<const f32x4*>(cA + 32 * (at0 + j) + 8 * c + 4 * g);
@@ -310,8 +328,9 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         load_f(rawf[1 - par], n + 3); load_q(rawq[1 - par], n + 3);
         HGRN2_STAMP(0);
         // P^T blocks (J <= I), one per wave
-        if (w < 3) {
-            const int I = (w == 0) ? 0 : 1, J = (w == 2) ? 1 : 0;     // 0:(0,0) 1:(0,1) 2:(1,1) as (J,I)
+        if (is_p) {
+            const int pb = w - PW0;
+            const int I = (pb == 0) ? 0 : 1, J = (pb == 2) ? 1 : 0;   // 0:(0,0) 1:(0,1) 2:(1,1) as (J,I)
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -350,30 +369,35 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
 #pragma unroll
         for (int ks = 0; ks < C / 16; ++ks) {
             const frag vf = M::load_kmajor(Vm, PV, 16 * ks, 32 * bt, lane);
-            M::mma(accS[0], M::load(Kc + (32 * at0 + r32) * PT + 16 * ks + 8 * g), vf);
-            M::mma(accS[1], M::load(Kc + (32 * (at0 + 1) + r32) * PT + 16 * ks + 8 * g), vf);
-            M::mma(accO, vf, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g));   // zero block included
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                const int ks2 = 2 * ks + hh;
-                M::mma(accO, *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane)),
-                       M::load(Qc + (32 * rt + r32) * PQ + 16 * ks2 + 8 * g));
+            for (int j = 0; j < NST; ++j)
+                M::mma(accS[j], M::load(Kc + (32 * (at0 + j) + r32) * PT + 16 * ks + 8 * g), vf);
+            if (has_o) {
+                M::mma(accO, vf, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g));   // zero block included
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    const int ks2 = 2 * ks + hh;
+                    M::mma(accO, *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane)),
+                           M::load(Qc + (32 * rt + r32) * PQ + 16 * ks2 + 8 * g));
+                }
             }
         }
         HGRN2_STAMP(3);
         prep_tiles(n + 1);
         HGRN2_STAMP(4);
         // accO[v] = O[token 32 rt + r32][channel 32 bt + 8 (v/4) + 4 g + v%4]
+        if (has_o) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            bf16x4 pk;
+            for (int c = 0; c < 4; ++c) {
+                bf16x4 pk;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)accO[4 * c + jj];
-            *reinterpret_cast<bf16x4*>(Ost + (size_t)(32 * rt + r32) * PO + 32 * bt + 8 * c + 4 * g) = pk;
+                for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)accO[4 * c + jj];
+                *reinterpret_cast<bf16x4*>(Ost + (size_t)(32 * rt + r32) * PO + 32 * bt + 8 * c + 4 * g) = pk;
+            }
         }
         HGRN2_STAMP(5);
 #pragma unroll
-        for (int k = 0; k < C * (DV / 8) / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
+        for (int k = 0; k < C * VPR / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
         __syncthreads();
         HGRN2_STAMP(6);
     };
@@ -387,17 +411,17 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
 
 #ifdef HGRN2_PHASE_TIMING
     if (lane == 0 && p.dbg)
-        for (int k = 0; k < 16; ++k) p.dbg[((size_t)bh * NW + w) * 16 + k] = ph[k];
+        for (int k = 0; k < 16; ++k) p.dbg[((size_t)blockIdx.x * NW + w) * 16 + k] = ph[k];
 #endif
     if (p.hT) {
         // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1)
         float* s1 = p.hT + (size_t)bh * DK * DV;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NST; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int a = 32 * (at0 + j) + acc_row(v, lane);
-                s1[(size_t)a * DV + 32 * bt + r32] = cA[a] * accS[j][v];
+                s1[(size_t)a * DV + dv0 + 32 * bt + r32] = cA[a] * accS[j][v];
             }
     }
 }
@@ -407,20 +431,29 @@ bool fwd_fused_supported(const SeqDims& d)
     return d.io_bf16 && d.dk == 128 && d.dv == 128 && d.BH >= 64;
 }
 
+template <int NSPLIT>
+static hipError_t launch_fused(const SeqDims& d, const FwdFusedParams& p, hipStream_t stream)
+{
+    typedef FwdFusedLds<NSPLIT> L;
+    auto kern = d.gate_bf16 ? fwd_fused_kernel<true, NSPLIT> : fwd_fused_kernel<false, NSPLIT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
+    if (e != hipSuccess) return e;
+    const unsigned grid = (NSPLIT == 1) ? (unsigned)d.BH : (unsigned)(NSPLIT * 8 * ((d.BH + 7) / 8));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedThreads), L::total, stream, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, const void* v, const float* h0,
                             void* o, float* hT, hipStream_t stream)
 {
     if (d.BH == 0) return hipSuccess;
-    typedef FwdFusedLds L;
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
-    p.N = d.N; p.NC = d.NC;
-    auto kern = d.gate_bf16 ? fwd_fused_kernel<true> : fwd_fused_kernel<false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(d.BH), dim3(kFusedThreads), L::total, stream, p);
-    return hipGetLastError();
+    p.N = d.N; p.NC = d.NC; p.BH = d.BH;
+    // one workgroup per sequence fills the 256 compute units from 256 sequences on; below that,
+    // two workgroups per sequence (each half of the dv columns) keep twice as many units busy
+    return d.BH > 192 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
 }
 
 }   // namespace hgrn2

@@ -106,6 +106,27 @@ def test_fwd_fused_path(N, gate):
     run_fwd(w)
 
 
+@pytest.mark.parametrize("N", [65, 200])
+@pytest.mark.parametrize("gate", ["bf16", "f32"])
+def test_fwd_fused_path_many_sequences(N, gate):
+    """More than 192 sequences: one workgroup per sequence owning all dv columns (below that, two
+    workgroups share a sequence, which is what the other fused-path cases run)."""
+    print("\n[fwd fused] B*H=203 N=%d gate=%s" % (N, gate), flush=True)
+    w = synth.make_sequence(700 + N, 29, 7, N, 128, 128, io_dtype="bf16", gate_dtype=gate, lb=0.2, with_h0=True)
+    run_fwd(w)
+
+
+def test_fwd_fused_path_no_h0_no_hT():
+    print("\n[fwd fused] B*H=66, no h0, no hT", flush=True)
+    w = synth.make_sequence(91, 6, 11, 130, 128, 128, io_dtype="bf16", lb=0.3)
+    q, f, v = dev(w.q, "bf16"), dev(w.f, "bf16"), dev(w.v, "bf16")
+    o, hT = binding.hgrn2_fwd(q, f, v, None, want_hT=False)
+    torch.cuda.synchronize()
+    assert hT is None
+    ro, _ = oracle.fwd(w.q, w.f, w.v, None)
+    check("o", host(o), ro, TOL["bf16"])
+
+
 def test_fwd_fused_matches_two_kernel_path():
     """The single-pass kernel and sweep + read-out agree to bf16 rounding on the same inputs."""
     w = synth.make_sequence(77, 8, 8, 300, 128, 128, io_dtype="bf16", lb=0.3, with_h0=True)
