@@ -38,8 +38,8 @@ MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 738.9e6}    # 537.6 MB read + 201.3
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--layer", type=int, default=12, help="gate statistics: layer of the 24-layer stack (0, 12, 23)")
     ap.add_argument("--decode-steps", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,7 +114,7 @@ def main():
     half = ws.numel() // 2
     ws_a, ws_b = ws[:half], ws[half:]
 
-    def timed(fn, reps=10):
+    def timed(fn, reps=30):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for i, (a, b) in enumerate(ev):
             a.record()

@@ -72,7 +72,8 @@ template <int NSPLIT> struct FwdFusedLds {
     static constexpr size_t vm = km + (size_t)2 * DK * PT * 2;          // V     [C][PV]
     static constexpr size_t pm = vm + (size_t)C * PV * 2;               // P   [C][PC]
     static constexpr size_t sb = pm + (size_t)C * PC * 2;               // G_m S_n, bf16, fragment order
-    static constexpr size_t ost = sb + (size_t)DK * DVW * 2;            // O   [C][PO]
+    static constexpr int NSB = (NSPLIT == 2) ? 2 : 1;                  // copies of the published state (see LATE_QS)
+    static constexpr size_t ost = sb + (size_t)NSB * DK * DVW * 2;      // O   [C][PO]
     static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals + one row of ones
     static constexpr size_t ca = tot + (size_t)(kFusedWaves + 1) * DK * 4;   // [DK] fp32 state rescale
     static constexpr size_t total = ca + (size_t)DK * 4;
@@ -92,6 +93,17 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     constexpr int NST = (DK / 32) * NBT / NW;        // state tiles per wave: 2 (whole dv) or 1 (half)
     constexpr int NOT = (C / 32) * NBT;              // output tiles of the workgroup: waves 0 .. NOT-1 own one
     constexpr int PW0 = (NOT == NW) ? 0 : NOT;       // first of the three waves that compute the P blocks
+    // With half the dv columns per workgroup only four waves own an output tile; their read-out of
+    // the incoming state, Q~ (G_m S_n), is then issued one stage late, in stage A of the next pass,
+    // next to the P blocks the other waves compute there (the published state is double-buffered
+    // for that, and O(n) leaves in stage B of pass n+1).  This evens out the matrix work of the
+    // two stages.
+    constexpr bool LATE_QS = (NSPLIT == 2);
+    // With the smaller register footprint of the split variant, every MFMA chain requests all its
+    // operand fragments first and the instruction scheduler is told not to sink those loads back
+    // between the MFMAs: one LDS latency per chain instead of one per k-step pair.
+    constexpr bool BATCH_LOADS = (NSPLIT == 2);
+    constexpr int KB8 = BATCH_LOADS ? DK / 16 : 2, KB4 = BATCH_LOADS ? kChunk / 16 : 1;   // k-steps per batch
     static_assert(RW == 8 && NST * NW == (DK / 32) * NBT && NOT <= NW && PW0 + 3 <= NW, "tile/wave mapping");
 
     extern __shared__ __align__(16) char smem[];
@@ -162,21 +174,10 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     const char* vbase = reinterpret_cast<const char*>(vg + seq_v + dv0);
     const int last_row = p.N - 1;
     auto load_f = [&](RawRows<RW>& d, int c) {
-        const int row0 = c * C + RW * w;
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const char* rp = fbase + (size_t)min(row0 + i, last_row) * (DK * (GATE_BF16 ? 2 : 4));
-            if (GATE_BF16) d.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + 4 * lane));
-            else d.r[i] = *reinterpret_cast<const f32x2*>(rp + 8 * lane);
-        }
+        load_rows_clamped<RW, GATE_BF16>(d, fbase, c * C + RW * w, last_row, DK, 2 * lane);
     };
     auto load_q = [&](RawRows<RW>& d, int c) {
-        const int row0 = c * C + RW * w;
-#pragma unroll
-        for (int i = 0; i < RW; ++i) {
-            const char* rp = qbase + (size_t)min(row0 + i, last_row) * (DK * 2);
-            d.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + 4 * lane));
-        }
+        load_rows_clamped<RW, true>(d, qbase, c * C + RW * w, last_row, DK, 2 * lane);
     };
     auto load_v = [&](u32x4 (&d)[NVV], int c) {
         const int row0 = c * C + RW * w;
@@ -299,14 +300,51 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     prep_tiles(0);
     __syncthreads();
 
+    // output tile accumulator, transposed: accO[v] = O[token 32 rt + r32][channel 32 bt + 8 (v/4) + 4 g + v%4]
+    f32x16 accO;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
+    // (all operand fragments are requested before the first MFMA, so that one LDS latency is paid,
+    // not one per k-step)
+    auto read_out_state = [&](const T* Qx, const T* Sx) {        // accO += ((G_m S)^T Q~^T) tile (bt, rt)
+#pragma unroll
+        for (int k0 = 0; k0 < NKS; k0 += KB8) {
+            frag sa[KB8], qa[KB8];
+#pragma unroll
+            for (int k = 0; k < KB8; ++k) {
+                const int ks2 = k0 + k;
+                sa[k] = *reinterpret_cast<const frag*>(Sx + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane));
+                qa[k] = M::load(Qx + (32 * rt + r32) * PQ + 16 * ks2 + 8 * g);
+            }
+            if (BATCH_LOADS) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < KB8; ++k) M::mma(accO, sa[k], qa[k]);
+        }
+    };
+    auto stage_o = [&]() {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            bf16x4 pk;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)accO[4 * c + jj];
+            *reinterpret_cast<bf16x4*>(Ost + (size_t)(32 * rt + r32) * PO + 32 * bt + 8 * c + 4 * g) = pk;
+        }
+    };
+    auto pin_obuf = [&]() {
+#pragma unroll
+        for (int k = 0; k < C * VPR / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
+    };
+
     auto chunk = [&](auto PAR, int n) {
         constexpr int par = decltype(PAR)::value;
         const T* Qc = Qm + (size_t)par * C * PQ;
         const T* Kc = Km + (size_t)par * DK * PT;
+        T* Sp = Sb + (LATE_QS ? (size_t)par * DK * DVW : 0);      // where this pass publishes G_m(n) S_n
         // ======================= stage A =======================
-        store_o(n - 1);
+        if (!LATE_QS) store_o(n - 1);
         store_v(rawv);
         load_v(rawv, n + 1);
+        HGRN2_STAMP(7);
         // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
 #pragma unroll
         for (int j = 0; j < NST; ++j) {
@@ -321,12 +359,22 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
                 float x[8];
 #pragma unroll
                 for (int s = 0; s < 8; ++s) x[s] = accS[j][8 * half + s];
-                *reinterpret_cast<frag*>(Sb + state_frag_offset(at0 + j, bt, NBT, half, lane)) = M::pack(x);
+                *reinterpret_cast<frag*>(Sp + state_frag_offset(at0 + j, bt, NBT, half, lane)) = M::pack(x);
             }
         }
+        HGRN2_STAMP(8);
         prep_gates(rawf[1 - par], rawq[1 - par], n + 1);
+        HGRN2_STAMP(9);
         load_f(rawf[1 - par], n + 3); load_q(rawq[1 - par], n + 3);
         HGRN2_STAMP(0);
+        if (LATE_QS) {
+            // O(n-1) is completed here: its P V part was accumulated in stage B of the previous pass
+            if (has_o) {
+                read_out_state(Qm + (size_t)(1 - par) * C * PQ, Sb + (size_t)(1 - par) * DK * DVW);
+                stage_o();
+            }
+            pin_obuf();
+        }
         // P^T blocks (J <= I), one per wave
         if (is_p) {
             const int pb = w - PW0;
@@ -340,11 +388,19 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
             const int i16 = lane & 15;
             const T* kp = Kc + (size_t)(4 * g + (i16 >> 2)) * PT + 32 * J + (lane & 16) + 4 * (i16 & 3);
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks) * PT));
-                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks + 8) * PT));
-                M::mma(acc, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7),
-                       M::load(Qc + (32 * I + r32) * PQ + 16 * ks + 8 * g));     // acc[row j][col i]
+            for (int k0 = 0; k0 < NKS; k0 += KB8) {
+                frag ka[KB8], qf[KB8];
+#pragma unroll
+                for (int k = 0; k < KB8; ++k) {
+                    const int ks = k0 + k;
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks) * PT));
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(kp + (size_t)(16 * ks + 8) * PT));
+                    ka[k] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    qf[k] = M::load(Qc + (32 * I + r32) * PQ + 16 * ks + 8 * g);
+                }
+                if (BATCH_LOADS) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int k = 0; k < KB8; ++k) M::mma(acc, ka[k], qf[k]);     // acc[row j][col i]
             }
             const int i_glob = 32 * I + r32;
 #pragma unroll
@@ -363,41 +419,37 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         HGRN2_STAMP(2);
         // ======================= stage B =======================
         // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
-        f32x16 accO;
+        if (LATE_QS) store_o(n - 1);
 #pragma unroll
         for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
 #pragma unroll
-        for (int ks = 0; ks < C / 16; ++ks) {
-            const frag vf = M::load_kmajor(Vm, PV, 16 * ks, 32 * bt, lane);
+        for (int k0 = 0; k0 < C / 16; k0 += KB4) {
+            frag vf[KB4], kf[KB4][NST], pf[KB4];
 #pragma unroll
-            for (int j = 0; j < NST; ++j)
-                M::mma(accS[j], M::load(Kc + (32 * (at0 + j) + r32) * PT + 16 * ks + 8 * g), vf);
-            if (has_o) {
-                M::mma(accO, vf, M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g));   // zero block included
+            for (int k = 0; k < KB4; ++k) {
+                const int ks = k0 + k;
+                vf[k] = M::load_kmajor(Vm, PV, 16 * ks, 32 * bt, lane);
 #pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const int ks2 = 2 * ks + hh;
-                    M::mma(accO, *reinterpret_cast<const frag*>(Sb + state_frag_offset(ks2 >> 1, bt, NBT, ks2 & 1, lane)),
-                           M::load(Qc + (32 * rt + r32) * PQ + 16 * ks2 + 8 * g));
-                }
+                for (int j = 0; j < NST; ++j) kf[k][j] = M::load(Kc + (32 * (at0 + j) + r32) * PT + 16 * ks + 8 * g);
+                if (has_o) pf[k] = M::load(Pm + (32 * rt + r32) * PC + 16 * ks + 8 * g);   // zero block included
+            }
+            if (BATCH_LOADS) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < KB4; ++k) {
+#pragma unroll
+                for (int j = 0; j < NST; ++j) M::mma(accS[j], kf[k][j], vf[k]);
+                if (has_o) M::mma(accO, vf[k], pf[k]);
             }
         }
+        if (!LATE_QS) read_out_state(Qc, Sp);
         HGRN2_STAMP(3);
         prep_tiles(n + 1);
         HGRN2_STAMP(4);
-        // accO[v] = O[token 32 rt + r32][channel 32 bt + 8 (v/4) + 4 g + v%4]
-        if (has_o) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                bf16x4 pk;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)accO[4 * c + jj];
-                *reinterpret_cast<bf16x4*>(Ost + (size_t)(32 * rt + r32) * PO + 32 * bt + 8 * c + 4 * g) = pk;
-            }
+        if (!LATE_QS) {
+            if (has_o) stage_o();
+            pin_obuf();
         }
         HGRN2_STAMP(5);
-#pragma unroll
-        for (int k = 0; k < C * VPR / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
         __syncthreads();
         HGRN2_STAMP(6);
     };
@@ -407,7 +459,20 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
         chunk(std::integral_constant<int, 0>(), n_end);
         chunk(std::integral_constant<int, 1>(), n_end + 1);
     }
-    store_o(n_end - 1);
+    if (LATE_QS) {
+        // an even number of chunks leaves the last one without its state read-out (an odd number
+        // is followed by a pass over an empty chunk, which has done it)
+        if (NC % 2 == 0) {
+            if (has_o) {
+                read_out_state(Qm + (size_t)((NC - 1) & 1) * C * PQ, Sb + (size_t)((NC - 1) & 1) * DK * DVW);
+                stage_o();
+            }
+            __syncthreads();
+            store_o(NC - 1);
+        }
+    } else {
+        store_o(n_end - 1);
+    }
 
 #ifdef HGRN2_PHASE_TIMING
     if (lane == 0 && p.dbg)
