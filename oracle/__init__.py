@@ -130,3 +130,47 @@ def bwd(q, f, v, dO, h0=None, dhT=None, want_dh0=True):
     _check(_load().hgrn2_oracle_bwd(B, H, N, dk, dv, _p(q), _p(f), _p(v), _p(h0), _p(dO), _p(dhT),
                                     _p(dq), _p(df), _p(dvv), _p(dh0)))
     return dq, df, dvv, dh0
+
+
+# ---------------------------------------------------------------------------------------------
+# Lower-bounded forget gate (paper Section 2, Eq. 2) and the cumulative-softmax lower bounds.
+# Plain numpy in fp64, written from the definitions:
+#     beta = cumsum(softmax(Gamma, over layers), over layers) - (its first row)
+#     f    = beta + (1 - beta) * g,   g = sigmoid(z)
+# Layouts: z, f: [B,H,N,dk]; beta: [H,dk] (one lower bound per channel of the layer, shared by
+# batch and time); Gamma, the bounds of all layers: [L, d].
+# ---------------------------------------------------------------------------------------------
+def cumax(gamma):
+    """Lower bounds of all layers from the learnable matrix Gamma [L, d]: softmax over the layer
+    axis, cumulative sum over the layer axis, minus the first layer's row (so that the first
+    layer has bound zero and the last stays below one)."""
+    gamma = np.asarray(gamma, dtype=np.float64)
+    e = np.exp(gamma - gamma.max(axis=0, keepdims=True))
+    p = e / e.sum(axis=0, keepdims=True)
+    c = np.cumsum(p, axis=0)
+    return c - c[0:1]
+
+
+def gate(z, beta):
+    """f = beta + (1 - beta) * sigmoid(z), Eq. 2.  z: [B,H,N,dk]; beta: [H,dk]."""
+    z = np.asarray(z, dtype=np.float64)
+    b = np.asarray(beta, dtype=np.float64)[None, :, None, :]
+    g = 1.0 / (1.0 + np.exp(-z))
+    return b + (1.0 - b) * g
+
+
+def fwd_gated(q, z, beta, v, h0=None, want_hT=True):
+    """Eq. 3 with the gate of Eq. 2 formed from its pre-activation z."""
+    return fwd(q, gate(z, beta), v, h0, want_hT)
+
+
+def bwd_gated(q, z, beta, v, dO, h0=None, dhT=None, want_dh0=True):
+    """Gradients of L = sum(o * dO) + sum(hT * dhT) w.r.t. q, z, beta, v, h0 (chain rule through
+    Eq. 2: df/dz = (1 - beta) g (1 - g), df/dbeta = 1 - g, summed over batch and time for beta)."""
+    z = np.asarray(z, dtype=np.float64)
+    b = np.asarray(beta, dtype=np.float64)[None, :, None, :]
+    g = 1.0 / (1.0 + np.exp(-z))
+    dq, df, dv, dh0 = bwd(q, b + (1.0 - b) * g, v, dO, h0, dhT, want_dh0)
+    dz = df * (1.0 - b) * g * (1.0 - g)
+    dbeta = (df * (1.0 - g)).sum(axis=(0, 2))
+    return dq, dz, dbeta, dv, dh0

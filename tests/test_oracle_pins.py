@@ -352,3 +352,76 @@ def test_pins_detect_planted_mistakes():
     # untied key k = 1 would violate the convexity pin
     o_bad, h_bad = oracle.fwd_untied(q, np.ones_like(q), f, np.ones_like(v), np.ones_like(h0))
     assert np.max(np.abs(h_bad - 1.0)) > 1e-3
+
+
+# ------------------------------------------------------------------ lower-bounded gate (Eq. 2)
+def test_gate_closed_forms_and_library_sigmoid():
+    """z = 0 gives (1 + beta)/2; z -> +-inf gives 1 and beta; beta = 0 reduces to the logistic
+    function, checked against scipy's."""
+    from scipy.special import expit
+    rng = np.random.default_rng(5)
+    beta = rng.uniform(0.0, 0.95, size=(3, 8))
+    z0 = np.zeros((2, 3, 5, 8))
+    assert np.allclose(oracle.gate(z0, beta), (1.0 + beta)[None, :, None, :] / 2.0, rtol=0, atol=1e-15)
+    assert np.allclose(oracle.gate(z0 + 50.0, beta), 1.0, rtol=0, atol=1e-15)
+    assert np.allclose(oracle.gate(z0 - 50.0, beta), np.broadcast_to(beta[None, :, None, :], z0.shape), rtol=0, atol=1e-15)
+    z = rng.standard_normal((2, 3, 5, 8)) * 3.0
+    assert np.allclose(oracle.gate(z, np.zeros((3, 8))), expit(z), rtol=1e-14, atol=0)
+    f = oracle.gate(z, beta)
+    b = np.broadcast_to(beta[None, :, None, :], z.shape)
+    assert np.all(f > b) and np.all(f < 1.0)                     # the bound is a bound
+    assert np.all(oracle.gate(z + 0.1, beta) > f)                # increasing in z
+    assert np.allclose((f - b) / (1.0 - b), expit(z), rtol=1e-13)  # the residual is the plain gate
+
+
+def test_cumax_properties_and_uniform_case():
+    """Rows increase with the layer, the first is zero, the last is 1 - softmax_0 < 1; a constant
+    Gamma gives l / L (the bounds the layer-shaped workload uses); softmax/cumsum against scipy/numpy."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(6)
+    gamma = rng.standard_normal((24, 16))
+    beta = oracle.cumax(gamma)
+    assert np.all(beta[0] == 0.0)
+    assert np.all(np.diff(beta, axis=0) > 0.0)
+    p = softmax(gamma, axis=0)
+    assert np.allclose(beta[-1], 1.0 - p[0], rtol=1e-13)
+    assert np.allclose(beta, np.cumsum(p, axis=0) - p[0], rtol=1e-13, atol=1e-15)
+    uni = oracle.cumax(np.full((24, 4), 0.37))
+    assert np.allclose(uni, (np.arange(24) / 24.0)[:, None], rtol=1e-13, atol=1e-15)
+    from paper_2404_07904_amd import synth
+    assert abs(uni[12, 0] - synth.layer_lower_bound(12)) < 1e-15
+
+
+def test_bwd_gated_finite_differences():
+    """Central differences of L w.r.t. every entry of z and beta (and a sample of q, v) on a tiny case."""
+    rng = np.random.default_rng(8)
+    B, H, N, dk, dv = 2, 2, 9, 3, 4
+    q, v = rng.standard_normal((B, H, N, dk)), rng.standard_normal((B, H, N, dv))
+    z = rng.standard_normal((B, H, N, dk))
+    beta = rng.uniform(0.0, 0.9, size=(H, dk))
+    h0 = 0.3 * rng.standard_normal((B, H, dk, dv))
+    dO, dhT = rng.standard_normal((B, H, N, dv)), rng.standard_normal((B, H, dk, dv))
+
+    def loss(z_, beta_, q_=q, v_=v):
+        o, hT = oracle.fwd_gated(q_, z_, beta_, v_, h0)
+        return float((o * dO).sum() + (hT * dhT).sum())
+
+    dq, dz, dbeta, dvv, _ = oracle.bwd_gated(q, z, beta, v, dO, h0, dhT)
+    eps = 1e-6
+    num = np.zeros_like(z)
+    for idx in np.ndindex(*z.shape):
+        zp, zm = z.copy(), z.copy()
+        zp[idx] += eps; zm[idx] -= eps
+        num[idx] = (loss(zp, beta) - loss(zm, beta)) / (2 * eps)
+    assert np.max(np.abs(num - dz)) <= 1e-7 * max(1.0, np.max(np.abs(dz)))
+    numb = np.zeros_like(beta)
+    for idx in np.ndindex(*beta.shape):
+        bp, bm = beta.copy(), beta.copy()
+        bp[idx] += eps; bm[idx] -= eps
+        numb[idx] = (loss(z, bp) - loss(z, bm)) / (2 * eps)
+    assert np.max(np.abs(numb - dbeta)) <= 1e-7 * max(1.0, np.max(np.abs(dbeta)))
+    # planted mistake: dropping the (1 - beta) factor of dz must be caught by the same check
+    g = 1.0 / (1.0 + np.exp(-z))
+    wrong = dz / (1.0 - beta[None, :, None, :])
+    assert np.max(np.abs(num - wrong)) > 1e-3 * np.max(np.abs(dz))
+    assert g.shape == z.shape
