@@ -108,6 +108,37 @@ int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, i
                void* hip_stream);
 
 /*
+ * The same passes with the lower-bounded forget gate of the paper's Section 2, Eq. 2, formed
+ * inside the kernels, so that the gate tensor itself is never written to memory:
+ *     f = beta + (1 - beta) * sigmoid(z)
+ *   z         in   device [B][H][N][dk], gate_dtype: pre-activation of the gate (takes the place of f)
+ *   beta      in   device fp32 [H][dk]: lower bound of every channel of this layer, 0 <= beta < 1,
+ *                  shared by batch and time
+ *   grad_z    out  device [B][H][N][dk], io_dtype: gradient w.r.t. z, tied path k = 1 - f included
+ *   grad_beta out  device fp32 [H][dk]: gradient w.r.t. beta, summed over batch and time in a fixed
+ *                  order (bit-reproducible)
+ * Everything else as for hgrn2_fwd / hgrn2_bwd; the backward workspace is sized by
+ * hgrn2_bwd_gated_workspace_bytes(shape), the forward one by hgrn2_fwd_workspace_bytes(shape).
+ */
+size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape);
+int hgrn2_fwd_gated(const hgrn2_shape* shape, const void* q, const void* z, const float* beta,
+                    const void* v, const float* h0, void* o, float* hT, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, const float* beta,
+                    const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                    void* grad_q, void* grad_z, float* grad_beta, void* grad_v, float* grad_h0,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Lower bounds of all L layers from the learnable matrix Gamma (Section 2): softmax over the layer
+ * axis, cumulative sum over the layer axis, minus the first layer's row, so that the bounds rise
+ * monotonically from zero in the first layer and stay below one in the last.
+ *   gamma     in   device fp32 [L][d]        beta  out  device fp32 [L][d]
+ * (row l of beta, viewed as [H][dk], is the `beta` argument of layer l above).  Needs no workspace.
+ */
+int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream);
+
+/*
  * Stage entry points.  hgrn2_fwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_FWD) followed by
  * hgrn2_fwd_readout; hgrn2_bwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_BWD), then
  * hgrn2_state_sweep(HGRN2_SWEEP_STATE_GRAD), then hgrn2_bwd_chunk_grads.  They exist for callers

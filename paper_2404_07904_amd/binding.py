@@ -17,7 +17,7 @@ HGRN2_F32, HGRN2_BF16 = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
+           "hgrn2_step", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
@@ -55,6 +55,14 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_bwd.restype = ctypes.c_int
         L.hgrn2_bwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_bwd_gated_workspace_bytes.restype = sz
+        L.hgrn2_bwd_gated_workspace_bytes.argtypes = [sp]
+        L.hgrn2_fwd_gated.restype = ctypes.c_int
+        L.hgrn2_fwd_gated.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_bwd_gated.restype = ctypes.c_int
+        L.hgrn2_bwd_gated.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_cumax.restype = ctypes.c_int
+        L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.hgrn2_state_sweep.restype = ctypes.c_int
@@ -145,6 +153,56 @@ def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chu
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd")
     return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgrn2_bwd_gated_workspace_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_bwd_gated_workspace_bytes(ctypes.byref(shape)))
+
+
+def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, workspace=None):
+    """hgrn2_fwd with the gate f = beta + (1 - beta) sigmoid(z) formed inside the kernels.
+    z: [B,H,N,dk]; beta: fp32 [H,dk]."""
+    shape = make_shape(q, v, z)
+    assert beta.dtype == torch.float32 and tuple(beta.shape) == (shape.H, shape.dk)
+    if o is None:
+        o = torch.empty_like(v)
+    if hT is None and want_hT:
+        hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    ws = _workspace(hgrn2_fwd_workspace_bytes(shape), q.device, workspace)
+    rc = lib().hgrn2_fwd_gated(ctypes.byref(shape), _ptr(q), _ptr(z), _ptr(beta), _ptr(v), _ptr(h0), _ptr(o),
+                               _ptr(hT), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_fwd_gated")
+    return o, hT
+
+
+def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
+                    grad_q=None, grad_z=None, grad_beta=None, grad_v=None, grad_h0=None):
+    """grad_q, grad_z, grad_beta, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
+    shape = make_shape(q, v, z)
+    grad_q = torch.empty_like(q) if grad_q is None else grad_q
+    grad_z = torch.empty_like(q) if grad_z is None else grad_z
+    grad_v = torch.empty_like(v) if grad_v is None else grad_v
+    grad_beta = torch.empty_like(beta) if grad_beta is None else grad_beta
+    if grad_h0 is None and want_grad_h0:
+        grad_h0 = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    ws = _workspace(hgrn2_bwd_gated_workspace_bytes(shape), q.device, workspace)
+    rc = lib().hgrn2_bwd_gated(ctypes.byref(shape), _ptr(q), _ptr(z), _ptr(beta), _ptr(v), _ptr(h0), _ptr(grad_o),
+                               _ptr(grad_hT), _ptr(grad_q), _ptr(grad_z), _ptr(grad_beta), _ptr(grad_v),
+                               _ptr(grad_h0), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd_gated")
+    return grad_q, grad_z, grad_beta, grad_v, grad_h0
+
+
+def hgrn2_cumax(gamma):
+    """beta [L,d] = cumulative softmax of gamma [L,d] over the layer axis, minus its first row."""
+    assert gamma.dtype == torch.float32 and gamma.dim() == 2
+    beta = torch.empty_like(gamma)
+    rc = lib().hgrn2_cumax(gamma.shape[0], gamma.shape[1], _ptr(gamma), _ptr(beta), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_cumax")
+    return beta
 
 
 def hgrn2_step(q_t, f_t, v_t, state, o_t=None):

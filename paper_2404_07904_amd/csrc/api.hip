@@ -32,6 +32,8 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
     d->dv = s->dv;
     d->io_bf16 = s->io_dtype == HGRN2_BF16;
     d->gate_bf16 = s->gate_dtype == HGRN2_BF16;
+    d->H = s->H > 0 ? s->H : 1;
+    d->beta = nullptr;
     return HGRN2_OK;
 }
 
@@ -55,14 +57,18 @@ size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
     return 2 * round256(state_ws_bytes(d));
 }
 
-int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
-              void* o, float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
+// Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
+static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                    const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape(shape, false, &d);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
     if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
+    if (gated && has_tokens && !beta) return HGRN2_ERR_NULL;
+    d.beta = gated ? beta : nullptr;
     const size_t need = round256(state_ws_bytes(d));
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -75,25 +81,82 @@ int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void
     return HGRN2_OK;
 }
 
-int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
-              const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v,
-              float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+int hgrn2_fwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+              void* o, float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return fwd_impl(shape, q, f, nullptr, false, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
+}
+
+int hgrn2_fwd_gated(const hgrn2_shape* shape, const void* q, const void* z, const float* beta, const void* v,
+                    const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
+{
+    return fwd_impl(shape, q, z, beta, true, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
+}
+
+size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    return 2 * round256(state_ws_bytes(d)) + round256(beta_partials_bytes(d));
+}
+
+// Backward pass; `gated`: `f` holds pre-activations, grad_f receives dL/dz and grad_beta dL/dbeta.
+static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                    const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                    void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                    size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape(shape, true, &d);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
+    if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
+    d.beta = gated ? beta : nullptr;
     const size_t one = round256(state_ws_bytes(d));
-    if (one > 0 && (!workspace || workspace_bytes < 2 * one || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    const size_t part = gated ? round256(beta_partials_bytes(d)) : 0;
+    const size_t need = 2 * one + part;
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (d.BH == 0) return HGRN2_OK;
-    if (!has_tokens && !grad_h0) return HGRN2_OK;
     void* ws_s = workspace;
     void* ws_ds = static_cast<char*>(workspace) + one;
-    if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess) return HGRN2_ERR_HIP;
-    if (has_tokens &&
-        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    float* ws_part = gated ? reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * one) : nullptr;
+    if (d.BH > 0 && (has_tokens || grad_h0)) {
+        if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (has_tokens && launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part,
+                                          stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+    }
+    // an empty batch or sequence has NC = 0 or B = 0: the reduction then writes zeros
+    if (gated && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+              const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v,
+              float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return bwd_impl(shape, q, f, nullptr, false, v, h0, grad_o, grad_hT, grad_q, grad_f, nullptr, grad_v, grad_h0,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, const float* beta, const void* v,
+                    const float* h0, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_z,
+                    float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
+{
+    return bwd_impl(shape, q, z, beta, true, v, h0, grad_o, grad_hT, grad_q, grad_z, grad_beta, grad_v, grad_h0,
+                    workspace, workspace_bytes, hip_stream);
+}
+
+int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream)
+{
+    if (L < 0 || d < 0) return HGRN2_ERR_SHAPE;
+    if ((size_t)L * d == 0) return HGRN2_OK;
+    if (!gamma || !beta) return HGRN2_ERR_NULL;
+    if (launch_cumax(L, d, gamma, beta, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
 
@@ -157,7 +220,7 @@ int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f
     if (!q || !f || !v || !grad_o || !chunk_states || !chunk_state_grads || !grad_q || !grad_f || !grad_v)
         return HGRN2_ERR_NULL;
     if (((uintptr_t)chunk_states & 255) || ((uintptr_t)chunk_state_grads & 255)) return HGRN2_ERR_WORKSPACE;
-    if (launch_bwd_grad(d, q, f, v, grad_o, chunk_states, chunk_state_grads, grad_q, grad_f, grad_v,
+    if (launch_bwd_grad(d, q, f, v, grad_o, chunk_states, chunk_state_grads, grad_q, grad_f, grad_v, nullptr,
                         static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;

@@ -58,6 +58,9 @@ struct BwdGradParams {
     void* df;
     void* dv;
     int BH, N, NC;
+    const float* beta;       // [H][dk] lower bounds, or null: the gate tensor holds f itself
+    float* beta_partials;    // [B*H*NC][8][dk] per-wave partial sums of the gradient w.r.t. beta
+    int H;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][24] clock ticks per phase (diagnostic builds only)
 #endif
@@ -236,6 +239,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     const int row0 = n * C + RW * w;
     f32x2 rf[RW], rq[RW];
     convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
+    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, p.N);
     convert_rows<RW>(rq, raw_q, row0, p.N, k_act, true, 0.0f);
 
     // ---------------- gate products; scaled operand tiles ----------------
@@ -430,6 +434,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
     convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
+    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, p.N);
     // rows of this wave's block to global memory: one address and constant offsets when the
     // whole block lies inside the sequence, row by row otherwise
     auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
@@ -497,6 +502,21 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             gs0[i] = (gs0[i] + add.x) * fast_rcp(rf[i].x + 1e-30f) - dk0[i];
             gs1[i] = (gs1[i] + add.y) * fast_rcp(rf[i].y + 1e-30f) - dk1[i];
         }
+        if (p.beta) {
+            // gate formed from its pre-activation z (paper Eq. 2): with g = sigmoid(z) = (f - beta)/(1 - beta),
+            //   dL/dz = df (1 - beta) g (1 - g) = df (f - beta)(1 - f)/(1 - beta),   dL/dbeta = sum df (1 - g)
+            // (rows past the end of the sequence have f = 1 and drop out of the sum by themselves)
+            const f32x2 b = *reinterpret_cast<const f32x2*>(p.beta + (size_t)(bh % p.H) * DK + 2 * lane);
+            const float inv0 = fast_rcp(1.0f - b.x), inv1 = fast_rcp(1.0f - b.y);
+            float sb0 = 0.0f, sb1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < RW; ++i) {
+                const float u0 = gs0[i] * (1.0f - rf[i].x) * inv0, u1 = gs1[i] * (1.0f - rf[i].y) * inv1;
+                sb0 += u0; sb1 += u1;
+                gs0[i] = u0 * (rf[i].x - b.x); gs1[i] = u1 * (rf[i].y - b.y);
+            }
+            *reinterpret_cast<f32x2*>(p.beta_partials + ((size_t)chunk * NW + w) * DK + 2 * lane) = f32x2{sb0, sb1};
+        }
         store_block(dfg, gs0, gs1);
     }
 #ifdef HGRN2_PHASE_TIMING
@@ -528,7 +548,7 @@ static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream
 
 hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
                            const void* ws_state, const void* ws_dstate, void* grad_q, void* grad_f,
-                           void* grad_v, hipStream_t stream)
+                           void* grad_v, float* beta_partials, hipStream_t stream)
 {
     if ((size_t)d.BH * d.NC == 0) return hipSuccess;
     if (!d.io_bf16) return hipErrorInvalidValue;
@@ -536,6 +556,8 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = ws_dstate;
     p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC;
+    p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H;
+    if (d.beta && !beta_partials) return hipErrorInvalidValue;
 #ifdef HGRN2_PHASE_TIMING
     p.dbg = nullptr;
 #endif
@@ -544,6 +566,63 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     if (d.dk == 128 && d.dv == 64) return launch_one<__bf16, 128, 64>(d, p, stream);
     if (d.dk == 64 && d.dv == 128) return launch_one<__bf16, 64, 128>(d, p, stream);
     return hipErrorInvalidValue;
+}
+
+size_t beta_partials_bytes(const SeqDims& d)
+{
+    return (size_t)d.BH * d.NC * kBwdWaves * d.dk * sizeof(float);
+}
+
+// grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order
+// (one thread per output, so that the result does not depend on scheduling).
+__global__ void reduce_beta_kernel(const float* partials, float* grad_beta, int B, int H, int NC, int dk)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= H * dk) return;
+    const int h = idx / dk, a = idx % dk;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) {
+        const float* pp = partials + ((size_t)(b * H + h) * NC) * kBwdWaves * dk + a;
+        float sb = 0.0f;
+        for (int i = 0; i < NC * kBwdWaves; ++i) sb += pp[(size_t)i * dk];
+        s += sb;
+    }
+    grad_beta[idx] = s;
+}
+
+hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, float* grad_beta, hipStream_t stream)
+{
+    const int n = d.H * d.dk;
+    if (n == 0) return hipSuccess;
+    const int B = d.H > 0 ? d.BH / d.H : 0;
+    hipLaunchKernelGGL(reduce_beta_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, beta_partials, grad_beta, B, d.H,
+                       d.NC, d.dk);
+    return hipGetLastError();
+}
+
+// beta[l][c] = cumsum_l(softmax_l(gamma[:, c])) - its first row; one thread per channel, the
+// layer axis walked serially (L is a few dozen).
+__global__ void cumax_kernel(const float* gamma, float* beta, int L, int d)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= d) return;
+    float m = -3.0e38f;
+    for (int l = 0; l < L; ++l) m = fmaxf(m, gamma[(size_t)l * d + c]);
+    float z = 0.0f;
+    for (int l = 0; l < L; ++l) z += expf(gamma[(size_t)l * d + c] - m);
+    const float inv = 1.0f / z;
+    float run = 0.0f;
+    for (int l = 0; l < L; ++l) {
+        beta[(size_t)l * d + c] = run;          // cumulative sum up to layer l, minus the first layer's share
+        if (l + 1 < L) run += expf(gamma[(size_t)(l + 1) * d + c] - m) * inv;
+    }
+}
+
+hipError_t launch_cumax(int L, int d, const float* gamma, float* beta, hipStream_t stream)
+{
+    if (L <= 0 || d <= 0) return hipSuccess;
+    hipLaunchKernelGGL(cumax_kernel, dim3((d + 127) / 128), dim3(128), 0, stream, gamma, beta, L, d);
+    return hipGetLastError();
 }
 
 }   // namespace hgrn2

@@ -172,6 +172,30 @@ __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>
 
 template <typename T> __host__ __device__ constexpr bool is_bf16_type() { return sizeof(T) == 2; }
 
+// ---- lower-bounded forget gate (paper Section 2, Eq. 2) -------------------------------------------
+// The gate tensor may hold the pre-activation z of the gate instead of the gate itself; the gate
+// is then formed on the fly as f = beta + (1 - beta) * sigmoid(z), with one lower bound beta per
+// channel of the layer ([H][dk], shared by batch and time).  Rows past the end of the sequence
+// must read as f = 1 exactly, so the fill is applied after the transformation.
+__device__ __forceinline__ float lower_bounded_gate(float z, float beta)
+{
+    const float s = fast_rcp(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+    return fmaf(1.0f - beta, s, beta);
+}
+
+template <int RW>
+__device__ __forceinline__ void gate_rows(f32x2 (&rf)[RW], const float* beta_head, int col, bool lane_active,
+                                          int row0, int n_rows)
+{
+    const f32x2 b = *reinterpret_cast<const f32x2*>(beta_head + col);
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+        const bool ok = lane_active && (row0 + i < n_rows);
+        rf[i].x = ok ? lower_bounded_gate(rf[i].x, b.x) : 1.0f;
+        rf[i].y = ok ? lower_bounded_gate(rf[i].y, b.y) : 1.0f;
+    }
+}
+
 // ---- matrix-core policy -------------------------------------------------------------------------
 // One "k-step" contracts 16 values.  A fragment holds the 8 values one lane contributes to it:
 // lane (r = lane % 32, g = lane / 32) supplies row r of A (or column r of B) at k-slots 8g..8g+7.

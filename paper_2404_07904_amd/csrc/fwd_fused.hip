@@ -50,6 +50,8 @@ struct FwdFusedParams {
     void* o;
     float* hT;
     int N, NC, BH;
+    const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
+    int H;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][16] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -209,6 +211,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
         f32x2 rf[RW];
         convert_rows<RW>(rf, rf_raw, c * C + RW * w, p.N, true, GATE_BF16, 1.0f);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, 2 * lane, true, c * C + RW * w, p.N);
         float run0 = 1.0f, run1 = 1.0f;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
@@ -515,7 +518,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     if (d.BH == 0) return hipSuccess;
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
-    p.N = d.N; p.NC = d.NC; p.BH = d.BH;
+    p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H;
     // one workgroup per sequence fills the 256 compute units from 256 sequences on; below that,
     // two workgroups per sequence (each half of the dv columns) keep twice as many units busy
     return d.BH > 192 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);

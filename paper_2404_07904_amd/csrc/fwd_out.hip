@@ -24,6 +24,8 @@ struct FwdOutParams {
     const void* ws;
     void* o;
     int BH, N, NC, gate_bf16;
+    const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
+    int H;
 };
 
 template <typename T, int DK, int DV> struct FwdOutLds {
@@ -84,6 +86,7 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
         load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
         load_rows<RW>(raw_v, vg, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
         convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, p.N);
         convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
         convert_rows<RW>(rv, raw_v, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
     }
@@ -237,6 +240,7 @@ hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const 
     FwdOutParams p;
     p.q = q; p.f = f; p.v = v; p.ws = ws_state; p.o = o;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    p.beta = d.beta; p.H = d.H;
     return d.io_bf16 ? launch_dims<__bf16>(d, p, stream) : launch_dims<float>(d, p, stream);
 }
 

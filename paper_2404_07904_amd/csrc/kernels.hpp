@@ -18,6 +18,10 @@ struct SeqDims {
     int dk, dv;
     bool io_bf16;    // q, v, o, grad_* storage: bf16 (else fp32)
     bool gate_bf16;  // f storage
+    // Gate formed on the fly (paper Eq. 2): when `beta` is set, the gate tensor holds the
+    // pre-activation z and f = beta + (1 - beta) sigmoid(z); beta is [H][dk] fp32 on the device.
+    int H = 1;
+    const float* beta = nullptr;
 };
 
 // What a state sweep accumulates.
@@ -51,9 +55,18 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
                             void* o, float* hT, hipStream_t stream);
 
 // Per-chunk gradients dq, df, dv from the two state sweeps.
+// With d.beta set, grad_f receives the gradient w.r.t. the pre-activation z, and every wave of
+// every chunk leaves its partial sum of the gradient w.r.t. beta in `beta_partials`
+// ([B*H*NC][8][dk] fp32), which reduce_beta_partials() adds up in a fixed order.
 hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
                            const void* ws_state, const void* ws_dstate, void* grad_q, void* grad_f,
-                           void* grad_v, hipStream_t stream);
+                           void* grad_v, float* beta_partials, hipStream_t stream);
+size_t beta_partials_bytes(const SeqDims& d);
+hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, float* grad_beta, hipStream_t stream);
+
+// Lower bounds of all layers from Gamma [L][d] (paper Section 2): cumulative softmax over the
+// layer axis minus its first row.
+hipError_t launch_cumax(int L, int d, const float* gamma, float* beta, hipStream_t stream);
 
 // Decode step.
 hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, const void* q, const void* f,

@@ -24,6 +24,8 @@ struct SweepParams {
     float* fin;
     void* ws;
     int BH, N, NC, n_tile, gate_bf16;
+    const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
+    int H;
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][8] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -104,6 +106,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
         {
             const int row0 = n * C + RW * w;
             convert_rows<RW>(rf, raw_f, row0, p.N, a_act, gate_bf16, 1.0f);
+            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_a, a_act, row0, p.N);
             if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, p.N, a_act, is_bf16_type<T>(), 0.0f);
             convert_rows<RW>(rb, raw_b, row0, p.N, b_act, is_bf16_type<T>(), 0.0f);
         }
@@ -329,6 +332,7 @@ hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const v
     SweepParams p;
     p.q = q; p.f = f; p.bsrc = b_src; p.init = init_state; p.fin = final_state; p.ws = ws;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.n_tile = 1; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    p.beta = d.beta; p.H = d.H;
     if (d.io_bf16) {
         switch (mode) {
         case kSweepStateFwd: return launch_dims<__bf16, kSweepStateFwd>(d, p, stream);
@@ -352,6 +356,7 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
     pg.q = q; pg.f = f; pg.bsrc = grad_o; pg.init = grad_hT; pg.fin = grad_h0; pg.ws = ws_dstate;
     ps.BH = pg.BH = d.BH; ps.N = pg.N = d.N; ps.NC = pg.NC = d.NC; ps.n_tile = pg.n_tile = 1;
     ps.gate_bf16 = pg.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    ps.beta = pg.beta = d.beta; ps.H = pg.H = d.H;
     if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128>(d, ps, pg, stream);
     if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64>(d, ps, pg, stream);
     if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64>(d, ps, pg, stream);

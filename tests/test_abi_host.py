@@ -120,3 +120,33 @@ def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError):
         binding.lib()
+
+
+# ------------------------------------------------------------------ gate formed inside the kernels
+def test_gated_workspace_and_error_codes():
+    lib = binding.lib()
+    s = shape(B=8, H=16, N=2048, dk=128, dv=128)
+    one = 8 * 16 * 32 * 128 * 128 * 2
+    partials = 8 * 16 * 32 * 8 * 128 * 4
+    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == 2 * one + partials
+    assert binding.hgrn2_bwd_gated_workspace_bytes(shape(dk=96)) == 0
+    big = 1 << 40
+    fwd = lambda s_, q=FAKE, z=FAKE, beta=FAKE, v=FAKE, o=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_fwd_gated(
+        ctypes.byref(s_) if s_ is not None else None, q, z, beta, v, None, o, None, ws, n, None)
+    assert fwd(None) == E_NULL
+    assert fwd(shape(), beta=None) == E_NULL
+    assert fwd(shape(), z=None) == E_NULL
+    assert fwd(shape(dk=96)) == E_UNSUP
+    assert fwd(shape(), n=16) == E_WS
+    bwd = lambda s_, beta=FAKE, gz=FAKE, gb=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_bwd_gated(
+        ctypes.byref(s_), FAKE, FAKE, beta, FAKE, None, FAKE, None, FAKE, gz, gb, FAKE, None, ws, n, None)
+    assert bwd(shape(), beta=None) == E_NULL
+    assert bwd(shape(), gb=None) == E_NULL
+    assert bwd(shape(), gz=None) == E_NULL
+    assert bwd(shape(io=0, gate=0)) == E_UNSUP
+    need = binding.hgrn2_bwd_gated_workspace_bytes(shape())
+    assert bwd(shape(), n=need - 1) == E_WS
+    assert bwd(shape(), ws=ctypes.c_void_p(0x100010)) == E_WS
+    assert lib.hgrn2_cumax(-1, 4, FAKE, FAKE, None) == E_SHAPE
+    assert lib.hgrn2_cumax(3, 4, None, FAKE, None) == E_NULL
+    assert lib.hgrn2_cumax(0, 4, None, None, None) == OK
