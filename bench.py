@@ -12,6 +12,8 @@ Also reported on the same JSON line:
                 timings of the individual stages taken in this run
   mfma          algorithmic flops of fwd+bwd against the dense bf16 MFMA peak (2.5 PFLOP/s)
   cpu_baseline  the fp64 CPU oracle on the same inputs, all host cores, same run
+  gated         the same step through hgrn2_fwd_gated / hgrn2_bwd_gated (gate of Eq. 2 formed from
+                its pre-activation inside the kernels)
 """
 from __future__ import annotations
 
@@ -44,6 +46,7 @@ def parse():
     ap.add_argument("--decode-steps", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -203,6 +206,28 @@ def main():
         "calls": call_out,
         "stages": stage_out,
     }
+
+    # ---- the same step with the gate of Eq. 2 formed inside the kernels (z and beta instead of f) ----
+    if not args.no_gated:
+        rng = np.random.default_rng(synth.BASE_SEED + 7)
+        beta = torch.full((H, D), float(synth.layer_lower_bound(args.layer)), dtype=torch.float32, device=dev)
+        zs = [to_dev(synth.bf16_round(rng.standard_normal((B, H, N, D), dtype=np.float32))) for _ in range(2)]
+        wsg = torch.empty(binding.hgrn2_bwd_gated_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+        gb = torch.empty_like(beta)
+
+        def gated_step(i):
+            q, _, v, dO = sets[i % 2]
+            binding.hgrn2_fwd_gated(q, zs[i % 2], beta, v, None, o=o, hT=hT, workspace=wsg)
+            binding.hgrn2_bwd_gated(q, zs[i % 2], beta, v, dO, None, None, workspace=wsg, grad_q=gq, grad_z=gf,
+                                    grad_beta=gb, grad_v=gv)
+
+        for i in range(10):
+            gated_step(i)
+        dtg = timed(gated_step, reps=50)
+        result["gated"] = {"workload": "the same shape with z ~ N(0,1) (bf16) and beta = %.4f in place of f"
+                                       % synth.layer_lower_bound(args.layer),
+                           "ms_per_step": round(dtg * 1e3, 4), "tokens_per_s": round(tokens / dtg, 1)}
+        del zs, wsg
 
     # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----
     if not args.no_decode:

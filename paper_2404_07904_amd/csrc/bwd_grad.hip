@@ -573,30 +573,39 @@ size_t beta_partials_bytes(const SeqDims& d)
     return (size_t)d.BH * d.NC * kBwdWaves * d.dk * sizeof(float);
 }
 
-// grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order
-// (one thread per output, so that the result does not depend on scheduling).
-__global__ void reduce_beta_kernel(const float* partials, float* grad_beta, int B, int H, int NC, int dk)
+// grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order: one
+// workgroup per (head, 64 channels); 16 groups of 64 threads each add every 16th partial row
+// (coalesced across the channels) and the 16 group sums are added in order.
+constexpr int kRedGroups = 16;
+__global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* grad_beta, int B,
+                                                                      int H, int NC, int dk)
 {
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= H * dk) return;
-    const int h = idx / dk, a = idx % dk;
+    __shared__ float part[kRedGroups][64];
+    const int h = blockIdx.x / (dk / 64), a = 64 * (blockIdx.x % (dk / 64)) + (threadIdx.x & 63);
+    const int grp = threadIdx.x >> 6;
+    const int rows = NC * kBwdWaves;          // partial rows of one (batch, head)
     float s = 0.0f;
     for (int b = 0; b < B; ++b) {
-        const float* pp = partials + ((size_t)(b * H + h) * NC) * kBwdWaves * dk + a;
-        float sb = 0.0f;
-        for (int i = 0; i < NC * kBwdWaves; ++i) sb += pp[(size_t)i * dk];
-        s += sb;
+        const float* pp = partials + ((size_t)(b * H + h) * rows) * dk + a;
+#pragma unroll 8
+        for (int i = grp; i < rows; i += kRedGroups) s += pp[(size_t)i * dk];
     }
-    grad_beta[idx] = s;
+    part[grp][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (grp == 0) {
+        float t = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kRedGroups; ++j) t += part[j][threadIdx.x];
+        grad_beta[(size_t)h * dk + a] = t;
+    }
 }
 
 hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, float* grad_beta, hipStream_t stream)
 {
-    const int n = d.H * d.dk;
-    if (n == 0) return hipSuccess;
-    const int B = d.H > 0 ? d.BH / d.H : 0;
-    hipLaunchKernelGGL(reduce_beta_kernel, dim3((n + 63) / 64), dim3(64), 0, stream, beta_partials, grad_beta, B, d.H,
-                       d.NC, d.dk);
+    if (d.H * d.dk == 0) return hipSuccess;
+    const int B = d.BH / d.H;
+    hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64)), dim3(64 * kRedGroups), 0, stream, beta_partials,
+                       grad_beta, B, d.H, d.NC, d.dk);
     return hipGetLastError();
 }
 
