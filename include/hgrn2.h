@@ -53,11 +53,18 @@ typedef enum {
 
 typedef enum { HGRN2_F32 = 0, HGRN2_BF16 = 1 } hgrn2_dtype;
 
+/* Memory order of the sequence tensors.  The d channels of one token of one head are always
+ * contiguous; HGRN2_LAYOUT_BNHD is what a projection of a [B][N][model width] activation writes
+ * (heads side by side inside a token), so no transposition is needed before or after the call.
+ * States (h0, hT, their gradients, the decode state) are [B][H][dk][dv] in either case. */
+typedef enum { HGRN2_LAYOUT_BHND = 0, HGRN2_LAYOUT_BNHD = 1 } hgrn2_layout;
+
 typedef struct {
     int32_t B, H, N, dk, dv;
     int32_t chunk;      /* chunk length of the chunkwise algorithm; 0 selects the default (64) */
     int32_t io_dtype;   /* hgrn2_dtype of q, v, o and of every grad_* sequence tensor */
     int32_t gate_dtype; /* hgrn2_dtype of f (grad_f follows io_dtype) */
+    int32_t layout;     /* hgrn2_layout of every sequence tensor (q, f, v, o, grad_*); 0 = [B][H][N][d] */
 } hgrn2_shape;
 
 /* Bytes of device workspace hgrn2_fwd / hgrn2_bwd need for this shape (0 if the shape is

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhgrn2.so")
 
 HGRN2_F32, HGRN2_BF16 = 0, 1
+HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
@@ -25,7 +26,7 @@ SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 class hgrn2_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("chunk", ctypes.c_int32),
-                ("io_dtype", ctypes.c_int32), ("gate_dtype", ctypes.c_int32)]
+                ("io_dtype", ctypes.c_int32), ("gate_dtype", ctypes.c_int32), ("layout", ctypes.c_int32)]
 
 
 class Hgrn2Error(RuntimeError):
@@ -100,9 +101,14 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_shape(q, v, f, chunk=0) -> hgrn2_shape:
-    B, H, N, dk = q.shape
-    return hgrn2_shape(B, H, N, dk, v.shape[-1], chunk, _dt(q), _dt(f))
+def make_shape(q, v, f, chunk=0, layout=HGRN2_LAYOUT_BHND) -> hgrn2_shape:
+    """Shape descriptor of contiguous tensors q, f [B,H,N,dk], v [B,H,N,dv] (or [B,N,H,d] with
+    layout=HGRN2_LAYOUT_BNHD)."""
+    if layout == HGRN2_LAYOUT_BNHD:
+        B, N, H, dk = q.shape
+    else:
+        B, H, N, dk = q.shape
+    return hgrn2_shape(B, H, N, dk, v.shape[-1], chunk, _dt(q), _dt(f), layout)
 
 
 def hgrn2_fwd_workspace_bytes(shape: hgrn2_shape) -> int:
@@ -119,9 +125,10 @@ def _workspace(nbytes, device, workspace):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
-def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, workspace=None):
+def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, workspace=None,
+              layout=HGRN2_LAYOUT_BHND):
     """o, hT = chunkwise forward of the recurrence.  q, f: [B,H,N,dk]; v: [B,H,N,dv]; h0 fp32."""
-    shape = make_shape(q, v, f, chunk)
+    shape = make_shape(q, v, f, chunk, layout)
     assert v.dtype == q.dtype and f.shape == q.shape
     if o is None:
         o = torch.empty_like(v)
@@ -137,9 +144,9 @@ def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, works
 
 
 def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chunk=0, workspace=None,
-              grad_q=None, grad_f=None, grad_v=None, grad_h0=None):
+              grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND):
     """grad_q, grad_f, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
-    shape = make_shape(q, v, f, chunk)
+    shape = make_shape(q, v, f, chunk, layout)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_f = torch.empty_like(q) if grad_f is None else grad_f
     grad_v = torch.empty_like(v) if grad_v is None else grad_v
@@ -159,10 +166,11 @@ def hgrn2_bwd_gated_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_bwd_gated_workspace_bytes(ctypes.byref(shape)))
 
 
-def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, workspace=None):
+def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, workspace=None,
+                    layout=HGRN2_LAYOUT_BHND):
     """hgrn2_fwd with the gate f = beta + (1 - beta) sigmoid(z) formed inside the kernels.
     z: [B,H,N,dk]; beta: fp32 [H,dk]."""
-    shape = make_shape(q, v, z)
+    shape = make_shape(q, v, z, 0, layout)
     assert beta.dtype == torch.float32 and tuple(beta.shape) == (shape.H, shape.dk)
     if o is None:
         o = torch.empty_like(v)
@@ -177,9 +185,10 @@ def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, wo
 
 
 def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
-                    grad_q=None, grad_z=None, grad_beta=None, grad_v=None, grad_h0=None):
+                    grad_q=None, grad_z=None, grad_beta=None, grad_v=None, grad_h0=None,
+                    layout=HGRN2_LAYOUT_BHND):
     """grad_q, grad_z, grad_beta, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
-    shape = make_shape(q, v, z)
+    shape = make_shape(q, v, z, 0, layout)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_z = torch.empty_like(q) if grad_z is None else grad_z
     grad_v = torch.empty_like(v) if grad_v is None else grad_v

@@ -18,6 +18,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
     if (!s) return HGRN2_ERR_NULL;
     if (s->B < 0 || s->H < 0 || s->N < 0 || s->dk <= 0 || s->dv <= 0 || s->chunk < 0) return HGRN2_ERR_SHAPE;
     if (!dtype_ok(s->io_dtype) || !dtype_ok(s->gate_dtype)) return HGRN2_ERR_SHAPE;
+    if (s->layout != HGRN2_LAYOUT_BHND && s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;
     const long long bh = (long long)s->B * s->H;
     if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
     const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
@@ -34,6 +35,16 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
     d->gate_bf16 = s->gate_dtype == HGRN2_BF16;
     d->H = s->H > 0 ? s->H : 1;
     d->beta = nullptr;
+    const long long H = s->H, N = s->N, dk = s->dk, dv = s->dv;
+    d->lay.H = d->H;
+    if (s->layout == HGRN2_LAYOUT_BNHD) {
+        if (H * dk > INT_MAX / 8 || H * dv > INT_MAX / 8) return HGRN2_ERR_SHAPE;      // token stride is kept in an int
+        d->lay.sb_k = N * H * dk; d->lay.sh_k = dk; d->lay.sn_k = H * dk;
+        d->lay.sb_v = N * H * dv; d->lay.sh_v = dv; d->lay.sn_v = H * dv;
+    } else {
+        d->lay.sb_k = H * N * dk; d->lay.sh_k = N * dk; d->lay.sn_k = dk;
+        d->lay.sb_v = H * N * dv; d->lay.sh_v = N * dv; d->lay.sn_v = dv;
+    }
     return HGRN2_OK;
 }
 

@@ -61,6 +61,8 @@ struct BwdGradParams {
     const float* beta;       // [H][dk] lower bounds, or null: the gate tensor holds f itself
     float* beta_partials;    // [B*H*NC][8][dk] per-wave partial sums of the gradient w.r.t. beta
     int H;
+    TokenLayout lay;         // used when dense == 0
+    int dense;               // sequence tensors are [B][H][N][d]
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][24] clock ticks per phase (diagnostic builds only)
 #endif
@@ -112,8 +114,8 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <typename T, int DK, int DV, bool GATE_BF16>
-__global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
+template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE>
+__device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 {
     constexpr int C = kChunk, NW = kBwdWaves, RW = C / NW;
     typedef BwdGradLds<T, DK, DV> L;
@@ -175,15 +177,16 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, int chunk, int lane) {
         const int col_k = (2 * lane < DK) ? 2 * lane : 0;
         const int cn = chunk % p.NC, cbh = chunk / p.NC;
-        const size_t sk_ = (size_t)cbh * p.N * DK;
+        const size_t sk_ = DENSE ? (size_t)cbh * p.N * DK : p.lay.off_k(cbh);
         const int r0 = cn * C + RW * w;
-        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sk_ * GES, r0, p.N - 1, DK, col_k);
-        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sk_), r0, p.N - 1, DK, col_k);
+        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sk_ * GES, r0, p.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sk_), r0, p.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
     };
     auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], int chunk, int lane) {
         load_fq_rows(cf, cq, chunk, lane);
         const int cn = chunk % p.NC, cbh = chunk / p.NC;
-        const size_t vo = (size_t)cbh * p.N * DV + (size_t)min(cn * C + vd_row, p.N - 1) * DV + 16 * vd_grp;
+        const size_t vo = (DENSE ? (size_t)cbh * p.N * DV : p.lay.off_v(cbh)) +
+                          (size_t)min(cn * C + vd_row, p.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
         cv[0] = *reinterpret_cast<const u32x4*>(vg + vo);
         cv[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
         cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
@@ -217,7 +220,9 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     const int lane = lane_opaque, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK;
     const int n = chunk % p.NC, bh = chunk / p.NC;
-    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
+    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const size_t ld_k = DENSE ? (size_t)DK : (size_t)p.lay.sn_k, ld_v = DENSE ? (size_t)DV : (size_t)p.lay.sn_v;
     load_chunk_states(sS, sD, chunk, lane);      // first needed two barriers from here; covered by the element-wise stage
 
 #ifdef HGRN2_PHASE_TIMING
@@ -438,14 +443,14 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
     // rows of this wave's block to global memory: one address and constant offsets when the
     // whole block lies inside the sequence, row by row otherwise
     auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
-        T* bp = dst + seq_k + (size_t)row0 * DK + 2 * lane;
+        T* bp = dst + seq_k + (size_t)row0 * ld_k + 2 * lane;
         if (row0 + RW <= p.N) {
 #pragma unroll
-            for (int i = 0; i < RW; ++i) store_pair_t<T>(bp, (size_t)i * DK, x0[i], x1[i]);
+            for (int i = 0; i < RW; ++i) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < RW; ++i)
-                if (row0 + i < p.N) store_pair_t<T>(bp, (size_t)i * DK, x0[i], x1[i]);
+                if (row0 + i < p.N) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         }
     };
     if (k_act) {
@@ -480,7 +485,7 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
             if (grow < p.N)
-                *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * DV + cv * 8) =
+                *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * ld_v + cv * 8) =
                     *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * 8);
         }
     }
@@ -531,6 +536,13 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
   }
 }
 
+template <typename T, int DK, int DV, bool GATE_BF16>
+__global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
+{
+    if (p.dense) bwd_grad_body<T, DK, DV, GATE_BF16, true>(p);
+    else         bwd_grad_body<T, DK, DV, GATE_BF16, false>(p);
+}
+
 template <typename T, int DK, int DV>
 static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream_t stream)
 {
@@ -556,7 +568,7 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = ws_dstate;
     p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC;
-    p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H;
+    p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
 #ifdef HGRN2_PHASE_TIMING
     p.dbg = nullptr;

@@ -52,6 +52,8 @@ struct FwdFusedParams {
     int N, NC, BH;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
+    TokenLayout lay;     // used when dense == 0
+    int dense;           // sequence tensors are [B][H][N][d]: token strides are the compile-time dk, dv
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][16] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -82,8 +84,8 @@ template <int NSPLIT> struct FwdFusedLds {
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <bool GATE_BF16, int NSPLIT>
-__global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams p)
+template <bool GATE_BF16, int NSPLIT, bool DENSE>
+__device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
 {
     typedef __bf16 T;
     typedef Mma<T> M;
@@ -127,7 +129,9 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
-    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
+    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     T* og = static_cast<T*>(p.o);
@@ -176,17 +180,17 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     const char* vbase = reinterpret_cast<const char*>(vg + seq_v + dv0);
     const int last_row = p.N - 1;
     auto load_f = [&](RawRows<RW>& d, int c) {
-        load_rows_clamped<RW, GATE_BF16>(d, fbase, c * C + RW * w, last_row, DK, 2 * lane);
+        load_rows_clamped<RW, GATE_BF16>(d, fbase, c * C + RW * w, last_row, ld_k, 2 * lane);
     };
     auto load_q = [&](RawRows<RW>& d, int c) {
-        load_rows_clamped<RW, true>(d, qbase, c * C + RW * w, last_row, DK, 2 * lane);
+        load_rows_clamped<RW, true>(d, qbase, c * C + RW * w, last_row, ld_k, 2 * lane);
     };
     auto load_v = [&](u32x4 (&d)[NVV], int c) {
         const int row0 = c * C + RW * w;
 #pragma unroll
         for (int j = 0; j < NVV; ++j) {
             const int rc = min(row0 + lane / VPR + VRS * j, last_row);
-            d[j] = *reinterpret_cast<const u32x4*>(vbase + (size_t)rc * (DV * 2) + 2 * vcol);
+            d[j] = *reinterpret_cast<const u32x4*>(vbase + (size_t)rc * ((size_t)ld_v * 2) + 2 * vcol);
         }
     };
     // Rows past the end of the sequence need no masking here: their K~ is zero (f = 1 there), so
@@ -282,7 +286,7 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
             const int grow = c * C + row;
             obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
             if ((unsigned)grow < (unsigned)p.N)      // also false for the chunk "-1" of the first pass
-                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * DV + dv0 + cv * 8) = obuf[k];
+                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * ld_v + dv0 + cv * 8) = obuf[k];
         }
     };
 
@@ -494,6 +498,13 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams
     }
 }
 
+template <bool GATE_BF16, int NSPLIT>
+__global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams p)
+{
+    if (p.dense) fwd_fused_body<GATE_BF16, NSPLIT, true>(p);
+    else         fwd_fused_body<GATE_BF16, NSPLIT, false>(p);
+}
+
 bool fwd_fused_supported(const SeqDims& d)
 {
     return d.io_bf16 && d.dk == 128 && d.dv == 128 && d.BH >= 64;
@@ -518,7 +529,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     if (d.BH == 0) return hipSuccess;
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
-    p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H;
+    p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     // one workgroup per sequence fills the 256 compute units from 256 sequences on; below that,
     // two workgroups per sequence (each half of the dv columns) keep twice as many units busy
     return d.BH > 192 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);

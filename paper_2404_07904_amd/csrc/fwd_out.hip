@@ -26,6 +26,8 @@ struct FwdOutParams {
     int BH, N, NC, gate_bf16;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
+    TokenLayout lay;     // used when dense == 0
+    int dense;           // sequence tensors are [B][H][N][d]
 };
 
 template <typename T, int DK, int DV> struct FwdOutLds {
@@ -42,8 +44,8 @@ template <typename T, int DK, int DV> struct FwdOutLds {
     static constexpr size_t total = tot + (size_t)kWaves * DK * sizeof(float);
 };
 
-template <typename T, int DK, int DV>
-__global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
+template <typename T, int DK, int DV, bool DENSE>
+__device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
 {
     constexpr int C = kChunk, RW = C / kWaves;
     typedef FwdOutLds<T, DK, DV> L;
@@ -62,7 +64,9 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
     const int n = blockIdx.x % p.NC, bh = blockIdx.x / p.NC;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK, v_act = 2 * lane < DV;
-    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
+    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
@@ -82,9 +86,9 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
         RawRows<RW> raw_f, raw_q, raw_v;
         const int row0 = n * C + RW * w;
         const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
-        load_rows<RW>(raw_f, p.f, seq_k, DK, col_k, row0, p.N, gate_bf16);
-        load_rows<RW>(raw_q, qg, seq_k, DK, col_k, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_v, vg, seq_v, DV, col_v, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_k, row0, p.N, gate_bf16);
+        load_rows<RW>(raw_q, qg, seq_k, ld_k, col_k, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_v, vg, seq_v, ld_v, col_v, row0, p.N, is_bf16_type<T>());
         convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
         if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, p.N);
         convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
@@ -205,10 +209,17 @@ __global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
             const int grow = n * C + row;
             if (grow < p.N) {
                 const uint4 val = *reinterpret_cast<const uint4*>(Ost + (size_t)row * PO + cv * VEC);
-                *reinterpret_cast<uint4*>(og + seq_v + (size_t)grow * DV + cv * VEC) = val;
+                *reinterpret_cast<uint4*>(og + seq_v + (size_t)grow * ld_v + cv * VEC) = val;
             }
         }
     }
+}
+
+template <typename T, int DK, int DV>
+__global__ __launch_bounds__(kThreads) void fwd_out_kernel(FwdOutParams p)
+{
+    if (p.dense) fwd_out_body<T, DK, DV, true>(p);
+    else         fwd_out_body<T, DK, DV, false>(p);
 }
 
 template <typename T, int DK, int DV>
@@ -240,7 +251,7 @@ hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const 
     FwdOutParams p;
     p.q = q; p.f = f; p.v = v; p.ws = ws_state; p.o = o;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
-    p.beta = d.beta; p.H = d.H;
+    p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     return d.io_bf16 ? launch_dims<__bf16>(d, p, stream) : launch_dims<float>(d, p, stream);
 }
 

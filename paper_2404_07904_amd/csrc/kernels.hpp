@@ -11,6 +11,16 @@ namespace hgrn2 {
 // Compile-time chunk length of the chunkwise kernels.
 constexpr int kChunk = 64;
 
+// Where token (b, h, n) of q / f (channel count dk) and of v / o (dv) starts, in elements:
+// b * sb + h * sh + n * sn.  [B][H][N][d] has sb = H N d, sh = N d, sn = d; [B][N][H][d] (what a
+// projection writes) has sb = N H d, sh = d, sn = H d.  The d channels of a token are contiguous.
+struct TokenLayout {
+    long long sb_k, sh_k, sn_k, sb_v, sh_v, sn_v;
+    int H;
+    __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
+    __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
+};
+
 struct SeqDims {
     int BH;          // B * H independent sequences
     int N;           // tokens per sequence
@@ -22,6 +32,9 @@ struct SeqDims {
     // pre-activation z and f = beta + (1 - beta) sigmoid(z); beta is [H][dk] fp32 on the device.
     int H = 1;
     const float* beta = nullptr;
+    TokenLayout lay;
+    // [B][H][N][d]: the kernels then use compile-time token strides
+    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv; }
 };
 
 // What a state sweep accumulates.

@@ -26,6 +26,8 @@ struct SweepParams {
     int BH, N, NC, n_tile, gate_bf16;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
+    TokenLayout lay;     // used when dense == 0
+    int dense;           // sequence tensors are [B][H][N][d]: token strides are the compile-time dk, dv
 #ifdef HGRN2_PHASE_TIMING
     long long* dbg;      // [workgroup][wave][8] accumulated clock ticks per phase (diagnostic builds only)
 #endif
@@ -37,7 +39,7 @@ struct SweepParams {
 #define HGRN2_STAMP(k) do { } while (0)
 #endif
 
-template <typename T, int DK, int DV, int TV, int MODE>
+template <typename T, int DK, int DV, int TV, int MODE, bool DENSE>
 __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 {
     constexpr int C = kChunk, RW = C / kWaves;
@@ -61,7 +63,9 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
     const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;
-    const size_t seq_k = (size_t)bh * p.N * DK, seq_v = (size_t)bh * p.N * DV;
+    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
+    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qsrc = static_cast<const T*>(p.q);
     const T* bsrc = static_cast<const T*>(p.bsrc);
@@ -72,9 +76,9 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     const int col_a = a_act ? 2 * lane : 0, col_b = col0 + (b_act ? 2 * lane : 0);
     auto load_chunk = [&](int n) {
         const int row0 = n * C + RW * w;
-        load_rows<RW>(raw_f, p.f, seq_k, DK, col_a, row0, p.N, gate_bf16);
-        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, DK, col_a, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_b, bsrc, seq_v, DV, col_b, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_a, row0, p.N, gate_bf16);
+        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, ld_k, col_a, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_b, bsrc, seq_v, ld_v, col_b, row0, p.N, is_bf16_type<T>());
     };
 
     // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
@@ -242,7 +246,8 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 template <typename T, int DK, int DV, int TV, int MODE>
 __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
 {
-    sweep_body<T, DK, DV, TV, MODE>(p, blockIdx.x);
+    if (p.dense) sweep_body<T, DK, DV, TV, MODE, true>(p, blockIdx.x);
+    else         sweep_body<T, DK, DV, TV, MODE, false>(p, blockIdx.x);
 }
 
 // The two sweeps of the backward pass (forward states, reverse state gradients) are independent;
@@ -251,8 +256,13 @@ __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
 template <typename T, int DK, int DV, int TV>
 __global__ __launch_bounds__(kThreads) void sweep_pair_kernel(SweepParams ps, SweepParams pg, int half)
 {
-    if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd>(ps, blockIdx.x);
-    else                        sweep_body<T, DK, DV, TV, kSweepGrad>(pg, blockIdx.x - half);
+    if (ps.dense) {
+        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, true>(ps, blockIdx.x);
+        else                        sweep_body<T, DK, DV, TV, kSweepGrad, true>(pg, blockIdx.x - half);
+    } else {
+        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, false>(ps, blockIdx.x);
+        else                        sweep_body<T, DK, DV, TV, kSweepGrad, false>(pg, blockIdx.x - half);
+    }
 }
 
 template <typename T, int DK, int DV, int TV>
@@ -332,7 +342,7 @@ hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const v
     SweepParams p;
     p.q = q; p.f = f; p.bsrc = b_src; p.init = init_state; p.fin = final_state; p.ws = ws;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.n_tile = 1; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
-    p.beta = d.beta; p.H = d.H;
+    p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     if (d.io_bf16) {
         switch (mode) {
         case kSweepStateFwd: return launch_dims<__bf16, kSweepStateFwd>(d, p, stream);
@@ -356,7 +366,7 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
     pg.q = q; pg.f = f; pg.bsrc = grad_o; pg.init = grad_hT; pg.fin = grad_h0; pg.ws = ws_dstate;
     ps.BH = pg.BH = d.BH; ps.N = pg.N = d.N; ps.NC = pg.NC = d.NC; ps.n_tile = pg.n_tile = 1;
     ps.gate_bf16 = pg.gate_bf16 = d.gate_bf16 ? 1 : 0;
-    ps.beta = pg.beta = d.beta; ps.H = pg.H = d.H;
+    ps.beta = pg.beta = d.beta; ps.H = pg.H = d.H; ps.lay = pg.lay = d.lay; ps.dense = pg.dense = d.dense() ? 1 : 0;
     if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128>(d, ps, pg, stream);
     if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64>(d, ps, pg, stream);
     if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64>(d, ps, pg, stream);

@@ -37,8 +37,8 @@ def test_status_strings():
     assert "unknown" in binding.status_string(99)
 
 
-def shape(B=2, H=3, N=100, dk=64, dv=64, chunk=0, io=1, gate=1):
-    return hgrn2_shape(B, H, N, dk, dv, chunk, io, gate)
+def shape(B=2, H=3, N=100, dk=64, dv=64, chunk=0, io=1, gate=1, layout=0):
+    return hgrn2_shape(B, H, N, dk, dv, chunk, io, gate, layout)
 
 
 def test_workspace_sizes():
@@ -150,3 +150,10 @@ def test_gated_workspace_and_error_codes():
     assert lib.hgrn2_cumax(-1, 4, FAKE, FAKE, None) == E_SHAPE
     assert lib.hgrn2_cumax(3, 4, None, FAKE, None) == E_NULL
     assert lib.hgrn2_cumax(0, 4, None, None, None) == OK
+
+
+def test_layout_field():
+    assert call_fwd(shape(layout=1), ws_bytes=16) == E_WS          # a valid layout gets as far as the workspace check
+    assert call_fwd(shape(layout=2)) == E_SHAPE
+    assert call_fwd(shape(layout=-1)) == E_SHAPE
+    assert binding.hgrn2_fwd_workspace_bytes(shape(layout=1)) == binding.hgrn2_fwd_workspace_bytes(shape())
