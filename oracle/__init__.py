@@ -174,3 +174,39 @@ def bwd_gated(q, z, beta, v, dO, h0=None, dhT=None, want_dh0=True):
     dz = df * (1.0 - b) * g * (1.0 - g)
     dbeta = (df * (1.0 - g)).sum(axis=(0, 2))
     return dq, dz, dbeta, dv, dh0
+
+
+# ---------------------------------------------------------------------------------------------
+# HGRN1: the element-wise gated linear recurrence the paper starts from (Section 2, Eq. 1 with
+# the gate of Eq. 2 already formed):   h_t = f_t * h_{t-1} + (1 - f_t) * i_t,   y_t = h_t * o_t
+# per channel.  Plain numpy in fp64, one token at a time.  f, i, o: [B,N,d]; h0: [B,d] or None.
+# ---------------------------------------------------------------------------------------------
+def hgrn1_fwd(f, i, o, h0=None):
+    f, i, o = (np.asarray(x, dtype=np.float64) for x in (f, i, o))
+    B, N, d = f.shape
+    h = np.zeros((B, d)) if h0 is None else np.array(h0, dtype=np.float64)
+    y = np.empty((B, N, d))
+    for t in range(N):
+        h = f[:, t] * h + (1.0 - f[:, t]) * i[:, t]
+        y[:, t] = h * o[:, t]
+    return y, h
+
+
+def hgrn1_bwd(f, i, o, dy, h0=None, dhN=None):
+    """Reverse mode of the loop above for L = sum(y * dy) + sum(h_N * dhN).
+    Returns (df, di, do, dh0); df includes the tied input gate 1 - f."""
+    f, i, o, dy = (np.asarray(x, dtype=np.float64) for x in (f, i, o, dy))
+    B, N, d = f.shape
+    hs = np.empty((B, N + 1, d))
+    hs[:, 0] = 0.0 if h0 is None else np.asarray(h0, dtype=np.float64)
+    for t in range(N):
+        hs[:, t + 1] = f[:, t] * hs[:, t] + (1.0 - f[:, t]) * i[:, t]
+    dh = np.zeros((B, d)) if dhN is None else np.array(dhN, dtype=np.float64)
+    df, di, do = np.empty_like(f), np.empty_like(f), np.empty_like(f)
+    for t in range(N - 1, -1, -1):
+        dh = dh + dy[:, t] * o[:, t]                 # dL/dh_t
+        do[:, t] = dy[:, t] * hs[:, t + 1]
+        df[:, t] = dh * (hs[:, t] - i[:, t])
+        di[:, t] = dh * (1.0 - f[:, t])
+        dh = dh * f[:, t]                            # dL/dh_{t-1} through the recurrence
+    return df, di, do, dh

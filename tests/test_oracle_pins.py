@@ -425,3 +425,64 @@ def test_bwd_gated_finite_differences():
     wrong = dz / (1.0 - beta[None, :, None, :])
     assert np.max(np.abs(num - wrong)) > 1e-3 * np.max(np.abs(dz))
     assert g.shape == z.shape
+
+
+# ------------------------------------------------------------------ HGRN1 element-wise recurrence (Eq. 1)
+def test_hgrn1_brute_force_closed_forms_and_hgrn2_with_unit_state():
+    """h_t = sum_j (prod_{j<s<=t} f_s)(1 - f_j) i_j + (prod_{s<=t} f_s) h0 written out; constant gate
+    gives the geometric closed form; f = 0 copies the input, f = 1 freezes h0; and a 1 x 1 state of
+    the HGRN2 recurrence (q = output gate, v = input) is the same thing, computed by the C oracle."""
+    rng = np.random.default_rng(21)
+    B, N, d = 2, 17, 5
+    f = rng.uniform(0.05, 0.98, (B, N, d)); i = rng.standard_normal((B, N, d)); o = rng.uniform(0, 1, (B, N, d))
+    h0 = rng.standard_normal((B, d))
+    y, hN = oracle.hgrn1_fwd(f, i, o, h0)
+    ref = np.empty_like(y)
+    for t in range(N):
+        acc = np.prod(f[:, :t + 1], axis=1) * h0
+        for j in range(t + 1):
+            acc = acc + np.prod(f[:, j + 1:t + 1], axis=1) * (1.0 - f[:, j]) * i[:, j]
+        ref[:, t] = acc * o[:, t]
+    assert np.max(np.abs(y - ref)) <= 1e-13
+    c = 0.7
+    yc, hc = oracle.hgrn1_fwd(np.full((1, 9, 3), c), np.ones((1, 9, 3)), np.ones((1, 9, 3)))
+    assert np.allclose(yc[0, :, 0], 1.0 - c ** np.arange(1, 10), rtol=1e-13)
+    y0, _ = oracle.hgrn1_fwd(np.zeros_like(f), i, o, h0)
+    assert np.array_equal(y0, i * o)
+    y1, h1 = oracle.hgrn1_fwd(np.ones_like(f), i, o, h0)
+    assert np.array_equal(y1, h0[:, None, :] * o) and np.array_equal(h1, h0)
+    # HGRN2 with dk = dv = 1: one "head" per channel
+    q2 = o.transpose(0, 2, 1)[..., None]; f2 = f.transpose(0, 2, 1)[..., None]; v2 = i.transpose(0, 2, 1)[..., None]
+    o2, hT2 = oracle.fwd(q2, f2, v2, h0[..., None, None])
+    assert np.max(np.abs(o2[..., 0].transpose(0, 2, 1) - y)) <= 1e-13
+    assert np.max(np.abs(hT2[..., 0, 0] - hN)) <= 1e-13
+
+
+def test_hgrn1_bwd_finite_differences_and_hgrn2_unit_state():
+    rng = np.random.default_rng(22)
+    B, N, d = 2, 11, 3
+    f = rng.uniform(0.1, 0.95, (B, N, d)); i = rng.standard_normal((B, N, d)); o = rng.uniform(0, 1, (B, N, d))
+    h0 = rng.standard_normal((B, d)); dy = rng.standard_normal((B, N, d)); dhN = rng.standard_normal((B, d))
+
+    def loss(f_, i_, o_, h0_):
+        y, hN = oracle.hgrn1_fwd(f_, i_, o_, h0_)
+        return float((y * dy).sum() + (hN * dhN).sum())
+
+    df, di, do, dh0 = oracle.hgrn1_bwd(f, i, o, dy, h0, dhN)
+    eps = 1e-6
+    for name, x, g in (("f", f, df), ("i", i, di), ("o", o, do), ("h0", h0, dh0)):
+        num = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps; xm[idx] -= eps
+            args = {"f": f, "i": i, "o": o, "h0": h0}
+            ap, am = dict(args), dict(args)
+            ap[name], am[name] = xp, xm
+            num[idx] = (loss(ap["f"], ap["i"], ap["o"], ap["h0"]) - loss(am["f"], am["i"], am["o"], am["h0"])) / (2 * eps)
+        assert np.max(np.abs(num - g)) <= 1e-7 * max(1.0, np.max(np.abs(g))), name
+    # the same gradients from the HGRN2 oracle with a 1 x 1 state per channel
+    tr = lambda x: x.transpose(0, 2, 1)[..., None]
+    dq2, df2, dv2, dh02 = oracle.bwd(tr(o), tr(f), tr(i), tr(dy), h0[..., None, None], dhN[..., None, None])
+    back = lambda x: x[..., 0].transpose(0, 2, 1)
+    assert np.max(np.abs(back(df2) - df)) <= 1e-12 and np.max(np.abs(back(dv2) - di)) <= 1e-12
+    assert np.max(np.abs(back(dq2) - do)) <= 1e-12 and np.max(np.abs(dh02[..., 0, 0] - dh0)) <= 1e-12
