@@ -12,6 +12,7 @@ Also reported on the same JSON line:
                 timings of the individual stages taken in this run
   mfma          algorithmic flops of fwd+bwd against the dense bf16 MFMA peak (2.5 PFLOP/s)
   cpu_baseline  the fp64 CPU oracle on the same inputs, all host cores, same run
+  hgrn1         the element-wise recurrence of Eq. 1 at the same layer width (hgrn1_fwd, hgrn1_bwd)
   gated         the same step through hgrn2_fwd_gated / hgrn2_bwd_gated (gate of Eq. 2 formed from
                 its pre-activation inside the kernels)
 """
@@ -46,6 +47,7 @@ def parse():
     ap.add_argument("--decode-steps", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-hgrn1", action="store_true", help="skip the element-wise HGRN1 workload")
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
@@ -228,6 +230,42 @@ def main():
                                        % synth.layer_lower_bound(args.layer),
                            "ms_per_step": round(dtg * 1e3, 4), "tokens_per_s": round(tokens / dtg, 1)}
         del zs, wsg
+
+    # ---- second workload: the element-wise HGRN1 recurrence at the same layer (width 2048) ----
+    if not args.no_hgrn1:
+        d1 = H * D
+        rng = np.random.default_rng(synth.BASE_SEED + 8)
+        mk = lambda: to_dev(synth.bf16_round(rng.standard_normal((B, N, d1), dtype=np.float32)))
+        lb1 = float(synth.layer_lower_bound(args.layer))
+        sets1 = []
+        for _ in range(2):
+            g = 1.0 / (1.0 + np.exp(-rng.standard_normal((B, N, d1), dtype=np.float32)))
+            sets1.append((to_dev(synth.bf16_round((lb1 + (1.0 - lb1) * g).astype(np.float32))), mk(),
+                          to_dev(synth.bf16_round(g.astype(np.float32))), mk()))      # f, i, o, dy
+        ws1 = torch.empty(binding.hgrn1_workspace_bytes(B, N, d1), dtype=torch.uint8, device=dev)
+        y1 = torch.empty_like(sets1[0][1])
+
+        def h1_fwd(i):
+            f1, i1, o1, _ = sets1[i % 2]
+            binding.hgrn1_fwd(f1, i1, o1, None, y=y1, want_hN=False, workspace=ws1)
+
+        def h1_bwd(i):
+            f1, i1, o1, dy1 = sets1[i % 2]
+            binding.hgrn1_bwd(f1, i1, o1, dy1, None, None, workspace=ws1)
+
+        for i in range(6):
+            h1_fwd(i); h1_bwd(i)
+        tf, tb = timed(h1_fwd, reps=50), timed(h1_bwd, reps=50)
+        e1 = B * N * d1 * el
+        result["hgrn1"] = {
+            "workload": "element-wise recurrence (Eq. 1), B=%d N=%d d=%d bf16, same gate statistics" % (B, N, d1),
+            "fwd_us": round(tf * 1e6, 1), "bwd_us": round(tb * 1e6, 1),
+            "tokens_per_s_fwd_bwd": round(tokens / (tf + tb), 1),
+            "roofline_fwd": {"bound": "hbm", "achieved": round(4 * e1 / tf / 1e9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
+            "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tb / 1e9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}}
+        del sets1, ws1, y1
 
     # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----
     if not args.no_decode:

@@ -146,6 +146,29 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream);
 
 /*
+ * HGRN1, the element-wise gated linear recurrence the paper starts from (Section 2, Eq. 1, with the
+ * forget gate f of Eq. 2 given), per channel:
+ *     h_t = f_t * h_{t-1} + (1 - f_t) * i_t,      y_t = h_t * o_t
+ * and its reverse mode for L = sum(y * grad_y) + sum(h_N * grad_hN).  A second, bandwidth-bound
+ * workload beside the state-expanded recurrence above (which reduces to it for a 1 x 1 state).
+ *   f, i, o, y, grad_*   device [B][N][d], io_dtype (bf16 only; f may be fp32 via gate_dtype);
+ *                        d a multiple of 128
+ *   h0, grad_hN     in   device fp32 [B][d], or NULL for zero
+ *   hN, grad_h0     out  device fp32 [B][d], or NULL if not wanted
+ *   grad_f          out  includes the tied input gate 1 - f
+ *   workspace            device scratch of hgrn1_workspace_bytes(B, N, d) bytes, 256-byte aligned
+ * Status codes as above; hgrn2_status_string() describes them.
+ */
+size_t hgrn1_workspace_bytes(int32_t B, int32_t N, int32_t d);
+int hgrn1_fwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+              const void* i, const void* o, const float* h0, void* y, float* hN, void* workspace,
+              size_t workspace_bytes, void* hip_stream);
+int hgrn1_bwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+              const void* i, const void* o, const float* h0, const void* grad_y, const float* grad_hN,
+              void* grad_f, void* grad_i, void* grad_o, float* grad_h0, void* workspace,
+              size_t workspace_bytes, void* hip_stream);
+
+/*
  * Stage entry points.  hgrn2_fwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_FWD) followed by
  * hgrn2_fwd_readout; hgrn2_bwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_BWD), then
  * hgrn2_state_sweep(HGRN2_SWEEP_STATE_GRAD), then hgrn2_bwd_chunk_grads.  They exist for callers

@@ -18,7 +18,7 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
+           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
@@ -64,6 +64,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_bwd_gated.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_cumax.restype = ctypes.c_int
         L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
+        L.hgrn1_workspace_bytes.restype = sz
+        L.hgrn1_workspace_bytes.argtypes = [i32, i32, i32]
+        L.hgrn1_fwd.restype = ctypes.c_int
+        L.hgrn1_fwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn1_bwd.restype = ctypes.c_int
+        L.hgrn1_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.hgrn2_state_sweep.restype = ctypes.c_int
@@ -212,6 +218,38 @@ def hgrn2_cumax(gamma):
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_cumax")
     return beta
+
+
+def hgrn1_workspace_bytes(B, N, d) -> int:
+    return int(lib().hgrn1_workspace_bytes(B, N, d))
+
+
+def hgrn1_fwd(f, i, o, h0=None, *, want_hN=True, y=None, hN=None, workspace=None):
+    """y, hN of the element-wise recurrence h_t = f_t h_{t-1} + (1 - f_t) i_t, y_t = h_t o_t.
+    f, i, o: [B,N,d] (i, o bf16; f bf16 or fp32); h0: fp32 [B,d] or None."""
+    B, N, d = i.shape
+    y = torch.empty_like(i) if y is None else y
+    if hN is None and want_hN:
+        hN = torch.empty((B, d), dtype=torch.float32, device=i.device)
+    ws = _workspace(hgrn1_workspace_bytes(B, N, d), i.device, workspace)
+    rc = lib().hgrn1_fwd(B, N, d, _dt(i), _dt(f), _ptr(f), _ptr(i), _ptr(o), _ptr(h0), _ptr(y), _ptr(hN), _ptr(ws),
+                         ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn1_fwd")
+    return y, hN
+
+
+def hgrn1_bwd(f, i, o, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None):
+    """grad_f, grad_i, grad_o, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN)."""
+    B, N, d = i.shape
+    gf, gi, go = torch.empty_like(i), torch.empty_like(i), torch.empty_like(i)
+    gh0 = torch.empty((B, d), dtype=torch.float32, device=i.device) if want_grad_h0 else None
+    ws = _workspace(hgrn1_workspace_bytes(B, N, d), i.device, workspace)
+    rc = lib().hgrn1_bwd(B, N, d, _dt(i), _dt(f), _ptr(f), _ptr(i), _ptr(o), _ptr(h0), _ptr(grad_y), _ptr(grad_hN),
+                         _ptr(gf), _ptr(gi), _ptr(go), _ptr(gh0), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn1_bwd")
+    return gf, gi, go, gh0
 
 
 def hgrn2_step(q_t, f_t, v_t, state, o_t=None):

@@ -237,6 +237,54 @@ int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f
     return HGRN2_OK;
 }
 
+static int h1_check(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype)
+{
+    if (B < 0 || N < 0 || d < 0) return HGRN2_ERR_SHAPE;
+    if (!dtype_ok(io_dtype) || !dtype_ok(gate_dtype)) return HGRN2_ERR_SHAPE;
+    if ((long long)B * ((N + 31) / 32 + 1) * (d / 128 + 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;
+    if (d % 128 != 0 || io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
+    return HGRN2_OK;
+}
+
+size_t hgrn1_workspace_bytes(int32_t B, int32_t N, int32_t d)
+{
+    if (h1_check(B, N, d, HGRN2_BF16, HGRN2_BF16) != HGRN2_OK) return 0;
+    return round256(hgrn1_ws_bytes(B, N, d));
+}
+
+int hgrn1_fwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+              const void* i, const void* o, const float* h0, void* y, float* hN, void* workspace,
+              size_t workspace_bytes, void* hip_stream)
+{
+    const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)B * N * d > 0;
+    if (has_tokens && (!f || !i || !o || !y)) return HGRN2_ERR_NULL;
+    const size_t need = round256(hgrn1_ws_bytes(B, N, d));
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    if (launch_hgrn1_fwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, h0, y, hN, workspace,
+                         static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn1_bwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+              const void* i, const void* o, const float* h0, const void* grad_y, const float* grad_hN,
+              void* grad_f, void* grad_i, void* grad_o, float* grad_h0, void* workspace, size_t workspace_bytes,
+              void* hip_stream)
+{
+    const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)B * N * d > 0;
+    if (has_tokens && (!f || !i || !o || !grad_y || !grad_f || !grad_i || !grad_o)) return HGRN2_ERR_NULL;
+    const size_t need = round256(hgrn1_ws_bytes(B, N, d));
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    if (launch_hgrn1_bwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, h0, grad_y, grad_hN, grad_f, grad_i, grad_o,
+                         grad_h0, workspace, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
 const char* hgrn2_status_string(int status)
 {
     switch (status) {

@@ -18,7 +18,7 @@ FAKE_WS = ctypes.c_void_p(0x100000)      # 256-byte aligned
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "hgrn2.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hgrn2_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(hgrn[12]_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -157,3 +157,23 @@ def test_layout_field():
     assert call_fwd(shape(layout=2)) == E_SHAPE
     assert call_fwd(shape(layout=-1)) == E_SHAPE
     assert binding.hgrn2_fwd_workspace_bytes(shape(layout=1)) == binding.hgrn2_fwd_workspace_bytes(shape())
+
+
+def test_hgrn1_workspace_and_error_codes():
+    lib = binding.lib()
+    assert binding.hgrn1_workspace_bytes(8, 2048, 2048) == 3 * 8 * 64 * 2048 * 4
+    assert binding.hgrn1_workspace_bytes(8, 2048, 100) == 0
+    big = 1 << 40
+    fwd = lambda B=2, N=100, d=256, io=1, gate=1, f=FAKE, y=FAKE, ws=FAKE_WS, n=big: lib.hgrn1_fwd(
+        B, N, d, io, gate, f, FAKE, FAKE, None, y, None, ws, n, None)
+    assert fwd(B=-1) == E_SHAPE
+    assert fwd(d=100) == E_UNSUP
+    assert fwd(io=0) == E_UNSUP
+    assert fwd(f=None) == E_NULL
+    assert fwd(y=None) == E_NULL
+    assert fwd(n=16) == E_WS
+    bwd = lambda d=256, gf=FAKE, n=big: lib.hgrn1_bwd(2, 100, d, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None, gf, FAKE,
+                                                      FAKE, None, FAKE_WS, n, None)
+    assert bwd(d=64) == E_UNSUP
+    assert bwd(gf=None) == E_NULL
+    assert bwd(n=16) == E_WS
