@@ -4,30 +4,38 @@
 //     h_t = f_t * h_{t-1} + (1 - f_t) * i_t,      y_t = h_t * o_t        per channel,
 //
 // and its reverse mode.  Five flops per 8 bytes: the kernels are bound by HBM bandwidth, so they
-// are organised around coalesced streaming and enough independent work to keep the memory system
-// busy.  The recurrence is affine in h, so a segment of T consecutive tokens acts on its incoming
-// state as h_out = A h_in + H with A = prod f and H the segment's result from a zero state:
+// are organised to read every input once (the backward: the gates and inputs twice) with long
+// coalesced streams in flight.  The recurrence is affine in h, so a segment of T consecutive
+// tokens acts on its incoming state as h_out = A h_in + H with A = prod f and H the segment's
+// result from a zero state.
 //
-//   pass 1 (summaries)  every wave takes one (batch, segment, 128 channels), walks its T tokens
-//                       (one coalesced 256-byte row of each tensor per token, a channel pair per
-//                       lane) and stores A and H (backward: also the reverse counterpart Q);
-//   pass 2 (apply)      every wave composes the summaries of the segments before its own (after
-//                       it, for the reverse direction) into its incoming state -- a few dozen
-//                       fused multiply-adds on L2-resident data -- and walks its tokens again,
-//                       now producing the outputs.
-//
-// Nothing waits on another workgroup, B * N/T * d/128 waves are independent, and the gates and
-// inputs are read twice (the second time mostly from the 256 MB last-level cache).
+// A workgroup of eight waves owns 64 channels of one sequence and walks it in blocks of 16 x 32
+// tokens.  Every half-wave takes one 32-token segment of the block (a channel pair per lane, so a
+// load instruction of a wave fetches one 128-byte row piece for each of its two segments); with
+// 64 channels per workgroup a [8][2048][2048] problem already gives one workgroup to each of the
+// 256 compute units.  Per block:
+//   1. the half-wave walks its segment from a zero state out of registers that were filled one
+//      block ahead, and publishes (A, H) in LDS;
+//   2. after one barrier every lane chains the sixteen summaries (32 fused multiply-adds) into
+//      the state entering its own segment and the state leaving the block;
+//   3. it walks the same registers again from the true state, writes its outputs, and refills
+//      every register row with the next block's token as soon as the row is consumed.
+// The backward first runs steps 1-2 over the whole sequence to record the state entering every
+// segment (a few MB), then walks the blocks from the last to the first with the same scheme for
+// the reverse recurrence  r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t.
 // Tensors are [B][N][d] (token-major, d a multiple of 128), states [B][d] fp32.
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace hgrn2 {
 
-constexpr int kH1Threads = 256;          // four independent waves per workgroup
-constexpr int kH1Chan = 128;             // channels per wave: a pair per lane
-constexpr int kH1SegFwd = 64;            // tokens per segment, forward
-constexpr int kH1SegBwd = 32;            // backward: the wave keeps h_{t-1} of its segment in registers
+
+constexpr int kH1Waves = 8;                       // waves per workgroup
+constexpr int kH1Threads = 64 * kH1Waves;
+constexpr int kH1Chan = 64;                       // channels per workgroup: a pair per lane of a half-wave
+constexpr int kH1Segs = 2 * kH1Waves;             // segments per block: one per half-wave
+constexpr int kH1Seg = 32;                        // tokens per segment
+constexpr int kH1Block = kH1Segs * kH1Seg;        // tokens per block
 
 struct H1Params {
     const void* f;
@@ -36,162 +44,304 @@ struct H1Params {
     const void* dy;
     const float* h0;
     const float* dhN;
-    void* y;          // forward: y; backward: unused
+    void* y;
     void* df;
     void* di;
     void* dout;
     float* hN;
     float* dh0;
-    float* sumA;      // [B][NS][d]
-    float* sumH;      // [B][NS][d]
-    float* sumQ;      // [B][NS][d]  (backward)
-    int B, N, d, NS, NCB;
+    float* carry;     // [B][NBLK * kH1Segs][d]: state entering every segment (backward)
+    int B, N, d, NBLK, NCB;
 };
 
+// A channel pair as it sits in memory: packed bf16 (one register) or two floats.
+template <bool BF16> struct H1Raw {
+    typedef uint32_t type;
+    static __device__ __forceinline__ type one() { return 0x3f803f80u; }
+};
+template <> struct H1Raw<false> {
+    typedef f32x2 type;
+    static __device__ __forceinline__ type one() { return f32x2{1.0f, 1.0f}; }
+};
+
+// Token rows are addressed through buffer descriptors: one per tensor, covering the tokens from
+// the start of a block to the end of the sequence.  The whole address of an access is the scalar
+// descriptor plus a 32-bit per-lane byte offset, a read past the last token returns 0 and a write
+// past it is dropped, so the ragged last block needs no clamped addresses and no branches.
+typedef __amdgpu_buffer_rsrc_t H1Rsrc;
+
+__device__ __forceinline__ H1Rsrc h1_rows_from(const void* tensor, size_t seq_elem, int tok0, int N, int d, int esize)
+{
+    const int first = min(max(tok0, 0), N);
+    const unsigned long long bytes = (unsigned long long)(N - first) * d * esize;
+    const char* base = static_cast<const char*>(tensor) + (seq_elem + (size_t)first * d) * esize;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)(unsigned)min(bytes, 0xfffffff8ull), 0x00020000);
+}
+
 template <bool BF16>
-__device__ __forceinline__ f32x2 h1_load(const void* base, size_t elem)
+__device__ __forceinline__ typename H1Raw<BF16>::type h1_ld(H1Rsrc r, unsigned byte_off)
 {
-    return load_pair(base, elem, BF16);
-}
-
-// wave -> (batch, segment, channel block); waves next to each other share token rows
-__device__ __forceinline__ bool h1_map(const H1Params& p, int& b, int& seg, int& c0)
-{
-    const long long gw = (long long)blockIdx.x * (kH1Threads / 64) + (threadIdx.x >> 6);
-    if (gw >= (long long)p.B * p.NS * p.NCB) return false;
-    const int cb = (int)(gw % p.NCB);
-    seg = (int)((gw / p.NCB) % p.NS);
-    b = (int)(gw / ((long long)p.NCB * p.NS));
-    c0 = cb * kH1Chan + 2 * (threadIdx.x & 63);
-    return true;
-}
-
-// ---- pass 1: segment summaries --------------------------------------------------------------------
-template <bool GATE_BF16, int TS, bool BACKWARD>
-__global__ __launch_bounds__(kH1Threads) void hgrn1_summaries_kernel(H1Params p)
-{
-    int b, seg, c0;
-    if (!h1_map(p, b, seg, c0)) return;
-    const int t0 = seg * TS, nt = min(TS, p.N - t0);
-    const size_t base = ((size_t)b * p.N + t0) * p.d + c0;
-    float a0 = 1.0f, a1 = 1.0f, h0 = 0.0f, h1 = 0.0f;
-#pragma unroll 8
-    for (int t = 0; t < nt; ++t) {
-        const f32x2 f = h1_load<GATE_BF16>(p.f, base + (size_t)t * p.d);
-        const f32x2 x = h1_load<true>(p.i, base + (size_t)t * p.d);
-        a0 *= f.x; a1 *= f.y;
-        h0 = fmaf(f.x, h0 - x.x, x.x); h1 = fmaf(f.y, h1 - x.y, x.y);        // f h + (1 - f) x
-    }
-    const size_t so = ((size_t)b * p.NS + seg) * p.d + c0;
-    *reinterpret_cast<f32x2*>(p.sumA + so) = f32x2{a0, a1};
-    *reinterpret_cast<f32x2*>(p.sumH + so) = f32x2{h0, h1};
-    if (BACKWARD) {
-        // reverse direction: r_t = dy_t o_t + c_t, c_{t-1} = f_t r_t, from c = 0 at the segment's end
-        float c0r = 0.0f, c1r = 0.0f;
-#pragma unroll 8
-        for (int t = nt - 1; t >= 0; --t) {
-            const f32x2 f = h1_load<GATE_BF16>(p.f, base + (size_t)t * p.d);
-            const f32x2 g = h1_load<true>(p.dy, base + (size_t)t * p.d);
-            const f32x2 og = h1_load<true>(p.o, base + (size_t)t * p.d);
-            c0r = f.x * fmaf(g.x, og.x, c0r); c1r = f.y * fmaf(g.y, og.y, c1r);
-        }
-        *reinterpret_cast<f32x2*>(p.sumQ + so) = f32x2{c0r, c1r};
+    if constexpr (BF16) {
+        return __builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0);
+    } else {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 0);
+        return f32x2{__uint_as_float(v[0]), __uint_as_float(v[1])};
     }
 }
-
-// ---- pass 2, forward -----------------------------------------------------------------------------
-template <bool GATE_BF16, int TS>
-__global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_apply_kernel(H1Params p)
+__device__ __forceinline__ void h1_st(H1Rsrc r, unsigned byte_off, float a, float b)
 {
-    int b, seg, c0;
-    if (!h1_map(p, b, seg, c0)) return;
-    f32x2 h = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    bf16x2 h;
+    h.x = (__bf16)a;
+    h.y = (__bf16)b;
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, h), r, byte_off, 0, 0);
+}
+__device__ __forceinline__ f32x2 h1_cvt(uint32_t u)
+{
+    return f32x2{__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u)};
+}
+__device__ __forceinline__ f32x2 h1_cvt(f32x2 v) { return v; }
+
+// At the top of a row's work in a second or third walk over the same registers: makes the compiler
+// convert the packed values again there, instead of keeping 32 rows of converted floats alive or
+// moving the row's arithmetic away from its place between the scheduling fences.
+__device__ __forceinline__ void h1_forget(uint32_t& u) { asm volatile("" : "+v"(u)); }
+__device__ __forceinline__ void h1_forget(f32x2& v) { asm volatile("" : "+v"(v.x), "+v"(v.y)); }
+// The row pitch as a value the compiler recomputes offsets from (instead of keeping 32 of them).
+__device__ __forceinline__ unsigned h1_pitch(int d) { unsigned x = 2u * (unsigned)d; asm volatile("" : "+s"(x)); return x; }
+
+// chain the published summaries in ascending (forward) or descending (reverse) segment order:
+// `mine` = state entering segment `vs` (this half-wave's), return value = state leaving the block
+template <bool ASCENDING>
+__device__ __forceinline__ f32x2 h1_chain(const f32x2 (*sA)[32], const f32x2 (*sX)[32], int vs, int cp, f32x2 c, f32x2& mine)
+{
+    mine = c;
+#pragma unroll
+    for (int k = 0; k < kH1Segs; ++k) {
+        const int j = ASCENDING ? k : kH1Segs - 1 - k;
+        if (j == vs) mine = c;
+        const f32x2 A = sA[j][cp], X = sX[j][cp];
+        c = f32x2{fmaf(A.x, c.x, X.x), fmaf(A.y, c.y, X.y)};
+    }
+    return c;
+}
+
+// ---- forward -------------------------------------------------------------------------------------
+template <bool GATE_BF16>
+__global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
+{
+    constexpr int TS = kH1Seg;
+    constexpr int GS = GATE_BF16 ? 1 : 2;         // gate bytes per bf16 byte
+    typedef H1Raw<GATE_BF16> Gate;
+    __shared__ f32x2 sA[2][kH1Segs][32], sH[2][kH1Segs][32];
+    const int cp = threadIdx.x & 31;                             // channel pair of the workgroup's 64 channels
+    const int vs = threadIdx.x >> 5;                             // segment of the block: each half-wave walks its own
+    const int b = blockIdx.x / p.NCB, cb = blockIdx.x % p.NCB;
+    const size_t c0 = (size_t)cb * kH1Chan + 2 * cp;
+    const size_t seq = (size_t)b * p.N * p.d;
+    const unsigned lane_b = 2u * (unsigned)c0;                   // byte offset of this lane's pair in a bf16 row
+
+    typename Gate::type fr[TS];
+    uint32_t xr[TS], orw[TS];
     {
-        const float* sa = p.sumA + (size_t)b * p.NS * p.d + c0;
-        const float* sh = p.sumH + (size_t)b * p.NS * p.d + c0;
-#pragma unroll 4
-        for (int j = 0; j < seg; ++j) {
-            const f32x2 A = *reinterpret_cast<const f32x2*>(sa + (size_t)j * p.d);
-            const f32x2 H = *reinterpret_cast<const f32x2*>(sh + (size_t)j * p.d);
-            h.x = fmaf(A.x, h.x, H.x); h.y = fmaf(A.y, h.y, H.y);
+        const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2),
+                     ro = h1_rows_from(p.o, seq, 0, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            xr[t] = h1_ld<true>(ri, off);
+            orw[t] = h1_ld<true>(ro, off);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    const int t0 = seg * TS, nt = min(TS, p.N - t0);
-    const size_t base = ((size_t)b * p.N + t0) * p.d + c0;
-    __bf16* yg = static_cast<__bf16*>(p.y);
-#pragma unroll 8
-    for (int t = 0; t < nt; ++t) {
-        const f32x2 f = h1_load<GATE_BF16>(p.f, base + (size_t)t * p.d);
-        const f32x2 x = h1_load<true>(p.i, base + (size_t)t * p.d);
-        const f32x2 og = h1_load<true>(p.o, base + (size_t)t * p.d);
-        h.x = fmaf(f.x, h.x - x.x, x.x); h.y = fmaf(f.y, h.y - x.y, x.y);
-        store_pair_t<__bf16>(yg, base + (size_t)t * p.d, h.x * og.x, h.y * og.y);
+    f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+
+    for (int blk = 0; blk < p.NBLK; ++blk) {
+        const int t0 = blk * kH1Block + vs * TS;
+        const int par = blk & 1;
+        // 1. segment summary from a zero state (rows past the end: f = 1, and i was read as 0)
+        f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
+            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+            a = f32x2{a.x * f.x, a.y * f.y};
+            h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};      // f h + (1 - f) x
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sA[par][vs][cp] = a;
+        sH[par][vs][cp] = h;
+        __syncthreads();
+        // 2. state entering this wave's segment, state leaving the block
+        f32x2 mine;
+        carry = h1_chain<true>(sA[par], sH[par], vs, cp, carry, mine);
+        // 3. outputs; every row is refilled with the next block's token once it is consumed
+        const int nb = (blk + 1) * kH1Block;
+        const H1Rsrc ry = h1_rows_from(p.y, seq, blk * kH1Block, p.N, p.d, 2);
+        const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2),
+                     ro = h1_rows_from(p.o, seq, nb, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
+        h = mine;
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            h1_forget(fr[t]);
+            h1_forget(xr[t]);
+            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]), og = h1_cvt(orw[t]);
+            h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            h1_st(ry, off, h.x * og.x, h.y * og.y);
+            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            xr[t] = h1_ld<true>(ri, off);
+            orw[t] = h1_ld<true>(ro, off);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
-    if (p.hN && seg == p.NS - 1) *reinterpret_cast<f32x2*>(p.hN + (size_t)b * p.d + c0) = h;
+    if (p.hN && vs == 0) *reinterpret_cast<f32x2*>(p.hN + (size_t)b * p.d + c0) = carry;
 }
 
-// ---- pass 2, backward ----------------------------------------------------------------------------
+// ---- backward ------------------------------------------------------------------------------------
 //   dL/dh_t = r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t  (c_N = grad_hN)
 //   do_t = dy_t h_t,   df_t = r_t (h_{t-1} - i_t),   di_t = r_t (1 - f_t),   dh0 = c_0
-template <bool GATE_BF16, int TS>
-__global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_apply_kernel(H1Params p)
+template <bool GATE_BF16>
+__global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
 {
-    int b, seg, c0;
-    if (!h1_map(p, b, seg, c0)) return;
-    const float* sa = p.sumA + (size_t)b * p.NS * p.d + c0;
-    f32x2 h = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    constexpr int TS = kH1Seg;
+    constexpr int GS = GATE_BF16 ? 1 : 2;
+    typedef H1Raw<GATE_BF16> Gate;
+    __shared__ f32x2 sA[2][kH1Segs][32], sX[2][kH1Segs][32];      // sX: forward H, later the reverse summary
+    const int cp = threadIdx.x & 31;                             // channel pair of the workgroup's 64 channels
+    const int vs = threadIdx.x >> 5;                             // segment of the block: each half-wave walks its own
+    const int b = blockIdx.x / p.NCB, cb = blockIdx.x % p.NCB;
+    const size_t c0 = (size_t)cb * kH1Chan + 2 * cp;
+    const size_t seq = (size_t)b * p.N * p.d;
+    const unsigned lane_b = 2u * (unsigned)c0;
+    const int last_blk = p.NBLK - 1;
+    // this thread's own slots of the saved states: written in the forward phase, read back in the reverse one
+    float* my_carry = p.carry + ((size_t)b * p.NBLK * kH1Segs + vs) * p.d + c0;
+    const size_t carry_blk = (size_t)kH1Segs * p.d;
+
+    typename Gate::type fr[TS];
+    uint32_t xr[TS], orw[TS], gr[TS];
     {
-        const float* sh = p.sumH + (size_t)b * p.NS * p.d + c0;
-#pragma unroll 4
-        for (int j = 0; j < seg; ++j) {
-            const f32x2 A = *reinterpret_cast<const f32x2*>(sa + (size_t)j * p.d);
-            const f32x2 H = *reinterpret_cast<const f32x2*>(sh + (size_t)j * p.d);
-            h.x = fmaf(A.x, h.x, H.x); h.y = fmaf(A.y, h.y, H.y);
+        const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            xr[t] = h1_ld<true>(ri, off);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    f32x2 c = p.dhN ? *reinterpret_cast<const f32x2*>(p.dhN + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    int it = 0;       // LDS buffer parity runs over both phases
+
+    // ---- forward phase: the state entering every segment ----
+    f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    for (int blk = 0; blk < p.NBLK; ++blk, ++it) {
+        const int t0 = blk * kH1Block + vs * TS;
+        const int nb = min(blk + 1, last_blk) * kH1Block;     // the last block is read again: the reverse phase starts on it
+        const int par = it & 1;
+        const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
+        f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
+#pragma unroll
+        for (int t = 0; t < TS; ++t) {
+            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
+            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+            a = f32x2{a.x * f.x, a.y * f.y};
+            h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            xr[t] = h1_ld<true>(ri, off);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sA[par][vs][cp] = a;
+        sX[par][vs][cp] = h;
+        __syncthreads();
+        f32x2 mine;
+        carry = h1_chain<true>(sA[par], sX[par], vs, cp, carry, mine);
+        *reinterpret_cast<f32x2*>(my_carry + blk * carry_blk) = mine;
+    }
+
+    // ---- reverse phase ----
     {
-        const float* sq = p.sumQ + (size_t)b * p.NS * p.d + c0;
-#pragma unroll 4
-        for (int j = p.NS - 1; j > seg; --j) {
-            const f32x2 A = *reinterpret_cast<const f32x2*>(sa + (size_t)j * p.d);
-            const f32x2 Q = *reinterpret_cast<const f32x2*>(sq + (size_t)j * p.d);
-            c.x = fmaf(A.x, c.x, Q.x); c.y = fmaf(A.y, c.y, Q.y);
+        // o and dy of the last block; f and i of it are in place
+        const H1Rsrc rg = h1_rows_from(p.dy, seq, last_blk * kH1Block, p.N, p.d, 2),
+                     ro = h1_rows_from(p.o, seq, last_blk * kH1Block, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
+#pragma unroll
+        for (int t = TS - 1; t >= 0; --t) {
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            gr[t] = h1_ld<true>(rg, off);
+            orw[t] = h1_ld<true>(ro, off);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    const int t0 = seg * TS, nt = min(TS, p.N - t0);
-    const size_t base = ((size_t)b * p.N + t0) * p.d + c0;
-    // forward walk: keep f, i and the state BEFORE every token
-    f32x2 fr[TS], xr[TS], hp[TS];
+    f32x2 cr = p.dhN ? *reinterpret_cast<const f32x2*>(p.dhN + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    for (int blk = last_blk; blk >= 0; --blk, ++it) {
+        const int t0 = blk * kH1Block + vs * TS;
+        const int par = it & 1;
+        const f32x2 h_in = *reinterpret_cast<const f32x2*>(my_carry + blk * carry_blk);
+        // reverse summary of the segment from c = 0 at its end (rows past the end: f = 1, dy was read as 0)
+        f32x2 a = {1.0f, 1.0f}, q = {0.0f, 0.0f};
 #pragma unroll
-    for (int t = 0; t < TS; ++t) {
-        const size_t e = base + (size_t)min(t, nt - 1) * p.d;      // rows past the end re-read the last one, unused
-        fr[t] = h1_load<GATE_BF16>(p.f, e);
-        xr[t] = h1_load<true>(p.i, e);
-    }
+        for (int t = TS - 1; t >= 0; --t) {
+            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
+            const f32x2 f = h1_cvt(fr[t]), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
+            a = f32x2{a.x * f.x, a.y * f.y};
+            q = f32x2{f.x * fmaf(g.x, og.x, q.x), f.y * fmaf(g.y, og.y, q.y)};
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        sA[par][vs][cp] = a;
+        sX[par][vs][cp] = q;
+        __syncthreads();
+        f32x2 c;
+        cr = h1_chain<false>(sA[par], sX[par], vs, cp, cr, c);
+        // the state before every token of the segment
+        f32x2 hp[TS];
+        {
+            f32x2 h = h_in;
 #pragma unroll
-    for (int t = 0; t < TS; ++t) {
-        hp[t] = h;
-        if (t < nt) { h.x = fmaf(fr[t].x, h.x - xr[t].x, xr[t].x); h.y = fmaf(fr[t].y, h.y - xr[t].y, xr[t].y); }
-    }
-    __bf16* dfg = static_cast<__bf16*>(p.df);
-    __bf16* dig = static_cast<__bf16*>(p.di);
-    __bf16* dog = static_cast<__bf16*>(p.dout);
+            for (int t = 0; t < TS; ++t) {
+                h1_forget(fr[t]);
+                h1_forget(xr[t]);
+                const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+                hp[t] = h;
+                h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // gradients, last token first; every row is refilled with the previous block's token once consumed
+        const int pb = max(blk - 1, 0) * kH1Block, cb0 = blk * kH1Block;
+        const H1Rsrc rdo = h1_rows_from(p.dout, seq, cb0, p.N, p.d, 2), rdf = h1_rows_from(p.df, seq, cb0, p.N, p.d, 2),
+                     rdi = h1_rows_from(p.di, seq, cb0, p.N, p.d, 2);
+        const H1Rsrc rf = h1_rows_from(p.f, seq, pb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, pb, p.N, p.d, 2),
+                     rg = h1_rows_from(p.dy, seq, pb, p.N, p.d, 2), ro = h1_rows_from(p.o, seq, pb, p.N, p.d, 2);
+        const unsigned pitch = h1_pitch(p.d);
 #pragma unroll
-    for (int t = TS - 1; t >= 0; --t) {
-        if (t < nt) {
-            const size_t e = base + (size_t)t * p.d;
-            const f32x2 g = h1_load<true>(p.dy, e);
-            const f32x2 og = h1_load<true>(p.o, e);
-            const float ht0 = fmaf(fr[t].x, hp[t].x - xr[t].x, xr[t].x), ht1 = fmaf(fr[t].y, hp[t].y - xr[t].y, xr[t].y);
-            const float r0 = fmaf(g.x, og.x, c.x), r1 = fmaf(g.y, og.y, c.y);
-            store_pair_t<__bf16>(dog, e, g.x * ht0, g.y * ht1);
-            store_pair_t<__bf16>(dfg, e, r0 * (hp[t].x - xr[t].x), r1 * (hp[t].y - xr[t].y));
-            store_pair_t<__bf16>(dig, e, r0 * (1.0f - fr[t].x), r1 * (1.0f - fr[t].y));
-            c.x = fr[t].x * r0; c.y = fr[t].y * r1;
+        for (int t = TS - 1; t >= 0; --t) {
+            h1_forget(fr[t]);
+            h1_forget(xr[t]);
+            h1_forget(gr[t]);
+            h1_forget(orw[t]);
+            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
+            const f32x2 e = {hp[t].x - x.x, hp[t].y - x.y};
+            const f32x2 ht = {fmaf(f.x, e.x, x.x), fmaf(f.y, e.y, x.y)};
+            const f32x2 r = {fmaf(g.x, og.x, c.x), fmaf(g.y, og.y, c.y)};
+            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+            h1_st(rdo, off, g.x * ht.x, g.y * ht.y);
+            h1_st(rdf, off, r.x * e.x, r.y * e.y);
+            h1_st(rdi, off, r.x * (1.0f - f.x), r.y * (1.0f - f.y));
+            c = f32x2{f.x * r.x, f.y * r.y};
+            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            xr[t] = h1_ld<true>(ri, off);
+            gr[t] = h1_ld<true>(rg, off);
+            orw[t] = h1_ld<true>(ro, off);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (p.dh0 && seg == 0) *reinterpret_cast<f32x2*>(p.dh0 + (size_t)b * p.d + c0) = c;
+    if (p.dh0 && vs == 0) *reinterpret_cast<f32x2*>(p.dh0 + (size_t)b * p.d + c0) = cr;
 }
 
 // N = 0: the final state is the initial one (and the gradient of the initial state that of the final one)
@@ -202,23 +352,19 @@ __global__ void hgrn1_copy_state_kernel(const float* src, float* dst, size_t n)
 }
 
 // ---- host side -----------------------------------------------------------------------------------
+static int h1_blocks(int N) { return (N + kH1Block - 1) / kH1Block; }
+
 size_t hgrn1_ws_bytes(int B, int N, int d)
 {
-    const size_t ns = ((size_t)N + kH1SegBwd - 1) / kH1SegBwd;
-    return 3 * (size_t)B * ns * d * sizeof(float);
+    return (size_t)B * h1_blocks(N) * kH1Segs * d * sizeof(float);
 }
 
-static void h1_fill(H1Params& p, int B, int N, int d, int TS, void* ws)
+static H1Params h1_params(int B, int N, int d, void* ws)
 {
-    p.B = B; p.N = N; p.d = d; p.NS = (N + TS - 1) / TS; p.NCB = d / kH1Chan;
-    const size_t one = (size_t)B * p.NS * d;
-    p.sumA = static_cast<float*>(ws); p.sumH = p.sumA + one; p.sumQ = p.sumH + one;
-}
-
-static unsigned h1_grid(const H1Params& p)
-{
-    const long long waves = (long long)p.B * p.NS * p.NCB;
-    return (unsigned)((waves + kH1Threads / 64 - 1) / (kH1Threads / 64));
+    H1Params p = {};
+    p.B = B; p.N = N; p.d = d; p.NBLK = h1_blocks(N); p.NCB = d / kH1Chan;
+    p.carry = static_cast<float*>(ws);
+    return p;
 }
 
 hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
@@ -230,17 +376,11 @@ hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, 
                                    stream, h0, hN, (size_t)B * d);
         return hipGetLastError();
     }
-    H1Params p = {};
+    H1Params p = h1_params(B, N, d, ws);
     p.f = f; p.i = i; p.o = o; p.h0 = h0; p.y = y; p.hN = hN;
-    h1_fill(p, B, N, d, kH1SegFwd, ws);
-    const unsigned grid = h1_grid(p);
-    if (gate_bf16) {
-        hipLaunchKernelGGL((hgrn1_summaries_kernel<true, kH1SegFwd, false>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-        hipLaunchKernelGGL((hgrn1_fwd_apply_kernel<true, kH1SegFwd>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-    } else {
-        hipLaunchKernelGGL((hgrn1_summaries_kernel<false, kH1SegFwd, false>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-        hipLaunchKernelGGL((hgrn1_fwd_apply_kernel<false, kH1SegFwd>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-    }
+    const dim3 grid((unsigned)(B * p.NCB));
+    if (gate_bf16) hipLaunchKernelGGL(hgrn1_fwd_kernel<true>, grid, dim3(kH1Threads), 0, stream, p);
+    else hipLaunchKernelGGL(hgrn1_fwd_kernel<false>, grid, dim3(kH1Threads), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -254,17 +394,11 @@ hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, 
                                     stream, dhN, dh0, (size_t)B * d);
         return hipGetLastError();
     }
-    H1Params p = {};
+    H1Params p = h1_params(B, N, d, ws);
     p.f = f; p.i = i; p.o = o; p.dy = dy; p.h0 = h0; p.dhN = dhN; p.df = df; p.di = di; p.dout = dout; p.dh0 = dh0;
-    h1_fill(p, B, N, d, kH1SegBwd, ws);
-    const unsigned grid = h1_grid(p);
-    if (gate_bf16) {
-        hipLaunchKernelGGL((hgrn1_summaries_kernel<true, kH1SegBwd, true>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-        hipLaunchKernelGGL((hgrn1_bwd_apply_kernel<true, kH1SegBwd>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-    } else {
-        hipLaunchKernelGGL((hgrn1_summaries_kernel<false, kH1SegBwd, true>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-        hipLaunchKernelGGL((hgrn1_bwd_apply_kernel<false, kH1SegBwd>), dim3(grid), dim3(kH1Threads), 0, stream, p);
-    }
+    const dim3 grid((unsigned)(B * p.NCB));
+    if (gate_bf16) hipLaunchKernelGGL(hgrn1_bwd_kernel<true>, grid, dim3(kH1Threads), 0, stream, p);
+    else hipLaunchKernelGGL(hgrn1_bwd_kernel<false>, grid, dim3(kH1Threads), 0, stream, p);
     return hipGetLastError();
 }
 

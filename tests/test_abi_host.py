@@ -161,7 +161,11 @@ def test_layout_field():
 
 def test_hgrn1_workspace_and_error_codes():
     lib = binding.lib()
-    assert binding.hgrn1_workspace_bytes(8, 2048, 2048) == 3 * 8 * 64 * 2048 * 4
+    fwd_d_limit = lambda: lib.hgrn1_fwd(1, 4, (1 << 20) + 128, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1 << 40, None)
+    assert binding.hgrn1_workspace_bytes(8, 2048, 2048) == 8 * 64 * 2048 * 4     # one state per 32-token segment
+    assert binding.hgrn1_workspace_bytes(1, 257, 128) == 16 * 128 * 4             # whole 512-token blocks
+    assert binding.hgrn1_workspace_bytes(1, 513, 128) == 2 * 16 * 128 * 4
+    assert fwd_d_limit() == E_SHAPE
     assert binding.hgrn1_workspace_bytes(8, 2048, 100) == 0
     big = 1 << 40
     fwd = lambda B=2, N=100, d=256, io=1, gate=1, f=FAKE, y=FAKE, ws=FAKE_WS, n=big: lib.hgrn1_fwd(

@@ -51,7 +51,7 @@ def test_hgrn1_ragged(d, gate_dtype):
     run(*make(5000 + d, 3, 203, d, gate_dtype=gate_dtype), gate_dtype=gate_dtype)
 
 
-@pytest.mark.parametrize("N", [0, 1, 31, 32, 33, 64, 65, 97])
+@pytest.mark.parametrize("N", [0, 1, 31, 32, 33, 64, 65, 97, 255, 256, 257, 511, 512, 513, 545, 1100])
 def test_hgrn1_edge_lengths(N):
     print("\n[hgrn1] edge N=%d" % N, flush=True)
     run(*make(5100 + N, 2, N, 128))
