@@ -146,6 +146,34 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream);
 
 /*
+ * Variable-length batches: shape->B sequences of different lengths packed back to back along the
+ * token axis, as training on packed documents and serving ragged prefill batches produce them.
+ * The recurrence of Eq. 3 (Section 3.2) restarts at every sequence boundary: sequence b starts
+ * from its own h0[b] (zero if NULL) and ends in its own hT[b].
+ *   shape           B = number of sequences, N = T = total number of tokens of all sequences,
+ *                   layout = HGRN2_LAYOUT_BNHD (else HGRN2_ERR_SHAPE); other fields as above
+ *   cu_seqlens  in  device int32 [B + 1]: sequence b owns tokens cu_seqlens[b] ..
+ *                   cu_seqlens[b + 1] - 1 (cu_seqlens[0] = 0, cu_seqlens[B] = T; empty sequences
+ *                   are fine).  The array is read on the device only; it is not validated, but
+ *                   offsets are clamped to [0, T] and made non-decreasing first, so a wrong array
+ *                   gives wrong results and never an access outside the tensors.
+ *   q, f, v, o, grad_*   device [T][H][d]    h0, hT, grad_hT, grad_h0   device fp32 [B][H][dk][dv]
+ *   workspace       hgrn2_fwd_varlen_workspace_bytes / hgrn2_bwd_varlen_workspace_bytes bytes
+ *                   (sized for the worst split of the T tokens into B sequences), 256-byte aligned
+ * The gates are given (the forms that build the gate of Eq. 2 take equal-length batches).
+ * Same status codes, stream semantics and numerical contract as hgrn2_fwd / hgrn2_bwd.
+ */
+size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape);
+size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape);
+int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                     void* grad_f, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                     void* hip_stream);
+
+/*
  * HGRN1, the element-wise gated linear recurrence the paper starts from (Section 2, Eq. 1, with the
  * forget gate f of Eq. 2 given), per channel:
  *     h_t = f_t * h_{t-1} + (1 - f_t) * i_t,      y_t = h_t * o_t

@@ -18,7 +18,8 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
+           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
+           "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
@@ -62,6 +63,14 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_gated.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_bwd_gated.restype = ctypes.c_int
         L.hgrn2_bwd_gated.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_fwd_varlen_workspace_bytes.restype = sz
+        L.hgrn2_fwd_varlen_workspace_bytes.argtypes = [sp]
+        L.hgrn2_bwd_varlen_workspace_bytes.restype = sz
+        L.hgrn2_bwd_varlen_workspace_bytes.argtypes = [sp]
+        L.hgrn2_fwd_varlen.restype = ctypes.c_int
+        L.hgrn2_fwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_bwd_varlen.restype = ctypes.c_int
+        L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_cumax.restype = ctypes.c_int
         L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
         L.hgrn1_workspace_bytes.restype = sz
@@ -208,6 +217,51 @@ def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd_gated")
     return grad_q, grad_z, grad_beta, grad_v, grad_h0
+
+
+def make_shape_varlen(q, v, f, n_seq) -> hgrn2_shape:
+    """Shape descriptor of packed tensors q, f [T,H,dk], v [T,H,dv] holding n_seq sequences."""
+    T, H, dk = q.shape
+    return hgrn2_shape(n_seq, H, T, dk, v.shape[-1], 0, _dt(q), _dt(f), HGRN2_LAYOUT_BNHD)
+
+
+def hgrn2_fwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_fwd_varlen_workspace_bytes(ctypes.byref(shape)))
+
+
+def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_bwd_varlen_workspace_bytes(ctypes.byref(shape)))
+
+
+def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, workspace=None):
+    """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
+    int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv]."""
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
+    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
+    o = torch.empty_like(v)
+    hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device) if want_hT else None
+    ws = _workspace(hgrn2_fwd_varlen_workspace_bytes(shape), q.device, workspace)
+    rc = lib().hgrn2_fwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(o),
+                                _ptr(hT), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_fwd_varlen")
+    return o, hT
+
+
+def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None):
+    """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis."""
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
+    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
+    gq, gf, gv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v)
+    gh0 = (torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+           if want_grad_h0 else None)
+    ws = _workspace(hgrn2_bwd_varlen_workspace_bytes(shape), q.device, workspace)
+    rc = lib().hgrn2_bwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(v), _ptr(h0),
+                                _ptr(grad_o), _ptr(grad_hT), _ptr(gq), _ptr(gf), _ptr(gv), _ptr(gh0), _ptr(ws),
+                                ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd_varlen")
+    return gq, gf, gv, gh0
 
 
 def hgrn2_cumax(gamma):

@@ -48,6 +48,22 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
     return HGRN2_OK;
 }
 
+// Variable-length batches: shape->B sequences packed into shape->N tokens of [T][H][d] tensors.
+// Fills `d` with NC = the host's bound on the chunks of all sequences (N / chunk + B); the table
+// pointer is set by the caller once the workspace is known.
+int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d)
+{
+    const int rc = check_shape(s, backward, d);
+    if (rc != HGRN2_OK) return rc;
+    if (s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;          // packed tokens are token-major
+    const long long bound = (long long)s->N / kChunk + s->B;
+    if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2 || s->B > INT_MAX / 8) return HGRN2_ERR_SHAPE;
+    d->NC = (int)bound;
+    d->lay.sb_k = d->lay.sb_v = 0;
+    d->lay.B = s->B;
+    return HGRN2_OK;
+}
+
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 }   // namespace
@@ -160,6 +176,79 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 {
     return bwd_impl(shape, q, z, beta, true, v, h0, grad_o, grad_hT, grad_q, grad_z, grad_beta, grad_v, grad_h0,
                     workspace, workspace_bytes, hip_stream);
+}
+
+size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape_varlen(shape, false, &d) != HGRN2_OK) return 0;
+    static int dummy_table;
+    d.lay.vl = &dummy_table;          // sizes only: marks the dims as variable-length
+    return round256(varlen_table_bytes(shape->B)) + round256(state_ws_bytes(d));
+}
+
+size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
+    static int dummy_table;
+    d.lay.vl = &dummy_table;
+    return round256(varlen_table_bytes(shape->B)) + 2 * round256(state_ws_bytes(d));
+}
+
+int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                     void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, false, &d);
+    if (rc != HGRN2_OK) return rc;
+    if (d.BH == 0) return HGRN2_OK;
+    const bool has_tokens = d.N > 0;
+    if (!cu_seqlens || (has_tokens && (!q || !f || !v || !o))) return HGRN2_ERR_NULL;
+    const size_t need = hgrn2_fwd_varlen_workspace_bytes(shape);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    if (!has_tokens && !hT) return HGRN2_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* table = static_cast<int*>(workspace);
+    void* ws_s = static_cast<char*>(workspace) + round256(varlen_table_bytes(shape->B));
+    d.lay.vl = table;
+    if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (fwd_fused_supported(d))
+        return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                     void* grad_f, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                     void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, true, &d);
+    if (rc != HGRN2_OK) return rc;
+    if (d.BH == 0) return HGRN2_OK;
+    const bool has_tokens = d.N > 0;
+    if (!cu_seqlens || (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)))
+        return HGRN2_ERR_NULL;
+    const size_t need = hgrn2_bwd_varlen_workspace_bytes(shape);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    if (!has_tokens && !grad_h0) return HGRN2_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* table = static_cast<int*>(workspace);
+    d.lay.vl = table;
+    const size_t one = round256(state_ws_bytes(d));
+    void* ws_s = static_cast<char*>(workspace) + round256(varlen_table_bytes(shape->B));
+    void* ws_ds = static_cast<char*>(ws_s) + one;
+    if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    if (has_tokens &&
+        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, nullptr, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
 }
 
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream)

@@ -174,19 +174,28 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // element-wise stage is over.  Rows past the end of a sequence re-read its last row: their
     // gates are replaced by one and their q by zero, which makes whatever finite values stand in
     // for V and dO there drop out of every stored result.
+    // chunk index -> sequence and chunk within it (every chunk index handed in is a valid one)
+    auto where = [&](int chunk, int& cn, SeqView& sv) {
+        int cbh;
+        locate_chunk<DENSE>(p.lay, p.BH, p.NC, chunk, cbh, cn);
+        sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, cbh);
+        return cbh;
+    };
     auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, int chunk, int lane) {
         const int col_k = (2 * lane < DK) ? 2 * lane : 0;
-        const int cn = chunk % p.NC, cbh = chunk / p.NC;
-        const size_t sk_ = DENSE ? (size_t)cbh * p.N * DK : p.lay.off_k(cbh);
+        int cn;
+        SeqView sv;
+        where(chunk, cn, sv);
         const int r0 = cn * C + RW * w;
-        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sk_ * GES, r0, p.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
-        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sk_), r0, p.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sv.off_k * GES, r0, sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sv.off_k), r0, sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
     };
     auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], int chunk, int lane) {
         load_fq_rows(cf, cq, chunk, lane);
-        const int cn = chunk % p.NC, cbh = chunk / p.NC;
-        const size_t vo = (DENSE ? (size_t)cbh * p.N * DV : p.lay.off_v(cbh)) +
-                          (size_t)min(cn * C + vd_row, p.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+        int cn;
+        SeqView sv;
+        where(chunk, cn, sv);
+        const size_t vo = sv.off_v + (size_t)min(cn * C + vd_row, sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
         cv[0] = *reinterpret_cast<const u32x4*>(vg + vo);
         cv[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
         cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
@@ -203,7 +212,10 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         }
     };
 
-    const int n_chunks = p.BH * p.NC;
+    int n_chunks = p.BH * p.NC;
+    if constexpr (!DENSE) {
+        if (p.lay.vl) n_chunks = p.lay.vl[2 * (p.lay.B + 1) + p.lay.B] * p.lay.H;      // the table's total, not the host's bound
+    }
     RawRows<RW> raw_f, raw_q;
     u32x4 raw_v[2], raw_d[2];
     frag sS[2 * NBT], sD[2 * NBT];
@@ -219,9 +231,11 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     asm volatile("" : "+v"(lane_opaque));
     const int lane = lane_opaque, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK;
-    const int n = chunk % p.NC, bh = chunk / p.NC;
-    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
-    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    int n;
+    SeqView sv;
+    const int bh = where(chunk, n, sv);
+    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
+    const int N = sv.N;
     const size_t ld_k = DENSE ? (size_t)DK : (size_t)p.lay.sn_k, ld_v = DENSE ? (size_t)DV : (size_t)p.lay.sn_v;
     load_chunk_states(sS, sD, chunk, lane);      // first needed two barriers from here; covered by the element-wise stage
 
@@ -243,9 +257,9 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // rf is re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
     const int row0 = n * C + RW * w;
     f32x2 rf[RW], rq[RW];
-    convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
-    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, p.N);
-    convert_rows<RW>(rq, raw_q, row0, p.N, k_act, true, 0.0f);
+    convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
+    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
+    convert_rows<RW>(rq, raw_q, row0, N, k_act, true, 0.0f);
 
     // ---------------- gate products; scaled operand tiles ----------------
     // With a = inclusive gate product from the start of this wave's 8-row block, z = exclusive
@@ -438,19 +452,19 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     float gs0[RW], gs1[RW], dk0[RW], dk1[RW];
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
-    convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
-    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, p.N);
+    convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
+    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
     // rows of this wave's block to global memory: one address and constant offsets when the
     // whole block lies inside the sequence, row by row otherwise
     auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
         T* bp = dst + seq_k + (size_t)row0 * ld_k + 2 * lane;
-        if (row0 + RW <= p.N) {
+        if (row0 + RW <= N) {
 #pragma unroll
             for (int i = 0; i < RW; ++i) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < RW; ++i)
-                if (row0 + i < p.N) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
+                if (row0 + i < N) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         }
     };
     if (k_act) {
@@ -484,7 +498,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         for (int idx = tid; idx < C * VPR; idx += kBwdThreads) {
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
-            if (grow < p.N)
+            if (grow < N)
                 *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * ld_v + cv * 8) =
                     *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * 8);
         }
@@ -552,7 +566,7 @@ static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
     if (e != hipSuccess) return e;
     // one persistent workgroup per CU (the LDS footprint admits no more), each walking its share of chunks
-    const size_t n_chunks = (size_t)d.BH * d.NC;
+    const size_t n_chunks = d.total_chunks();
     const unsigned grid = (unsigned)(n_chunks < 256 ? n_chunks : 256);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBwdThreads), L::total, stream, p);
     return hipGetLastError();
@@ -562,7 +576,7 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
                            const void* ws_state, const void* ws_dstate, void* grad_q, void* grad_f,
                            void* grad_v, float* beta_partials, hipStream_t stream)
 {
-    if ((size_t)d.BH * d.NC == 0) return hipSuccess;
+    if (d.total_chunks() == 0) return hipSuccess;
     if (!d.io_bf16) return hipErrorInvalidValue;
     BwdGradParams p;
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = ws_dstate;
@@ -582,7 +596,7 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
 
 size_t beta_partials_bytes(const SeqDims& d)
 {
-    return (size_t)d.BH * d.NC * kBwdWaves * d.dk * sizeof(float);
+    return d.total_chunks() * kBwdWaves * d.dk * sizeof(float);
 }
 
 // grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order: one

@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels.hpp"
+
 namespace hgrn2 {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -33,6 +35,69 @@ constexpr float kTinyProduct = 7.888609052210118e-31f;   // 2^-100: floor under 
 template <typename T> __host__ __device__ constexpr int pad_elems() { return 16 / (int)sizeof(T); }
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// ---- which tokens a sequence (b, h) owns --------------------------------------------------------
+// N tokens, NC chunks, element offsets of its first token in q / f (off_k) and v / o (off_v), and
+// the index of its first chunk in the per-chunk workspaces.  `bh` must be uniform over the wave.
+struct SeqView {
+    size_t off_k, off_v, chunk0;
+    int N, NC;
+};
+
+template <bool DENSE, int DK, int DV>
+__device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int NC, int bh)
+{
+    SeqView s;
+    if constexpr (DENSE) {
+        s.N = N; s.NC = NC;
+        s.off_k = (size_t)bh * N * DK; s.off_v = (size_t)bh * N * DV;
+        s.chunk0 = (size_t)bh * NC;
+    } else {
+        if (lay.vl) {
+            const int b = bh / lay.H, h = bh - b * lay.H;
+            const int start = lay.vl[b];
+            s.N = lay.vl[lay.B + 1 + b];
+            s.NC = (s.N + kChunk - 1) / kChunk;
+            s.off_k = (size_t)start * lay.sn_k + (size_t)h * lay.sh_k;
+            s.off_v = (size_t)start * lay.sn_v + (size_t)h * lay.sh_v;
+            s.chunk0 = (size_t)lay.vl[2 * (lay.B + 1) + b] * lay.H + (size_t)h * s.NC;
+        } else {
+            s.N = N; s.NC = NC;
+            s.off_k = lay.off_k(bh); s.off_v = lay.off_v(bh);
+            s.chunk0 = (size_t)bh * NC;
+        }
+    }
+    return s;
+}
+
+// Global chunk index -> (sequence, chunk within it).  Chunk indices run over the sequences in
+// order, each sequence's NC chunks per head together; with variable lengths the batch entry is
+// found by bisection on the table's chunk counts.  Returns false past the last chunk.
+template <bool DENSE>
+__device__ __forceinline__ bool locate_chunk(const TokenLayout& lay, int BH, int NC, int chunk, int& bh, int& n)
+{
+    if constexpr (!DENSE) {
+        if (lay.vl) {
+            const int* cb = lay.vl + 2 * (lay.B + 1);
+            if (chunk >= cb[lay.B] * lay.H) return false;
+            int lo = 0, hi = lay.B;                    // invariant: cb[lo] * H <= chunk < cb[hi] * H
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (cb[mid] * lay.H <= chunk) lo = mid; else hi = mid;
+            }
+            const int nc = (lay.vl[lay.B + 1 + lo] + kChunk - 1) / kChunk;      // > 0: the range is not empty
+            const int rem = chunk - cb[lo] * lay.H;
+            const int h = rem / nc;
+            bh = lo * lay.H + h;
+            n = rem - h * nc;
+            return true;
+        }
+    }
+    if (chunk >= BH * NC) return false;
+    bh = chunk / NC;
+    n = chunk - bh * NC;
+    return true;
+}
 
 // ---- global memory access of element pairs, storage type chosen at run time -------------------
 __device__ __forceinline__ f32x2 load_pair(const void* base, size_t idx, bool is_bf16)

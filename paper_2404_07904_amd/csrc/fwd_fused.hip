@@ -129,13 +129,14 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
-    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
-    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
+    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
+    const int N = sv.N;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     T* og = static_cast<T*>(p.o);
-    const int NC = p.NC;
+    const int NC = sv.NC;
 
     const int rt = w / NBT, bt = w % NBT;    // output tile (rt, bt) of this wave, if w < NOT
     const int at0 = NST * (w / NBT);         // its state tiles: (at0 .. at0 + NST - 1, bt)
@@ -178,7 +179,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     const char* fbase = static_cast<const char*>(p.f) + seq_k * (GATE_BF16 ? 2 : 4);
     const char* qbase = reinterpret_cast<const char*>(qg + seq_k);
     const char* vbase = reinterpret_cast<const char*>(vg + seq_v + dv0);
-    const int last_row = p.N - 1;
+    const int last_row = N - 1;
     auto load_f = [&](RawRows<RW>& d, int c) {
         load_rows_clamped<RW, GATE_BF16>(d, fbase, c * C + RW * w, last_row, ld_k, 2 * lane);
     };
@@ -214,8 +215,8 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     float qa0[RW], qa1[RW], kz0[RW], kz1[RW], bt0, bt1;
     auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
         f32x2 rf[RW];
-        convert_rows<RW>(rf, rf_raw, c * C + RW * w, p.N, true, GATE_BF16, 1.0f);
-        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, 2 * lane, true, c * C + RW * w, p.N);
+        convert_rows<RW>(rf, rf_raw, c * C + RW * w, N, true, GATE_BF16, 1.0f);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, 2 * lane, true, c * C + RW * w, N);
         float run0 = 1.0f, run1 = 1.0f;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
@@ -285,7 +286,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = c * C + row;
             obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
-            if ((unsigned)grow < (unsigned)p.N)      // also false for the chunk "-1" of the first pass
+            if ((unsigned)grow < (unsigned)N)      // also false for the chunk "-1" of the first pass
                 *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * ld_v + dv0 + cv * 8) = obuf[k];
         }
     };

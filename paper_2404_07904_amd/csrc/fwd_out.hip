@@ -61,16 +61,18 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     T* Ost = reinterpret_cast<T*>(smem + L::ost);   // output staging aliases K~ once P has been formed
 
-    const int n = blockIdx.x % p.NC, bh = blockIdx.x / p.NC;
+    int n, bh;
+    if (!locate_chunk<DENSE>(p.lay, p.BH, p.NC, blockIdx.x, bh, n)) return;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK, v_act = 2 * lane < DV;
-    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
-    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
+    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
+    const int N = sv.N;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
-    const T* wsn = static_cast<const T*>(p.ws) + ((size_t)bh * p.NC + n) * DK * DV;
+    const T* wsn = static_cast<const T*>(p.ws) + (size_t)blockIdx.x * DK * DV;      // chunk indices are the workspace order
 
     // ---------------- loads ----------------
     // incoming state S_n, column block bt of this wave, as B-operand fragments (k runs over dk)
@@ -86,13 +88,13 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
         RawRows<RW> raw_f, raw_q, raw_v;
         const int row0 = n * C + RW * w;
         const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
-        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_k, row0, p.N, gate_bf16);
-        load_rows<RW>(raw_q, qg, seq_k, ld_k, col_k, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_v, vg, seq_v, ld_v, col_v, row0, p.N, is_bf16_type<T>());
-        convert_rows<RW>(rf, raw_f, row0, p.N, k_act, gate_bf16, 1.0f);
-        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, p.N);
-        convert_rows<RW>(rq, raw_q, row0, p.N, k_act, is_bf16_type<T>(), 0.0f);
-        convert_rows<RW>(rv, raw_v, row0, p.N, v_act, is_bf16_type<T>(), 0.0f);
+        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_k, row0, N, gate_bf16);
+        load_rows<RW>(raw_q, qg, seq_k, ld_k, col_k, row0, N, is_bf16_type<T>());
+        load_rows<RW>(raw_v, vg, seq_v, ld_v, col_v, row0, N, is_bf16_type<T>());
+        convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, N);
+        convert_rows<RW>(rq, raw_q, row0, N, k_act, is_bf16_type<T>(), 0.0f);
+        convert_rows<RW>(rv, raw_v, row0, N, v_act, is_bf16_type<T>(), 0.0f);
     }
 
     // ---------------- gate products and scaled operands ----------------
@@ -207,7 +209,7 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
         for (int idx = tid; idx < C * VPR; idx += kThreads) {
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
-            if (grow < p.N) {
+            if (grow < N) {
                 const uint4 val = *reinterpret_cast<const uint4*>(Ost + (size_t)row * PO + cv * VEC);
                 *reinterpret_cast<uint4*>(og + seq_v + (size_t)grow * ld_v + cv * VEC) = val;
             }
@@ -230,7 +232,7 @@ static hipError_t launch_one(const SeqDims& d, const FwdOutParams& p, hipStream_
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)d.BH * d.NC)), dim3(kThreads), L::total, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)d.total_chunks()), dim3(kThreads), L::total, stream, p);
     return hipGetLastError();
 }
 
@@ -247,7 +249,7 @@ static hipError_t launch_dims(const SeqDims& d, const FwdOutParams& p, hipStream
 hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,
                           void* o, hipStream_t stream)
 {
-    if ((size_t)d.BH * d.NC == 0) return hipSuccess;
+    if (d.total_chunks() == 0) return hipSuccess;
     FwdOutParams p;
     p.q = q; p.f = f; p.v = v; p.ws = ws_state; p.o = o;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;

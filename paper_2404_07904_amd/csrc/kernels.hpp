@@ -17,14 +17,20 @@ constexpr int kChunk = 64;
 struct TokenLayout {
     long long sb_k, sh_k, sn_k, sb_v, sh_v, sn_v;
     int H;
+    // Variable-length batches: B sequences packed back to back along the token axis of [T][H][d]
+    // tensors.  `vl` is then the device table varlen_table() builds, three arrays of B + 1 ints:
+    // first token of sequence b, its length, and the number of chunks of the sequences before it
+    // (entry B: of all sequences).  Null for equal-length batches.
+    const int* vl = nullptr;
+    int B = 0;
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
     __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
 };
 
 struct SeqDims {
     int BH;          // B * H independent sequences
-    int N;           // tokens per sequence
-    int NC;          // chunks per sequence = ceil(N / kChunk)
+    int N;           // tokens per sequence (variable-length batches: tokens of all sequences)
+    int NC;          // chunks per sequence = ceil(N / kChunk) (variable-length: upper bound N / kChunk + B of all sequences' chunks)
     int dk, dv;
     bool io_bf16;    // q, v, o, grad_* storage: bf16 (else fp32)
     bool gate_bf16;  // f storage
@@ -34,7 +40,9 @@ struct SeqDims {
     const float* beta = nullptr;
     TokenLayout lay;
     // [B][H][N][d]: the kernels then use compile-time token strides
-    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv; }
+    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv && !lay.vl; }
+    // chunk slots of the per-chunk workspaces and of the per-chunk grids
+    size_t total_chunks() const { return lay.vl ? (size_t)H * NC : (size_t)BH * NC; }
 };
 
 // What a state sweep accumulates.
@@ -96,5 +104,12 @@ hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, 
 
 // Bytes of one per-chunk state set in the workspace.
 size_t state_ws_bytes(const SeqDims& d);
+
+// Variable-length batches: builds the table TokenLayout::vl points to from cu_seqlens (device,
+// B + 1 ints, cu_seqlens[b] = first token of sequence b, cu_seqlens[B] = T).  Offsets are clamped
+// to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
+// see are disjoint pieces of the T tokens.
+size_t varlen_table_bytes(int B);
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);
 
 }   // namespace hgrn2

@@ -63,22 +63,23 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
     const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;
-    const size_t seq_k = DENSE ? (size_t)bh * p.N * DK : p.lay.off_k(bh);
-    const size_t seq_v = DENSE ? (size_t)bh * p.N * DV : p.lay.off_v(bh);
+    const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
+    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
+    const int N = sv.N, NC = sv.NC;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qsrc = static_cast<const T*>(p.q);
     const T* bsrc = static_cast<const T*>(p.bsrc);
-    T* ws = static_cast<T*>(p.ws) + (size_t)bh * p.NC * DK * DV;
+    T* ws = static_cast<T*>(p.ws) + sv.chunk0 * DK * DV;
 
     // raw rows of the chunk being prefetched; inactive lanes read column 0 and are ignored
     RawRows<RW> raw_f, raw_q, raw_b;
     const int col_a = a_act ? 2 * lane : 0, col_b = col0 + (b_act ? 2 * lane : 0);
     auto load_chunk = [&](int n) {
         const int row0 = n * C + RW * w;
-        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_a, row0, p.N, gate_bf16);
-        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, ld_k, col_a, row0, p.N, is_bf16_type<T>());
-        load_rows<RW>(raw_b, bsrc, seq_v, ld_v, col_b, row0, p.N, is_bf16_type<T>());
+        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_a, row0, N, gate_bf16);
+        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, ld_k, col_a, row0, N, is_bf16_type<T>());
+        load_rows<RW>(raw_b, bsrc, seq_v, ld_v, col_b, row0, N, is_bf16_type<T>());
     };
 
     // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
@@ -98,21 +99,21 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
         }
     }
 
-    if (p.NC > 0) load_chunk(REVERSE ? p.NC - 1 : 0);
+    if (NC > 0) load_chunk(REVERSE ? NC - 1 : 0);
 
 #ifdef HGRN2_PHASE_TIMING
     long long ph[8] = {0};
     long long t_prev = wall_clock64();
 #endif
-    for (int it = 0; it < p.NC; ++it) {
-        const int n = REVERSE ? p.NC - 1 - it : it;
+    for (int it = 0; it < NC; ++it) {
+        const int n = REVERSE ? NC - 1 - it : it;
         f32x2 rf[RW], rq[RW], rb[RW];
         {
             const int row0 = n * C + RW * w;
-            convert_rows<RW>(rf, raw_f, row0, p.N, a_act, gate_bf16, 1.0f);
-            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_a, a_act, row0, p.N);
-            if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, p.N, a_act, is_bf16_type<T>(), 0.0f);
-            convert_rows<RW>(rb, raw_b, row0, p.N, b_act, is_bf16_type<T>(), 0.0f);
+            convert_rows<RW>(rf, raw_f, row0, N, a_act, gate_bf16, 1.0f);
+            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_a, a_act, row0, N);
+            if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, N, a_act, is_bf16_type<T>(), 0.0f);
+            convert_rows<RW>(rb, raw_b, row0, N, b_act, is_bf16_type<T>(), 0.0f);
         }
 
         // ---- gate products of this thread's RW tokens, channel pair (2*lane, 2*lane+1) ----
@@ -165,7 +166,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             store_run<T, RW>(BT + (2 * lane + 1) * PC + RW * w, x1);
         }
         HGRN2_STAMP(2);
-        if (it + 1 < p.NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
+        if (it + 1 < NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
         HGRN2_STAMP(3);
         __syncthreads();
         HGRN2_STAMP(4);
@@ -376,7 +377,7 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
 
 size_t state_ws_bytes(const SeqDims& d)
 {
-    return (size_t)d.BH * d.NC * d.dk * d.dv * (d.io_bf16 ? 2 : 4);
+    return d.total_chunks() * d.dk * d.dv * (d.io_bf16 ? 2 : 4);
 }
 
 }   // namespace hgrn2

@@ -1,0 +1,62 @@
+// Variable-length batches: B sequences packed back to back along the token axis.  The kernels
+// find a sequence's tokens and its slots in the per-chunk workspaces through a small device table
+// (TokenLayout::vl) that this kernel builds from the caller's cumulative sequence lengths:
+//
+//   table[0 .. B]            first token of sequence b            (entry B: end of the last one)
+//   table[B+1 .. 2B+1]       length of sequence b                 (entry B: 0)
+//   table[2B+2 .. 3B+2]      chunks of the sequences before b     (entry B: chunks of all)
+//
+// The offsets are clamped to [0, T] and replaced by their running maximum, so the table always
+// describes disjoint, ordered pieces of the T tokens, whatever the caller's array holds: a wrong
+// array gives wrong results, never an access outside the tensors or the workspaces.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace hgrn2 {
+
+constexpr int kTabThreads = 256;
+
+__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab)
+{
+    __shared__ int part[kTabThreads];
+    const int n = B + 1, tid = threadIdx.x;
+    const int per = (n + kTabThreads - 1) / kTabThreads;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);      // this thread's entries
+    auto clamped = [&](int i) { return min(max(cu[i], 0), T); };
+
+    // starts: running maximum of the clamped offsets
+    int m = 0;
+    for (int i = lo; i < hi; ++i) m = max(m, clamped(i));
+    part[tid] = m;
+    __syncthreads();
+    int run = 0;
+    for (int j = 0; j < tid; ++j) run = max(run, part[j]);
+    for (int i = lo; i < hi; ++i) { run = max(run, clamped(i)); tab[i] = run; }
+    __syncthreads();                                              // starts of the neighbouring slices are visible
+
+    // lengths, and the chunk counts before every sequence
+    int c = 0;
+    for (int i = lo; i < hi; ++i) {
+        const int len = i < B ? tab[i + 1] - tab[i] : 0;
+        tab[n + i] = len;
+        c += (len + kChunk - 1) / kChunk;
+    }
+    part[tid] = c;
+    __syncthreads();
+    run = 0;
+    for (int j = 0; j < tid; ++j) run += part[j];
+    for (int i = lo; i < hi; ++i) {
+        tab[2 * n + i] = run;
+        run += (tab[n + i] + kChunk - 1) / kChunk;
+    }
+}
+
+size_t varlen_table_bytes(int B) { return 3 * ((size_t)B + 1) * sizeof(int); }
+
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream)
+{
+    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table);
+    return hipGetLastError();
+}
+
+}   // namespace hgrn2

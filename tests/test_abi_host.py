@@ -181,3 +181,30 @@ def test_hgrn1_workspace_and_error_codes():
     assert bwd(d=64) == E_UNSUP
     assert bwd(gf=None) == E_NULL
     assert bwd(n=16) == E_WS
+
+
+def test_varlen_workspace_and_error_codes():
+    lib = binding.lib()
+    s = shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1)
+    table = 256                                              # 3 * 7 ints, rounded up
+    states = (1000 // 64 + 6) * 3 * 64 * 64 * 2              # worst split of 1000 tokens into 6 sequences
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(s) == table + states
+    assert binding.hgrn2_bwd_varlen_workspace_bytes(s) == table + 2 * states
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0      # packed tokens are token-major
+    big = 1 << 40
+    fwd = lambda s_, cu=FAKE, q=FAKE, o=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_fwd_varlen(
+        ctypes.byref(s_) if s_ is not None else None, cu, q, FAKE, FAKE, None, o, None, ws, n, None)
+    assert fwd(None) == E_NULL
+    assert fwd(shape(layout=0)) == E_SHAPE
+    assert fwd(shape(layout=1, dk=96)) == E_UNSUP
+    assert fwd(s, cu=None) == E_NULL
+    assert fwd(s, q=None) == E_NULL
+    assert fwd(s, n=table + states - 1) == E_WS
+    assert fwd(s, ws=None) == E_WS
+    assert fwd(shape(B=0, layout=1), cu=None, q=None, o=None, ws=None, n=0) == OK
+    bwd = lambda s_, cu=FAKE, gq=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_bwd_varlen(
+        ctypes.byref(s_), cu, FAKE, FAKE, FAKE, None, FAKE, None, gq, FAKE, FAKE, None, ws, n, None)
+    assert bwd(shape(layout=1, io=0, gate=0)) == E_UNSUP
+    assert bwd(s, cu=None) == E_NULL
+    assert bwd(s, gq=None) == E_NULL
+    assert bwd(s, n=table + 2 * states - 1) == E_WS

@@ -1,0 +1,123 @@
+"""GPU parity of the variable-length entry points (hgrn2_fwd_varlen, hgrn2_bwd_varlen): sequences
+of different lengths packed along the token axis of [T][H][d] tensors, against the fp64 oracle run
+on every sequence by itself.  The recurrence restarts at every boundary, so a token of one
+sequence must not influence another: the oracle side never sees the packing.
+Inputs: one seeded [1][H][T][d] draw of the usual recipe, cut at the boundaries.
+Tolerance: max|x-y|/max|y| <= 2e-2 per tensor (bf16 storage), over the whole packed tensor."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2404_07904_amd import binding, synth
+from gpu_util import TOL, check, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def packed(x, dtype):
+    """[1][H][T][d] host array -> [T][H][d] device tensor"""
+    return dev(x, dtype)[0].permute(1, 0, 2).contiguous()
+
+
+def unpacked(t):
+    """[T][H][d] device tensor -> [H][T][d] host array"""
+    return host(t.permute(1, 0, 2))
+
+
+def run(seed, lens, H, dk, dv, gate_dtype="bf16", lb=0.3, with_states=True, cu_override=None):
+    lens = list(lens)
+    B, T = len(lens), int(sum(lens))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    w = synth.make_sequence(seed, 1, H, max(T, 1), dk, dv, io_dtype="bf16", gate_dtype=gate_dtype, lb=lb,
+                            with_dO=True)
+    rng = np.random.default_rng(seed + 1)
+    h0 = rng.standard_normal((B, H, dk, dv)).astype(np.float32) if with_states else None
+    dhT = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32) if with_states else None
+    wq, wf, wv, wd = (x[:, :, :T] for x in (w.q, w.f, w.v, w.dO))
+    q, f, v, dO = packed(wq, "bf16"), packed(wf, gate_dtype), packed(wv, "bf16"), packed(wd, "bf16")
+    cud = torch.from_numpy(cu if cu_override is None else np.asarray(cu_override, dtype=np.int32)).cuda()
+    o, hT = binding.hgrn2_fwd_varlen(q, f, v, cud, dev(h0))
+    gq, gf, gv, gh0 = binding.hgrn2_bwd_varlen(q, f, v, dO, cud, dev(h0), dev(dhT), want_grad_h0=True)
+    torch.cuda.synchronize()
+    # oracle: every sequence on its own
+    ro, rq, rf, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
+    rhT, rh0 = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv))
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        sl = (slice(None), slice(None), slice(s, e))
+        hb = None if h0 is None else h0[b:b + 1]
+        db = None if dhT is None else dhT[b:b + 1]
+        ob, hTb = oracle.fwd(wq[sl], wf[sl], wv[sl], hb)
+        gqb, gfb, gvb, gh0b = oracle.bwd(wq[sl], wf[sl], wv[sl], wd[sl], hb, db)
+        ro[:, s:e], rq[:, s:e], rf[:, s:e], rv[:, s:e] = ob[0], gqb[0], gfb[0], gvb[0]
+        rhT[b], rh0[b] = hTb[0], gh0b[0]
+    tol = TOL["bf16"]
+    check("o", unpacked(o), ro, tol)
+    check("hT", host(hT), rhT, tol)
+    check("dq", unpacked(gq), rq, tol)
+    check("dv", unpacked(gv), rv, tol)
+    check("df", unpacked(gf), rf, tol)
+    check("dh0", host(gh0), rh0, tol)
+
+
+@pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (64, 128), (128, 64)])
+def test_varlen_mixed_lengths(dk, dv):
+    lens = [70, 1, 64, 129, 5, 200]
+    print("\n[varlen] dk=%d dv=%d H=3 lens=%s" % (dk, dv, lens), flush=True)
+    run(6000 + dk + 2 * dv, lens, 3, dk, dv)
+
+
+def test_varlen_empty_sequences_and_no_states():
+    lens = [0, 37, 0, 0, 64, 1, 0]
+    print("\n[varlen] empty sequences, lens=%s" % lens, flush=True)
+    run(6100, lens, 2, 64, 64)
+    run(6101, lens, 2, 128, 128, with_states=False)
+
+
+def test_varlen_single_sequence_equals_fixed_length():
+    print("\n[varlen] one sequence of 300 tokens", flush=True)
+    run(6200, [300], 4, 128, 128)
+
+
+@pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
+def test_varlen_fused_forward_path(gate_dtype):
+    """Enough sequences (B*H >= 64) for the single-pass forward; both of its grid shapes."""
+    rng = np.random.default_rng(6300)
+    lens = [int(x) for x in rng.integers(1, 200, size=12)]
+    print("\n[varlen] fused forward, H=8, 12 sequences, lens=%s gate=%s" % (lens, gate_dtype), flush=True)
+    run(6301, lens, 8, 128, 128, gate_dtype=gate_dtype)
+    lens = [int(x) for x in rng.integers(1, 150, size=26)]
+    print("[varlen] fused forward, H=8, 26 sequences", flush=True)
+    run(6302, lens, 8, 128, 128, gate_dtype=gate_dtype)
+
+
+def test_varlen_all_empty():
+    print("\n[varlen] T = 0", flush=True)
+    run(6400, [0, 0, 0], 2, 64, 64)
+
+
+def test_varlen_document_mix_layer_width():
+    """H=16, d=128, 8192 tokens cut into documents with a long-tailed length mix."""
+    rng = np.random.default_rng(6500)
+    lens = []
+    while sum(lens) < 8192:
+        lens.append(int(min(8192 - sum(lens), max(1, rng.lognormal(5.5, 1.0)))))
+    print("\n[varlen] H=16 d=128 T=8192, %d documents, longest %d" % (len(lens), max(lens)), flush=True)
+    run(6501, lens, 16, 128, 128, lb=0.5)
+
+
+def test_varlen_offsets_out_of_order_stay_in_bounds():
+    """A non-monotone cu_seqlens is not an error the library can report (it is device data), but it
+    must not reach outside the tensors: the call completes and the outputs of the well-formed
+    part are finite."""
+    H, dk, dv, T = 2, 64, 64, 150
+    w = synth.make_sequence(6600, 1, H, T, dk, dv, io_dtype="bf16", lb=0.3, with_dO=True)
+    q, f, v = packed(w.q, "bf16"), packed(w.f, "bf16"), packed(w.v, "bf16")
+    cud = torch.tensor([0, 100, 40, 9999, 150], dtype=torch.int32).cuda()
+    o, hT = binding.hgrn2_fwd_varlen(q, f, v, cud, None)
+    torch.cuda.synchronize()
+    assert torch.isfinite(hT).all()
+    # the table turns the offsets into 0, 100, 100, 150, 150: the first sequence is well formed
+    ro, _ = oracle.fwd(w.q[:, :, :100], w.f[:, :, :100], w.v[:, :, :100], None)
+    check("o[:100]", unpacked(o)[:, :100], ro[0], TOL["bf16"])
