@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-hgrn1", action="store_true", help="skip the element-wise HGRN1 workload")
+    ap.add_argument("--no-varlen", action="store_true", help="skip the packed variable-length run")
+    ap.add_argument("--no-handoff", action="store_true", help="skip the prefill -> decode hand-off run")
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
@@ -266,6 +268,79 @@ def main():
             "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tb / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}}
         del sets1, ws1, y1
+
+    # ---- variable-length batch: the same 16384 tokens per head, packed as documents of mixed length ----
+    if not args.no_varlen:
+        T = B * N
+        rng = np.random.default_rng(synth.BASE_SEED + 9)
+        lens = []
+        while sum(lens) < T:
+            lens.append(int(min(T - sum(lens), max(1, rng.lognormal(6.0, 1.0)))))
+        pack = lambda t: t.permute(0, 2, 1, 3).reshape(T, H, D).contiguous()          # [B][H][N][d] -> [B N][H][d]
+        vsets = [tuple(pack(t) for t in st_) for st_ in sets]
+
+        def run_varlen(cu_list):
+            cu = torch.tensor(cu_list, dtype=torch.int32, device=dev)
+            shp = binding.make_shape_varlen(vsets[0][0], vsets[0][2], vsets[0][1], len(cu_list) - 1)
+            wsv = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shp), dtype=torch.uint8, device=dev)
+
+            ov, gqv, gfv, gvv = (torch.empty_like(vsets[0][0]) for _ in range(4))
+
+            def fn(i):
+                q, f, v, dO = vsets[i % 2]
+                binding.hgrn2_fwd_varlen(q, f, v, cu, None, want_hT=False, o=ov, workspace=wsv)
+                binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=wsv, grad_q=gqv, grad_f=gfv, grad_v=gvv)
+            for i in range(6):
+                fn(i)
+            return timed(fn, reps=30)
+        t_mix = run_varlen([0] + list(np.cumsum(lens)))
+        t_eq = run_varlen([N * b for b in range(B + 1)])
+
+        def fixed_bnhd(i):          # the same packing seen as an equal-length [B][N][H][d] batch
+            q, f, v, dO = (t.view(B, N, H, D) for t in vsets[i % 2])
+            binding.hgrn2_fwd(q, f, v, None, o=o.view(B, N, H, D), hT=hT, workspace=ws, layout=binding.HGRN2_LAYOUT_BNHD)
+            binding.hgrn2_bwd(q, f, v, dO, None, None, workspace=ws, grad_q=gq.view(B, N, H, D), grad_f=gf.view(B, N, H, D),
+                              grad_v=gv.view(B, N, H, D), layout=binding.HGRN2_LAYOUT_BNHD)
+        for i in range(6):
+            fixed_bnhd(i)
+        t_fix = timed(fixed_bnhd, reps=30)
+        result["varlen"] = {
+            "workload": "T=%d tokens, H=%d, d=%d packed [T][H][d]; %d documents, lengths lognormal(6, 1) "
+                        "(median %d, longest %d)" % (T, H, D, len(lens), int(np.median(lens)), max(lens)),
+            "fwd_bwd_us_document_mix": round(t_mix * 1e6, 1), "tokens_per_s_document_mix": round(T / t_mix, 1),
+            "fwd_bwd_us_8_equal_sequences": round(t_eq * 1e6, 1), "tokens_per_s_8_equal_sequences": round(T / t_eq, 1),
+            "fwd_bwd_us_same_data_equal_length_entry_points": round(t_fix * 1e6, 1)}
+        del vsets
+
+    # ---- prefill -> decode hand-off: the chunkwise forward leaves the state the decode step continues from ----
+    if not args.no_handoff:
+        Bp, Np, n_dec = 32, 2048, 64
+        wp = synth.make_sequence(synth.BASE_SEED + 10, Bp, H, Np, D, D, io_dtype="bf16",
+                                 lb=float(synth.layer_lower_bound(args.layer)))
+        qp, fp, vp = (to_dev(x) for x in (wp.q, wp.f, wp.v))
+        wdn = synth.config4(T=n_dec, B=Bp, H=H, d=D)
+        qn, fn_, vn = (to_dev(x) for x in (wdn.q, wdn.f, wdn.v))
+        shp = binding.make_shape(qp, vp, fp)
+        wsp = torch.empty(binding.hgrn2_fwd_workspace_bytes(shp), dtype=torch.uint8, device=dev)
+        op = torch.empty_like(vp)
+        state = torch.empty((Bp, H, D, D), dtype=torch.float32, device=dev)
+        on = torch.empty((Bp, H, D), dtype=torch.bfloat16, device=dev)
+
+        def prefill(i):
+            binding.hgrn2_fwd(qp, fp, vp, None, o=op, hT=state, workspace=wsp)
+
+        def decode(i):
+            for t in range(n_dec):
+                binding.hgrn2_step(qn[t], fn_[t], vn[t], state, on)
+        for i in range(3):
+            prefill(i); decode(i)
+        tp, td = timed(prefill, reps=10), timed(decode, reps=5)
+        result["handoff"] = {
+            "workload": "prefill B=%d H=%d N=%d d=%d, then %d decode steps in place on the state it returns "
+                        "(fp32 [B][H][dk][dv], no copy or conversion between the two)" % (Bp, H, Np, D, n_dec),
+            "prefill_us": round(tp * 1e6, 1), "prefill_tokens_per_s": round(Bp * Np / tp, 1),
+            "decode_us_per_step": round(td / n_dec * 1e6, 2), "decode_tokens_per_s": round(Bp * n_dec / td, 1)}
+        del qp, fp, vp, op, state
 
     # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----
     if not args.no_decode:

@@ -233,13 +233,15 @@ def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_bwd_varlen_workspace_bytes(ctypes.byref(shape)))
 
 
-def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, workspace=None):
+def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, o=None, hT=None, workspace=None):
     """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
     int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv]."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
-    o = torch.empty_like(v)
-    hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device) if want_hT else None
+    if o is None:
+        o = torch.empty_like(v)
+    if hT is None and want_hT:
+        hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
     ws = _workspace(hgrn2_fwd_varlen_workspace_bytes(shape), q.device, workspace)
     rc = lib().hgrn2_fwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(o),
                                 _ptr(hT), _ptr(ws), ws.numel(), _stream())
@@ -248,11 +250,14 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, workspace=No
     return o, hT
 
 
-def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None):
+def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
+                     grad_q=None, grad_f=None, grad_v=None):
     """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
-    gq, gf, gv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v)
+    gq = torch.empty_like(q) if grad_q is None else grad_q
+    gf = torch.empty_like(q) if grad_f is None else grad_f
+    gv = torch.empty_like(v) if grad_v is None else grad_v
     gh0 = (torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
            if want_grad_h0 else None)
     ws = _workspace(hgrn2_bwd_varlen_workspace_bytes(shape), q.device, workspace)

@@ -175,27 +175,25 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // gates are replaced by one and their q by zero, which makes whatever finite values stand in
     // for V and dO there drop out of every stored result.
     // chunk index -> sequence and chunk within it (every chunk index handed in is a valid one)
-    auto where = [&](int chunk, int& cn, SeqView& sv) {
-        int cbh;
-        locate_chunk<DENSE>(p.lay, p.BH, p.NC, chunk, cbh, cn);
-        sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, cbh);
-        return cbh;
+    // chunk index -> sequence and chunk within it (every chunk index handed in is a valid one);
+    // found once per chunk, when its rows are requested, and kept for the chunk's own pass
+    struct ChunkAt { SeqView sv; int bh, n; };
+    int seq_hint = 0;         // the workgroup asks for chunk indices in non-decreasing order
+    auto where = [&](int chunk) {
+        ChunkAt c;
+        locate_chunk<DENSE>(p.lay, p.BH, p.NC, chunk, c.bh, c.n, &seq_hint);
+        c.sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, c.bh);
+        return c;
     };
-    auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, int chunk, int lane) {
+    auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, const ChunkAt& c, int lane) {
         const int col_k = (2 * lane < DK) ? 2 * lane : 0;
-        int cn;
-        SeqView sv;
-        where(chunk, cn, sv);
-        const int r0 = cn * C + RW * w;
-        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + sv.off_k * GES, r0, sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
-        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + sv.off_k), r0, sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        const int r0 = c.n * C + RW * w;
+        load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + c.sv.off_k * GES, r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + c.sv.off_k), r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
     };
-    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], int chunk, int lane) {
-        load_fq_rows(cf, cq, chunk, lane);
-        int cn;
-        SeqView sv;
-        where(chunk, cn, sv);
-        const size_t vo = sv.off_v + (size_t)min(cn * C + vd_row, sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], const ChunkAt& c, int lane) {
+        load_fq_rows(cf, cq, c, lane);
+        const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
         cv[0] = *reinterpret_cast<const u32x4*>(vg + vo);
         cv[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
         cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
@@ -221,7 +219,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     frag sS[2 * NBT], sD[2 * NBT];
     if ((int)blockIdx.x >= n_chunks) return;
     for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
-    load_chunk_rows(raw_f, raw_q, raw_v, raw_d, blockIdx.x, tid & 63);
+    ChunkAt cur = where(blockIdx.x);
+    load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
 
   for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
     // Re-derive the lane-dependent indices inside the loop from a value the compiler cannot see
@@ -231,11 +230,9 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     asm volatile("" : "+v"(lane_opaque));
     const int lane = lane_opaque, r32 = lane & 31, g = lane >> 5;
     const bool k_act = 2 * lane < DK;
-    int n;
-    SeqView sv;
-    const int bh = where(chunk, n, sv);
-    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
-    const int N = sv.N;
+    const int n = cur.n, bh = cur.bh;
+    const size_t seq_k = cur.sv.off_k, seq_v = cur.sv.off_v;
+    const int N = cur.sv.N;
     const size_t ld_k = DENSE ? (size_t)DK : (size_t)p.lay.sn_k, ld_v = DENSE ? (size_t)DV : (size_t)p.lay.sn_v;
     load_chunk_states(sS, sD, chunk, lane);      // first needed two barriers from here; covered by the element-wise stage
 
@@ -425,7 +422,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // Every load is unconditional (the last chunk of a workgroup fetches itself again), which
     // keeps the count of outstanding loads exact, so that nothing below waits for these.
     RawRows<RW> nxt_f, nxt_q;
-    load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, min(chunk + (int)gridDim.x, n_chunks - 1), lane);   // v, dO of this chunk are dead
+    const ChunkAt nxt = where(min(chunk + (int)gridDim.x, n_chunks - 1));
+    load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, nxt, lane);   // v, dO of this chunk are dead
     HGRN2_STAMP(6);
     __syncthreads();     // every wave is done with the operand tiles
     HGRN2_STAMP(7);
@@ -546,6 +544,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 #endif
     raw_f = nxt_f;
     raw_q = nxt_q;
+    cur = nxt;
     if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
 }

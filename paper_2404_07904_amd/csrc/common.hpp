@@ -71,19 +71,30 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
 }
 
 // Global chunk index -> (sequence, chunk within it).  Chunk indices run over the sequences in
-// order, each sequence's NC chunks per head together; with variable lengths the batch entry is
-// found by bisection on the table's chunk counts.  Returns false past the last chunk.
+// order, each sequence's NC chunks per head together.  With variable lengths the batch entry is
+// found in the table's chunk counts: by bisection, or, for a caller that asks for non-decreasing
+// chunk indices, by walking forward from the entry of its previous question (`hint`, start at 0).
+// Returns false past the last chunk.
 template <bool DENSE>
-__device__ __forceinline__ bool locate_chunk(const TokenLayout& lay, int BH, int NC, int chunk, int& bh, int& n)
+__device__ __forceinline__ bool locate_chunk(const TokenLayout& lay, int BH, int NC, int chunk, int& bh, int& n,
+                                             int* hint = nullptr)
 {
     if constexpr (!DENSE) {
         if (lay.vl) {
             const int* cb = lay.vl + 2 * (lay.B + 1);
             if (chunk >= cb[lay.B] * lay.H) return false;
-            int lo = 0, hi = lay.B;                    // invariant: cb[lo] * H <= chunk < cb[hi] * H
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (cb[mid] * lay.H <= chunk) lo = mid; else hi = mid;
+            int lo;
+            if (hint) {
+                lo = *hint;                            // cb[lo] * H <= chunk holds from the previous question
+                while (cb[lo + 1] * lay.H <= chunk) ++lo;
+                *hint = lo;
+            } else {
+                lo = 0;
+                int hi = lay.B;                        // invariant: cb[lo] * H <= chunk < cb[hi] * H
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (cb[mid] * lay.H <= chunk) lo = mid; else hi = mid;
+                }
             }
             const int nc = (lay.vl[lay.B + 1 + lo] + kChunk - 1) / kChunk;      // > 0: the range is not empty
             const int rem = chunk - cb[lo] * lay.H;
