@@ -70,6 +70,21 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
     return s;
 }
 
+// Kernels that give a whole sequence to one workgroup: which (b, h) the workgroup numbered `id`
+// takes.  Workgroups start in index order, so variable-length batches hand out their sequences
+// longest first.
+template <bool DENSE>
+__device__ __forceinline__ int sequence_of_workgroup(const TokenLayout& lay, int id)
+{
+    if constexpr (!DENSE) {
+        if (lay.vl) {
+            const int slot = id / lay.H, h = id - slot * lay.H;
+            return lay.vl[3 * (lay.B + 1) + slot] * lay.H + h;
+        }
+    }
+    return id;
+}
+
 // Global chunk index -> (sequence, chunk within it).  Chunk indices run over the sequences in
 // order, each sequence's NC chunks per head together.  With variable lengths the batch entry is
 // found in the table's chunk counts: by bisection, or, for a caller that asks for non-decreasing

@@ -126,6 +126,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     if (NSPLIT == 1) { bh = blockIdx.x; split = 0; }
     else { const int x = blockIdx.x & 7, r = blockIdx.x >> 3; split = r % NSPLIT; bh = (r / NSPLIT) * 8 + x; }
     if (bh >= p.BH) return;                  // padding of the grid (uniform, before any barrier)
+    bh = sequence_of_workgroup<DENSE>(p.lay, bh);
     const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register

@@ -18,9 +18,10 @@ struct TokenLayout {
     long long sb_k, sh_k, sn_k, sb_v, sh_v, sn_v;
     int H;
     // Variable-length batches: B sequences packed back to back along the token axis of [T][H][d]
-    // tensors.  `vl` is then the device table varlen_table() builds, three arrays of B + 1 ints:
-    // first token of sequence b, its length, and the number of chunks of the sequences before it
-    // (entry B: of all sequences).  Null for equal-length batches.
+    // tensors.  `vl` is then the device table launch_varlen_table() builds, four arrays of B + 1
+    // ints: first token of sequence b, its length, the number of chunks of the sequences before it
+    // (entry B: of all sequences), and the sequences ordered by falling length.  Null for
+    // equal-length batches.
     const int* vl = nullptr;
     int B = 0;
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }

@@ -60,6 +60,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     int bh, tile;
     xcd_map(block_id, p.n_tile, bh, tile);
     if (bh >= p.BH) return;
+    bh = sequence_of_workgroup<DENSE>(p.lay, bh);
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
     const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;

@@ -5,6 +5,10 @@
 //   table[0 .. B]            first token of sequence b            (entry B: end of the last one)
 //   table[B+1 .. 2B+1]       length of sequence b                 (entry B: 0)
 //   table[2B+2 .. 3B+2]      chunks of the sequences before b     (entry B: chunks of all)
+//   table[3B+3 .. 4B+3]      the sequences ordered by falling length (entry B unused)
+// The last array is for the kernels that give a whole sequence to one workgroup: workgroups start
+// in index order, so handing out the longest sequences first keeps the longest one from being the
+// last to start (for more than kSortMax sequences the order is left as it is).
 //
 // The offsets are clamped to [0, T] and replaced by their running maximum, so the table always
 // describes disjoint, ordered pieces of the T tokens, whatever the caller's array holds: a wrong
@@ -15,6 +19,7 @@
 namespace hgrn2 {
 
 constexpr int kTabThreads = 256;
+constexpr int kSortMax = 8192;
 
 __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab)
 {
@@ -49,9 +54,24 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
         tab[2 * n + i] = run;
         run += (tab[n + i] + kChunk - 1) / kChunk;
     }
+    __syncthreads();                                              // all lengths are visible
+
+    // order by falling length: the rank of sequence b is the number of sequences that come before
+    // it (longer, or as long with a smaller index), counted directly
+    const int* len = tab + n;
+    int* order = tab + 3 * n;
+    for (int b = tid; b < B; b += kTabThreads) {
+        int rank = b;
+        if (B <= kSortMax) {
+            rank = 0;
+            const int mine = len[b];
+            for (int j = 0; j < B; ++j) rank += (len[j] > mine || (len[j] == mine && j < b)) ? 1 : 0;
+        }
+        order[rank] = b;
+    }
 }
 
-size_t varlen_table_bytes(int B) { return 3 * ((size_t)B + 1) * sizeof(int); }
+size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream)
 {
