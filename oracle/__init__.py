@@ -210,3 +210,39 @@ def hgrn1_bwd(f, i, o, dy, h0=None, dhN=None):
         di[:, t] = dh * (1.0 - f[:, t])
         dh = dh * f[:, t]                            # dL/dh_{t-1} through the recurrence
     return df, di, do, dh
+
+
+# ---------------------------------------------------------------------------------------------
+# The HGRN1 layer's element-wise part as the paper writes it (Section 2): the three vectors of
+# Eq. 1 come from pre-activations (the projections' outputs, biases included) through
+#     g = sigmoid(zf),   i = tau(zi) with tau = SiLU,   o = sigmoid(zo),
+# and the forget gate gets its lower bound by Eq. 2,  f = beta + (1 - beta) g,  beta: [d] per layer.
+# ---------------------------------------------------------------------------------------------
+def _sigmoid(z):
+    return 1.0 / (1.0 + np.exp(-np.asarray(z, dtype=np.float64)))
+
+
+def hgrn1_activations(zf, zi, zo, beta):
+    b = np.asarray(beta, dtype=np.float64)[None, None, :]
+    zi = np.asarray(zi, dtype=np.float64)
+    return b + (1.0 - b) * _sigmoid(zf), zi * _sigmoid(zi), _sigmoid(zo)
+
+
+def hgrn1_fwd_act(zf, zi, zo, beta, h0=None):
+    return hgrn1_fwd(*hgrn1_activations(zf, zi, zo, beta), h0)
+
+
+def hgrn1_bwd_act(zf, zi, zo, beta, dy, h0=None, dhN=None):
+    """Gradients of L = sum(y * dy) + sum(h_N * dhN) w.r.t. zf, zi, zo, beta, h0: the chain rule
+    through the activations, d sigmoid = s (1 - s), d SiLU(z) = s (1 + z (1 - s)), and
+    df/dbeta = 1 - g summed over batch and time."""
+    f, i, o = hgrn1_activations(zf, zi, zo, beta)
+    df, di, do, dh0 = hgrn1_bwd(f, i, o, dy, h0, dhN)
+    b = np.asarray(beta, dtype=np.float64)[None, None, :]
+    g, si = _sigmoid(zf), _sigmoid(zi)
+    zi = np.asarray(zi, dtype=np.float64)
+    dzf = df * (1.0 - b) * g * (1.0 - g)
+    dzi = di * si * (1.0 + zi * (1.0 - si))
+    dzo = do * o * (1.0 - o)
+    dbeta = (df * (1.0 - g)).sum(axis=(0, 1))
+    return dzf, dzi, dzo, dbeta, dh0

@@ -486,3 +486,64 @@ def test_hgrn1_bwd_finite_differences_and_hgrn2_unit_state():
     back = lambda x: x[..., 0].transpose(0, 2, 1)
     assert np.max(np.abs(back(df2) - df)) <= 1e-12 and np.max(np.abs(back(dv2) - di)) <= 1e-12
     assert np.max(np.abs(back(dq2) - do)) <= 1e-12 and np.max(np.abs(dh02[..., 0, 0] - dh0)) <= 1e-12
+
+
+# ------------------------------------------------------------------ HGRN1 with its activations (Eq. 1 + Eq. 2)
+def test_hgrn1_activations_special_values_and_limits():
+    """Pins of the activation step that do not re-type its formulas: known values of sigmoid and
+    SiLU (sigmoid(0) = 1/2, sigmoid(ln 3) = 3/4, SiLU(0) = 0, SiLU(z) - SiLU(-z) = z), the range of
+    the bounded gate (beta <= f <= 1, f = beta at zf -> -inf, f = 1 at zf -> +inf, beta = 0 leaves
+    the plain sigmoid), and math.tanh as an independent evaluation of the sigmoid."""
+    import math
+    z = np.array([[[0.0, math.log(3.0), -math.log(3.0), 40.0, -40.0]]])
+    beta = np.array([0.25, 0.0, 0.5, 0.9, 0.9])
+    f, i, o = oracle.hgrn1_activations(z, z, z, beta)
+    assert np.allclose(f[0, 0], [0.25 + 0.75 * 0.5, 0.75, 0.5 + 0.5 * 0.25, 1.0, 0.9], atol=1e-15)
+    assert np.allclose(o[0, 0, :3], [0.5, 0.75, 0.25], atol=1e-15)
+    assert i[0, 0, 0] == 0.0 and abs(i[0, 0, 1] - 0.75 * math.log(3.0)) <= 1e-15
+    zz = np.linspace(-6, 6, 25)[None, None, :]
+    _, ip, _ = oracle.hgrn1_activations(zz, zz, zz, np.zeros(25))
+    _, im, _ = oracle.hgrn1_activations(zz, -zz, zz, np.zeros(25))
+    assert np.max(np.abs(ip - im - zz)) <= 1e-14                      # SiLU(z) - SiLU(-z) = z
+    f0, _, o0 = oracle.hgrn1_activations(zz, zz, zz, np.zeros(25))
+    th = np.array([0.5 * (1.0 + math.tanh(0.5 * x)) for x in zz[0, 0]])
+    assert np.max(np.abs(f0[0, 0] - th)) <= 1e-15 and np.max(np.abs(o0[0, 0] - th)) <= 1e-15
+    rng = np.random.default_rng(31)
+    b = rng.uniform(0, 0.95, 7)
+    fz, _, _ = oracle.hgrn1_activations(rng.standard_normal((3, 9, 7)) * 4, np.zeros((3, 9, 7)), np.zeros((3, 9, 7)), b)
+    assert np.all(fz >= b[None, None, :]) and np.all(fz <= 1.0)
+
+
+def test_hgrn1_act_bwd_finite_differences():
+    """Central differences of L = sum(y dy) + sum(h_N dhN) through the activations, for every input
+    including the per-channel lower bound; and a planted mistake (dropping the factor 1 - beta from
+    dzf, or the z (1 - s) term from the SiLU derivative) is far outside the bound."""
+    rng = np.random.default_rng(32)
+    B, N, d = 2, 9, 3
+    zf, zi, zo = (rng.standard_normal((B, N, d)) * 1.5 for _ in range(3))
+    beta = rng.uniform(0.05, 0.8, d)
+    h0 = rng.standard_normal((B, d)); dy = rng.standard_normal((B, N, d)); dhN = rng.standard_normal((B, d))
+
+    def loss(a):
+        y, hN = oracle.hgrn1_fwd_act(a["zf"], a["zi"], a["zo"], a["beta"], a["h0"])
+        return float((y * dy).sum() + (hN * dhN).sum())
+
+    dzf, dzi, dzo, dbeta, dh0 = oracle.hgrn1_bwd_act(zf, zi, zo, beta, dy, h0, dhN)
+    args = {"zf": zf, "zi": zi, "zo": zo, "beta": beta, "h0": h0}
+    eps = 1e-6
+    nums = {}
+    for name, g in (("zf", dzf), ("zi", dzi), ("zo", dzo), ("beta", dbeta), ("h0", dh0)):
+        x = args[name]
+        num = np.zeros_like(x)
+        for idx in np.ndindex(*x.shape):
+            ap, am = dict(args), dict(args)
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps; xm[idx] -= eps
+            ap[name], am[name] = xp, xm
+            num[idx] = (loss(ap) - loss(am)) / (2 * eps)
+        nums[name] = num
+        assert np.max(np.abs(num - g)) <= 2e-7 * max(1.0, np.max(np.abs(g))), name
+    assert np.max(np.abs(nums["zf"] - dzf / (1.0 - beta)[None, None, :])) > 1e-3 * np.max(np.abs(dzf))
+    s = 1.0 / (1.0 + np.exp(-zi))
+    di_only = dzi / (s * (1.0 + zi * (1.0 - s))) * s
+    assert np.max(np.abs(nums["zi"] - di_only)) > 1e-3 * np.max(np.abs(dzi))
