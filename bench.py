@@ -258,10 +258,26 @@ def main():
         for i in range(6):
             h1_fwd(i); h1_bwd(i)
         tf, tb = timed(h1_fwd, reps=50), timed(h1_bwd, reps=50)
+        # the same layer from its pre-activations (Eq. 1 activations and the Eq. 2 bound formed in the kernels);
+        # the N(0,1) tensors stand in for zf, zi, zo
+        beta1 = torch.full((d1,), lb1, dtype=torch.float32, device=dev)
+
+        def h1_fwd_act(i):
+            _, a, o1, c = sets1[i % 2]
+            binding.hgrn1_fwd_act(c, a, o1, beta1, None, y=y1, want_hN=False, workspace=ws1)
+
+        def h1_bwd_act(i):
+            f1, a, o1, c = sets1[i % 2]
+            binding.hgrn1_bwd_act(c, a, o1, beta1, f1, None, None, workspace=ws1)
+
+        for i in range(6):
+            h1_fwd_act(i); h1_bwd_act(i)
+        tfa, tba = timed(h1_fwd_act, reps=50), timed(h1_bwd_act, reps=50)
         e1 = B * N * d1 * el
         result["hgrn1"] = {
             "workload": "element-wise recurrence (Eq. 1), B=%d N=%d d=%d bf16, same gate statistics" % (B, N, d1),
             "fwd_us": round(tf * 1e6, 1), "bwd_us": round(tb * 1e6, 1),
+            "fwd_act_us": round(tfa * 1e6, 1), "bwd_act_us": round(tba * 1e6, 1),
             "tokens_per_s_fwd_bwd": round(tokens / (tf + tb), 1),
             "roofline_fwd": {"bound": "hbm", "achieved": round(4 * e1 / tf / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},

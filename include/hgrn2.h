@@ -197,6 +197,25 @@ int hgrn1_bwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dt
               size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The same recurrence taken from the pre-activations of Eq. 1 (Section 2), i.e. from what the
+ * layer's three projections (biases included) write, with the forget gate's lower bound of Eq. 2:
+ *     f = beta + (1 - beta) * sigmoid(zf),   i = SiLU(zi),   o = sigmoid(zo)
+ * formed inside the kernels, so that f, i and o never reach memory.
+ *   zf, zi, zo      in   device [B][N][d] (zf in gate_dtype, the others bf16)
+ *   beta            in   device fp32 [d]: the layer's lower bounds, each in [0, 1) (hgrn2_cumax)
+ *   grad_zf, grad_zi, grad_zo   out  device [B][N][d] bf16
+ *   grad_beta       out  device fp32 [d], summed over batch and time in a fixed order
+ * Everything else (states, workspace, status codes) as for hgrn1_fwd / hgrn1_bwd.
+ */
+int hgrn1_fwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                  const void* zi, const void* zo, const float* beta, const float* h0, void* y, float* hN,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+int hgrn1_bwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                  const void* zi, const void* zo, const float* beta, const float* h0, const void* grad_y,
+                  const float* grad_hN, void* grad_zf, void* grad_zi, void* grad_zo, float* grad_beta,
+                  float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Stage entry points.  hgrn2_fwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_FWD) followed by
  * hgrn2_fwd_readout; hgrn2_bwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_BWD), then
  * hgrn2_state_sweep(HGRN2_SWEEP_STATE_GRAD), then hgrn2_bwd_chunk_grads.  They exist for callers

@@ -18,7 +18,7 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
+           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
@@ -79,6 +79,10 @@ def lib() -> ctypes.CDLL:
         L.hgrn1_fwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn1_bwd.restype = ctypes.c_int
         L.hgrn1_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn1_fwd_act.restype = ctypes.c_int
+        L.hgrn1_fwd_act.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn1_bwd_act.restype = ctypes.c_int
+        L.hgrn1_bwd_act.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.hgrn2_state_sweep.restype = ctypes.c_int
@@ -309,6 +313,38 @@ def hgrn1_bwd(f, i, o, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, wor
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn1_bwd")
     return gf, gi, go, gh0
+
+
+def hgrn1_fwd_act(zf, zi, zo, beta, h0=None, *, want_hN=True, y=None, hN=None, workspace=None):
+    """y, hN of the element-wise recurrence from the pre-activations of Eq. 1 and the lower bounds
+    beta [d] of Eq. 2.  zf, zi, zo: [B,N,d]."""
+    B, N, d = zf.shape
+    assert zi.shape == zf.shape and zo.shape == zf.shape and beta.dtype == torch.float32 and beta.numel() == d
+    if y is None:
+        y = torch.empty_like(zi)
+    if hN is None and want_hN:
+        hN = torch.empty((B, d), dtype=torch.float32, device=zf.device)
+    ws = _workspace(hgrn1_workspace_bytes(B, N, d), zf.device, workspace)
+    rc = lib().hgrn1_fwd_act(B, N, d, _dt(zi), _dt(zf), _ptr(zf), _ptr(zi), _ptr(zo), _ptr(beta), _ptr(h0), _ptr(y),
+                             _ptr(hN), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn1_fwd_act")
+    return y, hN
+
+
+def hgrn1_bwd_act(zf, zi, zo, beta, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None):
+    """grad_zf, grad_zi, grad_zo, grad_beta, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN)."""
+    B, N, d = zf.shape
+    gf, gi, go = torch.empty_like(zi), torch.empty_like(zi), torch.empty_like(zi)
+    gb = torch.empty((d,), dtype=torch.float32, device=zf.device)
+    gh0 = torch.empty((B, d), dtype=torch.float32, device=zf.device) if want_grad_h0 else None
+    ws = _workspace(hgrn1_workspace_bytes(B, N, d), zf.device, workspace)
+    rc = lib().hgrn1_bwd_act(B, N, d, _dt(zi), _dt(zf), _ptr(zf), _ptr(zi), _ptr(zo), _ptr(beta), _ptr(h0),
+                             _ptr(grad_y), _ptr(grad_hN), _ptr(gf), _ptr(gi), _ptr(go), _ptr(gb), _ptr(gh0), _ptr(ws),
+                             ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn1_bwd_act")
+    return gf, gi, go, gb, gh0
 
 
 def hgrn2_step(q_t, f_t, v_t, state, o_t=None):

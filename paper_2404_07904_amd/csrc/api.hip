@@ -341,20 +341,51 @@ size_t hgrn1_workspace_bytes(int32_t B, int32_t N, int32_t d)
     return round256(hgrn1_ws_bytes(B, N, d));
 }
 
-int hgrn1_fwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
-              const void* i, const void* o, const float* h0, void* y, float* hN, void* workspace,
-              size_t workspace_bytes, void* hip_stream)
+static int h1_fwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+                       const void* i, const void* o, const float* beta, bool act, const float* h0, void* y, float* hN,
+                       void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)B * N * d > 0;
-    if (has_tokens && (!f || !i || !o || !y)) return HGRN2_ERR_NULL;
+    if (has_tokens && (!f || !i || !o || !y || (act && !beta))) return HGRN2_ERR_NULL;
     const size_t need = round256(hgrn1_ws_bytes(B, N, d));
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
-    if (launch_hgrn1_fwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, h0, y, hN, workspace,
+    if (launch_hgrn1_fwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, act ? beta : nullptr, h0, y, hN, workspace,
                          static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;
+}
+
+static int h1_bwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+                       const void* i, const void* o, const float* beta, bool act, const float* h0, const void* grad_y,
+                       const float* grad_hN, void* grad_f, void* grad_i, void* grad_o, float* grad_beta,
+                       float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)B * N * d > 0;
+    if (has_tokens && (!f || !i || !o || !grad_y || !grad_f || !grad_i || !grad_o || (act && !beta)))
+        return HGRN2_ERR_NULL;
+    if (act && d > 0 && !grad_beta) return HGRN2_ERR_NULL;
+    const size_t need = round256(hgrn1_ws_bytes(B, N, d));
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (act && !has_tokens && d > 0) {        // nothing contributes: the gradient of beta is zero
+        if (hipMemsetAsync(grad_beta, 0, (size_t)d * sizeof(float), stream) != hipSuccess) return HGRN2_ERR_HIP;
+    }
+    if (launch_hgrn1_bwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, act ? beta : nullptr, h0, grad_y, grad_hN, grad_f,
+                         grad_i, grad_o, act && has_tokens ? grad_beta : nullptr, grad_h0, workspace, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
+int hgrn1_fwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+              const void* i, const void* o, const float* h0, void* y, float* hN, void* workspace,
+              size_t workspace_bytes, void* hip_stream)
+{
+    return h1_fwd_impl(B, N, d, io_dtype, gate_dtype, f, i, o, nullptr, false, h0, y, hN, workspace, workspace_bytes,
+                       hip_stream);
 }
 
 int hgrn1_bwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
@@ -362,16 +393,25 @@ int hgrn1_bwd(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dt
               void* grad_f, void* grad_i, void* grad_o, float* grad_h0, void* workspace, size_t workspace_bytes,
               void* hip_stream)
 {
-    const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
-    if (rc != HGRN2_OK) return rc;
-    const bool has_tokens = (size_t)B * N * d > 0;
-    if (has_tokens && (!f || !i || !o || !grad_y || !grad_f || !grad_i || !grad_o)) return HGRN2_ERR_NULL;
-    const size_t need = round256(hgrn1_ws_bytes(B, N, d));
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
-    if (launch_hgrn1_bwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, h0, grad_y, grad_hN, grad_f, grad_i, grad_o,
-                         grad_h0, workspace, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    return HGRN2_OK;
+    return h1_bwd_impl(B, N, d, io_dtype, gate_dtype, f, i, o, nullptr, false, h0, grad_y, grad_hN, grad_f, grad_i,
+                       grad_o, nullptr, grad_h0, workspace, workspace_bytes, hip_stream);
+}
+
+int hgrn1_fwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                  const void* zi, const void* zo, const float* beta, const float* h0, void* y, float* hN,
+                  void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return h1_fwd_impl(B, N, d, io_dtype, gate_dtype, zf, zi, zo, beta, true, h0, y, hN, workspace, workspace_bytes,
+                       hip_stream);
+}
+
+int hgrn1_bwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                  const void* zi, const void* zo, const float* beta, const float* h0, const void* grad_y,
+                  const float* grad_hN, void* grad_zf, void* grad_zi, void* grad_zo, float* grad_beta,
+                  float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return h1_bwd_impl(B, N, d, io_dtype, gate_dtype, zf, zi, zo, beta, true, h0, grad_y, grad_hN, grad_zf, grad_zi,
+                       grad_zo, grad_beta, grad_h0, workspace, workspace_bytes, hip_stream);
 }
 
 const char* hgrn2_status_string(int status)

@@ -24,6 +24,11 @@
 // segment (a few MB), then walks the blocks from the last to the first with the same scheme for
 // the reverse recurrence  r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t.
 // Tensors are [B][N][d] (token-major, d a multiple of 128), states [B][d] fp32.
+//
+// The "act" forms take the three pre-activations of Eq. 1 instead (the outputs of the layer's
+// projections) and the layer's lower bounds of Eq. 2, and form
+//     f = beta + (1 - beta) sigmoid(zf),   i = SiLU(zi),   o = sigmoid(zo)
+// when a register row is first used: the layer never writes f, i or o to memory.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -34,23 +39,25 @@ constexpr int kH1Waves = 8;                       // waves per workgroup
 constexpr int kH1Threads = 64 * kH1Waves;
 constexpr int kH1Chan = 64;                       // channels per workgroup: a pair per lane of a half-wave
 constexpr int kH1Segs = 2 * kH1Waves;             // segments per block: one per half-wave
-constexpr int kH1Seg = 32;                        // tokens per segment
-constexpr int kH1Block = kH1Segs * kH1Seg;        // tokens per block
+constexpr int kH1SegLong = 32;                    // tokens per segment
+constexpr int kH1SegShort = 16;                   // ... of the backward with activations (it holds more per token)
 
 struct H1Params {
-    const void* f;
-    const void* i;
-    const void* o;
+    const void* f;        // gates, or their pre-activations zf
+    const void* i;        // inputs, or zi
+    const void* o;        // output gates, or zo
     const void* dy;
     const float* h0;
     const float* dhN;
+    const float* beta;    // [d] lower bounds (act forms)
     void* y;
     void* df;
     void* di;
     void* dout;
     float* hN;
     float* dh0;
-    float* carry;     // [B][NBLK * kH1Segs][d]: state entering every segment (backward)
+    float* carry;         // [B][NBLK * kH1Segs][d]: state entering every segment (backward)
+    float* dbeta_part;    // [B][d]: every sequence's share of the gradient of beta (act backward)
     int B, N, d, NBLK, NCB;
 };
 
@@ -88,12 +95,16 @@ __device__ __forceinline__ typename H1Raw<BF16>::type h1_ld(H1Rsrc r, unsigned b
         return f32x2{__uint_as_float(v[0]), __uint_as_float(v[1])};
     }
 }
-__device__ __forceinline__ void h1_st(H1Rsrc r, unsigned byte_off, float a, float b)
+__device__ __forceinline__ uint32_t h1_pack(float a, float b)
 {
     bf16x2 h;
     h.x = (__bf16)a;
     h.y = (__bf16)b;
-    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, h), r, byte_off, 0, 0);
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ void h1_st(H1Rsrc r, unsigned byte_off, float a, float b)
+{
+    __builtin_amdgcn_raw_buffer_store_b32(h1_pack(a, b), r, byte_off, 0, 0);
 }
 __device__ __forceinline__ f32x2 h1_cvt(uint32_t u)
 {
@@ -101,12 +112,16 @@ __device__ __forceinline__ f32x2 h1_cvt(uint32_t u)
 }
 __device__ __forceinline__ f32x2 h1_cvt(f32x2 v) { return v; }
 
+__device__ __forceinline__ float h1_sigmoid(float z) { return fast_rcp(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z)); }
+__device__ __forceinline__ f32x2 h1_sigmoid(f32x2 z) { return f32x2{h1_sigmoid(z.x), h1_sigmoid(z.y)}; }
+__device__ __forceinline__ f32x2 h1_silu(f32x2 z) { return f32x2{z.x * h1_sigmoid(z.x), z.y * h1_sigmoid(z.y)}; }
+
 // At the top of a row's work in a second or third walk over the same registers: makes the compiler
-// convert the packed values again there, instead of keeping 32 rows of converted floats alive or
+// convert the packed values again there, instead of keeping a segment of converted floats alive or
 // moving the row's arithmetic away from its place between the scheduling fences.
 __device__ __forceinline__ void h1_forget(uint32_t& u) { asm volatile("" : "+v"(u)); }
 __device__ __forceinline__ void h1_forget(f32x2& v) { asm volatile("" : "+v"(v.x), "+v"(v.y)); }
-// The row pitch as a value the compiler recomputes offsets from (instead of keeping 32 of them).
+// The row pitch as a value the compiler recomputes offsets from (instead of keeping one per row).
 __device__ __forceinline__ unsigned h1_pitch(int d) { unsigned x = 2u * (unsigned)d; asm volatile("" : "+s"(x)); return x; }
 
 // chain the published summaries in ascending (forward) or descending (reverse) segment order:
@@ -125,13 +140,43 @@ __device__ __forceinline__ f32x2 h1_chain(const f32x2 (*sA)[32], const f32x2 (*s
     return c;
 }
 
+// The forget gate of a register row when it is first used: the stored gate, or Eq. 2 on its
+// pre-activation; a row past the end of the sequence gets exactly 1 (its input reads as 0).
+template <bool GATE_BF16, bool ACT>
+__device__ __forceinline__ f32x2 h1_first_gate(typename H1Raw<GATE_BF16>::type raw, f32x2 beta, bool valid)
+{
+    f32x2 f = h1_cvt(raw);
+    if constexpr (ACT) f = f32x2{lower_bounded_gate(f.x, beta.x), lower_bounded_gate(f.y, beta.y)};
+    return valid ? f : f32x2{1.0f, 1.0f};
+}
+
+// Register rows of the gate: fr holds what was loaded (the next block's, from the moment the row
+// is refilled).  Stored bf16 gates are used straight from it (one register per channel pair,
+// converted at every use); fp32 gates and gates formed from pre-activations are kept as two
+// floats in fa once the row has been used for the first time.
+template <bool GATE_BF16, bool ACT, typename RAW>
+__device__ __forceinline__ void h1_touch_gate(RAW& raw, f32x2& kept, f32x2 beta, bool valid)
+{
+    if constexpr (GATE_BF16 && !ACT) raw = valid ? raw : H1Raw<true>::one();
+    else kept = h1_first_gate<GATE_BF16, ACT>(raw, beta, valid);
+}
+template <bool GATE_BF16, bool ACT, typename RAW>
+__device__ __forceinline__ f32x2 h1_gate(RAW& raw, const f32x2& kept, bool again)
+{
+    if constexpr (GATE_BF16 && !ACT) {
+        if (again) h1_forget(raw);
+        return h1_cvt(raw);
+    } else {
+        return kept;
+    }
+}
+
 // ---- forward -------------------------------------------------------------------------------------
-template <bool GATE_BF16>
+template <bool GATE_BF16, bool ACT>
 __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
 {
-    constexpr int TS = kH1Seg;
+    constexpr int TS = kH1SegLong, BLOCK = kH1Segs * TS;
     constexpr int GS = GATE_BF16 ? 1 : 2;         // gate bytes per bf16 byte
-    typedef H1Raw<GATE_BF16> Gate;
     __shared__ f32x2 sA[2][kH1Segs][32], sH[2][kH1Segs][32];
     const int cp = threadIdx.x & 31;                             // channel pair of the workgroup's 64 channels
     const int vs = threadIdx.x >> 5;                             // segment of the block: each half-wave walks its own
@@ -139,8 +184,10 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
     const size_t c0 = (size_t)cb * kH1Chan + 2 * cp;
     const size_t seq = (size_t)b * p.N * p.d;
     const unsigned lane_b = 2u * (unsigned)c0;                   // byte offset of this lane's pair in a bf16 row
+    const f32x2 beta = ACT ? *reinterpret_cast<const f32x2*>(p.beta + c0) : f32x2{0.0f, 0.0f};
 
-    typename Gate::type fr[TS];
+    typename H1Raw<GATE_BF16>::type fr[TS];
+    f32x2 fa[TS];
     uint32_t xr[TS], orw[TS];
     {
         const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2),
@@ -158,14 +205,15 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
     f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
 
     for (int blk = 0; blk < p.NBLK; ++blk) {
-        const int t0 = blk * kH1Block + vs * TS;
+        const int t0 = blk * BLOCK + vs * TS;
         const int par = blk & 1;
-        // 1. segment summary from a zero state (rows past the end: f = 1, and i was read as 0)
+        // 1. segment summary from a zero state
         f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
-            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
-            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+            h1_touch_gate<GATE_BF16, ACT>(fr[t], fa[t], beta, t0 + t < p.N);
+            if constexpr (ACT) { const f32x2 x = h1_silu(h1_cvt(xr[t])); xr[t] = h1_pack(x.x, x.y); }
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], false), x = h1_cvt(xr[t]);
             a = f32x2{a.x * f.x, a.y * f.y};
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};      // f h + (1 - f) x
             __builtin_amdgcn_sched_barrier(0);
@@ -173,21 +221,22 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
         sA[par][vs][cp] = a;
         sH[par][vs][cp] = h;
         __syncthreads();
-        // 2. state entering this wave's segment, state leaving the block
+        // 2. state entering this half-wave's segment, state leaving the block
         f32x2 mine;
         carry = h1_chain<true>(sA[par], sH[par], vs, cp, carry, mine);
         // 3. outputs; every row is refilled with the next block's token once it is consumed
-        const int nb = (blk + 1) * kH1Block;
-        const H1Rsrc ry = h1_rows_from(p.y, seq, blk * kH1Block, p.N, p.d, 2);
+        const int nb = (blk + 1) * BLOCK;
+        const H1Rsrc ry = h1_rows_from(p.y, seq, blk * BLOCK, p.N, p.d, 2);
         const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2),
                      ro = h1_rows_from(p.o, seq, nb, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
         h = mine;
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
-            h1_forget(fr[t]);
             h1_forget(xr[t]);
-            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]), og = h1_cvt(orw[t]);
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], true), x = h1_cvt(xr[t]);
+            f32x2 og = h1_cvt(orw[t]);
+            if constexpr (ACT) og = h1_sigmoid(og);
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
             const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
             h1_st(ry, off, h.x * og.x, h.y * og.y);
@@ -203,26 +252,38 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
 // ---- backward ------------------------------------------------------------------------------------
 //   dL/dh_t = r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t  (c_N = grad_hN)
 //   do_t = dy_t h_t,   df_t = r_t (h_{t-1} - i_t),   di_t = r_t (1 - f_t),   dh0 = c_0
-template <bool GATE_BF16>
+// act forms, through the activations (s = sigmoid):
+//   dzo = do o (1 - o),   dzi = di s(zi) (1 + zi (1 - s(zi))),
+//   dzf = df (f - beta)(1 - f) / (1 - beta),   dbeta = sum over batch and time of df (1 - f) / (1 - beta)
+template <bool GATE_BF16, bool ACT>
 __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
 {
-    constexpr int TS = kH1Seg;
+    constexpr int TS = ACT ? kH1SegShort : kH1SegLong, BLOCK = kH1Segs * TS;
     constexpr int GS = GATE_BF16 ? 1 : 2;
-    typedef H1Raw<GATE_BF16> Gate;
     __shared__ f32x2 sA[2][kH1Segs][32], sX[2][kH1Segs][32];      // sX: forward H, later the reverse summary
-    const int cp = threadIdx.x & 31;                             // channel pair of the workgroup's 64 channels
-    const int vs = threadIdx.x >> 5;                             // segment of the block: each half-wave walks its own
+    const int cp = threadIdx.x & 31;
+    const int vs = threadIdx.x >> 5;
     const int b = blockIdx.x / p.NCB, cb = blockIdx.x % p.NCB;
     const size_t c0 = (size_t)cb * kH1Chan + 2 * cp;
     const size_t seq = (size_t)b * p.N * p.d;
     const unsigned lane_b = 2u * (unsigned)c0;
     const int last_blk = p.NBLK - 1;
+    const f32x2 beta = ACT ? *reinterpret_cast<const f32x2*>(p.beta + c0) : f32x2{0.0f, 0.0f};
+    const f32x2 inv1mb = {1.0f / (1.0f - beta.x), 1.0f / (1.0f - beta.y)};
     // this thread's own slots of the saved states: written in the forward phase, read back in the reverse one
     float* my_carry = p.carry + ((size_t)b * p.NBLK * kH1Segs + vs) * p.d + c0;
     const size_t carry_blk = (size_t)kH1Segs * p.d;
 
-    typename Gate::type fr[TS];
+    typename H1Raw<GATE_BF16>::type fr[TS];
+    f32x2 fa[TS];
     uint32_t xr[TS], orw[TS], gr[TS];
+    // the input of a row as the recurrence uses it (act: its pre-activation stays in the register,
+    // the reverse walk needs it for the derivative)
+    auto input_of = [&](uint32_t raw) {
+        const f32x2 z = h1_cvt(raw);
+        if constexpr (ACT) return h1_silu(z);
+        else return z;
+    };
     {
         const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
@@ -239,16 +300,15 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
     // ---- forward phase: the state entering every segment ----
     f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
     for (int blk = 0; blk < p.NBLK; ++blk, ++it) {
-        const int t0 = blk * kH1Block + vs * TS;
-        const int nb = min(blk + 1, last_blk) * kH1Block;     // the last block is read again: the reverse phase starts on it
+        const int t0 = blk * BLOCK + vs * TS;
+        const int nb = min(blk + 1, last_blk) * BLOCK;     // the last block is read again: the reverse phase starts on it
         const int par = it & 1;
         const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
         f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
-            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
-            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+            const f32x2 f = h1_first_gate<GATE_BF16, ACT>(fr[t], beta, t0 + t < p.N), x = input_of(xr[t]);
             a = f32x2{a.x * f.x, a.y * f.y};
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
             const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
@@ -267,8 +327,8 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
     // ---- reverse phase ----
     {
         // o and dy of the last block; f and i of it are in place
-        const H1Rsrc rg = h1_rows_from(p.dy, seq, last_blk * kH1Block, p.N, p.d, 2),
-                     ro = h1_rows_from(p.o, seq, last_blk * kH1Block, p.N, p.d, 2);
+        const H1Rsrc rg = h1_rows_from(p.dy, seq, last_blk * BLOCK, p.N, p.d, 2),
+                     ro = h1_rows_from(p.o, seq, last_blk * BLOCK, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
 #pragma unroll
         for (int t = TS - 1; t >= 0; --t) {
@@ -279,16 +339,18 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         }
     }
     f32x2 cr = p.dhN ? *reinterpret_cast<const f32x2*>(p.dhN + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
+    f32x2 dbeta = {0.0f, 0.0f};
     for (int blk = last_blk; blk >= 0; --blk, ++it) {
-        const int t0 = blk * kH1Block + vs * TS;
+        const int t0 = blk * BLOCK + vs * TS;
         const int par = it & 1;
         const f32x2 h_in = *reinterpret_cast<const f32x2*>(my_carry + blk * carry_blk);
         // reverse summary of the segment from c = 0 at its end (rows past the end: f = 1, dy was read as 0)
         f32x2 a = {1.0f, 1.0f}, q = {0.0f, 0.0f};
 #pragma unroll
         for (int t = TS - 1; t >= 0; --t) {
-            fr[t] = t0 + t < p.N ? fr[t] : Gate::one();
-            const f32x2 f = h1_cvt(fr[t]), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
+            h1_touch_gate<GATE_BF16, ACT>(fr[t], fa[t], beta, t0 + t < p.N);
+            if constexpr (ACT) { const f32x2 s = h1_sigmoid(h1_cvt(orw[t])); orw[t] = h1_pack(s.x, s.y); }
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], false), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
             a = f32x2{a.x * f.x, a.y * f.y};
             q = f32x2{f.x * fmaf(g.x, og.x, q.x), f.y * fmaf(g.y, og.y, q.y)};
             __builtin_amdgcn_sched_barrier(0);
@@ -304,16 +366,15 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
             f32x2 h = h_in;
 #pragma unroll
             for (int t = 0; t < TS; ++t) {
-                h1_forget(fr[t]);
                 h1_forget(xr[t]);
-                const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]);
+                const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], true), x = input_of(xr[t]);
                 hp[t] = h;
                 h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         // gradients, last token first; every row is refilled with the previous block's token once consumed
-        const int pb = max(blk - 1, 0) * kH1Block, cb0 = blk * kH1Block;
+        const int pb = max(blk - 1, 0) * BLOCK, cb0 = blk * BLOCK;
         const H1Rsrc rdo = h1_rows_from(p.dout, seq, cb0, p.N, p.d, 2), rdf = h1_rows_from(p.df, seq, cb0, p.N, p.d, 2),
                      rdi = h1_rows_from(p.di, seq, cb0, p.N, p.d, 2);
         const H1Rsrc rf = h1_rows_from(p.f, seq, pb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, pb, p.N, p.d, 2),
@@ -321,18 +382,28 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         const unsigned pitch = h1_pitch(p.d);
 #pragma unroll
         for (int t = TS - 1; t >= 0; --t) {
-            h1_forget(fr[t]);
             h1_forget(xr[t]);
             h1_forget(gr[t]);
             h1_forget(orw[t]);
-            const f32x2 f = h1_cvt(fr[t]), x = h1_cvt(xr[t]), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], true), z = h1_cvt(xr[t]), g = h1_cvt(gr[t]), og = h1_cvt(orw[t]);
+            f32x2 x = z, sx = {0.0f, 0.0f};
+            if constexpr (ACT) { sx = h1_sigmoid(z); x = f32x2{z.x * sx.x, z.y * sx.y}; }
             const f32x2 e = {hp[t].x - x.x, hp[t].y - x.y};
             const f32x2 ht = {fmaf(f.x, e.x, x.x), fmaf(f.y, e.y, x.y)};
             const f32x2 r = {fmaf(g.x, og.x, c.x), fmaf(g.y, og.y, c.y)};
+            f32x2 go = {g.x * ht.x, g.y * ht.y}, gf = {r.x * e.x, r.y * e.y};
+            f32x2 gi = {r.x * (1.0f - f.x), r.y * (1.0f - f.y)};
+            if constexpr (ACT) {
+                go = f32x2{go.x * og.x * (1.0f - og.x), go.y * og.y * (1.0f - og.y)};
+                gi = f32x2{gi.x * sx.x * fmaf(z.x, 1.0f - sx.x, 1.0f), gi.y * sx.y * fmaf(z.y, 1.0f - sx.y, 1.0f)};
+                const f32x2 u = {gf.x * (1.0f - f.x) * inv1mb.x, gf.y * (1.0f - f.y) * inv1mb.y};      // df (1 - g)
+                dbeta = f32x2{dbeta.x + u.x, dbeta.y + u.y};              // rows past the end add r e = c (h - 0) times 1 - f = 0
+                gf = f32x2{u.x * (f.x - beta.x), u.y * (f.y - beta.y)};
+            }
             const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
-            h1_st(rdo, off, g.x * ht.x, g.y * ht.y);
-            h1_st(rdf, off, r.x * e.x, r.y * e.y);
-            h1_st(rdi, off, r.x * (1.0f - f.x), r.y * (1.0f - f.y));
+            h1_st(rdo, off, go.x, go.y);
+            h1_st(rdf, off, gf.x, gf.y);
+            h1_st(rdi, off, gi.x, gi.y);
             c = f32x2{f.x * r.x, f.y * r.y};
             fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
             xr[t] = h1_ld<true>(ri, off);
@@ -342,6 +413,28 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         }
     }
     if (p.dh0 && vs == 0) *reinterpret_cast<f32x2*>(p.dh0 + (size_t)b * p.d + c0) = cr;
+    if constexpr (ACT) {
+        // this sequence's share of the gradient of beta: the sixteen segments' sums, added in order
+        __syncthreads();
+        sX[0][vs][cp] = dbeta;
+        __syncthreads();
+        if (vs == 0) {
+            f32x2 t = {0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < kH1Segs; ++j) { const f32x2 u = sX[0][j][cp]; t = f32x2{t.x + u.x, t.y + u.y}; }
+            *reinterpret_cast<f32x2*>(p.dbeta_part + (size_t)b * p.d + c0) = t;
+        }
+    }
+}
+
+// grad_beta[c] = sum over the batch of the sequences' shares, in index order
+__global__ void hgrn1_reduce_beta_kernel(const float* part, float* grad_beta, int B, int d)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= d) return;
+    float s = 0.0f;
+    for (int b = 0; b < B; ++b) s += part[(size_t)b * d + c];
+    grad_beta[c] = s;
 }
 
 // N = 0: the final state is the initial one (and the gradient of the initial state that of the final one)
@@ -352,23 +445,26 @@ __global__ void hgrn1_copy_state_kernel(const float* src, float* dst, size_t n)
 }
 
 // ---- host side -----------------------------------------------------------------------------------
-static int h1_blocks(int N) { return (N + kH1Block - 1) / kH1Block; }
+static int h1_blocks(int N, int seg) { return (N + kH1Segs * seg - 1) / (kH1Segs * seg); }
 
+// saved segment states of the backward (sized for its shorter segments) and the per-sequence shares of grad_beta
+static size_t h1_carry_floats(int B, int N, int d) { return (size_t)B * h1_blocks(N, kH1SegShort) * kH1Segs * d; }
 size_t hgrn1_ws_bytes(int B, int N, int d)
 {
-    return (size_t)B * h1_blocks(N) * kH1Segs * d * sizeof(float);
+    return (h1_carry_floats(B, N, d) + (size_t)B * d) * sizeof(float);
 }
 
-static H1Params h1_params(int B, int N, int d, void* ws)
+static H1Params h1_params(int B, int N, int d, int seg, void* ws)
 {
     H1Params p = {};
-    p.B = B; p.N = N; p.d = d; p.NBLK = h1_blocks(N); p.NCB = d / kH1Chan;
+    p.B = B; p.N = N; p.d = d; p.NBLK = h1_blocks(N, seg); p.NCB = d / kH1Chan;
     p.carry = static_cast<float*>(ws);
+    p.dbeta_part = p.carry + h1_carry_floats(B, N, d);
     return p;
 }
 
 hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
-                            const float* h0, void* y, float* hN, void* ws, hipStream_t stream)
+                            const float* beta, const float* h0, void* y, float* hN, void* ws, hipStream_t stream)
 {
     if ((size_t)B * d == 0) return hipSuccess;
     if (N == 0) {
@@ -376,29 +472,35 @@ hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, 
                                    stream, h0, hN, (size_t)B * d);
         return hipGetLastError();
     }
-    H1Params p = h1_params(B, N, d, ws);
-    p.f = f; p.i = i; p.o = o; p.h0 = h0; p.y = y; p.hN = hN;
+    H1Params p = h1_params(B, N, d, kH1SegLong, ws);
+    p.f = f; p.i = i; p.o = o; p.beta = beta; p.h0 = h0; p.y = y; p.hN = hN;
     const dim3 grid((unsigned)(B * p.NCB));
-    if (gate_bf16) hipLaunchKernelGGL(hgrn1_fwd_kernel<true>, grid, dim3(kH1Threads), 0, stream, p);
-    else hipLaunchKernelGGL(hgrn1_fwd_kernel<false>, grid, dim3(kH1Threads), 0, stream, p);
+    auto kern = beta ? (gate_bf16 ? hgrn1_fwd_kernel<true, true> : hgrn1_fwd_kernel<false, true>)
+                     : (gate_bf16 ? hgrn1_fwd_kernel<true, false> : hgrn1_fwd_kernel<false, false>);
+    hipLaunchKernelGGL(kern, grid, dim3(kH1Threads), 0, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
-                            const float* h0, const void* dy, const float* dhN, void* df, void* di, void* dout,
-                            float* dh0, void* ws, hipStream_t stream)
+                            const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
+                            void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream)
 {
     if ((size_t)B * d == 0) return hipSuccess;
     if (N == 0) {
         if (dh0) hipLaunchKernelGGL(hgrn1_copy_state_kernel, dim3((unsigned)(((size_t)B * d + 255) / 256)), dim3(256), 0,
                                     stream, dhN, dh0, (size_t)B * d);
+        if (beta && dbeta) hipLaunchKernelGGL(hgrn1_reduce_beta_kernel, dim3((d + 255) / 256), dim3(256), 0, stream,
+                                              static_cast<const float*>(nullptr), dbeta, 0, d);
         return hipGetLastError();
     }
-    H1Params p = h1_params(B, N, d, ws);
-    p.f = f; p.i = i; p.o = o; p.dy = dy; p.h0 = h0; p.dhN = dhN; p.df = df; p.di = di; p.dout = dout; p.dh0 = dh0;
+    H1Params p = h1_params(B, N, d, beta ? kH1SegShort : kH1SegLong, ws);
+    p.f = f; p.i = i; p.o = o; p.beta = beta; p.dy = dy; p.h0 = h0; p.dhN = dhN; p.df = df; p.di = di; p.dout = dout; p.dh0 = dh0;
     const dim3 grid((unsigned)(B * p.NCB));
-    if (gate_bf16) hipLaunchKernelGGL(hgrn1_bwd_kernel<true>, grid, dim3(kH1Threads), 0, stream, p);
-    else hipLaunchKernelGGL(hgrn1_bwd_kernel<false>, grid, dim3(kH1Threads), 0, stream, p);
+    auto kern = beta ? (gate_bf16 ? hgrn1_bwd_kernel<true, true> : hgrn1_bwd_kernel<false, true>)
+                     : (gate_bf16 ? hgrn1_bwd_kernel<true, false> : hgrn1_bwd_kernel<false, false>);
+    hipLaunchKernelGGL(kern, grid, dim3(kH1Threads), 0, stream, p);
+    if (beta && dbeta)
+        hipLaunchKernelGGL(hgrn1_reduce_beta_kernel, dim3((d + 255) / 256), dim3(256), 0, stream, p.dbeta_part, dbeta, B, d);
     return hipGetLastError();
 }
 

@@ -96,12 +96,14 @@ hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, con
 
 // HGRN1, the element-wise recurrence h_t = f_t h_{t-1} + (1 - f_t) i_t, y_t = h_t o_t (paper Eq. 1),
 // on [B][N][d] bf16 tensors (d a multiple of 128), states [B][d] fp32; `ws` holds hgrn1_ws_bytes().
+// With `beta` ([d] fp32) set, f, i, o are the pre-activations of Eq. 1 and the gate gets the lower
+// bound of Eq. 2; the backward then returns the gradients of the pre-activations and of beta.
 size_t hgrn1_ws_bytes(int B, int N, int d);
 hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
-                            const float* h0, void* y, float* hN, void* ws, hipStream_t stream);
+                            const float* beta, const float* h0, void* y, float* hN, void* ws, hipStream_t stream);
 hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
-                            const float* h0, const void* dy, const float* dhN, void* df, void* di, void* dout,
-                            float* dh0, void* ws, hipStream_t stream);
+                            const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
+                            void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream);
 
 // Bytes of one per-chunk state set in the workspace.
 size_t state_ws_bytes(const SeqDims& d);

@@ -162,9 +162,10 @@ def test_layout_field():
 def test_hgrn1_workspace_and_error_codes():
     lib = binding.lib()
     fwd_d_limit = lambda: lib.hgrn1_fwd(1, 4, (1 << 20) + 128, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1 << 40, None)
-    assert binding.hgrn1_workspace_bytes(8, 2048, 2048) == 8 * 64 * 2048 * 4     # one state per 32-token segment
-    assert binding.hgrn1_workspace_bytes(1, 257, 128) == 16 * 128 * 4             # whole 512-token blocks
-    assert binding.hgrn1_workspace_bytes(1, 513, 128) == 2 * 16 * 128 * 4
+    # one saved state per 16-token segment (whole 256-token blocks) plus one row of grad_beta shares per sequence
+    assert binding.hgrn1_workspace_bytes(8, 2048, 2048) == (8 * 128 * 2048 + 8 * 2048) * 4
+    assert binding.hgrn1_workspace_bytes(1, 257, 128) == (2 * 16 * 128 + 128) * 4
+    assert binding.hgrn1_workspace_bytes(1, 513, 128) == (3 * 16 * 128 + 128) * 4
     assert fwd_d_limit() == E_SHAPE
     assert binding.hgrn1_workspace_bytes(8, 2048, 100) == 0
     big = 1 << 40
@@ -181,6 +182,17 @@ def test_hgrn1_workspace_and_error_codes():
     assert bwd(d=64) == E_UNSUP
     assert bwd(gf=None) == E_NULL
     assert bwd(n=16) == E_WS
+    # the forms that take the pre-activations of Eq. 1 and the lower bounds of Eq. 2
+    fwd_act = lambda d=256, beta=FAKE, n=big: lib.hgrn1_fwd_act(2, 100, d, 1, 1, FAKE, FAKE, FAKE, beta, None, FAKE, None,
+                                                                FAKE_WS, n, None)
+    assert fwd_act(beta=None) == E_NULL
+    assert fwd_act(d=100) == E_UNSUP
+    assert fwd_act(n=16) == E_WS
+    bwd_act = lambda beta=FAKE, gb=FAKE, n=big: lib.hgrn1_bwd_act(2, 100, 256, 1, 1, FAKE, FAKE, FAKE, beta, None, FAKE, None,
+                                                                  FAKE, FAKE, FAKE, gb, None, FAKE_WS, n, None)
+    assert bwd_act(beta=None) == E_NULL
+    assert bwd_act(gb=None) == E_NULL
+    assert bwd_act(n=16) == E_WS
 
 
 def test_varlen_workspace_and_error_codes():

@@ -82,3 +82,63 @@ def test_hgrn1_layer_shape(lb):
 def test_hgrn1_long_sequence_gates_near_one():
     print("\n[hgrn1] B=2 N=16384 d=2048, f in [0.99, 1], fp32 gates", flush=True)
     run(*make(5500, 2, 16384, 2048, lb=0.99, gate_dtype="f32"), gate_dtype="f32")
+
+
+# ------------------------------------------------------------------ activations formed inside the kernels
+def make_act(seed, B, N, d, gate_dtype="bf16", beta_max=0.9):
+    """Pre-activations zf, zi, zo ~ 1.5 N(0,1), rounded once to their storage type; beta ~ U(0, beta_max)."""
+    rng = np.random.default_rng(seed)
+    mk = lambda: synth.bf16_round((1.5 * rng.standard_normal((B, N, d), dtype=np.float32)).astype(np.float32))
+    zf = (1.5 * rng.standard_normal((B, N, d), dtype=np.float32)).astype(np.float32)
+    zf = synth.bf16_round(zf) if gate_dtype == "bf16" else zf
+    zi, zo = mk(), mk()
+    beta = rng.uniform(0.0, beta_max, size=d).astype(np.float32)
+    dy = synth.bf16_round(rng.standard_normal((B, N, d), dtype=np.float32))
+    h0 = rng.standard_normal((B, d)).astype(np.float32)
+    dhN = rng.standard_normal((B, d)).astype(np.float32)
+    return zf, zi, zo, beta, dy, h0, dhN
+
+
+def run_act(zf, zi, zo, beta, dy, h0, dhN, gate_dtype="bf16"):
+    zfd, zid, zod, dyd = dev(zf, gate_dtype), dev(zi, "bf16"), dev(zo, "bf16"), dev(dy, "bf16")
+    bd = torch.from_numpy(beta).cuda()
+    h0d = None if h0 is None else dev(h0)
+    dhNd = None if dhN is None else dev(dhN)
+    y, hN = binding.hgrn1_fwd_act(zfd, zid, zod, bd, h0d)
+    gf, gi, go, gb, gh0 = binding.hgrn1_bwd_act(zfd, zid, zod, bd, dyd, h0d, dhNd, want_grad_h0=True)
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    ry, rh = oracle.hgrn1_fwd_act(zf, zi, zo, beta, h0)
+    check("y", host(y), ry, tol)
+    check("hN", host(hN), rh, tol)           # i is rounded to bf16 once it is formed
+    rf, ri, ro, rb, rh0 = oracle.hgrn1_bwd_act(zf, zi, zo, beta, dy, h0, dhN)
+    check("dzf", host(gf), rf, tol)
+    check("dzi", host(gi), ri, tol)
+    check("dzo", host(go), ro, tol)
+    check("dbeta", host(gb), rb, tol)
+    check("dh0", host(gh0), rh0, tol)
+
+
+@pytest.mark.parametrize("d", [128, 384])
+@pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
+def test_hgrn1_act_ragged(d, gate_dtype):
+    print("\n[hgrn1 act] B=3 N=203 d=%d gate=%s" % (d, gate_dtype), flush=True)
+    run_act(*make_act(5600 + d, 3, 203, d, gate_dtype=gate_dtype), gate_dtype=gate_dtype)
+
+
+@pytest.mark.parametrize("N", [0, 1, 15, 16, 17, 255, 256, 257, 511, 512, 513, 800])
+def test_hgrn1_act_edge_lengths(N):
+    print("\n[hgrn1 act] edge N=%d" % N, flush=True)
+    run_act(*make_act(5700 + N, 2, N, 128))
+
+
+def test_hgrn1_act_no_states_and_zero_bound():
+    zf, zi, zo, beta, dy, _, _ = make_act(5800, 2, 100, 256)
+    beta[:] = 0.0                                     # the first layer: plain sigmoid gate
+    print("\n[hgrn1 act] no h0 / grad_hN, beta = 0", flush=True)
+    run_act(zf, zi, zo, beta, dy, None, None)
+
+
+def test_hgrn1_act_layer_shape():
+    print("\n[hgrn1 act] B=8 N=2048 d=2048", flush=True)
+    run_act(*make_act(5900, 8, 2048, 2048))
