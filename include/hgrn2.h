@@ -146,6 +146,15 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream);
 
 /*
+ * Decode step with the gate of Eq. 2 formed inside the kernel: z_t [B][H][dk] (gate_dtype) holds
+ * the pre-activations of this token's forget gate, beta [H][dk] fp32 the layer's lower bounds.
+ * Everything else as for hgrn2_step.
+ */
+int hgrn2_step_gated(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+                     const void* q_t, const void* z_t, const float* beta, const void* v_t, float* state, void* o_t,
+                     void* hip_stream);
+
+/*
  * Variable-length batches: shape->B sequences of different lengths packed back to back along the
  * token axis, as training on packed documents and serving ragged prefill batches produce them.
  * The recurrence of Eq. 3 (Section 3.2) restarts at every sequence boundary: sequence b starts

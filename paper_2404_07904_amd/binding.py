@@ -18,7 +18,7 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
+           "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.hgrn1_bwd_act.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_step_gated.restype = ctypes.c_int
+        L.hgrn2_step_gated.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_state_sweep.restype = ctypes.c_int
         L.hgrn2_state_sweep.argtypes = [sp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_fwd_readout.restype = ctypes.c_int
@@ -358,6 +360,22 @@ def hgrn2_step(q_t, f_t, v_t, state, o_t=None):
                           _ptr(o_t), _stream())
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_step")
+    return o_t
+
+
+def hgrn2_step_gated(q_t, z_t, beta, v_t, state, o_t=None):
+    """One decode step from the gate's pre-activations z_t [B,H,dk] and the layer's lower bounds
+    beta [H,dk] fp32 (Eq. 2); `state` is updated in place.  Returns o_t [B,H,dv]."""
+    B, H, dk = q_t.shape
+    dv = v_t.shape[-1]
+    assert state.dtype == torch.float32 and tuple(state.shape) == (B, H, dk, dv)
+    assert beta.dtype == torch.float32 and tuple(beta.shape) == (H, dk)
+    if o_t is None:
+        o_t = torch.empty_like(v_t)
+    rc = lib().hgrn2_step_gated(B, H, dk, dv, _dt(q_t), _dt(z_t), _ptr(q_t), _ptr(z_t), _ptr(beta), _ptr(v_t),
+                                _ptr(state), _ptr(o_t), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_step_gated")
     return o_t
 
 

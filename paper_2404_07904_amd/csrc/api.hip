@@ -260,19 +260,33 @@ int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip
     return HGRN2_OK;
 }
 
-int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
-               const void* q_t, const void* f_t, const void* v_t, float* state, void* o_t, void* hip_stream)
+static int step_impl(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+                     const void* q_t, const void* f_t, const float* beta, bool gated, const void* v_t, float* state,
+                     void* o_t, void* hip_stream)
 {
     if (B < 0 || H < 0 || dk <= 0 || dv <= 0) return HGRN2_ERR_SHAPE;
     if (!dtype_ok(io_dtype) || !dtype_ok(gate_dtype)) return HGRN2_ERR_SHAPE;
     const long long bh = (long long)B * H;
     if (bh > INT_MAX / 2) return HGRN2_ERR_SHAPE;
     if (!dim_ok(dk) || !dim_ok(dv)) return HGRN2_ERR_UNSUPPORTED;
-    if (bh > 0 && (!q_t || !f_t || !v_t || !state || !o_t)) return HGRN2_ERR_NULL;
+    if (bh > 0 && (!q_t || !f_t || !v_t || !state || !o_t || (gated && !beta))) return HGRN2_ERR_NULL;
     if (launch_step((int)bh, dk, dv, io_dtype == HGRN2_BF16, gate_dtype == HGRN2_BF16, q_t, f_t, v_t, state, o_t,
-                    static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+                    gated ? beta : nullptr, H > 0 ? H : 1, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;
+}
+
+int hgrn2_step(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+               const void* q_t, const void* f_t, const void* v_t, float* state, void* o_t, void* hip_stream)
+{
+    return step_impl(B, H, dk, dv, io_dtype, gate_dtype, q_t, f_t, nullptr, false, v_t, state, o_t, hip_stream);
+}
+
+int hgrn2_step_gated(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dtype, int32_t gate_dtype,
+                     const void* q_t, const void* z_t, const float* beta, const void* v_t, float* state, void* o_t,
+                     void* hip_stream)
+{
+    return step_impl(B, H, dk, dv, io_dtype, gate_dtype, q_t, z_t, beta, true, v_t, state, o_t, hip_stream);
 }
 
 int hgrn2_state_sweep(const hgrn2_shape* shape, int32_t mode, const void* q, const void* f, const void* b_src,

@@ -90,9 +90,9 @@ hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, fl
 // layer axis minus its first row.
 hipError_t launch_cumax(int L, int d, const float* gamma, float* beta, hipStream_t stream);
 
-// Decode step.
+// Decode step.  With `beta` ([H][dk] fp32) set, the gate tensor holds the pre-activation of Eq. 2.
 hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, const void* q, const void* f,
-                       const void* v, float* state, void* o, hipStream_t stream);
+                       const void* v, float* state, void* o, const float* beta, int H, hipStream_t stream);
 
 // HGRN1, the element-wise recurrence h_t = f_t h_{t-1} + (1 - f_t) i_t, y_t = h_t o_t (paper Eq. 1),
 // on [B][N][d] bf16 tensors (d a multiple of 128), states [B][d] fp32; `ws` holds hgrn1_ws_bytes().

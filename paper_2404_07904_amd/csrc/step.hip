@@ -11,7 +11,8 @@ namespace hgrn2 {
 template <typename T, int DK, int DV>
 __global__ __launch_bounds__(kThreads) void step_kernel(const T* __restrict__ q, const void* __restrict__ f,
                                                         const T* __restrict__ v, float* __restrict__ state,
-                                                        T* __restrict__ o, int gate_bf16)
+                                                        T* __restrict__ o, int gate_bf16,
+                                                        const float* __restrict__ beta, int H)
 {
     constexpr int CG = DV / 4;               // 16-byte column groups per row
     constexpr int RG = kThreads / CG;        // row groups
@@ -22,7 +23,11 @@ __global__ __launch_bounds__(kThreads) void step_kernel(const T* __restrict__ q,
     const int bh = blockIdx.x, tid = threadIdx.x;
     if (tid < DK / 2) {
         const f32x2 qq = load_pair_t<T>(q, (size_t)bh * DK + 2 * tid);
-        const f32x2 ff = load_pair(f, (size_t)bh * DK + 2 * tid, gate_bf16 != 0);
+        f32x2 ff = load_pair(f, (size_t)bh * DK + 2 * tid, gate_bf16 != 0);
+        if (beta) {      // the gate tensor holds the pre-activation: f = beta + (1 - beta) sigmoid(z), Eq. 2
+            const f32x2 bb = *reinterpret_cast<const f32x2*>(beta + (size_t)(bh % H) * DK + 2 * tid);
+            ff = f32x2{lower_bounded_gate(ff.x, bb.x), lower_bounded_gate(ff.y, bb.y)};
+        }
         sq[2 * tid] = qq.x; sq[2 * tid + 1] = qq.y;
         sf[2 * tid] = ff.x; sf[2 * tid + 1] = ff.y;
     }
@@ -59,31 +64,31 @@ __global__ __launch_bounds__(kThreads) void step_kernel(const T* __restrict__ q,
 
 template <typename T>
 static hipError_t launch_t(int BH, int dk, int dv, bool gate_bf16, const void* q, const void* f, const void* v,
-                           float* state, void* o, hipStream_t stream)
+                           float* state, void* o, const float* beta, int H, hipStream_t stream)
 {
     const T* qq = static_cast<const T*>(q);
     const T* vv = static_cast<const T*>(v);
     T* oo = static_cast<T*>(o);
     const int gb = gate_bf16 ? 1 : 0;
     if (dk == 128 && dv == 128)
-        hipLaunchKernelGGL((step_kernel<T, 128, 128>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb);
+        hipLaunchKernelGGL((step_kernel<T, 128, 128>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb, beta, H);
     else if (dk == 64 && dv == 64)
-        hipLaunchKernelGGL((step_kernel<T, 64, 64>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb);
+        hipLaunchKernelGGL((step_kernel<T, 64, 64>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb, beta, H);
     else if (dk == 128 && dv == 64)
-        hipLaunchKernelGGL((step_kernel<T, 128, 64>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb);
+        hipLaunchKernelGGL((step_kernel<T, 128, 64>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb, beta, H);
     else if (dk == 64 && dv == 128)
-        hipLaunchKernelGGL((step_kernel<T, 64, 128>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb);
+        hipLaunchKernelGGL((step_kernel<T, 64, 128>), dim3(BH), dim3(kThreads), 0, stream, qq, f, vv, state, oo, gb, beta, H);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
 hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, const void* q, const void* f,
-                       const void* v, float* state, void* o, hipStream_t stream)
+                       const void* v, float* state, void* o, const float* beta, int H, hipStream_t stream)
 {
     if (BH == 0) return hipSuccess;
-    return io_bf16 ? launch_t<__bf16>(BH, dk, dv, gate_bf16, q, f, v, state, o, stream)
-                   : launch_t<float>(BH, dk, dv, gate_bf16, q, f, v, state, o, stream);
+    return io_bf16 ? launch_t<__bf16>(BH, dk, dv, gate_bf16, q, f, v, state, o, beta, H, stream)
+                   : launch_t<float>(BH, dk, dv, gate_bf16, q, f, v, state, o, beta, H, stream);
 }
 
 }   // namespace hgrn2

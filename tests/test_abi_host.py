@@ -100,6 +100,10 @@ def test_step_argument_errors():
     assert step(1, 1, 48, 64, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_UNSUP
     assert step(1, 1, 64, 64, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None) == E_NULL
     assert step(0, 4, 64, 64, 1, 1, None, None, None, None, None, None) == OK
+    gated = binding.lib().hgrn2_step_gated
+    assert gated(1, 1, 64, 64, 1, 1, FAKE, FAKE, None, FAKE, FAKE, FAKE, None) == E_NULL       # beta missing
+    assert gated(1, 1, 48, 64, 1, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == E_UNSUP
+    assert gated(0, 4, 64, 64, 1, 1, None, None, None, None, None, None, None) == OK
 
 
 def test_stage_entry_point_errors():

@@ -106,3 +106,31 @@ def test_cumax_parity():
     assert float(beta[0].abs().max()) == 0.0
     uni = binding.hgrn2_cumax(torch.full((24, 64), 0.25, device="cuda"))
     check("uniform", host(uni), np.broadcast_to((np.arange(24) / 24.0)[:, None], (24, 64)), 1e-6)
+
+
+@pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (64, 128), (128, 64)])
+@pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
+def test_gated_decode_steps(dk, dv, gate_dtype):
+    """Twelve consecutive decode steps from the gate's pre-activations, in place, against the oracle's
+    step fed with the gate of Eq. 2; the state after the last step is compared too (fp32, so to 1e-4
+    of its largest entry after twelve updates is too tight for exp/rcp approximations: 1e-3)."""
+    B, H, T = 3, 5, 12
+    print("\n[gated step] dk=%d dv=%d gate=%s" % (dk, dv, gate_dtype), flush=True)
+    rng = np.random.default_rng(7700 + dk + 2 * dv)
+    q = synth.bf16_round(rng.standard_normal((T, B, H, dk), dtype=np.float32))
+    v = synth.bf16_round(rng.standard_normal((T, B, H, dv), dtype=np.float32))
+    z = (1.5 * rng.standard_normal((T, B, H, dk), dtype=np.float32)).astype(np.float32)
+    z = synth.bf16_round(z) if gate_dtype == "bf16" else z
+    beta = rng.uniform(0.0, 0.9, size=(H, dk)).astype(np.float32)
+    s0 = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    qd, vd, zd = dev(q, "bf16"), dev(v, "bf16"), dev(z, gate_dtype)
+    bd = torch.from_numpy(beta).cuda()
+    st = dev(s0)
+    ref_state = s0.astype(np.float64).copy()
+    for t in range(T):
+        o = binding.hgrn2_step_gated(qd[t], zd[t], bd, vd[t], st)
+        f_t = oracle.gate(z[t][:, :, None, :], beta)[:, :, 0, :]
+        ro = oracle.step(q[t], f_t, v[t], ref_state)
+        torch.cuda.synchronize()
+        check("o[%d]" % t, host(o), ro, TOL["bf16"])
+    check("state", host(st), ref_state, 1e-3)
