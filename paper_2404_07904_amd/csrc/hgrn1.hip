@@ -29,6 +29,8 @@
 // projections) and the layer's lower bounds of Eq. 2, and form
 //     f = beta + (1 - beta) sigmoid(zf),   i = SiLU(zi),   o = sigmoid(zo)
 // when a register row is first used: the layer never writes f, i or o to memory.
+#include <type_traits>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -298,12 +300,15 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
     int it = 0;       // LDS buffer parity runs over both phases
 
     // ---- forward phase: the state entering every segment ----
+    // The last block is not followed by a refill: its gates and inputs stay in their registers,
+    // which is where the reverse phase starts.
     f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
-    for (int blk = 0; blk < p.NBLK; ++blk, ++it) {
+    auto forward_block = [&](int blk, auto refill_tag) {
+        constexpr bool REFILL = decltype(refill_tag)::value;
         const int t0 = blk * BLOCK + vs * TS;
-        const int nb = min(blk + 1, last_blk) * BLOCK;     // the last block is read again: the reverse phase starts on it
         const int par = it & 1;
-        const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2);
+        const H1Rsrc rf = h1_rows_from(p.f, seq, (blk + 1) * BLOCK, p.N, p.d, 2 * GS),
+                     ri = h1_rows_from(p.i, seq, (blk + 1) * BLOCK, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
         f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
 #pragma unroll
@@ -311,9 +316,11 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
             const f32x2 f = h1_first_gate<GATE_BF16, ACT>(fr[t], beta, t0 + t < p.N), x = input_of(xr[t]);
             a = f32x2{a.x * f.x, a.y * f.y};
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
-            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
-            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
-            xr[t] = h1_ld<true>(ri, off);
+            if constexpr (REFILL) {
+                const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
+                fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+                xr[t] = h1_ld<true>(ri, off);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         sA[par][vs][cp] = a;
@@ -322,7 +329,10 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         f32x2 mine;
         carry = h1_chain<true>(sA[par], sX[par], vs, cp, carry, mine);
         *reinterpret_cast<f32x2*>(my_carry + blk * carry_blk) = mine;
-    }
+        ++it;
+    };
+    for (int blk = 0; blk < last_blk; ++blk) forward_block(blk, std::true_type{});
+    forward_block(last_blk, std::false_type{});
 
     // ---- reverse phase ----
     {
