@@ -81,7 +81,7 @@ typedef __amdgpu_buffer_rsrc_t H1Rsrc;
 
 __device__ __forceinline__ H1Rsrc h1_rows_from(const void* tensor, size_t seq_elem, int tok0, int N, int d, int esize)
 {
-    const int first = min(max(tok0, 0), N);
+    const int first = min((unsigned)tok0, (unsigned)N);        // a negative tok0 gives an empty range
     const unsigned long long bytes = (unsigned long long)(N - first) * d * esize;
     const char* base = static_cast<const char*>(tensor) + (seq_elem + (size_t)first * d) * esize;
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, (int)(unsigned)min(bytes, 0xfffffff8ull), 0x00020000);
@@ -384,7 +384,8 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
             }
         }
         // gradients, last token first; every row is refilled with the previous block's token once consumed
-        const int pb = max(blk - 1, 0) * BLOCK, cb0 = blk * BLOCK;
+        // block 0 has nothing before it: a negative first token makes its refills address an empty range
+        const int pb = (blk - 1) * BLOCK, cb0 = blk * BLOCK;
         const H1Rsrc rdo = h1_rows_from(p.dout, seq, cb0, p.N, p.d, 2), rdf = h1_rows_from(p.df, seq, cb0, p.N, p.d, 2),
                      rdi = h1_rows_from(p.di, seq, cb0, p.N, p.d, 2);
         const H1Rsrc rf = h1_rows_from(p.f, seq, pb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, pb, p.N, p.d, 2),
