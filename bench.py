@@ -35,7 +35,8 @@ CHUNK = 64
 # HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each
 # scaled by what the same counter reads for a plain copy kernel of known size; bytes per launch at
 # the benchmark workload.  None until measured; see profiles/.
-MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 738.9e6}    # 537.6 MB read + 201.3 MB written (profiles/pmc_hbm_traffic_config2.md)
+MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 739.0e6,     # 537.7 MB read + 201.3 MB written (profiles/pmc_hbm_traffic_config2.md)
+                          "hgrn1_fwd": 268.6e6, "hgrn1_bwd": 578.9e6}   # profiles/hgrn1_kernel_trace_and_traffic_b8_n2048_d2048.md
 
 
 def parse():
@@ -280,9 +281,11 @@ def main():
             "fwd_act_us": round(tfa * 1e6, 1), "bwd_act_us": round(tba * 1e6, 1),
             "tokens_per_s_fwd_bwd": round(tokens / (tf + tb), 1),
             "roofline_fwd": {"bound": "hbm", "achieved": round(4 * e1 / tf / 1e9, 1), "peak": HBM_PEAK_GBS,
-                             "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4), "traffic": None},
+                             "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4),
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_fwd")},
             "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tb / 1e9, 1), "peak": HBM_PEAK_GBS,
-                             "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}}
+                             "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4),
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_bwd")}}
         del sets1, ws1, y1
 
     # ---- variable-length batch: the same 16384 tokens per head, packed as documents of mixed length ----

@@ -169,18 +169,21 @@ int hgrn2_step_gated(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dt
  *   q, f, v, o, grad_*   device [T][H][d]    h0, hT, grad_hT, grad_h0   device fp32 [B][H][dk][dv]
  *   workspace       hgrn2_fwd_varlen_workspace_bytes / hgrn2_bwd_varlen_workspace_bytes bytes
  *                   (sized for the worst split of the T tokens into B sequences), 256-byte aligned
- * The gates are given (the forms that build the gate of Eq. 2 take equal-length batches).
+ *   beta            NULL: `f` holds the gates.  Else device fp32 [H][dk], the layer's lower bounds:
+ *                   `f` then holds the gates' pre-activations z and the gate of Eq. 2 is formed in the
+ *                   kernels, grad_f receives dL/dz and grad_beta (device fp32 [H][dk], required then)
+ *                   dL/dbeta, as for hgrn2_fwd_gated / hgrn2_bwd_gated.
  * Same status codes, stream semantics and numerical contract as hgrn2_fwd / hgrn2_bwd.
  */
 size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape);
 size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape);
 int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
-                     void* hip_stream);
+                     const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
 int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
-                     void* grad_f, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
-                     void* hip_stream);
+                     const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                     void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                     size_t workspace_bytes, void* hip_stream);
 
 /*
  * HGRN1, the element-wise gated linear recurrence the paper starts from (Section 2, Eq. 1, with the

@@ -68,9 +68,9 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_bwd_varlen_workspace_bytes.restype = sz
         L.hgrn2_bwd_varlen_workspace_bytes.argtypes = [sp]
         L.hgrn2_fwd_varlen.restype = ctypes.c_int
-        L.hgrn2_fwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_fwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_bwd_varlen.restype = ctypes.c_int
-        L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_cumax.restype = ctypes.c_int
         L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
         L.hgrn1_workspace_bytes.restype = sz
@@ -239,9 +239,10 @@ def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_bwd_varlen_workspace_bytes(ctypes.byref(shape)))
 
 
-def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, o=None, hT=None, workspace=None):
+def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o=None, hT=None, workspace=None):
     """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
-    int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv]."""
+    int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv].  With beta [H,dk] fp32, f holds the
+    gates' pre-activations (Eq. 2)."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
     if o is None:
@@ -249,16 +250,17 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, want_hT=True, o=None, hT=N
     if hT is None and want_hT:
         hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
     ws = _workspace(hgrn2_fwd_varlen_workspace_bytes(shape), q.device, workspace)
-    rc = lib().hgrn2_fwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(o),
-                                _ptr(hT), _ptr(ws), ws.numel(), _stream())
+    rc = lib().hgrn2_fwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0),
+                                _ptr(o), _ptr(hT), _ptr(ws), ws.numel(), _stream())
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_fwd_varlen")
     return o, hT
 
 
-def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
-                     grad_q=None, grad_f=None, grad_v=None):
-    """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis."""
+def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta=None, want_grad_h0=False,
+                     workspace=None, grad_q=None, grad_f=None, grad_v=None):
+    """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis; with beta also
+    grad_beta (returned as a fifth value), and grad_f is then the gradient of the pre-activations."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
     gq = torch.empty_like(q) if grad_q is None else grad_q
@@ -266,13 +268,14 @@ def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, want
     gv = torch.empty_like(v) if grad_v is None else grad_v
     gh0 = (torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
            if want_grad_h0 else None)
+    gb = torch.empty((shape.H, shape.dk), dtype=torch.float32, device=q.device) if beta is not None else None
     ws = _workspace(hgrn2_bwd_varlen_workspace_bytes(shape), q.device, workspace)
-    rc = lib().hgrn2_bwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(v), _ptr(h0),
-                                _ptr(grad_o), _ptr(grad_hT), _ptr(gq), _ptr(gf), _ptr(gv), _ptr(gh0), _ptr(ws),
+    rc = lib().hgrn2_bwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0),
+                                _ptr(grad_o), _ptr(grad_hT), _ptr(gq), _ptr(gf), _ptr(gb), _ptr(gv), _ptr(gh0), _ptr(ws),
                                 ws.numel(), _stream())
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd_varlen")
-    return gq, gf, gv, gh0
+    return (gq, gf, gv, gh0) if beta is None else (gq, gf, gv, gh0, gb)
 
 
 def hgrn2_cumax(gamma):

@@ -193,16 +193,17 @@ size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
     if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
     static int dummy_table;
     d.lay.vl = &dummy_table;
-    return round256(varlen_table_bytes(shape->B)) + 2 * round256(state_ws_bytes(d));
+    return round256(varlen_table_bytes(shape->B)) + 2 * round256(state_ws_bytes(d)) + round256(beta_partials_bytes(d));
 }
 
 int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
-                     void* hip_stream)
+                     const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
+                     size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape_varlen(shape, false, &d);
     if (rc != HGRN2_OK) return rc;
+    d.beta = beta;
     if (d.BH == 0) return HGRN2_OK;
     const bool has_tokens = d.N > 0;
     if (!cu_seqlens || (has_tokens && (!q || !f || !v || !o))) return HGRN2_ERR_NULL;
@@ -222,32 +223,42 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
 }
 
 int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
-                     void* grad_f, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
-                     void* hip_stream)
+                     const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                     void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                     size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape_varlen(shape, true, &d);
     if (rc != HGRN2_OK) return rc;
-    if (d.BH == 0) return HGRN2_OK;
+    d.beta = beta;
+    if (beta && !grad_beta && (size_t)shape->H * d.dk > 0) return HGRN2_ERR_NULL;
+    if (d.BH == 0) {
+        // no sequences: nothing contributes to the gradient of beta
+        if (beta && (size_t)shape->H * d.dk > 0 &&
+            hipMemsetAsync(grad_beta, 0, (size_t)shape->H * d.dk * sizeof(float), static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        return HGRN2_OK;
+    }
     const bool has_tokens = d.N > 0;
     if (!cu_seqlens || (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)))
         return HGRN2_ERR_NULL;
     const size_t need = hgrn2_bwd_varlen_workspace_bytes(shape);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
-    if (!has_tokens && !grad_h0) return HGRN2_OK;
+    if (!has_tokens && !grad_h0 && !beta) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int* table = static_cast<int*>(workspace);
     d.lay.vl = table;
     const size_t one = round256(state_ws_bytes(d));
     void* ws_s = static_cast<char*>(workspace) + round256(varlen_table_bytes(shape->B));
     void* ws_ds = static_cast<char*>(ws_s) + one;
+    float* ws_part = beta ? reinterpret_cast<float*>(static_cast<char*>(ws_ds) + one) : nullptr;
     if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     if (has_tokens &&
-        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, nullptr, stream) != hipSuccess)
+        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
+    if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
 

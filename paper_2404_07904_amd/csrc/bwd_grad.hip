@@ -603,15 +603,22 @@ size_t beta_partials_bytes(const SeqDims& d)
 // (coalesced across the channels) and the 16 group sums are added in order.
 constexpr int kRedGroups = 16;
 __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* grad_beta, int B,
-                                                                      int H, int NC, int dk)
+                                                                      int H, int NC, int dk, const int* vl)
 {
     __shared__ float part[kRedGroups][64];
     const int h = blockIdx.x / (dk / 64), a = 64 * (blockIdx.x % (dk / 64)) + (threadIdx.x & 63);
     const int grp = threadIdx.x >> 6;
-    const int rows = NC * kBwdWaves;          // partial rows of one (batch, head)
     float s = 0.0f;
     for (int b = 0; b < B; ++b) {
-        const float* pp = partials + ((size_t)(b * H + h) * rows) * dk + a;
+        // partial rows of (batch, head): kBwdWaves per chunk, the chunks of a sequence and head together
+        size_t first = (size_t)(b * H + h) * NC;
+        int nc = NC;
+        if (vl) {
+            nc = (vl[B + 1 + b] + kChunk - 1) / kChunk;
+            first = (size_t)vl[2 * (B + 1) + b] * H + (size_t)h * nc;
+        }
+        const int rows = nc * kBwdWaves;
+        const float* pp = partials + first * kBwdWaves * dk + a;
 #pragma unroll 8
         for (int i = grp; i < rows; i += kRedGroups) s += pp[(size_t)i * dk];
     }
@@ -630,7 +637,7 @@ hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, fl
     if (d.H * d.dk == 0) return hipSuccess;
     const int B = d.BH / d.H;
     hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64)), dim3(64 * kRedGroups), 0, stream, beta_partials,
-                       grad_beta, B, d.H, d.NC, d.dk);
+                       grad_beta, B, d.H, d.NC, d.dk, d.lay.vl);
     return hipGetLastError();
 }
 

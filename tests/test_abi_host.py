@@ -205,11 +205,12 @@ def test_varlen_workspace_and_error_codes():
     table = 256                                              # 4 * 7 ints, rounded up
     states = (1000 // 64 + 6) * 3 * 64 * 64 * 2              # worst split of 1000 tokens into 6 sequences
     assert binding.hgrn2_fwd_varlen_workspace_bytes(s) == table + states
-    assert binding.hgrn2_bwd_varlen_workspace_bytes(s) == table + 2 * states
+    partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4             # per-wave shares of grad_beta of every chunk slot
+    assert binding.hgrn2_bwd_varlen_workspace_bytes(s) == table + 2 * states + partials
     assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0      # packed tokens are token-major
     big = 1 << 40
     fwd = lambda s_, cu=FAKE, q=FAKE, o=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_fwd_varlen(
-        ctypes.byref(s_) if s_ is not None else None, cu, q, FAKE, FAKE, None, o, None, ws, n, None)
+        ctypes.byref(s_) if s_ is not None else None, cu, q, FAKE, None, FAKE, None, o, None, ws, n, None)
     assert fwd(None) == E_NULL
     assert fwd(shape(layout=0)) == E_SHAPE
     assert fwd(shape(layout=1, dk=96)) == E_UNSUP
@@ -218,9 +219,10 @@ def test_varlen_workspace_and_error_codes():
     assert fwd(s, n=table + states - 1) == E_WS
     assert fwd(s, ws=None) == E_WS
     assert fwd(shape(B=0, layout=1), cu=None, q=None, o=None, ws=None, n=0) == OK
-    bwd = lambda s_, cu=FAKE, gq=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_bwd_varlen(
-        ctypes.byref(s_), cu, FAKE, FAKE, FAKE, None, FAKE, None, gq, FAKE, FAKE, None, ws, n, None)
+    bwd = lambda s_, cu=FAKE, gq=FAKE, ws=FAKE_WS, n=big, beta=None, gb=None: lib.hgrn2_bwd_varlen(
+        ctypes.byref(s_), cu, FAKE, FAKE, beta, FAKE, None, FAKE, None, gq, FAKE, gb, FAKE, None, ws, n, None)
+    assert bwd(s, beta=FAKE, gb=None) == E_NULL                 # lower bounds given: their gradient must have a place
     assert bwd(shape(layout=1, io=0, gate=0)) == E_UNSUP
     assert bwd(s, cu=None) == E_NULL
     assert bwd(s, gq=None) == E_NULL
-    assert bwd(s, n=table + 2 * states - 1) == E_WS
+    assert bwd(s, n=table + 2 * states + partials - 1) == E_WS

@@ -121,3 +121,42 @@ def test_varlen_offsets_out_of_order_stay_in_bounds():
     # the table turns the offsets into 0, 100, 100, 150, 150: the first sequence is well formed
     ro, _ = oracle.fwd(w.q[:, :, :100], w.f[:, :, :100], w.v[:, :, :100], None)
     check("o[:100]", unpacked(o)[:, :100], ro[0], TOL["bf16"])
+
+
+@pytest.mark.parametrize("H,dk,dv,nseq", [(3, 64, 64, 5), (8, 128, 128, 10)])
+def test_varlen_with_gate_formed_in_the_kernels(H, dk, dv, nseq):
+    """Packed sequences with the pre-activations of the gate and the layer's lower bounds (Eq. 2):
+    dz per token and dbeta summed over all sequences, against the oracle run per sequence."""
+    rng = np.random.default_rng(6700 + H)
+    lens = [int(x) for x in rng.integers(0, 180, size=nseq)]
+    B, T = len(lens), int(sum(lens))
+    print("\n[varlen gated] H=%d dk=%d dv=%d lens=%s" % (H, dk, dv, lens), flush=True)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    w = synth.make_sequence(6701 + H, 1, H, T, dk, dv, io_dtype="bf16", with_dO=True)
+    z = synth.bf16_round((1.5 * rng.standard_normal((1, H, T, dk), dtype=np.float32)).astype(np.float32))
+    beta = rng.uniform(0.0, 0.9, size=(H, dk)).astype(np.float32)
+    h0 = rng.standard_normal((B, H, dk, dv)).astype(np.float32)
+    dhT = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    q, zd, v, dO = packed(w.q, "bf16"), packed(z, "bf16"), packed(w.v, "bf16"), packed(w.dO, "bf16")
+    cud, bd = torch.from_numpy(cu).cuda(), torch.from_numpy(beta).cuda()
+    o, hT = binding.hgrn2_fwd_varlen(q, zd, v, cud, dev(h0), beta=bd)
+    gq, gz, gv, gh0, gb = binding.hgrn2_bwd_varlen(q, zd, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    torch.cuda.synchronize()
+    ro, rq, rz, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
+    rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        sl = (slice(None), slice(None), slice(s, e))
+        ob, hTb = oracle.fwd_gated(w.q[sl], z[sl], beta, w.v[sl], h0[b:b + 1])
+        gqb, gzb, gbb, gvb, gh0b = oracle.bwd_gated(w.q[sl], z[sl], beta, w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+        ro[:, s:e], rq[:, s:e], rz[:, s:e], rv[:, s:e] = ob[0], gqb[0], gzb[0], gvb[0]
+        rhT[b], rh0[b] = hTb[0], gh0b[0]
+        rb += gbb
+    tol = TOL["bf16"]
+    check("o", unpacked(o), ro, tol)
+    check("hT", host(hT), rhT, tol)
+    check("dq", unpacked(gq), rq, tol)
+    check("dv", unpacked(gv), rv, tol)
+    check("dz", unpacked(gz), rz, tol)
+    check("dbeta", host(gb), rb, tol)
+    check("dh0", host(gh0), rh0, tol)
