@@ -9,17 +9,19 @@
 // tokens acts on its incoming state as h_out = A h_in + H with A = prod f and H the segment's
 // result from a zero state.
 //
-// A workgroup of eight waves owns 64 channels of one sequence and walks it in blocks of 16 x 32
-// tokens.  Every half-wave takes one 32-token segment of the block (a channel pair per lane, so a
-// load instruction of a wave fetches one 128-byte row piece for each of its two segments); with
-// 64 channels per workgroup a [8][2048][2048] problem already gives one workgroup to each of the
-// 256 compute units.  Per block:
+// A workgroup of eight waves owns 64 channels of one sequence and walks it in blocks of sixteen
+// segments.  Every half-wave takes one segment of the block (16 or 32 tokens, a channel pair per
+// lane, so a load instruction of a wave fetches one 128-byte row piece for each of its two
+// segments); with 64 channels per workgroup a [8][2048][2048] problem already gives one workgroup
+// to each of the 256 compute units.  Per block:
 //   1. the half-wave walks its segment from a zero state out of registers that were filled one
 //      block ahead, and publishes (A, H) in LDS;
 //   2. after one barrier every lane chains the sixteen summaries (32 fused multiply-adds) into
 //      the state entering its own segment and the state leaving the block;
-//   3. it walks the same registers again from the true state, writes its outputs, and refills
-//      every register row with the next block's token as soon as the row is consumed.
+//   3. it walks the same registers again from the true state and writes its outputs.
+// The forward keeps two register sets and requests a whole block ahead in one burst; the backward,
+// which holds more per token, refills every register row with the next block's token as soon as
+// the row is consumed.
 // The backward first runs steps 1-2 over the whole sequence to record the state entering every
 // segment (a few MB), then walks the blocks from the last to the first with the same scheme for
 // the reverse recurrence  r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t.
@@ -174,10 +176,13 @@ __device__ __forceinline__ f32x2 h1_gate(RAW& raw, const f32x2& kept, bool again
 }
 
 // ---- forward -------------------------------------------------------------------------------------
+// Two register sets: while one block is worked on out of one set, the loads of the next block,
+// issued in one burst before that work starts, fill the other.  (A wave can wait for "all but the
+// n youngest" of its loads only for n < 64, so a set is kept to 48 loads: 16-token segments.)
 template <bool GATE_BF16, bool ACT>
 __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
 {
-    constexpr int TS = kH1SegLong, BLOCK = kH1Segs * TS;
+    constexpr int TS = kH1SegShort, BLOCK = kH1Segs * TS;
     constexpr int GS = GATE_BF16 ? 1 : 2;         // gate bytes per bf16 byte
     __shared__ f32x2 sA[2][kH1Segs][32], sH[2][kH1Segs][32];
     const int cp = threadIdx.x & 31;                             // channel pair of the workgroup's 64 channels
@@ -188,34 +193,37 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
     const unsigned lane_b = 2u * (unsigned)c0;                   // byte offset of this lane's pair in a bf16 row
     const f32x2 beta = ACT ? *reinterpret_cast<const f32x2*>(p.beta + c0) : f32x2{0.0f, 0.0f};
 
-    typename H1Raw<GATE_BF16>::type fr[TS];
+    struct Rows {
+        typename H1Raw<GATE_BF16>::type fr[TS];
+        uint32_t xr[TS], orw[TS];
+    };
     f32x2 fa[TS];
-    uint32_t xr[TS], orw[TS];
-    {
-        const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2),
-                     ro = h1_rows_from(p.o, seq, 0, p.N, p.d, 2);
+    // all rows of a block; a block past the end of the sequence is an empty range and moves no data
+    auto load_block = [&](Rows& s, int blk) {
+        const H1Rsrc rf = h1_rows_from(p.f, seq, blk * BLOCK, p.N, p.d, 2 * GS),
+                     ri = h1_rows_from(p.i, seq, blk * BLOCK, p.N, p.d, 2), ro = h1_rows_from(p.o, seq, blk * BLOCK, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
             const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
-            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
-            xr[t] = h1_ld<true>(ri, off);
-            orw[t] = h1_ld<true>(ro, off);
+            s.fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
+            s.xr[t] = h1_ld<true>(ri, off);
+            s.orw[t] = h1_ld<true>(ro, off);
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    };
     f32x2 carry = p.h0 ? *reinterpret_cast<const f32x2*>(p.h0 + (size_t)b * p.d + c0) : f32x2{0.0f, 0.0f};
-
-    for (int blk = 0; blk < p.NBLK; ++blk) {
+    // one block out of one register set (a block past the end: every row neutral, every store dropped)
+    auto work = [&](Rows& s, int blk) {
         const int t0 = blk * BLOCK + vs * TS;
         const int par = blk & 1;
         // 1. segment summary from a zero state
         f32x2 a = {1.0f, 1.0f}, h = {0.0f, 0.0f};
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
-            h1_touch_gate<GATE_BF16, ACT>(fr[t], fa[t], beta, t0 + t < p.N);
-            if constexpr (ACT) { const f32x2 x = h1_silu(h1_cvt(xr[t])); xr[t] = h1_pack(x.x, x.y); }
-            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], false), x = h1_cvt(xr[t]);
+            h1_touch_gate<GATE_BF16, ACT>(s.fr[t], fa[t], beta, t0 + t < p.N);
+            if constexpr (ACT) { const f32x2 x = h1_silu(h1_cvt(s.xr[t])); s.xr[t] = h1_pack(x.x, x.y); }
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(s.fr[t], fa[t], false), x = h1_cvt(s.xr[t]);
             a = f32x2{a.x * f.x, a.y * f.y};
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};      // f h + (1 - f) x
             __builtin_amdgcn_sched_barrier(0);
@@ -226,27 +234,29 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
         // 2. state entering this half-wave's segment, state leaving the block
         f32x2 mine;
         carry = h1_chain<true>(sA[par], sH[par], vs, cp, carry, mine);
-        // 3. outputs; every row is refilled with the next block's token once it is consumed
-        const int nb = (blk + 1) * BLOCK;
+        // 3. outputs
         const H1Rsrc ry = h1_rows_from(p.y, seq, blk * BLOCK, p.N, p.d, 2);
-        const H1Rsrc rf = h1_rows_from(p.f, seq, nb, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, nb, p.N, p.d, 2),
-                     ro = h1_rows_from(p.o, seq, nb, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
         h = mine;
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
-            h1_forget(xr[t]);
-            const f32x2 f = h1_gate<GATE_BF16, ACT>(fr[t], fa[t], true), x = h1_cvt(xr[t]);
-            f32x2 og = h1_cvt(orw[t]);
+            h1_forget(s.xr[t]);
+            const f32x2 f = h1_gate<GATE_BF16, ACT>(s.fr[t], fa[t], true), x = h1_cvt(s.xr[t]);
+            f32x2 og = h1_cvt(s.orw[t]);
             if constexpr (ACT) og = h1_sigmoid(og);
             h = f32x2{fmaf(f.x, h.x - x.x, x.x), fmaf(f.y, h.y - x.y, x.y)};
-            const unsigned off = lane_b + (unsigned)(vs * TS + t) * pitch;
-            h1_st(ry, off, h.x * og.x, h.y * og.y);
-            fr[t] = h1_ld<GATE_BF16>(rf, off * GS);
-            xr[t] = h1_ld<true>(ri, off);
-            orw[t] = h1_ld<true>(ro, off);
+            h1_st(ry, lane_b + (unsigned)(vs * TS + t) * pitch, h.x * og.x, h.y * og.y);
             __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    Rows even, odd;
+    load_block(even, 0);
+    for (int blk = 0; blk < p.NBLK; blk += 2) {      // always whole pairs: the pass after the last block works on an empty one
+        load_block(odd, blk + 1);
+        work(even, blk);
+        load_block(even, blk + 2);
+        work(odd, blk + 1);
     }
     if (p.hN && vs == 0) *reinterpret_cast<f32x2*>(p.hN + (size_t)b * p.d + c0) = carry;
 }
@@ -483,7 +493,7 @@ hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, 
                                    stream, h0, hN, (size_t)B * d);
         return hipGetLastError();
     }
-    H1Params p = h1_params(B, N, d, kH1SegLong, ws);
+    H1Params p = h1_params(B, N, d, kH1SegShort, ws);
     p.f = f; p.i = i; p.o = o; p.beta = beta; p.h0 = h0; p.y = y; p.hN = hN;
     const dim3 grid((unsigned)(B * p.NCB));
     auto kern = beta ? (gate_bf16 ? hgrn1_fwd_kernel<true, true> : hgrn1_fwd_kernel<false, true>)
