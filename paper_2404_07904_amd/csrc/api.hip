@@ -13,7 +13,7 @@ bool dtype_ok(int32_t t) { return t == HGRN2_F32 || t == HGRN2_BF16; }
 bool dim_ok(int32_t d) { return d == 64 || d == 128; }
 
 // Validates a shape; on success fills `d`.
-int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
+int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = false)
 {
     if (!s) return HGRN2_ERR_NULL;
     if (s->B < 0 || s->H < 0 || s->N < 0 || s->dk <= 0 || s->dv <= 0 || s->chunk < 0) return HGRN2_ERR_SHAPE;
@@ -22,7 +22,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
     const long long bh = (long long)s->B * s->H;
     if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
     const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
-    if (bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk
+    if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
     if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
     if (s->chunk != 0 && s->chunk != kChunk) return HGRN2_ERR_UNSUPPORTED;
     if (backward && s->io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
@@ -53,7 +53,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d)
 // pointer is set by the caller once the workspace is known.
 int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d)
 {
-    const int rc = check_shape(s, backward, d);
+    const int rc = check_shape(s, backward, d, true);
     if (rc != HGRN2_OK) return rc;
     if (s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;          // packed tokens are token-major
     const long long bound = (long long)s->N / kChunk + s->B;
