@@ -192,7 +192,7 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
  * and its reverse mode for L = sum(y * grad_y) + sum(h_N * grad_hN).  A second, bandwidth-bound
  * workload beside the state-expanded recurrence above (which reduces to it for a 1 x 1 state).
  *   f, i, o, y, grad_*   device [B][N][d], io_dtype (bf16 only; f may be fp32 via gate_dtype);
- *                        d a multiple of 128
+ *                        d a multiple of 64
  *   h0, grad_hN     in   device fp32 [B][d], or NULL for zero
  *   hN, grad_h0     out  device fp32 [B][d], or NULL if not wanted
  *   grad_f          out  includes the tied input gate 1 - f

@@ -356,7 +356,7 @@ static int h1_check(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t g
     if (B < 0 || N < 0 || d < 0) return HGRN2_ERR_SHAPE;
     if (!dtype_ok(io_dtype) || !dtype_ok(gate_dtype)) return HGRN2_ERR_SHAPE;
     if ((long long)B * (d / 128 + 1) > INT_MAX / 2 || d > (1 << 20)) return HGRN2_ERR_SHAPE;   // grid size; 32-bit byte offsets inside a block of rows
-    if (d % 128 != 0 || io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
+    if (d % 64 != 0 || io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;          // a workgroup owns 64 channels
     return HGRN2_OK;
 }
 

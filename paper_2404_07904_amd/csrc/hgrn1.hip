@@ -25,7 +25,7 @@
 // The backward first runs steps 1-2 over the whole sequence to record the state entering every
 // segment (a few MB), then walks the blocks from the last to the first with the same scheme for
 // the reverse recurrence  r_t = dy_t o_t + c_t,  c_{t-1} = f_t r_t.
-// Tensors are [B][N][d] (token-major, d a multiple of 128), states [B][d] fp32.
+// Tensors are [B][N][d] (token-major, d a multiple of 64), states [B][d] fp32.
 //
 // The "act" forms take the three pre-activations of Eq. 1 instead (the outputs of the layer's
 // projections) and the layer's lower bounds of Eq. 2, and form

@@ -95,7 +95,7 @@ hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, con
                        const void* v, float* state, void* o, const float* beta, int H, hipStream_t stream);
 
 // HGRN1, the element-wise recurrence h_t = f_t h_{t-1} + (1 - f_t) i_t, y_t = h_t o_t (paper Eq. 1),
-// on [B][N][d] bf16 tensors (d a multiple of 128), states [B][d] fp32; `ws` holds hgrn1_ws_bytes().
+// on [B][N][d] bf16 tensors (d a multiple of 64), states [B][d] fp32; `ws` holds hgrn1_ws_bytes().
 // With `beta` ([d] fp32) set, f, i, o are the pre-activations of Eq. 1 and the gate gets the lower
 // bound of Eq. 2; the backward then returns the gradients of the pre-activations and of beta.
 size_t hgrn1_ws_bytes(int B, int N, int d);

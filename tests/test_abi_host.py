@@ -183,7 +183,7 @@ def test_hgrn1_workspace_and_error_codes():
     assert fwd(n=16) == E_WS
     bwd = lambda d=256, gf=FAKE, n=big: lib.hgrn1_bwd(2, 100, d, 1, 1, FAKE, FAKE, FAKE, None, FAKE, None, gf, FAKE,
                                                       FAKE, None, FAKE_WS, n, None)
-    assert bwd(d=64) == E_UNSUP
+    assert bwd(d=96) == E_UNSUP
     assert bwd(gf=None) == E_NULL
     assert bwd(n=16) == E_WS
     # the forms that take the pre-activations of Eq. 1 and the lower bounds of Eq. 2

@@ -44,7 +44,7 @@ def run(f, i, o, dy, h0, dhN, gate_dtype="bf16"):
     check("dh0", host(gh0), rh0, 3e-5)
 
 
-@pytest.mark.parametrize("d", [128, 384])
+@pytest.mark.parametrize("d", [64, 128, 384])
 @pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
 def test_hgrn1_ragged(d, gate_dtype):
     print("\n[hgrn1] B=3 N=203 d=%d gate=%s" % (d, gate_dtype), flush=True)
@@ -119,7 +119,7 @@ def run_act(zf, zi, zo, beta, dy, h0, dhN, gate_dtype="bf16"):
     check("dh0", host(gh0), rh0, tol)
 
 
-@pytest.mark.parametrize("d", [128, 384])
+@pytest.mark.parametrize("d", [192, 384])
 @pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
 def test_hgrn1_act_ragged(d, gate_dtype):
     print("\n[hgrn1 act] B=3 N=203 d=%d gate=%s" % (d, gate_dtype), flush=True)
