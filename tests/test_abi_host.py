@@ -226,3 +226,12 @@ def test_varlen_workspace_and_error_codes():
     assert bwd(s, cu=None) == E_NULL
     assert bwd(s, gq=None) == E_NULL
     assert bwd(s, n=table + 2 * states + partials - 1) == E_WS
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
