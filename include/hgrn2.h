@@ -155,6 +155,17 @@ int hgrn2_step_gated(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dt
                      void* hip_stream);
 
 /*
+ * Gate-domain probe for the contract stated at the top ("Gate domain"): writes to *min_product
+ * (device, one float) the smallest product of the gates of one channel over a half chunk -- tokens
+ * [64 n, 64 n + 32) and [64 n + 32, 64 n + 64) of every sequence, n = 0, 1, ... -- of the whole
+ * call.  hgrn2_fwd / hgrn2_bwd are exact up to rounding while it is above 2^-100 (7.9e-31).
+ * Reads f once; equal-length batches in either layout; with beta (device fp32 [H][dk]) `f` holds
+ * pre-activations and the gate of Eq. 2 is formed first.  An empty call writes 1.
+ */
+int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float* beta, float* min_product,
+                           void* hip_stream);
+
+/*
  * Variable-length batches: shape->B sequences of different lengths packed back to back along the
  * token axis, as training on packed documents and serving ragged prefill batches produce them.
  * The recurrence of Eq. 3 (Section 3.2) restarts at every sequence boundary: sequence b starts

@@ -246,3 +246,19 @@ def hgrn1_bwd_act(zf, zi, zo, beta, dy, h0=None, dhN=None):
     dzo = do * o * (1.0 - o)
     dbeta = (df * (1.0 - g)).sum(axis=(0, 1))
     return dzf, dzi, dzo, dbeta, dh0
+
+
+# ---------------------------------------------------------------------------------------------
+# What the exactness of a chunkwise evaluation with one reference row per chunk half depends on:
+# the smallest product of one channel's gates over a half chunk (tokens [C n, C n + C/2) and
+# [C n + C/2, C n + C) of every sequence; a ragged last piece counts with the tokens it has).
+# ---------------------------------------------------------------------------------------------
+def min_gate_product(f, chunk=64):
+    """f: [B,H,N,dk] -> float (1.0 for an empty input)."""
+    f = np.asarray(f, dtype=np.float64)
+    N = f.shape[2]
+    half = chunk // 2
+    best = 1.0
+    for s in range(0, N, half):
+        best = min(best, float(np.prod(f[:, :, s:s + half, :], axis=2).min()))
+    return best

@@ -18,7 +18,7 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax",
+           "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_bwd_varlen.restype = ctypes.c_int
         L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_min_gate_product.restype = ctypes.c_int
+        L.hgrn2_min_gate_product.argtypes = [sp, vp, vp, vp, vp]
         L.hgrn2_cumax.restype = ctypes.c_int
         L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
         L.hgrn1_workspace_bytes.restype = sz
@@ -276,6 +278,18 @@ def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd_varlen")
     return (gq, gf, gv, gh0) if beta is None else (gq, gf, gv, gh0, gb)
+
+
+def hgrn2_min_gate_product(f, beta=None, layout=HGRN2_LAYOUT_BHND):
+    """Smallest product of one channel's gates over a half chunk (32 tokens) in f [B,H,N,dk] (or
+    [B,N,H,dk]); a one-element fp32 device tensor.  The chunkwise passes are exact while it
+    exceeds 2**-100.  With beta [H,dk], f holds pre-activations (Eq. 2)."""
+    shape = make_shape(f, f, f, 0, layout)
+    out = torch.empty((1,), dtype=torch.float32, device=f.device)
+    rc = lib().hgrn2_min_gate_product(ctypes.byref(shape), _ptr(f), _ptr(beta), _ptr(out), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_min_gate_product")
+    return out
 
 
 def hgrn2_cumax(gamma):

@@ -262,6 +262,20 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     return HGRN2_OK;
 }
 
+int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float* beta, float* min_product,
+                           void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, false, &d);
+    if (rc != HGRN2_OK) return rc;
+    if (!min_product) return HGRN2_ERR_NULL;
+    if ((size_t)d.BH * d.N > 0 && !f) return HGRN2_ERR_NULL;
+    d.beta = beta;
+    if (launch_min_gate_product(d, f, min_product, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream)
 {
     if (L < 0 || d < 0) return HGRN2_ERR_SHAPE;

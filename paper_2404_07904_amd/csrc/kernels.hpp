@@ -105,6 +105,10 @@ hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, 
                             const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
                             void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream);
 
+// Smallest product of the gates of one channel over a half chunk (32 tokens), over the whole call:
+// what the exactness of the chunkwise kernels depends on.  `out`: one float on the device.
+hipError_t launch_min_gate_product(const SeqDims& d, const void* f, float* out, hipStream_t stream);
+
 // Bytes of one per-chunk state set in the workspace.
 size_t state_ws_bytes(const SeqDims& d);
 

@@ -151,6 +151,9 @@ def test_gated_workspace_and_error_codes():
     need = binding.hgrn2_bwd_gated_workspace_bytes(shape())
     assert bwd(shape(), n=need - 1) == E_WS
     assert bwd(shape(), ws=ctypes.c_void_p(0x100010)) == E_WS
+    assert lib.hgrn2_min_gate_product(ctypes.byref(shape()), FAKE, None, None, None) == E_NULL
+    assert lib.hgrn2_min_gate_product(ctypes.byref(shape()), None, None, FAKE, None) == E_NULL
+    assert lib.hgrn2_min_gate_product(ctypes.byref(shape(dk=96)), FAKE, None, FAKE, None) == E_UNSUP
     assert lib.hgrn2_cumax(-1, 4, FAKE, FAKE, None) == E_SHAPE
     assert lib.hgrn2_cumax(3, 4, None, FAKE, None) == E_NULL
     assert lib.hgrn2_cumax(0, 4, None, None, None) == OK

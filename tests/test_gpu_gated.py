@@ -134,3 +134,37 @@ def test_gated_decode_steps(dk, dv, gate_dtype):
         torch.cuda.synchronize()
         check("o[%d]" % t, host(o), ro, TOL["bf16"])
     check("state", host(st), ref_state, 1e-3)
+
+
+@pytest.mark.parametrize("case", ["bf16", "f32", "bnhd", "gated", "ragged"])
+def test_min_gate_product_probe(case):
+    """hgrn2_min_gate_product against the oracle's half-chunk minimum (products of 32 fp32 factors:
+    1e-4 relative), and what it is for: an input that leaves the stated domain is reported as such."""
+    rng = np.random.default_rng(7800)
+    B, H, N, dk = 2, 3, 203 if case == "ragged" else 256, 64
+    lo = 2.0 ** -100
+    if case == "gated":
+        z = synth.bf16_round((2.0 * rng.standard_normal((B, H, N, dk), dtype=np.float32)).astype(np.float32))
+        beta = rng.uniform(0.0, 0.5, size=(H, dk)).astype(np.float32)
+        got = binding.hgrn2_min_gate_product(dev(z, "bf16"), torch.from_numpy(beta).cuda())
+        ref = oracle.min_gate_product(oracle.gate(z, beta))
+    else:
+        f = rng.uniform(0.2, 1.0, (B, H, N, dk)).astype(np.float32)
+        dt = "f32" if case == "f32" else "bf16"
+        f = f if dt == "f32" else synth.bf16_round(f)
+        fd = dev(f, dt)
+        if case == "bnhd":
+            got = binding.hgrn2_min_gate_product(fd.permute(0, 2, 1, 3).contiguous(), layout=binding.HGRN2_LAYOUT_BNHD)
+        else:
+            got = binding.hgrn2_min_gate_product(fd)
+        ref = oracle.min_gate_product(f)
+    torch.cuda.synchronize()
+    print("\n[domain probe] %s: %.6e (oracle %.6e)" % (case, float(got), ref), flush=True)
+    assert abs(float(got) - ref) <= 1e-4 * ref
+    assert float(got) > lo
+    # a run of small gates in one channel takes the call out of the domain, and the probe says so
+    bad = np.ones((1, 1, 128, 64), dtype=np.float32)
+    bad[0, 0, 64:96, 5] = 0.05
+    got = float(binding.hgrn2_min_gate_product(dev(bad, "bf16")))
+    torch.cuda.synchronize()
+    assert got < lo and abs(got - oracle.min_gate_product(synth.bf16_round(bad))) <= 1e-3 * got

@@ -547,3 +547,26 @@ def test_hgrn1_act_bwd_finite_differences():
     s = 1.0 / (1.0 + np.exp(-zi))
     di_only = dzi / (s * (1.0 + zi * (1.0 - s))) * s
     assert np.max(np.abs(nums["zi"] - di_only)) > 1e-3 * np.max(np.abs(dzi))
+
+
+# ------------------------------------------------------------------ gate-domain probe
+def test_min_gate_product_constant_gate_and_brute_force():
+    """A constant gate c gives c^32 (c^r for a ragged last piece of r tokens is larger); a single
+    small gate shows up in exactly its own half chunk; token-by-token brute force on random gates."""
+    assert abs(oracle.min_gate_product(np.full((1, 1, 128, 4), 0.5)) - 0.5 ** 32) <= 1e-24
+    assert abs(oracle.min_gate_product(np.full((2, 1, 40, 4), 0.9)) - 0.9 ** 32) <= 1e-15      # pieces of 32 and 8 tokens
+    assert oracle.min_gate_product(np.zeros((1, 1, 0, 4))) == 1.0
+    f = np.ones((1, 2, 200, 3)); f[0, 1, 70, 2] = 1e-3
+    assert abs(oracle.min_gate_product(f) - 1e-3) <= 1e-18
+    rng = np.random.default_rng(41)
+    f = rng.uniform(0.3, 1.0, (2, 2, 77, 3))
+    best = 1.0
+    for b in range(2):
+        for h in range(2):
+            for a in range(3):
+                for s in range(0, 77, 32):
+                    p = 1.0
+                    for t in range(s, min(s + 32, 77)):
+                        p *= f[b, h, t, a]
+                    best = min(best, p)
+    assert abs(oracle.min_gate_product(f) - best) <= 1e-15 * best
