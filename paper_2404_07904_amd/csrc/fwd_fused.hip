@@ -170,7 +170,10 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     constexpr int VPR = DVW / 8;             // 16-byte vectors per V / O row
     constexpr int NVV = VPR / 8;             // vectors per thread
     constexpr int VRS = 64 / VPR;            // rows one wave covers per vector
-    u32x4 rawv[NVV];                 // V is fetched one chunk ahead only
+    // V: two chunks ahead too, in alternating sets, where the registers allow it (fp32 gates take
+    // twice the prefetch registers of bf16 ones; V is then fetched one chunk ahead)
+    constexpr int VD = GATE_BF16 ? 2 : 1;
+    u32x4 rawv[VD][NVV];
     const int vrow = RW * w + lane / VPR, vcol = 8 * (lane % VPR);      // V copy: 16 bytes per lane, rows vrow (+ VRS)
     // Every load is issued unconditionally (a row past the end of the sequence re-reads the last
     // row), and the chunk loop always runs an even number of passes, so that its body is
@@ -301,8 +304,9 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // the never-written block of P (rows 0..31 x columns 32..63) must read as zero
     for (int idx = tid; idx < 32 * 32; idx += kFusedThreads) Pm[(idx >> 5) * PC + 32 + (idx & 31)] = (T)0.0f;
     if (tid < DK) tot[NW * DK + tid] = 1.0f;
-    load_f(rawf[0], 0); load_q(rawq[0], 0); load_v(rawv, 0);
+    load_f(rawf[0], 0); load_q(rawq[0], 0); load_v(rawv[0], 0);
     load_f(rawf[1], 1); load_q(rawq[1], 1);
+    if (VD == 2) load_v(rawv[VD - 1], 1);
     prep_gates(rawf[0], rawq[0], 0);
     load_f(rawf[0], 2); load_q(rawq[0], 2);
     __syncthreads();
@@ -351,8 +355,8 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         T* Sp = Sb + (LATE_QS ? (size_t)par * DK * DVW : 0);      // where this pass publishes G_m(n) S_n
         // ======================= stage A =======================
         if (!LATE_QS) store_o(n - 1);
-        store_v(rawv);
-        load_v(rawv, n + 1);
+        store_v(rawv[VD == 2 ? par : 0]);
+        load_v(rawv[VD == 2 ? par : 0], n + VD);
         HGRN2_STAMP(7);
         // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
 #pragma unroll
