@@ -354,11 +354,19 @@ def main():
         for i in range(3):
             prefill(i); decode(i)
         tp, td = timed(prefill, reps=10), timed(decode, reps=5)
+        # the same decode steps captured once into a HIP graph (the entry points only enqueue kernels)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            decode(0)
+        graph.replay()
+        tg = timed(lambda i: graph.replay(), reps=5)
         result["handoff"] = {
             "workload": "prefill B=%d H=%d N=%d d=%d, then %d decode steps in place on the state it returns "
                         "(fp32 [B][H][dk][dv], no copy or conversion between the two)" % (Bp, H, Np, D, n_dec),
             "prefill_us": round(tp * 1e6, 1), "prefill_tokens_per_s": round(Bp * Np / tp, 1),
-            "decode_us_per_step": round(td / n_dec * 1e6, 2), "decode_tokens_per_s": round(Bp * n_dec / td, 1)}
+            "decode_us_per_step": round(td / n_dec * 1e6, 2), "decode_tokens_per_s": round(Bp * n_dec / td, 1),
+            "decode_us_per_step_hip_graph": round(tg / n_dec * 1e6, 2)}
         del qp, fp, vp, op, state
 
     # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----

@@ -235,7 +235,7 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     if (d.BH == 0) {
         // no sequences: nothing contributes to the gradient of beta
         if (beta && (size_t)shape->H * d.dk > 0 &&
-            hipMemsetAsync(grad_beta, 0, (size_t)shape->H * d.dk * sizeof(float), static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+            launch_zero_floats(grad_beta, (size_t)shape->H * d.dk, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
             return HGRN2_ERR_HIP;
         return HGRN2_OK;
     }
@@ -411,7 +411,7 @@ static int h1_bwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (act && !has_tokens && d > 0) {        // nothing contributes: the gradient of beta is zero
-        if (hipMemsetAsync(grad_beta, 0, (size_t)d * sizeof(float), stream) != hipSuccess) return HGRN2_ERR_HIP;
+        if (launch_zero_floats(grad_beta, (size_t)d, stream) != hipSuccess) return HGRN2_ERR_HIP;
     }
     if (launch_hgrn1_bwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, act ? beta : nullptr, h0, grad_y, grad_hN, grad_f,
                          grad_i, grad_o, act && has_tokens ? grad_beta : nullptr, grad_h0, workspace, stream) != hipSuccess)

@@ -117,6 +117,8 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
+// dst[0 .. n) = 0, as a kernel (safe under graph capture)
+hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);
 
 }   // namespace hgrn2

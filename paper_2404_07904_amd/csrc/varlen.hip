@@ -71,6 +71,21 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     }
 }
 
+// Zero fill as a kernel: a caller may have the stream under graph capture, where a memset node is
+// not an option.
+__global__ void zero_floats_kernel(float* dst, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = 0.0f;
+}
+
+hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream)
+{
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_floats_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, dst, n);
+    return hipGetLastError();
+}
+
 size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream)

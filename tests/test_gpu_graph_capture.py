@@ -1,0 +1,90 @@
+"""The entry points enqueue kernels only (no allocation, no memset node, no host synchronisation), so
+a caller can capture them into a HIP graph.  A captured forward + backward (and a captured run of
+decode steps) is replayed several times on fresh inputs, with eager work and synchronisations
+between the replays, and every replay must give exactly what the eager calls give."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_07904_amd import binding, synth
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def fresh(seed, B, H, N, d):
+    w = synth.make_sequence(seed, B, H, N, d, d, io_dtype="bf16", lb=0.3, with_h0=True, with_dO=True, with_dhT=True)
+    return [dev(x, "bf16") for x in (w.q, w.f, w.v, w.dO)] + [dev(w.h0), dev(w.dhT)]
+
+
+@pytest.mark.parametrize("B,H,N,d", [(2, 3, 200, 64), (8, 9, 130, 128)])
+def test_captured_forward_backward_replays(B, H, N, d):
+    print("\n[graph] B=%d H=%d N=%d d=%d" % (B, H, N, d), flush=True)
+    static = fresh(8600, B, H, N, d)
+    q, f, v, dO, h0, dhT = static
+    shape = binding.make_shape(q, v, f)
+    ws = torch.empty(binding.hgrn2_bwd_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    o, hT = torch.empty_like(v), torch.empty((B, H, d, d), device="cuda")
+    gq, gf, gv, gh0 = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty_like(hT)
+
+    def step():
+        binding.hgrn2_fwd(q, f, v, h0, o=o, hT=hT, workspace=ws)
+        binding.hgrn2_bwd(q, f, v, dO, h0, dhT, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv, grad_h0=gh0)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up outside the capture (first-launch set-up)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for k in range(4):
+        new = fresh(8601 + k, B, H, N, d)
+        for dst, src in zip(static, new):
+            dst.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (o, hT, gq, gf, gv, gh0)]
+        for t in (o, hT, gq, gf, gv, gh0):
+            t.zero_()                           # eager work between the replays
+        step()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "hT", "dq", "df", "dv", "dh0"), got, (o, hT, gq, gf, gv, gh0)):
+            assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (k, name)
+
+
+def test_captured_decode_steps_replay():
+    B, H, d, T = 4, 3, 64, 6
+    print("\n[graph] decode B=%d H=%d d=%d, %d steps per replay" % (B, H, d, T), flush=True)
+    w = synth.config4(T=T, B=B, H=H, d=d)
+    qs, fs, vs = (dev(x, "bf16") for x in (w.q, w.f, w.v))
+    state = dev(w.state)
+    outs = torch.empty((T, B, H, d), dtype=torch.bfloat16, device="cuda")
+
+    def run():
+        for t in range(T):
+            binding.hgrn2_step(qs[t], fs[t], vs[t], state, outs[t])
+
+    s0 = state.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    state.copy_(s0)
+    with torch.cuda.graph(graph):
+        run()
+    for k in range(3):
+        state.copy_(s0 * (1.0 + 0.25 * k))
+        graph.replay()
+        torch.cuda.synchronize()
+        got_o, got_s = outs.clone(), state.clone()
+        state.copy_(s0 * (1.0 + 0.25 * k))
+        outs.zero_()
+        run()
+        torch.cuda.synchronize()
+        assert torch.equal(got_o, outs) and torch.equal(got_s, state), "replay %d differs from eager" % k
