@@ -238,3 +238,23 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with warnings as errors, and a C program
+    that takes the address of every declared function links against the library."""
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "hgrn2.h")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr])
+    src = tmp_path / "use.c"
+    names = declared_functions()
+    src.write_text('#include "hgrn2.h"\n#include <stdio.h>\nint main(void) {\n    const void* fns[] = {%s};\n'
+                   '    printf("%%d\\n", (int)(sizeof fns / sizeof fns[0]));\n    return fns[0] == 0;\n}\n'
+                   % ", ".join("(const void*)%s" % n for n in names))
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=gnu99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                           "-L", libdir, "-l:" + os.path.basename(binding.LIB_PATH), "-Wl,-rpath," + libdir,
+                           "-Wl,--allow-shlib-undefined"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0 and int(out.stdout) == len(names)
