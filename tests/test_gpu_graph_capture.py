@@ -88,3 +88,29 @@ def test_captured_decode_steps_replay():
         run()
         torch.cuda.synchronize()
         assert torch.equal(got_o, outs) and torch.equal(got_s, state), "replay %d differs from eager" % k
+
+
+def test_two_streams_with_their_own_workspaces():
+    """The library keeps no state between calls: two calls on two streams, each with its own
+    workspace and outputs, give what the same calls give one after the other."""
+    B, H, N, d = 2, 3, 300, 64
+    a, b = fresh(8700, B, H, N, d), fresh(8701, B, H, N, d)
+    torch.cuda.synchronize()
+    ref = []
+    for q, f, v, dO, h0, dhT in (a, b):
+        o, hT = binding.hgrn2_fwd(q, f, v, h0)
+        g = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True)
+        ref.append((o, hT) + tuple(g))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    got = [None, None]
+    for rep in range(3):
+        for k, (q, f, v, dO, h0, dhT) in enumerate((a, b)):
+            with torch.cuda.stream(streams[k]):
+                o, hT = binding.hgrn2_fwd(q, f, v, h0)
+                g = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True)
+                got[k] = (o, hT) + tuple(g)
+        torch.cuda.synchronize()
+        for k in range(2):
+            for x, y in zip(got[k], ref[k]):
+                assert torch.equal(x, y)
