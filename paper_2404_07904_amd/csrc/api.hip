@@ -59,6 +59,7 @@ int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d)
     const long long bound = (long long)s->N / kChunk + s->B;
     if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2 || s->B > INT_MAX / 8) return HGRN2_ERR_SHAPE;
     d->NC = (int)bound;
+    d->packed = true;
     d->lay.sb_k = d->lay.sb_v = 0;
     d->lay.B = s->B;
     return HGRN2_OK;
@@ -182,8 +183,6 @@ size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, false, &d) != HGRN2_OK) return 0;
-    static int dummy_table;
-    d.lay.vl = &dummy_table;          // sizes only: marks the dims as variable-length
     return round256(varlen_table_bytes(shape->B)) + round256(state_ws_bytes(d));
 }
 
@@ -191,8 +190,6 @@ size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
-    static int dummy_table;
-    d.lay.vl = &dummy_table;
     return round256(varlen_table_bytes(shape->B)) + 2 * round256(state_ws_bytes(d)) + round256(beta_partials_bytes(d));
 }
 

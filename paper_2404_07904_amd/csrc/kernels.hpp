@@ -41,9 +41,12 @@ struct SeqDims {
     const float* beta = nullptr;
     TokenLayout lay;
     // [B][H][N][d]: the kernels then use compile-time token strides
-    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv && !lay.vl; }
+    // variable-length batch: N and NC then describe the packed token axis (lay.vl is set once the
+    // workspace that holds the sequence table is known)
+    bool packed = false;
+    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv && !packed; }
     // chunk slots of the per-chunk workspaces and of the per-chunk grids
-    size_t total_chunks() const { return lay.vl ? (size_t)H * NC : (size_t)BH * NC; }
+    size_t total_chunks() const { return packed ? (size_t)H * NC : (size_t)BH * NC; }
 };
 
 // What a state sweep accumulates.
