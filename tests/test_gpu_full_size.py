@@ -96,3 +96,63 @@ def test_config4_full_size_512_steps():
     eps = 1e-5
     assert np.all(st_gpu >= vmin - eps) and np.all(st_gpu <= vmax + eps), "state left the convex hull"
     assert np.all(np.isfinite(host(outs[T - 1])))
+
+
+def test_config2_full_size_token_major_gated_and_packed():
+    """The benchmark shape through the other entry-point families, every output element compared:
+    token-major tensors; the gate of Eq. 2 formed in the kernels (layer 12: beta = 0.5); and the same
+    16384 tokens per head packed as documents of mixed length."""
+    w = synth.config2(12)
+    B, H, N, d = w.q.shape
+    tol = TOL["bf16"]
+    rq, rf, rv, _ = oracle.bwd(w.q, w.f, w.v, w.dO, None, None, want_dh0=False)
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, None)
+    # token-major
+    print("\n[full] config2 layer 12, [B][N][H][d]", flush=True)
+    tm = lambda x, dt="bf16": dev(x, dt).permute(0, 2, 1, 3).contiguous()
+    back = lambda t: host(t.permute(0, 2, 1, 3))
+    q, f, v, dO = tm(w.q), tm(w.f, w.gate_dtype), tm(w.v), tm(w.dO)
+    L = binding.HGRN2_LAYOUT_BNHD
+    o, hT = binding.hgrn2_fwd(q, f, v, None, layout=L)
+    gq, gf, gv, _ = binding.hgrn2_bwd(q, f, v, dO, None, None, layout=L)
+    torch.cuda.synchronize()
+    check("o", back(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", back(gq), rq, tol); check("df", back(gf), rf, tol); check("dv", back(gv), rv, tol)
+    del o, gq, gf, gv
+    # packed: the batch entries cut into documents (every cut restarts the recurrence)
+    print("[full] config2 layer 12, packed documents", flush=True)
+    rng = np.random.default_rng(9900)
+    cuts = sorted(set([0, B * N] + [int(x) for x in rng.integers(1, B * N, size=40)]))
+    cu = torch.tensor(cuts, dtype=torch.int32, device="cuda")
+    pk = lambda t: t.reshape(B * N, H, d)
+    po, phT = binding.hgrn2_fwd_varlen(pk(q), pk(f), pk(v), cu, None)
+    pq, pf, pv, _ = binding.hgrn2_bwd_varlen(pk(q), pk(f), pk(v), pk(dO), cu, None, None)
+    torch.cuda.synchronize()
+    flat = lambda x: np.ascontiguousarray(np.transpose(x, (1, 0, 2, 3)).reshape(H, B * N, d))     # [H][T][d]
+    wq, wf, wv, wd = flat(w.q), flat(w.f), flat(w.v), flat(w.dO)
+    eo, eq, ef, ev = (np.zeros((H, B * N, d)) for _ in range(4))
+    ehT = np.zeros((len(cuts) - 1, H, d, d))
+    for b in range(len(cuts) - 1):
+        s, e = cuts[b], cuts[b + 1]
+        sl = (None, slice(None), slice(s, e))
+        ob, hb = oracle.fwd(wq[sl], wf[sl], wv[sl], None)
+        gqb, gfb, gvb, _ = oracle.bwd(wq[sl], wf[sl], wv[sl], wd[sl], None, None, want_dh0=False)
+        eo[:, s:e], eq[:, s:e], ef[:, s:e], ev[:, s:e], ehT[b] = ob[0], gqb[0], gfb[0], gvb[0], hb[0]
+    un = lambda t: host(t.permute(1, 0, 2))
+    check("o", un(po), eo, tol); check("hT", host(phT), ehT, tol)
+    check("dq", un(pq), eq, tol); check("df", un(pf), ef, tol); check("dv", un(pv), ev, tol)
+    del po, pq, pf, pv
+    # gate formed in the kernels
+    print("[full] config2 shape, gate from pre-activations", flush=True)
+    z = synth.bf16_round((1.5 * rng.standard_normal((B, H, N, d), dtype=np.float32)).astype(np.float32))
+    beta = np.full((H, d), 0.5, dtype=np.float32)
+    qd, zd, vd, dOd = dev(w.q, "bf16"), dev(z, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+    bd = torch.from_numpy(beta).cuda()
+    o, hT = binding.hgrn2_fwd_gated(qd, zd, bd, vd, None)
+    gq, gz, gb, gv, _ = binding.hgrn2_bwd_gated(qd, zd, bd, vd, dOd, None, None)
+    torch.cuda.synchronize()
+    go, ghT = oracle.fwd_gated(w.q, z, beta, w.v, None)
+    oq, oz, ob_, ov, _ = oracle.bwd_gated(w.q, z, beta, w.v, w.dO, None, None, want_dh0=False)
+    check("o", host(o), go, tol); check("hT", host(hT), ghT, tol)
+    check("dq", host(gq), oq, tol); check("dz", host(gz), oz, tol); check("dv", host(gv), ov, tol)
+    check("dbeta", host(gb), ob_, tol)
