@@ -67,6 +67,51 @@ int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d)
 
 size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Long sequences in a small batch leave most of the chip idle in the kernels that walk a sequence
+// chunk by chunk.  Those then see every sequence cut into runs of whole chunks: a first walk per
+// run from a zero state yields what the run adds and how it decays what enters it, a carry over
+// the runs turns that into the state entering each run, and the usual walk starts run by run.
+// Returns the number of runs (1: not cut) and the chunks of a full run.
+int plan_runs(const SeqDims& d, bool backward, int* run_chunks)
+{
+    *run_chunks = d.NC;
+    // Measured on long sequences of 128-wide heads: the forward gains up to 64 sequences and with
+    // about 256 runs in all, down to runs of 4 chunks; the two backward sweeps share the chip, so
+    // they gain up to 32 sequences, with about 128 runs each and runs of 8 chunks or more.
+    if (d.packed || d.NC < 32 || d.BH == 0 || d.BH > (backward ? 32 : 64)) return 1;
+    const int fill = ((backward ? 128 : 256) + d.BH - 1) / d.BH;
+    const int by_length = d.NC / (backward ? 8 : 4);
+    const int seg = fill < by_length ? fill : by_length;
+    if (seg < 2) return 1;
+    const int rc = (d.NC + seg - 1) / seg;
+    *run_chunks = rc;
+    return (d.NC + rc - 1) / rc;                         // every run holds at least one chunk
+}
+
+SeqDims as_runs(const SeqDims& d, int seg, int run_chunks)
+{
+    SeqDims r = d;
+    r.BH = d.BH * seg; r.NC = run_chunks; r.N = run_chunks * kChunk;
+    r.lay.seg = seg; r.lay.n_tokens = d.N;
+    return r;
+}
+
+// per sweep: what every run adds to the state, fp32 [BH * seg][dk][dv]
+size_t run_state_bytes(const SeqDims& d, bool backward)
+{
+    int rc;
+    const int seg = plan_runs(d, backward, &rc);
+    return seg > 1 ? round256((size_t)d.BH * seg * d.dk * d.dv * sizeof(float)) : 0;
+}
+
+// the gate products of the runs, fp32 [BH * seg][dk]
+size_t run_decay_bytes(const SeqDims& d, bool backward)
+{
+    int rc;
+    const int seg = plan_runs(d, backward, &rc);
+    return seg > 1 ? round256((size_t)d.BH * seg * d.dk * sizeof(float)) : 0;
+}
+
 }   // namespace
 
 extern "C" {
@@ -75,14 +120,14 @@ size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, false, &d) != HGRN2_OK) return 0;
-    return round256(state_ws_bytes(d));
+    return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
 }
 
 size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
-    return 2 * round256(state_ws_bytes(d));
+    return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true);
 }
 
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
@@ -97,14 +142,31 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
     if (gated && has_tokens && !beta) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
-    const size_t need = round256(state_ws_bytes(d));
+    const size_t one = round256(state_ws_bytes(d));
+    const size_t need = one + run_state_bytes(d, false) + run_decay_bytes(d, false);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (d.BH == 0) return HGRN2_OK;
     if (!has_tokens && !hT) return HGRN2_OK;
+    int run_chunks;
+    const int seg = plan_runs(d, false, &run_chunks);
+    if (seg > 1) {
+        const SeqDims r = as_runs(d, seg, run_chunks);
+        float* run_state = reinterpret_cast<float*>(static_cast<char*>(workspace) + one);
+        float* run_decay = reinterpret_cast<float*>(reinterpret_cast<char*>(run_state) + run_state_bytes(d, false));
+        if (launch_sweep(r, kSweepStateFwd, q, f, v, nullptr, run_state, nullptr, run_decay, stream) != hipSuccess ||
+            launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_state, run_decay, hT, false, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (fwd_fused_supported(r))
+            return launch_fwd_fused(r, q, f, v, run_state, o, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+        if (launch_sweep(r, kSweepStateFwd, q, f, v, run_state, nullptr, workspace, nullptr, stream) != hipSuccess ||
+            launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        return HGRN2_OK;
+    }
     if (fwd_fused_supported(d))
         return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
-    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, workspace, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, workspace, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
@@ -126,7 +188,8 @@ size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
-    return 2 * round256(state_ws_bytes(d)) + round256(beta_partials_bytes(d));
+    return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true) +
+           round256(beta_partials_bytes(d));
 }
 
 // Backward pass; `gated`: `f` holds pre-activations, grad_f receives dL/dz and grad_beta dL/dbeta.
@@ -144,12 +207,28 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     d.beta = gated ? beta : nullptr;
     const size_t one = round256(state_ws_bytes(d));
     const size_t part = gated ? round256(beta_partials_bytes(d)) : 0;
-    const size_t need = 2 * one + part;
+    const size_t rs = run_state_bytes(d, true), rd = run_decay_bytes(d, true);
+    const size_t need = 2 * (one + rs) + rd + part;
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    void* ws_s = workspace;
-    void* ws_ds = static_cast<char*>(workspace) + one;
-    float* ws_part = gated ? reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * one) : nullptr;
+    char* base = static_cast<char*>(workspace);
+    void* ws_s = base;
+    void* ws_ds = base + one;
+    float* ws_part = gated ? reinterpret_cast<float*>(base + 2 * (one + rs) + rd) : nullptr;
+    int run_chunks;
+    const int seg = plan_runs(d, true, &run_chunks);
+    if (seg > 1) {
+        const SeqDims r = as_runs(d, seg, run_chunks);
+        float* run_s = reinterpret_cast<float*>(base + 2 * one);
+        float* run_ds = reinterpret_cast<float*>(base + 2 * one + rs);
+        float* run_decay = reinterpret_cast<float*>(base + 2 * (one + rs));
+        if (launch_sweep_pair_ends(r, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
+            launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_s, run_decay, nullptr, false, stream) != hipSuccess ||
+            launch_run_carry(d.BH, seg, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true, stream) != hipSuccess ||
+            launch_sweep_pair(r, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess ||
+            launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+    } else
     if (d.BH > 0 && (has_tokens || grad_h0)) {
         if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
@@ -214,7 +293,7 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (fwd_fused_supported(d))
         return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
-    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
@@ -325,7 +404,7 @@ int hgrn2_state_sweep(const hgrn2_shape* shape, int32_t mode, const void* q, con
     if (need > 0 && (!chunk_states || chunk_states_bytes < need || ((uintptr_t)chunk_states & 255)))
         return HGRN2_ERR_WORKSPACE;
     if (d.BH == 0) return HGRN2_OK;
-    if (launch_sweep(d, static_cast<SweepMode>(mode), q, f, b_src, init_state, final_state, chunk_states,
+    if (launch_sweep(d, static_cast<SweepMode>(mode), q, f, b_src, init_state, final_state, chunk_states, nullptr,
                      static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;

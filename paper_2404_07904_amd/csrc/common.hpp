@@ -48,6 +48,22 @@ template <bool DENSE, int DK, int DV>
 __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int NC, int bh)
 {
     SeqView s;
+    if (lay.seg > 1) {
+        // run r of sequence bh / seg: N tokens (NC chunks) unless it is the last, shorter one
+        const int whole = bh / lay.seg, r = bh - whole * lay.seg;
+        const int nc_all = (lay.n_tokens + kChunk - 1) / kChunk;
+        s.N = min(N, lay.n_tokens - r * N);
+        s.NC = min(NC, nc_all - r * NC);
+        s.chunk0 = (size_t)whole * nc_all + (size_t)r * NC;
+        if constexpr (DENSE) {
+            s.off_k = ((size_t)whole * lay.n_tokens + (size_t)r * N) * DK;
+            s.off_v = ((size_t)whole * lay.n_tokens + (size_t)r * N) * DV;
+        } else {
+            s.off_k = lay.off_k(whole) + (size_t)r * N * lay.sn_k;
+            s.off_v = lay.off_v(whole) + (size_t)r * N * lay.sn_v;
+        }
+        return s;
+    }
     if constexpr (DENSE) {
         s.N = N; s.NC = NC;
         s.off_k = (size_t)bh * N * DK; s.off_v = (size_t)bh * N * DV;

@@ -220,7 +220,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
         f32x2 rf[RW];
         convert_rows<RW>(rf, rf_raw, c * C + RW * w, N, true, GATE_BF16, 1.0f);
-        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, 2 * lane, true, c * C + RW * w, N);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh / p.lay.seg % p.H) * DK, 2 * lane, true, c * C + RW * w, N);
         float run0 = 1.0f, run1 = 1.0f;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {

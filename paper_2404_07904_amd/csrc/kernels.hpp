@@ -24,6 +24,12 @@ struct TokenLayout {
     // equal-length batches.
     const int* vl = nullptr;
     int B = 0;
+    // Segmented sweeps: each of the sequences the strides describe is cut into `seg` runs of whole
+    // chunks that the sequential kernels treat as sequences of their own, `seg` per original one,
+    // numbered run-fastest.  The kernels' N and NC are then those of a full run; `n_tokens` keeps
+    // the length of the uncut sequence, whose last run may be shorter.
+    int seg = 1;
+    int n_tokens = 0;
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
     __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
 };
@@ -61,13 +67,24 @@ enum SweepMode {
 // (`final_state`, may be null) in plain fp32 [dk][dv].  `a_src` is f (modes 0/1) or q (mode 2);
 // `b_src` is v (modes 0/1) or grad_o (mode 2).
 hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
-                        const float* init_state, float* final_state, void* ws, hipStream_t stream);
+                        const float* init_state, float* final_state, void* ws, float* decay, hipStream_t stream);
 
 // Both sweeps of the backward pass (kSweepStateBwd into ws_state, kSweepGrad into ws_dstate) in
 // one launch.
 hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
                              const float* h0, const float* grad_hT, float* grad_h0, void* ws_state,
                              void* ws_dstate, hipStream_t stream);
+
+// Segmented sweeps.  A sweep with a null workspace walks every sequence from a zero state and
+// leaves the state after its last chunk in `final_state` and the per-channel product of all its
+// gates in `decay` ([BH][dk]); launch_sweep_pair_ends does so for both backward sweeps (one copy of
+// the gate products).  Called on the runs of segmented sequences (TokenLayout::seg), these give
+// launch_run_carry what it needs to turn run_state ([n_seq * seg][dk][dv], overwritten) into the
+// state entering each run, from which the ordinary sweeps then start run by run.
+hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                                  float* run_state, float* run_dstate, float* run_decay, hipStream_t stream);
+hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* carried_in, float* run_state,
+                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream);
 
 // Per-chunk forward read-out  O = tril(Q~ K~^T) V + (Q G) S_n.
 hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,

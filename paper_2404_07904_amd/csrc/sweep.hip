@@ -11,6 +11,12 @@
 // dS_{n+1}) and rounded to the operand type, to the workspace in MFMA-fragment order so that the
 // per-chunk kernels can load it straight into operand registers.  The contraction runs over time, so both operands are
 // staged in LDS token-contiguous (see common.hpp for the thread layout that makes this free).
+//
+// A batch of few, long sequences would leave most of the chip idle in such a walk.  The recurrence
+// is linear in the state, so a sequence can be cut into runs of whole chunks: a walk per run from
+// a zero state (no workspace writes) gives the run's own contribution A_r and the product D_r of
+// its gates, the short recurrence  S <- Diag(D_r) S + A_r  over the runs (run_carry_kernel) gives
+// the state entering every run, and the walk proper then starts run by run, all runs at once.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -23,6 +29,7 @@ struct SweepParams {
     const float* init;
     float* fin;
     void* ws;
+    float* decay;        // walks from zero (null ws): per-channel product of all gates of the sequence, [BH][dk], or null
     int BH, N, NC, n_tile, gate_bf16;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
@@ -39,7 +46,7 @@ struct SweepParams {
 #define HGRN2_STAMP(k) do { } while (0)
 #endif
 
-template <typename T, int DK, int DV, int TV, int MODE, bool DENSE>
+template <typename T, int DK, int DV, int TV, int MODE, bool DENSE, bool ENDS>
 __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 {
     constexpr int C = kChunk, RW = C / kWaves;
@@ -57,6 +64,8 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     float* tot = gam + DK;                       // [4][DK] per-wave block products
     float* hsc = tot + kWaves * DK;              // [DK] half-chunk decay folded into the stored fragments
 
+    // ENDS: the walk starts from a zero slab and hands nothing to the workspace; what it leaves is
+    // the slab after the last chunk and the product of all gates it passed, per channel.
     int bh, tile;
     xcd_map(block_id, p.n_tile, bh, tile);
     if (bh >= p.BH) return;
@@ -91,7 +100,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             float x = 0.0f;
-            if (p.init) {
+            if (!ENDS && p.init) {
                 const float* s0 = p.init + (size_t)bh * DK * DV;
                 x = TRANS ? s0[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)]
                           : s0[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32];
@@ -100,6 +109,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
         }
     }
 
+    float run_decay = 1.0f;      // ENDS: thread t < DK, gate product of channel t so far
     if (NC > 0) load_chunk(REVERSE ? NC - 1 : 0);
 
 #ifdef HGRN2_PHASE_TIMING
@@ -112,7 +122,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
         {
             const int row0 = n * C + RW * w;
             convert_rows<RW>(rf, raw_f, row0, N, a_act, gate_bf16, 1.0f);
-            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_a, a_act, row0, N);
+            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh / p.lay.seg % p.H) * DK, col_a, a_act, row0, N);
             if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, N, a_act, is_bf16_type<T>(), 0.0f);
             convert_rows<RW>(rb, raw_b, row0, N, b_act, is_bf16_type<T>(), 0.0f);
         }
@@ -174,8 +184,9 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 
         // ---- hand the slab as it stands (state entering / gradient leaving chunk n) to the workspace
         T* wsn = ws + (size_t)n * DK * DV;
+        if (ENDS && tid < DK) run_decay *= gam[tid];
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
+        for (int j = 0; j < (ENDS ? 0 : TPW); ++j) {
             const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -231,6 +242,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     if (lane == 0 && p.dbg)
         for (int k = 0; k < 8; ++k) p.dbg[((size_t)block_id * kWaves + w) * 8 + k] = ph[k];
 #endif
+    if (ENDS && tile == 0 && tid < DK && p.decay) p.decay[(size_t)bh * DK + tid] = run_decay;
     if (p.fin) {
         float* s1 = p.fin + (size_t)bh * DK * DV;
 #pragma unroll
@@ -245,36 +257,36 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     }
 }
 
-template <typename T, int DK, int DV, int TV, int MODE>
+template <typename T, int DK, int DV, int TV, int MODE, bool ENDS>
 __global__ __launch_bounds__(kThreads) void sweep_kernel(SweepParams p)
 {
-    if (p.dense) sweep_body<T, DK, DV, TV, MODE, true>(p, blockIdx.x);
-    else         sweep_body<T, DK, DV, TV, MODE, false>(p, blockIdx.x);
+    if (p.dense) sweep_body<T, DK, DV, TV, MODE, true, ENDS>(p, blockIdx.x);
+    else         sweep_body<T, DK, DV, TV, MODE, false, ENDS>(p, blockIdx.x);
 }
 
 // The two sweeps of the backward pass (forward states, reverse state gradients) are independent;
 // one launch runs both, the first half of the grid walking forwards and the second backwards, so
 // that two latency-bound sequential kernels share the chip instead of running one after the other.
-template <typename T, int DK, int DV, int TV>
+template <typename T, int DK, int DV, int TV, bool ENDS>
 __global__ __launch_bounds__(kThreads) void sweep_pair_kernel(SweepParams ps, SweepParams pg, int half)
 {
     if (ps.dense) {
-        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, true>(ps, blockIdx.x);
-        else                        sweep_body<T, DK, DV, TV, kSweepGrad, true>(pg, blockIdx.x - half);
+        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, true, ENDS>(ps, blockIdx.x);
+        else                        sweep_body<T, DK, DV, TV, kSweepGrad, true, ENDS>(pg, blockIdx.x - half);
     } else {
-        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, false>(ps, blockIdx.x);
-        else                        sweep_body<T, DK, DV, TV, kSweepGrad, false>(pg, blockIdx.x - half);
+        if ((int)blockIdx.x < half) sweep_body<T, DK, DV, TV, kSweepStateBwd, false, ENDS>(ps, blockIdx.x);
+        else                        sweep_body<T, DK, DV, TV, kSweepGrad, false, ENDS>(pg, blockIdx.x - half);
     }
 }
 
-template <typename T, int DK, int DV, int TV>
+template <typename T, int DK, int DV, int TV, bool ENDS>
 static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, const SweepParams& pg0, hipStream_t stream)
 {
     SweepParams ps = ps0, pg = pg0;
     ps.n_tile = pg.n_tile = DV / TV;
     constexpr int PC = kChunk + pad_elems<T>();
     const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
-    auto kern = sweep_pair_kernel<T, DK, DV, TV>;
+    auto kern = sweep_pair_kernel<T, DK, DV, TV, ENDS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -283,29 +295,29 @@ static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, cons
     return hipGetLastError();
 }
 
-template <typename T, int DK, int DV>
+template <typename T, int DK, int DV, bool ENDS>
 static hipError_t launch_pair_tv(const SeqDims& d, const SweepParams& ps, const SweepParams& pg, hipStream_t stream)
 {
     // The sweeps are bound by the element-wise work on the gates, which every column slab of a
     // sequence repeats: use the widest slab that still gives each of the 256 CUs a workgroup
     // (two sweeps share the grid).
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH < 48) return launch_pair_one<T, DK, DV, 32>(d, ps, pg, stream);
+        if (d.BH < 48) return launch_pair_one<T, DK, DV, 32, ENDS>(d, ps, pg, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH < 128) return launch_pair_one<T, DK, DV, 64>(d, ps, pg, stream);
+        if (d.BH < 128) return launch_pair_one<T, DK, DV, 64, ENDS>(d, ps, pg, stream);
     }
-    return launch_pair_one<T, DK, DV, DV>(d, ps, pg, stream);
+    return launch_pair_one<T, DK, DV, DV, ENDS>(d, ps, pg, stream);
 }
 
-template <typename T, int DK, int DV, int TV, int MODE>
+template <typename T, int DK, int DV, int TV, int MODE, bool ENDS>
 static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_t stream)
 {
     SweepParams p = p0;
     p.n_tile = DV / TV;
     constexpr int PC = kChunk + pad_elems<T>();
     const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
-    auto kern = sweep_kernel<T, DK, DV, TV, MODE>;
+    auto kern = sweep_kernel<T, DK, DV, TV, MODE, ENDS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -314,35 +326,42 @@ static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_
     return hipGetLastError();
 }
 
-template <typename T, int DK, int DV, int MODE>
+template <typename T, int DK, int DV, int MODE, bool ENDS>
 static hipError_t launch_tv(const SeqDims& d, const SweepParams& p, hipStream_t stream)
 {
     // Narrow slabs when there are few sequences, so that the sweep still covers the 256 CUs.
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH < 96) return launch_one<T, DK, DV, 32, MODE>(d, p, stream);
+        if (d.BH < 96) return launch_one<T, DK, DV, 32, MODE, ENDS>(d, p, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH < 256) return launch_one<T, DK, DV, 64, MODE>(d, p, stream);
+        if (d.BH < 256) return launch_one<T, DK, DV, 64, MODE, ENDS>(d, p, stream);
     }
-    return launch_one<T, DK, DV, DV, MODE>(d, p, stream);
+    return launch_one<T, DK, DV, DV, MODE, ENDS>(d, p, stream);
 }
 
-template <typename T, int MODE>
-static hipError_t launch_dims(const SeqDims& d, const SweepParams& p, hipStream_t stream)
+template <typename T, int MODE, bool ENDS>
+static hipError_t launch_dims_e(const SeqDims& d, const SweepParams& p, hipStream_t stream)
 {
-    if (d.dk == 128 && d.dv == 128) return launch_tv<T, 128, 128, MODE>(d, p, stream);
-    if (d.dk == 64 && d.dv == 64) return launch_tv<T, 64, 64, MODE>(d, p, stream);
-    if (d.dk == 128 && d.dv == 64) return launch_tv<T, 128, 64, MODE>(d, p, stream);
-    if (d.dk == 64 && d.dv == 128) return launch_tv<T, 64, 128, MODE>(d, p, stream);
+    if (d.dk == 128 && d.dv == 128) return launch_tv<T, 128, 128, MODE, ENDS>(d, p, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_tv<T, 64, 64, MODE, ENDS>(d, p, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_tv<T, 128, 64, MODE, ENDS>(d, p, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_tv<T, 64, 128, MODE, ENDS>(d, p, stream);
     return hipErrorInvalidValue;
 }
 
+// no workspace to fill: only the end state and the gate product are wanted
+template <typename T, int MODE>
+static hipError_t launch_dims(const SeqDims& d, const SweepParams& p, hipStream_t stream)
+{
+    return p.ws ? launch_dims_e<T, MODE, false>(d, p, stream) : launch_dims_e<T, MODE, true>(d, p, stream);
+}
+
 hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
-                        const float* init_state, float* final_state, void* ws, hipStream_t stream)
+                        const float* init_state, float* final_state, void* ws, float* decay, hipStream_t stream)
 {
     if (d.BH == 0) return hipSuccess;
     SweepParams p;
-    p.q = q; p.f = f; p.bsrc = b_src; p.init = init_state; p.fin = final_state; p.ws = ws;
+    p.q = q; p.f = f; p.bsrc = b_src; p.init = init_state; p.fin = final_state; p.ws = ws; p.decay = decay;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.n_tile = 1; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
     p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     if (d.io_bf16) {
@@ -364,16 +383,71 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
     if (d.BH == 0) return hipSuccess;
     if (!d.io_bf16) return hipErrorInvalidValue;
     SweepParams ps, pg;
+    ps.decay = pg.decay = nullptr;
     ps.q = nullptr; ps.f = f; ps.bsrc = v; ps.init = h0; ps.fin = nullptr; ps.ws = ws_state;
     pg.q = q; pg.f = f; pg.bsrc = grad_o; pg.init = grad_hT; pg.fin = grad_h0; pg.ws = ws_dstate;
     ps.BH = pg.BH = d.BH; ps.N = pg.N = d.N; ps.NC = pg.NC = d.NC; ps.n_tile = pg.n_tile = 1;
     ps.gate_bf16 = pg.gate_bf16 = d.gate_bf16 ? 1 : 0;
     ps.beta = pg.beta = d.beta; ps.H = pg.H = d.H; ps.lay = pg.lay = d.lay; ps.dense = pg.dense = d.dense() ? 1 : 0;
-    if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128>(d, ps, pg, stream);
-    if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64>(d, ps, pg, stream);
-    if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64>(d, ps, pg, stream);
-    if (d.dk == 64 && d.dv == 128) return launch_pair_tv<__bf16, 64, 128>(d, ps, pg, stream);
+    if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128, false>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64, false>(d, ps, pg, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64, false>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_pair_tv<__bf16, 64, 128, false>(d, ps, pg, stream);
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                                  float* run_state, float* run_dstate, float* run_decay, hipStream_t stream)
+{
+    if (d.BH == 0) return hipSuccess;
+    if (!d.io_bf16) return hipErrorInvalidValue;
+    SweepParams ps, pg;
+    ps.decay = run_decay; pg.decay = nullptr;        // both walks pass the same gates: one copy of their product
+    ps.q = nullptr; ps.f = f; ps.bsrc = v; ps.init = nullptr; ps.fin = run_state; ps.ws = nullptr;
+    pg.q = q; pg.f = f; pg.bsrc = grad_o; pg.init = nullptr; pg.fin = run_dstate; pg.ws = nullptr;
+    ps.BH = pg.BH = d.BH; ps.N = pg.N = d.N; ps.NC = pg.NC = d.NC; ps.n_tile = pg.n_tile = 1;
+    ps.gate_bf16 = pg.gate_bf16 = d.gate_bf16 ? 1 : 0;
+    ps.beta = pg.beta = d.beta; ps.H = pg.H = d.H; ps.lay = pg.lay = d.lay; ps.dense = pg.dense = d.dense() ? 1 : 0;
+    if (d.dk == 128 && d.dv == 128) return launch_pair_tv<__bf16, 128, 128, true>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_pair_tv<__bf16, 64, 64, true>(d, ps, pg, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_pair_tv<__bf16, 128, 64, true>(d, ps, pg, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_pair_tv<__bf16, 64, 128, true>(d, ps, pg, stream);
+    return hipErrorInvalidValue;
+}
+
+// ---- segmented sweeps: the state entering every run ------------------------------------------
+// run_state[s][r] holds what run r of sequence s adds (the slab a walk from zero leaves),
+// run_decay[s][r][k] the product of the run's gates.  Walking the runs in order (backwards for
+// the gradient) with  S <- Diag(decay_r) S + add_r  from the carried-in state gives the state
+// entering each run, which replaces add_r in place, and the state leaving the sequence.
+__global__ __launch_bounds__(256) void run_carry_kernel(const float* carried_in, float* run_state, const float* run_decay,
+                                                        float* carried_out, int seg, int dk, int dv, int reverse)
+{
+    const size_t per = (size_t)dk * dv;
+    const size_t e4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (e4 >= per) return;
+    const int s = blockIdx.y, k = (int)(e4 / dv);
+    f32x4 st = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (carried_in) st = *reinterpret_cast<const f32x4*>(carried_in + (size_t)s * per + e4);
+    for (int j = 0; j < seg; ++j) {
+        const size_t r = (size_t)s * seg + (reverse ? seg - 1 - j : j);
+        f32x4* slot = reinterpret_cast<f32x4*>(run_state + r * per + e4);
+        const f32x4 add = *slot;
+        const float g = run_decay[r * dk + k];
+        *slot = st;
+        st = st * g + add;
+    }
+    if (carried_out) *reinterpret_cast<f32x4*>(carried_out + (size_t)s * per + e4) = st;
+}
+
+hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* carried_in, float* run_state,
+                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream)
+{
+    if (n_seq == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
+    hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, n_seq), dim3(256), 0, stream, carried_in, run_state, run_decay,
+                       carried_out, seg, dk, dv, reverse ? 1 : 0);
+    return hipGetLastError();
 }
 
 size_t state_ws_bytes(const SeqDims& d)

@@ -52,6 +52,11 @@ def test_workspace_sizes():
     assert binding.hgrn2_fwd_workspace_bytes(shape(N=65)) == 2 * 3 * 2 * 64 * 64 * 2   # ragged: 2 chunks
     assert binding.hgrn2_fwd_workspace_bytes(shape(N=0)) == 0
     assert binding.hgrn2_fwd_workspace_bytes(shape(dk=96)) == 0
+    # few long sequences are walked in runs: per run an fp32 state and a decay vector on top
+    long = shape(B=2, H=16, N=16384, dk=128, dv=128)
+    one = 32 * 256 * 128 * 128 * 2
+    assert binding.hgrn2_fwd_workspace_bytes(long) == one + 32 * 8 * (128 * 128 + 128) * 4      # 8 runs forward
+    assert binding.hgrn2_bwd_workspace_bytes(long) == 2 * (one + 32 * 4 * 128 * 128 * 4) + 32 * 4 * 128 * 4   # 4 runs backward
 
 
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):

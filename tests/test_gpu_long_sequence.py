@@ -1,0 +1,97 @@
+"""Long sequences in a small batch: the kernels that walk a sequence chunk by chunk then see it cut
+into runs (a walk per run from a zero state, a carry over the runs, the walk proper run by run),
+so these shapes get parity cases of their own against the fp64 oracle: ragged and whole last
+chunks and runs, all four head-dimension pairs, both layouts, both gate storages, gates given and
+formed from pre-activations, with and without carried states, and the fp32 forward.
+Tolerance: max|x-y|/max|y| <= 2e-2 per tensor for bf16 tensors, 1e-4 for fp32 ones."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2404_07904_amd import binding, synth
+from gpu_util import TOL, check, dev, host
+
+pytestmark = pytest.mark.gpu
+BNHD = binding.HGRN2_LAYOUT_BNHD
+
+CASES = [
+    # B, H, N, dk, dv, layout, gate, states, lower bound
+    (1, 2, 4133, 128, 128, 0, "bf16", True, 0.9),
+    (2, 1, 4096, 64, 128, 1, "f32", False, 0.8),
+    (1, 3, 4100, 128, 64, 0, "f32", True, 0.95),
+    (2, 2, 4225, 64, 64, 1, "bf16", True, 0.5),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "B%dH%dN%d_%dx%d_l%d_%s" % c[:7])
+def test_long_sequence_fwd_bwd(case):
+    B, H, N, dk, dv, layout, gate_dtype, with_state, lb = case
+    print("\n[long] B=%d H=%d N=%d dk=%d dv=%d layout=%d gate=%s states=%s lb=%.2f" % case, flush=True)
+    w = synth.make_sequence(7100 + N, B, H, N, dk, dv, io_dtype="bf16", gate_dtype=gate_dtype, lb=lb,
+                            with_h0=with_state, with_dO=True, with_dhT=with_state)
+    put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
+    get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
+    q, f, v, dO = put(dev(w.q, "bf16")), put(dev(w.f, gate_dtype)), put(dev(w.v, "bf16")), put(dev(w.dO, "bf16"))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout)
+    gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout)
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    rq, rf, rv, rh = oracle.bwd(w.q, w.f, w.v, w.dO, w.h0, w.dhT)
+    check("o", get(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
+    check("dh0", host(gh0), rh, tol)
+
+
+def test_long_sequence_gated():
+    B, H, N, dk, dv = 1, 2, 4170, 128, 128
+    print("\n[long gated] B=%d H=%d N=%d dk=%d dv=%d" % (B, H, N, dk, dv), flush=True)
+    rng = np.random.default_rng(7301)
+    w = synth.make_sequence(7300, B, H, N, dk, dv, io_dtype="bf16", with_h0=True, with_dO=True, with_dhT=True)
+    z = synth.bf16_round((1.5 * rng.standard_normal((B, H, N, dk))).astype(np.float32))
+    beta = rng.uniform(0.6, 0.98, size=(H, dk)).astype(np.float32)
+    q, zd, v, dO = dev(w.q, "bf16"), dev(z, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+    bd = torch.from_numpy(beta).cuda()
+    o, hT = binding.hgrn2_fwd_gated(q, zd, bd, v, dev(w.h0))
+    gq, gz, gb, gv, gh0 = binding.hgrn2_bwd_gated(q, zd, bd, v, dO, dev(w.h0), dev(w.dhT), want_grad_h0=True)
+    torch.cuda.synchronize()
+    ro, rhT = oracle.fwd_gated(w.q, z, beta, w.v, w.h0)
+    rq, rz, rb, rv, rh = oracle.bwd_gated(w.q, z, beta, w.v, w.dO, w.h0, w.dhT)
+    tol = TOL["bf16"]
+    check("o", host(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", host(gq), rq, tol); check("dz", host(gz), rz, tol); check("dbeta", host(gb), rb, tol)
+    check("dv", host(gv), rv, tol); check("dh0", host(gh0), rh, tol)
+
+
+def test_long_sequence_fp32_forward():
+    B, H, N, dk, dv = 1, 2, 4160, 64, 64
+    print("\n[long fp32] B=%d H=%d N=%d dk=%d dv=%d" % (B, H, N, dk, dv), flush=True)
+    w = synth.make_sequence(7400, B, H, N, dk, dv, io_dtype="f32", lb=0.9, with_h0=True)
+    o, hT = binding.hgrn2_fwd(dev(w.q), dev(w.f), dev(w.v), dev(w.h0))
+    torch.cuda.synchronize()
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    check("o", host(o), ro, TOL["f32"]); check("hT", host(hT), rhT, TOL["f32"])
+
+
+def test_cut_and_uncut_walks_agree():
+    """31 chunks are walked in one piece, 32 in runs: the first 31 chunks of outputs of the longer
+    sequence see the same tokens, so the two must agree to the rounding of the stored states."""
+    B, H, dk, dv = 1, 4, 128, 128
+    print("\n[long boundary] 31 against 32 chunks", flush=True)
+    w = synth.make_sequence(7500, B, H, 32 * 64, dk, dv, io_dtype="bf16", lb=0.9, with_dO=True)
+    q, f, v, dO = dev(w.q, "bf16"), dev(w.f, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+    cut = lambda t: t[:, :, : 31 * 64].contiguous()
+    o32, _ = binding.hgrn2_fwd(q, f, v, None)
+    o31, _ = binding.hgrn2_fwd(cut(q), cut(f), cut(v), None)
+    torch.cuda.synchronize()
+    check("o", host(o32[:, :, : 31 * 64]), host(o31), 1e-2)
+    # the backward of the longer sequence with no gradient arriving at its last chunk
+    dO0 = dO.clone()
+    dO0[:, :, 31 * 64:] = 0
+    g32 = binding.hgrn2_bwd(q, f, v, dO0, None, None)
+    g31 = binding.hgrn2_bwd(cut(q), cut(f), cut(v), cut(dO), None, None)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dq", "df", "dv"), g32, g31):
+        check(name, host(a[:, :, : 31 * 64]), host(b), 1e-2)
