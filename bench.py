@@ -52,6 +52,7 @@ def parse():
     ap.add_argument("--no-varlen", action="store_true", help="skip the packed variable-length run")
     ap.add_argument("--no-handoff", action="store_true", help="skip the prefill -> decode hand-off run")
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
+    ap.add_argument("--no-long", action="store_true", help="skip the long-sequence shape (B=2, N=16384)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -233,6 +234,36 @@ def main():
                                        % synth.layer_lower_bound(args.layer),
                            "ms_per_step": round(dtg * 1e3, 4), "tokens_per_s": round(tokens / dtg, 1)}
         del zs, wsg
+
+    # ---- long sequences in a small batch: twice the tokens of the main shape in 32 sequences ----
+    if not args.no_long:
+        Bl, Nl = 2, 16384
+        gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 11)
+        rnd = lambda: torch.randn((Bl, H, Nl, D), generator=gen, device=dev).to(torch.bfloat16)
+        ql, vl_, dOl = rnd(), rnd(), rnd()
+        fl = (0.99 + 0.01 * torch.rand((Bl, H, Nl, D), generator=gen, device=dev)).to(torch.bfloat16)   # long-range layer: gates in [0.99, 1]
+        shl = binding.make_shape(ql, vl_, fl, 0, binding.HGRN2_LAYOUT_BHND)
+        wsl = torch.empty(binding.hgrn2_bwd_workspace_bytes(shl), dtype=torch.uint8, device=dev)
+        ol, gql, gfl, gvl = (torch.empty_like(ql) for _ in range(4))
+        hTl = torch.empty((Bl, H, D, D), dtype=torch.float32, device=dev)
+
+        def long_fwd(i):
+            binding.hgrn2_fwd(ql, fl, vl_, None, o=ol, hT=hTl, workspace=wsl)
+
+        def long_bwd(i):
+            binding.hgrn2_bwd(ql, fl, vl_, dOl, None, None, workspace=wsl, grad_q=gql, grad_f=gfl, grad_v=gvl)
+
+        for i in range(5):
+            long_fwd(i); long_bwd(i)
+        tf, tb = timed(long_fwd, reps=30), timed(long_bwd, reps=30)
+        io_long = 11 * Bl * H * Nl * D * 2          # q, f, v, o; q, f, v, dO, dq, df, dv
+        result["long_sequence"] = {"workload": "B=%d, H=%d, N=%d, d=%d, bf16, gates in [0.99, 1]; each sequence walked in runs"
+                                               % (Bl, H, Nl, D),
+                                   "fwd_ms": round(tf * 1e3, 4), "bwd_ms": round(tb * 1e3, 4),
+                                   "ms_per_step": round((tf + tb) * 1e3, 4),
+                                   "tokens_per_s": round(Bl * Nl / (tf + tb), 1),
+                                   "algorithmic_GBps": round(io_long / (tf + tb) / 1e9, 1)}
+        del ql, vl_, dOl, fl, wsl, ol, gql, gfl, gvl
 
     # ---- second workload: the element-wise HGRN1 recurrence at the same layer (width 2048) ----
     if not args.no_hgrn1:
