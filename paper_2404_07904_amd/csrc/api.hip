@@ -112,6 +112,56 @@ size_t run_decay_bytes(const SeqDims& d, bool backward)
     return seg > 1 ? round256((size_t)d.BH * seg * d.dk * sizeof(float)) : 0;
 }
 
+// A packed batch is cut the way an equal-length batch of its mean sequence length would be (the
+// host does not know the lengths): runs of `run_chunks` chunks (0: not cut), at most `R` of them.
+struct PackedRuns {
+    int run_chunks = 0, R = 0;
+    size_t table_bytes = 0;      // sequence table, then run table and first_run
+    size_t state_bytes = 0;      // per sweep: fp32 [R * H][dk][dv]
+    size_t decay_bytes = 0;      // fp32 [R * H][dk]
+};
+
+PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backward)
+{
+    PackedRuns p;
+    p.R = s->B;
+    p.table_bytes = round256(varlen_table_bytes(s->B));
+    if (s->B == 0) return p;
+    SeqDims mean = d;
+    mean.packed = false;
+    mean.NC = (int)(((long long)d.N / kChunk + s->B - 1) / s->B);
+    int rc;
+    if (plan_runs(mean, backward, &rc) <= 1) return p;
+    const long long bound = s->B + ((long long)d.N / kChunk + s->B) / rc + 1;       // >= sum_b ceil(NC_b / rc)
+    if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2) return p;
+    p.run_chunks = rc;
+    p.R = (int)bound;
+    p.table_bytes += round256(varlen_run_table_bytes(s->B, p.R));
+    p.state_bytes = round256((size_t)p.R * s->H * d.dk * d.dv * sizeof(float));
+    p.decay_bytes = round256((size_t)p.R * s->H * d.dk * sizeof(float));
+    return p;
+}
+
+// Builds the table(s) at the head of the workspace and points `d` at the one the kernels use;
+// returns first_run (null when the batch is not cut).
+hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const int32_t* cu_seqlens, void* workspace,
+                               SeqDims* d, const int** first_run, hipStream_t stream)
+{
+    int* seq_table = static_cast<int*>(workspace);
+    *first_run = nullptr;
+    d->lay.vl = seq_table;
+    hipError_t e = launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream);
+    if (e != hipSuccess || p.run_chunks == 0) return e;
+    int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
+    int* fr = run_table + 4 * ((size_t)p.R + 1);
+    e = launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream);
+    d->lay.vl = run_table;
+    d->lay.B = p.R;
+    d->BH = p.R * s->H;
+    *first_run = fr;
+    return e;
+}
+
 }   // namespace
 
 extern "C" {
@@ -262,14 +312,17 @@ size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, false, &d) != HGRN2_OK) return 0;
-    return round256(varlen_table_bytes(shape->B)) + round256(state_ws_bytes(d));
+    const PackedRuns p = plan_packed_runs(shape, d, false);
+    return p.table_bytes + round256(state_ws_bytes(d)) + p.state_bytes + p.decay_bytes;
 }
 
 size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
-    return round256(varlen_table_bytes(shape->B)) + 2 * round256(state_ws_bytes(d)) + round256(beta_partials_bytes(d));
+    const PackedRuns p = plan_packed_runs(shape, d, true);
+    return p.table_bytes + 2 * (round256(state_ws_bytes(d)) + p.state_bytes) + p.decay_bytes +
+           round256(beta_partials_bytes(d));
 }
 
 int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
@@ -287,10 +340,26 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
     if (!has_tokens && !hT) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    int* table = static_cast<int*>(workspace);
-    void* ws_s = static_cast<char*>(workspace) + round256(varlen_table_bytes(shape->B));
-    d.lay.vl = table;
-    if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    const PackedRuns pr = plan_packed_runs(shape, d, false);
+    const size_t one = round256(state_ws_bytes(d));
+    void* ws_s = static_cast<char*>(workspace) + pr.table_bytes;
+    const int* first_run;
+    if (build_packed_tables(shape, pr, cu_seqlens, workspace, &d, &first_run, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (first_run) {
+        // d now describes the runs: walk each from zero, carry the states over the runs of a sequence, walk again
+        float* run_state = reinterpret_cast<float*>(static_cast<char*>(ws_s) + one);
+        float* run_decay = reinterpret_cast<float*>(static_cast<char*>(ws_s) + one + pr.state_bytes);
+        if (launch_sweep(d, kSweepStateFwd, q, f, v, nullptr, run_state, nullptr, run_decay, stream) != hipSuccess ||
+            launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_state, run_decay, hT, false,
+                                    stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (fwd_fused_supported(d))
+            return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+        if (launch_sweep(d, kSweepStateFwd, q, f, v, run_state, nullptr, ws_s, nullptr, stream) != hipSuccess ||
+            launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        return HGRN2_OK;
+    }
     if (fwd_fused_supported(d))
         return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
     if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
@@ -322,13 +391,26 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
     if (!has_tokens && !grad_h0 && !beta) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    int* table = static_cast<int*>(workspace);
-    d.lay.vl = table;
+    const PackedRuns pr = plan_packed_runs(shape, d, true);
     const size_t one = round256(state_ws_bytes(d));
-    void* ws_s = static_cast<char*>(workspace) + round256(varlen_table_bytes(shape->B));
-    void* ws_ds = static_cast<char*>(ws_s) + one;
-    float* ws_part = beta ? reinterpret_cast<float*>(static_cast<char*>(ws_ds) + one) : nullptr;
-    if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    char* base = static_cast<char*>(workspace) + pr.table_bytes;
+    void* ws_s = base;
+    void* ws_ds = base + one;
+    float* ws_part = beta ? reinterpret_cast<float*>(base + 2 * (one + pr.state_bytes) + pr.decay_bytes) : nullptr;
+    const int* first_run;
+    if (build_packed_tables(shape, pr, cu_seqlens, workspace, &d, &first_run, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (first_run) {
+        float* run_s = reinterpret_cast<float*>(base + 2 * one);
+        float* run_ds = reinterpret_cast<float*>(base + 2 * one + pr.state_bytes);
+        float* run_decay = reinterpret_cast<float*>(base + 2 * (one + pr.state_bytes));
+        if (launch_sweep_pair_ends(d, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
+            launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_s, run_decay, nullptr, false,
+                                    stream) != hipSuccess ||
+            launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true,
+                                    stream) != hipSuccess ||
+            launch_sweep_pair(d, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+    } else
     if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     if (has_tokens &&

@@ -85,6 +85,11 @@ hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f
                                   float* run_state, float* run_dstate, float* run_decay, hipStream_t stream);
 hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* carried_in, float* run_state,
                             const float* run_decay, float* carried_out, bool reverse, hipStream_t stream);
+// The same for a packed batch cut by launch_varlen_run_table: sequence b of head h owns the runs
+// first_run[b] .. first_run[b + 1] - 1, whose states sit at [run * H + h].
+hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, int dv, const float* carried_in,
+                                   float* run_state, const float* run_decay, float* carried_out, bool reverse,
+                                   hipStream_t stream);
 
 // Per-chunk forward read-out  O = tril(Q~ K~^T) V + (Q G) S_n.
 hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,
@@ -137,6 +142,10 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
+// Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
+size_t varlen_run_table_bytes(int B, int R);
+hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
+                                   int* first_run, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);

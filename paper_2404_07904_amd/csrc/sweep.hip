@@ -421,16 +421,26 @@ hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f
 // the gradient) with  S <- Diag(decay_r) S + add_r  from the carried-in state gives the state
 // entering each run, which replaces add_r in place, and the state leaving the sequence.
 __global__ __launch_bounds__(256) void run_carry_kernel(const float* carried_in, float* run_state, const float* run_decay,
-                                                        float* carried_out, int seg, int dk, int dv, int reverse)
+                                                        float* carried_out, int seg, const int* first_run, int H,
+                                                        int dk, int dv, int reverse)
 {
     const size_t per = (size_t)dk * dv;
     const size_t e4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (e4 >= per) return;
     const int s = blockIdx.y, k = (int)(e4 / dv);
+    // runs of sequence s: `seg` consecutive slots, or (packed batch) those the table names, H slots apart
+    size_t slot0 = (size_t)s * seg, step = 1;
+    int n_runs = seg;
+    if (first_run) {
+        const int b = s / H, h = s - b * H;
+        slot0 = (size_t)first_run[b] * H + h;
+        step = H;
+        n_runs = first_run[b + 1] - first_run[b];
+    }
     f32x4 st = {0.0f, 0.0f, 0.0f, 0.0f};
     if (carried_in) st = *reinterpret_cast<const f32x4*>(carried_in + (size_t)s * per + e4);
-    for (int j = 0; j < seg; ++j) {
-        const size_t r = (size_t)s * seg + (reverse ? seg - 1 - j : j);
+    for (int j = 0; j < n_runs; ++j) {
+        const size_t r = slot0 + step * (reverse ? n_runs - 1 - j : j);
         f32x4* slot = reinterpret_cast<f32x4*>(run_state + r * per + e4);
         const f32x4 add = *slot;
         const float g = run_decay[r * dk + k];
@@ -446,7 +456,18 @@ hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* car
     if (n_seq == 0) return hipSuccess;
     const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
     hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, n_seq), dim3(256), 0, stream, carried_in, run_state, run_decay,
-                       carried_out, seg, dk, dv, reverse ? 1 : 0);
+                       carried_out, seg, static_cast<const int*>(nullptr), 1, dk, dv, reverse ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, int dv, const float* carried_in,
+                                   float* run_state, const float* run_decay, float* carried_out, bool reverse,
+                                   hipStream_t stream)
+{
+    if (B * H == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
+    hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, B * H), dim3(256), 0, stream, carried_in, run_state, run_decay,
+                       carried_out, 0, first_run, H, dk, dv, reverse ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -71,6 +71,55 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     }
 }
 
+// Long sequences of a packed batch are walked in runs of at most `run_chunks` chunks: the kernels
+// then get a table whose entries are the runs (same four arrays, R entries, those past the last
+// run empty), in which a run is a sequence like any other; only the carried states know which
+// runs make up a sequence, through first_run[b] = number of runs of the sequences before b
+// (B + 1 entries).  Runs are whole chunks, so the chunk counts of the run table add up as those of
+// the sequence table do.  The runs keep their order (no sorting by length: none is long).
+__global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int* seq_tab, int B, int T, int run_chunks,
+                                                                       int R, int* run_tab, int* first_run)
+{
+    __shared__ int part[kTabThreads];
+    const int n = B + 1, tid = threadIdx.x;
+    const int per = (n + kTabThreads - 1) / kTabThreads;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);
+    const int* start = seq_tab;
+    const int* len = seq_tab + n;
+    const int* before = seq_tab + 2 * n;
+    auto runs_of = [&](int b) {
+        const int nc = b < B ? (len[b] + kChunk - 1) / kChunk : 0;
+        return (nc + run_chunks - 1) / run_chunks;
+    };
+    int c = 0;
+    for (int b = lo; b < hi; ++b) c += runs_of(b);
+    part[tid] = c;
+    __syncthreads();
+    int first = 0;
+    for (int j = 0; j < tid; ++j) first += part[j];
+    const int m = R + 1, run_tokens = run_chunks * kChunk;
+    for (int b = lo; b < hi; ++b) {
+        first_run[b] = first;
+        const int nr = runs_of(b);
+        for (int k = 0; k < nr && first + k < R; ++k) {           // R bounds the runs of any batch of T tokens
+            const int r = first + k;
+            run_tab[r] = start[b] + k * run_tokens;
+            run_tab[m + r] = min(run_tokens, len[b] - k * run_tokens);
+            run_tab[2 * m + r] = before[b] + k * run_chunks;
+            run_tab[3 * m + r] = r;
+        }
+        first += nr;
+    }
+    __syncthreads();
+    const int used = min(first_run[B], R);
+    for (int r = used + tid; r <= R; r += kTabThreads) {           // empty entries, and entry R of every array
+        run_tab[r] = T;
+        run_tab[m + r] = 0;
+        run_tab[2 * m + r] = before[B];
+        run_tab[3 * m + r] = r;
+    }
+}
+
 // Zero fill as a kernel: a caller may have the stream under graph capture, where a memset node is
 // not an option.
 __global__ void zero_floats_kernel(float* dst, size_t n)
@@ -91,6 +140,16 @@ size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream)
 {
     hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table);
+    return hipGetLastError();
+}
+
+size_t varlen_run_table_bytes(int B, int R) { return varlen_table_bytes(R) + ((size_t)B + 1) * sizeof(int); }
+
+hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
+                                   int* first_run, hipStream_t stream)
+{
+    hipLaunchKernelGGL(varlen_run_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, seq_table, B, T, run_chunks, R,
+                       run_table, first_run);
     return hipGetLastError();
 }
 

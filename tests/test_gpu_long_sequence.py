@@ -95,3 +95,51 @@ def test_cut_and_uncut_walks_agree():
     torch.cuda.synchronize()
     for name, a, b in zip(("dq", "df", "dv"), g32, g31):
         check(name, host(a[:, :, : 31 * 64]), host(b), 1e-2)
+
+
+@pytest.mark.parametrize("lens,H,dk,dv,gated", [
+    ([3000, 700, 0, 4600], 2, 128, 128, False),
+    ([2112, 6100], 1, 64, 128, True),
+    ([5000, 1, 3333], 3, 64, 64, False),
+], ids=["4docs_128", "2docs_gated_64x128", "3docs_64"])
+def test_long_documents_in_a_packed_batch(lens, H, dk, dv, gated):
+    """Packed batches are cut as an equal-length batch of their mean length would be, so the long
+    documents here span several runs, the short ones one, the empty one none."""
+    B, T = len(lens), int(sum(lens))
+    print("\n[long packed] H=%d dk=%d dv=%d gated=%s lens=%s" % (H, dk, dv, gated, lens), flush=True)
+    rng = np.random.default_rng(7600 + T)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    w = synth.make_sequence(7600 + B, 1, H, T, dk, dv, io_dtype="bf16", lb=0.9, with_dO=True)
+    z = synth.bf16_round((1.5 * rng.standard_normal((1, H, T, dk))).astype(np.float32))
+    beta = rng.uniform(0.7, 0.98, size=(H, dk)).astype(np.float32)
+    gate_in = z if gated else w.f
+    pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
+    un = lambda t: host(t.permute(1, 0, 2))
+    h0 = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    dhT = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
+    cud = torch.from_numpy(cu).cuda()
+    bd = torch.from_numpy(beta).cuda() if gated else None
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    torch.cuda.synchronize()
+    ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
+    rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        sl = (slice(None), slice(None), slice(s, e))
+        if gated:
+            ob, hTb = oracle.fwd_gated(w.q[sl], z[sl], beta, w.v[sl], h0[b:b + 1])
+            gqb, ggb, gbb, gvb, gh0b = oracle.bwd_gated(w.q[sl], z[sl], beta, w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+            rb += gbb
+        else:
+            ob, hTb = oracle.fwd(w.q[sl], w.f[sl], w.v[sl], h0[b:b + 1])
+            gqb, ggb, gvb, gh0b = oracle.bwd(w.q[sl], w.f[sl], w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+        ro[:, s:e], rq[:, s:e], rg[:, s:e], rv[:, s:e] = ob[0], gqb[0], ggb[0], gvb[0]
+        rhT[b], rh0[b] = hTb[0], gh0b[0]
+    tol = TOL["bf16"]
+    check("o", un(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", un(res[0]), rq, tol); check("dgate", un(res[1]), rg, tol); check("dv", un(res[2]), rv, tol)
+    check("dh0", host(res[3]), rh0, tol)
+    if gated:
+        check("dbeta", host(res[4]), rb, tol)
