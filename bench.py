@@ -264,6 +264,31 @@ def main():
                                    "tokens_per_s": round(Bl * Nl / (tf + tb), 1),
                                    "algorithmic_GBps": round(io_long / (tf + tb) / 1e9, 1)}
         del ql, vl_, dOl, fl, wsl, ol, gql, gfl, gvl
+        # the same number of tokens as two documents of unequal length packed along the token axis
+        docs = [20000, 12768]
+        Tl = sum(docs)
+        rndp = lambda: torch.randn((Tl, H, D), generator=gen, device=dev).to(torch.bfloat16)
+        qp, vp, dOp = rndp(), rndp(), rndp()
+        fp = (0.99 + 0.01 * torch.rand((Tl, H, D), generator=gen, device=dev)).to(torch.bfloat16)
+        cup = torch.tensor(np.concatenate([[0], np.cumsum(docs)]).astype(np.int32), device=dev)
+        shp = binding.make_shape_varlen(qp, vp, fp, len(docs))
+        wsp = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shp), dtype=torch.uint8, device=dev)
+        op, gqp, gfp, gvp = (torch.empty_like(qp) for _ in range(4))
+        hTp = torch.empty((len(docs), H, D, D), dtype=torch.float32, device=dev)
+
+        def packed_fwd(i):
+            binding.hgrn2_fwd_varlen(qp, fp, vp, cup, None, o=op, hT=hTp, workspace=wsp)
+
+        def packed_bwd(i):
+            binding.hgrn2_bwd_varlen(qp, fp, vp, dOp, cup, None, None, workspace=wsp, grad_q=gqp, grad_f=gfp, grad_v=gvp)
+
+        for i in range(5):
+            packed_fwd(i); packed_bwd(i)
+        tpf, tpb = timed(packed_fwd, reps=30), timed(packed_bwd, reps=30)
+        result["long_sequence"]["packed"] = {"workload": "documents of %s tokens packed as [T][H][d]" % docs,
+                                             "fwd_ms": round(tpf * 1e3, 4), "bwd_ms": round(tpb * 1e3, 4),
+                                             "tokens_per_s": round(Tl / (tpf + tpb), 1)}
+        del qp, vp, dOp, fp, wsp, op, gqp, gfp, gvp
 
     # ---- second workload: the element-wise HGRN1 recurrence at the same layer (width 2048) ----
     if not args.no_hgrn1:
