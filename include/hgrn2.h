@@ -254,6 +254,9 @@ int hgrn1_bwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gat
  *   hgrn2_state_sweep: b_src is v (STATE_FWD, STATE_BWD) or grad_o (STATE_GRAD); q is read only
  *     in STATE_GRAD; init_state is h0 (or grad_hT), may be NULL = 0; final_state receives hT
  *     (or grad_h0), may be NULL.
+ * A stage call walks every sequence in one piece; hgrn2_fwd / hgrn2_bwd cut few, long sequences
+ * into runs that are walked at the same time (same results up to fp32 summation order), which is
+ * why their workspaces can be larger than the chunk_states buffers here.
  */
 typedef enum { HGRN2_SWEEP_STATE_FWD = 0, HGRN2_SWEEP_STATE_BWD = 1, HGRN2_SWEEP_STATE_GRAD = 2 } hgrn2_sweep_mode;
 
