@@ -135,3 +135,34 @@ def test_random_elementwise_recurrence(seed):
     check("y", host(y), ry, tol); check("hN", host(hN), rh, tol)
     check("df", host(gf), rf, tol); check("di", host(gi), ri, tol); check("do", host(go), ro, tol)
     check("dh0", host(gh0), rh0, tol)
+
+
+@pytest.mark.parametrize("seed", range(9300, 9306))
+def test_random_long_sequences(seed):
+    """Few sequences of 32 chunks or more: the sweeps and the single-pass forward walk them in runs
+    (uneven run counts, a shorter last run, a ragged last chunk)."""
+    rng = np.random.default_rng(seed)
+    dk, dv = (int(rng.choice([64, 128])) for _ in range(2))
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    N = int(rng.integers(2048, 5200))
+    layout = int(rng.integers(0, 2))
+    gate_dtype = str(rng.choice(["bf16", "f32"]))
+    with_state = bool(rng.integers(0, 2))
+    lb = float(rng.choice([0.5, 0.9, 0.97]))
+    print("\n[random long] seed=%d B=%d H=%d N=%d dk=%d dv=%d layout=%d gate=%s states=%s lb=%.2f"
+          % (seed, B, H, N, dk, dv, layout, gate_dtype, with_state, lb), flush=True)
+    w = synth.make_sequence(seed, B, H, N, dk, dv, io_dtype="bf16", gate_dtype=gate_dtype, lb=lb,
+                            with_h0=with_state, with_dO=True, with_dhT=with_state)
+    put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
+    get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
+    q, f, v, dO = put(dev(w.q, "bf16")), put(dev(w.f, gate_dtype)), put(dev(w.v, "bf16")), put(dev(w.dO, "bf16"))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout)
+    gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout)
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    rq, rf, rv, rh = oracle.bwd(w.q, w.f, w.v, w.dO, w.h0, w.dhT)
+    check("o", get(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
+    check("dh0", host(gh0), rh, tol)
