@@ -233,6 +233,21 @@ def main():
         result["gated"] = {"workload": "the same shape with z ~ N(0,1) (bf16) and beta = %.4f in place of f"
                                        % synth.layer_lower_bound(args.layer),
                            "ms_per_step": round(dtg * 1e3, 4), "tokens_per_s": round(tokens / dtg, 1)}
+        # ... and on token-major [B][N][H][d] tensors, the layout the layer's projections write
+        BNHD = binding.HGRN2_LAYOUT_BNHD
+        tm = lambda t: t.view(B, N, H, D)          # timing only: the same bytes read as [B][N][H][d]
+
+        def gated_step_token_major(i):
+            q, _, v, dO = sets[i % 2]
+            binding.hgrn2_fwd_gated(tm(q), tm(zs[i % 2]), beta, tm(v), None, o=tm(o), hT=hT, workspace=wsg, layout=BNHD)
+            binding.hgrn2_bwd_gated(tm(q), tm(zs[i % 2]), beta, tm(v), tm(dO), None, None, workspace=wsg, grad_q=tm(gq),
+                                    grad_z=tm(gf), grad_beta=gb, grad_v=tm(gv), layout=BNHD)
+
+        for i in range(10):
+            gated_step_token_major(i)
+        dtm = timed(gated_step_token_major, reps=50)
+        result["gated"]["token_major_ms_per_step"] = round(dtm * 1e3, 4)
+        result["gated"]["token_major_tokens_per_s"] = round(tokens / dtm, 1)
         del zs, wsg
 
     # ---- long sequences in a small batch: twice the tokens of the main shape in 32 sequences ----

@@ -593,21 +593,27 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     return hipErrorInvalidValue;
 }
 
+constexpr int kRedGroups = 16;      // groups of 64 threads per workgroup, each adding every 16th row of its share
+constexpr int kRedSlices = 8;       // workgroups that share the rows of one (head, 64 channels)
+
 size_t beta_partials_bytes(const SeqDims& d)
 {
-    return d.total_chunks() * kBwdWaves * d.dk * sizeof(float);
+    // the per-wave rows of every chunk slot, then the sums of the slices
+    if (d.total_chunks() == 0) return 0;
+    return (d.total_chunks() * kBwdWaves + (size_t)kRedSlices * d.H) * d.dk * sizeof(float);
 }
 
-// grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order: one
-// workgroup per (head, 64 channels); 16 groups of 64 threads each add every 16th partial row
-// (coalesced across the channels) and the 16 group sums are added in order.
-constexpr int kRedGroups = 16;
-__global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* grad_beta, int B,
+// grad_beta[h][a] = sum over batch, chunks and waves of the partial sums, in a fixed order.  First
+// pass: workgroup (head, 64 channels, slice) adds its share of the partial rows (the groups of 16
+// consecutive rows numbered slice, slice + 8, ... of every sequence; 16 groups of 64 threads take a
+// row each, coalesced across the channels, and the 16 group sums are added in order).  Second
+// pass: the slice sums are added in order.
+__global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* slice_sums, int B,
                                                                       int H, int NC, int dk, const int* vl)
 {
     __shared__ float part[kRedGroups][64];
     const int h = blockIdx.x / (dk / 64), a = 64 * (blockIdx.x % (dk / 64)) + (threadIdx.x & 63);
-    const int grp = threadIdx.x >> 6;
+    const int grp = threadIdx.x >> 6, slice = blockIdx.y;
     float s = 0.0f;
     for (int b = 0; b < B; ++b) {
         // partial rows of (batch, head): kBwdWaves per chunk, the chunks of a sequence and head together
@@ -619,8 +625,8 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
         }
         const int rows = nc * kBwdWaves;
         const float* pp = partials + first * kBwdWaves * dk + a;
-#pragma unroll 8
-        for (int i = grp; i < rows; i += kRedGroups) s += pp[(size_t)i * dk];
+#pragma unroll 4
+        for (int i = grp + kRedGroups * slice; i < rows; i += kRedGroups * kRedSlices) s += pp[(size_t)i * dk];
     }
     part[grp][threadIdx.x & 63] = s;
     __syncthreads();
@@ -628,16 +634,29 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
         float t = 0.0f;
 #pragma unroll
         for (int j = 0; j < kRedGroups; ++j) t += part[j][threadIdx.x];
-        grad_beta[(size_t)h * dk + a] = t;
+        slice_sums[((size_t)slice * H + h) * dk + a] = t;
     }
 }
 
-hipError_t reduce_beta_partials(const SeqDims& d, const float* beta_partials, float* grad_beta, hipStream_t stream)
+__global__ void reduce_beta_slices_kernel(const float* slice_sums, float* grad_beta, int n)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n) return;
+    float t = 0.0f;
+#pragma unroll
+    for (int j = 0; j < kRedSlices; ++j) t += slice_sums[(size_t)j * n + c];
+    grad_beta[c] = t;
+}
+
+hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream)
 {
     if (d.H * d.dk == 0) return hipSuccess;
-    const int B = d.BH / d.H;
-    hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64)), dim3(64 * kRedGroups), 0, stream, beta_partials,
-                       grad_beta, B, d.H, d.NC, d.dk, d.lay.vl);
+    const int B = d.BH / d.H, n = d.H * d.dk;
+    if (d.total_chunks() == 0) return launch_zero_floats(grad_beta, (size_t)n, stream);      // nothing contributes
+    float* slice_sums = beta_partials + d.total_chunks() * kBwdWaves * d.dk;
+    hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64), kRedSlices), dim3(64 * kRedGroups), 0, stream,
+                       beta_partials, slice_sums, B, d.H, d.NC, d.dk, d.lay.vl);
+    hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n);
     return hipGetLastError();
 }
 

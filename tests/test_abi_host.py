@@ -136,7 +136,7 @@ def test_gated_workspace_and_error_codes():
     lib = binding.lib()
     s = shape(B=8, H=16, N=2048, dk=128, dv=128)
     one = 8 * 16 * 32 * 128 * 128 * 2
-    partials = 8 * 16 * 32 * 8 * 128 * 4
+    partials = 8 * 16 * 32 * 8 * 128 * 4 + 8 * 16 * 128 * 4     # per-wave rows of every chunk, then 8 slice sums per head
     assert binding.hgrn2_bwd_gated_workspace_bytes(s) == 2 * one + partials
     assert binding.hgrn2_bwd_gated_workspace_bytes(shape(dk=96)) == 0
     big = 1 << 40
@@ -213,7 +213,7 @@ def test_varlen_workspace_and_error_codes():
     table = 256                                              # 4 * 7 ints, rounded up
     states = (1000 // 64 + 6) * 3 * 64 * 64 * 2              # worst split of 1000 tokens into 6 sequences
     assert binding.hgrn2_fwd_varlen_workspace_bytes(s) == table + states
-    partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4             # per-wave shares of grad_beta of every chunk slot
+    partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4 + 8 * 3 * 64 * 4     # per-wave shares of grad_beta of every chunk slot, then 8 slice sums per head
     assert binding.hgrn2_bwd_varlen_workspace_bytes(s) == table + 2 * states + partials
     assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0      # packed tokens are token-major
     # two documents in 32768 tokens of 16 heads are cut like 2 x 16384: 8 (4) runs of 32 (64) chunks per
@@ -227,7 +227,7 @@ def test_varlen_workspace_and_error_codes():
     Rb = 2 + (512 + 2) // 64 + 1
     assert binding.hgrn2_bwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rb + 1) * 4 + 3 * 4) + 2 * st
                                                             + 2 * Rb * 16 * 128 * 128 * 4 + Rb * 16 * 128 * 4
-                                                            + (32768 // 64 + 2) * 16 * 8 * 128 * 4)
+                                                            + (32768 // 64 + 2) * 16 * 8 * 128 * 4 + 8 * 16 * 128 * 4)
     big = 1 << 40
     fwd = lambda s_, cu=FAKE, q=FAKE, o=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_fwd_varlen(
         ctypes.byref(s_) if s_ is not None else None, cu, q, FAKE, None, FAKE, None, o, None, ws, n, None)
