@@ -17,7 +17,7 @@ def fresh(seed, B, H, N, d):
     return [dev(x, "bf16") for x in (w.q, w.f, w.v, w.dO)] + [dev(w.h0), dev(w.dhT)]
 
 
-@pytest.mark.parametrize("B,H,N,d", [(2, 3, 200, 64), (8, 9, 130, 128)])
+@pytest.mark.parametrize("B,H,N,d", [(2, 3, 200, 64), (8, 9, 130, 128), (1, 2, 2400, 128)])      # the last: sequences walked in runs
 def test_captured_forward_backward_replays(B, H, N, d):
     print("\n[graph] B=%d H=%d N=%d d=%d" % (B, H, N, d), flush=True)
     static = fresh(8600, B, H, N, d)
