@@ -75,10 +75,11 @@ size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 int plan_runs(const SeqDims& d, bool backward, int* run_chunks)
 {
     *run_chunks = d.NC;
-    // Measured on long sequences of 128-wide heads: the forward gains up to 64 sequences and with
-    // about 256 runs in all, down to runs of 4 chunks; the two backward sweeps share the chip, so
-    // they gain up to 32 sequences, with about 128 runs each and runs of 8 chunks or more.
-    if (d.packed || d.NC < 32 || d.BH == 0 || d.BH > (backward ? 32 : 64)) return 1;
+    // Measured with 64- and 128-wide heads: the forward gains from 16 chunks on, up to 64 sequences
+    // and with about 256 runs in all, down to runs of 4 chunks; the two backward sweeps share the
+    // chip, so they gain from 32 chunks on, up to 32 sequences, with about 128 runs each and runs
+    // of 8 chunks or more.
+    if (d.packed || d.NC < (backward ? 32 : 16) || d.BH == 0 || d.BH > (backward ? 32 : 64)) return 1;
     const int fill = ((backward ? 128 : 256) + d.BH - 1) / d.BH;
     const int by_length = d.NC / (backward ? 8 : 4);
     const int seg = fill < by_length ? fill : by_length;

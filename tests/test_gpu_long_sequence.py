@@ -75,26 +75,29 @@ def test_long_sequence_fp32_forward():
     check("o", host(o), ro, TOL["f32"]); check("hT", host(hT), rhT, TOL["f32"])
 
 
-def test_cut_and_uncut_walks_agree():
-    """31 chunks are walked in one piece, 32 in runs: the first 31 chunks of outputs of the longer
-    sequence see the same tokens, so the two must agree to the rounding of the stored states."""
+@pytest.mark.parametrize("n", [16, 32])
+def test_cut_and_uncut_walks_agree(n):
+    """The forward cuts sequences from 16 chunks on, the backward from 32: n - 1 chunks are walked in
+    one piece, n in runs.  The first n - 1 chunks of outputs of the longer sequence see the same
+    tokens, so the two must agree to the rounding of the stored states."""
     B, H, dk, dv = 1, 4, 128, 128
-    print("\n[long boundary] 31 against 32 chunks", flush=True)
-    w = synth.make_sequence(7500, B, H, 32 * 64, dk, dv, io_dtype="bf16", lb=0.9, with_dO=True)
+    print("\n[long boundary] %d against %d chunks" % (n - 1, n), flush=True)
+    w = synth.make_sequence(7500 + n, B, H, n * 64, dk, dv, io_dtype="bf16", lb=0.9, with_dO=True)
     q, f, v, dO = dev(w.q, "bf16"), dev(w.f, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
-    cut = lambda t: t[:, :, : 31 * 64].contiguous()
-    o32, _ = binding.hgrn2_fwd(q, f, v, None)
-    o31, _ = binding.hgrn2_fwd(cut(q), cut(f), cut(v), None)
+    m = (n - 1) * 64
+    cut = lambda t: t[:, :, :m].contiguous()
+    o_n, _ = binding.hgrn2_fwd(q, f, v, None)
+    o_m, _ = binding.hgrn2_fwd(cut(q), cut(f), cut(v), None)
     torch.cuda.synchronize()
-    check("o", host(o32[:, :, : 31 * 64]), host(o31), 1e-2)
+    check("o", host(o_n[:, :, :m]), host(o_m), 1e-2)
     # the backward of the longer sequence with no gradient arriving at its last chunk
     dO0 = dO.clone()
-    dO0[:, :, 31 * 64:] = 0
-    g32 = binding.hgrn2_bwd(q, f, v, dO0, None, None)
-    g31 = binding.hgrn2_bwd(cut(q), cut(f), cut(v), cut(dO), None, None)
+    dO0[:, :, m:] = 0
+    g_n = binding.hgrn2_bwd(q, f, v, dO0, None, None)
+    g_m = binding.hgrn2_bwd(cut(q), cut(f), cut(v), cut(dO), None, None)
     torch.cuda.synchronize()
-    for name, a, b in zip(("dq", "df", "dv"), g32, g31):
-        check(name, host(a[:, :, : 31 * 64]), host(b), 1e-2)
+    for name, a, b in zip(("dq", "df", "dv"), g_n, g_m):
+        check(name, host(a[:, :, :m]), host(b), 1e-2)
 
 
 @pytest.mark.parametrize("lens,H,dk,dv,gated", [
