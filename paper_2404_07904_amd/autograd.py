@@ -25,10 +25,10 @@ def _c(t):
 
 class _Hgrn2(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, f, v, h0, layout):
-        o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout)
+    def forward(ctx, q, f, v, h0, layout, chunk):
+        o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=chunk)
         ctx.save_for_backward(q, f, v, h0)
-        ctx.layout = layout
+        ctx.layout, ctx.chunk = layout, chunk
         ctx.set_materialize_grads(False)
         return o, hT
 
@@ -39,8 +39,8 @@ class _Hgrn2(torch.autograd.Function):
             grad_o = torch.zeros_like(v)
         want_h0 = h0 is not None and ctx.needs_input_grad[3]
         gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, _c(grad_o), h0, _c(grad_hT), want_grad_h0=want_h0,
-                                            layout=ctx.layout)
-        return gq, gf.to(f.dtype), gv, gh0, None
+                                            layout=ctx.layout, chunk=ctx.chunk)
+        return gq, gf.to(f.dtype), gv, gh0, None, None
 
 
 class _Hgrn2Gated(torch.autograd.Function):
@@ -120,10 +120,11 @@ class _Hgrn1Layer(torch.autograd.Function):
         return gf.to(zf.dtype), gi, go, gb, gh0
 
 
-def hgrn2_recurrence(q, f, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND):
+def hgrn2_recurrence(q, f, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND, chunk=0):
     """o, hT of Eq. 3 with the gates given.  q, f: [B,H,N,dk], v: [B,H,N,dv] (or [B,N,H,d] with
-    layout=HGRN2_LAYOUT_BNHD), contiguous; h0: fp32 [B,H,dk,dv] or None."""
-    return _Hgrn2.apply(q, f, v, h0, layout)
+    layout=HGRN2_LAYOUT_BNHD), contiguous; h0: fp32 [B,H,dk,dv] or None.  chunk=16 selects the
+    small-gate mode of the library (reference rows every 16 tokens, four times the work)."""
+    return _Hgrn2.apply(q, f, v, h0, layout, chunk)
 
 
 def hgrn2_recurrence_gated(q, z, beta, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND):

@@ -280,11 +280,12 @@ def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta
     return (gq, gf, gv, gh0) if beta is None else (gq, gf, gv, gh0, gb)
 
 
-def hgrn2_min_gate_product(f, beta=None, layout=HGRN2_LAYOUT_BHND):
-    """Smallest product of one channel's gates over a half chunk (32 tokens) in f [B,H,N,dk] (or
-    [B,N,H,dk]); a one-element fp32 device tensor.  The chunkwise passes are exact while it
-    exceeds 2**-100.  With beta [H,dk], f holds pre-activations (Eq. 2)."""
-    shape = make_shape(f, f, f, 0, layout)
+def hgrn2_min_gate_product(f, beta=None, layout=HGRN2_LAYOUT_BHND, chunk=0):
+    """Smallest product of one channel's gates over a half chunk (32 tokens; 8 with chunk=16, the
+    small-gate mode) in f [B,H,N,dk] (or [B,N,H,dk]); a one-element fp32 device tensor.  The
+    chunkwise passes are exact while it exceeds 2**-100.  With beta [H,dk], f holds
+    pre-activations (Eq. 2)."""
+    shape = make_shape(f, f, f, chunk, layout)
     out = torch.empty((1,), dtype=torch.float32, device=f.device)
     rc = lib().hgrn2_min_gate_product(ctypes.byref(shape), _ptr(f), _ptr(beta), _ptr(out), _stream())
     if rc != 0:

@@ -12,8 +12,9 @@ namespace {
 bool dtype_ok(int32_t t) { return t == HGRN2_F32 || t == HGRN2_BF16; }
 bool dim_ok(int32_t d) { return d == 64 || d == 128; }
 
-// Validates a shape; on success fills `d`.
-int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = false)
+// Validates a shape; on success fills `d`.  `fine_ok`: the entry point also takes chunk = 16, the
+// small-gate mode, in which it runs on sequences spread to four times their length.
+int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = false, bool fine_ok = false)
 {
     if (!s) return HGRN2_ERR_NULL;
     if (s->B < 0 || s->H < 0 || s->N < 0 || s->dk <= 0 || s->dv <= 0 || s->chunk < 0) return HGRN2_ERR_SHAPE;
@@ -24,7 +25,11 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
     if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
     if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
-    if (s->chunk != 0 && s->chunk != kChunk) return HGRN2_ERR_UNSUPPORTED;
+    if (s->chunk == kFineChunk && fine_ok) {
+        if (s->N > INT_MAX / 8 || bh * (nc * 4 + 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;      // the spread sequences must pass this check too
+    } else if (s->chunk != 0 && s->chunk != kChunk) {
+        return HGRN2_ERR_UNSUPPORTED;
+    }
     if (backward && s->io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
     d->BH = (int)bh;
     d->N = s->N;
@@ -163,6 +168,24 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     return e;
 }
 
+// ---- small-gate mode: the same passes on spread sequences (spread.hip) -------------------------
+bool fine_mode(const hgrn2_shape* s) { return s && s->chunk == kFineChunk; }
+
+hgrn2_shape spread_shape(const hgrn2_shape& s)
+{
+    hgrn2_shape e = s;
+    e.N = spread_tokens(s.N);
+    e.chunk = 0;
+    e.layout = HGRN2_LAYOUT_BHND;
+    return e;
+}
+
+// bytes of one spread tensor of `width` channels
+size_t spread_bytes(const hgrn2_shape& e, int width, bool bf16)
+{
+    return round256((size_t)e.B * e.H * e.N * width * (bf16 ? 2 : 4));
+}
+
 }   // namespace
 
 extern "C" {
@@ -170,15 +193,103 @@ extern "C" {
 size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape(shape, false, &d) != HGRN2_OK) return 0;
+    if (check_shape(shape, false, &d, false, true) != HGRN2_OK) return 0;
+    if (fine_mode(shape)) {
+        // spread q, f, v, o, then what the forward needs on the spread shape
+        const hgrn2_shape e = spread_shape(*shape);
+        return spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) + 2 * spread_bytes(e, d.dv, d.io_bf16) +
+               hgrn2_fwd_workspace_bytes(&e);
+    }
     return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
 }
 
 size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
+    if (fine_mode(shape)) {
+        // spread q, grad_q, grad_f; f; v, grad_o, grad_v; then what the backward needs on the spread shape
+        const hgrn2_shape e = spread_shape(*shape);
+        return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
+               3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_workspace_bytes(&e);
+    }
     return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true);
+}
+
+static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                    const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                    const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                    void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+// Small-gate mode of the forward pass: spread the inputs, run the pass on the spread shape, gather o.
+static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0, void* o,
+                    float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, false, &d, false, true);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)d.BH * d.N > 0;
+    if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
+    const size_t need = hgrn2_fwd_workspace_bytes(shape);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const hgrn2_shape e = spread_shape(*shape);
+    char* at = static_cast<char*>(workspace);
+    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
+    void* qs = take(spread_bytes(e, d.dk, d.io_bf16));
+    void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
+    void* vs = take(spread_bytes(e, d.dv, d.io_bf16));
+    void* os = take(spread_bytes(e, d.dv, d.io_bf16));
+    if (launch_spread(d, true, d.io_bf16, false, q, qs, stream) != hipSuccess ||
+        launch_spread(d, true, d.gate_bf16, true, f, fs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, false, v, vs, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    const int inner = fwd_impl(&e, qs, fs, nullptr, false, vs, h0, os, hT, at, workspace_bytes - (size_t)(at - static_cast<char*>(workspace)),
+                               hip_stream);
+    if (inner != HGRN2_OK) return inner;
+    return launch_gather(d, false, d.io_bf16, os, o, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+}
+
+// Small-gate mode of the backward pass.
+static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+                    const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v, float* grad_h0,
+                    void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d, false, true);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = (size_t)d.BH * d.N > 0;
+    if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
+    const size_t need = hgrn2_bwd_workspace_bytes(shape);
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const hgrn2_shape e = spread_shape(*shape);
+    char* at = static_cast<char*>(workspace);
+    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
+    const size_t ek = spread_bytes(e, d.dk, d.io_bf16), ev = spread_bytes(e, d.dv, d.io_bf16);
+    void* qs = take(ek);
+    void* gqs = take(ek);
+    void* gfs = take(ek);
+    void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
+    void* vs = take(ev);
+    void* gos = take(ev);
+    void* gvs = take(ev);
+    if (launch_spread(d, true, d.io_bf16, false, q, qs, stream) != hipSuccess ||
+        launch_spread(d, true, d.gate_bf16, true, f, fs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, false, v, vs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, false, grad_o, gos, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    const int inner = bwd_impl(&e, qs, fs, nullptr, false, vs, h0, gos, grad_hT, gqs, gfs, nullptr, gvs, grad_h0, at,
+                               workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
+    if (inner != HGRN2_OK) return inner;
+    if (launch_gather(d, true, d.io_bf16, gqs, grad_q, stream) != hipSuccess ||
+        launch_gather(d, true, d.io_bf16, gfs, grad_f, stream) != hipSuccess ||
+        launch_gather(d, false, d.io_bf16, gvs, grad_v, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
 }
 
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
@@ -186,6 +297,8 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream)
 {
+    if (fine_mode(shape))
+        return gated ? HGRN2_ERR_UNSUPPORTED : fwd_fine(shape, q, f, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape(shape, false, &d);
     if (rc != HGRN2_OK) return rc;
@@ -249,6 +362,10 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                     size_t workspace_bytes, void* hip_stream)
 {
+    if (fine_mode(shape))
+        return gated ? HGRN2_ERR_UNSUPPORTED
+                     : bwd_fine(shape, q, f, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_v, grad_h0, workspace,
+                                workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape(shape, true, &d);
     if (rc != HGRN2_OK) return rc;
@@ -425,12 +542,13 @@ int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float*
                            void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, false, &d);
+    const int rc = check_shape(shape, false, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     if (!min_product) return HGRN2_ERR_NULL;
     if ((size_t)d.BH * d.N > 0 && !f) return HGRN2_ERR_NULL;
     d.beta = beta;
-    if (launch_min_gate_product(d, f, min_product, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    if (launch_min_gate_product(d, (fine_mode(shape) ? kFineChunk : kChunk) / 2, f, min_product,
+                                static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }

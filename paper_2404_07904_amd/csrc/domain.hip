@@ -4,7 +4,8 @@
 // 2^-100.  This kernel reads the gates once and returns the smallest such half-chunk product of
 // the whole call, so that a caller can check its inputs against that bound:
 //     min over (b, h, chunk n, half s, channel a) of  prod_{t in half s of chunk n} f[b, h, t, a]
-// One wave per (sequence, half chunk): a channel pair per lane, 32 coalesced rows, a butterfly
+// (with reference rows every 16 tokens the windows are 8 tokens long instead of 32).
+// One wave per (sequence, window): a channel pair per lane, coalesced rows, a butterfly
 // minimum over the lanes, one atomic minimum per wave (non-negative floats order like their bit
 // patterns, so the integer atomic serves).
 #include "common.hpp"
@@ -16,7 +17,7 @@ struct DomainParams {
     const void* f;
     const float* beta;
     float* out;
-    int BH, N, NC, dk, gate_bf16, H;
+    int BH, N, n_win, window, dk, gate_bf16, H;
     TokenLayout lay;
 };
 
@@ -25,18 +26,18 @@ __global__ void domain_init_kernel(float* out) { *out = 1.0f; }
 __global__ __launch_bounds__(256) void domain_min_kernel(DomainParams p)
 {
     const int lane = threadIdx.x & 63;
-    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);      // (sequence, half chunk)
-    const long long n_waves = (long long)p.BH * p.NC * 2;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);      // (sequence, window)
+    const long long n_waves = (long long)p.BH * p.n_win;
     if (wave >= n_waves) return;
-    const int bh = (int)(wave / (2 * p.NC)), hc = (int)(wave % (2 * p.NC));
-    const int row0 = hc * (kChunk / 2);
+    const int bh = (int)(wave / p.n_win), hc = (int)(wave % p.n_win);
+    const int row0 = hc * p.window;
     const bool active = 2 * lane < p.dk;
     const int col = active ? 2 * lane : 0;
     const size_t seq = p.lay.off_k(bh);
     f32x2 b = {0.0f, 0.0f};
     if (p.beta) b = *reinterpret_cast<const f32x2*>(p.beta + (size_t)(bh % p.H) * p.dk + col);
     float p0 = 1.0f, p1 = 1.0f;
-    for (int i = 0; i < kChunk / 2; ++i) {
+    for (int i = 0; i < p.window; ++i) {
         const int row = row0 + i;
         if (row >= p.N) break;                                  // uniform over the wave
         f32x2 g = load_pair(p.f, seq + (size_t)row * p.lay.sn_k + col, p.gate_bf16 != 0);
@@ -50,13 +51,14 @@ __global__ __launch_bounds__(256) void domain_min_kernel(DomainParams p)
     if (lane == 0) atomicMin(reinterpret_cast<int*>(p.out), __float_as_int(m));
 }
 
-hipError_t launch_min_gate_product(const SeqDims& d, const void* f, float* out, hipStream_t stream)
+hipError_t launch_min_gate_product(const SeqDims& d, int window, const void* f, float* out, hipStream_t stream)
 {
     hipLaunchKernelGGL(domain_init_kernel, dim3(1), dim3(1), 0, stream, out);
-    const long long n_waves = (long long)d.BH * d.NC * 2;
+    const int n_win = (d.N + window - 1) / window;
+    const long long n_waves = (long long)d.BH * n_win;
     if (n_waves > 0) {
         DomainParams p;
-        p.f = f; p.beta = d.beta; p.out = out; p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.dk = d.dk;
+        p.f = f; p.beta = d.beta; p.out = out; p.BH = d.BH; p.N = d.N; p.n_win = n_win; p.window = window; p.dk = d.dk;
         p.gate_bf16 = d.gate_bf16 ? 1 : 0; p.H = d.H; p.lay = d.lay;
         hipLaunchKernelGGL(domain_min_kernel, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, stream, p);
     }

@@ -10,6 +10,7 @@ namespace hgrn2 {
 
 // Compile-time chunk length of the chunkwise kernels.
 constexpr int kChunk = 64;
+constexpr int kFineChunk = 16;     // spacing of the reference rows in the small-gate mode (see spread.hip)
 
 // Where token (b, h, n) of q / f (channel count dk) and of v / o (dv) starts, in elements:
 // b * sb + h * sh + n * sn.  [B][H][N][d] has sb = H N d, sh = N d, sn = d; [B][N][H][d] (what a
@@ -131,9 +132,11 @@ hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, 
                             const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
                             void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream);
 
-// Smallest product of the gates of one channel over a half chunk (32 tokens), over the whole call:
-// what the exactness of the chunkwise kernels depends on.  `out`: one float on the device.
-hipError_t launch_min_gate_product(const SeqDims& d, const void* f, float* out, hipStream_t stream);
+// Smallest product of the gates of one channel over `window` consecutive tokens (windows aligned at
+// multiples of `window` in every sequence), over the whole call: what the exactness of the chunkwise
+// kernels depends on, with window = half a chunk (32; 8 in the small-gate mode).  `out`: one float
+// on the device.
+hipError_t launch_min_gate_product(const SeqDims& d, int window, const void* f, float* out, hipStream_t stream);
 
 // Bytes of one per-chunk state set in the workspace.
 size_t state_ws_bytes(const SeqDims& d);
@@ -143,6 +146,16 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
+// Small-gate mode (spread.hip): every block of kFineChunk tokens becomes a chunk of its own, padded
+// with tokens that change nothing.  spread_tokens(N) is the length of the spread sequence;
+// launch_spread copies a caller's tensor (q, f: key_side; v, o, gradients alike) into a dense
+// [BH][spread_tokens(N)][d] one, the filler being 0, or 1 for the gates; launch_gather copies the
+// real tokens of such a tensor back into a caller's tensor.  `d` describes the caller's tensors.
+int spread_tokens(int N);
+hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, bool is_gate, const void* src, void* dst,
+                         hipStream_t stream);
+hipError_t launch_gather(const SeqDims& d, bool key_side, bool bf16, const void* src, void* dst, hipStream_t stream);
+
 // Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
 size_t varlen_run_table_bytes(int B, int R);
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,

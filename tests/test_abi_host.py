@@ -59,6 +59,26 @@ def test_workspace_sizes():
     assert binding.hgrn2_bwd_workspace_bytes(long) == 2 * (one + 32 * 4 * 128 * 128 * 4) + 32 * 4 * 128 * 4   # 4 runs backward
 
 
+def test_small_gate_mode_workspace_and_support():
+    """chunk = 16: four (seven) spread tensors, then the workspace of the pass on the spread shape."""
+    s = shape(B=2, H=3, N=200, dk=64, dv=128, chunk=16)
+    spread = 2 * 3 * (13 * 64)                                  # 13 blocks of 16 tokens, a chunk each
+    inner = shape(B=2, H=3, N=13 * 64, dk=64, dv=128)
+    assert binding.hgrn2_fwd_workspace_bytes(s) == spread * (64 + 64 + 128 + 128) * 2 + binding.hgrn2_fwd_workspace_bytes(inner)
+    assert binding.hgrn2_bwd_workspace_bytes(s) == spread * (4 * 64 + 3 * 128) * 2 + binding.hgrn2_bwd_workspace_bytes(inner)
+    lib = binding.lib()
+    sp = ctypes.byref(s)
+    big = 1 << 40
+    # not offered with the gate formed in the kernels, for packed batches or for the stage calls
+    assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
+    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == 0
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=2, H=3, N=200, layout=1, chunk=16)) == 0
+    assert lib.hgrn2_state_sweep(sp, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_UNSUP
+    assert lib.hgrn2_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1024, None) == E_WS
+    assert lib.hgrn2_fwd(sp, None, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL
+    assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=32)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
+
+
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):
     return binding.lib().hgrn2_fwd(ctypes.byref(s) if s is not None else None, q, f, v, h0, o, hT, ws, ws_bytes, None)
 
