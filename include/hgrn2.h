@@ -28,11 +28,11 @@
  *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
  *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
  *     intra-chunk terms degrade smoothly (they stay finite) instead of failing.
- *     Small-gate mode: with chunk = 16, hgrn2_fwd and hgrn2_bwd place their reference rows every
- *     16 tokens instead of every 64, and the bound applies to the product of 8 consecutive gates
- *     (guaranteed for f >= 1.8e-4).  The passes then run on sequences spread to four times their
- *     length: about six times the time, and a workspace that also holds the spread tensors.
- *     hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     Small-gate mode: with chunk = 16, hgrn2_fwd, hgrn2_bwd and their _gated forms place their
+ *     reference rows every 16 tokens instead of every 64, and the bound applies to the product
+ *     of 8 consecutive gates (guaranteed for f >= 1.8e-4).  The passes then run on sequences
+ *     spread to four times their length: about six times the time, and a workspace that also
+ *     holds the spread tensors.  hgrn2_min_gate_product tells which mode a set of gates needs.
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 16 where stated; any
  *     B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.

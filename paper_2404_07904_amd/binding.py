@@ -190,10 +190,10 @@ def hgrn2_bwd_gated_workspace_bytes(shape: hgrn2_shape) -> int:
 
 
 def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, workspace=None,
-                    layout=HGRN2_LAYOUT_BHND):
+                    layout=HGRN2_LAYOUT_BHND, chunk=0):
     """hgrn2_fwd with the gate f = beta + (1 - beta) sigmoid(z) formed inside the kernels.
     z: [B,H,N,dk]; beta: fp32 [H,dk]."""
-    shape = make_shape(q, v, z, 0, layout)
+    shape = make_shape(q, v, z, chunk, layout)
     assert beta.dtype == torch.float32 and tuple(beta.shape) == (shape.H, shape.dk)
     if o is None:
         o = torch.empty_like(v)
@@ -209,9 +209,9 @@ def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, wo
 
 def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
                     grad_q=None, grad_z=None, grad_beta=None, grad_v=None, grad_h0=None,
-                    layout=HGRN2_LAYOUT_BHND):
+                    layout=HGRN2_LAYOUT_BHND, chunk=0):
     """grad_q, grad_z, grad_beta, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
-    shape = make_shape(q, v, z, 0, layout)
+    shape = make_shape(q, v, z, chunk, layout)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_z = torch.empty_like(q) if grad_z is None else grad_z
     grad_v = torch.empty_like(v) if grad_v is None else grad_v

@@ -225,14 +225,14 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     size_t workspace_bytes, void* hip_stream);
 
 // Small-gate mode of the forward pass: spread the inputs, run the pass on the spread shape, gather o.
-static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0, void* o,
-                    float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
+static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated, const void* v,
+                    const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape(shape, false, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
-    if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
+    if (has_tokens && (!q || !f || !v || !o || (gated && !beta))) return HGRN2_ERR_NULL;
     const size_t need = hgrn2_fwd_workspace_bytes(shape);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -243,27 +243,29 @@ static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, cons
     void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
     void* vs = take(spread_bytes(e, d.dv, d.io_bf16));
     void* os = take(spread_bytes(e, d.dv, d.io_bf16));
-    if (launch_spread(d, true, d.io_bf16, false, q, qs, stream) != hipSuccess ||
-        launch_spread(d, true, d.gate_bf16, true, f, fs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, false, v, vs, stream) != hipSuccess)
+    if (launch_spread(d, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
+        launch_spread(d, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
-    const int inner = fwd_impl(&e, qs, fs, nullptr, false, vs, h0, os, hT, at, workspace_bytes - (size_t)(at - static_cast<char*>(workspace)),
+    const int inner = fwd_impl(&e, qs, fs, beta, gated, vs, h0, os, hT, at, workspace_bytes - (size_t)(at - static_cast<char*>(workspace)),
                                hip_stream);
     if (inner != HGRN2_OK) return inner;
     return launch_gather(d, false, d.io_bf16, os, o, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
 }
 
 // Small-gate mode of the backward pass.
-static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
-                    const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v, float* grad_h0,
-                    void* workspace, size_t workspace_bytes, void* hip_stream)
+static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated, const void* v,
+                    const float* h0, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f,
+                    float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
 {
     SeqDims d;
     const int rc = check_shape(shape, true, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
-    const size_t need = hgrn2_bwd_workspace_bytes(shape);
+    if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
+    const size_t need = gated ? hgrn2_bwd_gated_workspace_bytes(shape) : hgrn2_bwd_workspace_bytes(shape);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const hgrn2_shape e = spread_shape(*shape);
@@ -277,12 +279,13 @@ static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, cons
     void* vs = take(ev);
     void* gos = take(ev);
     void* gvs = take(ev);
-    if (launch_spread(d, true, d.io_bf16, false, q, qs, stream) != hipSuccess ||
-        launch_spread(d, true, d.gate_bf16, true, f, fs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, false, v, vs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, false, grad_o, gos, stream) != hipSuccess)
+    if (launch_spread(d, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
+        launch_spread(d, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess ||
+        launch_spread(d, false, d.io_bf16, kFillZero, grad_o, gos, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
-    const int inner = bwd_impl(&e, qs, fs, nullptr, false, vs, h0, gos, grad_hT, gqs, gfs, nullptr, gvs, grad_h0, at,
+    // the filler rows add nothing to grad_beta: their gate is exactly 1, and its share carries the factor 1 - f
+    const int inner = bwd_impl(&e, qs, fs, beta, gated, vs, h0, gos, grad_hT, gqs, gfs, grad_beta, gvs, grad_h0, at,
                                workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
     if (inner != HGRN2_OK) return inner;
     if (launch_gather(d, true, d.io_bf16, gqs, grad_q, stream) != hipSuccess ||
@@ -297,8 +300,7 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream)
 {
-    if (fine_mode(shape))
-        return gated ? HGRN2_ERR_UNSUPPORTED : fwd_fine(shape, q, f, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
+    if (fine_mode(shape)) return fwd_fine(shape, q, f, beta, gated, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape(shape, false, &d);
     if (rc != HGRN2_OK) return rc;
@@ -351,7 +353,12 @@ int hgrn2_fwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
+    if (fine_mode(shape)) {
+        const hgrn2_shape e = spread_shape(*shape);
+        return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
+               3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_gated_workspace_bytes(&e);
+    }
     return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true) +
            round256(beta_partials_bytes(d));
 }
@@ -363,9 +370,8 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     size_t workspace_bytes, void* hip_stream)
 {
     if (fine_mode(shape))
-        return gated ? HGRN2_ERR_UNSUPPORTED
-                     : bwd_fine(shape, q, f, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_v, grad_h0, workspace,
-                                workspace_bytes, hip_stream);
+        return bwd_fine(shape, q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                        workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape(shape, true, &d);
     if (rc != HGRN2_OK) return rc;

@@ -149,10 +149,11 @@ size_t varlen_table_bytes(int B);
 // Small-gate mode (spread.hip): every block of kFineChunk tokens becomes a chunk of its own, padded
 // with tokens that change nothing.  spread_tokens(N) is the length of the spread sequence;
 // launch_spread copies a caller's tensor (q, f: key_side; v, o, gradients alike) into a dense
-// [BH][spread_tokens(N)][d] one, the filler being 0, or 1 for the gates; launch_gather copies the
+// [BH][spread_tokens(N)][d] one with the given filler; launch_gather copies the
 // real tokens of such a tensor back into a caller's tensor.  `d` describes the caller's tensors.
 int spread_tokens(int N);
-hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, bool is_gate, const void* src, void* dst,
+enum SpreadFill { kFillZero, kFillOne, kFillPlusInf };      // q, v, gradients; gates f; gate pre-activations z
+hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, SpreadFill fill, const void* src, void* dst,
                          hipStream_t stream);
 hipError_t launch_gather(const SeqDims& d, bool key_side, bool bf16, const void* src, void* dst, hipStream_t stream);
 

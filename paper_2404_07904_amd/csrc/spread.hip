@@ -4,7 +4,8 @@
 // tokens (hgrn2_shape::chunk = 16).  That mode is built from the same kernels: every block of 16
 // tokens is spread into a chunk of its own, at rows 24 .. 39 around the chunk's reference row,
 // and the other 48 rows are filled with tokens that change nothing (f = 1, hence k = 0; q = 0;
-// v = 0; grad_o = 0).  Eq. 3 over the spread sequence is the recurrence over the original one with
+// v = 0; grad_o = 0; where the kernels form f = beta + (1 - beta) sigmoid(z) themselves, z = +inf,
+// for which that expression is exactly 1 in fp32).  Eq. 3 over the spread sequence is the recurrence over the original one with
 // identity steps in between, so outputs, gradients and states of the real tokens are the same,
 // while no quotient spans more than 8 real tokens.  It costs four times the work and the memory
 // of the spread tensors: a path for inputs outside the normal domain, not a fast one.
@@ -94,11 +95,12 @@ hipError_t launch_rows(K kern, const SpreadParams& p, int elem_size, hipStream_t
 
 int spread_tokens(int N) { return (N + kFineChunk - 1) / kFineChunk * kChunk; }
 
-hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, bool is_gate, const void* src, void* dst,
+hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, SpreadFill fill, const void* src, void* dst,
                          hipStream_t stream)
 {
     SpreadParams p = make_params(d, key_side, src, dst, true);
-    if (is_gate) p.fill = bf16 ? 0x3f803f80u : 0x3f800000u;      // f = 1
+    if (fill == kFillOne) p.fill = bf16 ? 0x3f803f80u : 0x3f800000u;
+    if (fill == kFillPlusInf) p.fill = bf16 ? 0x7f807f80u : 0x7f800000u;
     return bf16 ? launch_rows(spread_kernel<2>, p, 2, stream) : launch_rows(spread_kernel<4>, p, 4, stream);
 }
 

@@ -69,9 +69,10 @@ def test_small_gate_mode_workspace_and_support():
     lib = binding.lib()
     sp = ctypes.byref(s)
     big = 1 << 40
-    # not offered with the gate formed in the kernels, for packed batches or for the stage calls
-    assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
-    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == 0
+    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == (spread * (4 * 64 + 3 * 128) * 2
+                                                          + binding.hgrn2_bwd_gated_workspace_bytes(inner))
+    assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL      # beta missing
+    # not offered for packed batches or for the stage calls
     assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=2, H=3, N=200, layout=1, chunk=16)) == 0
     assert lib.hgrn2_state_sweep(sp, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_UNSUP
     assert lib.hgrn2_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1024, None) == E_WS

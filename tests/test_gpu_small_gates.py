@@ -86,3 +86,29 @@ def test_fine_and_coarse_reference_rows_agree_on_ordinary_gates():
     o, hT = binding.hgrn2_fwd(e, e, e, dev(w.h0), chunk=16)
     torch.cuda.synchronize()
     assert o.shape[2] == 0 and torch.equal(hT, dev(w.h0))
+
+
+def test_small_gates_with_the_gate_formed_in_the_kernels():
+    """Pre-activations around -5 and next to no lower bound: gates of 7e-3, far outside the ordinary domain."""
+    B, H, N, dk, dv = 2, 2, 170, 128, 64
+    print("\n[small gates gated] B=%d H=%d N=%d dk=%d dv=%d" % (B, H, N, dk, dv), flush=True)
+    rng = np.random.default_rng(8001)
+    w = synth.make_sequence(8000, B, H, N, dk, dv, io_dtype="bf16", with_h0=True, with_dO=True, with_dhT=True)
+    z = synth.bf16_round((-5.0 + 1.5 * rng.standard_normal((B, H, N, dk))).astype(np.float32))
+    beta = rng.uniform(0.0, 1e-3, size=(H, dk)).astype(np.float32)
+    q, zd, v, dO = dev(w.q, "bf16"), dev(z, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+    bd = torch.from_numpy(beta).cuda()
+    coarse = float(binding.hgrn2_min_gate_product(zd, bd).item())
+    fine = float(binding.hgrn2_min_gate_product(zd, bd, chunk=16).item())
+    print("    smallest gate product: %.3e over 32 tokens, %.3e over 8 tokens (limit %.3e)" % (coarse, fine, LIMIT), flush=True)
+    assert coarse < LIMIT < fine
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    o, hT = binding.hgrn2_fwd_gated(q, zd, bd, v, h0, chunk=16)
+    gq, gz, gb, gv, gh0 = binding.hgrn2_bwd_gated(q, zd, bd, v, dO, h0, dhT, want_grad_h0=True, chunk=16)
+    torch.cuda.synchronize()
+    ro, rhT = oracle.fwd_gated(w.q, z, beta, w.v, w.h0)
+    rq, rz, rb, rv, rh = oracle.bwd_gated(w.q, z, beta, w.v, w.dO, w.h0, w.dhT)
+    tol = TOL["bf16"]
+    check("o", host(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", host(gq), rq, tol); check("dz", host(gz), rz, tol); check("dbeta", host(gb), rb, tol)
+    check("dv", host(gv), rv, tol); check("dh0", host(gh0), rh, tol)
