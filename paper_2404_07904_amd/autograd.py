@@ -45,10 +45,10 @@ class _Hgrn2(torch.autograd.Function):
 
 class _Hgrn2Gated(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, z, beta, v, h0, layout):
-        o, hT = binding.hgrn2_fwd_gated(q, z, beta, v, h0, layout=layout)
+    def forward(ctx, q, z, beta, v, h0, layout, chunk):
+        o, hT = binding.hgrn2_fwd_gated(q, z, beta, v, h0, layout=layout, chunk=chunk)
         ctx.save_for_backward(q, z, beta, v, h0)
-        ctx.layout = layout
+        ctx.layout, ctx.chunk = layout, chunk
         ctx.set_materialize_grads(False)
         return o, hT
 
@@ -59,8 +59,8 @@ class _Hgrn2Gated(torch.autograd.Function):
             grad_o = torch.zeros_like(v)
         want_h0 = h0 is not None and ctx.needs_input_grad[4]
         gq, gz, gb, gv, gh0 = binding.hgrn2_bwd_gated(q, z, beta, v, _c(grad_o), h0, _c(grad_hT),
-                                                      want_grad_h0=want_h0, layout=ctx.layout)
-        return gq, gz.to(z.dtype), gb, gv, gh0, None
+                                                      want_grad_h0=want_h0, layout=ctx.layout, chunk=ctx.chunk)
+        return gq, gz.to(z.dtype), gb, gv, gh0, None, None
 
 
 class _Hgrn2Varlen(torch.autograd.Function):
@@ -127,10 +127,10 @@ def hgrn2_recurrence(q, f, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND, chunk=0
     return _Hgrn2.apply(q, f, v, h0, layout, chunk)
 
 
-def hgrn2_recurrence_gated(q, z, beta, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND):
+def hgrn2_recurrence_gated(q, z, beta, v, h0=None, layout=binding.HGRN2_LAYOUT_BHND, chunk=0):
     """o, hT of Eq. 3 with f = beta + (1 - beta) sigmoid(z) (Eq. 2) formed in the kernels;
-    beta: fp32 [H,dk]."""
-    return _Hgrn2Gated.apply(q, z, beta, v, h0, layout)
+    beta: fp32 [H,dk]; chunk=16: the small-gate mode."""
+    return _Hgrn2Gated.apply(q, z, beta, v, h0, layout, chunk)
 
 
 def hgrn2_recurrence_varlen(q, f, v, cu_seqlens, h0=None, beta=None):

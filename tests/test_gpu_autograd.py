@@ -121,3 +121,23 @@ def test_hgrn1_autograd_both_forms():
     pf, pi, po, _ = binding.hgrn1_bwd(f.detach(), i.detach(), o.detach(), dyd, None, None)
     torch.cuda.synchronize()
     same(f.grad, pf); same(i.grad, pi); same(o.grad, po)
+
+
+def test_autograd_passes_the_small_gate_mode_on():
+    """chunk=16 reaches both library calls of a wrapper: same tensors as the binding with chunk=16."""
+    w = synth.make_sequence(8300, 1, 2, 90, 64, 64, io_dtype="bf16", lb=0.3, with_dO=True)
+    dO = dev(w.dO, "bf16")
+    q, f, v = leaf(w.q), leaf(w.f), leaf(w.v)
+    o, _ = autograd.hgrn2_recurrence(q, f, v, chunk=16)
+    (o.float() * dO.float()).sum().backward()
+    ro, _ = binding.hgrn2_fwd(q.detach(), f.detach(), v.detach(), None, chunk=16)
+    rq, rf, rv, _ = binding.hgrn2_bwd(q.detach(), f.detach(), v.detach(), dO, None, None, chunk=16)
+    torch.cuda.synchronize()
+    same(o.detach(), ro); same(q.grad, rq); same(f.grad, rf); same(v.grad, rv)
+    beta = torch.full((2, 64), 0.2, device="cuda", requires_grad=True)
+    q2, z2, v2 = leaf(w.q), leaf(w.f), leaf(w.v)
+    o2, _ = autograd.hgrn2_recurrence_gated(q2, z2, beta, v2, chunk=16)
+    (o2.float() * dO.float()).sum().backward()
+    g = binding.hgrn2_bwd_gated(q2.detach(), z2.detach(), beta.detach(), v2.detach(), dO, None, None, chunk=16)
+    torch.cuda.synchronize()
+    same(q2.grad, g[0]); same(z2.grad, g[1]); same(beta.grad, g[2]); same(v2.grad, g[3])
