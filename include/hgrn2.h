@@ -28,13 +28,14 @@
  *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
  *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
  *     intra-chunk terms degrade smoothly (they stay finite) instead of failing.
- *     Small-gate mode: with chunk = 16, hgrn2_fwd, hgrn2_bwd and their _gated forms place their
- *     reference rows every 16 tokens instead of every 64, and the bound applies to the product
- *     of 8 consecutive gates (guaranteed for f >= 1.8e-4).  The passes then run on sequences
- *     spread to four times their length: about six times the time, and a workspace that also
- *     holds the spread tensors.  hgrn2_min_gate_product tells which mode a set of gates needs.
- *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 16 where stated; any
- *     B, H, N >= 0.
+ *     Small-gate modes: with chunk = 32 or 16, hgrn2_fwd, hgrn2_bwd and their _gated forms place
+ *     their reference rows every 32 or 16 tokens instead of every 64, and the bound applies to
+ *     the product of 16 or 8 consecutive gates (guaranteed for f >= 0.014, f >= 1.8e-4).  The
+ *     passes then run on sequences spread to twice or four times their length: about three or
+ *     six times the time, and a workspace that also holds the spread tensors.
+ *     hgrn2_min_gate_product tells which mode a set of gates needs.
+ *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
+ *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
  *     io_dtype F32 is supported by hgrn2_fwd and hgrn2_step (hgrn2_bwd: BF16 only).
  */
@@ -165,8 +166,8 @@ int hgrn2_step_gated(int32_t B, int32_t H, int32_t dk, int32_t dv, int32_t io_dt
  * (device, one float) the smallest product of the gates of one channel over a half chunk -- tokens
  * [64 n, 64 n + 32) and [64 n + 32, 64 n + 64) of every sequence, n = 0, 1, ... -- of the whole
  * call.  hgrn2_fwd / hgrn2_bwd are exact up to rounding while it is above 2^-100 (7.9e-31).
- * With shape->chunk = 16 the products are those the small-gate mode depends on: over tokens
- * [8 m, 8 m + 8) of every sequence.
+ * With shape->chunk = 32 or 16 the products are those that small-gate mode depends on: over
+ * tokens [16 m, 16 m + 16) or [8 m, 8 m + 8) of every sequence.
  * Reads f once; equal-length batches in either layout; with beta (device fp32 [H][dk]) `f` holds
  * pre-activations and the gate of Eq. 2 is formed first.  An empty call writes 1.
  */

@@ -25,7 +25,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
     if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
     if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
-    if (s->chunk == kFineChunk && fine_ok) {
+    if ((s->chunk == kFineChunk || s->chunk == 2 * kFineChunk) && fine_ok) {
         if (s->N > INT_MAX / 8 || bh * (nc * 4 + 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;      // the spread sequences must pass this check too
     } else if (s->chunk != 0 && s->chunk != kChunk) {
         return HGRN2_ERR_UNSUPPORTED;
@@ -169,12 +169,12 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
 }
 
 // ---- small-gate mode: the same passes on spread sequences (spread.hip) -------------------------
-bool fine_mode(const hgrn2_shape* s) { return s && s->chunk == kFineChunk; }
+bool fine_mode(const hgrn2_shape* s) { return s && (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk); }
 
 hgrn2_shape spread_shape(const hgrn2_shape& s)
 {
     hgrn2_shape e = s;
-    e.N = spread_tokens(s.N);
+    e.N = spread_tokens(s.N, s.chunk);
     e.chunk = 0;
     e.layout = HGRN2_LAYOUT_BHND;
     return e;
@@ -243,14 +243,14 @@ static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, cons
     void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
     void* vs = take(spread_bytes(e, d.dv, d.io_bf16));
     void* os = take(spread_bytes(e, d.dv, d.io_bf16));
-    if (launch_spread(d, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
-        launch_spread(d, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess)
+    if (launch_spread(d, shape->chunk, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
+        launch_spread(d, shape->chunk, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
+        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     const int inner = fwd_impl(&e, qs, fs, beta, gated, vs, h0, os, hT, at, workspace_bytes - (size_t)(at - static_cast<char*>(workspace)),
                                hip_stream);
     if (inner != HGRN2_OK) return inner;
-    return launch_gather(d, false, d.io_bf16, os, o, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+    return launch_gather(d, shape->chunk, false, d.io_bf16, os, o, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
 }
 
 // Small-gate mode of the backward pass.
@@ -279,18 +279,18 @@ static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, cons
     void* vs = take(ev);
     void* gos = take(ev);
     void* gvs = take(ev);
-    if (launch_spread(d, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
-        launch_spread(d, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess ||
-        launch_spread(d, false, d.io_bf16, kFillZero, grad_o, gos, stream) != hipSuccess)
+    if (launch_spread(d, shape->chunk, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
+        launch_spread(d, shape->chunk, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
+        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess ||
+        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, grad_o, gos, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     // the filler rows add nothing to grad_beta: their gate is exactly 1, and its share carries the factor 1 - f
     const int inner = bwd_impl(&e, qs, fs, beta, gated, vs, h0, gos, grad_hT, gqs, gfs, grad_beta, gvs, grad_h0, at,
                                workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
     if (inner != HGRN2_OK) return inner;
-    if (launch_gather(d, true, d.io_bf16, gqs, grad_q, stream) != hipSuccess ||
-        launch_gather(d, true, d.io_bf16, gfs, grad_f, stream) != hipSuccess ||
-        launch_gather(d, false, d.io_bf16, gvs, grad_v, stream) != hipSuccess)
+    if (launch_gather(d, shape->chunk, true, d.io_bf16, gqs, grad_q, stream) != hipSuccess ||
+        launch_gather(d, shape->chunk, true, d.io_bf16, gfs, grad_f, stream) != hipSuccess ||
+        launch_gather(d, shape->chunk, false, d.io_bf16, gvs, grad_v, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
@@ -553,7 +553,7 @@ int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float*
     if (!min_product) return HGRN2_ERR_NULL;
     if ((size_t)d.BH * d.N > 0 && !f) return HGRN2_ERR_NULL;
     d.beta = beta;
-    if (launch_min_gate_product(d, (fine_mode(shape) ? kFineChunk : kChunk) / 2, f, min_product,
+    if (launch_min_gate_product(d, (fine_mode(shape) ? shape->chunk : kChunk) / 2, f, min_product,
                                 static_cast<hipStream_t>(hip_stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;

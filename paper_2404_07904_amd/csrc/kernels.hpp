@@ -10,7 +10,7 @@ namespace hgrn2 {
 
 // Compile-time chunk length of the chunkwise kernels.
 constexpr int kChunk = 64;
-constexpr int kFineChunk = 16;     // spacing of the reference rows in the small-gate mode (see spread.hip)
+constexpr int kFineChunk = 16;     // closest spacing of the reference rows in the small-gate modes (spread.hip); 32 is the other
 
 // Where token (b, h, n) of q / f (channel count dk) and of v / o (dv) starts, in elements:
 // b * sb + h * sh + n * sn.  [B][H][N][d] has sb = H N d, sh = N d, sn = d; [B][N][H][d] (what a
@@ -146,16 +146,17 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
-// Small-gate mode (spread.hip): every block of kFineChunk tokens becomes a chunk of its own, padded
-// with tokens that change nothing.  spread_tokens(N) is the length of the spread sequence;
+// Small-gate modes (spread.hip): every block of `block` (16 or 32) tokens becomes a chunk of its own,
+// padded with tokens that change nothing.  spread_tokens(N, block) is the length of the spread sequence;
 // launch_spread copies a caller's tensor (q, f: key_side; v, o, gradients alike) into a dense
-// [BH][spread_tokens(N)][d] one with the given filler; launch_gather copies the
+// [BH][spread_tokens(N, block)][d] one with the given filler; launch_gather copies the
 // real tokens of such a tensor back into a caller's tensor.  `d` describes the caller's tensors.
-int spread_tokens(int N);
+int spread_tokens(int N, int block);
 enum SpreadFill { kFillZero, kFillOne, kFillPlusInf };      // q, v, gradients; gates f; gate pre-activations z
-hipError_t launch_spread(const SeqDims& d, bool key_side, bool bf16, SpreadFill fill, const void* src, void* dst,
+hipError_t launch_spread(const SeqDims& d, int block, bool key_side, bool bf16, SpreadFill fill, const void* src, void* dst,
                          hipStream_t stream);
-hipError_t launch_gather(const SeqDims& d, bool key_side, bool bf16, const void* src, void* dst, hipStream_t stream);
+hipError_t launch_gather(const SeqDims& d, int block, bool key_side, bool bf16, const void* src, void* dst,
+                         hipStream_t stream);
 
 // Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
 size_t varlen_run_table_bytes(int B, int R);

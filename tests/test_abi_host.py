@@ -77,7 +77,11 @@ def test_small_gate_mode_workspace_and_support():
     assert lib.hgrn2_state_sweep(sp, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_UNSUP
     assert lib.hgrn2_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1024, None) == E_WS
     assert lib.hgrn2_fwd(sp, None, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL
-    assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=32)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
+    assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=48)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
+    # reference rows every 32 tokens: 7 blocks of 32 tokens, a chunk each
+    s32 = shape(B=2, H=3, N=200, dk=64, dv=128, chunk=32)
+    assert binding.hgrn2_fwd_workspace_bytes(s32) == (2 * 3 * 7 * 64 * (64 + 64 + 128 + 128) * 2
+                                                      + binding.hgrn2_fwd_workspace_bytes(shape(B=2, H=3, N=7 * 64, dk=64, dv=128)))
 
 
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):
@@ -98,7 +102,7 @@ def test_fwd_argument_errors():
     assert call_fwd(shape(B=1 << 20, H=1 << 20)) == E_SHAPE
     assert call_fwd(shape(dk=96)) == E_UNSUP
     assert call_fwd(shape(dv=256)) == E_UNSUP
-    assert call_fwd(shape(chunk=32)) == E_UNSUP
+    assert call_fwd(shape(chunk=48)) == E_UNSUP
     assert call_fwd(shape(), q=None) == E_NULL
     assert call_fwd(shape(), o=None) == E_NULL
     assert call_fwd(shape(), ws=None) == E_WS

@@ -1,7 +1,7 @@
 """Small gates.  With a reference row every 64 tokens the chunkwise kernels are exact while the gate
-product of every half chunk stays above 2^-100; chunk = 16 in the shape asks for reference rows
-every 16 tokens (the passes then run on sequences spread to four times their length), which moves
-that bound to products of 8 gates.  The cases here lie outside the first domain and inside the
+product of every half chunk stays above 2^-100; chunk = 16 (32) in the shape asks for reference rows
+every 16 (32) tokens (the passes then run on sequences spread to four times (twice) their length),
+which moves that bound to products of 8 (16) gates.  The cases here lie outside the first domain and inside the
 second and are compared with the fp64 oracle, which has no such limit; the probe must say so for
 both spacings.  Tolerance: max|x-y|/max|y| <= 2e-2 per tensor (bf16), 1e-4 (fp32 forward)."""
 import numpy as np
@@ -24,32 +24,37 @@ def small_gate_workload(seed, B, H, N, dk, dv, kind, io_dtype="bf16"):
     rng = np.random.default_rng(seed + 1)
     if kind == "loguniform":
         f = 10.0 ** rng.uniform(-3.0, 0.0, size=w.f.shape)
+    elif kind == "loguniform32":          # for reference rows every 32 tokens: 16 gates multiply to 6e-28 at worst
+        f = 10.0 ** rng.uniform(np.log10(0.02), 0.0, size=w.f.shape)
     else:
         f = np.where(rng.random(w.f.shape) < 1.0 / 12.0, 1e-4, 0.9 + 0.1 * rng.random(w.f.shape))
     w.f = synth.bf16_round(f.astype(np.float32)) if io_dtype == "bf16" else f.astype(np.float32)
     return w
 
 
-@pytest.mark.parametrize("kind,B,H,N,dk,dv,layout", [
-    ("loguniform", 2, 3, 200, 64, 64, 0),
-    ("resets", 1, 2, 333, 128, 128, 1),
-    ("loguniform", 9, 8, 130, 128, 128, 0),      # enough sequences for the single-pass forward
-    ("resets", 1, 2, 1100, 64, 128, 0),          # spread to 69 chunks: walked in runs
+@pytest.mark.parametrize("kind,B,H,N,dk,dv,layout,chunk", [
+    ("loguniform", 2, 3, 200, 64, 64, 0, 16),
+    ("resets", 1, 2, 333, 128, 128, 1, 16),
+    ("loguniform", 9, 8, 130, 128, 128, 0, 16),      # enough sequences for the single-pass forward
+    ("resets", 1, 2, 1100, 64, 128, 0, 16),          # spread to 69 chunks: walked in runs
+    ("loguniform32", 2, 2, 300, 128, 64, 1, 32),
+    ("loguniform32", 1, 3, 700, 64, 64, 0, 32),
 ])
-def test_small_gates_fwd_bwd(kind, B, H, N, dk, dv, layout):
-    print("\n[small gates] %s B=%d H=%d N=%d dk=%d dv=%d layout=%d" % (kind, B, H, N, dk, dv, layout), flush=True)
+def test_small_gates_fwd_bwd(kind, B, H, N, dk, dv, layout, chunk):
+    print("\n[small gates] %s B=%d H=%d N=%d dk=%d dv=%d layout=%d chunk=%d" % (kind, B, H, N, dk, dv, layout, chunk), flush=True)
     w = small_gate_workload(7700 + N, B, H, N, dk, dv, kind)
     put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
     get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
     q, f, v, dO = put(dev(w.q, "bf16")), put(dev(w.f, "bf16")), put(dev(w.v, "bf16")), put(dev(w.dO, "bf16"))
     h0, dhT = dev(w.h0), dev(w.dhT)
     coarse = float(binding.hgrn2_min_gate_product(f, layout=layout).item())
-    fine = float(binding.hgrn2_min_gate_product(f, layout=layout, chunk=16).item())
-    print("    smallest gate product: %.3e over 32 tokens, %.3e over 8 tokens (limit %.3e)" % (coarse, fine, LIMIT), flush=True)
+    fine = float(binding.hgrn2_min_gate_product(f, layout=layout, chunk=chunk).item())
+    print("    smallest gate product: %.3e over 32 tokens, %.3e over %d tokens (limit %.3e)"
+          % (coarse, fine, chunk // 2, LIMIT), flush=True)
     assert coarse < LIMIT < fine
-    assert abs(fine - oracle.min_gate_product(w.f, chunk=16)) <= 1e-4 * fine
-    o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=16)
-    gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=16)
+    assert abs(fine - oracle.min_gate_product(w.f, chunk=chunk)) <= 1e-4 * fine
+    o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=chunk)
+    gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=chunk)
     o64, _ = binding.hgrn2_fwd(q, f, v, h0, layout=layout)
     torch.cuda.synchronize()
     tol = TOL["bf16"]
