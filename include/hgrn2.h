@@ -28,12 +28,12 @@
  *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
  *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
  *     intra-chunk terms degrade smoothly (they stay finite) instead of failing.
- *     Small-gate modes: with chunk = 32 or 16, hgrn2_fwd, hgrn2_bwd and their _gated forms place
- *     their reference rows every 32 or 16 tokens instead of every 64, and the bound applies to
- *     the product of 16 or 8 consecutive gates (guaranteed for f >= 0.014, f >= 1.8e-4).  The
- *     passes then run on sequences spread to twice or four times their length: about three or
- *     six times the time, and a workspace that also holds the spread tensors.
- *     hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     Small-gate modes: with chunk = 32 or 16, hgrn2_fwd, hgrn2_bwd and their _gated and
+ *     _varlen forms place their reference rows every 32 or 16 tokens instead of every 64, and
+ *     the bound applies to the product of 16 or 8 consecutive gates (guaranteed for
+ *     f >= 0.014, f >= 1.8e-4).  The passes then run on sequences spread to twice or four
+ *     times their length: about three or six times the time, and a workspace that also holds
+ *     the spread tensors.  hgrn2_min_gate_product tells which mode a set of gates needs.
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.

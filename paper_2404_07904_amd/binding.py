@@ -227,10 +227,10 @@ def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h
     return grad_q, grad_z, grad_beta, grad_v, grad_h0
 
 
-def make_shape_varlen(q, v, f, n_seq) -> hgrn2_shape:
+def make_shape_varlen(q, v, f, n_seq, chunk=0) -> hgrn2_shape:
     """Shape descriptor of packed tensors q, f [T,H,dk], v [T,H,dv] holding n_seq sequences."""
     T, H, dk = q.shape
-    return hgrn2_shape(n_seq, H, T, dk, v.shape[-1], 0, _dt(q), _dt(f), HGRN2_LAYOUT_BNHD)
+    return hgrn2_shape(n_seq, H, T, dk, v.shape[-1], chunk, _dt(q), _dt(f), HGRN2_LAYOUT_BNHD)
 
 
 def hgrn2_fwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
@@ -241,12 +241,13 @@ def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_bwd_varlen_workspace_bytes(ctypes.byref(shape)))
 
 
-def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o=None, hT=None, workspace=None):
+def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o=None, hT=None, workspace=None,
+                     chunk=0):
     """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
     int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv].  With beta [H,dk] fp32, f holds the
     gates' pre-activations (Eq. 2)."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
-    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
+    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk)
     if o is None:
         o = torch.empty_like(v)
     if hT is None and want_hT:
@@ -260,11 +261,11 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o
 
 
 def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta=None, want_grad_h0=False,
-                     workspace=None, grad_q=None, grad_f=None, grad_v=None):
+                     workspace=None, grad_q=None, grad_f=None, grad_v=None, chunk=0):
     """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis; with beta also
     grad_beta (returned as a fifth value), and grad_f is then the gradient of the pre-activations."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
-    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1)
+    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk)
     gq = torch.empty_like(q) if grad_q is None else grad_q
     gf = torch.empty_like(q) if grad_f is None else grad_f
     gv = torch.empty_like(v) if grad_v is None else grad_v

@@ -56,11 +56,16 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
 // Variable-length batches: shape->B sequences packed into shape->N tokens of [T][H][d] tensors.
 // Fills `d` with NC = the host's bound on the chunks of all sequences (N / chunk + B); the table
 // pointer is set by the caller once the workspace is known.
-int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d)
+int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d, bool fine_ok = false)
 {
-    const int rc = check_shape(s, backward, d, true);
+    const int rc = check_shape(s, backward, d, true, fine_ok);
     if (rc != HGRN2_OK) return rc;
     if (s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;          // packed tokens are token-major
+    if (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk) {
+        // small-gate mode: the spread batch must pass this check too
+        const long long spread = ((long long)s->N / s->chunk + s->B) * kChunk;
+        if (spread > INT_MAX / 8 || (spread / kChunk + s->B) * (s->H > 0 ? s->H : 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;
+    }
     const long long bound = (long long)s->N / kChunk + s->B;
     if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2 || s->B > INT_MAX / 8) return HGRN2_ERR_SHAPE;
     d->NC = (int)bound;
@@ -184,6 +189,26 @@ hgrn2_shape spread_shape(const hgrn2_shape& s)
 size_t spread_bytes(const hgrn2_shape& e, int width, bool bf16)
 {
     return round256((size_t)e.B * e.H * e.N * width * (bf16 ? 2 : 4));
+}
+
+// packed batches: N counts the tokens of all sequences
+hgrn2_shape spread_shape_packed(const hgrn2_shape& s)
+{
+    hgrn2_shape e = s;
+    e.N = spread_tokens_packed(s.N, s.B, s.chunk);
+    e.chunk = 0;
+    return e;
+}
+
+size_t packed_spread_bytes(const hgrn2_shape& e, int width, bool bf16)
+{
+    return round256((size_t)e.N * e.H * width * (bf16 ? 2 : 4));
+}
+
+// the batch's sequence table and the spread batch's cumulative lengths, at the head of the workspace
+size_t packed_fine_head_bytes(const hgrn2_shape& s)
+{
+    return round256(varlen_table_bytes(s.B)) + round256(((size_t)s.B + 1) * sizeof(int));
 }
 
 }   // namespace
@@ -432,10 +457,84 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
                     workspace, workspace_bytes, hip_stream);
 }
 
+// Small-gate modes of the packed entry points, forward (backward = false: o, hT) and backward: every
+// sequence is spread on its own, the spread batch goes through the packed entry point, and the
+// real tokens' rows are gathered back.
+static int varlen_fine(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                       const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                       void* o, float* hT, void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0,
+                       bool backward, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, backward, &d, true);
+    if (rc != HGRN2_OK) return rc;
+    const bool has_tokens = d.N > 0;
+    if (backward) {
+        if (beta && !grad_beta && (size_t)shape->H * d.dk > 0) return HGRN2_ERR_NULL;
+        if (d.BH > 0 && (!cu_seqlens || (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v))))
+            return HGRN2_ERR_NULL;
+    } else {
+        if (d.BH == 0) return HGRN2_OK;
+        if (!cu_seqlens || (has_tokens && (!q || !f || !v || !o))) return HGRN2_ERR_NULL;
+    }
+    const hgrn2_shape e = spread_shape_packed(*shape);
+    const size_t need = backward ? hgrn2_bwd_varlen_workspace_bytes(shape) : hgrn2_fwd_varlen_workspace_bytes(shape);
+    if (d.BH > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    if (d.BH == 0)       // no sequences: the packed entry point itself knows what that means for grad_beta
+        return hgrn2_bwd_varlen(&e, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+                                grad_h0, workspace, workspace_bytes, hip_stream);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int T = d.N, B = shape->B, block = shape->chunk;
+    char* at = static_cast<char*>(workspace);
+    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
+    int* seq_table = reinterpret_cast<int*>(take(round256(varlen_table_bytes(B))));
+    int* cu_spread = reinterpret_cast<int*>(take(round256(((size_t)B + 1) * sizeof(int))));
+    const int io = d.io_bf16 ? 2 : 4, ge = d.gate_bf16 ? 2 : 4;
+    const int row_k = shape->H * d.dk * io, row_g = shape->H * d.dk * ge, row_v = shape->H * d.dv * io;
+    const size_t ek = packed_spread_bytes(e, d.dk, d.io_bf16), eg = packed_spread_bytes(e, d.dk, d.gate_bf16),
+                 ev = packed_spread_bytes(e, d.dv, d.io_bf16);
+    if (launch_varlen_table(cu_seqlens, B, T, seq_table, stream) != hipSuccess ||
+        launch_spread_offsets(seq_table, B, block, cu_spread, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    auto spread = [&](const void* src, void* dst, int row_bytes, SpreadFill fill, bool bf16) {
+        return launch_spread_packed(T, B, block, row_bytes, fill, bf16, seq_table, cu_spread, src, dst, true, stream) == hipSuccess;
+    };
+    auto gather = [&](const void* src, void* dst, int row_bytes) {
+        return launch_spread_packed(T, B, block, row_bytes, kFillZero, true, seq_table, cu_spread, src, dst, false, stream) == hipSuccess;
+    };
+    void* qs = take(ek);
+    void* fs = take(eg);
+    void* vs = take(ev);
+    if (!spread(q, qs, row_k, kFillZero, d.io_bf16) || !spread(f, fs, row_g, beta ? kFillPlusInf : kFillOne, d.gate_bf16) ||
+        !spread(v, vs, row_v, kFillZero, d.io_bf16))
+        return HGRN2_ERR_HIP;
+    if (!backward) {
+        void* os = take(ev);
+        const int inner = hgrn2_fwd_varlen(&e, cu_spread, qs, fs, beta, vs, h0, os, hT, at,
+                                           workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
+        if (inner != HGRN2_OK) return inner;
+        return gather(os, o, row_v) ? HGRN2_OK : HGRN2_ERR_HIP;
+    }
+    void* gos = take(ev);
+    void* gqs = take(ek);
+    void* gfs = take(ek);
+    void* gvs = take(ev);
+    if (!spread(grad_o, gos, row_v, kFillZero, d.io_bf16)) return HGRN2_ERR_HIP;
+    const int inner = hgrn2_bwd_varlen(&e, cu_spread, qs, fs, beta, vs, h0, gos, grad_hT, gqs, gfs, grad_beta, gvs, grad_h0, at,
+                                       workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
+    if (inner != HGRN2_OK) return inner;
+    return gather(gqs, grad_q, row_k) && gather(gfs, grad_f, row_k) && gather(gvs, grad_v, row_v) ? HGRN2_OK : HGRN2_ERR_HIP;
+}
+
 size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape_varlen(shape, false, &d) != HGRN2_OK) return 0;
+    if (check_shape_varlen(shape, false, &d, true) != HGRN2_OK) return 0;
+    if (fine_mode(shape)) {
+        const hgrn2_shape e = spread_shape_packed(*shape);
+        return packed_fine_head_bytes(*shape) + packed_spread_bytes(e, d.dk, d.io_bf16) + packed_spread_bytes(e, d.dk, d.gate_bf16) +
+               2 * packed_spread_bytes(e, d.dv, d.io_bf16) + hgrn2_fwd_varlen_workspace_bytes(&e);
+    }
     const PackedRuns p = plan_packed_runs(shape, d, false);
     return p.table_bytes + round256(state_ws_bytes(d)) + p.state_bytes + p.decay_bytes;
 }
@@ -443,7 +542,13 @@ size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
+    if (fine_mode(shape)) {
+        const hgrn2_shape e = spread_shape_packed(*shape);
+        return packed_fine_head_bytes(*shape) + 3 * packed_spread_bytes(e, d.dk, d.io_bf16) +
+               packed_spread_bytes(e, d.dk, d.gate_bf16) + 3 * packed_spread_bytes(e, d.dv, d.io_bf16) +
+               hgrn2_bwd_varlen_workspace_bytes(&e);
+    }
     const PackedRuns p = plan_packed_runs(shape, d, true);
     return p.table_bytes + 2 * (round256(state_ws_bytes(d)) + p.state_bytes) + p.decay_bytes +
            round256(beta_partials_bytes(d));
@@ -453,6 +558,9 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                      const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
                      size_t workspace_bytes, void* hip_stream)
 {
+    if (fine_mode(shape))
+        return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, nullptr, nullptr, o, hT, nullptr, nullptr, nullptr,
+                           nullptr, nullptr, false, workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape_varlen(shape, false, &d);
     if (rc != HGRN2_OK) return rc;
@@ -496,6 +604,9 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                      void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                      size_t workspace_bytes, void* hip_stream)
 {
+    if (fine_mode(shape))
+        return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, nullptr, nullptr, grad_q, grad_f,
+                           grad_beta, grad_v, grad_h0, true, workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape_varlen(shape, true, &d);
     if (rc != HGRN2_OK) return rc;

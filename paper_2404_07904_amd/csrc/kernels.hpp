@@ -158,6 +158,15 @@ hipError_t launch_spread(const SeqDims& d, int block, bool key_side, bool bf16, 
 hipError_t launch_gather(const SeqDims& d, int block, bool key_side, bool bf16, const void* src, void* dst,
                          hipStream_t stream);
 
+// The same for a packed batch, whose sequences are spread one by one: spread_tokens_packed() bounds
+// the rows of the spread batch, launch_spread_offsets writes the first spread row of every sequence
+// (B + 1 ints, the spread batch's cumulative sequence lengths) from the batch's sequence table, and
+// launch_spread_packed copies [T][row] tensors to spread ones (to_spread) or back.
+int spread_tokens_packed(int T, int B, int block);
+hipError_t launch_spread_offsets(const int* seq_table, int B, int block, int* cu_spread, hipStream_t stream);
+hipError_t launch_spread_packed(int T, int B, int block, int row_bytes, SpreadFill fill, bool bf16, const int* seq_table,
+                                const int* cu_spread, const void* src, void* dst, bool to_spread, hipStream_t stream);
+
 // Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
 size_t varlen_run_table_bytes(int B, int R);
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,

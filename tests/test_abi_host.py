@@ -72,8 +72,12 @@ def test_small_gate_mode_workspace_and_support():
     assert binding.hgrn2_bwd_gated_workspace_bytes(s) == (spread * (4 * 64 + 3 * 128) * 2
                                                           + binding.hgrn2_bwd_gated_workspace_bytes(inner))
     assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL      # beta missing
-    # not offered for packed batches or for the stage calls
-    assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=2, H=3, N=200, layout=1, chunk=16)) == 0
+    # packed batches: sequence table, spread offsets, the spread tensors of (200 // 16 + 2) chunks, the inner call
+    sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=16)
+    inner_v = shape(B=2, H=3, N=14 * 64, dk=64, dv=128, layout=1)
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == (256 + 256 + 14 * 64 * 3 * (64 + 64 + 128 + 128) * 2
+                                                            + binding.hgrn2_fwd_varlen_workspace_bytes(inner_v))
+    # not offered for the stage calls
     assert lib.hgrn2_state_sweep(sp, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_UNSUP
     assert lib.hgrn2_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1024, None) == E_WS
     assert lib.hgrn2_fwd(sp, None, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL

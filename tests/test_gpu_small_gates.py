@@ -117,3 +117,51 @@ def test_small_gates_with_the_gate_formed_in_the_kernels():
     check("o", host(o), ro, tol); check("hT", host(hT), rhT, tol)
     check("dq", host(gq), rq, tol); check("dz", host(gz), rz, tol); check("dbeta", host(gb), rb, tol)
     check("dv", host(gv), rv, tol); check("dh0", host(gh0), rh, tol)
+
+
+@pytest.mark.parametrize("lens,H,dk,dv,gated,chunk", [
+    ([150, 0, 37, 260], 2, 64, 64, False, 16),
+    ([90, 300], 3, 128, 64, True, 16),
+    ([200, 1, 333], 2, 128, 128, False, 32),
+])
+def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk):
+    """Every sequence of a packed batch is spread on its own (ragged last blocks, an empty and a
+    one-token sequence), with the gates given or formed in the kernels."""
+    B, T = len(lens), int(sum(lens))
+    print("\n[small gates packed] H=%d dk=%d dv=%d gated=%s chunk=%d lens=%s" % (H, dk, dv, gated, chunk, lens), flush=True)
+    rng = np.random.default_rng(8100 + T)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    w = small_gate_workload(8100 + B, 1, H, T, dk, dv, "loguniform" if chunk == 16 else "loguniform32")
+    z = synth.bf16_round((-4.5 + 1.5 * rng.standard_normal((1, H, T, dk))).astype(np.float32))
+    beta = rng.uniform(0.0, 1e-3, size=(H, dk)).astype(np.float32)
+    gate_in = z if gated else w.f
+    pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
+    un = lambda t: host(t.permute(1, 0, 2))
+    h0 = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    dhT = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
+    cud = torch.from_numpy(cu).cuda()
+    bd = torch.from_numpy(beta).cuda() if gated else None
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk)
+    torch.cuda.synchronize()
+    ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
+    rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        sl = (slice(None), slice(None), slice(s, e))
+        if gated:
+            ob, hTb = oracle.fwd_gated(w.q[sl], z[sl], beta, w.v[sl], h0[b:b + 1])
+            gqb, ggb, gbb, gvb, gh0b = oracle.bwd_gated(w.q[sl], z[sl], beta, w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+            rb += gbb
+        else:
+            ob, hTb = oracle.fwd(w.q[sl], w.f[sl], w.v[sl], h0[b:b + 1])
+            gqb, ggb, gvb, gh0b = oracle.bwd(w.q[sl], w.f[sl], w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+        ro[:, s:e], rq[:, s:e], rg[:, s:e], rv[:, s:e] = ob[0], gqb[0], ggb[0], gvb[0]
+        rhT[b], rh0[b] = hTb[0], gh0b[0]
+    tol = TOL["bf16"]
+    check("o", un(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", un(res[0]), rq, tol); check("dgate", un(res[1]), rg, tol); check("dv", un(res[2]), rv, tol)
+    check("dh0", host(res[3]), rh0, tol)
+    if gated:
+        check("dbeta", host(res[4]), rb, tol)
