@@ -65,9 +65,10 @@ class _Hgrn2Gated(torch.autograd.Function):
 
 class _Hgrn2Varlen(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, f, v, cu_seqlens, h0, beta):
-        o, hT = binding.hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0, beta=beta)
+    def forward(ctx, q, f, v, cu_seqlens, h0, beta, chunk):
+        o, hT = binding.hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0, beta=beta, chunk=chunk)
         ctx.save_for_backward(q, f, v, cu_seqlens, h0, beta)
+        ctx.chunk = chunk
         ctx.set_materialize_grads(False)
         return o, hT
 
@@ -77,10 +78,11 @@ class _Hgrn2Varlen(torch.autograd.Function):
         if grad_o is None:
             grad_o = torch.zeros_like(v)
         want_h0 = h0 is not None and ctx.needs_input_grad[4]
-        res = binding.hgrn2_bwd_varlen(q, f, v, _c(grad_o), cu, h0, _c(grad_hT), beta=beta, want_grad_h0=want_h0)
+        res = binding.hgrn2_bwd_varlen(q, f, v, _c(grad_o), cu, h0, _c(grad_hT), beta=beta, want_grad_h0=want_h0,
+                                       chunk=ctx.chunk)
         gq, gf, gv, gh0 = res[:4]
         gb = res[4] if beta is not None else None
-        return gq, gf.to(f.dtype), gv, None, gh0, gb
+        return gq, gf.to(f.dtype), gv, None, gh0, gb, None
 
 
 class _Hgrn1(torch.autograd.Function):
@@ -133,10 +135,10 @@ def hgrn2_recurrence_gated(q, z, beta, v, h0=None, layout=binding.HGRN2_LAYOUT_B
     return _Hgrn2Gated.apply(q, z, beta, v, h0, layout, chunk)
 
 
-def hgrn2_recurrence_varlen(q, f, v, cu_seqlens, h0=None, beta=None):
+def hgrn2_recurrence_varlen(q, f, v, cu_seqlens, h0=None, beta=None, chunk=0):
     """o, hT for sequences packed along the token axis: q, f [T,H,dk], v [T,H,dv], cu_seqlens int32
     [n_seq + 1] on the device, h0 / hT fp32 [n_seq,H,dk,dv]; with beta, f holds pre-activations."""
-    return _Hgrn2Varlen.apply(q, f, v, cu_seqlens, h0, beta)
+    return _Hgrn2Varlen.apply(q, f, v, cu_seqlens, h0, beta, chunk)
 
 
 def hgrn1_recurrence(f, i, o, h0=None):
