@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--no-handoff", action="store_true", help="skip the prefill -> decode hand-off run")
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--no-long", action="store_true", help="skip the long-sequence shape (B=2, N=16384)")
+    ap.add_argument("--no-small-gates", action="store_true", help="skip the small-gate modes (chunk = 32, 16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -249,6 +250,27 @@ def main():
         result["gated"]["token_major_ms_per_step"] = round(dtm * 1e3, 4)
         result["gated"]["token_major_tokens_per_s"] = round(tokens / dtm, 1)
         del zs, wsg
+
+    # ---- the same step in the small-gate modes: reference rows every 32 and every 16 tokens ----
+    if not args.no_small_gates:
+        fine = {}
+        for ck in (32, 16):
+            shf = binding.make_shape(sets[0][0], sets[0][2], sets[0][1], ck)
+            wsf = torch.empty(binding.hgrn2_bwd_workspace_bytes(shf), dtype=torch.uint8, device=dev)
+
+            def fine_step(i):
+                q, f, v, dO = sets[i % 2]
+                binding.hgrn2_fwd(q, f, v, None, o=o, hT=hT, workspace=wsf, chunk=ck)
+                binding.hgrn2_bwd(q, f, v, dO, None, None, workspace=wsf, grad_q=gq, grad_f=gf, grad_v=gv, chunk=ck)
+
+            for i in range(4):
+                fine_step(i)
+            dtf = timed(fine_step, reps=20)
+            fine["chunk_%d" % ck] = {"ms_per_step": round(dtf * 1e3, 4), "tokens_per_s": round(tokens / dtf, 1),
+                                     "workspace_MB": round(wsf.numel() / 1e6, 1)}
+            del wsf
+        fine["workload"] = "the main shape and gates; every 32 (16) tokens spread into a chunk of their own"
+        result["small_gate_modes"] = fine
 
     # ---- long sequences in a small batch: twice the tokens of the main shape in 32 sequences ----
     if not args.no_long:
