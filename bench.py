@@ -300,7 +300,15 @@ def main():
                                    "ms_per_step": round((tf + tb) * 1e3, 4),
                                    "tokens_per_s": round(Bl * Nl / (tf + tb), 1),
                                    "algorithmic_GBps": round(io_long / (tf + tb) / 1e9, 1)}
-        del ql, vl_, dOl, fl, wsl, ol, gql, gfl, gvl
+        # bf16 has three values in [0.99, 1]; the same gates kept in fp32 (4 bytes per gate)
+        fl32 = 0.99 + 0.01 * torch.rand((Bl, H, Nl, D), generator=gen, device=dev)
+        fl = fl32
+        for i in range(3):
+            long_fwd(i); long_bwd(i)
+        tf32, tb32 = timed(long_fwd, reps=20), timed(long_bwd, reps=20)
+        result["long_sequence"]["fp32_gates"] = {"fwd_ms": round(tf32 * 1e3, 4), "bwd_ms": round(tb32 * 1e3, 4),
+                                                 "tokens_per_s": round(Bl * Nl / (tf32 + tb32), 1)}
+        del ql, vl_, dOl, fl, fl32, wsl, ol, gql, gfl, gvl
         # the same number of tokens as two documents of unequal length packed along the token axis
         docs = [20000, 12768]
         Tl = sum(docs)
