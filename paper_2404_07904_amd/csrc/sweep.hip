@@ -9,8 +9,9 @@
 // keeping the slab in fp32 MFMA accumulators.  Before each update it writes the slab, scaled by
 // the half-chunk gate product its consumer would apply anyway (G_m of chunk n for S_n, g/G_m for
 // dS_{n+1}) and rounded to the operand type, to the workspace in MFMA-fragment order so that the
-// per-chunk kernels can load it straight into operand registers.  The contraction runs over time, so both operands are
-// staged in LDS token-contiguous (see common.hpp for the thread layout that makes this free).
+// per-chunk kernels can load it straight into operand registers.  The contraction runs over time,
+// so both operands are staged in LDS token-contiguous (see common.hpp for the thread layout that
+// makes this free).
 //
 // A batch of few, long sequences would leave most of the chip idle in such a walk.  The recurrence
 // is linear in the state, so a sequence can be cut into runs of whole chunks: a walk per run from
