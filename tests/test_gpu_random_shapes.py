@@ -166,3 +166,53 @@ def test_random_long_sequences(seed):
     check("o", get(o), ro, tol); check("hT", host(hT), rhT, tol)
     check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
     check("dh0", host(gh0), rh, tol)
+
+
+@pytest.mark.parametrize("seed", range(9400, 9405))
+def test_random_packed_long_documents(seed):
+    """Packed batches long enough on average to be cut into runs: documents of many runs, of one,
+    of none, in random order; gates given or formed in the kernels."""
+    rng = np.random.default_rng(seed)
+    dk, dv = (int(rng.choice([64, 128])) for _ in range(2))
+    B, H = int(rng.integers(2, 5)), int(rng.integers(1, 3))
+    lens = [int(rng.choice([0, int(rng.integers(1, 200)), int(rng.integers(2000, 4500))], p=[0.15, 0.25, 0.6]))
+            for _ in range(B)]
+    lens[int(rng.integers(0, B))] = int(rng.integers(B * 2100, B * 2100 + 1500))      # the mean length is past the cut
+    T = int(sum(lens))
+    gated = bool(rng.integers(0, 2))
+    print("\n[random packed long] seed=%d H=%d dk=%d dv=%d gated=%s lens=%s" % (seed, H, dk, dv, gated, lens), flush=True)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    w = synth.make_sequence(seed, 1, H, T, dk, dv, io_dtype="bf16", lb=0.8, with_dO=True)
+    z = synth.bf16_round((1.0 + 1.5 * rng.standard_normal((1, H, T, dk), dtype=np.float32)).astype(np.float32))
+    beta = rng.uniform(0.5, 0.95, size=(H, dk)).astype(np.float32)
+    gate_in = z if gated else w.f
+    pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
+    un = lambda t: host(t.permute(1, 0, 2))
+    h0 = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    dhT = (0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32)
+    q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
+    cud = torch.from_numpy(cu).cuda()
+    bd = torch.from_numpy(beta).cuda() if gated else None
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    torch.cuda.synchronize()
+    ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
+    rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
+    for b in range(B):
+        s, e = int(cu[b]), int(cu[b + 1])
+        sl = (slice(None), slice(None), slice(s, e))
+        if gated:
+            ob, hTb = oracle.fwd_gated(w.q[sl], z[sl], beta, w.v[sl], h0[b:b + 1])
+            gqb, ggb, gbb, gvb, gh0b = oracle.bwd_gated(w.q[sl], z[sl], beta, w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+            rb += gbb
+        else:
+            ob, hTb = oracle.fwd(w.q[sl], w.f[sl], w.v[sl], h0[b:b + 1])
+            gqb, ggb, gvb, gh0b = oracle.bwd(w.q[sl], w.f[sl], w.v[sl], w.dO[sl], h0[b:b + 1], dhT[b:b + 1])
+        ro[:, s:e], rq[:, s:e], rg[:, s:e], rv[:, s:e] = ob[0], gqb[0], ggb[0], gvb[0]
+        rhT[b], rh0[b] = hTb[0], gh0b[0]
+    tol = TOL["bf16"]
+    check("o", un(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", un(res[0]), rq, tol); check("dgate", un(res[1]), rg, tol); check("dv", un(res[2]), rv, tol)
+    check("dh0", host(res[3]), rh0, tol)
+    if gated:
+        check("dbeta", host(res[4]), rb, tol)
