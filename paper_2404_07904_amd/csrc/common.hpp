@@ -44,11 +44,13 @@ struct SeqView {
     int N, NC;
 };
 
-template <bool DENSE, int DK, int DV>
+// RUNS: the caller is one of the kernels that walk a sequence and may be handed the runs of
+// segmented sequences (TokenLayout::seg); the per-chunk kernels never are.
+template <bool DENSE, int DK, int DV, bool RUNS = false>
 __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int NC, int bh)
 {
     SeqView s;
-    if (lay.seg > 1) {
+    if (RUNS && lay.seg > 1) {
         // run r of sequence bh / seg: N tokens (NC chunks) unless it is the last, shorter one
         const int whole = bh / lay.seg, r = bh - whole * lay.seg;
         const int nc_all = (lay.n_tokens + kChunk - 1) / kChunk;

@@ -130,7 +130,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
-    const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
+    const SeqView sv = seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh);
     const size_t seq_k = sv.off_k, seq_v = sv.off_v;
     const int N = sv.N;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements

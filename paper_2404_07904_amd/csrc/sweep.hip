@@ -74,7 +74,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
     const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;
-    const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
+    const SeqView sv = seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh);
     const size_t seq_k = sv.off_k, seq_v = sv.off_v;
     const int N = sv.N, NC = sv.NC;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
