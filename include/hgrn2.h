@@ -206,6 +206,16 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                      size_t workspace_bytes, void* hip_stream);
 
 /*
+ * hgrn2_min_gate_product for a packed batch: the windows (half chunks: 32 tokens; 16 or 8 with
+ * shape->chunk = 32 or 16) start anew with every sequence, as they do inside hgrn2_fwd_varlen /
+ * hgrn2_bwd_varlen.  f (or the pre-activations, with beta) is [T][H][dk]; the workspace of
+ * hgrn2_min_gate_product_varlen_workspace_bytes(shape) bytes holds the sequence table.
+ */
+size_t hgrn2_min_gate_product_varlen_workspace_bytes(const hgrn2_shape* shape);
+int hgrn2_min_gate_product_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* f, const float* beta,
+                                  float* min_product, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * HGRN1, the element-wise gated linear recurrence the paper starts from (Section 2, Eq. 1, with the
  * forget gate f of Eq. 2 given), per channel:
  *     h_t = f_t * h_{t-1} + (1 - f_t) * i_t,      y_t = h_t * o_t

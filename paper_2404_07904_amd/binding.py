@@ -20,7 +20,7 @@ STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ER
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
            "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
-           "hgrn2_status_string"]
+           "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_min_gate_product.restype = ctypes.c_int
         L.hgrn2_min_gate_product.argtypes = [sp, vp, vp, vp, vp]
+        L.hgrn2_min_gate_product_varlen_workspace_bytes.restype = sz
+        L.hgrn2_min_gate_product_varlen_workspace_bytes.argtypes = [sp]
+        L.hgrn2_min_gate_product_varlen.restype = ctypes.c_int
+        L.hgrn2_min_gate_product_varlen.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_cumax.restype = ctypes.c_int
         L.hgrn2_cumax.argtypes = [i32, i32, vp, vp, vp]
         L.hgrn1_workspace_bytes.restype = sz
@@ -291,6 +295,20 @@ def hgrn2_min_gate_product(f, beta=None, layout=HGRN2_LAYOUT_BHND, chunk=0):
     rc = lib().hgrn2_min_gate_product(ctypes.byref(shape), _ptr(f), _ptr(beta), _ptr(out), _stream())
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_min_gate_product")
+    return out
+
+
+def hgrn2_min_gate_product_varlen(f, cu_seqlens, beta=None, chunk=0):
+    """hgrn2_min_gate_product for sequences packed along the token axis: f [T,H,dk], cu_seqlens int32
+    [n_seq + 1] on the device; the windows start anew with every sequence."""
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
+    shape = make_shape_varlen(f, f, f, cu_seqlens.numel() - 1, chunk)
+    out = torch.empty((1,), dtype=torch.float32, device=f.device)
+    ws = _workspace(int(lib().hgrn2_min_gate_product_varlen_workspace_bytes(ctypes.byref(shape))), f.device, None)
+    rc = lib().hgrn2_min_gate_product_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(f), _ptr(beta), _ptr(out),
+                                             _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_min_gate_product_varlen")
     return out
 
 

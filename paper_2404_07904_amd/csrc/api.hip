@@ -670,6 +670,36 @@ int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float*
     return HGRN2_OK;
 }
 
+size_t hgrn2_min_gate_product_varlen_workspace_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape_varlen(shape, false, &d, true) != HGRN2_OK) return 0;
+    return round256(varlen_table_bytes(shape->B));
+}
+
+int hgrn2_min_gate_product_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* f, const float* beta,
+                                  float* min_product, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, false, &d, true);
+    if (rc != HGRN2_OK) return rc;
+    if (!min_product) return HGRN2_ERR_NULL;
+    if (d.BH > 0 && (!cu_seqlens || (d.N > 0 && !f))) return HGRN2_ERR_NULL;
+    const size_t need = hgrn2_min_gate_product_varlen_workspace_bytes(shape);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    d.beta = beta;
+    if (d.BH == 0) d.NC = 0;                  // no sequences: the probe writes 1
+    else {
+        int* table = static_cast<int*>(workspace);
+        d.lay.vl = table;
+        if (launch_varlen_table(cu_seqlens, shape->B, d.N, table, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    }
+    if (launch_min_gate_product(d, (fine_mode(shape) ? shape->chunk : kChunk) / 2, f, min_product, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
+    return HGRN2_OK;
+}
+
 int hgrn2_cumax(int32_t L, int32_t d, const float* gamma, float* beta, void* hip_stream)
 {
     if (L < 0 || d < 0) return HGRN2_ERR_SHAPE;

@@ -5,6 +5,7 @@
 // the whole call, so that a caller can check its inputs against that bound:
 //     min over (b, h, chunk n, half s, channel a) of  prod_{t in half s of chunk n} f[b, h, t, a]
 // (with reference rows every 16 tokens the windows are 8 tokens long instead of 32).
+// In a packed batch the windows start anew with every sequence, as the chunks do.
 // One wave per (sequence, window): a channel pair per lane, coalesced rows, a butterfly
 // minimum over the lanes, one atomic minimum per wave (non-negative floats order like their bit
 // patterns, so the integer atomic serves).
@@ -18,6 +19,7 @@ struct DomainParams {
     const float* beta;
     float* out;
     int BH, N, n_win, window, dk, gate_bf16, H;
+    long long n_waves;
     TokenLayout lay;
 };
 
@@ -27,19 +29,31 @@ __global__ __launch_bounds__(256) void domain_min_kernel(DomainParams p)
 {
     const int lane = threadIdx.x & 63;
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);      // (sequence, window)
-    const long long n_waves = (long long)p.BH * p.n_win;
-    if (wave >= n_waves) return;
-    const int bh = (int)(wave / p.n_win), hc = (int)(wave % p.n_win);
-    const int row0 = hc * p.window;
+    if (wave >= p.n_waves) return;
+    int bh, row0, n_rows = p.N;
+    size_t seq;
+    if (p.lay.vl) {
+        // packed batch: windows are numbered chunk by chunk through the batch's sequence table
+        const int per_chunk = kChunk / p.window;
+        int n;
+        if (!locate_chunk<false>(p.lay, 0, 0, (int)(wave / per_chunk), bh, n)) return;
+        const SeqView sv = seq_view<false, 0, 0>(p.lay, 0, 0, bh);
+        row0 = n * kChunk + (int)(wave % per_chunk) * p.window;
+        n_rows = sv.N;
+        seq = sv.off_k;
+    } else {
+        bh = (int)(wave / p.n_win);
+        row0 = (int)(wave % p.n_win) * p.window;
+        seq = p.lay.off_k(bh);
+    }
     const bool active = 2 * lane < p.dk;
     const int col = active ? 2 * lane : 0;
-    const size_t seq = p.lay.off_k(bh);
     f32x2 b = {0.0f, 0.0f};
     if (p.beta) b = *reinterpret_cast<const f32x2*>(p.beta + (size_t)(bh % p.H) * p.dk + col);
     float p0 = 1.0f, p1 = 1.0f;
     for (int i = 0; i < p.window; ++i) {
         const int row = row0 + i;
-        if (row >= p.N) break;                                  // uniform over the wave
+        if (row >= n_rows) break;                               // uniform over the wave
         f32x2 g = load_pair(p.f, seq + (size_t)row * p.lay.sn_k + col, p.gate_bf16 != 0);
         if (p.beta) g = f32x2{lower_bounded_gate(g.x, b.x), lower_bounded_gate(g.y, b.y)};
         p0 *= g.x; p1 *= g.y;
@@ -54,11 +68,12 @@ __global__ __launch_bounds__(256) void domain_min_kernel(DomainParams p)
 hipError_t launch_min_gate_product(const SeqDims& d, int window, const void* f, float* out, hipStream_t stream)
 {
     hipLaunchKernelGGL(domain_init_kernel, dim3(1), dim3(1), 0, stream, out);
-    const int n_win = (d.N + window - 1) / window;
-    const long long n_waves = (long long)d.BH * n_win;
+    // packed batch: a bound on the windows of all sequences, a chunk's worth at a time (d.NC bounds the chunks)
+    const int n_win = d.packed ? d.NC * (kChunk / window) : (d.N + window - 1) / window;
+    const long long n_waves = d.packed ? (long long)d.H * n_win : (long long)d.BH * n_win;
     if (n_waves > 0) {
         DomainParams p;
-        p.f = f; p.beta = d.beta; p.out = out; p.BH = d.BH; p.N = d.N; p.n_win = n_win; p.window = window; p.dk = d.dk;
+        p.f = f; p.beta = d.beta; p.out = out; p.BH = d.BH; p.N = d.N; p.n_win = n_win; p.window = window; p.dk = d.dk; p.n_waves = n_waves;
         p.gate_bf16 = d.gate_bf16 ? 1 : 0; p.H = d.H; p.lay = d.lay;
         hipLaunchKernelGGL(domain_min_kernel, dim3((unsigned)((n_waves + 3) / 4)), dim3(256), 0, stream, p);
     }

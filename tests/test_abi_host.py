@@ -277,6 +277,21 @@ def test_varlen_workspace_and_error_codes():
     assert bwd(s, n=table + 2 * states + partials - 1) == E_WS
 
 
+def test_packed_gate_probe_error_codes():
+    lib = binding.lib()
+    s = shape(B=3, H=2, N=500, layout=1)
+    assert binding.lib().hgrn2_min_gate_product_varlen_workspace_bytes(ctypes.byref(s)) == 256
+    call = lambda s_, cu=FAKE, f=FAKE, out=FAKE, ws=FAKE_WS, n=1 << 20: lib.hgrn2_min_gate_product_varlen(
+        ctypes.byref(s_), cu, f, None, out, ws, n, None)
+    assert call(shape(B=3, H=2, N=500, layout=0)) == E_SHAPE            # packed tokens are token-major
+    assert call(s, out=None) == E_NULL
+    assert call(s, cu=None) == E_NULL
+    assert call(s, f=None) == E_NULL
+    assert call(s, ws=None) == E_WS
+    assert call(s, n=255) == E_WS
+    assert call(shape(B=3, H=2, N=500, layout=1, chunk=48)) == E_UNSUP
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
     import subprocess

@@ -144,6 +144,13 @@ def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk):
     bd = torch.from_numpy(beta).cuda() if gated else None
     o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk)
     res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk)
+    # the probe on the packed batch: windows restart with every sequence
+    gates = oracle.gate(z, beta) if gated else w.f
+    for ck in (0, chunk):
+        got = float(binding.hgrn2_min_gate_product_varlen(g, cud, beta=bd, chunk=ck).item())
+        ref = min([oracle.min_gate_product(gates[:, :, int(cu[b]):int(cu[b + 1])], chunk=ck or 64) for b in range(B)] + [1.0])
+        print("    smallest gate product, chunk=%d: %.3e (oracle %.3e)" % (ck, got, ref), flush=True)
+        assert abs(got - ref) <= 1e-3 * ref + 1e-44
     torch.cuda.synchronize()
     ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
     rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
