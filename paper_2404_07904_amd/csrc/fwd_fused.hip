@@ -536,9 +536,11 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
     p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
-    // one workgroup per sequence fills the 256 compute units from 256 sequences on; below that,
-    // two workgroups per sequence (each half of the dv columns) keep twice as many units busy
-    return d.BH > 192 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
+    // Two workgroups per sequence (each half of the dv columns) keep twice as many compute units
+    // busy, but a compute unit holds one workgroup: beyond 128 sequences the halves would no longer
+    // all run at once (a second round: 137 us instead of 84 us for 144 sequences of 2048 tokens), so
+    // from there on a sequence gets one workgroup.
+    return d.BH > 128 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
 }
 
 }   // namespace hgrn2

@@ -109,7 +109,7 @@ def test_fwd_fused_path(N, gate):
 @pytest.mark.parametrize("N", [65, 200])
 @pytest.mark.parametrize("gate", ["bf16", "f32"])
 def test_fwd_fused_path_many_sequences(N, gate):
-    """More than 192 sequences: one workgroup per sequence owning all dv columns (below that, two
+    """More than 128 sequences: one workgroup per sequence owning all dv columns (up to 128, two
     workgroups share a sequence, which is what the other fused-path cases run)."""
     print("\n[fwd fused] B*H=203 N=%d gate=%s" % (N, gate), flush=True)
     w = synth.make_sequence(700 + N, 29, 7, N, 128, 128, io_dtype="bf16", gate_dtype=gate, lb=0.2, with_h0=True)
