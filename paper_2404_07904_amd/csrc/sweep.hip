@@ -300,13 +300,14 @@ template <typename T, int DK, int DV, bool ENDS>
 static hipError_t launch_pair_tv(const SeqDims& d, const SweepParams& ps, const SweepParams& pg, hipStream_t stream)
 {
     // The sweeps are bound by the element-wise work on the gates, which every column slab of a
-    // sequence repeats: use the widest slab that still gives each of the 256 CUs a workgroup
-    // (two sweeps share the grid).
+    // sequence repeats, and two workgroups on one compute unit take twice as long: narrower slabs
+    // only as long as all workgroups still find a compute unit of their own (two sweeps share the
+    // grid: 2 x 32 sequences x 4 slabs, 2 x 64 x 2, 2 x 128 x 1 fill the 256 units).
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH < 48) return launch_pair_one<T, DK, DV, 32, ENDS>(d, ps, pg, stream);
+        if (d.BH <= 32) return launch_pair_one<T, DK, DV, 32, ENDS>(d, ps, pg, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH < 128) return launch_pair_one<T, DK, DV, 64, ENDS>(d, ps, pg, stream);
+        if (d.BH <= 64) return launch_pair_one<T, DK, DV, 64, ENDS>(d, ps, pg, stream);
     }
     return launch_pair_one<T, DK, DV, DV, ENDS>(d, ps, pg, stream);
 }
@@ -330,12 +331,12 @@ static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_
 template <typename T, int DK, int DV, int MODE, bool ENDS>
 static hipError_t launch_tv(const SeqDims& d, const SweepParams& p, hipStream_t stream)
 {
-    // Narrow slabs when there are few sequences, so that the sweep still covers the 256 CUs.
+    // Narrow slabs when there are few sequences, as long as every workgroup gets a compute unit of its own.
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH < 96) return launch_one<T, DK, DV, 32, MODE, ENDS>(d, p, stream);
+        if (d.BH <= 64) return launch_one<T, DK, DV, 32, MODE, ENDS>(d, p, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH < 256) return launch_one<T, DK, DV, 64, MODE, ENDS>(d, p, stream);
+        if (d.BH <= 128) return launch_one<T, DK, DV, 64, MODE, ENDS>(d, p, stream);
     }
     return launch_one<T, DK, DV, DV, MODE, ENDS>(d, p, stream);
 }
