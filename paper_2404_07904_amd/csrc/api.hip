@@ -90,7 +90,7 @@ int plan_runs(const SeqDims& d, bool backward, int* run_chunks)
     // chip, so they gain from 32 chunks on, up to 32 sequences, with about 128 runs each and runs
     // of 8 chunks or more.
     if (d.packed || d.NC < (backward ? 32 : 16) || d.BH == 0 || d.BH > (backward ? 32 : 64)) return 1;
-    const int fill = (backward ? 128 : 256) / d.BH;      // rounded down: one run more than fits would need a second round
+    const int fill = (backward ? 128 : 256) / d.BH;      // rounded down: a walk more than there are units has to wait for a free one
     const int by_length = d.NC / (backward ? 8 : 4);
     const int seg = fill < by_length ? fill : by_length;
     if (seg < 2) return 1;

@@ -538,7 +538,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     // Two workgroups per sequence (each half of the dv columns) keep twice as many compute units
     // busy, but a compute unit holds one workgroup: beyond 128 sequences the halves would no longer
-    // all run at once (a second round: 137 us instead of 84 us for 144 sequences of 2048 tokens), so
+    // all run at once (the rest waits for a free unit: 137 us instead of 84 us for 144 sequences of 2048 tokens), so
     // from there on a sequence gets one workgroup.
     return d.BH > 128 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
 }
