@@ -63,16 +63,8 @@ struct BwdGradParams {
     int H;
     TokenLayout lay;         // used when dense == 0
     int dense;               // sequence tensors are [B][H][N][d]
-#ifdef HGRN2_PHASE_TIMING
-    long long* dbg;      // [workgroup][wave][24] clock ticks per phase (diagnostic builds only)
-#endif
 };
 
-#ifdef HGRN2_PHASE_TIMING
-#define HGRN2_STAMP(k) do { const long long t_now = wall_clock64(); ph[k] = t_now - t_prev; t_prev = t_now; } while (0)
-#else
-#define HGRN2_STAMP(k) do { } while (0)
-#endif
 
 template <typename T, int DK, int DV> struct BwdGradLds {
     static constexpr int C = kChunk;
@@ -236,11 +228,6 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     const size_t ld_k = DENSE ? (size_t)DK : (size_t)p.lay.sn_k, ld_v = DENSE ? (size_t)DV : (size_t)p.lay.sn_v;
     load_chunk_states(sS, sD, chunk, lane);      // first needed two barriers from here; covered by the element-wise stage
 
-#ifdef HGRN2_PHASE_TIMING
-    long long ph[24] = {0};
-    long long t_prev = wall_clock64();
-    ph[20] = t_prev;
-#endif
     // V, dO tiles: raw bits, the four 4-column quads of a 16-column group stored in the order
     // (0, 2, 1, 3), i.e. column b at position b with bits 2 and 3 swapped
     if (vd_act) {
@@ -279,9 +266,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 #pragma unroll
         for (int i = RW - 1; i >= 0; --i) { z0[i] = u0; z1[i] = u1; u0 *= rf[i].x; u1 *= rf[i].y; }
         if (k_act) *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{t0, t1};
-        HGRN2_STAMP(0);
         __syncthreads();
-        HGRN2_STAMP(1);
         if (k_act) {
             // product of the (at most three) block totals between this block and the reference
             // row; the row addresses are wave-uniform, an absent factor reads the row of ones
@@ -328,9 +313,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         for (int v = 0; v < 16; ++v) rs = (v == vsel) ? accR[v] : rs;
         if (g == ((r32 >> 2) & 1)) Rp[ch] = rs;
     }
-    HGRN2_STAMP(2);
     __syncthreads();
-    HGRN2_STAMP(3);
 
     // ---------------- P^T and dP^T blocks ----------------
     // waves 0..2: P blocks (I,J) = (0,0), (1,0), (1,1); waves 3..5: the same for dP; waves 6, 7 zero
@@ -377,9 +360,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1)) = z;
         *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1) + 8) = z;
     }
-    HGRN2_STAMP(4);
     __syncthreads();
-    HGRN2_STAMP(5);
 
     // ---------------- main contractions ----------------
     // dv tile (rt_b, bt) first: P^T dO over the chunk and K~ (H_m dS) over the channels (the masked
@@ -424,9 +405,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     RawRows<RW> nxt_f, nxt_q;
     const ChunkAt nxt = where(min(chunk + (int)gridDim.x, n_chunks - 1));
     load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, nxt, lane);   // v, dO of this chunk are dead
-    HGRN2_STAMP(6);
     __syncthreads();     // every wave is done with the operand tiles
-    HGRN2_STAMP(7);
 
     // ---------------- staging: X, Y1, Ks as [row][channel] fp32, 16 bytes per store ----------------
     if (has_a) {
@@ -438,9 +417,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             *reinterpret_cast<f32x4*>(cKs + o) = f32x4{aKs[4 * c], aKs[4 * c + 1], aKs[4 * c + 2], aKs[4 * c + 3]};
         }
     }
-    HGRN2_STAMP(8);
     __syncthreads();
-    HGRN2_STAMP(9);
 
     // ---------------- element-wise epilogue in the row-block / channel-pair layout ----------------
     //   dq = sq X,  dk = sk (Y1 + Ks),  e' = bf16(Q~) X - bf16(K~) Y1,  kk = bf16(K~) Ks
@@ -501,9 +478,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                     *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * 8);
         }
     }
-    HGRN2_STAMP(10);
     __syncthreads();
-    HGRN2_STAMP(12);
     if (k_act) {
         // R + block sums of e' of the later blocks + block sums of K~ Ks of the earlier ones (row
         // addresses are wave-uniform; this block's own slot reads the row of zeros)
@@ -536,12 +511,6 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         }
         store_block(dfg, gs0, gs1);
     }
-#ifdef HGRN2_PHASE_TIMING
-    HGRN2_STAMP(17);
-    ph[21] = t_prev;
-    if (lane == 0 && p.dbg)
-        for (int k = 0; k < 24; ++k) p.dbg[((size_t)chunk * NW + w) * 24 + k] = ph[k];
-#endif
     raw_f = nxt_f;
     raw_q = nxt_q;
     cur = nxt;
@@ -561,8 +530,7 @@ static hipError_t launch_one(const SeqDims& d, const BwdGradParams& p, hipStream
 {
     typedef BwdGradLds<T, DK, DV> L;
     auto kern = d.gate_bf16 ? bwd_grad_kernel<T, DK, DV, true> : bwd_grad_kernel<T, DK, DV, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
     if (e != hipSuccess) return e;
     // one persistent workgroup per CU (the LDS footprint admits no more), each walking its share of chunks
     const size_t n_chunks = d.total_chunks();
@@ -583,9 +551,6 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     p.BH = d.BH; p.N = d.N; p.NC = d.NC;
     p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
-#ifdef HGRN2_PHASE_TIMING
-    p.dbg = nullptr;
-#endif
     if (d.dk == 128 && d.dv == 128) return launch_one<__bf16, 128, 128>(d, p, stream);
     if (d.dk == 64 && d.dv == 64) return launch_one<__bf16, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 64) return launch_one<__bf16, 128, 64>(d, p, stream);

@@ -54,16 +54,8 @@ struct FwdFusedParams {
     int H;
     TokenLayout lay;     // used when dense == 0
     int dense;           // sequence tensors are [B][H][N][d]: token strides are the compile-time dk, dv
-#ifdef HGRN2_PHASE_TIMING
-    long long* dbg;      // [workgroup][wave][16] accumulated clock ticks per phase (diagnostic builds only)
-#endif
 };
 
-#ifdef HGRN2_PHASE_TIMING
-#define HGRN2_STAMP(k) do { const long long t_now = wall_clock64(); ph[k] += t_now - t_prev; t_prev = t_now; } while (0)
-#else
-#define HGRN2_STAMP(k) do { } while (0)
-#endif
 
 template <int NSPLIT> struct FwdFusedLds {
     static constexpr int DK = 128, DV = 128, DVW = DV / NSPLIT, C = kChunk;   // DVW: dv columns of one workgroup
@@ -295,10 +287,6 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         }
     };
 
-#ifdef HGRN2_PHASE_TIMING
-    long long ph[16] = {0};
-    long long t_prev = wall_clock64();
-#endif
 
     // ---- prologue: rows of chunks 0 and 1 in flight, element-wise work of chunk 0 ----
     // the never-written block of P (rows 0..31 x columns 32..63) must read as zero
@@ -357,7 +345,6 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         if (!LATE_QS) store_o(n - 1);
         store_v(rawv[VD == 2 ? par : 0]);
         load_v(rawv[VD == 2 ? par : 0], n + VD);
-        HGRN2_STAMP(7);
         // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
 #pragma unroll
         for (int j = 0; j < NST; ++j) {
@@ -375,11 +362,8 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
                 *reinterpret_cast<frag*>(Sp + state_frag_offset(at0 + j, bt, NBT, half, lane)) = M::pack(x);
             }
         }
-        HGRN2_STAMP(8);
         prep_gates(rawf[1 - par], rawq[1 - par], n + 1);
-        HGRN2_STAMP(9);
         load_f(rawf[1 - par], n + 3); load_q(rawq[1 - par], n + 3);
-        HGRN2_STAMP(0);
         if (LATE_QS) {
             // O(n-1) is completed here: its P V part was accumulated in stage B of the previous pass
             if (has_o) {
@@ -427,9 +411,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
                 *reinterpret_cast<bf16x4*>(Pm + (size_t)i_glob * PC + j0) = pk;
             }
         }
-        HGRN2_STAMP(1);
         __syncthreads();
-        HGRN2_STAMP(2);
         // ======================= stage B =======================
         // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
         if (LATE_QS) store_o(n - 1);
@@ -455,16 +437,12 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             }
         }
         if (!LATE_QS) read_out_state(Qc, Sp);
-        HGRN2_STAMP(3);
         prep_tiles(n + 1);
-        HGRN2_STAMP(4);
         if (!LATE_QS) {
             if (has_o) stage_o();
             pin_obuf();
         }
-        HGRN2_STAMP(5);
         __syncthreads();
-        HGRN2_STAMP(6);
     };
 
     int n_end = 0;
@@ -487,10 +465,6 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         store_o(n_end - 1);
     }
 
-#ifdef HGRN2_PHASE_TIMING
-    if (lane == 0 && p.dbg)
-        for (int k = 0; k < 16; ++k) p.dbg[((size_t)blockIdx.x * NW + w) * 16 + k] = ph[k];
-#endif
     if (p.hT) {
         // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1)
         float* s1 = p.hT + (size_t)bh * DK * DV;
@@ -521,8 +495,7 @@ static hipError_t launch_fused(const SeqDims& d, const FwdFusedParams& p, hipStr
 {
     typedef FwdFusedLds<NSPLIT> L;
     auto kern = d.gate_bf16 ? fwd_fused_kernel<true, NSPLIT> : fwd_fused_kernel<false, NSPLIT>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
     if (e != hipSuccess) return e;
     const unsigned grid = (NSPLIT == 1) ? (unsigned)d.BH : (unsigned)(NSPLIT * 8 * ((d.BH + 7) / 8));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedThreads), L::total, stream, p);

@@ -229,8 +229,7 @@ static hipError_t launch_one(const SeqDims& d, const FwdOutParams& p, hipStream_
 {
     typedef FwdOutLds<T, DK, DV> L;
     auto kern = fwd_out_kernel<T, DK, DV>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)L::total);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)d.total_chunks()), dim3(kThreads), L::total, stream, p);
     return hipGetLastError();

@@ -56,6 +56,33 @@ struct SeqDims {
     size_t total_chunks() const { return packed ? (size_t)H * NC : (size_t)BH * NC; }
 };
 
+// A kernel that uses more dynamic LDS than the default limit must have the limit raised once per
+// device; the setting is remembered here so that a launch does not repeat the runtime call.
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes)
+{
+    struct Slot { const void* kernel; unsigned long long devices; };
+    static Slot slots[256];                 // racing first launches at worst repeat the runtime call
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    size_t i = (reinterpret_cast<size_t>(kernel) >> 4) & 255;
+    for (int probe = 0; probe < 256; ++probe, i = (i + 1) & 255) {
+        if (slots[i].kernel == kernel) {
+            if (slots[i].devices & bit) return hipSuccess;
+            break;
+        }
+        if (slots[i].kernel == nullptr) break;
+    }
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    if (slots[i].kernel == nullptr || slots[i].kernel == kernel) {
+        slots[i].kernel = kernel;
+        slots[i].devices |= bit;
+    }
+    return hipSuccess;
+}
+
 // What a state sweep accumulates.
 enum SweepMode {
     kSweepStateFwd = 0,   // S_n for the forward read-out   (fragments contract over dk)
@@ -76,8 +103,8 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
                              const float* h0, const float* grad_hT, float* grad_h0, void* ws_state,
                              void* ws_dstate, hipStream_t stream);
 
-// Segmented sweeps.  A sweep with a null workspace walks every sequence from a zero state and
-// leaves the state after its last chunk in `final_state` and the per-channel product of all its
+// Segmented sweeps.  A sweep given a `decay` array walks every sequence from a zero state, writes
+// nothing per chunk (`ws` is ignored) and leaves the state after its last chunk in `final_state` and the per-channel product of all its
 // gates in `decay` ([BH][dk]); launch_sweep_pair_ends does so for both backward sweeps (one copy of
 // the gate products).  Called on the runs of segmented sequences (TokenLayout::seg), these give
 // launch_run_carry what it needs to turn run_state ([n_seq * seg][dk][dv], overwritten) into the

@@ -30,22 +30,14 @@ struct SweepParams {
     const float* init;
     float* fin;
     void* ws;
-    float* decay;        // walks from zero (null ws): per-channel product of all gates of the sequence, [BH][dk], or null
+    float* decay;        // set: walk from zero, nothing per chunk; receives the per-channel product of all gates of the sequence, [BH][dk], or null
     int BH, N, NC, n_tile, gate_bf16;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
     TokenLayout lay;     // used when dense == 0
     int dense;           // sequence tensors are [B][H][N][d]: token strides are the compile-time dk, dv
-#ifdef HGRN2_PHASE_TIMING
-    long long* dbg;      // [workgroup][wave][8] accumulated clock ticks per phase (diagnostic builds only)
-#endif
 };
 
-#ifdef HGRN2_PHASE_TIMING
-#define HGRN2_STAMP(k) do { const long long t_now = wall_clock64(); ph[k] += t_now - t_prev; t_prev = t_now; } while (0)
-#else
-#define HGRN2_STAMP(k) do { } while (0)
-#endif
 
 template <typename T, int DK, int DV, int TV, int MODE, bool DENSE, bool ENDS>
 __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
@@ -113,10 +105,6 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     float run_decay = 1.0f;      // ENDS: thread t < DK, gate product of channel t so far
     if (NC > 0) load_chunk(REVERSE ? NC - 1 : 0);
 
-#ifdef HGRN2_PHASE_TIMING
-    long long ph[8] = {0};
-    long long t_prev = wall_clock64();
-#endif
     for (int it = 0; it < NC; ++it) {
         const int n = REVERSE ? NC - 1 - it : it;
         f32x2 rf[RW], rq[RW], rb[RW];
@@ -142,9 +130,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             tot[w * DK + 2 * lane] = a0[RW - 1];
             tot[w * DK + 2 * lane + 1] = a1[RW - 1];
         }
-        HGRN2_STAMP(0);
         __syncthreads();
-        HGRN2_STAMP(1);
         if (a_act) {
             const BlockDecay d0 = block_decay(tot, DK, w, 2 * lane);
             const BlockDecay d1 = block_decay(tot, DK, w, 2 * lane + 1);
@@ -177,11 +163,8 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             store_run<T, RW>(BT + (2 * lane) * PC + RW * w, x0);
             store_run<T, RW>(BT + (2 * lane + 1) * PC + RW * w, x1);
         }
-        HGRN2_STAMP(2);
         if (it + 1 < NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
-        HGRN2_STAMP(3);
         __syncthreads();
-        HGRN2_STAMP(4);
 
         // ---- hand the slab as it stands (state entering / gradient leaving chunk n) to the workspace
         T* wsn = ws + (size_t)n * DK * DV;
@@ -207,7 +190,6 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             }
         }
 
-        HGRN2_STAMP(5);
         // ---- slab = Diag(g) slab + A^T B over the chunk ----
 #pragma unroll
         for (int j = 0; j < TPW; ++j) {
@@ -236,13 +218,8 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
                 else       M::mma(acc[j], fa, fb);
             }
         }
-        HGRN2_STAMP(6);
     }
 
-#ifdef HGRN2_PHASE_TIMING
-    if (lane == 0 && p.dbg)
-        for (int k = 0; k < 8; ++k) p.dbg[((size_t)block_id * kWaves + w) * 8 + k] = ph[k];
-#endif
     if (ENDS && tile == 0 && tid < DK && p.decay) p.decay[(size_t)bh * DK + tid] = run_decay;
     if (p.fin) {
         float* s1 = p.fin + (size_t)bh * DK * DV;
@@ -288,8 +265,7 @@ static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, cons
     constexpr int PC = kChunk + pad_elems<T>();
     const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
     auto kern = sweep_pair_kernel<T, DK, DV, TV, ENDS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds);
     if (e != hipSuccess) return e;
     const int half = (d.BH + 7) / 8 * 8 * ps.n_tile;
     hipLaunchKernelGGL(kern, dim3(2 * half), dim3(kThreads), lds, stream, ps, pg, half);
@@ -320,8 +296,7 @@ static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_
     constexpr int PC = kChunk + pad_elems<T>();
     const size_t lds = (size_t)(DK + TV) * PC * sizeof(T) + (size_t)(2 + kWaves) * DK * sizeof(float);
     auto kern = sweep_kernel<T, DK, DV, TV, MODE, ENDS>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds);
     if (e != hipSuccess) return e;
     const int seq_pad = (d.BH + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(seq_pad * p.n_tile), dim3(kThreads), lds, stream, p);
@@ -351,11 +326,13 @@ static hipError_t launch_dims_e(const SeqDims& d, const SweepParams& p, hipStrea
     return hipErrorInvalidValue;
 }
 
-// no workspace to fill: only the end state and the gate product are wanted
+// A caller that asks for the gate products wants a walk from zero: only the end state and the
+// products, nothing per chunk.  (A null workspace alone does not say so: an empty sequence needs
+// none, and its end state is the initial one.)
 template <typename T, int MODE>
 static hipError_t launch_dims(const SeqDims& d, const SweepParams& p, hipStream_t stream)
 {
-    return p.ws ? launch_dims_e<T, MODE, false>(d, p, stream) : launch_dims_e<T, MODE, true>(d, p, stream);
+    return p.decay ? launch_dims_e<T, MODE, true>(d, p, stream) : launch_dims_e<T, MODE, false>(d, p, stream);
 }
 
 hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const void* f, const void* b_src,
