@@ -289,6 +289,26 @@ int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f
                           const void* chunk_state_grads /* STATE_GRAD */, void* grad_q, void* grad_f,
                           void* grad_v, void* hip_stream);
 
+/*
+ * hgrn2_bwd for callers that cannot allocate device memory or pass a workspace: code that runs
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  The
+ * call allocates nothing; its workspace is a fixed array of hgrn2_noalloc_workspace_limit() bytes
+ * (32 MiB) of device memory that is part of the library itself (every GPU the library is used on
+ * holds its own copy until the process ends).  Arguments, results and status codes are those of
+ * hgrn2_bwd; a shape whose hgrn2_bwd_workspace_bytes exceeds the limit returns
+ * HGRN2_ERR_WORKSPACE before anything is launched.  The array is shared by all calls on a GPU
+ * and keeps the last call's contents (the kernels write every part of it before they read it):
+ * two such calls that overlap in time on one GPU, e.g. on two streams, race.
+ * hgrn2_noalloc_init() looks up the array's address on the current device (the entry point does
+ * so itself on its first call on a device; a caller that captures graphs calls it, or the entry
+ * point, once beforehand).
+ */
+size_t hgrn2_noalloc_workspace_limit(void);
+int hgrn2_noalloc_init(void);
+int hgrn2_bwd_noalloc(const hgrn2_shape* shape, const void* q, const void* f, const void* v,
+                      const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                      void* grad_f, void* grad_v, float* grad_h0, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* hgrn2_status_string(int status);
 

@@ -20,7 +20,8 @@ STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ER
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
            "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
-           "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string"]
+           "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
+           "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
@@ -99,6 +100,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_readout.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_bwd_chunk_grads.restype = ctypes.c_int
         L.hgrn2_bwd_chunk_grads.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_noalloc_workspace_limit.restype = sz
+        L.hgrn2_noalloc_workspace_limit.argtypes = []
+        L.hgrn2_noalloc_init.restype = ctypes.c_int
+        L.hgrn2_noalloc_init.argtypes = []
+        L.hgrn2_bwd_noalloc.restype = ctypes.c_int
+        L.hgrn2_bwd_noalloc.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_status_string.restype = ctypes.c_char_p
         L.hgrn2_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -186,6 +193,22 @@ def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chu
                          _ptr(ws), ws.numel(), _stream())
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd")
+    return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgrn2_noalloc_workspace_limit() -> int:
+    return int(lib().hgrn2_noalloc_workspace_limit())
+
+
+def hgrn2_bwd_noalloc(q, f, v, grad_o, h0, grad_hT, grad_q, grad_f, grad_v, grad_h0=None, *, chunk=0,
+                      layout=HGRN2_LAYOUT_BHND):
+    """hgrn2_bwd on the library's built-in scratch array: every output is the caller's, nothing is
+    allocated here or in the library."""
+    shape = make_shape(q, v, f, chunk, layout)
+    rc = lib().hgrn2_bwd_noalloc(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(grad_o),
+                                 _ptr(grad_hT), _ptr(grad_q), _ptr(grad_f), _ptr(grad_v), _ptr(grad_h0), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd_noalloc")
     return grad_q, grad_f, grad_v, grad_h0
 
 

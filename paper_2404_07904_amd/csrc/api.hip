@@ -448,6 +448,56 @@ int hgrn2_bwd(const hgrn2_shape* shape, const void* q, const void* f, const void
                     workspace, workspace_bytes, hip_stream);
 }
 
+// ---- hgrn2_bwd for callers that may not allocate ------------------------------------------------
+// The workspace is a fixed array in device memory that belongs to the library's code object: every
+// GPU the library runs on holds its own copy, at its own address, until the process ends.
+namespace {
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+}
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+void* scratch_ptr[kMaxDevices];          // address of `scratch` on each device, once asked for
+
+// The array's name is only a handle on the host; its device address has to be looked up, once per
+// device, with that device current.
+int scratch_of_current_device(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HGRN2_ERR_HIP;
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return HGRN2_ERR_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return HGRN2_OK;
+}
+}   // namespace
+
+size_t hgrn2_noalloc_workspace_limit(void) { return kScratchBytes; }
+
+int hgrn2_noalloc_init(void)
+{
+    void* ptr;
+    return scratch_of_current_device(&ptr);
+}
+
+int hgrn2_bwd_noalloc(const hgrn2_shape* shape, const void* q, const void* f, const void* v, const float* h0,
+                      const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f, void* grad_v,
+                      float* grad_h0, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d, false, true);
+    if (rc != HGRN2_OK) return rc;
+    if (hgrn2_bwd_workspace_bytes(shape) > kScratchBytes) return HGRN2_ERR_WORKSPACE;
+    void* ws = nullptr;
+    const int rs = scratch_of_current_device(&ws);
+    if (rs != HGRN2_OK) return rs;
+    return bwd_impl(shape, q, f, nullptr, false, v, h0, grad_o, grad_hT, grad_q, grad_f, nullptr, grad_v, grad_h0, ws,
+                    kScratchBytes, hip_stream);
+}
+
 int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, const float* beta, const void* v,
                     const float* h0, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_z,
                     float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
@@ -884,7 +934,7 @@ const char* hgrn2_status_string(int status)
     case HGRN2_ERR_NULL: return "a required pointer is NULL";
     case HGRN2_ERR_SHAPE: return "invalid shape or dtype";
     case HGRN2_ERR_UNSUPPORTED: return "shape, chunk or dtype outside the supported set";
-    case HGRN2_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+    case HGRN2_ERR_WORKSPACE: return "workspace missing, too small or misaligned (or the shape needs more than the built-in scratch array holds)";
     case HGRN2_ERR_HIP: return "HIP launch error";
     default: return "unknown status";
     }

@@ -1,0 +1,63 @@
+"""hgrn2_bwd_noalloc, the backward entry point that allocates nothing (its workspace is an array
+inside the library), against hgrn2_bwd on the same inputs: two calls in a row, the second on a
+smaller input, so that what the first call left in the shared array must not matter."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_07904_amd import binding, synth
+from gpu_util import TOL, dev, host, check
+
+pytestmark = pytest.mark.gpu
+
+
+def run_pair(seed, B, H, N, dk, dv, layout=binding.HGRN2_LAYOUT_BHND):
+    w = synth.make_sequence(seed, B, H, N, dk, dv, io_dtype="bf16", lb=0.2, with_h0=True, with_dO=True,
+                            with_dhT=True)
+    q, f, v, dO = (dev(x, "bf16") for x in (w.q, w.f, w.v, w.dO))
+    if layout == binding.HGRN2_LAYOUT_BNHD:
+        q, f, v, dO = (t.permute(0, 2, 1, 3).contiguous() for t in (q, f, v, dO))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    ref = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout)
+    # outputs pre-filled with a pattern: the call has to write every element
+    outs = [torch.full_like(q, 7.0), torch.full_like(q, 7.0), torch.full_like(v, 7.0),
+            torch.full((B, H, dk, dv), 7.0, dtype=torch.float32, device=q.device)]
+    got = binding.hgrn2_bwd_noalloc(q, f, v, dO, h0, dhT, *outs, layout=layout)
+    torch.cuda.synchronize()
+    for name, x, r in zip(("dq", "df", "dv", "dh0"), got, ref):
+        check(name, host(x), host(r), TOL["bf16"])
+        # same kernels, same inputs, deterministic summation order: the two agree bit for bit
+        assert torch.equal(x, r), "%s differs from hgrn2_bwd" % name
+
+
+def test_two_calls_second_smaller():
+    print("\n  first call: B=2 H=3 N=300 dk=128 dv=64", flush=True)
+    run_pair(901, 2, 3, 300, 128, 64)
+    print("  second call (smaller): B=1 H=2 N=70 dk=64 dv=64", flush=True)
+    run_pair(902, 1, 2, 70, 64, 64)
+    print("  third call, token-major: B=2 H=2 N=130 dk=128 dv=128", flush=True)
+    run_pair(903, 2, 2, 130, 128, 128, layout=binding.HGRN2_LAYOUT_BNHD)
+
+
+def test_limit_is_enforced_before_any_launch():
+    limit = binding.hgrn2_noalloc_workspace_limit()
+    assert limit == 32 << 20
+    big = binding.hgrn2_shape(8, 16, 2048, 128, 128, 0, binding.HGRN2_BF16, binding.HGRN2_BF16, 0)
+    assert binding.hgrn2_bwd_workspace_bytes(big) > limit
+    fake = ctypes.c_void_p(0x10000)       # never dereferenced: the call fails on the host
+    rc = binding.lib().hgrn2_bwd_noalloc(ctypes.byref(big), fake, fake, fake, None, fake, None, fake, fake, fake,
+                                         None, None)
+    assert rc == 4, rc                     # HGRN2_ERR_WORKSPACE
+    assert binding.lib().hgrn2_noalloc_init() == 0
+
+
+def test_empty_call():
+    q = torch.empty((2, 3, 0, 64), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty((2, 3, 0, 64), dtype=torch.bfloat16, device="cuda")
+    dhT = torch.randn((2, 3, 64, 64), dtype=torch.float32, device="cuda")
+    dh0 = torch.zeros_like(dhT)
+    binding.hgrn2_bwd_noalloc(q, q, v, v, None, dhT, q.clone(), q.clone(), v.clone(), dh0)
+    torch.cuda.synchronize()
+    assert torch.equal(dh0, dhT)           # no tokens: the state gradient passes through unchanged
