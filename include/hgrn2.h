@@ -22,8 +22,10 @@
  *     frees or retains device memory and keeps no state between calls.
  *   - Work is enqueued on the caller's HIP stream (`hip_stream` is a hipStream_t, NULL = the
  *     default stream).  No entry point synchronises with the host.
- *   - Return value: an hgrn2_status.  Argument errors are detected on the host before anything
- *     is launched; on error nothing has been enqueued.  Nothing throws or aborts across the ABI.
+ *   - Return value: an hgrn2_status.  Argument errors (every status but HGRN2_ERR_HIP) are
+ *     detected on the host before anything is launched: nothing has been enqueued then.
+ *     HGRN2_ERR_HIP reports a failed launch; earlier kernels of the same call may have been
+ *     enqueued.  Nothing throws or aborts across the ABI.
  *   - Gate domain: f in [0, 1].  Results are exact (up to rounding) while the product of the
  *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
  *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
@@ -142,6 +144,33 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
                     const void* v, const float* h0, const void* grad_o, const float* grad_hT,
                     void* grad_q, void* grad_z, float* grad_beta, void* grad_v, float* grad_h0,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Training pair.  The backward pass needs the state S_n entering every chunk of 64 tokens (the
+ * chunkwise regrouping of Eq. 3, Section 3.2).  hgrn2_bwd recomputes them with a sweep over f and v;
+ * a caller that runs the forward pass of the same step anyway can have it keep them instead:
+ * hgrn2_fwd_saving is hgrn2_fwd (beta == NULL) or hgrn2_fwd_gated (beta given: `f` holds the
+ * pre-activations z of Eq. 2) that also fills `saved_states`, and hgrn2_bwd_saved is hgrn2_bwd /
+ * hgrn2_bwd_gated that reads them and runs no sweep of its own.
+ *   saved_states   device, hgrn2_saved_states_bytes(shape) bytes (2 dk dv bytes per chunk and
+ *                  (batch, head): bf16, in a private order), 256-byte aligned.  Valid for the very
+ *                  q, f (or z, beta), v, h0 and shape of the forward call that wrote it.
+ *   workspace      hgrn2_fwd_workspace_bytes(shape) for the forward call,
+ *                  hgrn2_bwd_saved_workspace_bytes(shape, gated) for the backward call
+ *   grad_beta      required when beta is given, ignored otherwise
+ * BF16 storage, chunk = 0 or 64, equal-length batches in either layout; other arguments, results
+ * (those of the stateless calls up to the rounding of the states), status codes and stream
+ * semantics as above.
+ */
+size_t hgrn2_saved_states_bytes(const hgrn2_shape* shape);
+size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated);
+int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,
+                     const float* h0, void* o, float* hT, void* saved_states, size_t saved_states_bytes,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,
+                    const void* saved_states, size_t saved_states_bytes, const void* grad_o,
+                    const float* grad_hT, void* grad_q, void* grad_f, float* grad_beta, void* grad_v,
+                    float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Lower bounds of all L layers from the learnable matrix Gamma (Section 2): softmax over the layer

@@ -21,7 +21,8 @@ EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd"
            "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
-           "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc"]
+           "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc",
+           "hgrn2_saved_states_bytes", "hgrn2_bwd_saved_workspace_bytes", "hgrn2_fwd_saving", "hgrn2_bwd_saved"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
@@ -100,6 +101,14 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_readout.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_bwd_chunk_grads.restype = ctypes.c_int
         L.hgrn2_bwd_chunk_grads.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_saved_states_bytes.restype = sz
+        L.hgrn2_saved_states_bytes.argtypes = [sp]
+        L.hgrn2_bwd_saved_workspace_bytes.restype = sz
+        L.hgrn2_bwd_saved_workspace_bytes.argtypes = [sp, i32]
+        L.hgrn2_fwd_saving.restype = ctypes.c_int
+        L.hgrn2_fwd_saving.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.hgrn2_bwd_saved.restype = ctypes.c_int
+        L.hgrn2_bwd_saved.argtypes = [sp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_noalloc_workspace_limit.restype = sz
         L.hgrn2_noalloc_workspace_limit.argtypes = []
         L.hgrn2_noalloc_init.restype = ctypes.c_int
@@ -194,6 +203,53 @@ def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chu
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd")
     return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgrn2_saved_states_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_saved_states_bytes(ctypes.byref(shape)))
+
+
+def hgrn2_bwd_saved_workspace_bytes(shape: hgrn2_shape, gated: bool) -> int:
+    return int(lib().hgrn2_bwd_saved_workspace_bytes(ctypes.byref(shape), 1 if gated else 0))
+
+
+def hgrn2_fwd_saving(q, f, v, h0=None, *, beta=None, want_hT=True, o=None, hT=None, saved_states=None, workspace=None,
+                     layout=HGRN2_LAYOUT_BHND):
+    """hgrn2_fwd (or hgrn2_fwd_gated when beta is given) that also keeps the per-chunk states for
+    hgrn2_bwd_saved.  Returns o, hT, saved_states (a uint8 device buffer)."""
+    shape = make_shape(q, v, f, 0, layout)
+    if o is None:
+        o = torch.empty_like(v)
+    if hT is None and want_hT:
+        hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    if saved_states is None:
+        saved_states = torch.empty(max(hgrn2_saved_states_bytes(shape), 256), dtype=torch.uint8, device=q.device)
+    ws = _workspace(hgrn2_fwd_workspace_bytes(shape), q.device, workspace)
+    rc = lib().hgrn2_fwd_saving(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0), _ptr(o), _ptr(hT),
+                                _ptr(saved_states), saved_states.numel(), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_fwd_saving")
+    return o, hT, saved_states
+
+
+def hgrn2_bwd_saved(q, f, v, saved_states, grad_o, grad_hT=None, *, beta=None, want_grad_h0=False, workspace=None,
+                    grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND):
+    """hgrn2_bwd (hgrn2_bwd_gated when beta is given) from the states hgrn2_fwd_saving kept.  Returns
+    grad_q, grad_f, grad_v, grad_h0 and, with beta, grad_beta as a fifth value."""
+    shape = make_shape(q, v, f, 0, layout)
+    grad_q = torch.empty_like(q) if grad_q is None else grad_q
+    grad_f = torch.empty_like(q) if grad_f is None else grad_f
+    grad_v = torch.empty_like(v) if grad_v is None else grad_v
+    if grad_h0 is None and want_grad_h0:
+        grad_h0 = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
+    gb = torch.empty_like(beta) if beta is not None else None
+    ws = _workspace(hgrn2_bwd_saved_workspace_bytes(shape, beta is not None), q.device, workspace)
+    rc = lib().hgrn2_bwd_saved(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(saved_states),
+                               saved_states.numel(), _ptr(grad_o), _ptr(grad_hT), _ptr(grad_q), _ptr(grad_f), _ptr(gb),
+                               _ptr(grad_v), _ptr(grad_h0), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_bwd_saved")
+    return (grad_q, grad_f, grad_v, grad_h0) if beta is None else (grad_q, grad_f, grad_v, grad_h0, gb)
 
 
 def hgrn2_noalloc_workspace_limit() -> int:

@@ -101,6 +101,7 @@ int plan_runs(const SeqDims& d, bool backward, int* run_chunks)
 
 SeqDims as_runs(const SeqDims& d, int seg, int run_chunks)
 {
+    if (seg <= 1) return d;               // one run: the sequence itself, with its own length
     SeqDims r = d;
     r.BH = d.BH * seg; r.NC = run_chunks; r.N = run_chunks * kChunk;
     r.lay.seg = seg; r.lay.n_tokens = d.N;
@@ -121,6 +122,37 @@ size_t run_decay_bytes(const SeqDims& d, bool backward)
     int rc;
     const int seg = plan_runs(d, backward, &rc);
     return seg > 1 ? round256((size_t)d.BH * seg * d.dk * sizeof(float)) : 0;
+}
+
+// Workspace of the backward pass of an equal-length batch: the forward states of every chunk (with
+// the run states of their sweep when few long sequences are walked in runs), what the reverse walk
+// needs at its run boundaries, and the partial sums of the gradient of beta.
+struct BwdLayout {
+    BwdFusedPlan plan;
+    size_t states = 0;                    // at offset 0
+    size_t fwd_run_state = 0, fwd_run_decay = 0;
+    size_t tail_state = 0, tail_decay = 0, bound0 = 0;
+    size_t partials = 0;
+    size_t total() const { return states + fwd_run_state + fwd_run_decay + tail_state + tail_decay + bound0 + partials; }
+};
+
+BwdLayout bwd_layout(const SeqDims& d, bool gated, bool states_given = false)
+{
+    BwdLayout l;
+    l.plan = plan_bwd_fused(d);
+    if (!states_given) {
+        l.states = round256(state_ws_bytes(d));
+        l.fwd_run_state = run_state_bytes(d, false);
+        l.fwd_run_decay = run_decay_bytes(d, false);
+    }
+    if (l.plan.R > 1 && !l.plan.light) {
+        const size_t slots = (size_t)d.BH * l.plan.seg_tail;
+        l.tail_state = round256(slots * d.dk * d.dv * sizeof(float));
+        l.tail_decay = round256(slots * d.dk * sizeof(float));
+        l.bound0 = round256((size_t)d.BH * d.dk * d.dv * sizeof(float));
+    }
+    l.partials = gated ? round256(beta_partials_bytes(d)) : 0;
+    return l;
 }
 
 // A packed batch is cut the way an equal-length batch of its mean sequence length would be (the
@@ -238,16 +270,16 @@ size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
         return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
                3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_workspace_bytes(&e);
     }
-    return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true);
+    return bwd_layout(d, false).total();
 }
 
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
-                    void* hip_stream);
+                    void* hip_stream, void* save_states = nullptr);
 static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
-                    size_t workspace_bytes, void* hip_stream);
+                    size_t workspace_bytes, void* hip_stream, const void* saved_states = nullptr);
 
 // Small-gate mode of the forward pass: spread the inputs, run the pass on the spread shape, gather o.
 static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated, const void* v,
@@ -323,8 +355,9 @@ static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, cons
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
-                    void* hip_stream)
+                    void* hip_stream, void* save_states)
 {
+    if (fine_mode(shape) && save_states) return HGRN2_ERR_UNSUPPORTED;
     if (fine_mode(shape)) return fwd_fine(shape, q, f, beta, gated, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
     SeqDims d;
     const int rc = check_shape(shape, false, &d);
@@ -339,6 +372,12 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (d.BH == 0) return HGRN2_OK;
     if (!has_tokens && !hT) return HGRN2_OK;
+    // States for a later backward pass: the single-pass kernel hands them over as it goes; the
+    // other paths (whose sweep keeps the states in the read-out's orientation) run a sweep for them.
+    auto save_by_sweep = [&]() {
+        return !save_states || !has_tokens ||
+               launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, save_states, nullptr, stream) == hipSuccess;
+    };
     int run_chunks;
     const int seg = plan_runs(d, false, &run_chunks);
     if (seg > 1) {
@@ -349,16 +388,16 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
             launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_state, run_decay, hT, false, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
         if (fwd_fused_supported(r))
-            return launch_fwd_fused(r, q, f, v, run_state, o, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+            return launch_fwd_fused(r, q, f, v, run_state, o, nullptr, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
         if (launch_sweep(r, kSweepStateFwd, q, f, v, run_state, nullptr, workspace, nullptr, stream) != hipSuccess ||
-            launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess)
+            launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess || !save_by_sweep())
             return HGRN2_ERR_HIP;
         return HGRN2_OK;
     }
     if (fwd_fused_supported(d))
-        return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+        return launch_fwd_fused(d, q, f, v, h0, o, hT, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
     if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, workspace, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
-    if (launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_fwd_out(d, q, f, v, workspace, o, stream) != hipSuccess || !save_by_sweep()) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
 
@@ -384,16 +423,16 @@ size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
         return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
                3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_gated_workspace_bytes(&e);
     }
-    return 2 * (round256(state_ws_bytes(d)) + run_state_bytes(d, true)) + run_decay_bytes(d, true) +
-           round256(beta_partials_bytes(d));
+    return bwd_layout(d, true).total();
 }
 
 // Backward pass; `gated`: `f` holds pre-activations, grad_f receives dL/dz and grad_beta dL/dbeta.
 static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
-                    size_t workspace_bytes, void* hip_stream)
+                    size_t workspace_bytes, void* hip_stream, const void* saved_states)
 {
+    if (fine_mode(shape) && saved_states) return HGRN2_ERR_UNSUPPORTED;
     if (fine_mode(shape))
         return bwd_fine(shape, q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
                         workspace, workspace_bytes, hip_stream);
@@ -404,35 +443,60 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
     if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
-    const size_t one = round256(state_ws_bytes(d));
-    const size_t part = gated ? round256(beta_partials_bytes(d)) : 0;
-    const size_t rs = run_state_bytes(d, true), rd = run_decay_bytes(d, true);
-    const size_t need = 2 * (one + rs) + rd + part;
+    const BwdLayout l = bwd_layout(d, gated, saved_states != nullptr);
+    const size_t need = l.total();
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    char* base = static_cast<char*>(workspace);
-    void* ws_s = base;
-    void* ws_ds = base + one;
-    float* ws_part = gated ? reinterpret_cast<float*>(base + 2 * (one + rs) + rd) : nullptr;
-    int run_chunks;
-    const int seg = plan_runs(d, true, &run_chunks);
-    if (seg > 1) {
-        const SeqDims r = as_runs(d, seg, run_chunks);
-        float* run_s = reinterpret_cast<float*>(base + 2 * one);
-        float* run_ds = reinterpret_cast<float*>(base + 2 * one + rs);
-        float* run_decay = reinterpret_cast<float*>(base + 2 * (one + rs));
-        if (launch_sweep_pair_ends(r, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
-            launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_s, run_decay, nullptr, false, stream) != hipSuccess ||
-            launch_run_carry(d.BH, seg, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true, stream) != hipSuccess ||
-            launch_sweep_pair(r, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess ||
-            launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess)
+    char* at = static_cast<char*>(workspace);
+    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
+    const void* ws_s = saved_states ? saved_states : take(l.states);
+    float* fwd_run_state = reinterpret_cast<float*>(take(l.fwd_run_state));
+    float* fwd_run_decay = reinterpret_cast<float*>(take(l.fwd_run_decay));
+    float* tail_state = reinterpret_cast<float*>(take(l.tail_state));
+    float* tail_decay = reinterpret_cast<float*>(take(l.tail_decay));
+    float* bound0 = reinterpret_cast<float*>(take(l.bound0));
+    float* ws_part = gated ? reinterpret_cast<float*>(take(l.partials)) : nullptr;
+    if (d.BH > 0 && !has_tokens) {
+        // no tokens: the state gradient passes through unchanged (the sweep of an empty sequence does that)
+        if (grad_h0 && launch_sweep(d, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, nullptr, nullptr, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
-    } else
-    if (d.BH > 0 && (has_tokens || grad_h0)) {
-        if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
+    } else if (d.BH > 0) {
+        // 1. forward states of every chunk (few long sequences: in runs, as the forward pass walks them)
+        int run_chunks;
+        const int seg = saved_states ? 1 : plan_runs(d, false, &run_chunks);
+        void* ws_out = saved_states ? nullptr : const_cast<void*>(ws_s);
+        if (saved_states) {
+            // a forward pass has left them
+        } else if (seg > 1) {
+            const SeqDims r = as_runs(d, seg, run_chunks);
+            if (launch_sweep(r, kSweepStateBwd, nullptr, f, v, nullptr, fwd_run_state, nullptr, fwd_run_decay, stream) != hipSuccess ||
+                launch_run_carry(d.BH, seg, d.dk, d.dv, h0, fwd_run_state, fwd_run_decay, nullptr, false, stream) != hipSuccess ||
+                launch_sweep(r, kSweepStateBwd, nullptr, f, v, fwd_run_state, nullptr, ws_out, nullptr, stream) != hipSuccess)
+                return HGRN2_ERR_HIP;
+        } else if (launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_out, nullptr, stream) != hipSuccess) {
             return HGRN2_ERR_HIP;
-        if (has_tokens && launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part,
-                                          stream) != hipSuccess)
+        }
+        // 2. the state gradient at the run boundaries of the reverse walk: a zero-start gradient sweep
+        //    over the tokens after run 0, in short sub-runs, and its carry from grad_hT
+        const BwdFusedPlan& pl = l.plan;
+        if (pl.R > 1 && !pl.light) {
+            SeqDims t = d;
+            t.window = true;
+            const long long skip = (long long)pl.rc * kChunk;             // tokens of run 0
+            t.N = d.N - (int)skip;
+            t.NC = d.NC - pl.rc;
+            const SeqDims r = as_runs(t, pl.seg_tail, pl.sub_chunks);
+            const size_t io = 2, ge = d.gate_bf16 ? 2 : 4;               // bytes per element (the backward is bf16-only)
+            const char* q_t = static_cast<const char*>(q) + (size_t)skip * d.lay.sn_k * io;
+            const char* f_t = static_cast<const char*>(f) + (size_t)skip * d.lay.sn_k * ge;
+            const char* g_t = static_cast<const char*>(grad_o) + (size_t)skip * d.lay.sn_v * io;
+            if (launch_sweep(r, kSweepGrad, q_t, f_t, g_t, nullptr, tail_state, nullptr, tail_decay, stream) != hipSuccess ||
+                launch_run_carry(d.BH, pl.seg_tail, d.dk, d.dv, grad_hT, tail_state, tail_decay, bound0, true, stream) != hipSuccess)
+                return HGRN2_ERR_HIP;
+        }
+        // 3. the reverse walk: dq, df, dv of every chunk, grad_h0
+        if (launch_bwd_fused(d, pl, q, f, v, grad_o, ws_s, grad_hT, grad_h0, bound0, tail_state, grad_q, grad_f, grad_v,
+                             ws_part, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
     }
     // an empty batch or sequence has NC = 0 or B = 0: the reduction then writes zeros
@@ -505,6 +569,51 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 {
     return bwd_impl(shape, q, z, beta, true, v, h0, grad_o, grad_hT, grad_q, grad_z, grad_beta, grad_v, grad_h0,
                     workspace, workspace_bytes, hip_stream);
+}
+
+size_t hgrn2_saved_states_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    return round256(state_ws_bytes(d));
+}
+
+size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated)
+{
+    SeqDims d;
+    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    return bwd_layout(d, gated != 0, true).total();
+}
+
+int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,
+                     const float* h0, void* o, float* hT, void* saved_states, size_t saved_states_bytes,
+                     void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d);           // the shapes the backward pass takes
+    if (rc != HGRN2_OK) return rc;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
+    return fwd_impl(shape, q, f, beta, beta != nullptr, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
+                    need > 0 ? saved_states : nullptr);
+}
+
+int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,
+                    const void* saved_states, size_t saved_states_bytes, const void* grad_o, const float* grad_hT,
+                    void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                    size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape(shape, true, &d);
+    if (rc != HGRN2_OK) return rc;
+    if (fine_mode(shape)) return HGRN2_ERR_UNSUPPORTED;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need == 0)      // no chunks: nothing was saved, the ordinary pass handles what is left (grad_h0, grad_beta)
+        return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+                        grad_h0, workspace, workspace_bytes, hip_stream);
+    if (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255)) return HGRN2_ERR_WORKSPACE;
+    return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+                    grad_h0, workspace, workspace_bytes, hip_stream, saved_states);
 }
 
 // Small-gate modes of the packed entry points, forward (backward = false: o, hT) and backward: every
@@ -636,14 +745,14 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                                     stream) != hipSuccess)
             return HGRN2_ERR_HIP;
         if (fwd_fused_supported(d))
-            return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+            return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
         if (launch_sweep(d, kSweepStateFwd, q, f, v, run_state, nullptr, ws_s, nullptr, stream) != hipSuccess ||
             launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
         return HGRN2_OK;
     }
     if (fwd_fused_supported(d))
-        return launch_fwd_fused(d, q, f, v, h0, o, hT, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+        return launch_fwd_fused(d, q, f, v, h0, o, hT, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
     if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;

@@ -44,6 +44,7 @@
 
 namespace hgrn2 {
 
+constexpr int kMaxLightRuns = 4;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = 64 * kBwdWaves;
 
@@ -63,6 +64,22 @@ struct BwdGradParams {
     int H;
     TokenLayout lay;         // used when dense == 0
     int dense;               // sequence tensors are [B][H][N][d]
+    // Fused reverse walk (see bwd_grad_body<..., FUSED>): the state gradient is carried in registers
+    // instead of being read from ws_ds.  Every sequence is cut into R runs of rc chunks, one
+    // workgroup each; a run starts from grad_hT (the last one), from bound0[bh] (run 0) or from
+    // run_state[bh * seg_tail + r * s_sub - 1] (the state gradient at the end of run r, which a
+    // zero-start sweep over the later tokens and its carry have left there); run 0 leaves grad_h0.
+    // With few runs (`light`), no boundary states are needed: a workgroup first walks the chunks
+    // after its run, from grad_hT, doing nothing but the state-gradient recurrence (a fraction of a
+    // chunk's full work), and the runs are cut at bnd[0] = 0 < bnd[1] < ... < bnd[R] = NC so that
+    // all workgroups finish together.
+    const float* dhT;
+    float* dh0;
+    const float* bound0;
+    const float* run_state;
+    int R, rc, s_sub, seg_tail;
+    int light;
+    int bnd[kMaxLightRuns + 1];
 };
 
 
@@ -106,7 +123,14 @@ template <typename T, int DK, int DV> struct BwdGradLds {
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE>
+// FUSED: the workgroup owns run `r` of sequence `bh` and walks its chunks from the last to the
+// first with the state gradient in fp32 MFMA accumulators, oriented [dv][channel]:
+//     E_n = D'_n + Q~_n^T dO_n ,   D'_n = (g_n / G_m,n) dS_{n+1} ,   dS_n = G_m,n E_n
+// so that before each chunk the accumulators are scaled by (second-half gate product of this
+// chunk) x (first-half gate product of the chunk just done), published to the LDS tile the
+// contractions read D' from, and after the chunk's contractions receive Q~^T dO.  Only the forward
+// states S_n come from the workspace.
+template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE, bool FUSED>
 __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 {
     constexpr int C = kChunk, NW = kBwdWaves, RW = C / NW;
@@ -198,7 +222,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
             cS[kk] = *reinterpret_cast<const frag*>(wsS + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
-            cD[kk] = *reinterpret_cast<const frag*>(wsD + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
+            if constexpr (!FUSED) cD[kk] = *reinterpret_cast<const frag*>(wsD + state_frag_offset(at, kk >> 1, NBT, kk & 1, lane));
         }
     };
 
@@ -209,12 +233,145 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     RawRows<RW> raw_f, raw_q;
     u32x4 raw_v[2], raw_d[2];
     frag sS[2 * NBT], sD[2 * NBT];
-    if ((int)blockIdx.x >= n_chunks) return;
-    for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
-    ChunkAt cur = where(blockIdx.x);
-    load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
+    // chunks of this workgroup: every gridDim.x-th one, or (FUSED) those of its run, last to first
+    int n_iter, f_bh = 0, f_run = 0, f_first = 0, f_last = 0;
+    if constexpr (FUSED) {
+        f_bh = (int)blockIdx.x / p.R;
+        f_run = (int)blockIdx.x - f_bh * p.R;
+        if (f_bh >= p.BH) return;
+        if (p.light) {
+            f_first = p.bnd[f_run];
+            f_last = p.bnd[f_run + 1] - 1;
+        } else {
+            f_first = f_run * p.rc;
+            f_last = min(p.NC, f_first + p.rc) - 1;
+        }
+        n_iter = f_last - f_first + 1;
+    } else {
+        if ((int)blockIdx.x >= n_chunks) return;
+        n_iter = (n_chunks - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+    }
+    auto chunk_of = [&](int it) {         // global chunk index of iteration `it`, clamped to the workgroup's last one
+        if constexpr (FUSED) return f_bh * p.NC + max(f_last - it, f_first);
+        else return min((int)blockIdx.x + it * (int)gridDim.x, n_chunks - 1);
+    };
 
-  for (int chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+    // FUSED: accumulator tiles of the state gradient owned by this wave, tile id w + 8 j -> (channel
+    // tile id % NAT, which is this wave's `at`; dv tile id / NAT), as [dv][channel]
+    constexpr int NDT = NAT * NBT, TPW = (NDT + NW - 1) / NW;
+    const bool has_d = FUSED && ((NDT % NW == 0) || w < NDT);
+    f32x16 accD[FUSED ? TPW : 1];
+    float gm_prev = 1.0f;                 // first-half gate product of the chunk done before, channel 32 at + lane % 32
+    if constexpr (FUSED) {
+        const int r32i = tid & 31, gi = (tid >> 5) & 1;
+        const float* init = (f_run == p.R - 1 || p.light) ? p.dhT : (f_run == 0) ? p.bound0 : p.run_state;
+        if (init) {
+            if (f_run == p.R - 1 || f_run == 0 || p.light) init += (size_t)f_bh * DK * DV;
+            else init += ((size_t)f_bh * p.seg_tail + (size_t)f_run * p.s_sub - 1) * DK * DV;
+        }
+#pragma unroll
+        for (int j = 0; j < TPW; ++j) {
+            const int btj = (w + NW * j) / NAT;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                accD[j][v] = (init && has_d) ? init[(size_t)(32 * at + r32i) * DV + 32 * btj + 8 * (v >> 2) + 4 * gi + (v & 3)] : 0.0f;
+        }
+    }
+    if (n_iter <= 0) return;              // (FUSED) a sequence without tokens: the host routes those elsewhere
+    for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
+    ChunkAt cur;
+    bool rows_loaded = false;
+    if constexpr (FUSED) {
+        const int n_light = p.light ? p.NC - 1 - f_last : 0;
+        if (n_light > 0) {
+            // ---- light walk over the chunks after this run: dS_n = Diag(g_n) dS_{n+1} + Q^_n^T dO_n with
+            // Q^ = q G (G the gate product from the chunk start: no quotient), true state gradient in
+            // the accumulators.  Three barriers per chunk; the Q~ and dO tiles and the block totals are reused.
+            auto load_light = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cd)[2], const ChunkAt& c, int lane) {
+                load_fq_rows(cf, cq, c, lane);
+                const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+                cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
+                cd[1] = *reinterpret_cast<const u32x4*>(dog + vo + 8);
+            };
+            cur = where(f_bh * p.NC + p.NC - 1);
+            load_light(raw_f, raw_q, raw_d, cur, tid & 63);
+            for (int li = 0; li < n_light; ++li) {
+                int lane_opaque = threadIdx.x & 63;
+                asm volatile("" : "+v"(lane_opaque));
+                const int lane = lane_opaque, r32 = lane & 31;
+                const bool k_act = 2 * lane < DK;
+                if (vd_act) {
+                    T* ddst = dOm + (size_t)vd_row * PV + 16 * vd_grp;
+                    *reinterpret_cast<u32x4*>(ddst) = u32x4{raw_d[0][0], raw_d[0][1], raw_d[1][0], raw_d[1][1]};
+                    *reinterpret_cast<u32x4*>(ddst + 8) = u32x4{raw_d[0][2], raw_d[0][3], raw_d[1][2], raw_d[1][3]};
+                }
+                const int row0 = cur.n * C + RW * w;
+                f32x2 rf[RW], rq[RW];
+                convert_rows<RW>(rf, raw_f, row0, cur.sv.N, k_act, gate_bf16, 1.0f);
+                if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(f_bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cur.sv.N);
+                convert_rows<RW>(rq, raw_q, row0, cur.sv.N, k_act, true, 0.0f);
+                float a0[RW], a1[RW], t0 = 1.0f, t1 = 1.0f;
+#pragma unroll
+                for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; a0[i] = t0; a1[i] = t1; }
+                if (k_act) *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{t0, t1};
+                __syncthreads();
+                // rows of the next chunk of the walk (after the last light chunk: the run's own last chunk)
+                RawRows<RW> nxt_f, nxt_q;
+                const ChunkAt nxt = where(f_bh * p.NC + p.NC - 2 - li);
+                load_light(nxt_f, nxt_q, raw_d, nxt, lane);
+                if (k_act) {
+                    float pre0 = 1.0f, pre1 = 1.0f;
+#pragma unroll
+                    for (int i = 0; i < NW - 1; ++i) {
+                        const float* src = (i < w) ? tot + i * DK : ones;       // wave-uniform row address
+                        const f32x2 t = *reinterpret_cast<const f32x2*>(src + 2 * lane);
+                        pre0 *= t.x; pre1 *= t.y;
+                    }
+#pragma unroll
+                    for (int i = 0; i < RW; ++i) {
+                        bf16x2 x;
+                        x.x = (T)(rq[i].x * (pre0 * a0[i])); x.y = (T)(rq[i].y * (pre1 * a1[i]));
+                        *reinterpret_cast<bf16x2*>(Qm + (size_t)(RW * w + i) * PK + 2 * lane) = x;
+                    }
+                }
+                float g_all = 1.0f;
+                if (has_d) {
+#pragma unroll
+                    for (int i = 0; i < NW; ++i) g_all *= tot[i * DK + 32 * at + r32];
+                }
+                __syncthreads();
+                if (has_d) {
+#pragma unroll
+                    for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) accD[j][v] *= g_all;
+#pragma unroll
+                    for (int ks = 0; ks < 2 * NRT; ++ks) {
+                        const frag qf = M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane);
+#pragma unroll
+                        for (int j = 0; j < TPW; ++j)
+                            M::mma(accD[j], M::load_kmajor_swapped(dOm, PV, 16 * ks, 32 * ((w + NW * j) / NAT), lane), qf);
+                    }
+                }
+                raw_f = nxt_f;
+                raw_q = nxt_q;
+                cur = nxt;
+                __syncthreads();          // the tiles and totals are free for the next chunk
+            }
+            // what the full pass over the run's last chunk needs on top: its V rows
+            const size_t vo = cur.sv.off_v + (size_t)min(cur.n * C + vd_row, cur.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+            raw_v[0] = *reinterpret_cast<const u32x4*>(vg + vo);
+            raw_v[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
+            rows_loaded = true;
+        }
+    }
+    if (!rows_loaded) {
+        cur = where(chunk_of(0));
+        load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
+    }
+
+  for (int it = 0; it < n_iter; ++it) {
+    const int chunk = chunk_of(it);
     // Re-derive the lane-dependent indices inside the loop from a value the compiler cannot see
     // through: otherwise it hoists dozens of loop-invariant LDS addresses out of the loop, keeps
     // them in registers across the whole body and spills.
@@ -296,7 +453,30 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv position] (the fragments hold
     // it already scaled and rounded, and in position order: their bits go to LDS as they are), and
     // R = rowsum((H_m dS) * (G_m S_n)) = g * rowsum(dS * S_n).  Once per channel tile (row tile 0).
-    if (w < NAT) {
+    if constexpr (FUSED) {
+        // scale the carried state gradient to D'_n and publish it as the bf16 tile the contractions read
+        if (has_d) {
+            const int ch = 32 * at + r32;
+            const float hn = (tot[4 * DK + ch] * tot[5 * DK + ch]) * (tot[6 * DK + ch] * tot[7 * DK + ch]);
+            const float gm = (tot[0 * DK + ch] * tot[1 * DK + ch]) * (tot[2 * DK + ch] * tot[3 * DK + ch]);
+            const float c = hn * gm_prev;
+            gm_prev = gm;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                const int btj = (w + NW * j) / NAT;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) accD[j][v] *= c;
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    float x[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] = accD[j][8 * half + e];
+                    *reinterpret_cast<frag*>(dSm + (size_t)ch * PV + 32 * btj + 16 * half + 8 * g) = M::pack(x);
+                }
+            }
+        }
+    }
+    if (!FUSED && w < NAT) {
         const int ch = 32 * at + r32;
         f32x16 accR;
 #pragma unroll
@@ -314,6 +494,23 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         if (g == ((r32 >> 2) & 1)) Rp[ch] = rs;
     }
     __syncthreads();
+
+    if constexpr (FUSED) {
+        // R on the last NAT waves, D'_n of their channel tile read back from the tile as operand fragments
+        if (w >= NW - NAT) {
+            f32x16 accR;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) accR[v] = 0.0f;
+#pragma unroll
+            for (int kk = 0; kk < 2 * NBT; ++kk)
+                M::mma(accR, sS[kk], *reinterpret_cast<const frag*>(dSm + (size_t)(32 * at + r32) * PV + 16 * kk + 8 * g));
+            const int vsel = 4 * (r32 >> 3) + (r32 & 3);
+            float rs = 0.0f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) rs = (v == vsel) ? accR[v] : rs;
+            if (g == ((r32 >> 2) & 1)) Rp[32 * at + r32] = rs;
+        }
+    }
 
     // ---------------- P^T and dP^T blocks ----------------
     // waves 0..2: P blocks (I,J) = (0,0), (1,0), (1,1); waves 3..5: the same for dP; waves 6, 7 zero
@@ -391,7 +588,11 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 #pragma unroll
         for (int kk = 0; kk < 2 * NBT; ++kk) {
             M::mma(aX, sS[kk], M::load(dOm + (32 * rt_a + r32) * PV + 16 * kk + 8 * g));
-            M::mma(aKs, sD[kk], M::load(Vm + (32 * rt_a + r32) * PVR + 16 * kk + 8 * g));
+            if constexpr (FUSED)
+                M::mma(aKs, *reinterpret_cast<const frag*>(dSm + (size_t)(32 * at + r32) * PV + 16 * kk + 8 * g),
+                       M::load(Vm + (32 * rt_a + r32) * PVR + 16 * kk + 8 * g));
+            else
+                M::mma(aKs, sD[kk], M::load(Vm + (32 * rt_a + r32) * PVR + 16 * kk + 8 * g));
         }
 #pragma unroll
         for (int ks = 0; ks < 2 * NRT; ++ks) {
@@ -402,8 +603,20 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // next chunk of this workgroup: its row loads are in flight during the staging / epilogue below
     // Every load is unconditional (the last chunk of a workgroup fetches itself again), which
     // keeps the count of outstanding loads exact, so that nothing below waits for these.
+    if constexpr (FUSED) {
+        // E_n = D'_n + Q~^T dO: rows = dv (true column order), columns = channels
+        if (has_d) {
+#pragma unroll
+            for (int ks = 0; ks < 2 * NRT; ++ks) {
+                const frag qf = M::load_kmajor(Qm, PK, 16 * ks, 32 * at, lane);
+#pragma unroll
+                for (int j = 0; j < TPW; ++j)
+                    M::mma(accD[j], M::load_kmajor_swapped(dOm, PV, 16 * ks, 32 * ((w + NW * j) / NAT), lane), qf);
+            }
+        }
+    }
     RawRows<RW> nxt_f, nxt_q;
-    const ChunkAt nxt = where(min(chunk + (int)gridDim.x, n_chunks - 1));
+    const ChunkAt nxt = where(chunk_of(it + 1));
     load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, nxt, lane);   // v, dO of this chunk are dead
     __syncthreads();     // every wave is done with the operand tiles
 
@@ -429,6 +642,16 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     T* dfg = static_cast<T*>(p.df);
     convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
     if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
+    if constexpr (FUSED) {
+        // the gate products again (32 multiplications) rather than 32 registers kept through the contractions
+        asm volatile("" : "+v"(rf[0].x), "+v"(rf[0].y));
+        float t0 = 1.0f, t1 = 1.0f;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; a0[i] = t0; a1[i] = t1; }
+        float u0 = 1.0f, u1 = 1.0f;
+#pragma unroll
+        for (int i = RW - 1; i >= 0; --i) { z0[i] = u0; z1[i] = u1; u0 *= rf[i].x; u1 *= rf[i].y; }
+    }
     // rows of this wave's block to global memory: one address and constant offsets when the
     // whole block lies inside the sequence, row by row otherwise
     auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
@@ -516,13 +739,34 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     cur = nxt;
     if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
+    if constexpr (FUSED) {
+        // run 0 ends at the start of the sequence: dS_0 = G_m E of its first chunk is grad_h0
+        if (f_run == 0 && p.dh0 && has_d) {
+            const int r32i = tid & 31, gi = (tid >> 5) & 1;
+            float* out = p.dh0 + (size_t)f_bh * DK * DV;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                const int btj = (w + NW * j) / NAT;
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    out[(size_t)(32 * at + r32i) * DV + 32 * btj + 8 * (v >> 2) + 4 * gi + (v & 3)] = accD[j][v] * gm_prev;
+            }
+        }
+    }
 }
 
 template <typename T, int DK, int DV, bool GATE_BF16>
 __global__ __launch_bounds__(kBwdThreads) void bwd_grad_kernel(BwdGradParams p)
 {
-    if (p.dense) bwd_grad_body<T, DK, DV, GATE_BF16, true>(p);
-    else         bwd_grad_body<T, DK, DV, GATE_BF16, false>(p);
+    if (p.dense) bwd_grad_body<T, DK, DV, GATE_BF16, true, false>(p);
+    else         bwd_grad_body<T, DK, DV, GATE_BF16, false, false>(p);
+}
+
+template <typename T, int DK, int DV, bool GATE_BF16>
+__global__ __launch_bounds__(kBwdThreads) void bwd_fused_kernel(BwdGradParams p)
+{
+    if (p.dense) bwd_grad_body<T, DK, DV, GATE_BF16, true, true>(p);
+    else         bwd_grad_body<T, DK, DV, GATE_BF16, false, true>(p);
 }
 
 template <typename T, int DK, int DV>
@@ -550,11 +794,99 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC;
     p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
+    p.dhT = nullptr; p.dh0 = nullptr; p.bound0 = nullptr; p.run_state = nullptr; p.R = 1; p.rc = d.NC; p.s_sub = 1; p.seg_tail = 0;
+    p.light = 0;
+    for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = 0;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
     if (d.dk == 128 && d.dv == 128) return launch_one<__bf16, 128, 128>(d, p, stream);
     if (d.dk == 64 && d.dv == 64) return launch_one<__bf16, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 64) return launch_one<__bf16, 128, 64>(d, p, stream);
     if (d.dk == 64 && d.dv == 128) return launch_one<__bf16, 64, 128>(d, p, stream);
+    return hipErrorInvalidValue;
+}
+
+template <typename T, int DK, int DV>
+static hipError_t launch_fused_one(const SeqDims& d, const BwdGradParams& p, hipStream_t stream)
+{
+    typedef BwdGradLds<T, DK, DV> L;
+    auto kern = d.gate_bf16 ? bwd_fused_kernel<T, DK, DV, true> : bwd_fused_kernel<T, DK, DV, false>;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(d.BH * p.R)), dim3(kBwdThreads), L::total, stream, p);
+    return hipGetLastError();
+}
+
+BwdFusedPlan plan_bwd_fused(const SeqDims& d)
+{
+    // One workgroup per run and one run per compute unit at a time: as many runs per sequence as it
+    // takes to fill the chip, but at least four chunks each.  The zero-start sweep that supplies the
+    // state gradient at the run boundaries walks sub-runs of about four chunks.
+    BwdFusedPlan pl;
+    pl.light = 0;
+    for (int i = 0; i <= kMaxLightRuns; ++i) pl.bnd[i] = 0;
+    int R = d.BH > 0 ? 256 / d.BH : 1;
+    if (R > d.NC / 4) R = d.NC / 4;
+    if (R < 1) R = 1;
+    if (R >= 2 && R <= kMaxLightRuns) {
+        // Few runs: each workgroup walks the chunks after its run itself, at `rho` of a chunk's full
+        // cost (measured), and the cuts are placed so that all runs take the same time T:
+        // len_r = T - rho (NC - end_r), from the last run (len = T) backwards; T by bisection.
+        const double rho = 0.16;
+        double lo = 0.0, hi = (double)d.NC;
+        for (int iter = 0; iter < 50; ++iter) {
+            const double T = 0.5 * (lo + hi);
+            double end = (double)d.NC;
+            for (int r = R - 1; r >= 0; --r) end -= T - rho * ((double)d.NC - end);
+            if (end > 0.0) lo = T; else hi = T;        // runs too short: raise T
+        }
+        double end = (double)d.NC;
+        pl.bnd[R] = d.NC;
+        for (int r = R - 1; r >= 1; --r) {
+            end -= hi - rho * ((double)d.NC - end);
+            int b = (int)(end + 0.5);
+            if (b < r) b = r;                          // every run keeps at least one chunk
+            if (b > pl.bnd[r + 1] - 1) b = pl.bnd[r + 1] - 1;
+            pl.bnd[r] = b;
+        }
+        pl.bnd[0] = 0;
+        pl.light = 1;
+        pl.R = R; pl.rc = 0; pl.s_sub = 1; pl.sub_chunks = 0; pl.seg_tail = 0;
+        return pl;
+    }
+    int rc = (d.NC + R - 1) / R;
+    int s = rc / 4;
+    if (s < 1) s = 1;
+    if (R > 1) rc = (rc + s - 1) / s * s;         // whole sub-runs per run
+    pl.rc = rc;
+    pl.R = rc > 0 ? (d.NC + rc - 1) / rc : 1;
+    if (pl.R < 1) pl.R = 1;
+    pl.s_sub = s;
+    pl.sub_chunks = rc / s;
+    pl.seg_tail = pl.R > 1 ? (d.NC - rc + pl.sub_chunks - 1) / pl.sub_chunks : 0;
+    return pl;
+}
+
+hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void* q, const void* f, const void* v,
+                            const void* grad_o, const void* ws_state, const float* grad_hT, float* grad_h0,
+                            const float* bound0, const float* run_state, void* grad_q, void* grad_f, void* grad_v,
+                            float* beta_partials, hipStream_t stream)
+{
+    if (d.total_chunks() == 0) return hipSuccess;
+    if (!d.io_bf16 || d.packed || d.lay.vl) return hipErrorInvalidValue;
+    if (d.beta && !beta_partials) return hipErrorInvalidValue;
+    BwdGradParams p;
+    p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = nullptr;
+    p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
+    p.BH = d.BH; p.N = d.N; p.NC = d.NC;
+    p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
+    p.dhT = grad_hT; p.dh0 = grad_h0; p.bound0 = bound0; p.run_state = run_state;
+    p.R = pl.R; p.rc = pl.rc; p.s_sub = pl.s_sub; p.seg_tail = pl.seg_tail;
+    p.light = pl.light;
+    for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = pl.bnd[i];
+    if (d.dk == 128 && d.dv == 128) return launch_fused_one<__bf16, 128, 128>(d, p, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_fused_one<__bf16, 64, 64>(d, p, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_fused_one<__bf16, 128, 64>(d, p, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_fused_one<__bf16, 64, 128>(d, p, stream);
     return hipErrorInvalidValue;
 }
 

@@ -345,6 +345,20 @@ template <> struct Mma<__bf16> {
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * pitch));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     }
+    // The same for a tile whose columns are stored, inside every group of 16, in the order the state
+    // fragments keep their contraction index (column c at position c with bits 2 and 3 swapped):
+    // lane x0 + lane % 32 receives the TRUE column x0 + lane % 32.  Only the quad of columns a
+    // source lane supplies changes (quads 1 and 2 trade places).
+    static __device__ __forceinline__ frag load_kmajor_swapped(const __bf16* tile, int pitch, int k0, int x0, int lane)
+    {
+        typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+        const int i16 = lane & 15;
+        const int quad = ((i16 & 1) << 1) | ((i16 & 2) >> 1);
+        const __bf16* p = tile + (k0 + 8 * (lane >> 5) + (i16 >> 2)) * pitch + x0 + (lane & 16) + 4 * quad;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p + 4 * pitch));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
     static __device__ __forceinline__ frag pack(const float* x)
     {
         frag r;

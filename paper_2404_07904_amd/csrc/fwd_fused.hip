@@ -49,6 +49,7 @@ struct FwdFusedParams {
     const float* h0;
     void* o;
     float* hT;
+    void* save;          // null, or where every chunk's scaled incoming state G_m S_n goes for a later backward pass
     int N, NC, BH;
     const float* beta;   // [H][dk] lower bounds, or null: the gate tensor holds f itself
     int H;
@@ -336,6 +337,30 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         for (int k = 0; k < C * VPR / kFusedThreads; ++k) asm volatile("" :: "v"(obuf[k]));
     };
 
+    // The published state holds, per lane, 8 channels of one dv column (the read-out contracts over
+    // the channels).  A backward pass contracts over dv and wants 8 dv columns of one channel per
+    // lane: the same bf16 values, regrouped by LDS transpose reads -- 16 lanes fetch 4 consecutive
+    // channels of 4 dv columns each and get back 4 dv columns of one channel -- and written to
+    // global memory as fragments (tile (channel tile, dv tile), half, lane) of 16 bytes per lane.
+    constexpr int NSF = (DK / 32) * NBT * 2 / NW;        // fragments per wave and chunk
+    auto save_state = [&](const T* Sx, int n) {
+        typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+        T* dst = static_cast<T*>(p.save) + (sv.chunk0 + (size_t)n) * DK * DV;
+        const int i16 = lane & 15;
+        const int m = ((lane & 16) >> 2) + (i16 & 3);    // which 4 channels of the tile's 32 this lane fetches
+        const int hs = m >> 2, q4 = (m >> 1) & 1, gs = m & 1;
+#pragma unroll
+        for (int j = 0; j < NSF; ++j) {
+            const int id = w * NSF + j, half = id & 1, tb = (id >> 1) % NBT, ta = (id >> 1) / NBT;
+            const int dl = 32 * tb + 16 * half + 4 * g + (i16 >> 2);        // local dv column this lane fetches (first read)
+            const T* src = Sx + state_frag_offset(ta, tb, NBT, hs, 32 * gs + (dl & 31)) + 4 * q4;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src + 8 * 8));   // dv column + 8: lane + 8
+            const frag out = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            *reinterpret_cast<frag*>(dst + state_frag_offset(ta, dv0 / 32 + tb, DV / 32, half, lane)) = out;
+        }
+    };
+
     auto chunk = [&](auto PAR, int n) {
         constexpr int par = decltype(PAR)::value;
         const T* Qc = Qm + (size_t)par * C * PQ;
@@ -415,6 +440,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         // ======================= stage B =======================
         // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
         if (LATE_QS) store_o(n - 1);
+        if (p.save && n < NC) save_state(Sp, n);
 #pragma unroll
         for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
 #pragma unroll
@@ -503,11 +529,11 @@ static hipError_t launch_fused(const SeqDims& d, const FwdFusedParams& p, hipStr
 }
 
 hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, const void* v, const float* h0,
-                            void* o, float* hT, hipStream_t stream)
+                            void* o, float* hT, void* save_states, hipStream_t stream)
 {
     if (d.BH == 0) return hipSuccess;
     FwdFusedParams p;
-    p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT;
+    p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT; p.save = save_states;
     p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
     // Two workgroups per sequence (each half of the dv columns) keep twice as many compute units
     // busy, but a compute unit holds one workgroup: beyond 128 sequences the halves would no longer

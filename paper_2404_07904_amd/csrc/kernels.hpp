@@ -51,7 +51,10 @@ struct SeqDims {
     // variable-length batch: N and NC then describe the packed token axis (lay.vl is set once the
     // workspace that holds the sequence table is known)
     bool packed = false;
-    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv && !packed; }
+    // the tensors are a window of larger ones (the tokens after a sequence's first run): strides
+    // come from `lay` even when a token's row is as wide as the head
+    bool window = false;
+    bool dense() const { return lay.sn_k == dk && lay.sn_v == dv && !packed && !window; }
     // chunk slots of the per-chunk workspaces and of the per-chunk grids
     size_t total_chunks() const { return packed ? (size_t)H * NC : (size_t)BH * NC; }
 };
@@ -126,8 +129,10 @@ hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const 
 // Fused forward (state recurrence + read-out in one pass, states never leave the chip); only for
 // the shapes fwd_fused_supported() accepts.
 bool fwd_fused_supported(const SeqDims& d);
+// `save_states` (may be null): receives G_m S_n of every chunk in the fragment order of a
+// kSweepStateBwd sweep, state_ws_bytes() in all, for a backward pass that then needs no such sweep.
 hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, const void* v, const float* h0,
-                            void* o, float* hT, hipStream_t stream);
+                            void* o, float* hT, void* save_states, hipStream_t stream);
 
 // Per-chunk gradients dq, df, dv from the two state sweeps.
 // With d.beta set, grad_f receives the gradient w.r.t. the pre-activation z, and every wave of
@@ -137,6 +142,21 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
 hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
                            const void* ws_state, const void* ws_dstate, void* grad_q, void* grad_f,
                            void* grad_v, float* beta_partials, hipStream_t stream);
+// The same gradients from the forward states alone: one workgroup per run of a sequence walks the
+// run's chunks from the last to the first with the state gradient in registers (bwd_grad.hip).
+// plan_bwd_fused() cuts the sequences into R runs of rc chunks; for R > 1 the caller provides the
+// state gradient at the run boundaries: a zero-start gradient sweep over the tokens after run 0, cut
+// into seg_tail sub-runs of sub_chunks chunks, and its reverse carry from grad_hT leave it in
+// run_state ([BH][seg_tail][dk][dv], entry t = at the end of sub-run t) and bound0 ([BH][dk][dv], at
+// the end of run 0).  grad_h0 may be null.  Equal-length batches only.
+// With few runs (light != 0) nothing of that is needed: every workgroup first walks the chunks after
+// its own run from grad_hT, carrying only the state gradient, and the runs are cut at bnd[0..R].
+struct BwdFusedPlan { int R, rc, s_sub, sub_chunks, seg_tail, light, bnd[5]; };
+BwdFusedPlan plan_bwd_fused(const SeqDims& d);
+hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void* q, const void* f, const void* v,
+                            const void* grad_o, const void* ws_state, const float* grad_hT, float* grad_h0,
+                            const float* bound0, const float* run_state, void* grad_q, void* grad_f, void* grad_v,
+                            float* beta_partials, hipStream_t stream);
 size_t beta_partials_bytes(const SeqDims& d);
 hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream);
 

@@ -45,7 +45,10 @@ def test_workspace_sizes():
     s = shape(B=8, H=16, N=2048, dk=128, dv=128)
     one = 8 * 16 * 32 * 128 * 128 * 2
     assert binding.hgrn2_fwd_workspace_bytes(s) == one
-    assert binding.hgrn2_bwd_workspace_bytes(s) == 2 * one
+    # backward: the forward states; the two runs per sequence of the reverse walk need nothing more
+    assert binding.hgrn2_bwd_workspace_bytes(s) == one
+    assert binding.hgrn2_saved_states_bytes(s) == one
+    assert binding.hgrn2_bwd_saved_workspace_bytes(s, False) == 0
     s32 = shape(B=1, H=1, N=256, io=0, gate=0)
     assert binding.hgrn2_fwd_workspace_bytes(s32) == 4 * 64 * 64 * 4
     assert binding.hgrn2_bwd_workspace_bytes(s32) == 0           # fp32 backward is unsupported
@@ -56,7 +59,9 @@ def test_workspace_sizes():
     long = shape(B=2, H=16, N=16384, dk=128, dv=128)
     one = 32 * 256 * 128 * 128 * 2
     assert binding.hgrn2_fwd_workspace_bytes(long) == one + 32 * 8 * (128 * 128 + 128) * 4      # 8 runs forward
-    assert binding.hgrn2_bwd_workspace_bytes(long) == 2 * (one + 32 * 4 * 128 * 128 * 4) + 32 * 4 * 128 * 4   # 4 runs backward
+    # backward: forward states in 8 runs; reverse walk in 8 runs of 32 chunks, boundaries from 56 sub-runs of 4 chunks
+    assert binding.hgrn2_bwd_workspace_bytes(long) == (one + 32 * 8 * (128 * 128 + 128) * 4
+                                                       + 32 * 56 * (128 * 128 + 128) * 4 + 32 * 128 * 128 * 4)
 
 
 def test_small_gate_mode_workspace_and_support():
@@ -122,8 +127,7 @@ def test_bwd_argument_errors():
     assert call_bwd(shape(dk=32)) == E_UNSUP
     assert call_bwd(shape(), go=None) == E_NULL
     assert call_bwd(shape(), gf=None) == E_NULL
-    one = binding.hgrn2_fwd_workspace_bytes(shape())
-    assert call_bwd(shape(), ws_bytes=2 * one - 1) == E_WS
+    assert call_bwd(shape(), ws_bytes=binding.hgrn2_bwd_workspace_bytes(shape()) - 1) == E_WS
     assert call_bwd(shape(B=0), q=None, f=None, v=None, go=None, gq=None, gf=None, gv=None, ws=None, ws_bytes=0) == OK
 
 
@@ -166,7 +170,7 @@ def test_gated_workspace_and_error_codes():
     s = shape(B=8, H=16, N=2048, dk=128, dv=128)
     one = 8 * 16 * 32 * 128 * 128 * 2
     partials = 8 * 16 * 32 * 8 * 128 * 4 + 8 * 16 * 128 * 4     # per-wave rows of every chunk, then 8 slice sums per head
-    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == 2 * one + partials
+    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == binding.hgrn2_bwd_workspace_bytes(s) + partials
     assert binding.hgrn2_bwd_gated_workspace_bytes(shape(dk=96)) == 0
     big = 1 << 40
     fwd = lambda s_, q=FAKE, z=FAKE, beta=FAKE, v=FAKE, o=FAKE, ws=FAKE_WS, n=big: lib.hgrn2_fwd_gated(
