@@ -3,9 +3,9 @@ workspace of hgrn2_bwd_workspace_bytes, preallocated outputs, default chunk), th
 
 Every (batch, head) pair is an independent recurrence, so the fp64 oracle can check any subset of
 sequences one by one.  The training shapes are cheap enough for the oracle that every output
-element of every sequence is compared; the decode workload (512 steps over 4096 states) is
-compared on a seeded sample of (batch, head) pairs for every step, plus properties that hold for
-all of them.  Tolerance: max|x-y|/max|y| <= 2e-2 per output tensor (bf16 storage)."""
+element of every sequence is compared, and so is the decode workload (512 steps over 4096 states:
+every output of every step and the final states), plus a property of the states that holds at any
+size.  Tolerance: max|x-y|/max|y| <= 2e-2 per output tensor (bf16 storage)."""
 import numpy as np
 import pytest
 import torch
@@ -58,10 +58,10 @@ def test_config3_full_size(gate_dtype):
 
 
 def test_config4_full_size_512_steps():
-    """B=256, H=16, dk=dv=128, fp32 state updated in place over 512 distinct tokens.  Sampled
-    (batch, head) pairs are compared with the oracle at every step and in the final state; for
-    all pairs the final state must stay inside the convex hull of its inputs (each state row is
-    a convex combination of the initial row and past values, because key and gate sum to one)."""
+    """B=256, H=16, dk=dv=128, fp32 state updated in place over 512 distinct tokens.  All 4096
+    (batch, head) pairs are compared with the oracle at every step and in the final state; the
+    final state must also stay inside the convex hull of its inputs (each state row is a convex
+    combination of the initial row and past values, because key and gate sum to one)."""
     T = 512
     print("\n[full] config4: B=256 H=16 d=128, %d steps" % T, flush=True)
     w = synth.config4(T=T)
@@ -74,20 +74,17 @@ def test_config4_full_size_512_steps():
     torch.cuda.synchronize()
     print("    steps done", flush=True)
 
-    rng = np.random.default_rng(7)
-    pairs = sorted(set((int(b), int(h)) for b, h in zip(rng.integers(0, B, 48), rng.integers(0, H, 48))))
-    pairs += [(0, 0), (B - 1, H - 1)]
-    bs = np.array([p[0] for p in pairs]); hs = np.array([p[1] for p in pairs])
-    # the oracle sees the sampled pairs as a [T, n_pairs, 1, d] batch
-    qs, fs, vs = (np.ascontiguousarray(x[:, bs, hs][:, :, None, :]) for x in (w.q, w.f, w.v))
-    st_ref = np.ascontiguousarray(w.state[bs, hs][:, None]).astype(np.float64)
+    # every (batch, head) pair, every step: the oracle sees them as a [T, B*H, 1, d] batch
+    qs, fs, vs = (np.ascontiguousarray(x.reshape(T, B * H, 1, d)) for x in (w.q, w.f, w.v))
+    st_ref = np.ascontiguousarray(w.state.reshape(B * H, 1, d, d)).astype(np.float64)
     o_ref = oracle.steps(qs, fs, vs, st_ref)
-    o_gpu = host(outs[:, torch.from_numpy(bs).cuda(), torch.from_numpy(hs).cuda()])[:, :, None, :]
+    print("    oracle done", flush=True)
+    o_gpu = host(outs).reshape(T, B * H, 1, d)
     check("o[all t]", o_gpu, o_ref, 2e-2)
     for t in (0, 1, T // 2, T - 1):
         check("o[%d]" % t, o_gpu[t], o_ref[t], 2e-2)
     st_gpu = host(st)
-    check("state", st_gpu[bs, hs][:, None], st_ref, 1e-5)
+    check("state", st_gpu.reshape(B * H, 1, d, d), st_ref, 1e-5)
 
     # all pairs: finite, and min(S_0[a,b], min_t v_t[b]) <= S[a,b] <= max(S_0[a,b], max_t v_t[b])
     assert np.all(np.isfinite(st_gpu))

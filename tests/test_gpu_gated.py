@@ -112,8 +112,8 @@ def test_cumax_parity():
 @pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
 def test_gated_decode_steps(dk, dv, gate_dtype):
     """Twelve consecutive decode steps from the gate's pre-activations, in place, against the oracle's
-    step fed with the gate of Eq. 2; the state after the last step is compared too (fp32, so to 1e-4
-    of its largest entry after twelve updates is too tight for exp/rcp approximations: 1e-3)."""
+    step fed with the gate of Eq. 2; the fp32 state after the last step is compared too, at the fp32
+    tolerance of 1e-4 (the gate's exp / rcp approximations leave about 2e-7)."""
     B, H, T = 3, 5, 12
     print("\n[gated step] dk=%d dv=%d gate=%s" % (dk, dv, gate_dtype), flush=True)
     rng = np.random.default_rng(7700 + dk + 2 * dv)
@@ -133,7 +133,7 @@ def test_gated_decode_steps(dk, dv, gate_dtype):
         ro = oracle.step(q[t], f_t, v[t], ref_state)
         torch.cuda.synchronize()
         check("o[%d]" % t, host(o), ro, TOL["bf16"])
-    check("state", host(st), ref_state, 1e-3)
+    check("state", host(st), ref_state, TOL["f32"])
 
 
 @pytest.mark.parametrize("case", ["bf16", "f32", "bnhd", "gated", "ragged"])
