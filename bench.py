@@ -31,15 +31,33 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 CHUNK = 64
 
-# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each
-# scaled by what the same counter reads for a plain copy kernel of known size; bytes per launch at
-# the benchmark workload.  None until measured; see profiles/.
-MEASURED_TRAFFIC_BYTES = {"bwd_chunk_grads": 739.0e6,     # 537.7 MB read + 201.3 MB written (profiles/pmc_hbm_traffic_config2.md)
-                          "hgrn1_fwd": 268.6e6, "hgrn1_bwd": 578.9e6}   # profiles/hgrn1_kernel_trace_and_traffic_b8_n2048_d2048.md
+
+def published_peaks():
+    """The published MI355X peaks, kept in one header (include/mi355x_peaks.h)."""
+    import re
+    text = open(os.path.join(ROOT, "include", "mi355x_peaks.h")).read()
+    return {m.group(1): float(m.group(2)) for m in re.finditer(r"#define\s+MI355X_(\w+)\s+([0-9.]+)", text)}
+
+
+PEAKS = published_peaks()
+HBM_PEAK_GBS = PEAKS["HBM_GBPS"]
+MFMA_BF16_PEAK_TFLOPS = PEAKS["MFMA_BF16_TFLOPS"]
+
+
+def measured_traffic():
+    """HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark, as
+    paper_2404_07904_amd/pmc_summary.py wrote them (scaled by the copy probe); {} if never taken."""
+    path = os.path.join(ROOT, "profiles", "measured_traffic.json")
+    if not os.path.exists(path):
+        return {}
+    with open(path) as fh:
+        data = json.load(fh)
+    return {k: v["bytes"] for k, v in data.get("kernels", {}).items()}
+
+
+MEASURED_TRAFFIC_BYTES = measured_traffic()
 
 
 def parse():
@@ -113,11 +131,11 @@ def main():
         train_fwd(i)
         train_bwd(i)
 
-    if args.calibrate_copy:
+    if args.calibrate_copy:          # the known-size kernel the --pmc byte counters are scaled by
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            binding.hgrn2_probe_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
 
@@ -239,6 +257,43 @@ def main():
         "calls": call_out,
         "stages": stage_out,
     }
+
+    # ---- what this machine sustains: a plain copy and a loop of bf16 matrix instructions ----
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        binding.hgrn2_probe_copy(dst, src)
+    t_copy = timed(lambda i: binding.hgrn2_probe_copy(dst, src), reps=10)
+    del src, dst
+    mf_flops, mf_out = binding.hgrn2_probe_mfma(2000)
+    t_mfma = timed(lambda i: binding.hgrn2_probe_mfma(2000, mf_out), reps=5)
+    result["empirical_peaks"] = {
+        "copy_GBps": round(2 * (1 << 30) / t_copy / 1e9, 1), "copy_frac_of_published": round(2 * (1 << 30) / t_copy / 1e9 / HBM_PEAK_GBS, 4),
+        "mfma_bf16_TFLOPs": round(mf_flops / t_mfma / 1e12, 1),
+        "mfma_frac_of_published": round(mf_flops / t_mfma / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "what": "hgrn2_probe_copy of 1 GiB (2 GiB of traffic); hgrn2_probe_mfma: 8192 waves x 2000 x 4 independent 32x32x16 bf16 MFMAs",
+        "published": {"hbm_GBps": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS, "header": "include/mi355x_peaks.h"}}
+    result["roofline"]["frac_of_copy_rate"] = round(result["roofline"]["achieved"] / result["empirical_peaks"]["copy_GBps"], 4)
+
+    # ---- the three layers configs[2] names (gates of layers 0, 12, 23 of the 24-layer stack) ----
+    layers = {}
+    for layer in (0, 12, 23):
+        a = sets[0] if layer == args.layer else tuple(to_dev(x) for x in (lambda wl: (wl.q, wl.f, wl.v, wl.dO))(synth.config2(layer)))
+        b = tuple(t.clone() for t in a)          # the same data at other addresses: no step finds its inputs in cache
+        pair = (a, b)
+
+        def layer_step(i):
+            q, f, v, dO = pair[i % 2]
+            binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=saved[i % 2], workspace=ws)
+            binding.hgrn2_bwd_saved(q, f, v, saved[i % 2], dO, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv)
+
+        for i in range(4):
+            layer_step(i)
+        tl = timed(layer_step, reps=30)
+        layers["layer_%d" % layer] = {"lower_bound": round(synth.layer_lower_bound(layer), 4), "ms_per_step": round(tl * 1e3, 4),
+                                      "tokens_per_s": round(tokens / tl, 1)}
+        del pair, a, b
+    result["layers"] = layers
 
     # ---- the same step with the gate of Eq. 2 formed inside the kernels (z and beta instead of f) ----
     if not args.no_gated:
@@ -409,10 +464,10 @@ def main():
             "tokens_per_s_fwd_bwd": round(tokens / (tf + tb), 1),
             "roofline_fwd": {"bound": "hbm", "achieved": round(4 * e1 / tf / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4),
-                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_fwd")},
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_fwd_kernel")},
             "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tb / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4),
-                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_bwd")}}
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_bwd_kernel")}}
         del sets1, ws1, y1
 
     # ---- variable-length batch: the same 16384 tokens per head, packed as documents of mixed length ----
@@ -498,7 +553,7 @@ def main():
 
     # ---- decode: 512 consecutive in-place steps at B=256, H=16, d=128 ----
     if not args.no_decode:
-        Bd, Hd, T_distinct = 256, 16, 64
+        Bd, Hd, T_distinct = 256, 16, args.decode_steps          # a distinct token per step
         wd = synth.config4(T=T_distinct, B=Bd, H=Hd, d=D)
         qd, fd, vd = (to_dev(x) for x in (wd.q, wd.f, wd.v))
         st = to_dev(wd.state, torch.float32)
@@ -515,12 +570,14 @@ def main():
         torch.cuda.synchronize()
         dt = a.elapsed_time(b) * 1e-3 / args.decode_steps
         step_bytes = 2 * Bd * Hd * D * D * 4 + 4 * Bd * Hd * D * el
-        result["decode"] = {"workload": "configs[4]: B=256 H=16 dk=dv=128, %d in-place steps, %d distinct tokens cycled"
-                                        % (args.decode_steps, T_distinct),
+        result["decode"] = {"workload": "configs[4]: B=256 H=16 dk=dv=128, %d in-place steps, a distinct token per step"
+                                        % args.decode_steps,
                             "us_per_step": round(dt * 1e6, 2), "GBps": round(step_bytes / dt / 1e9, 1),
                             "roofline": {"bound": "hbm", "achieved": round(step_bytes / dt / 1e9, 1),
                                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                         "frac": round(step_bytes / dt / 1e9 / HBM_PEAK_GBS, 4), "traffic": None}}
+                                         "frac": round(step_bytes / dt / 1e9 / HBM_PEAK_GBS, 4),
+                                         "algorithmic_bytes": step_bytes,
+                                         "traffic": MEASURED_TRAFFIC_BYTES.get("step_kernel")}}
 
     # ---- CPU baseline: the fp64 oracle as it stands, on the same seeded inputs ----
     if not args.no_cpu_baseline:

@@ -338,6 +338,21 @@ int hgrn2_bwd_noalloc(const hgrn2_shape* shape, const void* q, const void* f, co
                       const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
                       void* grad_f, void* grad_v, float* grad_h0, void* hip_stream);
 
+/*
+ * Measurement probes (no part of the method): what this GPU sustains for a plain copy and for a
+ * loop of bf16 matrix instructions, the practical ceilings next to the published peaks of
+ * mi355x_peaks.h that roofline fractions are quoted against.
+ *   hgrn2_probe_copy   copies `bytes` (a multiple of 16; both pointers 16-byte aligned) from src to
+ *                      dst on the device: 2 * bytes of traffic.
+ *   hgrn2_probe_mfma   every wave of a grid that fills the chip issues `iters` rounds of four
+ *                      independent 32x32x16 bf16 matrix instructions; *flops (host, may be NULL)
+ *                      receives the number of floating-point operations of the launch; `out`
+ *                      (device, hgrn2_probe_mfma_out_floats() floats) receives one sum per thread.
+ */
+int hgrn2_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+size_t hgrn2_probe_mfma_out_floats(void);
+int hgrn2_probe_mfma(int32_t iters, float* out, double* flops, void* hip_stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* hgrn2_status_string(int status);
 

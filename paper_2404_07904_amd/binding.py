@@ -22,7 +22,8 @@ EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd"
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
            "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc",
-           "hgrn2_saved_states_bytes", "hgrn2_bwd_saved_workspace_bytes", "hgrn2_fwd_saving", "hgrn2_bwd_saved"]
+           "hgrn2_saved_states_bytes", "hgrn2_bwd_saved_workspace_bytes", "hgrn2_fwd_saving", "hgrn2_bwd_saved",
+           "hgrn2_probe_copy", "hgrn2_probe_mfma_out_floats", "hgrn2_probe_mfma"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
@@ -101,6 +102,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_readout.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_bwd_chunk_grads.restype = ctypes.c_int
         L.hgrn2_bwd_chunk_grads.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hgrn2_probe_copy.restype = ctypes.c_int
+        L.hgrn2_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.hgrn2_probe_mfma_out_floats.restype = sz
+        L.hgrn2_probe_mfma_out_floats.argtypes = []
+        L.hgrn2_probe_mfma.restype = ctypes.c_int
+        L.hgrn2_probe_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.hgrn2_saved_states_bytes.restype = sz
         L.hgrn2_saved_states_bytes.argtypes = [sp]
         L.hgrn2_bwd_saved_workspace_bytes.restype = sz
@@ -203,6 +210,25 @@ def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chu
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd")
     return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgrn2_probe_copy(dst, src):
+    """Plain device copy of src into dst (uint8 tensors of equal size, a multiple of 16 bytes)."""
+    assert dst.numel() == src.numel() and dst.dtype == torch.uint8 and src.dtype == torch.uint8
+    rc = lib().hgrn2_probe_copy(_ptr(dst), _ptr(src), src.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_probe_copy")
+
+
+def hgrn2_probe_mfma(iters, out=None):
+    """A launch of nothing but bf16 matrix instructions; returns (flops of the launch, out)."""
+    if out is None:
+        out = torch.empty(int(lib().hgrn2_probe_mfma_out_floats()), dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    rc = lib().hgrn2_probe_mfma(int(iters), _ptr(out), ctypes.byref(flops), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgrn2_probe_mfma")
+    return flops.value, out
 
 
 def hgrn2_saved_states_bytes(shape: hgrn2_shape) -> int:
