@@ -39,7 +39,10 @@
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
- *     io_dtype F32 is supported by hgrn2_fwd and hgrn2_step (hgrn2_bwd: BF16 only).
+ *     io_dtype F32 is supported by hgrn2_fwd, hgrn2_step and, for heads of dk = dv = 64, by hgrn2_bwd
+ *     and its gated / saving forms (the same kernels with fp32 tiles and fp32 matrix instructions:
+ *     the fp32 tiles of wider heads exceed the LDS); packed batches and the chunk-gradient stage
+ *     call are BF16-only in the backward direction.
  */
 #ifndef HGRN2_H
 #define HGRN2_H

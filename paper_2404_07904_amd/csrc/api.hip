@@ -30,7 +30,9 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     } else if (s->chunk != 0 && s->chunk != kChunk) {
         return HGRN2_ERR_UNSUPPORTED;
     }
-    if (backward && s->io_dtype != HGRN2_BF16) return HGRN2_ERR_UNSUPPORTED;
+    // fp32 storage in the backward pass: heads of 64 x 64 only (the fp32 tiles of wider heads exceed
+    // the LDS), equal-length batches only
+    if (backward && s->io_dtype != HGRN2_BF16 && (packed || s->dk != 64 || s->dv != 64)) return HGRN2_ERR_UNSUPPORTED;
     d->BH = (int)bh;
     d->N = s->N;
     d->NC = (int)nc;
@@ -486,7 +488,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
             t.N = d.N - (int)skip;
             t.NC = d.NC - pl.rc;
             const SeqDims r = as_runs(t, pl.seg_tail, pl.sub_chunks);
-            const size_t io = 2, ge = d.gate_bf16 ? 2 : 4;               // bytes per element (the backward is bf16-only)
+            const size_t io = d.io_bf16 ? 2 : 4, ge = d.gate_bf16 ? 2 : 4;   // bytes per element
             const char* q_t = static_cast<const char*>(q) + (size_t)skip * d.lay.sn_k * io;
             const char* f_t = static_cast<const char*>(f) + (size_t)skip * d.lay.sn_k * ge;
             const char* g_t = static_cast<const char*>(grad_o) + (size_t)skip * d.lay.sn_v * io;
@@ -938,6 +940,7 @@ int hgrn2_bwd_chunk_grads(const hgrn2_shape* shape, const void* q, const void* f
     SeqDims d;
     const int rc = check_shape(shape, true, &d);
     if (rc != HGRN2_OK) return rc;
+    if (!d.io_bf16) return HGRN2_ERR_UNSUPPORTED;          // this stage exists for bf16 storage only
     if ((size_t)d.BH * d.N == 0) return HGRN2_OK;
     if (!q || !f || !v || !grad_o || !chunk_states || !chunk_state_grads || !grad_q || !grad_f || !grad_v)
         return HGRN2_ERR_NULL;

@@ -138,10 +138,12 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     constexpr int PK = L::PK, PV = L::PV, PVR = L::PVR, PC = L::PC, PF = L::PF;
     constexpr int NRT = C / 32, NAT = DK / 32, NBT = DV / 32;
     static_assert(NRT == 2 && NRT * NAT <= NW && NRT * NBT <= NW, "one tile per wave");
-    static_assert(sizeof(T) == 2, "bf16 storage");
     typedef Mma<T> M;
     typedef typename M::frag frag;
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef T tx2 __attribute__((ext_vector_type(2)));
+    typedef T tx4 __attribute__((ext_vector_type(4)));
+    constexpr bool io_bf16 = is_bf16_type<T>();
+    constexpr int VEC = 16 / (int)sizeof(T);            // elements per 16-byte vector
 
     extern __shared__ __align__(16) char smem[];
     T* Qm = reinterpret_cast<T*>(smem + L::qm);
@@ -205,15 +207,13 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         const int col_k = (2 * lane < DK) ? 2 * lane : 0;
         const int r0 = c.n * C + RW * w;
         load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + c.sv.off_k * GES, r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
-        load_rows_clamped<RW, true>(cq, reinterpret_cast<const char*>(qg + c.sv.off_k), r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
+        load_rows_clamped<RW, io_bf16>(cq, reinterpret_cast<const char*>(qg + c.sv.off_k), r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
     };
-    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cv)[2], u32x4 (&cd)[2], const ChunkAt& c, int lane) {
+    auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, Raw16<T>& cv, Raw16<T>& cd, const ChunkAt& c, int lane) {
         load_fq_rows(cf, cq, c, lane);
         const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
-        cv[0] = *reinterpret_cast<const u32x4*>(vg + vo);
-        cv[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
-        cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
-        cd[1] = *reinterpret_cast<const u32x4*>(dog + vo + 8);
+        cv.load(vg + vo);
+        cd.load(dog + vo);
     };
     auto load_chunk_states = [&](frag (&cS)[2 * NBT], frag (&cD)[2 * NBT], int chunk, int lane) {
         const size_t slot = (size_t)chunk * DK * DV;
@@ -231,7 +231,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         if (p.lay.vl) n_chunks = p.lay.vl[2 * (p.lay.B + 1) + p.lay.B] * p.lay.H;      // the table's total, not the host's bound
     }
     RawRows<RW> raw_f, raw_q;
-    u32x4 raw_v[2], raw_d[2];
+    Raw16<T> raw_v, raw_d;
     frag sS[2 * NBT], sD[2 * NBT];
     // chunks of this workgroup: every gridDim.x-th one, or (FUSED) those of its run, last to first
     int n_iter, f_bh = 0, f_run = 0, f_first = 0, f_last = 0;
@@ -287,11 +287,10 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             // ---- light walk over the chunks after this run: dS_n = Diag(g_n) dS_{n+1} + Q^_n^T dO_n with
             // Q^ = q G (G the gate product from the chunk start: no quotient), true state gradient in
             // the accumulators.  Three barriers per chunk; the Q~ and dO tiles and the block totals are reused.
-            auto load_light = [&](RawRows<RW>& cf, RawRows<RW>& cq, u32x4 (&cd)[2], const ChunkAt& c, int lane) {
+            auto load_light = [&](RawRows<RW>& cf, RawRows<RW>& cq, Raw16<T>& cd, const ChunkAt& c, int lane) {
                 load_fq_rows(cf, cq, c, lane);
                 const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
-                cd[0] = *reinterpret_cast<const u32x4*>(dog + vo);
-                cd[1] = *reinterpret_cast<const u32x4*>(dog + vo + 8);
+                cd.load(dog + vo);
             };
             cur = where(f_bh * p.NC + p.NC - 1);
             load_light(raw_f, raw_q, raw_d, cur, tid & 63);
@@ -300,16 +299,12 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 asm volatile("" : "+v"(lane_opaque));
                 const int lane = lane_opaque, r32 = lane & 31;
                 const bool k_act = 2 * lane < DK;
-                if (vd_act) {
-                    T* ddst = dOm + (size_t)vd_row * PV + 16 * vd_grp;
-                    *reinterpret_cast<u32x4*>(ddst) = u32x4{raw_d[0][0], raw_d[0][1], raw_d[1][0], raw_d[1][1]};
-                    *reinterpret_cast<u32x4*>(ddst + 8) = u32x4{raw_d[0][2], raw_d[0][3], raw_d[1][2], raw_d[1][3]};
-                }
+                if (vd_act) raw_d.store_swapped(dOm + (size_t)vd_row * PV + 16 * vd_grp);
                 const int row0 = cur.n * C + RW * w;
                 f32x2 rf[RW], rq[RW];
                 convert_rows<RW>(rf, raw_f, row0, cur.sv.N, k_act, gate_bf16, 1.0f);
                 if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(f_bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cur.sv.N);
-                convert_rows<RW>(rq, raw_q, row0, cur.sv.N, k_act, true, 0.0f);
+                convert_rows<RW>(rq, raw_q, row0, cur.sv.N, k_act, io_bf16, 0.0f);
                 float a0[RW], a1[RW], t0 = 1.0f, t1 = 1.0f;
 #pragma unroll
                 for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; a0[i] = t0; a1[i] = t1; }
@@ -329,9 +324,9 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                     }
 #pragma unroll
                     for (int i = 0; i < RW; ++i) {
-                        bf16x2 x;
+                        tx2 x;
                         x.x = (T)(rq[i].x * (pre0 * a0[i])); x.y = (T)(rq[i].y * (pre1 * a1[i]));
-                        *reinterpret_cast<bf16x2*>(Qm + (size_t)(RW * w + i) * PK + 2 * lane) = x;
+                        *reinterpret_cast<tx2*>(Qm + (size_t)(RW * w + i) * PK + 2 * lane) = x;
                     }
                 }
                 float g_all = 1.0f;
@@ -360,8 +355,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             }
             // what the full pass over the run's last chunk needs on top: its V rows
             const size_t vo = cur.sv.off_v + (size_t)min(cur.n * C + vd_row, cur.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
-            raw_v[0] = *reinterpret_cast<const u32x4*>(vg + vo);
-            raw_v[1] = *reinterpret_cast<const u32x4*>(vg + vo + 8);
+            raw_v.load(vg + vo);
             rows_loaded = true;
         }
     }
@@ -388,19 +382,15 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // V, dO tiles: raw bits, the four 4-column quads of a 16-column group stored in the order
     // (0, 2, 1, 3), i.e. column b at position b with bits 2 and 3 swapped
     if (vd_act) {
-        T* vdst = Vm + (size_t)vd_row * PVR + 16 * vd_grp;
-        T* ddst = dOm + (size_t)vd_row * PV + 16 * vd_grp;
-        *reinterpret_cast<u32x4*>(vdst) = u32x4{raw_v[0][0], raw_v[0][1], raw_v[1][0], raw_v[1][1]};
-        *reinterpret_cast<u32x4*>(vdst + 8) = u32x4{raw_v[0][2], raw_v[0][3], raw_v[1][2], raw_v[1][3]};
-        *reinterpret_cast<u32x4*>(ddst) = u32x4{raw_d[0][0], raw_d[0][1], raw_d[1][0], raw_d[1][1]};
-        *reinterpret_cast<u32x4*>(ddst + 8) = u32x4{raw_d[0][2], raw_d[0][3], raw_d[1][2], raw_d[1][3]};
+        raw_v.store_swapped(Vm + (size_t)vd_row * PVR + 16 * vd_grp);
+        raw_d.store_swapped(dOm + (size_t)vd_row * PV + 16 * vd_grp);
     }
     // rf is re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
     const int row0 = n * C + RW * w;
     f32x2 rf[RW], rq[RW];
     convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
     if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
-    convert_rows<RW>(rq, raw_q, row0, N, k_act, true, 0.0f);
+    convert_rows<RW>(rq, raw_q, row0, N, k_act, io_bf16, 0.0f);
 
     // ---------------- gate products; scaled operand tiles ----------------
     // With a = inclusive gate product from the start of this wave's 8-row block, z = exclusive
@@ -414,7 +404,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // it stays finite outside the supported gate range.  a, z, s_a, s_z are kept for the
     // epilogue (dq = sq * (...), dk = sk * (...)).
     float a0[RW], a1[RW], z0[RW], z1[RW], sa0 = 1.0f, sa1 = 1.0f, sz0 = 1.0f, sz1 = 1.0f;
-    bf16x2 qb[RW], kb[RW];      // Q~, K~ of this thread's elements exactly as rounded for the MFMAs (epilogue)
+    tx2 qb[RW], kb[RW];         // Q~, K~ of this thread's elements exactly as rounded for the MFMAs (epilogue)
     {
         float t0 = 1.0f, t1 = 1.0f;
 #pragma unroll
@@ -442,12 +432,12 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 const int row = RW * w + i;
                 qb[i].x = (T)(rq[i].x * (sa0 * a0[i])); qb[i].y = (T)(rq[i].y * (sa1 * a1[i]));
                 kb[i].x = (T)((1.0f - rf[i].x) * (sz0 * z0[i])); kb[i].y = (T)((1.0f - rf[i].y) * (sz1 * z1[i]));
-                *reinterpret_cast<bf16x2*>(Qm + (size_t)row * PK + 2 * lane) = qb[i];
-                *reinterpret_cast<bf16x2*>(Km + (size_t)row * PK + 2 * lane) = kb[i];
+                *reinterpret_cast<tx2*>(Qm + (size_t)row * PK + 2 * lane) = qb[i];
+                *reinterpret_cast<tx2*>(Km + (size_t)row * PK + 2 * lane) = kb[i];
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < RW; ++i) { qb[i] = bf16x2{(T)0.0f, (T)0.0f}; kb[i] = qb[i]; }
+            for (int i = 0; i < RW; ++i) { qb[i] = tx2{(T)0.0f, (T)0.0f}; kb[i] = qb[i]; }
         }
     }
     // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv position] (the fragments hold
@@ -546,16 +536,17 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int i0 = 32 * I + 8 * c + 4 * g;
-            bf16x4 pk;
+            tx4 pk;
 #pragma unroll
             for (int ii = 0; ii < 4; ++ii) pk[ii] = (T)((j_glob <= i0 + ii) ? acc0[4 * c + ii] + acc1[4 * c + ii] : 0.0f);
-            *reinterpret_cast<bf16x4*>(dst + (size_t)j_glob * PC + i0) = pk;
+            *reinterpret_cast<tx4*>(dst + (size_t)j_glob * PC + i0) = pk;
         }
     } else {
         T* dst = (w == 6) ? Pt : dPt;    // rows 32..63, columns 0..31: 32 x 32 values, 16 per lane
         const u32x4 z = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1)) = z;
-        *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1) + 8) = z;
+#pragma unroll
+        for (int k = 0; k < 16 / VEC; ++k)
+            *reinterpret_cast<u32x4*>(dst + (size_t)(32 + (lane >> 1)) * PC + 16 * (lane & 1) + VEC * k) = z;
     }
     __syncthreads();
 
@@ -691,14 +682,14 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     }
     // coalesced store of dv
     {
-        constexpr int VPR = DV / 8;
+        constexpr int VPR = DV / VEC;
         T* dvg = static_cast<T*>(p.dv);
         for (int idx = tid; idx < C * VPR; idx += kBwdThreads) {
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = n * C + row;
             if (grow < N)
-                *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * ld_v + cv * 8) =
-                    *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * 8);
+                *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * ld_v + cv * VEC) =
+                    *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * VEC);
         }
     }
     __syncthreads();
@@ -872,7 +863,8 @@ hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void
                             float* beta_partials, hipStream_t stream)
 {
     if (d.total_chunks() == 0) return hipSuccess;
-    if (!d.io_bf16 || d.packed || d.lay.vl) return hipErrorInvalidValue;
+    if (d.packed || d.lay.vl) return hipErrorInvalidValue;
+    if (!d.io_bf16 && !(d.dk == 64 && d.dv == 64)) return hipErrorInvalidValue;    // fp32 tiles of wider heads exceed the LDS
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
     BwdGradParams p;
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = nullptr;
@@ -883,6 +875,7 @@ hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void
     p.R = pl.R; p.rc = pl.rc; p.s_sub = pl.s_sub; p.seg_tail = pl.seg_tail;
     p.light = pl.light;
     for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = pl.bnd[i];
+    if (!d.io_bf16) return launch_fused_one<float, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 128) return launch_fused_one<__bf16, 128, 128>(d, p, stream);
     if (d.dk == 64 && d.dv == 64) return launch_fused_one<__bf16, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 64) return launch_fused_one<__bf16, 128, 64>(d, p, stream);

@@ -27,6 +27,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr float kTinyProduct = 7.888609052210118e-31f;   // 2^-100: floor under a reciprocal
@@ -404,6 +406,12 @@ template <> struct Mma<float> {
     {
         return gather(tile + (k0 + 8 * (lane >> 5)) * pitch + x0 + (lane & 31), pitch);
     }
+    // columns stored with bits 2 and 3 of their index swapped: lane x0 + lane % 32 receives the true column
+    static __device__ __forceinline__ frag load_kmajor_swapped(const float* tile, int pitch, int k0, int x0, int lane)
+    {
+        const int c = lane & 31, pos = (c & ~12) | ((c & 4) << 1) | ((c & 8) >> 1);
+        return gather(tile + (k0 + 8 * (lane >> 5)) * pitch + x0 + pos, pitch);
+    }
     static __device__ __forceinline__ frag pack(const float* x)
     {
         frag r;
@@ -417,6 +425,39 @@ template <> struct Mma<float> {
     {
 #pragma unroll
         for (int s = 0; s < 8; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[s], b.v[s], acc, 0, 0, 0);
+    }
+};
+
+// 16 consecutive columns of one row as raw bits, on their way from global memory to an LDS tile
+// whose columns are kept, inside every group of 16, in the order the state fragments hold their
+// contraction index: the four quads of columns land in the order (0, 2, 1, 3).
+template <typename T> struct Raw16;
+template <> struct Raw16<__bf16> {
+    u32x4 v[2];
+    __device__ __forceinline__ void load(const __bf16* p)
+    {
+        v[0] = *reinterpret_cast<const u32x4*>(p);
+        v[1] = *reinterpret_cast<const u32x4*>(p + 8);
+    }
+    __device__ __forceinline__ void store_swapped(__bf16* dst) const
+    {
+        *reinterpret_cast<u32x4*>(dst) = u32x4{v[0][0], v[0][1], v[1][0], v[1][1]};
+        *reinterpret_cast<u32x4*>(dst + 8) = u32x4{v[0][2], v[0][3], v[1][2], v[1][3]};
+    }
+};
+template <> struct Raw16<float> {
+    u32x4 v[4];
+    __device__ __forceinline__ void load(const float* p)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x4*>(p + 4 * i);
+    }
+    __device__ __forceinline__ void store_swapped(float* dst) const
+    {
+        *reinterpret_cast<u32x4*>(dst) = v[0];
+        *reinterpret_cast<u32x4*>(dst + 4) = v[2];
+        *reinterpret_cast<u32x4*>(dst + 8) = v[1];
+        *reinterpret_cast<u32x4*>(dst + 12) = v[3];
     }
 };
 

@@ -350,7 +350,11 @@ hipError_t launch_sweep(const SeqDims& d, SweepMode mode, const void* q, const v
         case kSweepGrad:     return launch_dims<__bf16, kSweepGrad>(d, p, stream);
         }
     } else {
-        if (mode == kSweepStateFwd) return launch_dims<float, kSweepStateFwd>(d, p, stream);
+        switch (mode) {
+        case kSweepStateFwd: return launch_dims<float, kSweepStateFwd>(d, p, stream);
+        case kSweepStateBwd: return launch_dims<float, kSweepStateBwd>(d, p, stream);
+        case kSweepGrad:     return launch_dims<float, kSweepGrad>(d, p, stream);
+        }
     }
     return hipErrorInvalidValue;
 }

@@ -51,7 +51,8 @@ def test_workspace_sizes():
     assert binding.hgrn2_bwd_saved_workspace_bytes(s, False) == 0
     s32 = shape(B=1, H=1, N=256, io=0, gate=0)
     assert binding.hgrn2_fwd_workspace_bytes(s32) == 4 * 64 * 64 * 4
-    assert binding.hgrn2_bwd_workspace_bytes(s32) == 0           # fp32 backward is unsupported
+    assert binding.hgrn2_bwd_workspace_bytes(s32) == 4 * 64 * 64 * 4   # fp32 backward: heads of 64 x 64 only
+    assert binding.hgrn2_bwd_workspace_bytes(shape(B=1, H=1, N=256, dk=128, dv=128, io=0, gate=0)) == 0
     assert binding.hgrn2_fwd_workspace_bytes(shape(N=65)) == 2 * 3 * 2 * 64 * 64 * 2   # ragged: 2 chunks
     assert binding.hgrn2_fwd_workspace_bytes(shape(N=0)) == 0
     assert binding.hgrn2_fwd_workspace_bytes(shape(dk=96)) == 0
@@ -123,7 +124,8 @@ def test_fwd_argument_errors():
 
 def test_bwd_argument_errors():
     assert call_bwd(None) == E_NULL
-    assert call_bwd(shape(io=0)) == E_UNSUP          # fp32 storage: forward and step only
+    assert call_bwd(shape(io=0, dk=128)) == E_UNSUP  # fp32 storage in the backward pass: heads of 64 x 64 only
+    assert call_bwd(shape(io=0, dv=128)) == E_UNSUP
     assert call_bwd(shape(dk=32)) == E_UNSUP
     assert call_bwd(shape(), go=None) == E_NULL
     assert call_bwd(shape(), gf=None) == E_NULL
@@ -150,8 +152,10 @@ def test_stage_entry_point_errors():
     assert lib.hgrn2_state_sweep(ctypes.byref(s), 5, FAKE, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_SHAPE
     assert lib.hgrn2_state_sweep(ctypes.byref(s), 2, None, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_NULL
     assert lib.hgrn2_state_sweep(ctypes.byref(s), 0, None, FAKE, FAKE, None, None, FAKE_WS, 10, None) == E_WS
-    s32 = shape(io=0, gate=0)
+    s32 = shape(io=0, gate=0, dk=128)
     assert lib.hgrn2_state_sweep(ctypes.byref(s32), 1, None, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == E_UNSUP
+    s32 = shape(io=0, gate=0)
+    assert lib.hgrn2_bwd_chunk_grads(ctypes.byref(s32), FAKE, FAKE, FAKE, FAKE, FAKE_WS, FAKE_WS, FAKE, FAKE, FAKE, None) == E_UNSUP
     assert lib.hgrn2_fwd_readout(ctypes.byref(s), FAKE, FAKE, FAKE, None, FAKE, None) == E_NULL
     assert lib.hgrn2_bwd_chunk_grads(ctypes.byref(s), FAKE, FAKE, FAKE, FAKE, FAKE_WS, ctypes.c_void_p(0x100008),
                                      FAKE, FAKE, FAKE, None) == E_WS
@@ -185,7 +189,7 @@ def test_gated_workspace_and_error_codes():
     assert bwd(shape(), beta=None) == E_NULL
     assert bwd(shape(), gb=None) == E_NULL
     assert bwd(shape(), gz=None) == E_NULL
-    assert bwd(shape(io=0, gate=0)) == E_UNSUP
+    assert bwd(shape(io=0, gate=0, dk=128)) == E_UNSUP
     need = binding.hgrn2_bwd_gated_workspace_bytes(shape())
     assert bwd(shape(), n=need - 1) == E_WS
     assert bwd(shape(), ws=ctypes.c_void_p(0x100010)) == E_WS

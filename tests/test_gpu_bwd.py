@@ -88,3 +88,53 @@ def test_bwd_deterministic():
     torch.cuda.synchronize()
     for x, y in zip(r1, r2):
         assert torch.equal(x, y)
+
+
+# ---- fp32 storage (heads of 64 x 64): the same kernels with fp32 tiles and fp32 matrix
+# instructions, which holds the chunkwise backward algebra to 1e-4 instead of the 2e-2 that bf16
+# operands allow.  Wider heads are bf16-only: their fp32 tiles do not fit the LDS.
+@pytest.mark.parametrize("B,H,N,gate_dtype,note", [
+    (2, 3, 203, "f32", "one run, ragged last chunk"),
+    (1, 2, 1, "f32", "a single token"),
+    (3, 2, 64, "f32", "exactly one chunk"),
+    (1, 2, 640, "f32", "two runs, light walk over the second"),
+    (1, 3, 1100, "bf16", "four runs"),
+    (1, 1, 2500, "f32", "nine runs: boundary states from the zero-start sweep"),
+    (4, 16, 520, "f32", "64 sequences of 9 chunks"),
+])
+def test_bwd_fp32_storage(B, H, N, gate_dtype, note):
+    print("\n[bwd fp32] B=%d H=%d N=%d gate=%s (%s)" % (B, H, N, gate_dtype, note), flush=True)
+    w = synth.make_sequence(2600 + N, B, H, N, 64, 64, io_dtype="f32", gate_dtype=gate_dtype, lb=0.1,
+                            with_h0=True, with_dO=True, with_dhT=True)
+    run_bwd(w)
+
+
+def test_bwd_fp32_storage_token_major_and_gated():
+    B, H, N, d = 2, 3, 333, 64
+    print("\n[bwd fp32] token-major, gate formed in the kernels", flush=True)
+    rng = np.random.default_rng(2700)
+    w = synth.make_sequence(2701, B, H, N, d, d, io_dtype="f32", with_h0=True, with_dO=True, with_dhT=True)
+    z = rng.standard_normal((B, H, N, d)).astype(np.float32)
+    beta = rng.uniform(0.0, 0.9, size=(H, d)).astype(np.float32)
+    tm = lambda x: dev(x).permute(0, 2, 1, 3).contiguous()
+    back = lambda t: host(t.permute(0, 2, 1, 3))
+    BNHD = binding.HGRN2_LAYOUT_BNHD
+    bd = torch.from_numpy(beta).cuda()
+    gq, gz, gb, gv, gh0 = binding.hgrn2_bwd_gated(tm(w.q), tm(z), bd, tm(w.v), tm(w.dO), dev(w.h0), dev(w.dhT),
+                                                  want_grad_h0=True, layout=BNHD)
+    torch.cuda.synchronize()
+    rq, rz, rb, rv, rh = oracle.bwd_gated(w.q, z, beta, w.v, w.dO, w.h0, w.dhT)
+    tol = TOL["f32"]
+    check("dq", back(gq), rq, tol); check("dz", back(gz), rz, tol); check("dbeta", host(gb), rb, tol)
+    check("dv", back(gv), rv, tol); check("dh0", host(gh0), rh, tol)
+
+
+def test_bwd_fp32_storage_small_gates():
+    """The chunk-local gate gradient at small gates, where the cancelling pair terms matter most:
+    gates down to 0.05 (inside the ordinary domain), fp32, 1e-4."""
+    B, H, N = 2, 2, 300
+    print("\n[bwd fp32] gates in [0.05, 1]", flush=True)
+    w = synth.make_sequence(2800, B, H, N, 64, 64, io_dtype="f32", lb=0.05, with_h0=True, with_dO=True, with_dhT=True)
+    rng = np.random.default_rng(2801)
+    w.f = (0.05 + 0.95 * rng.random(w.f.shape)).astype(np.float32)
+    run_bwd(w)
