@@ -26,10 +26,16 @@
  *     detected on the host before anything is launched: nothing has been enqueued then.
  *     HGRN2_ERR_HIP reports a failed launch; earlier kernels of the same call may have been
  *     enqueued.  Nothing throws or aborts across the ABI.
- *   - Gate domain: f in [0, 1].  Results are exact (up to rounding) while the product of the
- *     gates of every 32 consecutive tokens of one channel stays above 2^-100 -- guaranteed for
- *     f >= 0.12 and true by a wide margin for sigmoid-type gates; below that the affected
- *     intra-chunk terms degrade smoothly (they stay finite) instead of failing.
+ *   - Gate domain: f in [0, 1].  The chunkwise kernels factor the decay between two tokens of a
+ *     chunk around the chunk's middle row, which needs the reciprocal of a product of up to 32
+ *     consecutive gates of one channel.  Results are exact (up to rounding) while every such
+ *     product stays above 2^-100 -- guaranteed for f >= 0.12 and true by a wide margin for
+ *     sigmoid-type gates.  Below that the reciprocal is taken of 2^-100 instead: everything stays
+ *     finite, but the affected chunks' outputs and gradients are WRONG (by up to 100%), and the
+ *     call still returns HGRN2_OK -- the host cannot know the gates.  Two ways to know:
+ *     shape->gate_domain_flag (a device int the kernels set when it happens, at no cost), and
+ *     hgrn2_min_gate_product (a probe that reads the gates once, before the call).  grad_f also
+ *     divides by f itself (floored at 1e-30): at f = 0 exactly it is not meaningful.
  *     Small-gate modes: with chunk = 32 or 16, hgrn2_fwd, hgrn2_bwd and their _gated and
  *     _varlen forms place their reference rows every 32 or 16 tokens instead of every 64, and
  *     the bound applies to the product of 16 or 8 consecutive gates (guaranteed for
@@ -77,6 +83,9 @@ typedef struct {
     int32_t io_dtype;   /* hgrn2_dtype of q, v, o and of every grad_* sequence tensor */
     int32_t gate_dtype; /* hgrn2_dtype of f (grad_f follows io_dtype) */
     int32_t layout;     /* hgrn2_layout of every sequence tensor (q, f, v, o, grad_*); 0 = [B][H][N][d] */
+    int32_t* gate_domain_flag; /* NULL, or a DEVICE int32 that the forward / backward kernels set to 1 when
+                           the gates of the call leave the gate domain described above (they never
+                           clear it: the caller zeroes it, and reads it after the stream has finished) */
 } hgrn2_shape;
 
 /* Bytes of device workspace hgrn2_fwd / hgrn2_bwd need for this shape (0 if the shape is

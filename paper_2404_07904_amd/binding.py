@@ -30,7 +30,8 @@ SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 class hgrn2_shape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32),
                 ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("chunk", ctypes.c_int32),
-                ("io_dtype", ctypes.c_int32), ("gate_dtype", ctypes.c_int32), ("layout", ctypes.c_int32)]
+                ("io_dtype", ctypes.c_int32), ("gate_dtype", ctypes.c_int32), ("layout", ctypes.c_int32),
+                ("gate_domain_flag", ctypes.c_void_p)]
 
 
 class Hgrn2Error(RuntimeError):
@@ -161,6 +162,15 @@ def make_shape(q, v, f, chunk=0, layout=HGRN2_LAYOUT_BHND) -> hgrn2_shape:
     return hgrn2_shape(B, H, N, dk, v.shape[-1], chunk, _dt(q), _dt(f), layout)
 
 
+def _flagged(shape: hgrn2_shape, domain_flag) -> hgrn2_shape:
+    """Point the shape at the caller's gate-domain flag (a one-element int32 device tensor the
+    kernels set to 1 when the gates leave the domain of the chunkwise kernels), if one is given."""
+    if domain_flag is not None:
+        assert domain_flag.dtype == torch.int32 and domain_flag.is_cuda and domain_flag.numel() >= 1
+        shape.gate_domain_flag = domain_flag.data_ptr()
+    return shape
+
+
 def hgrn2_fwd_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_fwd_workspace_bytes(ctypes.byref(shape)))
 
@@ -176,9 +186,9 @@ def _workspace(nbytes, device, workspace):
 
 
 def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, workspace=None,
-              layout=HGRN2_LAYOUT_BHND):
+              layout=HGRN2_LAYOUT_BHND, domain_flag=None):
     """o, hT = chunkwise forward of the recurrence.  q, f: [B,H,N,dk]; v: [B,H,N,dv]; h0 fp32."""
-    shape = make_shape(q, v, f, chunk, layout)
+    shape = _flagged(make_shape(q, v, f, chunk, layout), domain_flag)
     assert v.dtype == q.dtype and f.shape == q.shape
     if o is None:
         o = torch.empty_like(v)
@@ -194,9 +204,9 @@ def hgrn2_fwd(q, f, v, h0=None, *, want_hT=True, chunk=0, o=None, hT=None, works
 
 
 def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chunk=0, workspace=None,
-              grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND):
+              grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND, domain_flag=None):
     """grad_q, grad_f, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
-    shape = make_shape(q, v, f, chunk, layout)
+    shape = _flagged(make_shape(q, v, f, chunk, layout), domain_flag)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_f = torch.empty_like(q) if grad_f is None else grad_f
     grad_v = torch.empty_like(v) if grad_v is None else grad_v
@@ -240,10 +250,10 @@ def hgrn2_bwd_saved_workspace_bytes(shape: hgrn2_shape, gated: bool) -> int:
 
 
 def hgrn2_fwd_saving(q, f, v, h0=None, *, beta=None, want_hT=True, o=None, hT=None, saved_states=None, workspace=None,
-                     layout=HGRN2_LAYOUT_BHND):
+                     layout=HGRN2_LAYOUT_BHND, domain_flag=None):
     """hgrn2_fwd (or hgrn2_fwd_gated when beta is given) that also keeps the per-chunk states for
     hgrn2_bwd_saved.  Returns o, hT, saved_states (a uint8 device buffer)."""
-    shape = make_shape(q, v, f, 0, layout)
+    shape = _flagged(make_shape(q, v, f, 0, layout), domain_flag)
     if o is None:
         o = torch.empty_like(v)
     if hT is None and want_hT:
@@ -259,10 +269,10 @@ def hgrn2_fwd_saving(q, f, v, h0=None, *, beta=None, want_hT=True, o=None, hT=No
 
 
 def hgrn2_bwd_saved(q, f, v, saved_states, grad_o, grad_hT=None, *, beta=None, want_grad_h0=False, workspace=None,
-                    grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND):
+                    grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND, domain_flag=None):
     """hgrn2_bwd (hgrn2_bwd_gated when beta is given) from the states hgrn2_fwd_saving kept.  Returns
     grad_q, grad_f, grad_v, grad_h0 and, with beta, grad_beta as a fifth value."""
-    shape = make_shape(q, v, f, 0, layout)
+    shape = _flagged(make_shape(q, v, f, 0, layout), domain_flag)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_f = torch.empty_like(q) if grad_f is None else grad_f
     grad_v = torch.empty_like(v) if grad_v is None else grad_v
@@ -283,10 +293,10 @@ def hgrn2_noalloc_workspace_limit() -> int:
 
 
 def hgrn2_bwd_noalloc(q, f, v, grad_o, h0, grad_hT, grad_q, grad_f, grad_v, grad_h0=None, *, chunk=0,
-                      layout=HGRN2_LAYOUT_BHND):
+                      layout=HGRN2_LAYOUT_BHND, domain_flag=None):
     """hgrn2_bwd on the library's built-in scratch array: every output is the caller's, nothing is
     allocated here or in the library."""
-    shape = make_shape(q, v, f, chunk, layout)
+    shape = _flagged(make_shape(q, v, f, chunk, layout), domain_flag)
     rc = lib().hgrn2_bwd_noalloc(ctypes.byref(shape), _ptr(q), _ptr(f), _ptr(v), _ptr(h0), _ptr(grad_o),
                                  _ptr(grad_hT), _ptr(grad_q), _ptr(grad_f), _ptr(grad_v), _ptr(grad_h0), _stream())
     if rc != 0:
@@ -299,10 +309,10 @@ def hgrn2_bwd_gated_workspace_bytes(shape: hgrn2_shape) -> int:
 
 
 def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, workspace=None,
-                    layout=HGRN2_LAYOUT_BHND, chunk=0):
+                    layout=HGRN2_LAYOUT_BHND, chunk=0, domain_flag=None):
     """hgrn2_fwd with the gate f = beta + (1 - beta) sigmoid(z) formed inside the kernels.
     z: [B,H,N,dk]; beta: fp32 [H,dk]."""
-    shape = make_shape(q, v, z, chunk, layout)
+    shape = _flagged(make_shape(q, v, z, chunk, layout), domain_flag)
     assert beta.dtype == torch.float32 and tuple(beta.shape) == (shape.H, shape.dk)
     if o is None:
         o = torch.empty_like(v)
@@ -318,9 +328,9 @@ def hgrn2_fwd_gated(q, z, beta, v, h0=None, *, want_hT=True, o=None, hT=None, wo
 
 def hgrn2_bwd_gated(q, z, beta, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, workspace=None,
                     grad_q=None, grad_z=None, grad_beta=None, grad_v=None, grad_h0=None,
-                    layout=HGRN2_LAYOUT_BHND, chunk=0):
+                    layout=HGRN2_LAYOUT_BHND, chunk=0, domain_flag=None):
     """grad_q, grad_z, grad_beta, grad_v, grad_h0 of L = sum(o*grad_o) + sum(hT*grad_hT)."""
-    shape = make_shape(q, v, z, chunk, layout)
+    shape = _flagged(make_shape(q, v, z, chunk, layout), domain_flag)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_z = torch.empty_like(q) if grad_z is None else grad_z
     grad_v = torch.empty_like(v) if grad_v is None else grad_v
@@ -351,12 +361,12 @@ def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
 
 
 def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o=None, hT=None, workspace=None,
-                     chunk=0):
+                     chunk=0, domain_flag=None):
     """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
     int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv].  With beta [H,dk] fp32, f holds the
     gates' pre-activations (Eq. 2)."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
-    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk)
+    shape = _flagged(make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk), domain_flag)
     if o is None:
         o = torch.empty_like(v)
     if hT is None and want_hT:
@@ -370,11 +380,11 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o
 
 
 def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta=None, want_grad_h0=False,
-                     workspace=None, grad_q=None, grad_f=None, grad_v=None, chunk=0):
+                     workspace=None, grad_q=None, grad_f=None, grad_v=None, chunk=0, domain_flag=None):
     """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis; with beta also
     grad_beta (returned as a fifth value), and grad_f is then the gradient of the pre-activations."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
-    shape = make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk)
+    shape = _flagged(make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk), domain_flag)
     gq = torch.empty_like(q) if grad_q is None else grad_q
     gf = torch.empty_like(q) if grad_f is None else grad_f
     gv = torch.empty_like(v) if grad_v is None else grad_v

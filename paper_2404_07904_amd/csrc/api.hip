@@ -42,6 +42,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     d->gate_bf16 = s->gate_dtype == HGRN2_BF16;
     d->H = s->H > 0 ? s->H : 1;
     d->beta = nullptr;
+    d->domain_flag = s->gate_domain_flag;
     const long long H = s->H, N = s->N, dk = s->dk, dv = s->dv;
     d->lay.H = d->H;
     if (s->layout == HGRN2_LAYOUT_BNHD) {

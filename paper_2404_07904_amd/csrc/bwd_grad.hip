@@ -80,6 +80,7 @@ struct BwdGradParams {
     int R, rc, s_sub, seg_tail;
     int light;
     int bnd[kMaxLightRuns + 1];
+    int* flag;               // null, or set to 1 when a gate product falls below the floor of the reciprocals
 };
 
 
@@ -281,6 +282,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
     ChunkAt cur;
     bool rows_loaded = false;
+    float below_floor = 1.0f;             // smallest product a reciprocal was taken of (reported once, at the end)
     if constexpr (FUSED) {
         const int n_light = p.light ? p.NC - 1 - f_last : 0;
         if (n_light > 0) {
@@ -424,7 +426,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             const f32x2 m2 = *reinterpret_cast<const f32x2*>(r2 + 2 * lane);
             const f32x2 m3 = *reinterpret_cast<const f32x2*>(r3 + 2 * lane);
             const float mid0 = m1.x * m2.x * m3.x, mid1 = m1.y * m2.y * m3.y;
-            const float R0 = fast_rcp(mid0 * t0 + kTinyProduct), R1 = fast_rcp(mid1 * t1 + kTinyProduct);
+            const float R0 = fast_rcp(fmaxf(mid0 * t0, kTinyProduct)), R1 = fast_rcp(fmaxf(mid1 * t1, kTinyProduct));
+            below_floor = fminf(below_floor, fminf(mid0 * t0, mid1 * t1));
             sa0 = after ? mid0 : R0; sa1 = after ? mid1 : R1;
             sz0 = after ? R0 : mid0; sz1 = after ? R1 : mid1;
 #pragma unroll
@@ -730,6 +733,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     cur = nxt;
     if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
+    if (p.flag && below_floor < kTinyProduct) *p.flag = 1;
     if constexpr (FUSED) {
         // run 0 ends at the start of the sequence: dS_0 = G_m E of its first chunk is grad_h0
         if (f_run == 0 && p.dh0 && has_d) {
@@ -788,6 +792,7 @@ hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const
     p.dhT = nullptr; p.dh0 = nullptr; p.bound0 = nullptr; p.run_state = nullptr; p.R = 1; p.rc = d.NC; p.s_sub = 1; p.seg_tail = 0;
     p.light = 0;
     for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = 0;
+    p.flag = d.domain_flag;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
     if (d.dk == 128 && d.dv == 128) return launch_one<__bf16, 128, 128>(d, p, stream);
     if (d.dk == 64 && d.dv == 64) return launch_one<__bf16, 64, 64>(d, p, stream);
@@ -875,6 +880,7 @@ hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void
     p.R = pl.R; p.rc = pl.rc; p.s_sub = pl.s_sub; p.seg_tail = pl.seg_tail;
     p.light = pl.light;
     for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = pl.bnd[i];
+    p.flag = d.domain_flag;
     if (!d.io_bf16) return launch_fused_one<float, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 128) return launch_fused_one<__bf16, 128, 128>(d, p, stream);
     if (d.dk == 64 && d.dv == 64) return launch_fused_one<__bf16, 64, 64>(d, p, stream);

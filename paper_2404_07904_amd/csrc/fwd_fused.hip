@@ -55,6 +55,7 @@ struct FwdFusedParams {
     int H;
     TokenLayout lay;     // used when dense == 0
     int dense;           // sequence tensors are [B][H][N][d]: token strides are the compile-time dk, dv
+    int* flag;           // null, or set to 1 when a gate product falls below the floor of the reciprocals
 };
 
 
@@ -210,6 +211,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // the supported gate range.
     // First half (before the totals are exchanged): q a, k z, t.
     float qa0[RW], qa1[RW], kz0[RW], kz1[RW], bt0, bt1;
+    float below_floor = 1.0f;            // smallest product a reciprocal was taken of (reported once, at the end)
     auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
         f32x2 rf[RW];
         convert_rows<RW>(rf, rf_raw, c * C + RW * w, N, true, GATE_BF16, 1.0f);
@@ -244,8 +246,9 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         const f32x2 m2 = *reinterpret_cast<const f32x2*>(r2 + 2 * lane);
         const f32x2 m3 = *reinterpret_cast<const f32x2*>(r3 + 2 * lane);
         const float mid0 = m1.x * m2.x * m3.x, mid1 = m1.y * m2.y * m3.y;
-        const float R0 = fast_rcp(mid0 * bt0 + kTinyProduct);
-        const float R1 = fast_rcp(mid1 * bt1 + kTinyProduct);
+        const float R0 = fast_rcp(fmaxf(mid0 * bt0, kTinyProduct));
+        const float R1 = fast_rcp(fmaxf(mid1 * bt1, kTinyProduct));
+        below_floor = fminf(below_floor, fminf(mid0 * bt0, mid1 * bt1));
         const float sa0 = after ? mid0 : R0, sa1 = after ? mid1 : R1;       // multiplies q a
         const float sz0 = after ? R0 : mid0, sz1 = after ? R1 : mid1;       // multiplies k z
         // Q~: row-major, channel pair (2l, 2l+1) at column position sigma(2l) (bits 2 and 3 swapped);
@@ -491,6 +494,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         store_o(n_end - 1);
     }
 
+    if (p.flag && below_floor < kTinyProduct) *p.flag = 1;
     if (p.hT) {
         // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1)
         float* s1 = p.hT + (size_t)bh * DK * DV;
@@ -535,6 +539,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     FwdFusedParams p;
     p.q = q; p.f = f; p.v = v; p.h0 = h0; p.o = o; p.hT = hT; p.save = save_states;
     p.N = d.N; p.NC = d.NC; p.BH = d.BH; p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
+    p.flag = d.domain_flag;
     // Two workgroups per sequence (each half of the dv columns) keep twice as many compute units
     // busy, but a compute unit holds one workgroup: beyond 128 sequences the halves would no longer
     // all run at once (the rest waits for a free unit: 137 us instead of 84 us for 144 sequences of 2048 tokens), so

@@ -28,6 +28,7 @@ struct FwdOutParams {
     int H;
     TokenLayout lay;     // used when dense == 0
     int dense;           // sequence tensors are [B][H][N][d]
+    int* flag;           // null, or set to 1 when a gate product falls below the floor of the reciprocals
 };
 
 template <typename T, int DK, int DV> struct FwdOutLds {
@@ -115,6 +116,10 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
     if (k_act) {
         const BlockDecay d0 = block_decay(tot, DK, w, 2 * lane);
         const BlockDecay d1 = block_decay(tot, DK, w, 2 * lane + 1);
+        {   // the smallest product this thread takes a reciprocal of: its first row after the reference, its last before
+            const float s0 = d0.mid * (w >= 2 ? a0[RW - 1] : z0[0]), s1 = d1.mid * (w >= 2 ? a1[RW - 1] : z1[0]);
+            if (p.flag && fminf(s0, s1) < kTinyProduct) *p.flag = 1;
+        }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
             const int row = RW * w + i;
@@ -252,7 +257,7 @@ hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const 
     FwdOutParams p;
     p.q = q; p.f = f; p.v = v; p.ws = ws_state; p.o = o;
     p.BH = d.BH; p.N = d.N; p.NC = d.NC; p.gate_bf16 = d.gate_bf16 ? 1 : 0;
-    p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0;
+    p.beta = d.beta; p.H = d.H; p.lay = d.lay; p.dense = d.dense() ? 1 : 0; p.flag = d.domain_flag;
     return d.io_bf16 ? launch_dims<__bf16>(d, p, stream) : launch_dims<float>(d, p, stream);
 }
 

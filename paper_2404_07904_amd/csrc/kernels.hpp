@@ -46,6 +46,9 @@ struct SeqDims {
     // pre-activation z and f = beta + (1 - beta) sigmoid(z); beta is [H][dk] fp32 on the device.
     int H = 1;
     const float* beta = nullptr;
+    // Set to 1 (device int, may be null) by a kernel that meets a gate product below the floor of
+    // its reciprocals: its results are then not exact.  Never cleared by the library.
+    int* domain_flag = nullptr;
     TokenLayout lay;
     // [B][H][N][d]: the kernels then use compile-time token strides
     // variable-length batch: N and NC then describe the packed token axis (lay.vl is set once the

@@ -80,7 +80,7 @@ def test_training_pair_empty_and_errors():
     with pytest.raises(binding.Hgrn2Error) as err:
         binding.hgrn2_fwd_saving(q, q, q, saved_states=small)
     assert err.value.status == 4
-    q32 = torch.zeros((1, 1, 64, 64), dtype=torch.float32, device="cuda")
+    q32 = torch.zeros((1, 1, 64, 128), dtype=torch.float32, device="cuda")      # fp32 storage: heads of 64 x 64 only
     with pytest.raises(binding.Hgrn2Error) as err:
         binding.hgrn2_fwd_saving(q32, q32, q32)
     assert err.value.status == 3

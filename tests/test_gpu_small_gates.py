@@ -172,3 +172,34 @@ def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk):
     check("dh0", host(res[3]), rh0, tol)
     if gated:
         check("dbeta", host(res[4]), rb, tol)
+
+
+@pytest.mark.parametrize("dk,dv,B,H", [(64, 64, 2, 3), (128, 128, 8, 8), (128, 64, 1, 2)])
+def test_gate_domain_flag(dk, dv, B, H):
+    """shape->gate_domain_flag: set by the forward and by the backward kernels exactly when a product of
+    up to 32 gates falls below the floor of their reciprocals (the probe says the same), left alone by
+    ordinary gates and by the small-gate mode on gates inside ITS domain; never cleared by the library.
+    Covers the read-out kernel (64 x 64), the single-pass forward (64 sequences of 128 x 128) and the
+    reverse walk of the backward pass."""
+    N = 200
+    print("\n[domain flag] dk=%d dv=%d B=%d H=%d" % (dk, dv, B, H), flush=True)
+    w = small_gate_workload(9100 + dk, B, H, N, dk, dv, "loguniform")
+    q, f, v, dO = (dev(x, "bf16") for x in (w.q, w.f, w.v, w.dO))
+    ok = synth.make_sequence(9101, B, H, N, dk, dv, io_dtype="bf16", lb=0.0, with_dO=True)
+    fo = dev(ok.f, "bf16")
+    assert float(binding.hgrn2_min_gate_product(f).item()) < LIMIT < float(binding.hgrn2_min_gate_product(fo).item())
+    flag = lambda: torch.zeros(1, dtype=torch.int32, device="cuda")
+    a, b, c, d_, e, g = flag(), flag(), flag(), flag(), flag(), flag()
+    binding.hgrn2_fwd(q, f, v, domain_flag=a)                     # small gates, ordinary mode: outside the domain
+    binding.hgrn2_bwd(q, f, v, dO, domain_flag=b)
+    binding.hgrn2_fwd(q, fo, v, domain_flag=c)                    # sigmoid gates: inside
+    binding.hgrn2_bwd(q, fo, v, dO, domain_flag=d_)
+    binding.hgrn2_fwd(q, f, v, chunk=16, domain_flag=e)           # small gates, reference rows every 16 tokens: inside
+    binding.hgrn2_bwd(q, f, v, dO, chunk=16, domain_flag=g)
+    torch.cuda.synchronize()
+    got = [int(t.item()) for t in (a, b, c, d_, e, g)]
+    print("    flags: small gates fwd/bwd %s, ordinary gates %s, small-gate mode %s" % (got[:2], got[2:4], got[4:]), flush=True)
+    assert got == [1, 1, 0, 0, 0, 0]
+    binding.hgrn2_fwd(q, fo, v, domain_flag=a)                    # the library never clears a flag
+    torch.cuda.synchronize()
+    assert int(a.item()) == 1
