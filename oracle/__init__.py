@@ -253,6 +253,71 @@ def hgrn1_bwd_act(zf, zi, zo, beta, dy, h0=None, dhN=None):
 # the smallest product of one channel's gates over a half chunk (tokens [C n, C n + C/2) and
 # [C n + C/2, C n + C) of every sequence; a ragged last piece counts with the tokens it has).
 # ---------------------------------------------------------------------------------------------
+# ---- input side of the HGRU2 token mixer (paper Section 2, Eq. 1, feeding Eq. 2 and Eq. 3) --------
+# Three affine maps of the layer input x_t and their activations,
+#     g_t = sigmoid(U x_t + b_u),   i_t = SiLU(V x_t + b_v),   o_t = sigmoid(W x_t + b_w),
+# written out with numpy matmuls in fp64.  The forget gate's pre-activation z = U x + b_u is
+# returned instead of g, because the lower bound of Eq. 2 is applied to g inside `gate`.
+# Weights are [d_out, d_in] (row = output channel), x is [B, N, d].
+def hgru2_proj(x, U, V, W, bu, bv, bw):
+    x, U, V, W = (np.asarray(a, dtype=np.float64) for a in (x, U, V, W))
+    bu, bv, bw = (np.asarray(a, dtype=np.float64) for a in (bu, bv, bw))
+    z = x @ U.T + bu
+    av = x @ V.T + bv
+    aw = x @ W.T + bw
+    return z, av * _sigmoid(av), _sigmoid(aw)
+
+
+def hgru2_proj_bwd(x, U, V, W, bu, bv, bw, dz, di, do):
+    """Reverse mode of hgru2_proj for L = sum(z dz) + sum(i di) + sum(o do): dx, dU, dV, dW, dbu, dbv, dbw."""
+    x, U, V, W = (np.asarray(a, dtype=np.float64) for a in (x, U, V, W))
+    bv, bw = np.asarray(bv, dtype=np.float64), np.asarray(bw, dtype=np.float64)
+    dz, di, do = (np.asarray(a, dtype=np.float64) for a in (dz, di, do))
+    av = x @ V.T + bv
+    sv = _sigmoid(av)
+    o = _sigmoid(x @ W.T + bw)
+    dav = di * sv * (1.0 + av * (1.0 - sv))          # d SiLU(a) / da
+    daw = do * o * (1.0 - o)                          # d sigmoid(a) / da
+    d = x.shape[-1]
+    x2 = x.reshape(-1, d)
+    flat = lambda a: a.reshape(-1, a.shape[-1])
+    dx = dz @ U + dav @ V + daw @ W
+    return (dx, flat(dz).T @ x2, flat(dav).T @ x2, flat(daw).T @ x2,
+            flat(dz).sum(axis=0), flat(dav).sum(axis=0), flat(daw).sum(axis=0))
+
+
+def _split_heads(a, H):          # [B, N, H * dh] -> [B, H, N, dh]
+    B, N, d = a.shape
+    return np.ascontiguousarray(a.reshape(B, N, H, d // H).transpose(0, 2, 1, 3))
+
+
+def _merge_heads(a):             # [B, H, N, dh] -> [B, N, H * dh]
+    B, H, N, dh = a.shape
+    return np.ascontiguousarray(a.transpose(0, 2, 1, 3).reshape(B, N, H * dh))
+
+
+def hgru2_layer_fwd(x, U, V, W, bu, bv, bw, beta, H, h0=None):
+    """Eq. 1 -> Eq. 2 -> Eq. 3 with H heads: y [B, N, d] and the final states [B, H, dh, dh].
+    beta: the layer's lower bounds, [d] (viewed as [H][dh]).  Table 4's naming: q = o, v = i."""
+    z, i, o = hgru2_proj(x, U, V, W, bu, bv, bw)
+    d = z.shape[-1]
+    y, hT = fwd_gated(_split_heads(o, H), _split_heads(z, H), np.asarray(beta, dtype=np.float64).reshape(H, d // H),
+                      _split_heads(i, H), h0)
+    return _merge_heads(y), hT
+
+
+def hgru2_layer_bwd(x, U, V, W, bu, bv, bw, beta, H, dy, h0=None, dhT=None):
+    """Reverse mode of hgru2_layer_fwd for L = sum(y dy) + sum(hT dhT):
+    dx, dU, dV, dW, dbu, dbv, dbw, dbeta [d], dh0."""
+    z, i, o = hgru2_proj(x, U, V, W, bu, bv, bw)
+    d = z.shape[-1]
+    b2 = np.asarray(beta, dtype=np.float64).reshape(H, d // H)
+    dq, dz, dbeta, dv, dh0 = bwd_gated(_split_heads(o, H), _split_heads(z, H), b2, _split_heads(i, H),
+                                       _split_heads(np.asarray(dy, dtype=np.float64), H), h0, dhT)
+    g = hgru2_proj_bwd(x, U, V, W, bu, bv, bw, _merge_heads(dz), _merge_heads(dv), _merge_heads(dq))
+    return g + (dbeta.reshape(-1), dh0)
+
+
 def min_gate_product(f, chunk=64):
     """f: [B,H,N,dk] -> float (1.0 for an empty input)."""
     f = np.asarray(f, dtype=np.float64)

@@ -570,3 +570,109 @@ def test_min_gate_product_constant_gate_and_brute_force():
                         p *= f[b, h, t, a]
                     best = min(best, p)
     assert abs(oracle.min_gate_product(f) - best) <= 1e-15 * best
+
+
+# ------------------------------------------------------------------ input side of the token mixer (Eq. 1)
+def test_hgru2_proj_special_weights_and_written_out_sums():
+    """Identity weights and zero biases leave the three activations of x itself (SciPy's logistic
+    function and the HGRN1 oracle's activations as outside references); general weights against the
+    affine maps written out as explicit sums; a weight that only reads channel 0 against a scalar
+    closed form."""
+    from scipy.special import expit
+    rng = np.random.default_rng(51)
+    B, N, d = 2, 5, 6
+    x = rng.standard_normal((B, N, d))
+    I, zero = np.eye(d), np.zeros(d)
+    z, i, o = oracle.hgru2_proj(x, I, I, I, zero, zero, zero)
+    assert np.max(np.abs(z - x)) == 0.0
+    assert np.max(np.abs(i - x * expit(x))) <= 1e-15 and np.max(np.abs(o - expit(x))) <= 1e-15
+    f1, i1, o1 = oracle.hgrn1_activations(x, x, x, np.zeros(d))
+    assert np.max(np.abs(i1 - i)) <= 1e-15 and np.max(np.abs(o1 - o)) <= 1e-15 and np.max(np.abs(f1 - expit(z))) <= 1e-15
+    U, V, W = (rng.standard_normal((d, d)) for _ in range(3))
+    bu, bv, bw = (rng.standard_normal(d) for _ in range(3))
+    z, i, o = oracle.hgru2_proj(x, U, V, W, bu, bv, bw)
+    for b in range(B):
+        for t in range(N):
+            for c in range(d):
+                au = bu[c] + sum(U[c, k] * x[b, t, k] for k in range(d))
+                av = bv[c] + sum(V[c, k] * x[b, t, k] for k in range(d))
+                aw = bw[c] + sum(W[c, k] * x[b, t, k] for k in range(d))
+                assert abs(z[b, t, c] - au) <= 1e-13
+                assert abs(i[b, t, c] - av / (1.0 + np.exp(-av))) <= 1e-13
+                assert abs(o[b, t, c] - 1.0 / (1.0 + np.exp(-aw))) <= 1e-13
+    # transposed weights would pass the identity case: a weight with a single non-zero entry tells them apart
+    E = np.zeros((d, d)); E[2, 0] = 3.0                 # output channel 2 reads input channel 0
+    z, _, _ = oracle.hgru2_proj(x, E, I, I, zero, zero, zero)
+    assert np.max(np.abs(z[..., 2] - 3.0 * x[..., 0])) <= 1e-15 and np.max(np.abs(z[..., 0])) == 0.0
+
+
+def _fd(fun, args, name, eps=1e-6):
+    x = args[name]
+    num = np.zeros_like(x)
+    for idx in np.ndindex(*x.shape):
+        ap, am = dict(args), dict(args)
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += eps; xm[idx] -= eps
+        ap[name], am[name] = xp, xm
+        num[idx] = (fun(ap) - fun(am)) / (2 * eps)
+    return num
+
+
+def test_hgru2_proj_bwd_finite_differences():
+    rng = np.random.default_rng(52)
+    B, N, d = 2, 3, 4
+    args = {"x": rng.standard_normal((B, N, d)), "U": rng.standard_normal((d, d)), "V": rng.standard_normal((d, d)),
+            "W": rng.standard_normal((d, d)), "bu": rng.standard_normal(d), "bv": rng.standard_normal(d),
+            "bw": rng.standard_normal(d)}
+    dz, di, do = (rng.standard_normal((B, N, d)) for _ in range(3))
+
+    def loss(a):
+        z, i, o = oracle.hgru2_proj(a["x"], a["U"], a["V"], a["W"], a["bu"], a["bv"], a["bw"])
+        return float((z * dz).sum() + (i * di).sum() + (o * do).sum())
+    grads = oracle.hgru2_proj_bwd(args["x"], args["U"], args["V"], args["W"], args["bu"], args["bv"], args["bw"], dz, di, do)
+    for name, g in zip(("x", "U", "V", "W", "bu", "bv", "bw"), grads):
+        num = _fd(loss, args, name)
+        assert num.shape == g.shape, name
+        assert np.max(np.abs(num - g)) <= 3e-7 * max(1.0, np.max(np.abs(g))), name
+    # planted mistakes that the differences must catch: the SiLU derivative without its second term, a transposed weight gradient
+    num_v = _fd(loss, args, "V")
+    av = args["x"] @ args["V"].T + args["bv"]
+    s = 1.0 / (1.0 + np.exp(-av))
+    wrong = (di * s).reshape(-1, d).T @ args["x"].reshape(-1, d)
+    assert np.max(np.abs(num_v - wrong)) > 1e-2 * np.max(np.abs(num_v))
+    assert np.max(np.abs(num_v - grads[2].T)) > 1e-2 * np.max(np.abs(num_v))
+
+
+def test_hgru2_layer_reduces_to_the_gated_recurrence_and_finite_differences():
+    """With one head, identity weights and zero biases the layer IS fwd_gated on (sigmoid(x), x,
+    SiLU(x)); with two heads, every head sees its own slice of the channels; reverse mode against
+    finite differences through Eq. 1 -> Eq. 2 -> Eq. 3 for every parameter."""
+    from scipy.special import expit
+    rng = np.random.default_rng(53)
+    B, N, d = 1, 4, 4
+    x = rng.standard_normal((B, N, d))
+    I, zero = np.eye(d), np.zeros(d)
+    beta = rng.uniform(0.0, 0.8, d)
+    y, hT = oracle.hgru2_layer_fwd(x, I, I, I, zero, zero, zero, beta, 1)
+    y1, hT1 = oracle.fwd_gated(expit(x)[:, None], x[:, None], beta[None, :], (x * expit(x))[:, None])
+    assert np.max(np.abs(y - y1[:, 0])) <= 1e-14 and np.max(np.abs(hT - hT1)) <= 1e-14
+    H = 2
+    y2, hT2 = oracle.hgru2_layer_fwd(x, I, I, I, zero, zero, zero, beta, H)
+    for h in range(H):
+        sl = slice(h * d // H, (h + 1) * d // H)
+        yh, hTh = oracle.fwd_gated(expit(x[..., sl])[:, None], x[..., sl][:, None], beta[None, sl], (x * expit(x))[..., sl][:, None])
+        assert np.max(np.abs(y2[..., sl] - yh[:, 0])) <= 1e-14 and np.max(np.abs(hT2[:, h] - hTh[:, 0])) <= 1e-14
+    args = {"x": x, "U": 0.5 * rng.standard_normal((d, d)), "V": rng.standard_normal((d, d)), "W": rng.standard_normal((d, d)),
+            "bu": rng.standard_normal(d), "bv": rng.standard_normal(d), "bw": rng.standard_normal(d), "beta": beta,
+            "h0": 0.1 * rng.standard_normal((B, H, d // H, d // H))}
+    dy = rng.standard_normal((B, N, d))
+    dhT = rng.standard_normal((B, H, d // H, d // H))
+
+    def loss(a):
+        yy, hh = oracle.hgru2_layer_fwd(a["x"], a["U"], a["V"], a["W"], a["bu"], a["bv"], a["bw"], a["beta"], H, a["h0"])
+        return float((yy * dy).sum() + (hh * dhT).sum())
+    grads = oracle.hgru2_layer_bwd(args["x"], args["U"], args["V"], args["W"], args["bu"], args["bv"], args["bw"], beta, H, dy,
+                                   args["h0"], dhT)
+    for name, g in zip(("x", "U", "V", "W", "bu", "bv", "bw", "beta", "h0"), grads):
+        num = _fd(loss, args, name)
+        assert np.max(np.abs(num - g)) <= 5e-7 * max(1.0, np.max(np.abs(g))), name
