@@ -351,6 +351,39 @@ int hgrn2_bwd_noalloc(const hgrn2_shape* shape, const void* q, const void* f, co
                       void* grad_f, void* grad_v, float* grad_h0, void* hip_stream);
 
 /*
+ * Input side of the HGRU2 token mixer (Section 2, Eq. 1, feeding Eq. 2 and Eq. 3): the three
+ * projections of the layer input x_t and their activations, as one bf16 matrix product with bias
+ * and activation applied to the fp32 accumulators,
+ *     z = U x + b_u              pre-activation of the forget gate (Eq. 2 is formed inside
+ *                                hgrn2_fwd_gated and its relatives, which take z and beta),
+ *     v = SiLU(V x + b_v)        the paper's input vector i,
+ *     q = sigmoid(W x + b_w)     the paper's output gate o.
+ * The outputs are token-major [M][d] = [B][N][H][d/H], the layout HGRN2_LAYOUT_BNHD names, so
+ * projection -> recurrence needs no transposition and neither the gate nor the pre-activation of q
+ * reaches memory.  (What follows the recurrence in the block -- normalisation, output projection,
+ * the GLU channel mixer -- is defined by the paper only through a figure and is not part of this
+ * library.)
+ *   M = B * N tokens; d the model width, a multiple of 256 (else HGRN2_ERR_UNSUPPORTED)
+ *   x        in   device bf16 [M][d]
+ *   w3       in   device bf16 [3 d][d]: the rows of U, then of V, then of W (row = output channel)
+ *   b3       in   device fp32 [3 d]: b_u, b_v, b_w
+ *   z, v, q  out  device bf16 [M][d]
+ *   av       out  device bf16 [M][d] or NULL: V x + b_v, which the reverse mode needs (SiLU is not
+ *                 invertible)
+ * hgru2_proj_bwd: reverse mode for L = sum(z grad_z) + sum(v grad_v) + sum(q grad_q):
+ *   grad_x   out  device bf16 [M][d]
+ *   grad_w3  out  device fp32 [3 d][d];   grad_b3  out  device fp32 [3 d] (summed in a fixed order)
+ *   workspace     hgru2_proj_bwd_workspace_bytes(M, d) bytes, 256-byte aligned
+ * Status codes and stream semantics as everywhere in this header.
+ */
+size_t hgru2_proj_bwd_workspace_bytes(int32_t M, int32_t d);
+int hgru2_proj_fwd(int32_t M, int32_t d, const void* x, const void* w3, const float* b3, void* z, void* v,
+                   void* q, void* av, void* hip_stream);
+int hgru2_proj_bwd(int32_t M, int32_t d, const void* x, const void* w3, const void* q, const void* av,
+                   const void* grad_z, const void* grad_v, const void* grad_q, void* grad_x, float* grad_w3,
+                   float* grad_b3, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Measurement probes (no part of the method): what this GPU sustains for a plain copy and for a
  * loop of bf16 matrix instructions, the practical ceilings next to the published peaks of
  * mi355x_peaks.h that roofline fractions are quoted against.

@@ -23,7 +23,8 @@ EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd"
            "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
            "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc",
            "hgrn2_saved_states_bytes", "hgrn2_bwd_saved_workspace_bytes", "hgrn2_fwd_saving", "hgrn2_bwd_saved",
-           "hgrn2_probe_copy", "hgrn2_probe_mfma_out_floats", "hgrn2_probe_mfma"]
+           "hgrn2_probe_copy", "hgrn2_probe_mfma_out_floats", "hgrn2_probe_mfma",
+           "hgru2_proj_bwd_workspace_bytes", "hgru2_proj_fwd", "hgru2_proj_bwd"]
 SWEEP_STATE_FWD, SWEEP_STATE_BWD, SWEEP_STATE_GRAD = 0, 1, 2
 
 
@@ -103,6 +104,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_readout.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         L.hgrn2_bwd_chunk_grads.restype = ctypes.c_int
         L.hgrn2_bwd_chunk_grads.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hgru2_proj_bwd_workspace_bytes.restype = sz
+        L.hgru2_proj_bwd_workspace_bytes.argtypes = [i32, i32]
+        L.hgru2_proj_fwd.restype = ctypes.c_int
+        L.hgru2_proj_fwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hgru2_proj_bwd.restype = ctypes.c_int
+        L.hgru2_proj_bwd.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_probe_copy.restype = ctypes.c_int
         L.hgrn2_probe_copy.argtypes = [vp, vp, sz, vp]
         L.hgrn2_probe_mfma_out_floats.restype = sz
@@ -220,6 +227,39 @@ def hgrn2_bwd(q, f, v, grad_o, h0=None, grad_hT=None, *, want_grad_h0=False, chu
     if rc != 0:
         raise Hgrn2Error(rc, "hgrn2_bwd")
     return grad_q, grad_f, grad_v, grad_h0
+
+
+def hgru2_proj_fwd(x, w3, b3, *, keep_av=True, z=None, v=None, q=None, av=None):
+    """z, v, q (and av) of the three input projections of the HGRU2 token mixer (Eq. 1).  x: bf16
+    [..., d] (any leading shape, contiguous); w3: bf16 [3d, d] (rows of U, V, W); b3: fp32 [3d]."""
+    d = x.shape[-1]
+    M = x.numel() // d if d else 0
+    assert tuple(w3.shape) == (3 * d, d) and w3.dtype == torch.bfloat16 and x.dtype == torch.bfloat16
+    assert b3.dtype == torch.float32 and b3.numel() == 3 * d
+    z = torch.empty_like(x) if z is None else z
+    v = torch.empty_like(x) if v is None else v
+    q = torch.empty_like(x) if q is None else q
+    if av is None and keep_av:
+        av = torch.empty_like(x)
+    rc = lib().hgru2_proj_fwd(M, d, _ptr(x), _ptr(w3), _ptr(b3), _ptr(z), _ptr(v), _ptr(q), _ptr(av), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgru2_proj_fwd")
+    return z, v, q, av
+
+
+def hgru2_proj_bwd(x, w3, q, av, grad_z, grad_v, grad_q, *, workspace=None, grad_x=None, grad_w3=None, grad_b3=None):
+    """grad_x (bf16), grad_w3 (fp32 [3d, d]), grad_b3 (fp32 [3d]) of the three projections."""
+    d = x.shape[-1]
+    M = x.numel() // d if d else 0
+    grad_x = torch.empty_like(x) if grad_x is None else grad_x
+    grad_w3 = torch.empty((3 * d, d), dtype=torch.float32, device=x.device) if grad_w3 is None else grad_w3
+    grad_b3 = torch.empty((3 * d,), dtype=torch.float32, device=x.device) if grad_b3 is None else grad_b3
+    ws = _workspace(int(lib().hgru2_proj_bwd_workspace_bytes(M, d)), x.device, workspace)
+    rc = lib().hgru2_proj_bwd(M, d, _ptr(x), _ptr(w3), _ptr(q), _ptr(av), _ptr(grad_z), _ptr(grad_v), _ptr(grad_q),
+                              _ptr(grad_x), _ptr(grad_w3), _ptr(grad_b3), _ptr(ws), ws.numel(), _stream())
+    if rc != 0:
+        raise Hgrn2Error(rc, "hgru2_proj_bwd")
+    return grad_x, grad_w3, grad_b3
 
 
 def hgrn2_probe_copy(dst, src):

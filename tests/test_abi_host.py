@@ -18,7 +18,7 @@ FAKE_WS = ctypes.c_void_p(0x100000)      # 256-byte aligned
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "hgrn2.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hgrn[12]_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(hgr[nu][12]_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_loads_and_exports_every_declared_symbol():
