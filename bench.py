@@ -74,6 +74,7 @@ def parse():
     ap.add_argument("--no-handoff", action="store_true", help="skip the prefill -> decode hand-off run")
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--no-long", action="store_true", help="skip the long-sequence shape (B=2, N=16384)")
+    ap.add_argument("--no-layer", action="store_true", help="skip the layer run (projections + recurrence)")
     ap.add_argument("--no-small-gates", action="store_true", help="skip the small-gate modes (chunk = 32, 16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
@@ -295,6 +296,60 @@ def main():
         del pair, a, b
     result["layers"] = layers
 
+    # ---- the layer around the recurrence (Eq. 1 -> Eq. 2 -> Eq. 3): the three input projections of the
+    # token mixer as one bf16 MFMA product with bias + activation, the recurrence on its token-major
+    # outputs with the gate formed in the kernels, and the whole reverse mode ----
+    if not args.no_layer:
+        dm = H * D
+        gen = torch.Generator(device=dev).manual_seed(synth.BASE_SEED + 12)
+        xs = [torch.randn((B, N, dm), generator=gen, device=dev).to(torch.bfloat16) for _ in range(2)]
+        w3 = (torch.randn((3 * dm, dm), generator=gen, device=dev) / dm ** 0.5).to(torch.bfloat16)
+        b3 = 0.5 * torch.randn((3 * dm,), generator=gen, device=dev)
+        betal = torch.full((H, D), float(synth.layer_lower_bound(args.layer)), dtype=torch.float32, device=dev)
+        dys = [torch.randn((B, N, H, D), generator=gen, device=dev).to(torch.bfloat16) for _ in range(2)]
+        zl, vl2, ql, avl = (torch.empty((B, N, H, D), dtype=torch.bfloat16, device=dev) for _ in range(4))
+        yl = torch.empty_like(zl)
+        glq, glz, glv = (torch.empty_like(zl) for _ in range(3))
+        glx = torch.empty_like(xs[0])
+        glw = torch.empty((3 * dm, dm), dtype=torch.float32, device=dev)
+        glb = torch.empty((3 * dm,), dtype=torch.float32, device=dev)
+        shl = binding.make_shape(ql, vl2, zl, 0, binding.HGRN2_LAYOUT_BNHD)
+        wsl = torch.empty(max(binding.hgrn2_fwd_workspace_bytes(shl), binding.hgrn2_bwd_saved_workspace_bytes(shl, True)),
+                          dtype=torch.uint8, device=dev)
+        wsp = torch.empty(int(binding.lib().hgru2_proj_bwd_workspace_bytes(B * N, dm)), dtype=torch.uint8, device=dev)
+        BNHD = binding.HGRN2_LAYOUT_BNHD
+
+        def proj_fwd(i):
+            binding.hgru2_proj_fwd(xs[i % 2], w3, b3, z=zl.view(B, N, dm), v=vl2.view(B, N, dm), q=ql.view(B, N, dm),
+                                   av=avl.view(B, N, dm))
+
+        def proj_bwd(i):
+            binding.hgru2_proj_bwd(xs[i % 2], w3, ql.view(B, N, dm), avl.view(B, N, dm), glz.view(B, N, dm), glv.view(B, N, dm),
+                                   glq.view(B, N, dm), workspace=wsp, grad_x=glx, grad_w3=glw, grad_b3=glb)
+
+        def layer_step(i):
+            proj_fwd(i)
+            binding.hgrn2_fwd_saving(ql, zl, vl2, None, beta=betal, o=yl, hT=hT, saved_states=saved[0], workspace=wsl, layout=BNHD)
+            binding.hgrn2_bwd_saved(ql, zl, vl2, saved[0], dys[i % 2], None, beta=betal, workspace=wsl, grad_q=glq, grad_f=glz,
+                                    grad_v=glv, layout=BNHD)
+            proj_bwd(i)
+
+        for i in range(4):
+            layer_step(i)
+        t_pf, t_pb, t_layer = timed(proj_fwd, reps=20), timed(proj_bwd, reps=10), timed(layer_step, reps=10)
+        fl_f = 2.0 * B * N * dm * 3 * dm
+        result["layer"] = {
+            "workload": "Eq. 1 -> Eq. 2 -> Eq. 3 at B=%d N=%d width %d (H=%d, head %d), bf16: projections (one [%d, %d] x [%d, %d] "
+                        "product, bias + activation fused), recurrence with the gate formed in the kernels, reverse mode of both"
+                        % (B, N, dm, H, D, B * N, dm, dm, 3 * dm),
+            "proj_fwd_us": round(t_pf * 1e6, 1), "proj_bwd_us": round(t_pb * 1e6, 1), "ms_per_step": round(t_layer * 1e3, 4),
+            "tokens_per_s": round(tokens / t_layer, 1),
+            "roofline_proj_fwd": {"bound": "mfma", "achieved": round(fl_f / t_pf / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                                  "unit": "TFLOP/s", "frac": round(fl_f / t_pf / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                  "traffic": MEASURED_TRAFFIC_BYTES.get("hgru2_proj_kernel")},
+            "proj_bwd_TFLOPs": round(2 * fl_f / t_pb / 1e12, 1)}
+        del xs, w3, dys, zl, vl2, ql, avl, yl, glq, glz, glv, glx, glw, wsl, wsp
+
     # ---- the same step with the gate of Eq. 2 formed inside the kernels (z and beta instead of f) ----
     if not args.no_gated:
         rng = np.random.default_rng(synth.BASE_SEED + 7)
@@ -365,10 +420,15 @@ def main():
         ol, gql, gfl, gvl = (torch.empty_like(ql) for _ in range(4))
         hTl = torch.empty((Bl, H, D, D), dtype=torch.float32, device=dev)
 
-        def long_fwd(i):
-            binding.hgrn2_fwd(ql, fl, vl_, None, o=ol, hT=hTl, workspace=wsl)
+        savedl = torch.empty(binding.hgrn2_saved_states_bytes(shl), dtype=torch.uint8, device=dev)
+
+        def long_fwd(i):          # the training pair, as in the headline
+            binding.hgrn2_fwd_saving(ql, fl, vl_, None, o=ol, hT=hTl, saved_states=savedl, workspace=wsl)
 
         def long_bwd(i):
+            binding.hgrn2_bwd_saved(ql, fl, vl_, savedl, dOl, None, workspace=wsl, grad_q=gql, grad_f=gfl, grad_v=gvl)
+
+        def long_bwd_stateless(i):
             binding.hgrn2_bwd(ql, fl, vl_, dOl, None, None, workspace=wsl, grad_q=gql, grad_f=gfl, grad_v=gvl)
 
         for i in range(5):
@@ -380,7 +440,8 @@ def main():
                                    "fwd_ms": round(tf * 1e3, 4), "bwd_ms": round(tb * 1e3, 4),
                                    "ms_per_step": round((tf + tb) * 1e3, 4),
                                    "tokens_per_s": round(Bl * Nl / (tf + tb), 1),
-                                   "algorithmic_GBps": round(io_long / (tf + tb) / 1e9, 1)}
+                                   "algorithmic_GBps": round(io_long / (tf + tb) / 1e9, 1),
+                                   "stateless_bwd_ms": round(timed(long_bwd_stateless, reps=20) * 1e3, 4)}
         # bf16 has three values in [0.99, 1]; the same gates kept in fp32 (4 bytes per gate)
         fl32 = 0.99 + 0.01 * torch.rand((Bl, H, Nl, D), generator=gen, device=dev)
         fl = fl32
@@ -389,7 +450,7 @@ def main():
         tf32, tb32 = timed(long_fwd, reps=20), timed(long_bwd, reps=20)
         result["long_sequence"]["fp32_gates"] = {"fwd_ms": round(tf32 * 1e3, 4), "bwd_ms": round(tb32 * 1e3, 4),
                                                  "tokens_per_s": round(Bl * Nl / (tf32 + tb32), 1)}
-        del ql, vl_, dOl, fl, fl32, wsl, ol, gql, gfl, gvl
+        del ql, vl_, dOl, fl, fl32, wsl, ol, gql, gfl, gvl, savedl
         # the same number of tokens as two documents of unequal length packed along the token axis
         docs = [20000, 12768]
         Tl = sum(docs)
