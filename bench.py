@@ -132,6 +132,15 @@ def main():
         train_fwd(i)
         train_bwd(i)
 
+    # wake the GPU up before anything is timed (its clocks take tens of milliseconds of work to come
+    # up; a few launches of the matrix probe and of the step itself)
+    _, warm_out = binding.hgrn2_probe_mfma(2000)
+    for i in range(20):
+        binding.hgrn2_probe_mfma(2000, warm_out)
+        step(i)
+    torch.cuda.synchronize()
+    del warm_out
+
     if args.calibrate_copy:          # the known-size kernel the --pmc byte counters are scaled by
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)

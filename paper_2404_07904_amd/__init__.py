@@ -5,4 +5,4 @@ The binding (and with it the native library) is loaded on first use, so that imp
 package -- e.g. for the seeded input generators in ``synth`` -- works on a machine without a GPU.
 """
 
-__all__ = ["synth", "binding", "autograd", "build"]
+__all__ = ["synth", "binding", "build"]
