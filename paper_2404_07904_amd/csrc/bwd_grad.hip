@@ -816,7 +816,7 @@ BwdFusedPlan plan_bwd_fused(const SeqDims& d)
 {
     // One workgroup per run and one run per compute unit at a time: as many runs per sequence as it
     // takes to fill the chip, but at least four chunks each.  The zero-start sweep that supplies the
-    // state gradient at the run boundaries walks sub-runs of about four chunks.
+    // state gradient at the run boundaries walks sub-runs of about eight chunks.
     BwdFusedPlan pl;
     pl.light = 0;
     for (int i = 0; i <= kMaxLightRuns; ++i) pl.bnd[i] = 0;
@@ -850,7 +850,7 @@ BwdFusedPlan plan_bwd_fused(const SeqDims& d)
         return pl;
     }
     int rc = (d.NC + R - 1) / R;
-    int s = rc / 4;
+    int s = rc / 8;                               // sub-runs of about eight chunks: fewer, longer walks and fewer states to carry
     if (s < 1) s = 1;
     if (R > 1) rc = (rc + s - 1) / s * s;         // whole sub-runs per run
     pl.rc = rc;

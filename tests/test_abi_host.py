@@ -60,9 +60,9 @@ def test_workspace_sizes():
     long = shape(B=2, H=16, N=16384, dk=128, dv=128)
     one = 32 * 256 * 128 * 128 * 2
     assert binding.hgrn2_fwd_workspace_bytes(long) == one + 32 * 8 * (128 * 128 + 128) * 4      # 8 runs forward
-    # backward: forward states in 8 runs; reverse walk in 8 runs of 32 chunks, boundaries from 56 sub-runs of 4 chunks
+    # backward: forward states in 8 runs; reverse walk in 8 runs of 32 chunks, boundaries from 28 sub-runs of 8 chunks
     assert binding.hgrn2_bwd_workspace_bytes(long) == (one + 32 * 8 * (128 * 128 + 128) * 4
-                                                       + 32 * 56 * (128 * 128 + 128) * 4 + 32 * 128 * 128 * 4)
+                                                       + 32 * 28 * (128 * 128 + 128) * 4 + 32 * 128 * 128 * 4)
 
 
 def test_small_gate_mode_workspace_and_support():
