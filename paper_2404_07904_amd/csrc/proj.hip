@@ -114,21 +114,24 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    u32x4 ra[4], rb[4];
+    // Tiles travel global memory -> registers -> LDS.  The registers are loaded TWO steps ahead (two
+    // register sets, the loop unrolled by two so that each set is a fixed group of registers): one
+    // step of matrix work is shorter than a trip to memory.  Loads are unconditional (steps past
+    // the end fetch the last one again and are never stored).
+    u32x4 ra[2][4], rb[2][4];
     const int nk = (p.K + BK - 1) / BK;
-    tile_load<A_KM>(ra, p.A, p.lda, m0, 0, p.M, p.K, tid);
-    tile_load<B_KM>(rb, p.B, p.ldb, n0, 0, p.N, p.K, tid);
-    tile_store<A_KM>(At, ra, tid);
-    tile_store<B_KM>(Bt, rb, tid);
-    __syncthreads();
-    for (int kb = 0; kb < nk; ++kb) {
-        const __bf16* Ac = At + (size_t)(kb & 1) * kTileElems;
-        const __bf16* Bc = Bt + (size_t)(kb & 1) * kTileElems;
-        // the next step's tiles travel to registers while this step is multiplied (the last step
-        // fetches itself again: loads stay unconditional)
-        const int kn = min(kb + 1, nk - 1) * BK;
-        tile_load<A_KM>(ra, p.A, p.lda, m0, kn, p.M, p.K, tid);
-        tile_load<B_KM>(rb, p.B, p.ldb, n0, kn, p.N, p.K, tid);
+    auto fetch = [&](int set, int kb) {
+        const int k0 = min(kb, nk - 1) * BK;
+        tile_load<A_KM>(ra[set], p.A, p.lda, m0, k0, p.M, p.K, tid);
+        tile_load<B_KM>(rb[set], p.B, p.ldb, n0, k0, p.N, p.K, tid);
+    };
+    auto stash = [&](int set, int buf) {
+        tile_store<A_KM>(At + (size_t)buf * kTileElems, ra[set], tid);
+        tile_store<B_KM>(Bt + (size_t)buf * kTileElems, rb[set], tid);
+    };
+    auto multiply = [&](int buf) {
+        const __bf16* Ac = At + (size_t)buf * kTileElems;
+        const __bf16* Bc = Bt + (size_t)buf * kTileElems;
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             bf16x8 fa[4], fb[2];
@@ -141,8 +144,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmParams p)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) M::mma(acc[i][j], fb[j], fa[i]);       // rows = result columns
         }
-        tile_store<A_KM>(At + (size_t)((kb + 1) & 1) * kTileElems, ra, tid);
-        tile_store<B_KM>(Bt + (size_t)((kb + 1) & 1) * kTileElems, rb, tid);
+    };
+    fetch(0, 0);
+    stash(0, 0);
+    fetch(0, 1);
+    fetch(1, 2);
+    __syncthreads();
+    for (int kb = 0; kb < nk; kb += 2) {
+        multiply(0);                      // step kb
+        stash(0, 1);                      // step kb + 1 (fetched two steps ago)
+        fetch(0, kb + 3);
+        __syncthreads();
+        if (kb + 1 < nk) multiply(1);     // step kb + 1
+        stash(1, 0);                      // step kb + 2
+        fetch(1, kb + 4);
         __syncthreads();
     }
 
