@@ -15,7 +15,7 @@
 //
 // The matrix kernel: a 256 x 256 tile of the result per workgroup of eight waves (2 x 4, each
 // 128 x 64 = 4 x 2 MFMA tiles of 32 x 32), K in steps of 64 through double-buffered LDS tiles
-// filled from registers that were loaded one step ahead.  An operand whose contraction index is
+// filled from registers that were loaded two steps ahead.  An operand whose contraction index is
 // the slow axis of its array (W3 in dx; both operands in dW3) keeps its natural orientation in LDS
 // and is read with LDS transpose loads.  The accumulators are kept transposed (result column in
 // the register index), so that four consecutive result columns of a row leave a lane together.
