@@ -162,7 +162,9 @@ BwdLayout bwd_layout(const SeqDims& d, bool gated, bool states_given = false)
 // host does not know the lengths): runs of `run_chunks` chunks (0: not cut), at most `R` of them.
 struct PackedRuns {
     int run_chunks = 0, R = 0;
-    size_t table_bytes = 0;      // sequence table, then run table and first_run
+    int G = 0;                   // groups of table entries per head (walked back to back by one workgroup)
+    size_t groups_at = 0;        // where the group array starts
+    size_t table_bytes = 0;      // sequence table, then run table and first_run, then the groups
     size_t state_bytes = 0;      // per sweep: fp32 [R * H][dk][dv]
     size_t decay_bytes = 0;      // fp32 [R * H][dk]
 };
@@ -173,18 +175,32 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     p.R = s->B;
     p.table_bytes = round256(varlen_table_bytes(s->B));
     if (s->B == 0) return p;
+    // With at least as many entries per head as it takes to give every compute unit a walk, the
+    // entries are walked a group at a time, about one group per compute unit (fewer, longer ones keep
+    // a workgroup each, or are cut into runs).
+    auto with_groups = [&](PackedRuns& r) {
+        const int per_head = 256 / (s->H > 0 ? s->H : 1) > 0 ? 256 / (s->H > 0 ? s->H : 1) : 1;
+        if (r.R < per_head) return;
+        r.G = per_head;
+        r.groups_at = r.table_bytes;
+        r.table_bytes += round256(varlen_groups_bytes(r.G));
+    };
     SeqDims mean = d;
     mean.packed = false;
     mean.NC = (int)(((long long)d.N / kChunk + s->B - 1) / s->B);
     int rc;
-    if (plan_runs(mean, backward, &rc) <= 1) return p;
-    const long long bound = s->B + ((long long)d.N / kChunk + s->B) / rc + 1;       // >= sum_b ceil(NC_b / rc)
-    if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2) return p;
+    const long long bound = plan_runs(mean, backward, &rc) <= 1 ? 0
+                          : s->B + ((long long)d.N / kChunk + s->B) / rc + 1;       // >= sum_b ceil(NC_b / rc)
+    if (bound == 0 || bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2) {
+        with_groups(p);
+        return p;
+    }
     p.run_chunks = rc;
     p.R = (int)bound;
     p.table_bytes += round256(varlen_run_table_bytes(s->B, p.R));
     p.state_bytes = round256((size_t)p.R * s->H * d.dk * d.dv * sizeof(float));
     p.decay_bytes = round256((size_t)p.R * s->H * d.dk * sizeof(float));
+    with_groups(p);
     return p;
 }
 
@@ -197,14 +213,23 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     *first_run = nullptr;
     d->lay.vl = seq_table;
     hipError_t e = launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream);
-    if (e != hipSuccess || p.run_chunks == 0) return e;
-    int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
-    int* fr = run_table + 4 * ((size_t)p.R + 1);
-    e = launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream);
-    d->lay.vl = run_table;
-    d->lay.B = p.R;
-    d->BH = p.R * s->H;
-    *first_run = fr;
+    if (e != hipSuccess) return e;
+    if (p.run_chunks != 0) {
+        int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
+        int* fr = run_table + 4 * ((size_t)p.R + 1);
+        e = launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream);
+        if (e != hipSuccess) return e;
+        d->lay.vl = run_table;
+        d->lay.B = p.R;
+        d->BH = p.R * s->H;
+        *first_run = fr;
+    }
+    if (p.G > 0) {
+        int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
+        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
+        d->lay.groups = groups;
+        d->lay.G = p.G;
+    }
     return e;
 }
 
@@ -807,6 +832,15 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                                     stream) != hipSuccess ||
             launch_sweep_pair(d, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
+    } else if (d.lay.groups) {
+        // groups of whole sequences: one forward-state sweep, then the reverse walk that carries the
+        // state gradient in registers and produces the gradients chunk by chunk
+        if (launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess ||
+            launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
+                                     stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
+        return HGRN2_OK;
     } else
     if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
         return HGRN2_ERR_HIP;

@@ -131,9 +131,15 @@ template <typename T, int DK, int DV> struct BwdGradLds {
 // chunk) x (first-half gate product of the chunk just done), published to the LDS tile the
 // contractions read D' from, and after the chunk's contractions receive Q~^T dO.  Only the forward
 // states S_n come from the workspace.
-template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE, bool FUSED>
+// GROUPED (a FUSED walk over a packed batch with a group table): the workgroup owns the sequences
+// [groups[g], groups[g + 1]) of one head and walks them from the last to the first, each from its last
+// chunk to its first: the state gradient starts from the sequence's grad_hT (or zero) at its last
+// chunk and leaves as its grad_h0 after its first, and the rows of the next chunk of the walk --
+// be it of the sequence before -- are always in flight during the epilogue of the current one.
+template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE, bool FUSED, bool GROUPED = false>
 __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 {
+    static_assert(!GROUPED || (FUSED && !DENSE), "groups: fused walk over a packed batch");
     constexpr int C = kChunk, NW = kBwdWaves, RW = C / NW;
     typedef BwdGradLds<T, DK, DV> L;
     constexpr int PK = L::PK, PV = L::PV, PVR = L::PVR, PC = L::PC, PF = L::PF;
@@ -229,14 +235,48 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 
     int n_chunks = p.BH * p.NC;
     if constexpr (!DENSE) {
-        if (p.lay.vl) n_chunks = p.lay.vl[2 * (p.lay.B + 1) + p.lay.B] * p.lay.H;      // the table's total, not the host's bound
+        if (p.lay.vl) n_chunks = table_read(p.lay.vl, 2 * (p.lay.B + 1) + p.lay.B) * p.lay.H;      // the table's total, not the host's bound
     }
+    // GROUPED: the sequences e0 .. e1 - 1 of head g_head; chunk (e, n) of the walk as a ChunkAt
+    int e0 = 0, e1 = 0, g_head = 0;
+    auto chunk_en = [&](int e, int n) {
+        ChunkAt c;
+        c.bh = e * p.lay.H + g_head;
+        c.n = n;
+        c.sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, c.bh);
+        return c;
+    };
+    // the chunk the walk visits after c: the one before it in its sequence, else the last chunk of
+    // the nearest earlier sequence of the group that has tokens; after the very last one, c again
+    auto walk_next = [&](const ChunkAt& c) {
+        if (c.n > 0) { ChunkAt r = c; r.n = c.n - 1; return r; }
+        for (int e = c.bh / p.lay.H - 1; e >= e0; --e) {
+            const int len = table_read(p.lay.vl, p.lay.B + 1 + e);
+            if (len > 0) return chunk_en(e, (len + C - 1) / C - 1);
+        }
+        return c;
+    };
     RawRows<RW> raw_f, raw_q;
     Raw16<T> raw_v, raw_d;
     frag sS[2 * NBT], sD[2 * NBT];
     // chunks of this workgroup: every gridDim.x-th one, or (FUSED) those of its run, last to first
     int n_iter, f_bh = 0, f_run = 0, f_first = 0, f_last = 0;
-    if constexpr (FUSED) {
+    if constexpr (GROUPED) {
+        if ((int)blockIdx.x >= p.lay.G * p.lay.H) return;
+        const int grp = (int)blockIdx.x / p.lay.H;
+        g_head = (int)blockIdx.x - grp * p.lay.H;
+        e0 = table_read(p.lay.groups, grp);
+        e1 = table_read(p.lay.groups, grp + 1);
+        n_iter = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e1) - table_read(p.lay.vl, 2 * (p.lay.B + 1) + e0);
+        // a sequence without tokens hands the gradient of its final state on to its initial state
+        if (p.dh0)
+            for (int e = e0; e < e1; ++e)
+                if (table_read(p.lay.vl, p.lay.B + 1 + e) == 0)
+                    for (int i = tid; i < DK * DV; i += kBwdThreads) {
+                        const size_t x = (size_t)(e * p.lay.H + g_head) * DK * DV + i;
+                        p.dh0[x] = p.dhT ? p.dhT[x] : 0.0f;
+                    }
+    } else if constexpr (FUSED) {
         f_bh = (int)blockIdx.x / p.R;
         f_run = (int)blockIdx.x - f_bh * p.R;
         if (f_bh >= p.BH) return;
@@ -263,7 +303,15 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     const bool has_d = FUSED && ((NDT % NW == 0) || w < NDT);
     f32x16 accD[FUSED ? TPW : 1];
     float gm_prev = 1.0f;                 // first-half gate product of the chunk done before, channel 32 at + lane % 32
-    if constexpr (FUSED) {
+    // Element (tile j, register v) of this lane in a [dk][dv] fp32 state: a wave-uniform address
+    // (sequence, dv tile, group of four registers) plus one per-lane 32-bit byte offset plus a small
+    // constant, so that no access needs an address register of its own (GROUPED walks read and write
+    // such states in the middle of the chunk loop, where registers are scarce).
+    const uint32_t st_lane = (uint32_t)((32 * at + (tid & 31)) * DV + 4 * ((tid >> 5) & 1)) * 4u;
+    auto state_cols = [&](const float* base, int seq, int j, int c) {
+        return reinterpret_cast<const char*>(base) + ((size_t)seq * DK * DV + (size_t)(32 * ((w + NW * j) / NAT) + 8 * c)) * 4;
+    };
+    if constexpr (FUSED && !GROUPED) {
         const int r32i = tid & 31, gi = (tid >> 5) & 1;
         const float* init = (f_run == p.R - 1 || p.light) ? p.dhT : (f_run == 0) ? p.bound0 : p.run_state;
         if (init) {
@@ -283,7 +331,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     ChunkAt cur;
     bool rows_loaded = false;
     float below_floor = 1.0f;             // smallest product a reciprocal was taken of (reported once, at the end)
-    if constexpr (FUSED) {
+    if constexpr (FUSED && !GROUPED) {
         const int n_light = p.light ? p.NC - 1 - f_last : 0;
         if (n_light > 0) {
             // ---- light walk over the chunks after this run: dS_n = Diag(g_n) dS_{n+1} + Q^_n^T dO_n with
@@ -361,13 +409,20 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             rows_loaded = true;
         }
     }
+    if constexpr (GROUPED) {
+        // first chunk of the walk: the last chunk of the last sequence with tokens (n_iter > 0: there is one)
+        int e = e1 - 1;
+        while (table_read(p.lay.vl, p.lay.B + 1 + e) == 0) --e;
+        cur = chunk_en(e, (table_read(p.lay.vl, p.lay.B + 1 + e) + C - 1) / C - 1);
+        load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
+    } else
     if (!rows_loaded) {
         cur = where(chunk_of(0));
         load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
     }
 
   for (int it = 0; it < n_iter; ++it) {
-    const int chunk = chunk_of(it);
+    const int chunk = GROUPED ? (int)cur.sv.chunk0 + cur.n : chunk_of(it);
     // Re-derive the lane-dependent indices inside the loop from a value the compiler cannot see
     // through: otherwise it hoists dozens of loop-invariant LDS addresses out of the loop, keeps
     // them in registers across the whole body and spills.
@@ -446,6 +501,21 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // H_m * dS_{n+1} of channel tile `at` -> LDS, row-major [channel][dv position] (the fragments hold
     // it already scaled and rounded, and in position order: their bits go to LDS as they are), and
     // R = rowsum((H_m dS) * (G_m S_n)) = g * rowsum(dS * S_n).  Once per channel tile (row tile 0).
+    if constexpr (GROUPED) {
+        // the walk enters a sequence at its last chunk: the state gradient starts from its grad_hT
+        if (cur.n == cur.sv.NC - 1) {
+            gm_prev = 1.0f;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const char* cols = state_cols(p.dhT, cur.bh, j, c);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        accD[j][4 * c + e] = (p.dhT && has_d) ? *reinterpret_cast<const float*>(cols + st_lane + 4 * e) : 0.0f;
+                }
+        }
+    }
     if constexpr (FUSED) {
         // scale the carried state gradient to D'_n and publish it as the bf16 tile the contractions read
         if (has_d) {
@@ -609,8 +679,27 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             }
         }
     }
+    if constexpr (GROUPED) {
+        // the walk leaves a sequence after its first chunk: dS_0 = G_m E is its grad_h0 (formed in
+        // place: the next chunk of the walk starts from its own sequence's grad_hT)
+        if (cur.n == 0 && p.dh0 && has_d) {
+#pragma unroll
+            for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    char* cols = const_cast<char*>(state_cols(p.dh0, cur.bh, j, c));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        accD[j][4 * c + e] *= gm_prev;
+                        *reinterpret_cast<float*>(cols + st_lane + 4 * e) = accD[j][4 * c + e];
+                    }
+                }
+        }
+    }
     RawRows<RW> nxt_f, nxt_q;
-    const ChunkAt nxt = where(chunk_of(it + 1));
+    ChunkAt nxt;
+    if constexpr (GROUPED) nxt = walk_next(cur);
+    else nxt = where(chunk_of(it + 1));
     load_chunk_rows(nxt_f, nxt_q, raw_v, raw_d, nxt, lane);   // v, dO of this chunk are dead
     __syncthreads();     // every wave is done with the operand tiles
 
@@ -734,7 +823,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
     if (p.flag && below_floor < kTinyProduct) *p.flag = 1;
-    if constexpr (FUSED) {
+    if constexpr (FUSED && !GROUPED) {
         // run 0 ends at the start of the sequence: dS_0 = G_m E of its first chunk is grad_h0
         if (f_run == 0 && p.dh0 && has_d) {
             const int r32i = tid & 31, gi = (tid >> 5) & 1;
@@ -762,6 +851,13 @@ __global__ __launch_bounds__(kBwdThreads) void bwd_fused_kernel(BwdGradParams p)
 {
     if (p.dense) bwd_grad_body<T, DK, DV, GATE_BF16, true, true>(p);
     else         bwd_grad_body<T, DK, DV, GATE_BF16, false, true>(p);
+}
+
+// The fused reverse walk over groups of a packed batch's sequences (a kernel of its own).
+template <typename T, int DK, int DV, bool GATE_BF16>
+__global__ __launch_bounds__(kBwdThreads) void bwd_fused_grouped_kernel(BwdGradParams p)
+{
+    bwd_grad_body<T, DK, DV, GATE_BF16, false, true, true>(p);
 }
 
 template <typename T, int DK, int DV>
@@ -886,6 +982,40 @@ hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void
     if (d.dk == 64 && d.dv == 64) return launch_fused_one<__bf16, 64, 64>(d, p, stream);
     if (d.dk == 128 && d.dv == 64) return launch_fused_one<__bf16, 128, 64>(d, p, stream);
     if (d.dk == 64 && d.dv == 128) return launch_fused_one<__bf16, 64, 128>(d, p, stream);
+    return hipErrorInvalidValue;
+}
+
+template <int DK, int DV>
+static hipError_t launch_grouped_one(const SeqDims& d, const BwdGradParams& p, hipStream_t stream)
+{
+    typedef BwdGradLds<__bf16, DK, DV> L;
+    auto kern = d.gate_bf16 ? bwd_fused_grouped_kernel<__bf16, DK, DV, true> : bwd_fused_grouped_kernel<__bf16, DK, DV, false>;
+    hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(d.lay.G * d.lay.H)), dim3(kBwdThreads), L::total, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_fused_grouped(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                                    const void* ws_state, const float* grad_hT, float* grad_h0, void* grad_q,
+                                    void* grad_f, void* grad_v, float* beta_partials, hipStream_t stream)
+{
+    if (d.total_chunks() == 0) return hipSuccess;
+    if (!d.lay.vl || !d.lay.groups || !d.io_bf16) return hipErrorInvalidValue;
+    if (d.beta && !beta_partials) return hipErrorInvalidValue;
+    BwdGradParams p;
+    p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = nullptr;
+    p.dq = grad_q; p.df = grad_f; p.dv = grad_v;
+    p.BH = d.BH; p.N = d.N; p.NC = d.NC;
+    p.beta = d.beta; p.beta_partials = beta_partials; p.H = d.H; p.lay = d.lay; p.dense = 0;
+    p.dhT = grad_hT; p.dh0 = grad_h0; p.bound0 = nullptr; p.run_state = nullptr;
+    p.R = 1; p.rc = d.NC; p.s_sub = 1; p.seg_tail = 0; p.light = 0;
+    for (int i = 0; i <= kMaxLightRuns; ++i) p.bnd[i] = 0;
+    p.flag = d.domain_flag;
+    if (d.dk == 128 && d.dv == 128) return launch_grouped_one<128, 128>(d, p, stream);
+    if (d.dk == 64 && d.dv == 64) return launch_grouped_one<64, 64>(d, p, stream);
+    if (d.dk == 128 && d.dv == 64) return launch_grouped_one<128, 64>(d, p, stream);
+    if (d.dk == 64 && d.dv == 128) return launch_grouped_one<64, 128>(d, p, stream);
     return hipErrorInvalidValue;
 }
 

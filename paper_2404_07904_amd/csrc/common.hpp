@@ -38,6 +38,16 @@ template <typename T> __host__ __device__ constexpr int pad_elems() { return 16 
 
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 
+// Entry i of one of the small device tables (sequence table, groups).  An earlier kernel wrote
+// them and they are constant while a kernel of the passes runs, which the constant address space
+// tells the compiler: a wave-uniform read then becomes a scalar load, which neither waits for nor
+// is counted with the vector loads and stores a kernel has in flight.
+__device__ __forceinline__ int table_read(const int* table, int i)
+{
+    typedef const __attribute__((address_space(4))) int* const_ptr;
+    return ((const_ptr)table)[i];
+}
+
 // ---- which tokens a sequence (b, h) owns --------------------------------------------------------
 // N tokens, NC chunks, element offsets of its first token in q / f (off_k) and v / o (off_v), and
 // the index of its first chunk in the per-chunk workspaces.  `bh` must be uniform over the wave.
@@ -75,12 +85,12 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
     } else {
         if (lay.vl) {
             const int b = bh / lay.H, h = bh - b * lay.H;
-            const int start = lay.vl[b];
-            s.N = lay.vl[lay.B + 1 + b];
+            const int start = table_read(lay.vl, b);
+            s.N = table_read(lay.vl, lay.B + 1 + b);
             s.NC = (s.N + kChunk - 1) / kChunk;
             s.off_k = (size_t)start * lay.sn_k + (size_t)h * lay.sh_k;
             s.off_v = (size_t)start * lay.sn_v + (size_t)h * lay.sh_v;
-            s.chunk0 = (size_t)lay.vl[2 * (lay.B + 1) + b] * lay.H + (size_t)h * s.NC;
+            s.chunk0 = (size_t)table_read(lay.vl, 2 * (lay.B + 1) + b) * lay.H + (size_t)h * s.NC;
         } else {
             s.N = N; s.NC = NC;
             s.off_k = lay.off_k(bh); s.off_v = lay.off_v(bh);
@@ -99,7 +109,7 @@ __device__ __forceinline__ int sequence_of_workgroup(const TokenLayout& lay, int
     if constexpr (!DENSE) {
         if (lay.vl) {
             const int slot = id / lay.H, h = id - slot * lay.H;
-            return lay.vl[3 * (lay.B + 1) + slot] * lay.H + h;
+            return table_read(lay.vl, 3 * (lay.B + 1) + slot) * lay.H + h;
         }
     }
     return id;

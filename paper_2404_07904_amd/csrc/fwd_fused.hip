@@ -31,6 +31,11 @@
 //   * with fewer sequences than compute units, two workgroups share a sequence, each owning one
 //     half of the dv columns (of V, O and the state): the element-wise work on q and f and the
 //     P blocks are done twice, everything that scales with dv is halved, and the whole chip is busy.
+//   * a packed batch with a group table gives a workgroup a group of consecutive sequences of one
+//     head: the pipeline runs on across the sequence boundaries (the rows of the next sequence's
+//     first chunks are fetched while the current one ends), the state is replaced by the next
+//     sequence's initial state where it starts and written out where one ends.  Many short
+//     sequences then cost the start-up of a workgroup once per group, not once per sequence.
 // Used for bf16 storage with dk = dv = 128 when there are enough sequences to fill the chip;
 // other cases take the sweep + read-out path.
 #include "common.hpp"
@@ -74,13 +79,21 @@ template <int NSPLIT> struct FwdFusedLds {
     static constexpr size_t ost = sb + (size_t)NSB * DK * DVW * 2;      // O   [C][PO]
     static constexpr size_t tot = ost + (size_t)C * PO * 2;             // [8][DK] fp32 block totals + one row of ones
     static constexpr size_t ca = tot + (size_t)(kFusedWaves + 1) * DK * 4;   // [DK] fp32 state rescale
-    static constexpr size_t total = ca + (size_t)DK * 4;
+    static constexpr size_t ch = ca + (size_t)DK * 4;                   // [DK] fp32 h of the chunk before (grouped walks)
+    static constexpr size_t total = ch + (size_t)DK * 4;
     static_assert(total <= 160 * 1024, "LDS budget of one workgroup");
 };
 
-template <bool GATE_BF16, int NSPLIT, bool DENSE>
+// One chunk of the walk: tokens row0 .. row0 + C - 1 of a sequence of N tokens whose first token is
+// token tok0 of the packed tensors (grouped walks; 0 otherwise).  N = 0: a pass past the end.
+struct FusedChunk {
+    int tok0, row0, N, bh, first, last;
+};
+
+template <bool GATE_BF16, int NSPLIT, bool DENSE, bool GROUPED>
 __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
 {
+    static_assert(!(DENSE && GROUPED), "groups are a feature of packed batches");
     typedef __bf16 T;
     typedef Mma<T> M;
     typedef typename M::frag frag;
@@ -113,25 +126,45 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     T* Ost = reinterpret_cast<T*>(smem + L::ost);
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     float* cA = reinterpret_cast<float*>(smem + L::ca);
+    float* cH = reinterpret_cast<float*>(smem + L::ch);
 
     // workgroup -> (sequence, dv half): ids 8 apart land on the same XCD (ids are dealt to the 8
     // XCDs round-robin), so the two halves of a sequence share an L2 for the q, f rows both read
     int bh, split;
     if (NSPLIT == 1) { bh = blockIdx.x; split = 0; }
     else { const int x = blockIdx.x & 7, r = blockIdx.x >> 3; split = r % NSPLIT; bh = (r / NSPLIT) * 8 + x; }
-    if (bh >= p.BH) return;                  // padding of the grid (uniform, before any barrier)
-    bh = sequence_of_workgroup<DENSE>(p.lay, bh);
+    // padding of the grid (uniform, before any barrier)
+    if (bh >= (GROUPED ? p.lay.G * p.lay.H : p.BH)) return;
+    // grouped: the sequences e0 .. e1 - 1 of head `head`, found through the table's arrays
+    int e0 = 0, e1 = 0, head = 0;
+    const int* t_start = p.lay.vl;
+    const int* t_len = p.lay.vl + (p.lay.B + 1);
+    if constexpr (GROUPED) {
+        const int grp = bh / p.lay.H;
+        head = bh - grp * p.lay.H;
+        e0 = table_read(p.lay.groups, grp); e1 = table_read(p.lay.groups, grp + 1);
+        bh = e0 * p.lay.H + head;            // (only for the view below, whose chunk count is replaced)
+    } else {
+        bh = sequence_of_workgroup<DENSE>(p.lay, bh);
+    }
     const int dv0 = split * DVW;             // first dv column of this workgroup
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
-    const SeqView sv = seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh);
+    SeqView sv;
+    if constexpr (GROUPED) {
+        // addresses are formed from token numbers: the view is the head's slice of the whole tensor
+        sv.off_k = (size_t)head * p.lay.sh_k; sv.off_v = (size_t)head * p.lay.sh_v; sv.chunk0 = 0;
+        sv.N = 0;
+        sv.NC = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e1) - table_read(p.lay.vl, 2 * (p.lay.B + 1) + e0);   // chunks of all the group's sequences
+    } else {
+        sv = seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh);
+    }
     const size_t seq_k = sv.off_k, seq_v = sv.off_v;
-    const int N = sv.N;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const T* qg = static_cast<const T*>(p.q);
     const T* vg = static_cast<const T*>(p.v);
     T* og = static_cast<T*>(p.o);
-    const int NC = sv.NC;
+    const int NC = sv.NC;                    // passes over chunks with tokens
 
     const int rt = w / NBT, bt = w % NBT;    // output tile (rt, bt) of this wave, if w < NOT
     const int at0 = NST * (w / NBT);         // its state tiles: (at0 .. at0 + NST - 1, bt)
@@ -139,23 +172,100 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     const bool is_p = w >= PW0 && w < PW0 + 3;
     const bool after = w >= NW / 2;          // rows of this wave lie after the mid-chunk reference
 
-    if (NC == 0) {                           // empty sequence: hT = h0 (uniform early exit, before any barrier)
+    // a sequence without tokens ends in the state it starts from
+    auto pass_state_on = [&](int seq) {
         if (p.hT)
             for (int idx = tid; idx < DK * DVW; idx += kFusedThreads) {
-                const size_t e = (size_t)bh * DK * DV + (size_t)(idx / DVW) * DV + dv0 + idx % DVW;
+                const size_t e = (size_t)seq * DK * DV + (size_t)(idx / DVW) * DV + dv0 + idx % DVW;
                 p.hT[e] = p.h0 ? p.h0[e] : 0.0f;
             }
+    };
+    if constexpr (GROUPED) {
+        for (int e = e0; e < e1; ++e)
+            if (table_read(t_len, e) == 0) pass_state_on(e * p.lay.H + head);
+        if (NC == 0) return;                 // (uniform early exit, before any barrier)
+    } else if (NC == 0) {
+        pass_state_on(bh);
         return;
     }
 
+    // ---- the chunks of the walk, in order.  Grouped walks step through the group's sequences with
+    // a cursor that runs three chunks ahead of the pass (everything here is wave-uniform).
+    int cur_e = e0 - 1, cur_n = 0, cur_nc = 0, cur_tok = 0, cur_N = 0;
+    auto next_chunk = [&]() {
+        FusedChunk c;
+        if (cur_n + 1 < cur_nc) ++cur_n;
+        else {
+            int e = cur_e + 1, len = 0;
+            while (e < e1 && (len = table_read(t_len, e)) == 0) ++e;
+            if (e < e1) { cur_e = e; cur_N = len; cur_nc = (len + C - 1) / C; cur_tok = table_read(t_start, e); }
+            else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; }          // past the end, for good
+            cur_n = 0;
+        }
+        c.tok0 = cur_tok; c.row0 = cur_n * C; c.N = cur_N; c.bh = cur_e * p.lay.H + head;
+        c.first = cur_n == 0; c.last = cur_N > 0 && cur_n == cur_nc - 1;
+        return c;
+    };
+    const int N_one = sv.N;
+    auto chunk_at = [&](int c) {             // one sequence per workgroup: chunk c of it (any c >= -1)
+        FusedChunk k;
+        k.tok0 = 0; k.row0 = c * C; k.N = N_one; k.bh = bh; k.first = c == 0; k.last = c == NC - 1;
+        return k;
+    };
+    // window of the pass: ck[j] = chunk n - 1 + j of pass n (grouped walks only)
+    FusedChunk ck[5];
+    if constexpr (GROUPED) {
+        ck[0].tok0 = 0; ck[0].row0 = 0; ck[0].N = 0; ck[0].bh = bh; ck[0].first = 1; ck[0].last = 0;
+#pragma unroll
+        for (int j = 1; j < 5; ++j) ck[j] = next_chunk();
+    }
+    auto chunk_rel = [&](int n, int rel) { return GROUPED ? ck[rel + 1] : chunk_at(n + rel); };
+
     // ---- state: fp32 accumulators.  Between chunks they hold S_n / h(n-1); see stage A. ----
     f32x16 accS[NST];
+    // Element (tile j, register v) of this lane in a [dk][dv] fp32 state: a wave-uniform address
+    // (sequence, tile, group of four registers) plus one per-lane 32-bit byte offset plus a small
+    // constant, so that no access needs an address register of its own.
+    const uint32_t st_lane = (uint32_t)(4 * g * DV + dv0 + 32 * bt + r32) * 4u;
+    auto state_rows = [&](const float* base, int seq, int j, int c) {
+        return reinterpret_cast<const char*>(base) + ((size_t)seq * DK * DV + (size_t)(32 * (at0 + j) + 8 * c) * DV) * 4;
+    };
+    auto initial_state = [&](int seq) {
 #pragma unroll
-    for (int j = 0; j < NST; ++j)
+        for (int j = 0; j < NST; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            accS[j][v] = p.h0 ? p.h0[(size_t)bh * DK * DV + (size_t)(32 * (at0 + j) + acc_row(v, lane)) * DV + dv0 + 32 * bt + r32]
-                              : 0.0f;
+            for (int c = 0; c < 4; ++c) {
+                const char* rows = state_rows(p.h0, seq, j, c);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    accS[j][4 * c + jj] = p.h0 ? *reinterpret_cast<const float*>(rows + st_lane + jj * DV * 4) : 0.0f;
+            }
+    };
+    // accumulators *= per-channel factors in LDS (channel = accumulator row)
+    auto scale_state = [&](const float* factor) {
+#pragma unroll
+        for (int j = 0; j < NST; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const f32x4 cm = *reinterpret_cast<const f32x4*>(factor + 32 * (at0 + j) + 8 * c + 4 * g);
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) accS[j][4 * c + jj] *= cm[jj];
+            }
+    };
+    // the state after the chunk before: scale * accumulators, formed in place (what follows either
+    // replaces the accumulators or is the end of the walk)
+    auto final_state = [&](int seq, const float* scale) {
+        scale_state(scale);
+#pragma unroll
+        for (int j = 0; j < NST; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                char* rows = const_cast<char*>(state_rows(p.hT, seq, j, c));
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) *reinterpret_cast<float*>(rows + st_lane + jj * DV * 4) = accS[j][4 * c + jj];
+            }
+    };
+    initial_state(GROUPED ? ck[1].bh : bh);
     float hprev0 = 1.0f, hprev1 = 1.0f;      // h of the previous chunk, channels 2*lane, 2*lane+1 (wave 0 only)
 
     // ---- row fetch, two chunks ahead, two register sets ----
@@ -177,19 +287,20 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     const char* fbase = static_cast<const char*>(p.f) + seq_k * (GATE_BF16 ? 2 : 4);
     const char* qbase = reinterpret_cast<const char*>(qg + seq_k);
     const char* vbase = reinterpret_cast<const char*>(vg + seq_v + dv0);
-    const int last_row = N - 1;
-    auto load_f = [&](RawRows<RW>& d, int c) {
-        load_rows_clamped<RW, GATE_BF16>(d, fbase, c * C + RW * w, last_row, ld_k, 2 * lane);
+    auto load_f = [&](RawRows<RW>& d, const FusedChunk& c) {
+        load_rows_clamped<RW, GATE_BF16>(d, fbase + (size_t)c.tok0 * ((size_t)ld_k * (GATE_BF16 ? 2 : 4)), c.row0 + RW * w,
+                                         max(c.N - 1, 0), ld_k, 2 * lane);
     };
-    auto load_q = [&](RawRows<RW>& d, int c) {
-        load_rows_clamped<RW, true>(d, qbase, c * C + RW * w, last_row, ld_k, 2 * lane);
+    auto load_q = [&](RawRows<RW>& d, const FusedChunk& c) {
+        load_rows_clamped<RW, true>(d, qbase + (size_t)c.tok0 * ((size_t)ld_k * 2), c.row0 + RW * w, max(c.N - 1, 0), ld_k, 2 * lane);
     };
-    auto load_v = [&](u32x4 (&d)[NVV], int c) {
-        const int row0 = c * C + RW * w;
+    auto load_v = [&](u32x4 (&d)[NVV], const FusedChunk& c) {
+        const int row0 = c.row0 + RW * w, last_row = max(c.N - 1, 0);
+        const char* vb = vbase + (size_t)c.tok0 * ((size_t)ld_v * 2);
 #pragma unroll
         for (int j = 0; j < NVV; ++j) {
             const int rc = min(row0 + lane / VPR + VRS * j, last_row);
-            d[j] = *reinterpret_cast<const u32x4*>(vbase + (size_t)rc * ((size_t)ld_v * 2) + 2 * vcol);
+            d[j] = *reinterpret_cast<const u32x4*>(vb + (size_t)rc * ((size_t)ld_v * 2) + 2 * vcol);
         }
     };
     // Rows past the end of the sequence need no masking here: their K~ is zero (f = 1 there), so
@@ -212,10 +323,11 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // First half (before the totals are exchanged): q a, k z, t.
     float qa0[RW], qa1[RW], kz0[RW], kz1[RW], bt0, bt1;
     float below_floor = 1.0f;            // smallest product a reciprocal was taken of (reported once, at the end)
-    auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, int c) {
+    auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, const FusedChunk& c) {
         f32x2 rf[RW];
-        convert_rows<RW>(rf, rf_raw, c * C + RW * w, N, true, GATE_BF16, 1.0f);
-        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh / p.lay.seg % p.H) * DK, 2 * lane, true, c * C + RW * w, N);
+        convert_rows<RW>(rf, rf_raw, c.row0 + RW * w, c.N, true, GATE_BF16, 1.0f);
+        if (p.beta)
+            gate_rows<RW>(rf, p.beta + (size_t)(GROUPED ? head : bh / p.lay.seg % p.H) * DK, 2 * lane, true, c.row0 + RW * w, c.N);
         float run0 = 1.0f, run1 = 1.0f;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
@@ -235,7 +347,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         *reinterpret_cast<f32x2*>(tot + w * DK + 2 * lane) = f32x2{bt0, bt1};
     };
     // Second half: block factors from the exchanged totals, tiles to LDS.
-    auto prep_tiles = [&](int c) {
+    auto prep_tiles = [&](int c, bool starts_sequence) {      // c: only its parity matters (which tile buffer)
         // product of the (at most three) block totals between this block and the reference row;
         // the row addresses are wave-uniform, an absent factor reads the row of ones
         const float* ones = tot + NW * DK;
@@ -270,6 +382,12 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
 #pragma unroll
             for (int i = 0; i < NW; ++i) t[i] = *reinterpret_cast<const f32x2*>(tot + i * DK + 2 * lane);
             const float gm0 = (t[0].x * t[1].x) * (t[2].x * t[3].x), gm1 = (t[0].y * t[1].y) * (t[2].y * t[3].y);
+            if constexpr (GROUPED) {
+                // the state of a sequence's first chunk is its initial state, not what the walk carries;
+                // and h alone turns the carried accumulators into the state a sequence ends in
+                *reinterpret_cast<f32x2*>(cH + 2 * lane) = f32x2{hprev0, hprev1};
+                if (starts_sequence) { hprev0 = 1.0f; hprev1 = 1.0f; }
+            }
             *reinterpret_cast<f32x2*>(cA + 2 * lane) = f32x2{hprev0 * gm0, hprev1 * gm1};
             hprev0 = (t[4].x * t[5].x) * (t[6].x * t[7].x); hprev1 = (t[4].y * t[5].y) * (t[6].y * t[7].y);
         }
@@ -279,15 +397,15 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // a global store reads its data registers late, and overwriting them earlier would make the
     // wave wait for the store, and with it for every prefetch issued before it, to complete.
     u32x4 obuf[C * VPR / kFusedThreads];
-    auto store_o = [&](int c) {
+    auto store_o = [&](const FusedChunk& c) {
 #pragma unroll
         for (int k = 0; k < C * VPR / kFusedThreads; ++k) {
             const int idx = tid + k * kFusedThreads;
             const int row = idx / VPR, cv = idx % VPR;
-            const int grow = c * C + row;
+            const int grow = c.row0 + row;
             obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
-            if ((unsigned)grow < (unsigned)N)      // also false for the chunk "-1" of the first pass
-                *reinterpret_cast<u32x4*>(og + seq_v + (size_t)grow * ld_v + dv0 + cv * 8) = obuf[k];
+            if ((unsigned)grow < (unsigned)c.N)    // also false for the chunk "-1" of the first pass
+                *reinterpret_cast<u32x4*>(og + seq_v + ((size_t)c.tok0 + grow) * ld_v + dv0 + cv * 8) = obuf[k];
         }
     };
 
@@ -296,13 +414,13 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // the never-written block of P (rows 0..31 x columns 32..63) must read as zero
     for (int idx = tid; idx < 32 * 32; idx += kFusedThreads) Pm[(idx >> 5) * PC + 32 + (idx & 31)] = (T)0.0f;
     if (tid < DK) tot[NW * DK + tid] = 1.0f;
-    load_f(rawf[0], 0); load_q(rawq[0], 0); load_v(rawv[0], 0);
-    load_f(rawf[1], 1); load_q(rawq[1], 1);
-    if (VD == 2) load_v(rawv[VD - 1], 1);
-    prep_gates(rawf[0], rawq[0], 0);
-    load_f(rawf[0], 2); load_q(rawq[0], 2);
+    load_f(rawf[0], chunk_rel(0, 0)); load_q(rawq[0], chunk_rel(0, 0)); load_v(rawv[0], chunk_rel(0, 0));
+    load_f(rawf[1], chunk_rel(0, 1)); load_q(rawq[1], chunk_rel(0, 1));
+    if (VD == 2) load_v(rawv[VD - 1], chunk_rel(0, 1));
+    prep_gates(rawf[0], rawq[0], chunk_rel(0, 0));
+    load_f(rawf[0], chunk_rel(0, 2)); load_q(rawq[0], chunk_rel(0, 2));
     __syncthreads();
-    prep_tiles(0);
+    prep_tiles(0, true);
     __syncthreads();
 
     // output tile accumulator, transposed: accO[v] = O[token 32 rt + r32][channel 32 bt + 8 (v/4) + 4 g + v%4]
@@ -370,18 +488,19 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         const T* Kc = Km + (size_t)par * DK * PT;
         T* Sp = Sb + (LATE_QS ? (size_t)par * DK * DVW : 0);      // where this pass publishes G_m(n) S_n
         // ======================= stage A =======================
-        if (!LATE_QS) store_o(n - 1);
+        if (!LATE_QS) store_o(chunk_rel(n, -1));
         store_v(rawv[VD == 2 ? par : 0]);
-        load_v(rawv[VD == 2 ? par : 0], n + VD);
+        load_v(rawv[VD == 2 ? par : 0], chunk_rel(n, VD));
+        if constexpr (GROUPED) {
+            // sequence boundary: the walk's accumulators, times h of the chunk before, are the state
+            // the sequence before ends in; this chunk starts from its own sequence's initial state
+            if (ck[0].last && p.hT) final_state(ck[0].bh, cH);
+            if (ck[1].first && n > 0 && ck[1].N > 0) initial_state(ck[1].bh);
+        }
         // G_m(n) S_n = c(n) * accumulators, published as the bf16 operand of the read-out
+        scale_state(cA);
 #pragma unroll
         for (int j = 0; j < NST; ++j) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const f32x4 cm = *reinterpret_cast<const f32x4*>(cA + 32 * (at0 + j) + 8 * c + 4 * g);
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) accS[j][4 * c + jj] *= cm[jj];
-            }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 float x[8];
@@ -390,8 +509,8 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
                 *reinterpret_cast<frag*>(Sp + state_frag_offset(at0 + j, bt, NBT, half, lane)) = M::pack(x);
             }
         }
-        prep_gates(rawf[1 - par], rawq[1 - par], n + 1);
-        load_f(rawf[1 - par], n + 3); load_q(rawq[1 - par], n + 3);
+        prep_gates(rawf[1 - par], rawq[1 - par], chunk_rel(n, 1));
+        load_f(rawf[1 - par], chunk_rel(n, 3)); load_q(rawq[1 - par], chunk_rel(n, 3));
         if (LATE_QS) {
             // O(n-1) is completed here: its P V part was accumulated in stage B of the previous pass
             if (has_o) {
@@ -442,8 +561,8 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         __syncthreads();
         // ======================= stage B =======================
         // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
-        if (LATE_QS) store_o(n - 1);
-        if (p.save && n < NC) save_state(Sp, n);
+        if (LATE_QS) store_o(chunk_rel(n, -1));
+        if (!GROUPED && p.save && n < NC) save_state(Sp, n);
 #pragma unroll
         for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
 #pragma unroll
@@ -466,10 +585,15 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             }
         }
         if (!LATE_QS) read_out_state(Qc, Sp);
-        prep_tiles(n + 1);
+        prep_tiles(n + 1, chunk_rel(n, 1).first != 0);
         if (!LATE_QS) {
             if (has_o) stage_o();
             pin_obuf();
+        }
+        if constexpr (GROUPED) {             // the window moves on by one chunk
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ck[j] = ck[j + 1];
+            ck[4] = next_chunk();
         }
         __syncthreads();
     };
@@ -488,46 +612,62 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
                 stage_o();
             }
             __syncthreads();
-            store_o(NC - 1);
+            store_o(chunk_rel(NC, -1));
         }
     } else {
-        store_o(n_end - 1);
+        store_o(chunk_rel(n_end, -1));
     }
 
     if (p.flag && below_floor < kTinyProduct) *p.flag = 1;
     if (p.hT) {
-        // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1)
-        float* s1 = p.hT + (size_t)bh * DK * DV;
-#pragma unroll
-        for (int j = 0; j < NST; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int a = 32 * (at0 + j) + acc_row(v, lane);
-                s1[(size_t)a * DV + dv0 + 32 * bt + r32] = cA[a] * accS[j][v];
-            }
+        // S_N = pending rescale * accumulators (the chunk after the last one has G_m = 1).  A
+        // grouped walk has written the state of every sequence that a further pass followed; after
+        // an even number of chunks the last sequence is still to do.
+        if constexpr (GROUPED) {
+            if (NC % 2 == 0) final_state(ck[0].bh, cH);
+        } else {
+            final_state(bh, cA);
+        }
     }
 }
 
 template <bool GATE_BF16, int NSPLIT>
 __global__ __launch_bounds__(kFusedThreads) void fwd_fused_kernel(FwdFusedParams p)
 {
-    if (p.dense) fwd_fused_body<GATE_BF16, NSPLIT, true>(p);
-    else         fwd_fused_body<GATE_BF16, NSPLIT, false>(p);
+    if (p.dense) fwd_fused_body<GATE_BF16, NSPLIT, true, false>(p);
+    else         fwd_fused_body<GATE_BF16, NSPLIT, false, false>(p);
 }
+
+// The walk over groups of a packed batch's sequences (a kernel of its own: its register needs are
+// not those of the walk over one sequence).
+template <bool GATE_BF16, int NSPLIT>
+__global__ __launch_bounds__(kFusedThreads) void fwd_fused_grouped_kernel(FwdFusedParams p)
+{
+    fwd_fused_body<GATE_BF16, NSPLIT, false, true>(p);
+}
+
+// Groups of a packed batch's sequences are walked by one workgroup each when there are more
+// sequences than groups (with one sequence per group the plain walk does the same with less bookkeeping).
+static bool fused_grouped(const SeqDims& d) { return d.lay.vl && d.lay.groups && d.lay.B > d.lay.G; }
+// workgroups' worth of independent walks
+static int fused_walkers(const SeqDims& d) { return fused_grouped(d) ? d.lay.G * d.lay.H : d.BH; }
 
 bool fwd_fused_supported(const SeqDims& d)
 {
-    return d.io_bf16 && d.dk == 128 && d.dv == 128 && d.BH >= 64;
+    return d.io_bf16 && d.dk == 128 && d.dv == 128 && fused_walkers(d) >= 64;
 }
 
 template <int NSPLIT>
 static hipError_t launch_fused(const SeqDims& d, const FwdFusedParams& p, hipStream_t stream)
 {
     typedef FwdFusedLds<NSPLIT> L;
-    auto kern = d.gate_bf16 ? fwd_fused_kernel<true, NSPLIT> : fwd_fused_kernel<false, NSPLIT>;
+    const bool grouped = fused_grouped(d);
+    auto kern = grouped ? (d.gate_bf16 ? fwd_fused_grouped_kernel<true, NSPLIT> : fwd_fused_grouped_kernel<false, NSPLIT>)
+                        : (d.gate_bf16 ? fwd_fused_kernel<true, NSPLIT> : fwd_fused_kernel<false, NSPLIT>);
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
     if (e != hipSuccess) return e;
-    const unsigned grid = (NSPLIT == 1) ? (unsigned)d.BH : (unsigned)(NSPLIT * 8 * ((d.BH + 7) / 8));
+    const int walkers = fused_walkers(d);
+    const unsigned grid = (NSPLIT == 1) ? (unsigned)walkers : (unsigned)(NSPLIT * 8 * ((walkers + 7) / 8));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedThreads), L::total, stream, p);
     return hipGetLastError();
 }
@@ -544,7 +684,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
     // busy, but a compute unit holds one workgroup: beyond 128 sequences the halves would no longer
     // all run at once (the rest waits for a free unit: 137 us instead of 84 us for 144 sequences of 2048 tokens), so
     // from there on a sequence gets one workgroup.
-    return d.BH > 128 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
+    return fused_walkers(d) > 128 ? launch_fused<1>(d, p, stream) : launch_fused<2>(d, p, stream);
 }
 
 }   // namespace hgrn2

@@ -25,6 +25,12 @@ struct TokenLayout {
     // equal-length batches.
     const int* vl = nullptr;
     int B = 0;
+    // Packed batches of many short sequences: the kernels that walk sequences chunk by chunk give
+    // a workgroup a GROUP of consecutive sequences of one head, sequences [groups[g], groups[g+1])
+    // for group g of G (device array of G + 1 ints, launch_varlen_groups()), and walk them back to
+    // back.  Null: one workgroup per sequence.
+    const int* groups = nullptr;
+    int G = 0;
     // Segmented sweeps: each of the sequences the strides describe is cut into `seg` runs of whole
     // chunks that the sequential kernels treat as sequences of their own, `seg` per original one,
     // numbered run-fastest.  The kernels' N and NC are then those of a full run; `n_tokens` keeps
@@ -160,6 +166,13 @@ hipError_t launch_bwd_fused(const SeqDims& d, const BwdFusedPlan& pl, const void
                             const void* grad_o, const void* ws_state, const float* grad_hT, float* grad_h0,
                             const float* bound0, const float* run_state, void* grad_q, void* grad_f, void* grad_v,
                             float* beta_partials, hipStream_t stream);
+// The fused reverse walk for a packed batch with a group table (TokenLayout::groups): one workgroup
+// per (group, head) walks the group's sequences from the last to the first, each from its own
+// grad_hT[b] (may be null: zero) to its own grad_h0[b] (may be null).  ws_state: the forward states
+// of a kSweepStateBwd sweep over the same table.
+hipError_t launch_bwd_fused_grouped(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
+                                    const void* ws_state, const float* grad_hT, float* grad_h0, void* grad_q,
+                                    void* grad_f, void* grad_v, float* beta_partials, hipStream_t stream);
 size_t beta_partials_bytes(const SeqDims& d);
 hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream);
 
@@ -221,6 +234,11 @@ hipError_t launch_spread_packed(int T, int B, int block, int row_bytes, SpreadFi
 size_t varlen_run_table_bytes(int B, int R);
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
                                    int* first_run, hipStream_t stream);
+// Groups of a table's sequences (sequence or run table with n_entries entries): G + 1 ints, group g
+// = entries [groups[g], groups[g + 1]), cut where the chunk count reaches g / G of the total, so that
+// groups hold about equally many chunks (a group is never finer than one entry).
+size_t varlen_groups_bytes(int G);
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);

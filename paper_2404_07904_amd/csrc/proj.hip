@@ -30,6 +30,8 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int PKT = BK + 8;        // pitch of a tile kept [row][k]
 constexpr int PXT = 256 + 24;      // pitch of a tile kept [k][row]: transpose reads want rows 12 banks apart
 constexpr int kTileElems = (BM * PKT > BK * PXT) ? BM * PKT : BK * PXT;
+constexpr int kXcds = 8;         // accelerator dies; consecutive workgroup ids land on consecutive dies
+constexpr int kBandRows = 4;     // row blocks per band of the workgroup -> tile order
 constexpr int PST = BN + 8;        // pitch of the bf16 staging tile of the epilogue
 
 enum GemmEpilogue { kEpiProj = 0, kEpiPlain = 1, kEpiFloat = 2 };
@@ -100,9 +102,22 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmParams p)
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w >> 2, wn = w & 3;                              // wave tile: rows 128 wm .., columns 64 wn ..
-    // workgroups that share a row block of A (and walk the column blocks of B) get consecutive ids
-    const int n_bn = p.N / BN;
-    const int bm = (int)blockIdx.x / n_bn, bn = (int)blockIdx.x - bm * n_bn;
+    // Workgroup -> tile.  Workgroup ids go round the eight XCDs (id % 8), each with an L2 of its
+    // own, so the ids are first renumbered so that an XCD holds a contiguous range, and the range is
+    // laid over the tile grid in bands of kBandRows row blocks walked column by column: the 32
+    // workgroups an XCD runs together then cover about 4 x 8 tiles and share their operand panels
+    // in that XCD's L2 instead of each XCD streaming whole panels of its own.
+    const int n_bn = p.N / BN, n_bm = (p.M + BM - 1) / BM;
+    int bm, bn;
+    {
+        const int grid = (int)gridDim.x, id = (int)blockIdx.x;
+        const int per = grid / kXcds, rem = grid - per * kXcds, x = id % kXcds;
+        const int t = x * per + min(x, rem) + id / kXcds;             // position in the XCD-contiguous order
+        const int band_tiles = kBandRows * n_bn, band = t / band_tiles, in_band = t - band * band_tiles;
+        const int rows = min(kBandRows, n_bm - band * kBandRows);     // the last band may be shorter
+        bn = in_band / rows;
+        bm = band * kBandRows + in_band - bn * rows;
+    }
     const int m0 = bm * BM, n0 = bn * BN;
 
     // accumulators, transposed: acc[i][j][v] = C[m0 + 128 wm + 32 i + lane % 32][n0 + 64 wn + 32 j + 8 (v/4) + 4 g + v%4]

@@ -23,6 +23,13 @@
 
 namespace hgrn2 {
 
+// Workgroups (per column slab) a sweep needs: one per sequence, or one per group of a packed
+// batch's sequences (the walks from zero, ENDS, always take one per sequence).
+template <bool ENDS> static int sweep_walkers(const SeqDims& d)
+{
+    return (!ENDS && d.lay.vl && d.lay.groups) ? d.lay.G * d.lay.H : d.BH;
+}
+
 struct SweepParams {
     const void* q;
     const void* f;
@@ -59,54 +66,109 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
 
     // ENDS: the walk starts from a zero slab and hands nothing to the workspace; what it leaves is
     // the slab after the last chunk and the product of all gates it passed, per channel.
-    int bh, tile;
-    xcd_map(block_id, p.n_tile, bh, tile);
-    if (bh >= p.BH) return;
-    bh = sequence_of_workgroup<DENSE>(p.lay, bh);
+    //
+    // Which sequences this workgroup walks: one, or -- a packed batch with a group table -- the
+    // sequences [groups[g], groups[g + 1]) of one head, one after the other (each from its own initial
+    // slab to its own final one), with the first rows of the next sequence already in flight during
+    // the last chunk of the current one: a batch of many short sequences then costs a workgroup's
+    // start-up and a trip to memory once per group, not once per sequence.
+    int id, tile;
+    xcd_map(block_id, p.n_tile, id, tile);
+    int bh_first, bh_end, bh_step;
+    bool grouped = false;
+    if constexpr (!DENSE && !ENDS) grouped = p.lay.vl != nullptr && p.lay.groups != nullptr;
+    if (grouped) {
+        if (id >= p.lay.G * p.lay.H) return;
+        const int grp = id / p.lay.H, head = id - grp * p.lay.H;
+        bh_step = p.lay.H;
+        bh_first = table_read(p.lay.groups, grp) * p.lay.H + head;
+        bh_end = table_read(p.lay.groups, grp + 1) * p.lay.H + head;
+    } else {
+        if (id >= p.BH) return;
+        bh_first = sequence_of_workgroup<DENSE>(p.lay, id);
+        bh_step = 1;
+        bh_end = bh_first + 1;
+    }
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int col0 = tile * TV;
     const bool a_act = 2 * lane < DK, b_act = 2 * lane < TV;
-    const SeqView sv = seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh);
-    const size_t seq_k = sv.off_k, seq_v = sv.off_v;
-    const int N = sv.N, NC = sv.NC;
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qsrc = static_cast<const T*>(p.q);
     const T* bsrc = static_cast<const T*>(p.bsrc);
-    T* ws = static_cast<T*>(p.ws) + sv.chunk0 * DK * DV;
 
     // raw rows of the chunk being prefetched; inactive lanes read column 0 and are ignored
     RawRows<RW> raw_f, raw_q, raw_b;
     const int col_a = a_act ? 2 * lane : 0, col_b = col0 + (b_act ? 2 * lane : 0);
-    auto load_chunk = [&](int n) {
+    auto load_chunk = [&](const SeqView& s, int n) {
         const int row0 = n * C + RW * w;
-        load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_a, row0, N, gate_bf16);
-        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, seq_k, ld_k, col_a, row0, N, is_bf16_type<T>());
-        load_rows<RW>(raw_b, bsrc, seq_v, ld_v, col_b, row0, N, is_bf16_type<T>());
+        load_rows<RW>(raw_f, p.f, s.off_k, ld_k, col_a, row0, s.N, gate_bf16);
+        if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, s.off_k, ld_k, col_a, row0, s.N, is_bf16_type<T>());
+        load_rows<RW>(raw_b, bsrc, s.off_v, ld_v, col_b, row0, s.N, is_bf16_type<T>());
     };
+    auto view = [&](int bh) { return seq_view<DENSE, DK, DV, true>(p.lay, p.N, p.NC, bh); };
 
-    // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
-    f32x16 acc[TPW];
-#pragma unroll
-    for (int j = 0; j < TPW; ++j) {
-        const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float x = 0.0f;
-            if (!ENDS && p.init) {
-                const float* s0 = p.init + (size_t)bh * DK * DV;
-                x = TRANS ? s0[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)]
-                          : s0[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32];
+    // A sequence without chunks ends in the slab it starts from (zero, and all gate products one,
+    // for a walk from zero); these are dealt with first, the walk below steps over them.
+    for (int b = bh_first; b < bh_end; b += bh_step) {
+        if (view(b).NC > 0) continue;
+        if (p.fin)
+            for (int idx = tid; idx < DK * TV; idx += kThreads) {
+                const size_t e = (size_t)b * DK * DV + (size_t)(idx / TV) * DV + col0 + idx % TV;
+                p.fin[e] = (!ENDS && p.init) ? p.init[e] : 0.0f;
             }
-            acc[j][v] = x;
-        }
+        if (ENDS && tile == 0 && tid < DK && p.decay) p.decay[(size_t)b * DK + tid] = 1.0f;
     }
 
-    float run_decay = 1.0f;      // ENDS: thread t < DK, gate product of channel t so far
-    if (NC > 0) load_chunk(REVERSE ? NC - 1 : 0);
+    // The walk: chunk `it` (in walking order) of sequence bh, then the next one, which may be the
+    // first chunk of the group's next sequence with tokens.  The rows of the next chunk are always
+    // requested (past the end: the current ones again), so that the number of loads in flight never
+    // depends on where the walk is.
+    int next_open = bh_first;                    // first sequence not opened yet
+    auto open_sequence = [&](SeqView& v, int& bh_out) {
+        while (next_open < bh_end) {
+            const int b = next_open;
+            next_open += bh_step;
+            v = view(b);
+            if (v.NC > 0) { bh_out = b; return true; }
+        }
+        return false;
+    };
+    SeqView sv, sv_next;
+    int bh = 0, bh_next = 0, it = 0, it_next = 0;
+    bool more = open_sequence(sv, bh);
+    if (!more) return;                           // (uniform, before any barrier)
+    load_chunk(sv, REVERSE ? sv.NC - 1 : 0);
 
-    for (int it = 0; it < NC; ++it) {
+    f32x16 acc[TPW];             // accumulator tiles of this wave: tile id = w + 4j -> (at, bt)
+    float run_decay = 1.0f;      // ENDS: thread t < DK, gate product of channel t so far
+
+    while (more) {
+        const int N = sv.N, NC = sv.NC;
         const int n = REVERSE ? NC - 1 - it : it;
+        // the chunk after this one (scalar work only)
+        bool more_next = true;
+        if (it + 1 < NC) { sv_next = sv; bh_next = bh; it_next = it + 1; }
+        else { more_next = open_sequence(sv_next, bh_next); it_next = 0; }
+        if (it == 0) {
+            // a sequence starts: its initial slab, the product of its gates from one
+            run_decay = 1.0f;
+#pragma unroll
+            for (int j = 0; j < TPW; ++j) {
+                const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float x = 0.0f;
+                    if (!ENDS && p.init) {
+                        const float* s0 = p.init + (size_t)bh * DK * DV;
+                        x = TRANS ? s0[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)]
+                                  : s0[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32];
+                    }
+                    acc[j][v] = x;
+                }
+            }
+        }
+        T* ws = static_cast<T*>(p.ws) + sv.chunk0 * DK * DV;
         f32x2 rf[RW], rq[RW], rb[RW];
         {
             const int row0 = n * C + RW * w;
@@ -163,7 +225,13 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
             store_run<T, RW>(BT + (2 * lane) * PC + RW * w, x0);
             store_run<T, RW>(BT + (2 * lane + 1) * PC + RW * w, x1);
         }
-        if (it + 1 < NC) load_chunk(REVERSE ? n - 1 : n + 1);   // in flight during the MFMAs
+        // the next chunk's rows are in flight during the MFMAs (after the last chunk: this one's again)
+        {
+            SeqView pf = sv;
+            int pn = n;
+            if (more_next) { pf = sv_next; pn = REVERSE ? sv_next.NC - 1 - it_next : it_next; }
+            load_chunk(pf, pn);
+        }
         __syncthreads();
 
         // ---- hand the slab as it stands (state entering / gradient leaving chunk n) to the workspace
@@ -218,20 +286,23 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
                 else       M::mma(acc[j], fa, fb);
             }
         }
-    }
-
-    if (ENDS && tile == 0 && tid < DK && p.decay) p.decay[(size_t)bh * DK + tid] = run_decay;
-    if (p.fin) {
-        float* s1 = p.fin + (size_t)bh * DK * DV;
+        if (it == NC - 1) {
+            // the sequence ends: the slab as it stands, and the product of the gates it passed
+            if (ENDS && tile == 0 && tid < DK && p.decay) p.decay[(size_t)bh * DK + tid] = run_decay;
+            if (p.fin) {
+                float* s1 = p.fin + (size_t)bh * DK * DV;
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-            const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
+                for (int j = 0; j < TPW; ++j) {
+                    const int id = w + kWaves * j, at = id % NAT, bt = id / NAT;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                if (TRANS) s1[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)] = acc[j][v];
-                else       s1[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32] = acc[j][v];
+                    for (int v = 0; v < 16; ++v) {
+                        if (TRANS) s1[(size_t)(32 * at + r32) * DV + col0 + 32 * bt + acc_row(v, lane)] = acc[j][v];
+                        else       s1[(size_t)(32 * at + acc_row(v, lane)) * DV + col0 + 32 * bt + r32] = acc[j][v];
+                    }
+                }
             }
         }
+        sv = sv_next; bh = bh_next; it = it_next; more = more_next;
     }
 }
 
@@ -267,7 +338,7 @@ static hipError_t launch_pair_one(const SeqDims& d, const SweepParams& ps0, cons
     auto kern = sweep_pair_kernel<T, DK, DV, TV, ENDS>;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds);
     if (e != hipSuccess) return e;
-    const int half = (d.BH + 7) / 8 * 8 * ps.n_tile;
+    const int half = (sweep_walkers<ENDS>(d) + 7) / 8 * 8 * ps.n_tile;
     hipLaunchKernelGGL(kern, dim3(2 * half), dim3(kThreads), lds, stream, ps, pg, half);
     return hipGetLastError();
 }
@@ -280,10 +351,10 @@ static hipError_t launch_pair_tv(const SeqDims& d, const SweepParams& ps, const 
     // only as long as all workgroups still find a compute unit of their own (two sweeps share the
     // grid: 2 x 32 sequences x 4 slabs, 2 x 64 x 2, 2 x 128 x 1 fill the 256 units).
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH <= 32) return launch_pair_one<T, DK, DV, 32, ENDS>(d, ps, pg, stream);
+        if (sweep_walkers<ENDS>(d) <= 32) return launch_pair_one<T, DK, DV, 32, ENDS>(d, ps, pg, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH <= 64) return launch_pair_one<T, DK, DV, 64, ENDS>(d, ps, pg, stream);
+        if (sweep_walkers<ENDS>(d) <= 64) return launch_pair_one<T, DK, DV, 64, ENDS>(d, ps, pg, stream);
     }
     return launch_pair_one<T, DK, DV, DV, ENDS>(d, ps, pg, stream);
 }
@@ -298,7 +369,7 @@ static hipError_t launch_one(const SeqDims& d, const SweepParams& p0, hipStream_
     auto kern = sweep_kernel<T, DK, DV, TV, MODE, ENDS>;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds);
     if (e != hipSuccess) return e;
-    const int seq_pad = (d.BH + 7) / 8 * 8;
+    const int seq_pad = (sweep_walkers<ENDS>(d) + 7) / 8 * 8;
     hipLaunchKernelGGL(kern, dim3(seq_pad * p.n_tile), dim3(kThreads), lds, stream, p);
     return hipGetLastError();
 }
@@ -308,10 +379,10 @@ static hipError_t launch_tv(const SeqDims& d, const SweepParams& p, hipStream_t 
 {
     // Narrow slabs when there are few sequences, as long as every workgroup gets a compute unit of its own.
     if constexpr (DV == 128 && DK == 128) {
-        if (d.BH <= 64) return launch_one<T, DK, DV, 32, MODE, ENDS>(d, p, stream);
+        if (sweep_walkers<ENDS>(d) <= 64) return launch_one<T, DK, DV, 32, MODE, ENDS>(d, p, stream);
     }
     if constexpr (DV == 128) {
-        if (d.BH <= 128) return launch_one<T, DK, DV, 64, MODE, ENDS>(d, p, stream);
+        if (sweep_walkers<ENDS>(d) <= 128) return launch_one<T, DK, DV, 64, MODE, ENDS>(d, p, stream);
     }
     return launch_one<T, DK, DV, DV, MODE, ENDS>(d, p, stream);
 }

@@ -143,6 +143,36 @@ hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, 
     return hipGetLastError();
 }
 
+// Group g of G starts at the first entry e whose chunks-before count reaches g / G of all chunks
+// (bisection over the table's non-decreasing third array); the last group ends at the last entry,
+// so that empty entries at the end belong to a group too.
+__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
+{
+    const int* before = tab + 2 * (n_entries + 1);
+    const long long total = before[n_entries];
+    for (int grp = threadIdx.x; grp <= G; grp += kTabThreads) {
+        int first = n_entries;
+        if (grp < G) {
+            int lo = -1, hi = n_entries;                 // invariant: before[lo] G < grp total <= before[hi] G
+            const long long want = (long long)grp * total;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if ((long long)before[mid] * G >= want) hi = mid; else lo = mid;
+            }
+            first = hi;
+        }
+        groups[grp] = first;
+    }
+}
+
+size_t varlen_groups_bytes(int G) { return ((size_t)G + 1) * sizeof(int); }
+
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream)
+{
+    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, groups);
+    return hipGetLastError();
+}
+
 size_t varlen_run_table_bytes(int B, int R) { return varlen_table_bytes(R) + ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,

@@ -247,7 +247,7 @@ def test_hgrn1_workspace_and_error_codes():
 def test_varlen_workspace_and_error_codes():
     lib = binding.lib()
     s = shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1)
-    table = 256                                              # 4 * 7 ints, rounded up
+    table = 256                                              # 4 * 7 ints, rounded up (6 sequences: too few to be walked in groups)
     states = (1000 // 64 + 6) * 3 * 64 * 64 * 2              # worst split of 1000 tokens into 6 sequences
     assert binding.hgrn2_fwd_varlen_workspace_bytes(s) == table + states
     partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4 + 8 * 3 * 64 * 4     # per-wave shares of grad_beta of every chunk slot, then 8 slice sums per head
@@ -259,10 +259,11 @@ def test_varlen_workspace_and_error_codes():
     r256 = lambda x: (x + 255) // 256 * 256
     st = (32768 // 64 + 2) * 16 * 128 * 128 * 2
     Rf = 2 + (512 + 2) // 32 + 1
-    assert binding.hgrn2_fwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rf + 1) * 4 + 3 * 4) + st
+    groups = lambda R: r256((256 // 16 + 1) * 4) if R >= 256 // 16 else 0     # 16 groups of the runs of one head, given that many runs
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rf + 1) * 4 + 3 * 4) + groups(Rf) + st
                                                             + Rf * 16 * (128 * 128 + 128) * 4)
     Rb = 2 + (512 + 2) // 64 + 1
-    assert binding.hgrn2_bwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rb + 1) * 4 + 3 * 4) + 2 * st
+    assert binding.hgrn2_bwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rb + 1) * 4 + 3 * 4) + groups(Rb) + 2 * st
                                                             + 2 * Rb * 16 * 128 * 128 * 4 + Rb * 16 * 128 * 4
                                                             + (32768 // 64 + 2) * 16 * 8 * 128 * 4 + 8 * 16 * 128 * 4)
     big = 1 << 40

@@ -107,6 +107,32 @@ def test_varlen_document_mix_layer_width():
     run(6501, lens, 16, 128, 128, lb=0.5)
 
 
+@pytest.mark.parametrize("H,dk,dv,gate_dtype", [(16, 128, 128, "bf16"), (8, 128, 128, "f32"), (4, 64, 64, "bf16"), (2, 128, 64, "bf16")])
+def test_varlen_many_short_documents(H, dk, dv, gate_dtype):
+    """More sequences than workgroups: the walks take a group of consecutive sequences each, one
+    after the other.  Lengths of one token to a few chunks, empty sequences at the start, in the
+    middle (several in a row) and at the end, with every sequence's own initial and final state."""
+    rng = np.random.default_rng(6800 + H)
+    # (the walks go by groups from 256 / H sequences on)
+    lens = [0, 0] + [int(x) for x in rng.integers(1, 150 if H > 2 else 40, size=max(70, 256 // H + 12))]
+    for i in (5, 6, 7, 30, 51):
+        lens[i] = 0
+    lens += [64, 128, 1, 0, 0]
+    print("\n[varlen] H=%d dk=%d dv=%d, %d short documents (%d tokens) gate=%s"
+          % (H, dk, dv, len(lens), sum(lens), gate_dtype), flush=True)
+    run(6801 + H, lens, H, dk, dv, gate_dtype=gate_dtype)
+    run(6851 + H, lens, H, dk, dv, gate_dtype=gate_dtype, with_states=False)
+
+
+def test_varlen_one_chunk_documents_even_and_odd_counts():
+    """Groups whose chunk count is even and odd (the single-pass forward runs an even number of
+    passes and finishes the last sequence differently in the two cases)."""
+    for n_docs in (16, 17, 33):
+        lens = [64] * n_docs
+        print("\n[varlen] %d documents of 64 tokens, H=16" % n_docs, flush=True)
+        run(6900 + n_docs, lens, 16, 128, 128)
+
+
 def test_varlen_offsets_out_of_order_stay_in_bounds():
     """A non-monotone cu_seqlens is not an error the library can report (it is device data), but it
     must not reach outside the tensors: the call completes and the outputs of the well-formed
@@ -123,7 +149,7 @@ def test_varlen_offsets_out_of_order_stay_in_bounds():
     check("o[:100]", unpacked(o)[:, :100], ro[0], TOL["bf16"])
 
 
-@pytest.mark.parametrize("H,dk,dv,nseq", [(3, 64, 64, 5), (8, 128, 128, 10)])
+@pytest.mark.parametrize("H,dk,dv,nseq", [(3, 64, 64, 5), (8, 128, 128, 10), (16, 128, 128, 40), (8, 64, 128, 45)])
 def test_varlen_with_gate_formed_in_the_kernels(H, dk, dv, nseq):
     """Packed sequences with the pre-activations of the gate and the layer's lower bounds (Eq. 2):
     dz per token and dbeta summed over all sequences, against the oracle run per sequence."""
