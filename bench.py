@@ -566,6 +566,8 @@ def main():
             return timed(fn, reps=30)
         t_mix = run_varlen([0] + list(np.cumsum(lens)))
         t_eq = run_varlen([N * b for b in range(B + 1)])
+        # short documents: 1024, 256 and 64 tokens each (the walks then take groups of documents)
+        t_short = {L: run_varlen(list(range(0, T + 1, L))) for L in (1024, 256, 64)}
 
         def fixed_bnhd(i):          # the same packing seen as an equal-length [B][N][H][d] batch
             q, f, v, dO = (t.view(B, N, H, D) for t in vsets[i % 2])
@@ -580,7 +582,8 @@ def main():
                         "(median %d, longest %d)" % (T, H, D, len(lens), int(np.median(lens)), max(lens)),
             "fwd_bwd_us_document_mix": round(t_mix * 1e6, 1), "tokens_per_s_document_mix": round(T / t_mix, 1),
             "fwd_bwd_us_8_equal_sequences": round(t_eq * 1e6, 1), "tokens_per_s_8_equal_sequences": round(T / t_eq, 1),
-            "fwd_bwd_us_same_data_equal_length_entry_points": round(t_fix * 1e6, 1)}
+            "fwd_bwd_us_same_data_equal_length_entry_points": round(t_fix * 1e6, 1),
+            "fwd_bwd_us_equal_documents_of": {str(L): round(t * 1e6, 1) for L, t in t_short.items()}}
         del vsets
 
     # ---- prefill -> decode hand-off: the chunkwise forward leaves the state the decode step continues from ----
