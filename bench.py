@@ -75,6 +75,7 @@ def parse():
     ap.add_argument("--no-gated", action="store_true", help="skip the run with the gate formed inside the kernels")
     ap.add_argument("--no-long", action="store_true", help="skip the long-sequence shape (B=2, N=16384)")
     ap.add_argument("--no-layer", action="store_true", help="skip the layer run (projections + recurrence)")
+    ap.add_argument("--no-layers", action="store_true", help="skip the runs on the gates of the other layers (0, 23)")
     ap.add_argument("--no-small-gates", action="store_true", help="skip the small-gate modes (chunk = 32, 16)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy, the known-size kernel that rocprofv3 --pmc "
@@ -287,7 +288,7 @@ def main():
 
     # ---- the three layers configs[2] names (gates of layers 0, 12, 23 of the 24-layer stack) ----
     layers = {}
-    for layer in (0, 12, 23):
+    for layer in ((args.layer,) if args.no_layers else (0, 12, 23)):
         a = sets[0] if layer == args.layer else tuple(to_dev(x) for x in (lambda wl: (wl.q, wl.f, wl.v, wl.dO))(synth.config2(layer)))
         b = tuple(t.clone() for t in a)          # the same data at other addresses: no step finds its inputs in cache
         pair = (a, b)
@@ -355,7 +356,7 @@ def main():
             "tokens_per_s": round(tokens / t_layer, 1),
             "roofline_proj_fwd": {"bound": "mfma", "achieved": round(fl_f / t_pf / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                                   "unit": "TFLOP/s", "frac": round(fl_f / t_pf / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                                  "traffic": MEASURED_TRAFFIC_BYTES.get("hgru2_proj_kernel")},
+                                  "traffic": MEASURED_TRAFFIC_BYTES.get("proj_fwd_gemm")},
             "proj_bwd_TFLOPs": round(2 * fl_f / t_pb / 1e12, 1)}
         del xs, w3, dys, zl, vl2, ql, avl, yl, glq, glz, glv, glx, glw, wsl, wsp
 
@@ -394,6 +395,19 @@ def main():
         dtm = timed(gated_step_token_major, reps=50)
         result["gated"]["token_major_ms_per_step"] = round(dtm * 1e3, 4)
         result["gated"]["token_major_tokens_per_s"] = round(tokens / dtm, 1)
+
+        def gated_pair_token_major(i):     # ... and as a training pair (the forward pass keeps the states), as the layer uses it
+            q, _, v, dO = sets[i % 2]
+            binding.hgrn2_fwd_saving(tm(q), tm(zs[i % 2]), tm(v), None, beta=beta, o=tm(o), hT=hT, saved_states=saved[0],
+                                     workspace=wsg, layout=BNHD)
+            binding.hgrn2_bwd_saved(tm(q), tm(zs[i % 2]), tm(v), saved[0], tm(dO), None, beta=beta, workspace=wsg,
+                                    grad_q=tm(gq), grad_f=tm(gf), grad_v=tm(gv), layout=BNHD)
+
+        for i in range(10):
+            gated_pair_token_major(i)
+        dtp = timed(gated_pair_token_major, reps=50)
+        result["gated"]["token_major_training_pair_ms_per_step"] = round(dtp * 1e3, 4)
+        result["gated"]["token_major_training_pair_tokens_per_s"] = round(tokens / dtp, 1)
         del zs, wsg
 
     # ---- the same step in the small-gate modes: reference rows every 32 and every 16 tokens ----

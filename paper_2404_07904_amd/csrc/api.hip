@@ -200,8 +200,7 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     p.table_bytes += round256(varlen_run_table_bytes(s->B, p.R));
     p.state_bytes = round256((size_t)p.R * s->H * d.dk * d.dv * sizeof(float));
     p.decay_bytes = round256((size_t)p.R * s->H * d.dk * sizeof(float));
-    with_groups(p);
-    return p;
+    return p;             // (runs are many and equally long: a workgroup each)
 }
 
 // Builds the table(s) at the head of the workspace and points `d` at the one the kernels use;
@@ -226,7 +225,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     }
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
-        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
+        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, s->H, groups, stream);
         d->lay.groups = groups;
         d->lay.G = p.G;
     }
@@ -833,11 +832,26 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
             launch_sweep_pair(d, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
     } else if (d.lay.groups) {
-        // groups of whole sequences: one forward-state sweep, then the reverse walk that carries the
-        // state gradient in registers and produces the gradients chunk by chunk
-        if (launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess ||
-            launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
-                                     stream) != hipSuccess)
+        // Sequences walked in groups.  Two ways, and only the lengths (device data) tell which is
+        // faster: (1) one forward-state sweep, then the reverse walk that carries the state gradient
+        // in registers and produces the gradients chunk by chunk, as long as the largest group; (0)
+        // both sweeps and the per-chunk gradient kernel, which shares all chunks among the compute
+        // units.  The table kernel has chosen; the kernels of both are enqueued and those of the other
+        // way return at once.
+        SeqDims walk = d, split = d;
+        walk.lay.choice = split.lay.choice = d.lay.groups + d.lay.G + 1;
+        walk.lay.path = 1;
+        split.lay.path = 0;
+        if (shape->B < 4 * d.lay.G) {        // few sequences: longest first, a workgroup each, suits uneven lengths
+            split.lay.groups = nullptr;      // (with many, the walk is chosen nearly always, and a grid of
+            split.lay.G = 0;                 // groups that only has to return is the cheaper one)
+        }
+        if (launch_sweep(walk, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess ||
+            launch_bwd_fused_grouped(walk, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
+                                     stream) != hipSuccess ||
+            launch_sweep_pair(split, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess ||
+            (has_tokens &&
+             launch_bwd_grad(split, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess))
             return HGRN2_ERR_HIP;
         if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
         return HGRN2_OK;

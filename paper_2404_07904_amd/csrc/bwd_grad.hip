@@ -171,6 +171,10 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     float* ones = reinterpret_cast<float*>(smem + L::one);
     float* zeros = reinterpret_cast<float*>(smem + L::zero);
 
+    if constexpr (!DENSE) {
+        // a packed batch whose table chose the other backward pass: nothing to do here
+        if (p.lay.choice && table_read(p.lay.choice, 0) != p.lay.path) return;
+    }
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
     constexpr bool gate_bf16 = GATE_BF16;

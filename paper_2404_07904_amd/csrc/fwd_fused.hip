@@ -646,9 +646,10 @@ __global__ __launch_bounds__(kFusedThreads) void fwd_fused_grouped_kernel(FwdFus
     fwd_fused_body<GATE_BF16, NSPLIT, false, true>(p);
 }
 
-// Groups of a packed batch's sequences are walked by one workgroup each when there are more
-// sequences than groups (with one sequence per group the plain walk does the same with less bookkeeping).
-static bool fused_grouped(const SeqDims& d) { return d.lay.vl && d.lay.groups && d.lay.B > d.lay.G; }
+// Groups of a packed batch's sequences are walked by one workgroup each from two sequences per
+// group on (with fewer, a workgroup per sequence, longest first, balances uneven lengths better and
+// needs less bookkeeping).
+static bool fused_grouped(const SeqDims& d) { return d.lay.vl && d.lay.groups && d.lay.B >= 2 * d.lay.G; }
 // workgroups' worth of independent walks
 static int fused_walkers(const SeqDims& d) { return fused_grouped(d) ? d.lay.G * d.lay.H : d.BH; }
 

@@ -31,6 +31,13 @@ struct TokenLayout {
     // back.  Null: one workgroup per sequence.
     const int* groups = nullptr;
     int G = 0;
+    // The table kernel's choice between the two backward passes of such a batch (*choice = 1: the
+    // fused reverse walk over groups; 0: the two sweeps, a workgroup per sequence, and the per-chunk
+    // gradient kernel), made from the sizes of the groups; it is the int behind the group array.  The
+    // kernels of both passes are enqueued, each with `path` set to the choice it belongs to, and
+    // those of the other one return at once.  Null: no choice to make.
+    const int* choice = nullptr;
+    int path = -1;
     // Segmented sweeps: each of the sequences the strides describe is cut into `seg` runs of whole
     // chunks that the sequential kernels treat as sequences of their own, `seg` per original one,
     // numbered run-fastest.  The kernels' N and NC are then those of a full run; `n_tokens` keeps
@@ -236,9 +243,11 @@ hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_c
                                    int* first_run, hipStream_t stream);
 // Groups of a table's sequences (sequence or run table with n_entries entries): G + 1 ints, group g
 // = entries [groups[g], groups[g + 1]), cut where the chunk count reaches g / G of the total, so that
-// groups hold about equally many chunks (a group is never finer than one entry).
+// groups hold about equally many chunks (a group is never finer than one entry); and one more int,
+// the choice of backward pass (TokenLayout::path): the reverse walk over groups takes as long as its
+// largest group, the per-chunk pass as long as all chunks shared among the compute units.
 size_t varlen_groups_bytes(int G);
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int H, int* groups, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);

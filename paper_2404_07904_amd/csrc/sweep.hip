@@ -72,6 +72,10 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     // slab to its own final one), with the first rows of the next sequence already in flight during
     // the last chunk of the current one: a batch of many short sequences then costs a workgroup's
     // start-up and a trip to memory once per group, not once per sequence.
+    if constexpr (!DENSE) {
+        // a packed batch whose table chose the other backward pass: nothing to do here
+        if (p.lay.choice && table_read(p.lay.choice, 0) != p.lay.path) return;
+    }
     int id, tile;
     xcd_map(block_id, p.n_tile, id, tile);
     int bh_first, bh_end, bh_step;

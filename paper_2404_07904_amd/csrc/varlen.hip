@@ -146,7 +146,7 @@ hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, 
 // Group g of G starts at the first entry e whose chunks-before count reaches g / G of all chunks
 // (bisection over the table's non-decreasing third array); the last group ends at the last entry,
 // so that empty entries at the end belong to a group too.
-__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
+__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int H, int* groups)
 {
     const int* before = tab + 2 * (n_entries + 1);
     const long long total = before[n_entries];
@@ -163,13 +163,28 @@ __global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* t
         }
         groups[grp] = first;
     }
+    __syncthreads();
+    // Which backward pass: one chunk costs a reverse walk about 10 us, the forward-state sweep it
+    // needs and the two sweeps plus the per-chunk kernel of the other pass about 4.5 and 20 us per
+    // chunk of every compute unit's share (measured at 128-wide heads): the walk wins while its
+    // largest group holds less than 1.5 times that share.
+    __shared__ int largest[kTabThreads];
+    int mine = 0;
+    for (int grp = threadIdx.x; grp < G; grp += kTabThreads) mine = max(mine, before[groups[grp + 1]] - before[groups[grp]]);
+    largest[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int m = 0;
+        for (int j = 0; j < kTabThreads; ++j) m = max(m, largest[j]);
+        groups[G + 1] = (2LL * m * 256 < 3LL * total * H) ? 1 : 0;
+    }
 }
 
-size_t varlen_groups_bytes(int G) { return ((size_t)G + 1) * sizeof(int); }
+size_t varlen_groups_bytes(int G) { return ((size_t)G + 2) * sizeof(int); }
 
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream)
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int H, int* groups, hipStream_t stream)
 {
-    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, groups);
+    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, H, groups);
     return hipGetLastError();
 }
 

@@ -30,7 +30,10 @@ KERNELS = {
     "step_kernel": "step_kernel",
     "hgrn1_fwd_kernel": "hgrn1_fwd_kernel",
     "hgrn1_bwd_kernel": "hgrn1_bwd_kernel",
-    "hgru2_proj_kernel": "hgru2_proj",
+    "proj_fwd_gemm": "gemm_dl_kernel<0>",
+    "proj_dx_gemm": "gemm_dl_kernel<1>",
+    "proj_dw_gemm": "gemm_kernel<true, true, 2",
+    "proj_dact_kernel": "proj_dact_kernel",
 }
 
 

@@ -259,7 +259,7 @@ def test_varlen_workspace_and_error_codes():
     r256 = lambda x: (x + 255) // 256 * 256
     st = (32768 // 64 + 2) * 16 * 128 * 128 * 2
     Rf = 2 + (512 + 2) // 32 + 1
-    groups = lambda R: r256((256 // 16 + 1) * 4) if R >= 256 // 16 else 0     # 16 groups of the runs of one head, given that many runs
+    groups = lambda R: 0                                     # a batch cut into runs is not walked in groups
     assert binding.hgrn2_fwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rf + 1) * 4 + 3 * 4) + groups(Rf) + st
                                                             + Rf * 16 * (128 * 128 + 128) * 4)
     Rb = 2 + (512 + 2) // 64 + 1
@@ -277,6 +277,10 @@ def test_varlen_workspace_and_error_codes():
     assert fwd(s, n=table + states - 1) == E_WS
     assert fwd(s, ws=None) == E_WS
     assert fwd(shape(B=0, layout=1), cu=None, q=None, o=None, ws=None, n=0) == OK
+    # many short sequences are walked in groups: 16 per head at H = 16, two more ints than groups
+    many = shape(B=40, H=16, N=4096, dk=128, dv=128, layout=1)
+    st40 = (4096 // 64 + 40) * 16 * 128 * 128 * 2
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(many) == r256(4 * 41 * 4) + r256((16 + 2) * 4) + st40
     bwd = lambda s_, cu=FAKE, gq=FAKE, ws=FAKE_WS, n=big, beta=None, gb=None: lib.hgrn2_bwd_varlen(
         ctypes.byref(s_), cu, FAKE, FAKE, beta, FAKE, None, FAKE, None, gq, FAKE, gb, FAKE, None, ws, n, None)
     assert bwd(s, beta=FAKE, gb=None) == E_NULL                 # lower bounds given: their gradient must have a place

@@ -124,6 +124,15 @@ def test_varlen_many_short_documents(H, dk, dv, gate_dtype):
     run(6851 + H, lens, H, dk, dv, gate_dtype=gate_dtype, with_states=False)
 
 
+def test_varlen_one_long_document_among_short_ones():
+    """Enough sequences for groups, but one group far larger than the others: the table kernel then
+    sends the backward pass through the two sweeps and the per-chunk kernel instead of the reverse
+    walk over groups (both are enqueued; the choice is made on the device)."""
+    lens = [40, 3000] + [50, 7, 64, 90] * 5
+    print("\n[varlen] H=16, one document of 3000 tokens among %d short ones" % (len(lens) - 1), flush=True)
+    run(6950, lens, 16, 128, 128)
+
+
 def test_varlen_one_chunk_documents_even_and_odd_counts():
     """Groups whose chunk count is even and odd (the single-pass forward runs an even number of
     passes and finishes the last sequence differently in the two cases)."""
