@@ -32,7 +32,7 @@ namespace hgrn2 {
 constexpr int kGemmThreads = 512;
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int PKT = BK + 8;        // pitch of a tile kept [row][k]
-constexpr int PXT = 256 + 24;      // pitch of a tile kept [k][row]: transpose reads want rows 12 banks apart
+constexpr int PXT = 256 + 32;      // pitch of a tile kept [k][row]: a transpose read takes 4 rows x 64 bytes per half wave, so rows 16 banks apart
 constexpr int kTileElems = (BM * PKT > BK * PXT) ? BM * PKT : BK * PXT;
 constexpr int kXcds = 8;         // accelerator dies; consecutive workgroup ids land on consecutive dies
 constexpr int kBandRows = 4;     // row blocks per band of the workgroup -> tile order
