@@ -155,14 +155,17 @@ def main():
     ws_a = torch.empty(one_set, dtype=torch.uint8, device=dev)
     ws_b = torch.empty(one_set, dtype=torch.uint8, device=dev)
 
-    def timed(fn, reps=30):
+    def timed_all(fn, reps=30):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for i, (a, b) in enumerate(ev):
             a.record()
             fn(i)
             b.record()
         torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in ev) / reps * 1e-3   # seconds
+        return [a.elapsed_time(b) * 1e-3 for a, b in ev]             # seconds, per call
+
+    def timed(fn, reps=30):
+        return sum(timed_all(fn, reps)) / reps                       # seconds
 
     def s_fwd(i):
         q, f, v, _ = sets[i % 2]
@@ -242,12 +245,16 @@ def main():
     # events right after the headline, on the stream it is launched on
     for i in range(4):
         s_train_bwd(i)
-    dom_s = timed(s_train_bwd, reps=max(20, args.steps))
+    # (the median of the per-launch times: one launch delayed by something else on the machine would
+    # otherwise move the figure; mean, minimum and maximum are reported next to it)
+    dom_all = sorted(timed_all(s_train_bwd, reps=max(20, args.steps)))
+    dom_s = dom_all[len(dom_all) // 2]
     dom_bytes = 7 * seq_k
     achieved = dom_bytes / dom_s / 1e9
     roofline = {"kernel": "bwd_fused_kernel (hgrn2_bwd_saved)", "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "us": round(dom_s * 1e6, 2), "algorithmic_bytes": dom_bytes,
+                "us": round(dom_s * 1e6, 2), "us_mean_min_max": [round(x * 1e6, 1) for x in (sum(dom_all) / len(dom_all), dom_all[0], dom_all[-1])],
+                "algorithmic_bytes": dom_bytes,
                 "traffic": MEASURED_TRAFFIC_BYTES.get("bwd_fused_kernel")}
 
     flops = token_heads * ((4 * D * D + CHUNK * 2 * D) + (8 * D * D + CHUNK * 5 * D))   # fwd + bwd, algorithmic

@@ -727,8 +727,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     float gs0[RW], gs1[RW], dk0[RW], dk1[RW];
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
-    convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
-    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
+    // (gates formed from pre-activations are kept instead: a second round of exponentials and reciprocals costs more than 16 registers)
+    if (!p.beta) convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
     if constexpr (FUSED) {
         // the gate products again (32 multiplications) rather than 32 registers kept through the contractions
         asm volatile("" : "+v"(rf[0].x), "+v"(rf[0].y));
