@@ -95,6 +95,8 @@ def test_varlen_fused_forward_path(gate_dtype):
 def test_varlen_all_empty():
     print("\n[varlen] T = 0", flush=True)
     run(6400, [0, 0, 0], 2, 64, 64)
+    print("[varlen] T = 0, enough sequences for groups", flush=True)
+    run(6401, [0] * 20, 16, 128, 128)
 
 
 def test_varlen_document_mix_layer_width():
