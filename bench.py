@@ -529,9 +529,20 @@ def main():
             f1, i1, o1, dy1 = sets1[i % 2]
             binding.hgrn1_bwd(f1, i1, o1, dy1, None, None, workspace=ws1)
 
+        ws1p = [torch.empty_like(ws1) for _ in range(2)]     # training pair: one workspace per input set, as a step keeps it
+
+        def h1_fwd_keep(i):
+            f1, i1, o1, _ = sets1[i % 2]
+            binding.hgrn1_fwd(f1, i1, o1, None, y=y1, want_hN=False, workspace=ws1p[i % 2])
+
+        def h1_bwd_saved(i):
+            f1, i1, o1, dy1 = sets1[i % 2]
+            binding.hgrn1_bwd(f1, i1, o1, dy1, None, None, workspace=ws1p[i % 2], saved=True)
+
         for i in range(6):
-            h1_fwd(i); h1_bwd(i)
+            h1_fwd(i); h1_bwd(i); h1_fwd_keep(i); h1_bwd_saved(i)
         tf, tb = timed(h1_fwd, reps=50), timed(h1_bwd, reps=50)
+        tbs = timed(h1_bwd_saved, reps=50)
         # the same layer from its pre-activations (Eq. 1 activations and the Eq. 2 bound formed in the kernels);
         # the N(0,1) tensors stand in for zf, zi, zo
         beta1 = torch.full((d1,), lb1, dtype=torch.float32, device=dev)
@@ -550,16 +561,17 @@ def main():
         e1 = B * N * d1 * el
         result["hgrn1"] = {
             "workload": "element-wise recurrence (Eq. 1), B=%d N=%d d=%d bf16, same gate statistics" % (B, N, d1),
-            "fwd_us": round(tf * 1e6, 1), "bwd_us": round(tb * 1e6, 1),
+            "fwd_us": round(tf * 1e6, 1), "bwd_us": round(tb * 1e6, 1), "bwd_saved_us": round(tbs * 1e6, 1),
             "fwd_act_us": round(tfa * 1e6, 1), "bwd_act_us": round(tba * 1e6, 1),
-            "tokens_per_s_fwd_bwd": round(tokens / (tf + tb), 1),
+            "tokens_per_s_fwd_bwd": round(tokens / (tf + tbs), 1),
             "roofline_fwd": {"bound": "hbm", "achieved": round(4 * e1 / tf / 1e9, 1), "peak": HBM_PEAK_GBS,
                              "unit": "GB/s", "frac": round(4 * e1 / tf / 1e9 / HBM_PEAK_GBS, 4),
                              "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_fwd_kernel")},
-            "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tb / 1e9, 1), "peak": HBM_PEAK_GBS,
-                             "unit": "GB/s", "frac": round(7 * e1 / tb / 1e9 / HBM_PEAK_GBS, 4),
-                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_bwd_kernel")}}
-        del sets1, ws1, y1
+            "roofline_bwd": {"bound": "hbm", "achieved": round(7 * e1 / tbs / 1e9, 1), "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": round(7 * e1 / tbs / 1e9 / HBM_PEAK_GBS, 4),
+                             "kernel": "hgrn1_bwd_kernel (hgrn1_bwd_saved: the forward pass of the step kept the segment states)",
+                             "traffic": MEASURED_TRAFFIC_BYTES.get("hgrn1_bwd_saved_kernel")}}
+        del sets1, ws1, y1, ws1p
 
     # ---- variable-length batch: the same 16384 tokens per head, packed as documents of mixed length ----
     if not args.no_varlen:

@@ -299,6 +299,23 @@ int hgrn1_bwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gat
                   float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The backward passes of a training step whose forward pass has just run: hgrn1_fwd / hgrn1_fwd_act
+ * leave the state entering every 16-token segment of every sequence in their workspace (a few MB;
+ * the reverse mode of Eq. 1 needs h_{t-1} at every token), and hgrn1_bwd_saved / hgrn1_bwd_act_saved
+ * are hgrn1_bwd / hgrn1_bwd_act that read them there instead of walking f and i forwards once more.
+ * The workspace must be the one the forward call of the same B, N, d, inputs and h0 was given, untouched
+ * since (hgrn1_bwd / hgrn1_bwd_act overwrite it); everything else as for the calls above.
+ */
+int hgrn1_bwd_saved(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+                    const void* i, const void* o, const float* h0, const void* grad_y, const float* grad_hN,
+                    void* grad_f, void* grad_i, void* grad_o, float* grad_h0, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+int hgrn1_bwd_act_saved(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                        const void* zi, const void* zo, const float* beta, const float* h0, const void* grad_y,
+                        const float* grad_hN, void* grad_zf, void* grad_zi, void* grad_zo, float* grad_beta,
+                        float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Stage entry points.  hgrn2_fwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_FWD) followed by
  * hgrn2_fwd_readout; hgrn2_bwd is hgrn2_state_sweep(HGRN2_SWEEP_STATE_BWD), then
  * hgrn2_state_sweep(HGRN2_SWEEP_STATE_GRAD), then hgrn2_bwd_chunk_grads.  They exist for callers

@@ -18,7 +18,7 @@ HGRN2_LAYOUT_BHND, HGRN2_LAYOUT_BNHD = 0, 1
 STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ERR_UNSUPPORTED",
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
-           "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
+           "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn1_bwd_saved", "hgrn1_bwd_act_saved", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
            "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
            "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc",
@@ -94,6 +94,10 @@ def lib() -> ctypes.CDLL:
         L.hgrn1_fwd_act.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn1_bwd_act.restype = ctypes.c_int
         L.hgrn1_bwd_act.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn1_bwd_saved.restype = ctypes.c_int
+        L.hgrn1_bwd_saved.argtypes = L.hgrn1_bwd.argtypes
+        L.hgrn1_bwd_act_saved.restype = ctypes.c_int
+        L.hgrn1_bwd_act_saved.argtypes = L.hgrn1_bwd_act.argtypes
         L.hgrn2_step.restype = ctypes.c_int
         L.hgrn2_step.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
         L.hgrn2_step_gated.restype = ctypes.c_int
@@ -496,16 +500,19 @@ def hgrn1_fwd(f, i, o, h0=None, *, want_hN=True, y=None, hN=None, workspace=None
     return y, hN
 
 
-def hgrn1_bwd(f, i, o, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None):
-    """grad_f, grad_i, grad_o, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN)."""
+def hgrn1_bwd(f, i, o, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None, saved=False):
+    """grad_f, grad_i, grad_o, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN).  saved=True calls
+    hgrn1_bwd_saved: `workspace` is then the one hgrn1_fwd of the same inputs was given."""
     B, N, d = i.shape
     gf, gi, go = torch.empty_like(i), torch.empty_like(i), torch.empty_like(i)
     gh0 = torch.empty((B, d), dtype=torch.float32, device=i.device) if want_grad_h0 else None
+    assert workspace is not None or not saved
     ws = _workspace(hgrn1_workspace_bytes(B, N, d), i.device, workspace)
-    rc = lib().hgrn1_bwd(B, N, d, _dt(i), _dt(f), _ptr(f), _ptr(i), _ptr(o), _ptr(h0), _ptr(grad_y), _ptr(grad_hN),
-                         _ptr(gf), _ptr(gi), _ptr(go), _ptr(gh0), _ptr(ws), ws.numel(), _stream())
+    fn = lib().hgrn1_bwd_saved if saved else lib().hgrn1_bwd
+    rc = fn(B, N, d, _dt(i), _dt(f), _ptr(f), _ptr(i), _ptr(o), _ptr(h0), _ptr(grad_y), _ptr(grad_hN),
+            _ptr(gf), _ptr(gi), _ptr(go), _ptr(gh0), _ptr(ws), ws.numel(), _stream())
     if rc != 0:
-        raise Hgrn2Error(rc, "hgrn1_bwd")
+        raise Hgrn2Error(rc, "hgrn1_bwd_saved" if saved else "hgrn1_bwd")
     return gf, gi, go, gh0
 
 
@@ -526,18 +533,21 @@ def hgrn1_fwd_act(zf, zi, zo, beta, h0=None, *, want_hN=True, y=None, hN=None, w
     return y, hN
 
 
-def hgrn1_bwd_act(zf, zi, zo, beta, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None):
-    """grad_zf, grad_zi, grad_zo, grad_beta, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN)."""
+def hgrn1_bwd_act(zf, zi, zo, beta, grad_y, h0=None, grad_hN=None, *, want_grad_h0=False, workspace=None, saved=False):
+    """grad_zf, grad_zi, grad_zo, grad_beta, grad_h0 of L = sum(y*grad_y) + sum(hN*grad_hN).  saved=True
+    calls hgrn1_bwd_act_saved: `workspace` is then the one hgrn1_fwd_act of the same inputs was given."""
     B, N, d = zf.shape
+    assert workspace is not None or not saved
     gf, gi, go = torch.empty_like(zi), torch.empty_like(zi), torch.empty_like(zi)
     gb = torch.empty((d,), dtype=torch.float32, device=zf.device)
     gh0 = torch.empty((B, d), dtype=torch.float32, device=zf.device) if want_grad_h0 else None
     ws = _workspace(hgrn1_workspace_bytes(B, N, d), zf.device, workspace)
-    rc = lib().hgrn1_bwd_act(B, N, d, _dt(zi), _dt(zf), _ptr(zf), _ptr(zi), _ptr(zo), _ptr(beta), _ptr(h0),
-                             _ptr(grad_y), _ptr(grad_hN), _ptr(gf), _ptr(gi), _ptr(go), _ptr(gb), _ptr(gh0), _ptr(ws),
-                             ws.numel(), _stream())
+    fn = lib().hgrn1_bwd_act_saved if saved else lib().hgrn1_bwd_act
+    rc = fn(B, N, d, _dt(zi), _dt(zf), _ptr(zf), _ptr(zi), _ptr(zo), _ptr(beta), _ptr(h0),
+            _ptr(grad_y), _ptr(grad_hN), _ptr(gf), _ptr(gi), _ptr(go), _ptr(gb), _ptr(gh0), _ptr(ws),
+            ws.numel(), _stream())
     if rc != 0:
-        raise Hgrn2Error(rc, "hgrn1_bwd_act")
+        raise Hgrn2Error(rc, "hgrn1_bwd_act_saved" if saved else "hgrn1_bwd_act")
     return gf, gi, go, gb, gh0
 
 

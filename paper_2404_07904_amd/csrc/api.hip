@@ -1034,7 +1034,7 @@ static int h1_fwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_
 static int h1_bwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
                        const void* i, const void* o, const float* beta, bool act, const float* h0, const void* grad_y,
                        const float* grad_hN, void* grad_f, void* grad_i, void* grad_o, float* grad_beta,
-                       float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+                       float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream, bool states_saved = false)
 {
     const int rc = h1_check(B, N, d, io_dtype, gate_dtype);
     if (rc != HGRN2_OK) return rc;
@@ -1049,7 +1049,7 @@ static int h1_bwd_impl(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_
         if (launch_zero_floats(grad_beta, (size_t)d, stream) != hipSuccess) return HGRN2_ERR_HIP;
     }
     if (launch_hgrn1_bwd(B, N, d, gate_dtype == HGRN2_BF16, f, i, o, act ? beta : nullptr, h0, grad_y, grad_hN, grad_f,
-                         grad_i, grad_o, act && has_tokens ? grad_beta : nullptr, grad_h0, workspace, stream) != hipSuccess)
+                         grad_i, grad_o, act && has_tokens ? grad_beta : nullptr, grad_h0, workspace, states_saved, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
@@ -1086,6 +1086,24 @@ int hgrn1_bwd_act(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gat
 {
     return h1_bwd_impl(B, N, d, io_dtype, gate_dtype, zf, zi, zo, beta, true, h0, grad_y, grad_hN, grad_zf, grad_zi,
                        grad_zo, grad_beta, grad_h0, workspace, workspace_bytes, hip_stream);
+}
+
+int hgrn1_bwd_saved(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* f,
+                    const void* i, const void* o, const float* h0, const void* grad_y, const float* grad_hN,
+                    void* grad_f, void* grad_i, void* grad_o, float* grad_h0, void* workspace, size_t workspace_bytes,
+                    void* hip_stream)
+{
+    return h1_bwd_impl(B, N, d, io_dtype, gate_dtype, f, i, o, nullptr, false, h0, grad_y, grad_hN, grad_f, grad_i,
+                       grad_o, nullptr, grad_h0, workspace, workspace_bytes, hip_stream, true);
+}
+
+int hgrn1_bwd_act_saved(int32_t B, int32_t N, int32_t d, int32_t io_dtype, int32_t gate_dtype, const void* zf,
+                        const void* zi, const void* zo, const float* beta, const float* h0, const void* grad_y,
+                        const float* grad_hN, void* grad_zf, void* grad_zi, void* grad_zo, float* grad_beta,
+                        float* grad_h0, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return h1_bwd_impl(B, N, d, io_dtype, gate_dtype, zf, zi, zo, beta, true, h0, grad_y, grad_hN, grad_zf, grad_zi,
+                       grad_zo, grad_beta, grad_h0, workspace, workspace_bytes, hip_stream, true);
 }
 
 const char* hgrn2_status_string(int status)

@@ -63,6 +63,7 @@ struct H1Params {
     float* carry;         // [B][NBLK * kH1Segs][d]: state entering every segment (backward)
     float* dbeta_part;    // [B][d]: every sequence's share of the gradient of beta (act backward)
     int B, N, d, NBLK, NCB;
+    int NBLK16;           // blocks of 16-token segments: the granularity at which the forward pass leaves the states in `carry`
 };
 
 // A channel pair as it sits in memory: packed bf16 (one register) or two floats.
@@ -234,6 +235,9 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
         // 2. state entering this half-wave's segment, state leaving the block
         f32x2 mine;
         carry = h1_chain<true>(sA[par], sH[par], vs, cp, carry, mine);
+        // kept for a backward pass of the same step (hgrn1_bwd_saved): 8 bytes per lane and block
+        if (p.carry && blk < p.NBLK)
+            *reinterpret_cast<f32x2*>(p.carry + ((size_t)b * p.NBLK * kH1Segs + (size_t)blk * kH1Segs + vs) * p.d + c0) = mine;
         // 3. outputs
         const H1Rsrc ry = h1_rows_from(p.y, seq, blk * BLOCK, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
@@ -267,7 +271,9 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_fwd_kernel(H1Params p)
 // act forms, through the activations (s = sigmoid):
 //   dzo = do o (1 - o),   dzi = di s(zi) (1 + zi (1 - s(zi))),
 //   dzf = df (f - beta)(1 - f) / (1 - beta),   dbeta = sum over batch and time of df (1 - f) / (1 - beta)
-template <bool GATE_BF16, bool ACT>
+// SAVED: the forward pass of the same step has left the state entering every 16-token segment in
+// `carry`; the forward phase below (a second pass over f and i) is then left out.
+template <bool GATE_BF16, bool ACT, bool SAVED>
 __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
 {
     constexpr int TS = ACT ? kH1SegShort : kH1SegLong, BLOCK = kH1Segs * TS;
@@ -297,7 +303,9 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         else return z;
     };
     {
-        const H1Rsrc rf = h1_rows_from(p.f, seq, 0, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, 0, p.N, p.d, 2);
+        // first rows: of block 0 for the forward phase, of the last block when the states are given
+        const int first_tok = SAVED ? last_blk * BLOCK : 0;
+        const H1Rsrc rf = h1_rows_from(p.f, seq, first_tok, p.N, p.d, 2 * GS), ri = h1_rows_from(p.i, seq, first_tok, p.N, p.d, 2);
         const unsigned pitch = h1_pitch(p.d);
 #pragma unroll
         for (int t = 0; t < TS; ++t) {
@@ -341,8 +349,10 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
         *reinterpret_cast<f32x2*>(my_carry + blk * carry_blk) = mine;
         ++it;
     };
-    for (int blk = 0; blk < last_blk; ++blk) forward_block(blk, std::true_type{});
-    forward_block(last_blk, std::false_type{});
+    if constexpr (!SAVED) {
+        for (int blk = 0; blk < last_blk; ++blk) forward_block(blk, std::true_type{});
+        forward_block(last_blk, std::false_type{});
+    }
 
     // ---- reverse phase ----
     {
@@ -363,7 +373,15 @@ __global__ __launch_bounds__(kH1Threads) void hgrn1_bwd_kernel(H1Params p)
     for (int blk = last_blk; blk >= 0; --blk, ++it) {
         const int t0 = blk * BLOCK + vs * TS;
         const int par = it & 1;
-        const f32x2 h_in = *reinterpret_cast<const f32x2*>(my_carry + blk * carry_blk);
+        f32x2 h_in;
+        if constexpr (SAVED) {
+            // the forward pass's slot of the 16-token segment this one starts with (a segment that lies
+            // wholly past the end has none: any slot will do, its value reaches no result)
+            const int seg16 = min((blk * kH1Segs + vs) * (TS / kH1SegShort), p.NBLK16 * kH1Segs - 1);
+            h_in = *reinterpret_cast<const f32x2*>(p.carry + ((size_t)b * p.NBLK16 * kH1Segs + seg16) * p.d + c0);
+        } else {
+            h_in = *reinterpret_cast<const f32x2*>(my_carry + blk * carry_blk);
+        }
         // reverse summary of the segment from c = 0 at its end (rows past the end: f = 1, dy was read as 0)
         f32x2 a = {1.0f, 1.0f}, q = {0.0f, 0.0f};
 #pragma unroll
@@ -479,6 +497,7 @@ static H1Params h1_params(int B, int N, int d, int seg, void* ws)
 {
     H1Params p = {};
     p.B = B; p.N = N; p.d = d; p.NBLK = h1_blocks(N, seg); p.NCB = d / kH1Chan;
+    p.NBLK16 = h1_blocks(N, kH1SegShort);
     p.carry = static_cast<float*>(ws);
     p.dbeta_part = p.carry + h1_carry_floats(B, N, d);
     return p;
@@ -504,7 +523,7 @@ hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, 
 
 hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
                             const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
-                            void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream)
+                            void* dout, float* dbeta, float* dh0, void* ws, bool states_saved, hipStream_t stream)
 {
     if ((size_t)B * d == 0) return hipSuccess;
     if (N == 0) {
@@ -517,8 +536,11 @@ hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, 
     H1Params p = h1_params(B, N, d, beta ? kH1SegShort : kH1SegLong, ws);
     p.f = f; p.i = i; p.o = o; p.beta = beta; p.dy = dy; p.h0 = h0; p.dhN = dhN; p.df = df; p.di = di; p.dout = dout; p.dh0 = dh0;
     const dim3 grid((unsigned)(B * p.NCB));
-    auto kern = beta ? (gate_bf16 ? hgrn1_bwd_kernel<true, true> : hgrn1_bwd_kernel<false, true>)
-                     : (gate_bf16 ? hgrn1_bwd_kernel<true, false> : hgrn1_bwd_kernel<false, false>);
+    auto kern = states_saved
+                    ? (beta ? (gate_bf16 ? hgrn1_bwd_kernel<true, true, true> : hgrn1_bwd_kernel<false, true, true>)
+                            : (gate_bf16 ? hgrn1_bwd_kernel<true, false, true> : hgrn1_bwd_kernel<false, false, true>))
+                    : (beta ? (gate_bf16 ? hgrn1_bwd_kernel<true, true, false> : hgrn1_bwd_kernel<false, true, false>)
+                            : (gate_bf16 ? hgrn1_bwd_kernel<true, false, false> : hgrn1_bwd_kernel<false, false, false>));
     hipLaunchKernelGGL(kern, grid, dim3(kH1Threads), 0, stream, p);
     if (beta && dbeta)
         hipLaunchKernelGGL(hgrn1_reduce_beta_kernel, dim3((d + 255) / 256), dim3(256), 0, stream, p.dbeta_part, dbeta, B, d);

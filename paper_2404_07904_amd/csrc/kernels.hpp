@@ -198,9 +198,11 @@ hipError_t launch_step(int BH, int dk, int dv, bool io_bf16, bool gate_bf16, con
 size_t hgrn1_ws_bytes(int B, int N, int d);
 hipError_t launch_hgrn1_fwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
                             const float* beta, const float* h0, void* y, float* hN, void* ws, hipStream_t stream);
+// states_saved: `ws` still holds what launch_hgrn1_fwd on the same inputs left there (the state entering
+// every 16-token segment); the backward pass then does not walk f and i forwards first.
 hipError_t launch_hgrn1_bwd(int B, int N, int d, bool gate_bf16, const void* f, const void* i, const void* o,
                             const float* beta, const float* h0, const void* dy, const float* dhN, void* df, void* di,
-                            void* dout, float* dbeta, float* dh0, void* ws, hipStream_t stream);
+                            void* dout, float* dbeta, float* dh0, void* ws, bool states_saved, hipStream_t stream);
 
 // Smallest product of the gates of one channel over `window` consecutive tokens (windows aligned at
 // multiples of `window` in every sequence), over the whole call: what the exactness of the chunkwise

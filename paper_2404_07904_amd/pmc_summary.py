@@ -29,7 +29,8 @@ KERNELS = {
     "sweep_kernel_mode1": "sweep_kernelIDF16bLi128ELi128ELi64ELi1E",
     "step_kernel": "step_kernel",
     "hgrn1_fwd_kernel": "hgrn1_fwd_kernel",
-    "hgrn1_bwd_kernel": "hgrn1_bwd_kernel",
+    "hgrn1_bwd_kernel": "hgrn1_bwd_kernel<true, false, false>",
+    "hgrn1_bwd_saved_kernel": "hgrn1_bwd_kernel<true, false, true>",
     "proj_fwd_gemm": "gemm_dl_kernel<0>",
     "proj_dx_gemm": "gemm_dl_kernel<1>",
     "proj_dw_gemm": "gemm_kernel<true, true, 2",

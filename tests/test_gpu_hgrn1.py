@@ -42,6 +42,18 @@ def run(f, i, o, dy, h0, dhN, gate_dtype="bf16"):
     check("di", host(gi), ri, tol)
     check("do", host(go), ro, tol)
     check("dh0", host(gh0), rh0, 3e-5)
+    # the same as a training pair: the forward pass leaves the segment states in the workspace,
+    # hgrn1_bwd_saved reads them instead of walking f and i forwards again
+    B, N, d = i.shape
+    ws = torch.empty(max(binding.hgrn1_workspace_bytes(B, N, d), 256), dtype=torch.uint8, device="cuda")
+    y2, hN2 = binding.hgrn1_fwd(fd, idv, od, h0d, workspace=ws)
+    gf2, gi2, go2, gh02 = binding.hgrn1_bwd(fd, idv, od, dyd, h0d, dhNd, want_grad_h0=True, workspace=ws, saved=True)
+    torch.cuda.synchronize()
+    check("y (pair)", host(y2), ry, tol)
+    check("df (saved)", host(gf2), rf, tol)
+    check("di (saved)", host(gi2), ri, tol)
+    check("do (saved)", host(go2), ro, tol)
+    check("dh0 (saved)", host(gh02), rh0, 3e-5)
 
 
 @pytest.mark.parametrize("d", [64, 128, 384])
@@ -117,6 +129,17 @@ def run_act(zf, zi, zo, beta, dy, h0, dhN, gate_dtype="bf16"):
     check("dzo", host(go), ro, tol)
     check("dbeta", host(gb), rb, tol)
     check("dh0", host(gh0), rh0, tol)
+    B, N, d = zi.shape
+    ws = torch.empty(max(binding.hgrn1_workspace_bytes(B, N, d), 256), dtype=torch.uint8, device="cuda")
+    binding.hgrn1_fwd_act(zfd, zid, zod, bd, h0d, workspace=ws)
+    gf2, gi2, go2, gb2, gh02 = binding.hgrn1_bwd_act(zfd, zid, zod, bd, dyd, h0d, dhNd, want_grad_h0=True, workspace=ws,
+                                                     saved=True)
+    torch.cuda.synchronize()
+    check("dzf (saved)", host(gf2), rf, tol)
+    check("dzi (saved)", host(gi2), ri, tol)
+    check("dzo (saved)", host(go2), ro, tol)
+    check("dbeta (saved)", host(gb2), rb, tol)
+    check("dh0 (saved)", host(gh02), rh0, tol)
 
 
 @pytest.mark.parametrize("d", [192, 384])
