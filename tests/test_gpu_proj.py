@@ -26,7 +26,8 @@ def split(w3, b3, d):
     return w3[:d], w3[d:2 * d], w3[2 * d:], b3[:d], b3[d:2 * d], b3[2 * d:]
 
 
-@pytest.mark.parametrize("B,N,d", [(1, 256, 256), (3, 77, 256), (2, 300, 512), (1, 1, 256), (4, 129, 1024)])
+@pytest.mark.parametrize("B,N,d", [(1, 256, 256), (3, 77, 256), (2, 300, 512), (1, 1, 256), (4, 129, 1024),
+                                   (2, 160, 512), (1, 96, 1024), (1, 64, 3072)])   # whole 64-token steps of the dW3 product; a width whose dW3 takes 256-row tiles
 def test_proj_fwd_bwd(B, N, d):
     print("\n[proj] B=%d N=%d d=%d" % (B, N, d), flush=True)
     rng = np.random.default_rng(9200 + N + d)
