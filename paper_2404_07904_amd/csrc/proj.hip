@@ -567,13 +567,28 @@ __global__ __launch_bounds__(256) void proj_transpose_kernel(const __bf16* src, 
     for (int c = ty; c < 64; c += 4) dst[(size_t)(c0 + c) * rows + r0 + tx] = tile[tx][c];
 }
 
-__global__ void proj_bias_grad_kernel(const float* partial, float* db, int n_blocks, int n)
+// db[c] = sum over the row blocks of partial[block][c], in a fixed order: 32 columns per workgroup,
+// the blocks in eight consecutive slices (one per 32 threads) that are then added in order.
+constexpr int kBiasCols = 32, kBiasSlices = 8;
+
+__global__ __launch_bounds__(kBiasCols * kBiasSlices) void proj_bias_grad_kernel(const float* partial, float* db, int n_blocks, int n)
 {
-    const int c = (int)blockIdx.x * (int)blockDim.x + (int)threadIdx.x;
-    if (c >= n) return;
+    __shared__ float part[kBiasSlices][kBiasCols];
+    const int tx = (int)threadIdx.x % kBiasCols, ty = (int)threadIdx.x / kBiasCols;
+    const int c = (int)blockIdx.x * kBiasCols + tx;
+    const int per = (n_blocks + kBiasSlices - 1) / kBiasSlices;
+    const int b0 = ty * per, b1 = min(n_blocks, b0 + per);
     float s = 0.0f;
-    for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * n + c];
-    db[c] = s;
+    if (c < n)
+        for (int b = b0; b < b1; ++b) s += partial[(size_t)b * n + c];
+    part[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && c < n) {
+        float t = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kBiasSlices; ++k) t += part[k][tx];
+        db[c] = t;
+    }
 }
 
 }   // namespace hgrn2
@@ -641,7 +656,8 @@ int hgru2_proj_bwd(int32_t M, int32_t d, const void* x, const void* w3, const vo
     hipLaunchKernelGGL(proj_dact_kernel, dim3((3 * d / 2 + 255) / 256, blocks), dim3(256), 0, stream,
                        static_cast<const __bf16*>(grad_z), static_cast<const __bf16*>(grad_v), static_cast<const __bf16*>(grad_q),
                        static_cast<const __bf16*>(q), static_cast<const __bf16*>(av), dA, partial, M, d);
-    hipLaunchKernelGGL(proj_bias_grad_kernel, dim3((3 * d + 255) / 256), dim3(256), 0, stream, partial, grad_b3, blocks, 3 * d);
+    hipLaunchKernelGGL(proj_bias_grad_kernel, dim3((3 * d + kBiasCols - 1) / kBiasCols), dim3(kBiasCols * kBiasSlices), 0, stream, partial, grad_b3,
+                       blocks, 3 * d);
     if (hipGetLastError() != hipSuccess) return HGRN2_ERR_HIP;
     // dx [M][d] = dA [M][3d] . W3 [3d][d]: W3's contraction index is its slow axis, so it is transposed
     // first (25 MB at width 2048, a few microseconds) and the product takes the kernel for k-contiguous operands
