@@ -598,24 +598,30 @@ def main():
         pack = lambda t: t.permute(0, 2, 1, 3).reshape(T, H, D).contiguous()          # [B][H][N][d] -> [B N][H][d]
         vsets = [tuple(pack(t) for t in st_) for st_ in sets]
 
-        def run_varlen(cu_list):
+        def run_varlen(cu_list, pair=False):
+            # pair: the forward pass keeps the chunk states for the backward pass (hgrn2_fwd_varlen_saving /
+            # hgrn2_bwd_varlen_saved) instead of the backward pass recomputing them
             cu = torch.tensor(cu_list, dtype=torch.int32, device=dev)
             shp = binding.make_shape_varlen(vsets[0][0], vsets[0][2], vsets[0][1], len(cu_list) - 1)
             wsv = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shp), dtype=torch.uint8, device=dev)
-
+            kept = torch.empty(binding.hgrn2_saved_states_varlen_bytes(shp), dtype=torch.uint8, device=dev) if pair else None
             ov, gqv, gfv, gvv = (torch.empty_like(vsets[0][0]) for _ in range(4))
 
             def fn(i):
                 q, f, v, dO = vsets[i % 2]
-                binding.hgrn2_fwd_varlen(q, f, v, cu, None, want_hT=False, o=ov, workspace=wsv)
-                binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=wsv, grad_q=gqv, grad_f=gfv, grad_v=gvv)
+                binding.hgrn2_fwd_varlen(q, f, v, cu, None, want_hT=False, o=ov, workspace=wsv, saved_states=kept)
+                binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=wsv, grad_q=gqv, grad_f=gfv, grad_v=gvv,
+                                         saved_states=kept)
             for i in range(6):
                 fn(i)
             return timed(fn, reps=30)
-        t_mix = run_varlen([0] + list(np.cumsum(lens)))
+        cu_mix = [0] + list(np.cumsum(lens))
+        t_mix = run_varlen(cu_mix)
         t_eq = run_varlen([N * b for b in range(B + 1)])
         # short documents: 1024, 256 and 64 tokens each (the walks then take groups of documents)
         t_short = {L: run_varlen(list(range(0, T + 1, L))) for L in (1024, 256, 64)}
+        t_pair = {"document_mix": run_varlen(cu_mix, True), "8_equal_sequences": run_varlen([N * b for b in range(B + 1)], True)}
+        t_pair.update({str(L): run_varlen(list(range(0, T + 1, L)), True) for L in (1024, 256, 64)})
 
         def fixed_bnhd(i):          # the same packing seen as an equal-length [B][N][H][d] batch
             q, f, v, dO = (t.view(B, N, H, D) for t in vsets[i % 2])
@@ -631,7 +637,8 @@ def main():
             "fwd_bwd_us_document_mix": round(t_mix * 1e6, 1), "tokens_per_s_document_mix": round(T / t_mix, 1),
             "fwd_bwd_us_8_equal_sequences": round(t_eq * 1e6, 1), "tokens_per_s_8_equal_sequences": round(T / t_eq, 1),
             "fwd_bwd_us_same_data_equal_length_entry_points": round(t_fix * 1e6, 1),
-            "fwd_bwd_us_equal_documents_of": {str(L): round(t * 1e6, 1) for L, t in t_short.items()}}
+            "fwd_bwd_us_equal_documents_of": {str(L): round(t * 1e6, 1) for L, t in t_short.items()},
+            "training_pair_fwd_bwd_us": {k: round(t * 1e6, 1) for k, t in t_pair.items()}}
         del vsets
 
     # ---- prefill -> decode hand-off: the chunkwise forward leaves the state the decode step continues from ----

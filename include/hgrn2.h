@@ -247,6 +247,34 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
                      size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Training pair for packed batches (the chunk states of Eq. 3's chunkwise regrouping, Section 3.2,
+ * kept by the forward pass of a step for its backward pass; see hgrn2_fwd_saving above):
+ * hgrn2_fwd_varlen_saving is hgrn2_fwd_varlen that also fills `saved_states`, and
+ * hgrn2_bwd_varlen_saved is hgrn2_bwd_varlen that reads them instead of running a sweep over f and
+ * v of its own.
+ *   saved_states   device, hgrn2_saved_states_varlen_bytes(shape) bytes (sized, like the
+ *                  workspaces, for the worst split of the T tokens), 256-byte aligned.  Valid for
+ *                  the very cu_seqlens, q, f (or z, beta), v, h0 and shape of the forward call.
+ *   h0             both calls take the one initial state array.  A batch of few long sequences is
+ *                  cut into runs, differently by the two passes: nothing is kept then (the shape
+ *                  alone decides, so both calls agree) and the backward call recomputes the
+ *                  states, from h0, as hgrn2_bwd_varlen does.
+ *   workspace      hgrn2_fwd_varlen_workspace_bytes(shape) / hgrn2_bwd_varlen_workspace_bytes(shape)
+ * BF16 storage, chunk = 0 or 64 (HGRN2_ERR_UNSUPPORTED otherwise); other arguments, results (those
+ * of the stateless calls up to the rounding of the states), status codes and stream semantics as
+ * for hgrn2_fwd_varlen / hgrn2_bwd_varlen.
+ */
+size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape);
+int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                            const float* beta, const void* v, const float* h0, void* o, float* hT, void* saved_states,
+                            size_t saved_states_bytes, void* workspace, size_t workspace_bytes, void* hip_stream);
+int hgrn2_bwd_varlen_saved(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, const void* saved_states,
+                           size_t saved_states_bytes, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f,
+                           float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+
+/*
  * hgrn2_min_gate_product for a packed batch: the windows (half chunks: 32 tokens; 16 or 8 with
  * shape->chunk = 32 or 16) start anew with every sequence, as they do inside hgrn2_fwd_varlen /
  * hgrn2_bwd_varlen.  f (or the pre-activations, with beta) is [T][H][dk]; the workspace of

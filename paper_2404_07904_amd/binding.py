@@ -19,7 +19,7 @@ STATUS = {0: "HGRN2_OK", 1: "HGRN2_ERR_NULL", 2: "HGRN2_ERR_SHAPE", 3: "HGRN2_ER
           4: "HGRN2_ERR_WORKSPACE", 5: "HGRN2_ERR_HIP"}
 EXPORTS = ["hgrn2_fwd_workspace_bytes", "hgrn2_bwd_workspace_bytes", "hgrn2_fwd", "hgrn2_bwd",
            "hgrn2_step", "hgrn2_step_gated", "hgrn1_workspace_bytes", "hgrn1_fwd", "hgrn1_bwd", "hgrn1_fwd_act", "hgrn1_bwd_act", "hgrn1_bwd_saved", "hgrn1_bwd_act_saved", "hgrn2_bwd_gated_workspace_bytes", "hgrn2_fwd_gated", "hgrn2_bwd_gated", "hgrn2_cumax", "hgrn2_min_gate_product",
-           "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
+           "hgrn2_fwd_varlen_workspace_bytes", "hgrn2_bwd_varlen_workspace_bytes", "hgrn2_fwd_varlen", "hgrn2_bwd_varlen", "hgrn2_saved_states_varlen_bytes", "hgrn2_fwd_varlen_saving", "hgrn2_bwd_varlen_saved", "hgrn2_state_sweep", "hgrn2_fwd_readout", "hgrn2_bwd_chunk_grads",
            "hgrn2_min_gate_product_varlen_workspace_bytes", "hgrn2_min_gate_product_varlen", "hgrn2_status_string",
            "hgrn2_noalloc_workspace_limit", "hgrn2_noalloc_init", "hgrn2_bwd_noalloc",
            "hgrn2_saved_states_bytes", "hgrn2_bwd_saved_workspace_bytes", "hgrn2_fwd_saving", "hgrn2_bwd_saved",
@@ -76,6 +76,12 @@ def lib() -> ctypes.CDLL:
         L.hgrn2_fwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_bwd_varlen.restype = ctypes.c_int
         L.hgrn2_bwd_varlen.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.hgrn2_saved_states_varlen_bytes.restype = sz
+        L.hgrn2_saved_states_varlen_bytes.argtypes = [sp]
+        L.hgrn2_fwd_varlen_saving.restype = ctypes.c_int
+        L.hgrn2_fwd_varlen_saving.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.hgrn2_bwd_varlen_saved.restype = ctypes.c_int
+        L.hgrn2_bwd_varlen_saved.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.hgrn2_min_gate_product.restype = ctypes.c_int
         L.hgrn2_min_gate_product.argtypes = [sp, vp, vp, vp, vp]
         L.hgrn2_min_gate_product_varlen_workspace_bytes.restype = sz
@@ -404,11 +410,16 @@ def hgrn2_bwd_varlen_workspace_bytes(shape: hgrn2_shape) -> int:
     return int(lib().hgrn2_bwd_varlen_workspace_bytes(ctypes.byref(shape)))
 
 
+def hgrn2_saved_states_varlen_bytes(shape: hgrn2_shape) -> int:
+    return int(lib().hgrn2_saved_states_varlen_bytes(ctypes.byref(shape)))
+
+
 def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o=None, hT=None, workspace=None,
-                     chunk=0, domain_flag=None):
+                     chunk=0, domain_flag=None, saved_states=None):
     """o, hT for sequences packed along the token axis.  q, f: [T,H,dk]; v: [T,H,dv]; cu_seqlens:
     int32 device tensor [n_seq + 1]; h0, hT: fp32 [n_seq,H,dk,dv].  With beta [H,dk] fp32, f holds the
-    gates' pre-activations (Eq. 2)."""
+    gates' pre-activations (Eq. 2).  With saved_states (a uint8 device tensor of
+    hgrn2_saved_states_varlen_bytes bytes) the call is hgrn2_fwd_varlen_saving."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = _flagged(make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk), domain_flag)
     if o is None:
@@ -416,6 +427,13 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o
     if hT is None and want_hT:
         hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device=q.device)
     ws = _workspace(hgrn2_fwd_varlen_workspace_bytes(shape), q.device, workspace)
+    if saved_states is not None:
+        rc = lib().hgrn2_fwd_varlen_saving(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v),
+                                           _ptr(h0), _ptr(o), _ptr(hT), _ptr(saved_states), saved_states.numel(),
+                                           _ptr(ws), ws.numel(), _stream())
+        if rc != 0:
+            raise Hgrn2Error(rc, "hgrn2_fwd_varlen_saving")
+        return o, hT
     rc = lib().hgrn2_fwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0),
                                 _ptr(o), _ptr(hT), _ptr(ws), ws.numel(), _stream())
     if rc != 0:
@@ -424,9 +442,10 @@ def hgrn2_fwd_varlen(q, f, v, cu_seqlens, h0=None, *, beta=None, want_hT=True, o
 
 
 def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta=None, want_grad_h0=False,
-                     workspace=None, grad_q=None, grad_f=None, grad_v=None, chunk=0, domain_flag=None):
+                     workspace=None, grad_q=None, grad_f=None, grad_v=None, chunk=0, domain_flag=None, saved_states=None):
     """grad_q, grad_f, grad_v, grad_h0 for sequences packed along the token axis; with beta also
-    grad_beta (returned as a fifth value), and grad_f is then the gradient of the pre-activations."""
+    grad_beta (returned as a fifth value), and grad_f is then the gradient of the pre-activations.
+    With saved_states (filled by hgrn2_fwd_varlen of the same arguments) the call is hgrn2_bwd_varlen_saved."""
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_contiguous()
     shape = _flagged(make_shape_varlen(q, v, f, cu_seqlens.numel() - 1, chunk), domain_flag)
     gq = torch.empty_like(q) if grad_q is None else grad_q
@@ -436,11 +455,18 @@ def hgrn2_bwd_varlen(q, f, v, grad_o, cu_seqlens, h0=None, grad_hT=None, *, beta
            if want_grad_h0 else None)
     gb = torch.empty((shape.H, shape.dk), dtype=torch.float32, device=q.device) if beta is not None else None
     ws = _workspace(hgrn2_bwd_varlen_workspace_bytes(shape), q.device, workspace)
-    rc = lib().hgrn2_bwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0),
-                                _ptr(grad_o), _ptr(grad_hT), _ptr(gq), _ptr(gf), _ptr(gb), _ptr(gv), _ptr(gh0), _ptr(ws),
-                                ws.numel(), _stream())
+    if saved_states is not None:
+        rc = lib().hgrn2_bwd_varlen_saved(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v),
+                                          _ptr(h0), _ptr(saved_states), saved_states.numel(), _ptr(grad_o), _ptr(grad_hT),
+                                          _ptr(gq), _ptr(gf), _ptr(gb), _ptr(gv), _ptr(gh0), _ptr(ws), ws.numel(), _stream())
+        name = "hgrn2_bwd_varlen_saved"
+    else:
+        rc = lib().hgrn2_bwd_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(q), _ptr(f), _ptr(beta), _ptr(v), _ptr(h0),
+                                    _ptr(grad_o), _ptr(grad_hT), _ptr(gq), _ptr(gf), _ptr(gb), _ptr(gv), _ptr(gh0), _ptr(ws),
+                                    ws.numel(), _stream())
+        name = "hgrn2_bwd_varlen"
     if rc != 0:
-        raise Hgrn2Error(rc, "hgrn2_bwd_varlen")
+        raise Hgrn2Error(rc, name)
     return (gq, gf, gv, gh0) if beta is None else (gq, gf, gv, gh0, gb)
 
 

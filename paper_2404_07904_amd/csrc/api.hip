@@ -740,10 +740,19 @@ size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
            round256(beta_partials_bytes(d));
 }
 
-int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
-                     size_t workspace_bytes, void* hip_stream)
+// A packed batch's forward pass can hand its per-chunk states to the backward pass only when both
+// see the batch the same way: not cut into runs (the two passes cut differently).  Known from the
+// shape alone, so both entry points of the pair decide alike.
+static bool packed_states_kept(const hgrn2_shape* shape, const SeqDims& d)
 {
+    return plan_packed_runs(shape, d, false).run_chunks == 0 && plan_packed_runs(shape, d, true).run_chunks == 0;
+}
+
+static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, void* save_states)
+{
+    if (fine_mode(shape) && save_states) return HGRN2_ERR_UNSUPPORTED;
     if (fine_mode(shape))
         return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, nullptr, nullptr, o, hT, nullptr, nullptr, nullptr,
                            nullptr, nullptr, false, workspace, workspace_bytes, hip_stream);
@@ -779,17 +788,49 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
         return HGRN2_OK;
     }
     if (fwd_fused_supported(d))
-        return launch_fwd_fused(d, q, f, v, h0, o, hT, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+        return launch_fwd_fused(d, q, f, v, h0, o, hT, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
     if (launch_sweep(d, kSweepStateFwd, q, f, v, h0, hT, ws_s, nullptr, stream) != hipSuccess) return HGRN2_ERR_HIP;
     if (launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    // (this sweep keeps the states in the read-out's orientation: the backward pass's come from one of their own)
+    if (save_states && has_tokens &&
+        launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, save_states, nullptr, stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
 
-int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                     const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
-                     void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
                      size_t workspace_bytes, void* hip_stream)
 {
+    return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
+    return round256(state_ws_bytes(d));
+}
+
+int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                            const float* beta, const void* v, const float* h0, void* o, float* hT, void* saved_states,
+                            size_t saved_states_bytes, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, true, &d);      // the shapes the backward pass takes
+    if (rc != HGRN2_OK) return rc;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
+    return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
+                           need > 0 && packed_states_kept(shape, d) ? saved_states : nullptr);
+}
+
+static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                           void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, const void* saved_states)
+{
+    if (fine_mode(shape) && saved_states) return HGRN2_ERR_UNSUPPORTED;
     if (fine_mode(shape))
         return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, nullptr, nullptr, grad_q, grad_f,
                            grad_beta, grad_v, grad_h0, true, workspace, workspace_bytes, hip_stream);
@@ -815,7 +856,9 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     const PackedRuns pr = plan_packed_runs(shape, d, true);
     const size_t one = round256(state_ws_bytes(d));
     char* base = static_cast<char*>(workspace) + pr.table_bytes;
-    void* ws_s = base;
+    if (saved_states && (!has_tokens || !packed_states_kept(shape, d))) saved_states = nullptr;   // none were kept
+    // with states left by the forward pass, only the sweep of the state gradient remains to be run
+    void* ws_s = saved_states ? const_cast<void*>(saved_states) : base;
     void* ws_ds = base + one;
     float* ws_part = beta ? reinterpret_cast<float*>(base + 2 * (one + pr.state_bytes) + pr.decay_bytes) : nullptr;
     const int* first_run;
@@ -846,23 +889,50 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
             split.lay.groups = nullptr;      // (with many, the walk is chosen nearly always, and a grid of
             split.lay.G = 0;                 // groups that only has to return is the cheaper one)
         }
-        if (launch_sweep(walk, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess ||
+        if ((!saved_states && launch_sweep(walk, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess) ||
             launch_bwd_fused_grouped(walk, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
                                      stream) != hipSuccess ||
-            launch_sweep_pair(split, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess ||
+            (saved_states ? launch_sweep(split, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, nullptr, stream)
+                          : launch_sweep_pair(split, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream)) != hipSuccess ||
             (has_tokens &&
              launch_bwd_grad(split, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess))
             return HGRN2_ERR_HIP;
         if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
         return HGRN2_OK;
     } else
-    if (launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess)
+    if ((saved_states ? launch_sweep(d, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, nullptr, stream)
+                      : launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream)) != hipSuccess)
         return HGRN2_ERR_HIP;
     if (has_tokens &&
         launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess)
         return HGRN2_ERR_HIP;
     if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
+}
+
+int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                     const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                     void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                     size_t workspace_bytes, void* hip_stream)
+{
+    return bwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                           workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+int hgrn2_bwd_varlen_saved(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, const void* saved_states,
+                           size_t saved_states_bytes, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f,
+                           float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
+                           void* hip_stream)
+{
+    SeqDims d;
+    const int rc = check_shape_varlen(shape, true, &d);
+    if (rc != HGRN2_OK) return rc;
+    if (fine_mode(shape)) return HGRN2_ERR_UNSUPPORTED;
+    const size_t need = round256(state_ws_bytes(d));
+    if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
+    return bwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                           workspace, workspace_bytes, hip_stream, need > 0 ? saved_states : nullptr);
 }
 
 int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float* beta, float* min_product,

@@ -86,8 +86,9 @@ template <int NSPLIT> struct FwdFusedLds {
 
 // One chunk of the walk: tokens row0 .. row0 + C - 1 of a sequence of N tokens whose first token is
 // token tok0 of the packed tensors (grouped walks; 0 otherwise).  N = 0: a pass past the end.
+// `slot` is the chunk's place in an array with one entry per chunk of the batch (the kept states).
 struct FusedChunk {
-    int tok0, row0, N, bh, first, last;
+    int tok0, row0, N, bh, first, last, slot;
 };
 
 template <bool GATE_BF16, int NSPLIT, bool DENSE, bool GROUPED>
@@ -191,31 +192,34 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
 
     // ---- the chunks of the walk, in order.  Grouped walks step through the group's sequences with
     // a cursor that runs three chunks ahead of the pass (everything here is wave-uniform).
-    int cur_e = e0 - 1, cur_n = 0, cur_nc = 0, cur_tok = 0, cur_N = 0;
+    int cur_e = e0 - 1, cur_n = 0, cur_nc = 0, cur_tok = 0, cur_N = 0, cur_slot = 0;
     auto next_chunk = [&]() {
         FusedChunk c;
         if (cur_n + 1 < cur_nc) ++cur_n;
         else {
             int e = cur_e + 1, len = 0;
             while (e < e1 && (len = table_read(t_len, e)) == 0) ++e;
-            if (e < e1) { cur_e = e; cur_N = len; cur_nc = (len + C - 1) / C; cur_tok = table_read(t_start, e); }
-            else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; }          // past the end, for good
+            if (e < e1) {
+                cur_e = e; cur_N = len; cur_nc = (len + C - 1) / C; cur_tok = table_read(t_start, e);
+                // the chunks of (sequence, head) lie together, the heads of a sequence one after the other
+                cur_slot = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e) * p.lay.H + head * cur_nc;
+            } else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; cur_slot = 0; }          // past the end, for good
             cur_n = 0;
         }
         c.tok0 = cur_tok; c.row0 = cur_n * C; c.N = cur_N; c.bh = cur_e * p.lay.H + head;
-        c.first = cur_n == 0; c.last = cur_N > 0 && cur_n == cur_nc - 1;
+        c.first = cur_n == 0; c.last = cur_N > 0 && cur_n == cur_nc - 1; c.slot = cur_slot + cur_n;
         return c;
     };
     const int N_one = sv.N;
     auto chunk_at = [&](int c) {             // one sequence per workgroup: chunk c of it (any c >= -1)
         FusedChunk k;
-        k.tok0 = 0; k.row0 = c * C; k.N = N_one; k.bh = bh; k.first = c == 0; k.last = c == NC - 1;
+        k.tok0 = 0; k.row0 = c * C; k.N = N_one; k.bh = bh; k.first = c == 0; k.last = c == NC - 1; k.slot = sv.chunk0 + c;
         return k;
     };
     // window of the pass: ck[j] = chunk n - 1 + j of pass n (grouped walks only)
     FusedChunk ck[5];
     if constexpr (GROUPED) {
-        ck[0].tok0 = 0; ck[0].row0 = 0; ck[0].N = 0; ck[0].bh = bh; ck[0].first = 1; ck[0].last = 0;
+        ck[0].tok0 = 0; ck[0].row0 = 0; ck[0].N = 0; ck[0].bh = bh; ck[0].first = 1; ck[0].last = 0; ck[0].slot = 0;
 #pragma unroll
         for (int j = 1; j < 5; ++j) ck[j] = next_chunk();
     }
@@ -464,9 +468,9 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     // channels of 4 dv columns each and get back 4 dv columns of one channel -- and written to
     // global memory as fragments (tile (channel tile, dv tile), half, lane) of 16 bytes per lane.
     constexpr int NSF = (DK / 32) * NBT * 2 / NW;        // fragments per wave and chunk
-    auto save_state = [&](const T* Sx, int n) {
+    auto save_state = [&](const T* Sx, int slot) {
         typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-        T* dst = static_cast<T*>(p.save) + (sv.chunk0 + (size_t)n) * DK * DV;
+        T* dst = static_cast<T*>(p.save) + (size_t)slot * DK * DV;
         const int i16 = lane & 15;
         const int m = ((lane & 16) >> 2) + (i16 & 3);    // which 4 channels of the tile's 32 this lane fetches
         const int hs = m >> 2, q4 = (m >> 1) & 1, gs = m & 1;
@@ -562,7 +566,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         // ======================= stage B =======================
         // O^T tile (bt, rt) = V^T P^T + (G_m S)^T Q~^T   and   accumulators += K~^T V
         if (LATE_QS) store_o(chunk_rel(n, -1));
-        if (!GROUPED && p.save && n < NC) save_state(Sp, n);
+        if (p.save && n < NC) save_state(Sp, chunk_rel(n, 0).slot);
 #pragma unroll
         for (int v = 0; v < 16; ++v) accO[v] = 0.0f;
 #pragma unroll

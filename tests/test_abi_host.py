@@ -288,6 +288,26 @@ def test_varlen_workspace_and_error_codes():
     assert bwd(s, cu=None) == E_NULL
     assert bwd(s, gq=None) == E_NULL
     assert bwd(s, n=table + 2 * states + partials - 1) == E_WS
+    # the training pair: one slot per chunk for the kept states, checked before the call proper
+    assert binding.hgrn2_saved_states_varlen_bytes(s) == states
+    assert binding.hgrn2_saved_states_varlen_bytes(many) == st40
+    assert binding.hgrn2_saved_states_varlen_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0
+    fwd_s = lambda s_, cu=FAKE, q=FAKE, sv=FAKE_WS, sn=big, ws=FAKE_WS, n=big: lib.hgrn2_fwd_varlen_saving(
+        ctypes.byref(s_), cu, q, FAKE, None, FAKE, None, FAKE, None, sv, sn, ws, n, None)
+    bwd_s = lambda s_, cu=FAKE, gq=FAKE, sv=FAKE_WS, sn=big, ws=FAKE_WS, n=big: lib.hgrn2_bwd_varlen_saved(
+        ctypes.byref(s_), cu, FAKE, FAKE, None, FAKE, None, sv, sn, FAKE, None, gq, FAKE, None, FAKE, None, ws, n, None)
+    for call in (fwd_s, bwd_s):
+        assert call(shape(layout=0)) == E_SHAPE
+        assert call(shape(layout=1, io=0, gate=0)) == E_UNSUP        # the shapes the backward pass takes
+        assert call(shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1, chunk=16)) == E_UNSUP
+        assert call(s, sv=None) == E_WS
+        assert call(s, sn=states - 1) == E_WS
+        assert call(s, cu=None) == E_NULL
+        assert call(s, ws=None) == E_WS
+    assert fwd_s(s, q=None) == E_NULL
+    assert bwd_s(s, gq=None) == E_NULL
+    assert fwd_s(s, n=table + states - 1) == E_WS
+    assert bwd_s(s, n=table + 2 * states + partials - 1) == E_WS
 
 
 def test_packed_gate_probe_error_codes():

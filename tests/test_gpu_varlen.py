@@ -1,4 +1,5 @@
-"""GPU parity of the variable-length entry points (hgrn2_fwd_varlen, hgrn2_bwd_varlen): sequences
+"""GPU parity of the variable-length entry points (hgrn2_fwd_varlen, hgrn2_bwd_varlen, and the
+training pair hgrn2_fwd_varlen_saving / hgrn2_bwd_varlen_saved on the same inputs): sequences
 of different lengths packed along the token axis of [T][H][d] tensors, against the fp64 oracle run
 on every sequence by itself.  The recurrence restarts at every boundary, so a token of one
 sequence must not influence another: the oracle side never sees the packing.
@@ -25,6 +26,13 @@ def unpacked(t):
     return host(t.permute(1, 0, 2))
 
 
+def states_buffer(q, v, f, n_seq):
+    """Room for the states a forward pass keeps, filled with bytes that read as NaN: a state the
+    backward pass reads without the forward pass having written it cannot go unnoticed."""
+    shape = binding.make_shape_varlen(q, v, f, n_seq)
+    return torch.full((binding.hgrn2_saved_states_varlen_bytes(shape),), 0xFF, dtype=torch.uint8, device=q.device)
+
+
 def run(seed, lens, H, dk, dv, gate_dtype="bf16", lb=0.3, with_states=True, cu_override=None):
     lens = list(lens)
     B, T = len(lens), int(sum(lens))
@@ -39,6 +47,11 @@ def run(seed, lens, H, dk, dv, gate_dtype="bf16", lb=0.3, with_states=True, cu_o
     cud = torch.from_numpy(cu if cu_override is None else np.asarray(cu_override, dtype=np.int32)).cuda()
     o, hT = binding.hgrn2_fwd_varlen(q, f, v, cud, dev(h0))
     gq, gf, gv, gh0 = binding.hgrn2_bwd_varlen(q, f, v, dO, cud, dev(h0), dev(dhT), want_grad_h0=True)
+    # the same step as a training pair: the forward pass keeps the chunk states for the backward pass
+    saved = states_buffer(q, v, f, B)
+    o_s, hT_s = binding.hgrn2_fwd_varlen(q, f, v, cud, dev(h0), saved_states=saved)
+    gq_s, gf_s, gv_s, gh0_s = binding.hgrn2_bwd_varlen(q, f, v, dO, cud, dev(h0), dev(dhT), want_grad_h0=True,
+                                                       saved_states=saved)
     torch.cuda.synchronize()
     # oracle: every sequence on its own
     ro, rq, rf, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
@@ -59,6 +72,12 @@ def run(seed, lens, H, dk, dv, gate_dtype="bf16", lb=0.3, with_states=True, cu_o
     check("dv", unpacked(gv), rv, tol)
     check("df", unpacked(gf), rf, tol)
     check("dh0", host(gh0), rh0, tol)
+    check("o (pair)", unpacked(o_s), ro, tol)
+    check("hT (pair)", host(hT_s), rhT, tol)
+    check("dq (pair)", unpacked(gq_s), rq, tol)
+    check("dv (pair)", unpacked(gv_s), rv, tol)
+    check("df (pair)", unpacked(gf_s), rf, tol)
+    check("dh0 (pair)", host(gh0_s), rh0, tol)
 
 
 @pytest.mark.parametrize("dk,dv", [(64, 64), (128, 128), (64, 128), (128, 64)])
@@ -178,6 +197,10 @@ def test_varlen_with_gate_formed_in_the_kernels(H, dk, dv, nseq):
     cud, bd = torch.from_numpy(cu).cuda(), torch.from_numpy(beta).cuda()
     o, hT = binding.hgrn2_fwd_varlen(q, zd, v, cud, dev(h0), beta=bd)
     gq, gz, gv, gh0, gb = binding.hgrn2_bwd_varlen(q, zd, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    saved = states_buffer(q, v, zd, B)
+    o_s, hT_s = binding.hgrn2_fwd_varlen(q, zd, v, cud, dev(h0), beta=bd, saved_states=saved)
+    gq_s, gz_s, gv_s, gh0_s, gb_s = binding.hgrn2_bwd_varlen(q, zd, v, dO, cud, dev(h0), dev(dhT), beta=bd,
+                                                             want_grad_h0=True, saved_states=saved)
     torch.cuda.synchronize()
     ro, rq, rz, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
     rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
@@ -197,3 +220,10 @@ def test_varlen_with_gate_formed_in_the_kernels(H, dk, dv, nseq):
     check("dz", unpacked(gz), rz, tol)
     check("dbeta", host(gb), rb, tol)
     check("dh0", host(gh0), rh0, tol)
+    check("o (pair)", unpacked(o_s), ro, tol)
+    check("hT (pair)", host(hT_s), rhT, tol)
+    check("dq (pair)", unpacked(gq_s), rq, tol)
+    check("dv (pair)", unpacked(gv_s), rv, tol)
+    check("dz (pair)", unpacked(gz_s), rz, tol)
+    check("dbeta (pair)", host(gb_s), rb, tol)
+    check("dh0 (pair)", host(gh0_s), rh0, tol)
