@@ -162,7 +162,8 @@ BwdLayout bwd_layout(const SeqDims& d, bool gated, bool states_given = false)
 // host does not know the lengths): runs of `run_chunks` chunks (0: not cut), at most `R` of them.
 struct PackedRuns {
     int run_chunks = 0, R = 0;
-    int G = 0;                   // groups of table entries per head (walked back to back by one workgroup)
+    int G = 0;                   // groups of table entries per head (walked back to back by one workgroup); also the spans of the reverse walk
+    bool by_groups = false;      // enough sequences for the forward walks and sweeps to take a group each
     size_t groups_at = 0;        // where the group array starts
     size_t table_bytes = 0;      // sequence table, then run table and first_run, then the groups
     size_t state_bytes = 0;      // per sweep: fp32 [R * H][dk][dv]
@@ -175,12 +176,14 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     p.R = s->B;
     p.table_bytes = round256(varlen_table_bytes(s->B));
     if (s->B == 0) return p;
-    // With at least as many entries per head as it takes to give every compute unit a walk, the
-    // entries are walked a group at a time, about one group per compute unit (fewer, longer ones keep
-    // a workgroup each, or are cut into runs).
+    // A batch that is not cut into runs gets a group array of about one group per compute unit:
+    // the reverse walk takes equal spans of a head's chunks (the array's last int holds the table
+    // kernel's choice between the two backward passes), and with at least as many entries per head
+    // as groups the forward walks and sweeps take a group of entries each (fewer, longer ones keep a
+    // workgroup each).
     auto with_groups = [&](PackedRuns& r) {
         const int per_head = 256 / (s->H > 0 ? s->H : 1) > 0 ? 256 / (s->H > 0 ? s->H : 1) : 1;
-        if (r.R < per_head) return;
+        r.by_groups = r.R >= per_head;
         r.G = per_head;
         r.groups_at = r.table_bytes;
         r.table_bytes += round256(varlen_groups_bytes(r.G));
@@ -226,8 +229,11 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
         e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, s->H, groups, stream);
-        d->lay.groups = groups;
-        d->lay.G = p.G;
+        if (p.by_groups) {
+            d->lay.groups = groups;
+            d->lay.G = p.G;
+        }
+        d->lay.spans = p.G;
     }
     return e;
 }
@@ -874,18 +880,17 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                                     stream) != hipSuccess ||
             launch_sweep_pair(d, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
-    } else if (d.lay.groups) {
-        // Sequences walked in groups.  Two ways, and only the lengths (device data) tell which is
-        // faster: (1) one forward-state sweep, then the reverse walk that carries the state gradient
-        // in registers and produces the gradients chunk by chunk, as long as the largest group; (0)
-        // both sweeps and the per-chunk gradient kernel, which shares all chunks among the compute
-        // units.  The table kernel has chosen; the kernels of both are enqueued and those of the other
-        // way return at once.
+    } else if (d.lay.spans) {
+        // Two ways, and only the lengths (device data) tell which is faster: (1) one forward-state
+        // sweep, then the reverse walk over equal spans of chunks that carries the state gradient in
+        // registers and produces the gradients chunk by chunk; (0) both sweeps and the per-chunk
+        // gradient kernel (one sequence far longer than a span).  The table kernel has chosen; the
+        // kernels of both are enqueued and those of the other way return at once.
         SeqDims walk = d, split = d;
-        walk.lay.choice = split.lay.choice = d.lay.groups + d.lay.G + 1;
+        walk.lay.choice = split.lay.choice = reinterpret_cast<const int*>(static_cast<char*>(workspace) + pr.groups_at) + pr.G + 1;
         walk.lay.path = 1;
         split.lay.path = 0;
-        if (shape->B < 4 * d.lay.G) {        // few sequences: longest first, a workgroup each, suits uneven lengths
+        if (shape->B < 4 * d.lay.spans) {    // few sequences: longest first, a workgroup each, suits uneven lengths
             split.lay.groups = nullptr;      // (with many, the walk is chosen nearly always, and a grid of
             split.lay.G = 0;                 // groups that only has to return is the cheaper one)
         }

@@ -131,11 +131,13 @@ template <typename T, int DK, int DV> struct BwdGradLds {
 // chunk) x (first-half gate product of the chunk just done), published to the LDS tile the
 // contractions read D' from, and after the chunk's contractions receive Q~^T dO.  Only the forward
 // states S_n come from the workspace.
-// GROUPED (a FUSED walk over a packed batch with a group table): the workgroup owns the sequences
-// [groups[g], groups[g + 1]) of one head and walks them from the last to the first, each from its last
-// chunk to its first: the state gradient starts from the sequence's grad_hT (or zero) at its last
-// chunk and leaves as its grad_h0 after its first, and the rows of the next chunk of the walk --
-// be it of the sequence before -- are always in flight during the epilogue of the current one.
+// GROUPED (a FUSED walk over a packed batch): the chunks of one head, sequence after sequence, are
+// cut into `spans` equal pieces and the workgroup owns one, which may start and end inside a
+// sequence.  It walks its chunks from the last to the first: the state gradient starts from a
+// sequence's grad_hT (or zero) at its last chunk and leaves as its grad_h0 after its first, and the
+// rows of the next chunk of the walk -- be it of the sequence before -- are always in flight during
+// the epilogue of the current one.  A span that ends inside a sequence first takes the light walk
+// over the chunks between its end and the sequence's, which yields the state gradient it starts from.
 template <typename T, int DK, int DV, bool GATE_BF16, bool DENSE, bool FUSED, bool GROUPED = false>
 __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
 {
@@ -241,8 +243,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     if constexpr (!DENSE) {
         if (p.lay.vl) n_chunks = table_read(p.lay.vl, 2 * (p.lay.B + 1) + p.lay.B) * p.lay.H;      // the table's total, not the host's bound
     }
-    // GROUPED: the sequences e0 .. e1 - 1 of head g_head; chunk (e, n) of the walk as a ChunkAt
-    int e0 = 0, e1 = 0, g_head = 0;
+    // GROUPED: a span of the chunks of head g_head; chunk (e, n) of the walk as a ChunkAt
+    int g_head = 0;
     auto chunk_en = [&](int e, int n) {
         ChunkAt c;
         c.bh = e * p.lay.H + g_head;
@@ -254,7 +256,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // the nearest earlier sequence of the group that has tokens; after the very last one, c again
     auto walk_next = [&](const ChunkAt& c) {
         if (c.n > 0) { ChunkAt r = c; r.n = c.n - 1; return r; }
-        for (int e = c.bh / p.lay.H - 1; e >= e0; --e) {
+        for (int e = c.bh / p.lay.H - 1; e >= 0; --e) {
             const int len = table_read(p.lay.vl, p.lay.B + 1 + e);
             if (len > 0) return chunk_en(e, (len + C - 1) / C - 1);
         }
@@ -265,16 +267,19 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     frag sS[2 * NBT], sD[2 * NBT];
     // chunks of this workgroup: every gridDim.x-th one, or (FUSED) those of its run, last to first
     int n_iter, f_bh = 0, f_run = 0, f_first = 0, f_last = 0;
+    int span_end = 0;                     // GROUPED: one past the last chunk of the span, counted over the head's chunks
     if constexpr (GROUPED) {
-        if ((int)blockIdx.x >= p.lay.G * p.lay.H) return;
+        if ((int)blockIdx.x >= p.lay.spans * p.lay.H) return;
         const int grp = (int)blockIdx.x / p.lay.H;
         g_head = (int)blockIdx.x - grp * p.lay.H;
-        e0 = table_read(p.lay.groups, grp);
-        e1 = table_read(p.lay.groups, grp + 1);
-        n_iter = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e1) - table_read(p.lay.vl, 2 * (p.lay.B + 1) + e0);
+        const int total = table_read(p.lay.vl, 2 * (p.lay.B + 1) + p.lay.B);       // chunks of one head
+        const int span_start = (int)((long long)grp * total / p.lay.spans);
+        span_end = (int)((long long)(grp + 1) * total / p.lay.spans);
+        n_iter = span_end - span_start;
         // a sequence without tokens hands the gradient of its final state on to its initial state
+        // (such sequences lie in no span: they are dealt out by their number)
         if (p.dh0)
-            for (int e = e0; e < e1; ++e)
+            for (int e = grp; e < p.lay.B; e += p.lay.spans)
                 if (table_read(p.lay.vl, p.lay.B + 1 + e) == 0)
                     for (int i = tid; i < DK * DV; i += kBwdThreads) {
                         const size_t x = (size_t)(e * p.lay.H + g_head) * DK * DV + i;
@@ -335,8 +340,33 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     ChunkAt cur;
     bool rows_loaded = false;
     float below_floor = 1.0f;             // smallest product a reciprocal was taken of (reported once, at the end)
-    if constexpr (FUSED && !GROUPED) {
-        const int n_light = p.light ? p.NC - 1 - f_last : 0;
+    if constexpr (FUSED) {
+        int n_light = 0;
+        if constexpr (GROUPED) {
+            // the sequence the span ends in (found by the table kernel): the last one whose chunks
+            // start at or before the span's last chunk
+            const int* before = p.lay.vl + 2 * (p.lay.B + 1);
+            const int lo = min(max(table_read(p.lay.choice, 1 + (int)blockIdx.x / p.lay.H), 0), p.lay.B - 1);
+            const int nc_e = table_read(before, lo + 1) - table_read(before, lo);
+            cur = chunk_en(lo, nc_e - 1);                          // that sequence's last chunk
+            n_light = table_read(before, lo + 1) - span_end;       // its chunks after the span
+            if (n_light > 0) {
+                // the light walk starts from the sequence's grad_hT (the chunk loop does that itself
+                // for every sequence whose last chunk lies in the span)
+#pragma unroll
+                for (int j = 0; j < TPW; ++j)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const char* cols = state_cols(p.dhT, cur.bh, j, c);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            accD[j][4 * c + e] = (p.dhT && has_d) ? *reinterpret_cast<const float*>(cols + st_lane + 4 * e) : 0.0f;
+                    }
+            }
+        } else {
+            n_light = p.light ? p.NC - 1 - f_last : 0;
+            if (n_light > 0) cur = where(f_bh * p.NC + p.NC - 1);
+        }
         if (n_light > 0) {
             // ---- light walk over the chunks after this run: dS_n = Diag(g_n) dS_{n+1} + Q^_n^T dO_n with
             // Q^ = q G (G the gate product from the chunk start: no quotient), true state gradient in
@@ -346,7 +376,6 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
                 cd.load(dog + vo);
             };
-            cur = where(f_bh * p.NC + p.NC - 1);
             load_light(raw_f, raw_q, raw_d, cur, tid & 63);
             for (int li = 0; li < n_light; ++li) {
                 int lane_opaque = threadIdx.x & 63;
@@ -357,7 +386,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 const int row0 = cur.n * C + RW * w;
                 f32x2 rf[RW], rq[RW];
                 convert_rows<RW>(rf, raw_f, row0, cur.sv.N, k_act, gate_bf16, 1.0f);
-                if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(f_bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cur.sv.N);
+                if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(cur.bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cur.sv.N);
                 convert_rows<RW>(rq, raw_q, row0, cur.sv.N, k_act, io_bf16, 0.0f);
                 float a0[RW], a1[RW], t0 = 1.0f, t1 = 1.0f;
 #pragma unroll
@@ -366,7 +395,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 __syncthreads();
                 // rows of the next chunk of the walk (after the last light chunk: the run's own last chunk)
                 RawRows<RW> nxt_f, nxt_q;
-                const ChunkAt nxt = where(f_bh * p.NC + p.NC - 2 - li);
+                ChunkAt nxt = cur;            // the chunk before, in the same sequence
+                nxt.n = cur.n - 1;
                 load_light(nxt_f, nxt_q, raw_d, nxt, lane);
                 if (k_act) {
                     float pre0 = 1.0f, pre1 = 1.0f;
@@ -414,14 +444,14 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         }
     }
     if constexpr (GROUPED) {
-        // first chunk of the walk: the last chunk of the last sequence with tokens (n_iter > 0: there is one)
-        int e = e1 - 1;
-        while (table_read(p.lay.vl, p.lay.B + 1 + e) == 0) --e;
-        cur = chunk_en(e, (table_read(p.lay.vl, p.lay.B + 1 + e) + C - 1) / C - 1);
-        load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
-    } else
+        // Keeps the compiler from computing the chunk loop's lane-dependent values ahead of the light
+        // walk and carrying them through it in registers (which made the loop spill, and a reload in
+        // the loop waits for every load in flight, the next chunk's rows included).
+        int opaque = threadIdx.x & 63;
+        asm volatile("" : "+v"(opaque));
+    }
     if (!rows_loaded) {
-        cur = where(chunk_of(0));
+        if constexpr (!GROUPED) cur = where(chunk_of(0));     // (a span: its last chunk, found above)
         load_chunk_rows(raw_f, raw_q, raw_v, raw_d, cur, tid & 63);
     }
 
@@ -996,7 +1026,7 @@ static hipError_t launch_grouped_one(const SeqDims& d, const BwdGradParams& p, h
     auto kern = d.gate_bf16 ? bwd_fused_grouped_kernel<__bf16, DK, DV, true> : bwd_fused_grouped_kernel<__bf16, DK, DV, false>;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)L::total);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(d.lay.G * d.lay.H)), dim3(kBwdThreads), L::total, stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(d.lay.spans * d.lay.H)), dim3(kBwdThreads), L::total, stream, p);
     return hipGetLastError();
 }
 
@@ -1005,7 +1035,7 @@ hipError_t launch_bwd_fused_grouped(const SeqDims& d, const void* q, const void*
                                     void* grad_f, void* grad_v, float* beta_partials, hipStream_t stream)
 {
     if (d.total_chunks() == 0) return hipSuccess;
-    if (!d.lay.vl || !d.lay.groups || !d.io_bf16) return hipErrorInvalidValue;
+    if (!d.lay.vl || d.lay.spans <= 0 || !d.lay.choice || !d.io_bf16) return hipErrorInvalidValue;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
     BwdGradParams p;
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = nullptr;

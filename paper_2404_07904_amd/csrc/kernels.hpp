@@ -38,6 +38,11 @@ struct TokenLayout {
     // those of the other one return at once.  Null: no choice to make.
     const int* choice = nullptr;
     int path = -1;
+    // The fused reverse walk of a packed batch cuts the chunks of a head -- sequence after sequence,
+    // `total` of them -- into `spans` equal pieces, span s = chunks [s total / spans, (s + 1) total /
+    // spans), a workgroup each; a span may start and end inside a sequence.  0: no such walk.
+    // (The ints behind `choice` name, span by span, the sequence the span ends in.)
+    int spans = 0;
     // Segmented sweeps: each of the sequences the strides describe is cut into `seg` runs of whole
     // chunks that the sequential kernels treat as sequences of their own, `seg` per original one,
     // numbered run-fastest.  The kernels' N and NC are then those of a full run; `n_tokens` keeps

@@ -164,23 +164,36 @@ __global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* t
         groups[grp] = first;
     }
     __syncthreads();
-    // Which backward pass: one chunk costs a reverse walk about 10 us, the forward-state sweep it
-    // needs and the two sweeps plus the per-chunk kernel of the other pass about 4.5 and 20 us per
-    // chunk of every compute unit's share (measured at 128-wide heads): the walk wins while its
-    // largest group holds less than 1.5 times that share.
-    __shared__ int largest[kTabThreads];
+    // Which backward pass.  The reverse walk gives every workgroup a span of total / G chunks of a
+    // head (about 10 us a chunk) and has it first walk, at a sixth of that cost, the chunks between
+    // the end of its span and the end of the sequence the span ends in; the other pass (two sweeps,
+    // as long as the longest sequence at about 4.6 us a chunk, then the per-chunk kernel at 11 us per
+    // chunk of a compute unit's share) wins only when one sequence is several times longer than a
+    // span: the walk is chosen while the longest such tail is at most four spans long.
+    __shared__ int longest[kTabThreads];
     int mine = 0;
-    for (int grp = threadIdx.x; grp < G; grp += kTabThreads) mine = max(mine, before[groups[grp + 1]] - before[groups[grp]]);
-    largest[threadIdx.x] = mine;
+    for (int s = threadIdx.x; s < G; s += kTabThreads) {
+        const long long p0 = (long long)s * total / G, p1 = (long long)(s + 1) * total / G;
+        if (p1 <= p0) { groups[G + 2 + s] = 0; continue; }
+        int lo = 0, hi = n_entries;                      // invariant: before[lo] <= p1 - 1 < before[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (before[mid] <= p1 - 1) lo = mid; else hi = mid;
+        }
+        groups[G + 2 + s] = lo;                          // the sequence span s ends in
+        mine = max(mine, (int)(before[lo + 1] - p1));    // chunks of sequence `lo` after the span's last one
+    }
+    longest[threadIdx.x] = mine;
     __syncthreads();
     if (threadIdx.x == 0) {
         int m = 0;
-        for (int j = 0; j < kTabThreads; ++j) m = max(m, largest[j]);
-        groups[G + 1] = (2LL * m * 256 < 3LL * total * H) ? 1 : 0;
+        for (int j = 0; j < kTabThreads; ++j) m = max(m, longest[j]);
+        const long long share = (total + G - 1) / G;
+        groups[G + 1] = (m <= 4 * share) ? 1 : 0;
     }
 }
 
-size_t varlen_groups_bytes(int G) { return ((size_t)G + 2) * sizeof(int); }
+size_t varlen_groups_bytes(int G) { return (2 * (size_t)G + 2) * sizeof(int); }
 
 hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int H, int* groups, hipStream_t stream)
 {

@@ -247,7 +247,7 @@ def test_hgrn1_workspace_and_error_codes():
 def test_varlen_workspace_and_error_codes():
     lib = binding.lib()
     s = shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1)
-    table = 256                                              # 4 * 7 ints, rounded up (6 sequences: too few to be walked in groups)
+    table = 256 + 768                                        # 4 * 7 ints, rounded up; 2 ints for each of the 256 // 3 spans of the reverse walk + 2, rounded up
     states = (1000 // 64 + 6) * 3 * 64 * 64 * 2              # worst split of 1000 tokens into 6 sequences
     assert binding.hgrn2_fwd_varlen_workspace_bytes(s) == table + states
     partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4 + 8 * 3 * 64 * 4     # per-wave shares of grad_beta of every chunk slot, then 8 slice sums per head
@@ -277,10 +277,10 @@ def test_varlen_workspace_and_error_codes():
     assert fwd(s, n=table + states - 1) == E_WS
     assert fwd(s, ws=None) == E_WS
     assert fwd(shape(B=0, layout=1), cu=None, q=None, o=None, ws=None, n=0) == OK
-    # many short sequences are walked in groups: 16 per head at H = 16, two more ints than groups
+    # many short sequences are walked in groups: 16 per head at H = 16, two ints per group and two more
     many = shape(B=40, H=16, N=4096, dk=128, dv=128, layout=1)
     st40 = (4096 // 64 + 40) * 16 * 128 * 128 * 2
-    assert binding.hgrn2_fwd_varlen_workspace_bytes(many) == r256(4 * 41 * 4) + r256((16 + 2) * 4) + st40
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(many) == r256(4 * 41 * 4) + r256((2 * 16 + 2) * 4) + st40
     bwd = lambda s_, cu=FAKE, gq=FAKE, ws=FAKE_WS, n=big, beta=None, gb=None: lib.hgrn2_bwd_varlen(
         ctypes.byref(s_), cu, FAKE, FAKE, beta, FAKE, None, FAKE, None, gq, FAKE, gb, FAKE, None, ws, n, None)
     assert bwd(s, beta=FAKE, gb=None) == E_NULL                 # lower bounds given: their gradient must have a place

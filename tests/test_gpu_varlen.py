@@ -146,12 +146,30 @@ def test_varlen_many_short_documents(H, dk, dv, gate_dtype):
 
 
 def test_varlen_one_long_document_among_short_ones():
-    """Enough sequences for groups, but one group far larger than the others: the table kernel then
-    sends the backward pass through the two sweeps and the per-chunk kernel instead of the reverse
-    walk over groups (both are enqueued; the choice is made on the device)."""
+    """One document many times longer than a span of the reverse walk (16384 tokens among 1200 at 16
+    spans per head: a tail of up to 240 chunks after a span of 18): the table kernel then sends the
+    backward pass through the two sweeps and the per-chunk kernel instead (both are enqueued; the
+    choice is made on the device).  And one that is long, but not that long: the walk."""
+    run(6951, [40, 16384] + [50, 7, 64, 90] * 5, 16, 128, 128)
     lens = [40, 3000] + [50, 7, 64, 90] * 5
     print("\n[varlen] H=16, one document of 3000 tokens among %d short ones" % (len(lens) - 1), flush=True)
     run(6950, lens, 16, 128, 128)
+
+
+@pytest.mark.parametrize("H,dk,dv,lens", [
+    (16, 128, 128, [700, 130, 0, 1500, 64, 1]),           # 16 spans per head over 6 documents: most spans end inside one
+    (4, 64, 128, [2000, 0, 0, 333]),                      # 64 spans per head, more than there are chunks: empty spans
+    (16, 128, 128, [40]),                                 # one chunk in all: every span but one is empty
+    (2, 128, 64, [1000, 3000, 500]),                      # 128 spans per head, one or no chunk each
+])
+def test_varlen_reverse_walk_over_spans(H, dk, dv, lens):
+    """The reverse walk cuts a head's chunks into equal spans whatever the documents: spans that
+    start and end inside a document (the state gradient at their end comes from a light walk over
+    the rest of the document), documents inside a span, spans without chunks, with every sequence's
+    own grad_hT / grad_h0, and without."""
+    print("\n[varlen] H=%d dk=%d dv=%d lens=%s" % (H, dk, dv, lens), flush=True)
+    run(7000 + H, lens, H, dk, dv)
+    run(7050 + H, lens, H, dk, dv, with_states=False)
 
 
 def test_varlen_one_chunk_documents_even_and_odd_counts():
