@@ -514,13 +514,25 @@ def main():
         def packed_bwd(i):
             binding.hgrn2_bwd_varlen(qp, fp, vp, dOp, cup, None, None, workspace=wsp, grad_q=gqp, grad_f=gfp, grad_v=gvp)
 
+        keptp = torch.empty(binding.hgrn2_saved_states_varlen_bytes(shp), dtype=torch.uint8, device=dev)
+
+        def packed_fwd_saving(i):
+            binding.hgrn2_fwd_varlen(qp, fp, vp, cup, None, o=op, hT=hTp, workspace=wsp, saved_states=keptp)
+
+        def packed_bwd_saved(i):
+            binding.hgrn2_bwd_varlen(qp, fp, vp, dOp, cup, None, None, workspace=wsp, grad_q=gqp, grad_f=gfp, grad_v=gvp,
+                                     saved_states=keptp)
+
         for i in range(5):
-            packed_fwd(i); packed_bwd(i)
+            packed_fwd(i); packed_bwd(i); packed_fwd_saving(i); packed_bwd_saved(i)
         tpf, tpb = timed(packed_fwd, reps=30), timed(packed_bwd, reps=30)
+        tpfs, tpbs = timed(packed_fwd_saving, reps=30), timed(packed_bwd_saved, reps=30)
         result["long_sequence"]["packed"] = {"workload": "documents of %s tokens packed as [T][H][d]" % docs,
                                              "fwd_ms": round(tpf * 1e3, 4), "bwd_ms": round(tpb * 1e3, 4),
-                                             "tokens_per_s": round(Tl / (tpf + tpb), 1)}
-        del qp, vp, dOp, fp, wsp, op, gqp, gfp, gvp
+                                             "tokens_per_s": round(Tl / (tpf + tpb), 1),
+                                             "training_pair_fwd_ms": round(tpfs * 1e3, 4), "training_pair_bwd_ms": round(tpbs * 1e3, 4),
+                                             "training_pair_tokens_per_s": round(Tl / (tpfs + tpbs), 1)}
+        del qp, vp, dOp, fp, wsp, op, gqp, gfp, gvp, keptp
 
     # ---- second workload: the element-wise HGRN1 recurrence at the same layer (width 2048) ----
     if not args.no_hgrn1:

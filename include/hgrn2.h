@@ -256,9 +256,9 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
  *                  workspaces, for the worst split of the T tokens), 256-byte aligned.  Valid for
  *                  the very cu_seqlens, q, f (or z, beta), v, h0 and shape of the forward call.
  *   h0             both calls take the one initial state array.  A batch of few long sequences is
- *                  cut into runs, differently by the two passes: nothing is kept then (the shape
- *                  alone decides, so both calls agree) and the backward call recomputes the
- *                  states, from h0, as hgrn2_bwd_varlen does.
+ *                  cut into runs, and for some shapes only by the forward pass: nothing is kept
+ *                  then (the shape alone decides, so both calls agree) and the backward call
+ *                  recomputes the states, from h0, as hgrn2_bwd_varlen does.
  *   workspace      hgrn2_fwd_varlen_workspace_bytes(shape) / hgrn2_bwd_varlen_workspace_bytes(shape)
  * BF16 storage, chunk = 0 or 64 (HGRN2_ERR_UNSUPPORTED otherwise); other arguments, results (those
  * of the stateless calls up to the rounding of the states), status codes and stream semantics as

@@ -89,12 +89,12 @@ int plan_runs(const SeqDims& d, bool backward, int* run_chunks)
 {
     *run_chunks = d.NC;
     // Measured with 64- and 128-wide heads: the forward gains from 16 chunks on, up to 64 sequences
-    // and with about 256 runs in all, down to runs of 4 chunks; the two backward sweeps share the
-    // chip, so they gain from 32 chunks on, up to 32 sequences, with about 128 runs each and runs
-    // of 8 chunks or more.
+    // and with about 256 runs in all, down to runs of 4 chunks; the backward pass of a packed batch
+    // (the only one planned here: equal lengths have a plan of their own) cuts the same way, but
+    // only from 32 chunks on and up to 32 sequences.
     if (d.packed || d.NC < (backward ? 32 : 16) || d.BH == 0 || d.BH > (backward ? 32 : 64)) return 1;
-    const int fill = (backward ? 128 : 256) / d.BH;      // rounded down: a walk more than there are units has to wait for a free one
-    const int by_length = d.NC / (backward ? 8 : 4);
+    const int fill = 256 / d.BH;                         // rounded down: a walk more than there are units has to wait for a free one
+    const int by_length = d.NC / 4;
     const int seg = fill < by_length ? fill : by_length;
     if (seg < 2) return 1;
     const int rc = (d.NC + seg - 1) / seg;
@@ -201,6 +201,11 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     p.run_chunks = rc;
     p.R = (int)bound;
     p.table_bytes += round256(varlen_run_table_bytes(s->B, p.R));
+    if (backward) {          // the reverse walk takes spans of the runs' chunks
+        p.G = 256 / (s->H > 0 ? s->H : 1) > 0 ? 256 / (s->H > 0 ? s->H : 1) : 1;
+        p.groups_at = p.table_bytes;
+        p.table_bytes += round256(varlen_groups_bytes(p.G));
+    }
     p.state_bytes = round256((size_t)p.R * s->H * d.dk * d.dv * sizeof(float));
     p.decay_bytes = round256((size_t)p.R * s->H * d.dk * sizeof(float));
     return p;             // (runs are many and equally long: a workgroup each)
@@ -234,6 +239,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
             d->lay.G = p.G;
         }
         d->lay.spans = p.G;
+        d->lay.span_seq = groups + p.G + 2;
     }
     return e;
 }
@@ -747,11 +753,12 @@ size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 }
 
 // A packed batch's forward pass can hand its per-chunk states to the backward pass only when both
-// see the batch the same way: not cut into runs (the two passes cut differently).  Known from the
-// shape alone, so both entry points of the pair decide alike.
+// see the batch the same way: not cut into runs, or cut into the same runs (the chunk slots follow
+// the runs; the forward pass starts cutting at shorter and more sequences than the backward pass).
+// Known from the shape alone, so both entry points of the pair decide alike.
 static bool packed_states_kept(const hgrn2_shape* shape, const SeqDims& d)
 {
-    return plan_packed_runs(shape, d, false).run_chunks == 0 && plan_packed_runs(shape, d, true).run_chunks == 0;
+    return plan_packed_runs(shape, d, false).run_chunks == plan_packed_runs(shape, d, true).run_chunks;
 }
 
 static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
@@ -787,9 +794,12 @@ static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                                     stream) != hipSuccess)
             return HGRN2_ERR_HIP;
         if (fwd_fused_supported(d))
-            return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, nullptr, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+            return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
         if (launch_sweep(d, kSweepStateFwd, q, f, v, run_state, nullptr, ws_s, nullptr, stream) != hipSuccess ||
             launch_fwd_out(d, q, f, v, ws_s, o, stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (save_states && has_tokens &&
+            launch_sweep(d, kSweepStateBwd, nullptr, f, v, run_state, nullptr, save_states, nullptr, stream) != hipSuccess)
             return HGRN2_ERR_HIP;
         return HGRN2_OK;
     }
@@ -873,13 +883,27 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
         float* run_s = reinterpret_cast<float*>(base + 2 * one);
         float* run_ds = reinterpret_cast<float*>(base + 2 * one + pr.state_bytes);
         float* run_decay = reinterpret_cast<float*>(base + 2 * (one + pr.state_bytes));
-        if (launch_sweep_pair_ends(d, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
-            launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_s, run_decay, nullptr, false,
-                                    stream) != hipSuccess ||
-            launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true,
-                                    stream) != hipSuccess ||
-            launch_sweep_pair(d, q, f, v, grad_o, run_s, run_ds, nullptr, ws_s, ws_ds, stream) != hipSuccess)
+        // d now describes the runs.  What every run adds to the state gradient (and, unless the
+        // forward pass has left the states, to the state) from zero, the carries over the runs of a
+        // sequence, the forward states run by run, and the reverse walk over spans of the runs'
+        // chunks, for which a run is a sequence whose grad_hT is the state gradient the carry left
+        // at its end (the carry has written the sequences' grad_h0).
+        if (saved_states) {
+            if (launch_sweep(d, kSweepGrad, q, f, grad_o, nullptr, run_ds, nullptr, run_decay, stream) != hipSuccess)
+                return HGRN2_ERR_HIP;
+        } else if (launch_sweep_pair_ends(d, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
+                   launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_s, run_decay, nullptr, false,
+                                           stream) != hipSuccess ||
+                   launch_sweep(d, kSweepStateBwd, nullptr, f, v, run_s, nullptr, ws_s, nullptr, stream) != hipSuccess) {
             return HGRN2_ERR_HIP;
+        }
+        if (launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true,
+                                    stream) != hipSuccess ||
+            launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, run_ds, nullptr, grad_q, grad_f, grad_v, ws_part,
+                                     stream) != hipSuccess)
+            return HGRN2_ERR_HIP;
+        if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
+        return HGRN2_OK;
     } else if (d.lay.spans) {
         // Two ways, and only the lengths (device data) tell which is faster: (1) one forward-state
         // sweep, then the reverse walk over equal spans of chunks that carries the state gradient in

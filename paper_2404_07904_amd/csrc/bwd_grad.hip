@@ -346,7 +346,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             // the sequence the span ends in (found by the table kernel): the last one whose chunks
             // start at or before the span's last chunk
             const int* before = p.lay.vl + 2 * (p.lay.B + 1);
-            const int lo = min(max(table_read(p.lay.choice, 1 + (int)blockIdx.x / p.lay.H), 0), p.lay.B - 1);
+            const int lo = min(max(table_read(p.lay.span_seq, (int)blockIdx.x / p.lay.H), 0), p.lay.B - 1);
             const int nc_e = table_read(before, lo + 1) - table_read(before, lo);
             cur = chunk_en(lo, nc_e - 1);                          // that sequence's last chunk
             n_light = table_read(before, lo + 1) - span_end;       // its chunks after the span
@@ -1035,7 +1035,7 @@ hipError_t launch_bwd_fused_grouped(const SeqDims& d, const void* q, const void*
                                     void* grad_f, void* grad_v, float* beta_partials, hipStream_t stream)
 {
     if (d.total_chunks() == 0) return hipSuccess;
-    if (!d.lay.vl || d.lay.spans <= 0 || !d.lay.choice || !d.io_bf16) return hipErrorInvalidValue;
+    if (!d.lay.vl || d.lay.spans <= 0 || !d.lay.span_seq || !d.io_bf16) return hipErrorInvalidValue;
     if (d.beta && !beta_partials) return hipErrorInvalidValue;
     BwdGradParams p;
     p.q = q; p.f = f; p.v = v; p.dO = grad_o; p.ws_s = ws_state; p.ws_ds = nullptr;

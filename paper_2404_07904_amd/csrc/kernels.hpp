@@ -41,8 +41,10 @@ struct TokenLayout {
     // The fused reverse walk of a packed batch cuts the chunks of a head -- sequence after sequence,
     // `total` of them -- into `spans` equal pieces, span s = chunks [s total / spans, (s + 1) total /
     // spans), a workgroup each; a span may start and end inside a sequence.  0: no such walk.
-    // (The ints behind `choice` name, span by span, the sequence the span ends in.)
+    // `span_seq` names, span by span, the sequence the span ends in (device array of `spans` ints,
+    // launch_varlen_groups() writes it behind the choice).
     int spans = 0;
+    const int* span_seq = nullptr;
     // Segmented sweeps: each of the sequences the strides describe is cut into `seg` runs of whole
     // chunks that the sequential kernels treat as sequences of their own, `seg` per original one,
     // numbered run-fastest.  The kernels' N and NC are then those of a full run; `n_tokens` keeps

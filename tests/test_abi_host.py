@@ -253,17 +253,18 @@ def test_varlen_workspace_and_error_codes():
     partials = (1000 // 64 + 6) * 3 * 8 * 64 * 4 + 8 * 3 * 64 * 4     # per-wave shares of grad_beta of every chunk slot, then 8 slice sums per head
     assert binding.hgrn2_bwd_varlen_workspace_bytes(s) == table + 2 * states + partials
     assert binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0      # packed tokens are token-major
-    # two documents in 32768 tokens of 16 heads are cut like 2 x 16384: 8 (4) runs of 32 (64) chunks per
-    # document forward (backward), planned for the mean length; R bounds the runs of any split of the tokens
+    # two documents in 32768 tokens of 16 heads are cut like 2 x 16384: 8 runs of 32 chunks per document,
+    # planned for the mean length; R bounds the runs of any split of the tokens
     lp = shape(B=2, H=16, N=32768, dk=128, dv=128, layout=1)
     r256 = lambda x: (x + 255) // 256 * 256
     st = (32768 // 64 + 2) * 16 * 128 * 128 * 2
     Rf = 2 + (512 + 2) // 32 + 1
-    groups = lambda R: 0                                     # a batch cut into runs is not walked in groups
+    groups = lambda R: 0                                     # a batch cut into runs is not walked in groups ...
+    spans = 256                                              # ... but the reverse walk takes 16 spans per head of the runs' chunks (2 ints each + 2)
     assert binding.hgrn2_fwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rf + 1) * 4 + 3 * 4) + groups(Rf) + st
                                                             + Rf * 16 * (128 * 128 + 128) * 4)
-    Rb = 2 + (512 + 2) // 64 + 1
-    assert binding.hgrn2_bwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rb + 1) * 4 + 3 * 4) + groups(Rb) + 2 * st
+    Rb = Rf
+    assert binding.hgrn2_bwd_varlen_workspace_bytes(lp) == (256 + r256(4 * (Rb + 1) * 4 + 3 * 4) + spans + 2 * st
                                                             + 2 * Rb * 16 * 128 * 128 * 4 + Rb * 16 * 128 * 4
                                                             + (32768 // 64 + 2) * 16 * 8 * 128 * 4 + 8 * 16 * 128 * 4)
     big = 1 << 40

@@ -125,6 +125,11 @@ def test_long_documents_in_a_packed_batch(lens, H, dk, dv, gated):
     bd = torch.from_numpy(beta).cuda() if gated else None
     o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd)
     res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    # the same step as a training pair (states kept by the forward pass, run by run; the buffer starts as NaN patterns)
+    kept = torch.full((binding.hgrn2_saved_states_varlen_bytes(binding.make_shape_varlen(q, v, g, B)),), 0xFF,
+                      dtype=torch.uint8, device=q.device)
+    o_s, hT_s = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, saved_states=kept)
+    res_s = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, saved_states=kept)
     torch.cuda.synchronize()
     ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
     rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
@@ -146,3 +151,8 @@ def test_long_documents_in_a_packed_batch(lens, H, dk, dv, gated):
     check("dh0", host(res[3]), rh0, tol)
     if gated:
         check("dbeta", host(res[4]), rb, tol)
+    check("o (pair)", un(o_s), ro, tol); check("hT (pair)", host(hT_s), rhT, tol)
+    check("dq (pair)", un(res_s[0]), rq, tol); check("dgate (pair)", un(res_s[1]), rg, tol); check("dv (pair)", un(res_s[2]), rv, tol)
+    check("dh0 (pair)", host(res_s[3]), rh0, tol)
+    if gated:
+        check("dbeta (pair)", host(res_s[4]), rb, tol)
