@@ -902,9 +902,7 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
             launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, run_ds, nullptr, grad_q, grad_f, grad_v, ws_part,
                                      stream) != hipSuccess)
             return HGRN2_ERR_HIP;
-        if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
-        return HGRN2_OK;
-    } else if (d.lay.spans) {
+    } else {
         // Two ways, and only the lengths (device data) tell which is faster: (1) one forward-state
         // sweep, then the reverse walk over equal spans of chunks that carries the state gradient in
         // registers and produces the gradients chunk by chunk; (0) both sweeps and the per-chunk
@@ -926,15 +924,7 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
             (has_tokens &&
              launch_bwd_grad(split, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess))
             return HGRN2_ERR_HIP;
-        if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
-        return HGRN2_OK;
-    } else
-    if ((saved_states ? launch_sweep(d, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, nullptr, stream)
-                      : launch_sweep_pair(d, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream)) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    if (has_tokens &&
-        launch_bwd_grad(d, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess)
-        return HGRN2_ERR_HIP;
+    }
     if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
