@@ -240,6 +240,14 @@ def main():
     # ---- the headline: W untimed steps, then exactly K timed ones between two synchronisations.
     # It comes after the per-call timings above, so that the timed region does not start on a GPU
     # that has just woken up (its clocks take tens of milliseconds of work to come up).
+    # The per-call timings leave gaps between launches, during which the clocks fall back: a burst of
+    # back-to-back work (the matrix probe and the step, about 0.1 s) brings them up again first.
+    _, warm_out = binding.hgrn2_probe_mfma(2000)
+    for i in range(150):
+        binding.hgrn2_probe_mfma(2000, warm_out)
+        step(i)
+    torch.cuda.synchronize()
+    del warm_out
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
