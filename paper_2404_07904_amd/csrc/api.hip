@@ -233,7 +233,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     }
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
-        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, s->H, groups, stream);
+        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
         if (p.by_groups) {
             d->lay.groups = groups;
             d->lay.G = p.G;

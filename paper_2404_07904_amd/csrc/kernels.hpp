@@ -256,7 +256,7 @@ hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_c
 // the choice of backward pass (TokenLayout::path): the reverse walk over groups takes as long as its
 // largest group, the per-chunk pass as long as all chunks shared among the compute units.
 size_t varlen_groups_bytes(int G);
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int H, int* groups, hipStream_t stream);
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);

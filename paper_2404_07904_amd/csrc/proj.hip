@@ -17,7 +17,8 @@
 // kept transposed (result column in the register index), so that four consecutive result columns of
 // a row leave a lane together:
 //   gemm_dl_kernel  both operands k-contiguous (x W3^T; dA W3 with W3 transposed beforehand): four
-//                   waves of 128 x 128, LDS stages filled by direct global -> LDS loads (see there);
+//                   waves of 128 x 128 or eight of 128 x 64, LDS stages filled by direct
+//                   global -> LDS loads (see there);
 //   gemm_kernel     an operand whose contraction index is the slow axis of its array (both operands
 //                   of dW3 = dA^T x) keeps its natural orientation in LDS and is read with LDS
 //                   transpose loads: eight waves (2 x 4, each 128 x 64), K in steps of 64 through
@@ -278,7 +279,10 @@ static hipError_t launch_gemm(const GemmParams& p, hipStream_t stream)
 // (x W3^T of the forward pass; dA W3 of the reverse pass once W3 has been transposed.)  Four waves
 // (2 x 2), each owning 128 x 128 of the 256 x 256 tile as 4 x 4 MFMA tiles (an operand fragment read
 // from LDS feeds four MFMAs; the accumulators fill the 256 accumulation registers, the wave is
-// alone on its SIMD and overlaps its own LDS reads, loads and MFMAs).  K advances in steps of 32
+// alone on its SIMD and overlaps its own LDS reads, loads and MFMAs), or eight waves (2 x 4) of
+// 128 x 64, two per SIMD (half again as many fragment reads, but a wave's waits and its epilogue
+// are covered by its neighbour: the projection with its activation epilogue is 5% faster this way,
+// the plain product 4% slower).  K advances in steps of 32
 // through FIVE LDS stages that are filled by `global_load_lds` (16 bytes per lane, no registers in
 // between) four steps ahead.  Such a load writes the 64 lanes' vectors to consecutive LDS
 // addresses, so a tile row is 64 bytes with no padding; bank conflicts are avoided by a swizzle
@@ -287,7 +291,7 @@ static hipError_t launch_gemm(const GemmParams& p, hipStream_t stream)
 // cover all 64 banks for any piece.  One barrier per step: it ends the reads of the stage that
 // is refilled next and publishes the stage that is read next (each wave has waited for its own
 // loads of that stage; loads are counted by hand, the compiler does not track them).
-constexpr int kDlThreads = 256;
+
 constexpr int DBK = 32;                                  // k per stage
 constexpr int kDlStages = 5;                            // 5 x 32 KB: all of a compute unit's LDS
 constexpr int kDlTileBytes = 256 * DBK * 2;              // one operand's tile of one stage
@@ -298,16 +302,24 @@ static_assert(kDlLds <= 160 * 1024, "LDS budget");
 // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 
-template <int EPI>
-__global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
+// NWV waves: 4 (2 x 2, each 128 x 128, alone on its SIMD) or 8 (2 x 4, each 128 x 64, two per SIMD,
+// which can fill each other's waits).
+template <int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void gemm_dl_kernel(GemmParams p)
 {
+    static_assert(NWV == 4 || NWV == 8, "wave layouts: 2 x 2 or 2 x 4");
+    constexpr int THREADS = 64 * NWV;
+    constexpr int WNG = NWV / 2;                 // waves side by side
+    constexpr int TN = BN / WNG, NJ = TN / 32;   // columns of a wave's tile; its 32-column MFMA tiles
+    constexpr int LP = 16 / NWV;                 // load pairs (one instruction of A, one of B) per wave and stage
+    constexpr int WROWS = 256 / NWV;             // tile rows a wave loads
     typedef Mma<__bf16> M;
     typedef __attribute__((address_space(3))) void* lds_ptr;
     typedef const __attribute__((address_space(1))) void* global_ptr;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x, lane = tid & 63, r32 = lane & 31, g = lane >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;                              // wave tile: rows 128 wm .., columns 128 wn ..
+    const int wm = w / WNG, wn = w % WNG;                           // wave tile: rows 128 wm .., columns TN wn ..
     const int n_bn = p.N / BN, n_bm = (p.M + BM - 1) / BM;
     int bm, bn;
     {   // workgroup -> tile, as in gemm_kernel
@@ -321,25 +333,25 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
     }
     const int m0 = bm * BM, n0 = bn * BN;
 
-    // accumulators, transposed: acc[i][j][v] = C[m0 + 128 wm + 32 i + lane % 32][n0 + 128 wn + 32 j + 8 (v/4) + 4 g + v%4]
-    f32x16 acc[4][4];
+    // accumulators, transposed: acc[i][j][v] = C[m0 + 128 wm + 32 i + lane % 32][n0 + TN wn + 32 j + 8 (v/4) + 4 g + v%4]
+    f32x16 acc[4][NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // Loads: instruction j of wave w fills rows 64 w + 16 j .. + 15 of a tile (1 KB); lane l sits at
+    // Loads: instruction j of wave w fills rows WROWS w + 16 j .. + 15 of a tile (1 KB); lane l sits at
     // row l / 4, position l % 4 and fetches piece (l % 4) ^ ((row >> 2) & 3) = (l & 3) ^ ((l >> 4) & 3).
     // Rows past the end of A re-read its last row (never stored).
     const int piece = (lane & 3) ^ ((lane >> 4) & 3);
-    const char* ga[4];
-    const char* gb[4];
+    const char* ga[LP];
+    const char* gb[LP];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int ra = min(m0 + 64 * w + 16 * j + (lane >> 2), p.M - 1);
-        const int rb = n0 + 64 * w + 16 * j + (lane >> 2);
+    for (int j = 0; j < LP; ++j) {
+        const int ra = min(m0 + WROWS * w + 16 * j + (lane >> 2), p.M - 1);
+        const int rb = n0 + WROWS * w + 16 * j + (lane >> 2);
         ga[j] = reinterpret_cast<const char*>(p.A) + ((size_t)ra * p.lda) * 2 + piece * 16;
         gb[j] = reinterpret_cast<const char*>(p.B) + ((size_t)rb * p.ldb) * 2 + piece * 16;
     }
@@ -347,32 +359,44 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
     // loads j (one of A, one of B) of this wave for stage `stage`, k-step kb
     auto issue_pair = [&](int stage, int kb, int j) {
         const size_t ko = (size_t)min(kb, nk - 1) * (DBK * 2);       // steps past the end fetch the last one again (never read)
-        char* sa = smem + stage * kDlStageBytes + w * (64 * DBK * 2);
+        char* sa = smem + stage * kDlStageBytes + w * (WROWS * DBK * 2);
         __builtin_amdgcn_global_load_lds((global_ptr)(ga[j] + ko), (lds_ptr)(sa + j * 1024), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((global_ptr)(gb[j] + ko), (lds_ptr)(sa + kDlTileBytes + j * 1024), 16, 0, 0);
     };
     auto issue = [&](int stage, int kb) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) issue_pair(stage, kb, j);
+        for (int j = 0; j < LP; ++j) issue_pair(stage, kb, j);
     };
     // fragment of 32 rows x 16 k: lane (r32, g) reads piece 2 kk + g of its row
     const int frag_off0 = r32 * 64 + ((0 + g) ^ ((r32 >> 2) & 3)) * 16;
     const int frag_off1 = r32 * 64 + ((2 + g) ^ ((r32 >> 2) & 3)) * 16;
-    // Fragments of k-half kk (16 of the stage's 32 k) of a stage: four of A, four of B.
-    auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[4], int stage, int kk) {
+    // Fragments of k-half kk (16 of the stage's 32 k) of a stage: four of A, NJ of B.
+    auto read_frags = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[NJ], int stage, int kk) {
         const char* sa = smem + stage * kDlStageBytes + (128 * wm) * 64 + (kk ? frag_off1 : frag_off0);
-        const char* sb = smem + stage * kDlStageBytes + kDlTileBytes + (128 * wn) * 64 + (kk ? frag_off1 : frag_off0);
+        const char* sb = smem + stage * kDlStageBytes + kDlTileBytes + (TN * wn) * 64 + (kk ? frag_off1 : frag_off0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(sa + 32 * i * 64);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(sb + 32 * j * 64);
+        for (int j = 0; j < NJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(sb + 32 * j * 64);
     };
-    // the 16 MFMAs of one k-half, in two parts: the first kHead of them, and the rest
-    constexpr int kHead = 2;
-    auto multiply = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[4], int from, int to) {
+    // the NM MFMAs of one k-half, in parts: the first kHead of them, then HP segments, each followed
+    // by one pair of the stage refill's loads
+    constexpr int NM = 4 * NJ, kHead = 2, HP = LP / 2, SEG = (NM - kHead) / HP;
+    auto multiply = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[NJ], int from, int to) {
 #pragma unroll
-        for (int t = 0; t < 16; ++t)
-            if (t >= from && t < to) M::mma(acc[t >> 2][t & 3], fb[t & 3], fa[t >> 2]);   // rows = result columns
+        for (int t = 0; t < NM; ++t)
+            if (t >= from && t < to) M::mma(acc[t / NJ][t % NJ], fb[t % NJ], fa[t / NJ]);   // rows = result columns
+    };
+    // the rest of a half-step after its first MFMAs: segments of MFMAs, each followed by load pair
+    // pair0 + h of stage `stage`, k-step kf
+    auto rest_and_refill = [&](const bf16x8 (&fa)[4], const bf16x8 (&fb)[NJ], int stage, int kf, int pair0) {
+#pragma unroll
+        for (int h = 0; h < HP; ++h) {
+            multiply(fa, fb, kHead + h * SEG, h + 1 == HP ? NM : kHead + (h + 1) * SEG);
+            __builtin_amdgcn_sched_barrier(0);
+            issue_pair(stage, kf, pair0 + h);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
     // The loop is software-pipelined by hand (the scheduling barriers keep the order).  The compiler
@@ -384,11 +408,11 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
     //   first-half fragments of stage kb+1  <- during the MFMAs of the second half of stage kb
     // In between: this wave's loads of stage kb+1 have landed (those of the stages after may be in
     // flight), a barrier publishes stage kb+1 and retires stage kb-1, whose buffer is refilled.
-    bf16x8 fa0[4], fb0[4], fa1[4], fb1[4];
+    bf16x8 fa0[4], fb0[NJ], fa1[4], fb1[NJ];
     constexpr int S = kDlStages;
 #pragma unroll
     for (int st = 0; st < S - 1; ++st) issue(st, st);
-    __builtin_amdgcn_s_waitcnt(vmcnt_only(8 * (S - 2)));         // stage 0 (each stage: 8 loads per lane)
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(2 * LP * (S - 2)));    // stage 0 (each stage: 2 LP loads per lane)
     __builtin_amdgcn_s_barrier();
     read_frags(fa0, fb0, 0, 0);
     int s_cur = 0;                                               // kb % S
@@ -397,8 +421,8 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
         const int s_fill = s_cur == 0 ? S - 1 : s_cur - 1;       // (kb + S - 1) % S: the stage read before this one
         // The refill of a retired stage goes out a pair of loads at a time between the MFMAs, spread
         // over the two half-steps that follow the barrier (a wave that issues its loads in one burst
-        // stalls on the full memory queue, and its MFMAs with it): pairs 0, 1 behind the barrier of
-        // this step, pairs 2, 3 in the first half of the next one.
+        // stalls on the full memory queue, and its MFMAs with it): the first half of the pairs behind
+        // the barrier of this step, the second half in the first half of the next one.
         multiply(fa0, fb0, 0, kHead);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa1, fb1, s_cur, 1);
@@ -406,37 +430,23 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
         {
             // second half of the refill begun in the step before (first step: stage S - 2 once more)
             const int s_prev = s_fill == 0 ? S - 1 : s_fill - 1, k_prev = kb + S - 2;
-            multiply(fa0, fb0, kHead, kHead + 7);
-            __builtin_amdgcn_sched_barrier(0);
-            issue_pair(s_prev, k_prev, 2);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(fa0, fb0, kHead + 7, 16);
-            __builtin_amdgcn_sched_barrier(0);
-            issue_pair(s_prev, k_prev, 3);
-            __builtin_amdgcn_sched_barrier(0);
+            rest_and_refill(fa0, fb0, s_prev, k_prev, HP);
         }
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(8 * (S - 3)));     // stage kb + 1 (the S - 3 younger ones may be in flight)
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(2 * LP * (S - 3)));   // stage kb + 1 (the S - 3 younger ones may be in flight)
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         multiply(fa1, fb1, 0, kHead);
         __builtin_amdgcn_sched_barrier(0);
         read_frags(fa0, fb0, s_next, 0);                         // (after the last step: unused)
         __builtin_amdgcn_sched_barrier(0);
-        multiply(fa1, fb1, kHead, kHead + 7);
-        __builtin_amdgcn_sched_barrier(0);
-        issue_pair(s_fill, kb + S - 1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply(fa1, fb1, kHead + 7, 16);
-        __builtin_amdgcn_sched_barrier(0);
-        issue_pair(s_fill, kb + S - 1, 1);
-        __builtin_amdgcn_sched_barrier(0);
+        rest_and_refill(fa1, fb1, s_fill, kb + S - 1, 0);
         s_cur = s_next;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_only(0));           // no load may land in what the epilogue reuses
     __builtin_amdgcn_s_barrier();
 
-    // ---------------- epilogue: as in gemm_kernel, for the 2 x 2 wave layout ----------------
-    // With one wave per SIMD nothing hides the latency of this part, so it does no more than it
+    // ---------------- epilogue: as in gemm_kernel, for this wave layout ----------------
+    // With one wave per SIMD (NWV = 4) nothing hides the latency of this part, so it does no more than it
     // must: the activation is chosen by a wave-uniform branch around the loops (the gate's block
     // needs none, the second pass of v's block only the bias), and the copy from the staging tile to
     // global memory moves eight vectors per thread at a time.
@@ -450,10 +460,10 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
         auto stage_tile = [&](auto MODE) {
             constexpr int md = decltype(MODE)::value;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const int col = 128 * wn + 32 * j + 8 * c + 4 * g;
+                    const int col = TN * wn + 32 * j + 8 * c + 4 * g;
                     f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
                     if constexpr (EPI == kEpiProj) b = *reinterpret_cast<const f32x4*>(p.bias + n0 + col);
 #pragma unroll
@@ -490,16 +500,16 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
         }
         // 256 rows x 32 vectors of 16 bytes; a wave's 64 lanes cover two whole rows (1 KB contiguous in all)
         constexpr int kBatch = 8;
-        for (int v0 = tid; v0 < BM * (BN / 8); v0 += kDlThreads * kBatch) {
+        for (int v0 = tid; v0 < BM * (BN / 8); v0 += THREADS * kBatch) {
             u32x4 buf[kBatch];
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
-                const int vi = v0 + k * kDlThreads;
+                const int vi = v0 + k * THREADS;
                 buf[k] = *reinterpret_cast<const u32x4*>(St + (size_t)(vi >> 5) * PST + (vi & 31) * 8);
             }
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
-                const int vi = v0 + k * kDlThreads, row = vi >> 5;
+                const int vi = v0 + k * THREADS, row = vi >> 5;
                 if (m0 + row < p.M) *reinterpret_cast<u32x4*>(out + (size_t)(m0 + row) * ld + c0 + (vi & 31) * 8) = buf[k];
             }
         }
@@ -507,14 +517,14 @@ __global__ __launch_bounds__(kDlThreads) void gemm_dl_kernel(GemmParams p)
     }
 }
 
-template <int EPI>
+template <int EPI, int NWV>
 static hipError_t launch_gemm_dl(const GemmParams& p, hipStream_t stream)
 {
-    auto kern = gemm_dl_kernel<EPI>;
+    auto kern = gemm_dl_kernel<EPI, NWV>;
     hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kDlLds);
     if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)(((p.M + BM - 1) / BM) * (p.N / BN));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kDlThreads), kDlLds, stream, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWV), kDlLds, stream, p);
     return hipGetLastError();
 }
 
@@ -629,7 +639,7 @@ int hgru2_proj_fwd(int32_t M, int32_t d, const void* x, const void* w3, const fl
     p.M = M; p.N = 3 * d; p.K = d;
     p.bias = b3; p.z = static_cast<__bf16*>(z); p.v = static_cast<__bf16*>(v); p.q = static_cast<__bf16*>(q);
     p.av = static_cast<__bf16*>(av); p.d = d;
-    return launch_gemm_dl<kEpiProj>(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
+    return launch_gemm_dl<kEpiProj, 8>(p, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
 }
 
 int hgru2_proj_bwd(int32_t M, int32_t d, const void* x, const void* w3, const void* q, const void* av, const void* grad_z,
@@ -670,7 +680,7 @@ int hgru2_proj_bwd(int32_t M, int32_t d, const void* x, const void* w3, const vo
     px.B = w3t; px.ldb = 3 * d;
     px.M = M; px.N = d; px.K = 3 * d;
     px.C = static_cast<__bf16*>(grad_x); px.ldc = d;
-    if (launch_gemm_dl<kEpiPlain>(px, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (launch_gemm_dl<kEpiPlain, 4>(px, stream) != hipSuccess) return HGRN2_ERR_HIP;
     // dW3 [3d][d] = dA^T [3d][M] . x [M][d]: the token index is the slow axis of both
     GemmParams pw = {};
     pw.A = dA; pw.lda = 3 * d;

@@ -145,8 +145,10 @@ hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, 
 
 // Group g of G starts at the first entry e whose chunks-before count reaches g / G of all chunks
 // (bisection over the table's non-decreasing third array); the last group ends at the last entry,
-// so that empty entries at the end belong to a group too.
-__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int H, int* groups)
+// so that empty entries at the end belong to a group too.  Behind the G + 1 group starts: the choice
+// between the two backward passes, then, for each of the G equal spans of chunks the reverse walk
+// takes, the entry the span ends in.
+__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
 {
     const int* before = tab + 2 * (n_entries + 1);
     const long long total = before[n_entries];
@@ -195,9 +197,9 @@ __global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* t
 
 size_t varlen_groups_bytes(int G) { return (2 * (size_t)G + 2) * sizeof(int); }
 
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int H, int* groups, hipStream_t stream)
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream)
 {
-    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, H, groups);
+    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, groups);
     return hipGetLastError();
 }
 
