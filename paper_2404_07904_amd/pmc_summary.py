@@ -31,8 +31,8 @@ KERNELS = {
     "hgrn1_fwd_kernel": "hgrn1_fwd_kernel",
     "hgrn1_bwd_kernel": "hgrn1_bwd_kernel<true, false, false>",
     "hgrn1_bwd_saved_kernel": "hgrn1_bwd_kernel<true, false, true>",
-    "proj_fwd_gemm": "gemm_dl_kernel<0>",
-    "proj_dx_gemm": "gemm_dl_kernel<1>",
+    "proj_fwd_gemm": "gemm_dl_kernel<0,",
+    "proj_dx_gemm": "gemm_dl_kernel<1,",
     "proj_dw_gemm": "gemm_kernel<true, true, 2",
     "proj_dact_kernel": "proj_dact_kernel",
 }
