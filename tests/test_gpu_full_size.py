@@ -124,6 +124,11 @@ def test_config2_full_size_token_major_gated_and_packed():
     pk = lambda t: t.reshape(B * N, H, d)
     po, phT = binding.hgrn2_fwd_varlen(pk(q), pk(f), pk(v), cu, None)
     pq, pf, pv, _ = binding.hgrn2_bwd_varlen(pk(q), pk(f), pk(v), pk(dO), cu, None, None)
+    # ... and as a training pair (the forward pass keeps the chunk states; the buffer starts as NaN patterns)
+    kept = torch.full((binding.hgrn2_saved_states_varlen_bytes(binding.make_shape_varlen(pk(q), pk(v), pk(f), len(cuts) - 1)),),
+                      0xFF, dtype=torch.uint8, device="cuda")
+    so, shT = binding.hgrn2_fwd_varlen(pk(q), pk(f), pk(v), cu, None, saved_states=kept)
+    sq, sf, sv, _ = binding.hgrn2_bwd_varlen(pk(q), pk(f), pk(v), pk(dO), cu, None, None, saved_states=kept)
     torch.cuda.synchronize()
     flat = lambda x: np.ascontiguousarray(np.transpose(x, (1, 0, 2, 3)).reshape(H, B * N, d))     # [H][T][d]
     wq, wf, wv, wd = flat(w.q), flat(w.f), flat(w.v), flat(w.dO)
@@ -138,7 +143,9 @@ def test_config2_full_size_token_major_gated_and_packed():
     un = lambda t: host(t.permute(1, 0, 2))
     check("o", un(po), eo, tol); check("hT", host(phT), ehT, tol)
     check("dq", un(pq), eq, tol); check("df", un(pf), ef, tol); check("dv", un(pv), ev, tol)
-    del po, pq, pf, pv
+    check("o (pair)", un(so), eo, tol); check("hT (pair)", host(shT), ehT, tol)
+    check("dq (pair)", un(sq), eq, tol); check("df (pair)", un(sf), ef, tol); check("dv (pair)", un(sv), ev, tol)
+    del po, pq, pf, pv, so, sq, sf, sv, kept
     # gate formed in the kernels
     print("[full] config2 shape, gate from pre-activations", flush=True)
     z = synth.bf16_round((1.5 * rng.standard_normal((B, H, N, d), dtype=np.float32)).astype(np.float32))
