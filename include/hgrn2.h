@@ -252,9 +252,11 @@ int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
  * hgrn2_fwd_varlen_saving is hgrn2_fwd_varlen that also fills `saved_states`, and
  * hgrn2_bwd_varlen_saved is hgrn2_bwd_varlen that reads them instead of running a sweep over f and
  * v of its own.
- *   saved_states   device, hgrn2_saved_states_varlen_bytes(shape) bytes (sized, like the
- *                  workspaces, for the worst split of the T tokens), 256-byte aligned.  Valid for
- *                  the very cu_seqlens, q, f (or z, beta), v, h0 and shape of the forward call.
+ *   saved_states   device, hgrn2_saved_states_varlen_bytes(shape) bytes (the chunk states, sized
+ *                  like the workspaces for the worst split of the T tokens, and the tables made
+ *                  from cu_seqlens, which the backward call then does not build again), 256-byte
+ *                  aligned.  Valid for the very cu_seqlens, q, f (or z, beta), v, h0 and shape of
+ *                  the forward call.
  *   h0             both calls take the one initial state array.  A batch of few long sequences is
  *                  cut into runs, and for some shapes only by the forward pass: nothing is kept
  *                  then (the shape alone decides, so both calls agree) and the backward call

@@ -211,20 +211,21 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     return p;             // (runs are many and equally long: a workgroup each)
 }
 
-// Builds the table(s) at the head of the workspace and points `d` at the one the kernels use;
-// returns first_run (null when the batch is not cut).
+// Builds the table(s) at `workspace` (p.table_bytes bytes) and points `d` at the one the kernels
+// use; returns first_run (null when the batch is not cut).  launch = false: the tables are there
+// already (the forward pass of a training pair has left them), only `d` is set up.
 hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const int32_t* cu_seqlens, void* workspace,
-                               SeqDims* d, const int** first_run, hipStream_t stream)
+                               SeqDims* d, const int** first_run, hipStream_t stream, bool launch = true)
 {
     int* seq_table = static_cast<int*>(workspace);
     *first_run = nullptr;
     d->lay.vl = seq_table;
-    hipError_t e = launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream);
+    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream) : hipSuccess;
     if (e != hipSuccess) return e;
     if (p.run_chunks != 0) {
         int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
         int* fr = run_table + 4 * ((size_t)p.R + 1);
-        e = launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream);
+        e = launch ? launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream) : hipSuccess;
         if (e != hipSuccess) return e;
         d->lay.vl = run_table;
         d->lay.B = p.R;
@@ -233,7 +234,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     }
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
-        e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
+        if (launch) e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
         if (p.by_groups) {
             d->lay.groups = groups;
             d->lay.G = p.G;
@@ -784,7 +785,13 @@ static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     const size_t one = round256(state_ws_bytes(d));
     void* ws_s = static_cast<char*>(workspace) + pr.table_bytes;
     const int* first_run;
-    if (build_packed_tables(shape, pr, cu_seqlens, workspace, &d, &first_run, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    // A forward pass that keeps the states also leaves the tables, as the backward pass lays them
+    // out (the same entries, plus the spans of its walk), behind the states: that pass builds none.
+    const bool leave_tables = save_states != nullptr;
+    if (build_packed_tables(shape, leave_tables ? plan_packed_runs(shape, d, true) : pr, cu_seqlens,
+                            leave_tables ? static_cast<char*>(save_states) + one : workspace, &d, &first_run,
+                            stream) != hipSuccess)
+        return HGRN2_ERR_HIP;
     if (first_run) {
         // d now describes the runs: walk each from zero, carry the states over the runs of a sequence, walk again
         float* run_state = reinterpret_cast<float*>(static_cast<char*>(ws_s) + one);
@@ -821,11 +828,17 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream, nullptr);
 }
 
+// what the forward pass of a packed training pair leaves: the chunk states, then the tables
+static size_t packed_saved_bytes(const hgrn2_shape* shape, const SeqDims& d)
+{
+    return round256(state_ws_bytes(d)) + plan_packed_runs(shape, d, true).table_bytes;
+}
+
 size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
-    return round256(state_ws_bytes(d));
+    return packed_saved_bytes(shape, d);
 }
 
 int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
@@ -835,10 +848,10 @@ int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens,
     SeqDims d;
     const int rc = check_shape_varlen(shape, true, &d);      // the shapes the backward pass takes
     if (rc != HGRN2_OK) return rc;
-    const size_t need = round256(state_ws_bytes(d));
+    const size_t need = packed_saved_bytes(shape, d);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
     return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
-                           need > 0 && packed_states_kept(shape, d) ? saved_states : nullptr);
+                           state_ws_bytes(d) > 0 && packed_states_kept(shape, d) ? saved_states : nullptr);
 }
 
 static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
@@ -878,7 +891,10 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     void* ws_ds = base + one;
     float* ws_part = beta ? reinterpret_cast<float*>(base + 2 * (one + pr.state_bytes) + pr.decay_bytes) : nullptr;
     const int* first_run;
-    if (build_packed_tables(shape, pr, cu_seqlens, workspace, &d, &first_run, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    // (states kept: the forward pass has left the tables behind them)
+    void* tables = saved_states ? const_cast<char*>(static_cast<const char*>(saved_states)) + one : workspace;
+    if (build_packed_tables(shape, pr, cu_seqlens, tables, &d, &first_run, stream, saved_states == nullptr) != hipSuccess)
+        return HGRN2_ERR_HIP;
     if (first_run) {
         float* run_s = reinterpret_cast<float*>(base + 2 * one);
         float* run_ds = reinterpret_cast<float*>(base + 2 * one + pr.state_bytes);
@@ -909,7 +925,7 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
         // gradient kernel (one sequence far longer than a span).  The table kernel has chosen; the
         // kernels of both are enqueued and those of the other way return at once.
         SeqDims walk = d, split = d;
-        walk.lay.choice = split.lay.choice = reinterpret_cast<const int*>(static_cast<char*>(workspace) + pr.groups_at) + pr.G + 1;
+        walk.lay.choice = split.lay.choice = reinterpret_cast<const int*>(static_cast<char*>(tables) + pr.groups_at) + pr.G + 1;
         walk.lay.path = 1;
         split.lay.path = 0;
         if (shape->B < 4 * d.lay.spans) {    // few sequences: longest first, a workgroup each, suits uneven lengths
@@ -948,10 +964,10 @@ int hgrn2_bwd_varlen_saved(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     const int rc = check_shape_varlen(shape, true, &d);
     if (rc != HGRN2_OK) return rc;
     if (fine_mode(shape)) return HGRN2_ERR_UNSUPPORTED;
-    const size_t need = round256(state_ws_bytes(d));
+    const size_t need = packed_saved_bytes(shape, d);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
     return bwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
-                           workspace, workspace_bytes, hip_stream, need > 0 ? saved_states : nullptr);
+                           workspace, workspace_bytes, hip_stream, state_ws_bytes(d) > 0 ? saved_states : nullptr);
 }
 
 int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float* beta, float* min_product,

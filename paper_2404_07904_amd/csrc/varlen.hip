@@ -20,10 +20,34 @@ namespace hgrn2 {
 
 constexpr int kTabThreads = 256;
 constexpr int kSortMax = 8192;
+constexpr int kSortLds = 2048;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Exclusive prefix (sum, or running maximum of non-negative values) of one value per thread over the
+// workgroup: inside a wave by shuffles, across the waves through `wave_tot` (one int per wave).
+template <bool MAX>
+__device__ __forceinline__ int block_prefix(int v, int* wave_tot)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc = MAX ? max(inc, o) : inc + o;
+    }
+    __syncthreads();                    // (the previous use of wave_tot is over)
+    if (lane == 63) wave_tot[w] = inc;
+    __syncthreads();
+    int before = 0;
+    for (int j = 0; j < w; ++j) before = MAX ? max(before, wave_tot[j]) : before + wave_tot[j];
+    int exc = __shfl_up(inc, 1, 64);
+    if (lane == 0) exc = 0;
+    return MAX ? max(before, exc) : before + exc;
+}
 
 __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab)
 {
-    __shared__ int part[kTabThreads];
+    __shared__ int wave_tot[kTabThreads / 64];
     const int n = B + 1, tid = threadIdx.x;
     const int per = (n + kTabThreads - 1) / kTabThreads;
     const int lo = min(tid * per, n), hi = min(lo + per, n);      // this thread's entries
@@ -32,10 +56,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     // starts: running maximum of the clamped offsets
     int m = 0;
     for (int i = lo; i < hi; ++i) m = max(m, clamped(i));
-    part[tid] = m;
-    __syncthreads();
-    int run = 0;
-    for (int j = 0; j < tid; ++j) run = max(run, part[j]);
+    int run = block_prefix<true>(m, wave_tot);
     for (int i = lo; i < hi; ++i) { run = max(run, clamped(i)); tab[i] = run; }
     __syncthreads();                                              // starts of the neighbouring slices are visible
 
@@ -46,10 +67,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
         tab[n + i] = len;
         c += (len + kChunk - 1) / kChunk;
     }
-    part[tid] = c;
-    __syncthreads();
-    run = 0;
-    for (int j = 0; j < tid; ++j) run += part[j];
+    run = block_prefix<false>(c, wave_tot);
     for (int i = lo; i < hi; ++i) {
         tab[2 * n + i] = run;
         run += (tab[n + i] + kChunk - 1) / kChunk;
@@ -60,9 +78,24 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     // it (longer, or as long with a smaller index), counted directly
     const int* len = tab + n;
     int* order = tab + 3 * n;
+    // (up to kSortLds sequences the lengths are compared out of LDS, four at a time)
+    __shared__ int slen[kSortLds];
+    const bool in_lds = B <= kSortLds;
+    if (in_lds) {
+        for (int j = tid; j < kSortLds; j += kTabThreads) slen[j] = j < B ? len[j] : -1;     // padding never counts
+        __syncthreads();
+    }
     for (int b = tid; b < B; b += kTabThreads) {
         int rank = b;
-        if (B <= kSortMax) {
+        if (in_lds) {
+            rank = 0;
+            const int mine = slen[b];
+            for (int j = 0; j < ((B + 3) & ~3); j += 4) {
+                const i32x4 l = *reinterpret_cast<const i32x4*>(slen + j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rank += (l[e] > mine || (l[e] == mine && j + e < b)) ? 1 : 0;
+            }
+        } else if (B <= kSortMax) {
             rank = 0;
             const int mine = len[b];
             for (int j = 0; j < B; ++j) rank += (len[j] > mine || (len[j] == mine && j < b)) ? 1 : 0;

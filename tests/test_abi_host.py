@@ -289,9 +289,10 @@ def test_varlen_workspace_and_error_codes():
     assert bwd(s, cu=None) == E_NULL
     assert bwd(s, gq=None) == E_NULL
     assert bwd(s, n=table + 2 * states + partials - 1) == E_WS
-    # the training pair: one slot per chunk for the kept states, checked before the call proper
-    assert binding.hgrn2_saved_states_varlen_bytes(s) == states
-    assert binding.hgrn2_saved_states_varlen_bytes(many) == st40
+    # the training pair: one slot per chunk for the kept states, then the tables as the backward pass lays
+    # them out (it builds none of its own then); checked before the call proper
+    assert binding.hgrn2_saved_states_varlen_bytes(s) == states + table
+    assert binding.hgrn2_saved_states_varlen_bytes(many) == st40 + r256(4 * 41 * 4) + r256((2 * 16 + 2) * 4)
     assert binding.hgrn2_saved_states_varlen_bytes(shape(B=6, H=3, N=1000, layout=0)) == 0
     fwd_s = lambda s_, cu=FAKE, q=FAKE, sv=FAKE_WS, sn=big, ws=FAKE_WS, n=big: lib.hgrn2_fwd_varlen_saving(
         ctypes.byref(s_), cu, q, FAKE, None, FAKE, None, FAKE, None, sv, sn, ws, n, None)
@@ -302,7 +303,7 @@ def test_varlen_workspace_and_error_codes():
         assert call(shape(layout=1, io=0, gate=0)) == E_UNSUP        # the shapes the backward pass takes
         assert call(shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1, chunk=16)) == E_UNSUP
         assert call(s, sv=None) == E_WS
-        assert call(s, sn=states - 1) == E_WS
+        assert call(s, sn=states + table - 1) == E_WS
         assert call(s, cu=None) == E_NULL
         assert call(s, ws=None) == E_WS
     assert fwd_s(s, q=None) == E_NULL
