@@ -923,7 +923,16 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
         // sweep, then the reverse walk over equal spans of chunks that carries the state gradient in
         // registers and produces the gradients chunk by chunk; (0) both sweeps and the per-chunk
         // gradient kernel (one sequence far longer than a span).  The table kernel has chosen; the
-        // kernels of both are enqueued and those of the other way return at once.
+        // kernels of both are enqueued and those of the other way return at once.  With the states
+        // left by the forward pass the walk is the faster one for any lengths (measured also with one
+        // document of half or all of the tokens): it alone is enqueued then.
+        if (saved_states) {
+            if (launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
+                                         stream) != hipSuccess)
+                return HGRN2_ERR_HIP;
+            if (beta && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
+            return HGRN2_OK;
+        }
         SeqDims walk = d, split = d;
         walk.lay.choice = split.lay.choice = reinterpret_cast<const int*>(static_cast<char*>(tables) + pr.groups_at) + pr.G + 1;
         walk.lay.path = 1;
@@ -932,11 +941,10 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
             split.lay.groups = nullptr;      // (with many, the walk is chosen nearly always, and a grid of
             split.lay.G = 0;                 // groups that only has to return is the cheaper one)
         }
-        if ((!saved_states && launch_sweep(walk, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess) ||
+        if (launch_sweep(walk, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_s, nullptr, stream) != hipSuccess ||
             launch_bwd_fused_grouped(walk, q, f, v, grad_o, ws_s, grad_hT, grad_h0, grad_q, grad_f, grad_v, ws_part,
                                      stream) != hipSuccess ||
-            (saved_states ? launch_sweep(split, kSweepGrad, q, f, grad_o, grad_hT, grad_h0, ws_ds, nullptr, stream)
-                          : launch_sweep_pair(split, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream)) != hipSuccess ||
+            launch_sweep_pair(split, q, f, v, grad_o, h0, grad_hT, grad_h0, ws_s, ws_ds, stream) != hipSuccess ||
             (has_tokens &&
              launch_bwd_grad(split, q, f, v, grad_o, ws_s, ws_ds, grad_q, grad_f, grad_v, ws_part, stream) != hipSuccess))
             return HGRN2_ERR_HIP;
