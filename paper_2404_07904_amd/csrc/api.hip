@@ -220,7 +220,9 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     int* seq_table = static_cast<int*>(workspace);
     *first_run = nullptr;
     d->lay.vl = seq_table;
-    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream) : hipSuccess;
+    // (a batch that is not cut gets its group array, over the sequence table, in the same launch)
+    int* groups_here = (p.G > 0 && p.run_chunks == 0) ? reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at) : nullptr;
+    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream, p.G, groups_here) : hipSuccess;
     if (e != hipSuccess) return e;
     if (p.run_chunks != 0) {
         int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
@@ -234,7 +236,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     }
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
-        if (launch) e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
+        if (launch && !groups_here) e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
         if (p.by_groups) {
             d->lay.groups = groups;
             d->lay.G = p.G;

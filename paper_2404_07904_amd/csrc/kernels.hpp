@@ -259,6 +259,8 @@ size_t varlen_groups_bytes(int G);
 hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
-hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream);
+// (groups != null: the group array over the table's G groups, launch_varlen_groups(), in the same launch)
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G = 0,
+                               int* groups = nullptr);
 
 }   // namespace hgrn2

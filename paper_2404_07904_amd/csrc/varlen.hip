@@ -23,6 +23,64 @@ constexpr int kSortMax = 8192;
 constexpr int kSortLds = 2048;
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
+// Group g of G starts at the first entry e whose chunks-before count reaches g / G of all chunks
+// (bisection over the table's non-decreasing third array); the last group ends at the last entry,
+// so that empty entries at the end belong to a group too.  Behind the G + 1 group starts: the choice
+// between the two backward passes, then, for each of the G equal spans of chunks the reverse walk
+// takes, the entry the span ends in.
+// (Called by all threads of a one-workgroup kernel, after a barrier that follows the table's writes.)
+__device__ __forceinline__ void build_groups(const int* tab, int n_entries, int G, int* groups)
+{
+    const int* before = tab + 2 * (n_entries + 1);
+    const long long total = before[n_entries];
+    for (int grp = threadIdx.x; grp <= G; grp += kTabThreads) {
+        int first = n_entries;
+        if (grp < G) {
+            int lo = -1, hi = n_entries;                 // invariant: before[lo] G < grp total <= before[hi] G
+            const long long want = (long long)grp * total;
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if ((long long)before[mid] * G >= want) hi = mid; else lo = mid;
+            }
+            first = hi;
+        }
+        groups[grp] = first;
+    }
+    __syncthreads();
+    // Which backward pass.  The reverse walk gives every workgroup a span of total / G chunks of a
+    // head (about 10 us a chunk) and has it first walk, at a sixth of that cost, the chunks between
+    // the end of its span and the end of the sequence the span ends in; the other pass (two sweeps,
+    // as long as the longest sequence at about 4.6 us a chunk, then the per-chunk kernel at 11 us per
+    // chunk of a compute unit's share) wins only when one sequence is several times longer than a
+    // span: the walk is chosen while the longest such tail is at most four spans long.
+    __shared__ int longest[kTabThreads];
+    int mine = 0;
+    for (int s = threadIdx.x; s < G; s += kTabThreads) {
+        const long long p0 = (long long)s * total / G, p1 = (long long)(s + 1) * total / G;
+        if (p1 <= p0) { groups[G + 2 + s] = 0; continue; }
+        int lo = 0, hi = n_entries;                      // invariant: before[lo] <= p1 - 1 < before[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (before[mid] <= p1 - 1) lo = mid; else hi = mid;
+        }
+        groups[G + 2 + s] = lo;                          // the sequence span s ends in
+        mine = max(mine, (int)(before[lo + 1] - p1));    // chunks of sequence `lo` after the span's last one
+    }
+    longest[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int m = 0;
+        for (int j = 0; j < kTabThreads; ++j) m = max(m, longest[j]);
+        const long long share = (total + G - 1) / G;
+        groups[G + 1] = (m <= 4 * share) ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
+{
+    build_groups(tab, n_entries, G, groups);
+}
+
 // Exclusive prefix (sum, or running maximum of non-negative values) of one value per thread over the
 // workgroup: inside a wave by shuffles, across the waves through `wave_tot` (one int per wave).
 template <bool MAX>
@@ -45,7 +103,8 @@ __device__ __forceinline__ int block_prefix(int v, int* wave_tot)
     return MAX ? max(before, exc) : before + exc;
 }
 
-__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab)
+// With `groups` (null: none) the group array of the table is built in the same launch.
+__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab, int G, int* groups)
 {
     __shared__ int wave_tot[kTabThreads / 64];
     const int n = B + 1, tid = threadIdx.x;
@@ -101,6 +160,10 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
             for (int j = 0; j < B; ++j) rank += (len[j] > mine || (len[j] == mine && j < b)) ? 1 : 0;
         }
         order[rank] = b;
+    }
+    if (groups) {
+        __syncthreads();
+        build_groups(tab, B, G, groups);
     }
 }
 
@@ -170,62 +233,10 @@ hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream)
 
 size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
-hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream)
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups)
 {
-    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table);
+    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table, G, groups);
     return hipGetLastError();
-}
-
-// Group g of G starts at the first entry e whose chunks-before count reaches g / G of all chunks
-// (bisection over the table's non-decreasing third array); the last group ends at the last entry,
-// so that empty entries at the end belong to a group too.  Behind the G + 1 group starts: the choice
-// between the two backward passes, then, for each of the G equal spans of chunks the reverse walk
-// takes, the entry the span ends in.
-__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
-{
-    const int* before = tab + 2 * (n_entries + 1);
-    const long long total = before[n_entries];
-    for (int grp = threadIdx.x; grp <= G; grp += kTabThreads) {
-        int first = n_entries;
-        if (grp < G) {
-            int lo = -1, hi = n_entries;                 // invariant: before[lo] G < grp total <= before[hi] G
-            const long long want = (long long)grp * total;
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if ((long long)before[mid] * G >= want) hi = mid; else lo = mid;
-            }
-            first = hi;
-        }
-        groups[grp] = first;
-    }
-    __syncthreads();
-    // Which backward pass.  The reverse walk gives every workgroup a span of total / G chunks of a
-    // head (about 10 us a chunk) and has it first walk, at a sixth of that cost, the chunks between
-    // the end of its span and the end of the sequence the span ends in; the other pass (two sweeps,
-    // as long as the longest sequence at about 4.6 us a chunk, then the per-chunk kernel at 11 us per
-    // chunk of a compute unit's share) wins only when one sequence is several times longer than a
-    // span: the walk is chosen while the longest such tail is at most four spans long.
-    __shared__ int longest[kTabThreads];
-    int mine = 0;
-    for (int s = threadIdx.x; s < G; s += kTabThreads) {
-        const long long p0 = (long long)s * total / G, p1 = (long long)(s + 1) * total / G;
-        if (p1 <= p0) { groups[G + 2 + s] = 0; continue; }
-        int lo = 0, hi = n_entries;                      // invariant: before[lo] <= p1 - 1 < before[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (before[mid] <= p1 - 1) lo = mid; else hi = mid;
-        }
-        groups[G + 2 + s] = lo;                          // the sequence span s ends in
-        mine = max(mine, (int)(before[lo + 1] - p1));    // chunks of sequence `lo` after the span's last one
-    }
-    longest[threadIdx.x] = mine;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int m = 0;
-        for (int j = 0; j < kTabThreads; ++j) m = max(m, longest[j]);
-        const long long share = (total + G - 1) / G;
-        groups[G + 1] = (m <= 4 * share) ? 1 : 0;
-    }
 }
 
 size_t varlen_groups_bytes(int G) { return (2 * (size_t)G + 2) * sizeof(int); }
