@@ -114,3 +114,57 @@ def test_two_streams_with_their_own_workspaces():
         for k in range(2):
             for x, y in zip(got[k], ref[k]):
                 assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("H,d,n_docs", [(16, 128, 24), (4, 64, 5)])
+def test_captured_packed_training_pair_replays(H, d, n_docs):
+    """The packed entry points read cu_seqlens on the device only (their tables are built by a
+    kernel of the call), so a captured step serves batches cut differently: every replay gets new
+    tokens AND new document boundaries (same token count, same number of documents)."""
+    T = 3000
+    print("\n[graph] packed pair T=%d H=%d d=%d, %d documents" % (T, H, d, n_docs), flush=True)
+    rng = np.random.default_rng(8700 + H)
+
+    def fresh_packed(seed):
+        w = synth.make_sequence(seed, 1, H, T, d, d, io_dtype="bf16", lb=0.3, with_dO=True)
+        pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
+        cuts = np.sort(rng.integers(0, T + 1, size=n_docs - 1))
+        cu = torch.from_numpy(np.concatenate([[0], cuts, [T]]).astype(np.int32)).cuda()
+        return [pk(w.q), pk(w.f), pk(w.v), pk(w.dO), cu]
+
+    static = fresh_packed(8700)
+    q, f, v, dO, cu = static
+    shape = binding.make_shape_varlen(q, v, f, n_docs)
+    ws = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    kept = torch.empty(binding.hgrn2_saved_states_varlen_bytes(shape), dtype=torch.uint8, device="cuda")
+    o, hT = torch.empty_like(v), torch.empty((n_docs, H, d, d), device="cuda")
+    gq, gf, gv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v)
+
+    def step():
+        binding.hgrn2_fwd_varlen(q, f, v, cu, None, o=o, hT=hT, workspace=ws, saved_states=kept)
+        binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv,
+                                 saved_states=kept)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for k in range(4):
+        new = fresh_packed(8701 + k)
+        for dst, src in zip(static, new):
+            dst.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (o, hT, gq, gf, gv)]
+        for t in (o, hT, gq, gf, gv):
+            t.zero_()
+        kept.fill_(0xFF)
+        step()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "hT", "dq", "df", "dv"), got, (o, hT, gq, gf, gv)):
+            assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (k, name)
