@@ -542,7 +542,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
             return HGRN2_ERR_HIP;
     }
     // an empty batch or sequence has NC = 0 or B = 0: the reduction then writes zeros
-    if (gated && reduce_beta_partials(d, ws_part, grad_beta, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    if (gated && reduce_beta_partials(d, ws_part, grad_beta, stream, has_tokens ? l.plan.R : 0) != hipSuccess) return HGRN2_ERR_HIP;
     return HGRN2_OK;
 }
 

@@ -335,7 +335,19 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 accD[j][v] = (init && has_d) ? init[(size_t)(32 * at + r32i) * DV + 32 * btj + 8 * (v >> 2) + 4 * gi + (v & 3)] : 0.0f;
         }
     }
-    if (n_iter <= 0) return;              // (FUSED) a sequence without tokens: the host routes those elsewhere
+    // FUSED walks over one run add up their partial sums of the gradient w.r.t. beta chunk after chunk
+    // (a fixed order) and leave one row per wave and run, in the slot of chunk `run` of the sequence.
+    constexpr bool RUN_BETA = FUSED && !GROUPED;
+    float run_b0 = 0.0f, run_b1 = 0.0f;
+    auto store_run_beta = [&]() {
+        const int lane = threadIdx.x & 63;
+        if (RUN_BETA && p.beta && 2 * lane < DK)
+            *reinterpret_cast<f32x2*>(p.beta_partials + ((size_t)(f_bh * p.NC + f_run) * NW + w) * DK + 2 * lane) = f32x2{run_b0, run_b1};
+    };
+    if (n_iter <= 0) {                    // (FUSED) a sequence without tokens: the host routes those elsewhere
+        store_run_beta();
+        return;
+    }
     for (int i = tid; i < DK; i += kBwdThreads) { ones[i] = 1.0f; zeros[i] = 0.0f; }    // first read after a barrier
     ChunkAt cur;
     bool rows_loaded = false;
@@ -847,7 +859,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 sb0 += u0; sb1 += u1;
                 gs0[i] = u0 * (rf[i].x - b.x); gs1[i] = u1 * (rf[i].y - b.y);
             }
-            *reinterpret_cast<f32x2*>(p.beta_partials + ((size_t)chunk * NW + w) * DK + 2 * lane) = f32x2{sb0, sb1};
+            if constexpr (RUN_BETA) { run_b0 += sb0; run_b1 += sb1; }
+            else *reinterpret_cast<f32x2*>(p.beta_partials + ((size_t)chunk * NW + w) * DK + 2 * lane) = f32x2{sb0, sb1};
         }
         store_block(dfg, gs0, gs1);
     }
@@ -857,6 +870,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     if (L::end_barrier) __syncthreads();     // the block sums alias tiles the next chunk is about to write
   }
     if (p.flag && below_floor < kTinyProduct) *p.flag = 1;
+    store_run_beta();
     if constexpr (FUSED && !GROUPED) {
         // run 0 ends at the start of the sequence: dS_0 = G_m E of its first chunk is grad_h0
         if (f_run == 0 && p.dh0 && has_d) {
@@ -1069,7 +1083,7 @@ size_t beta_partials_bytes(const SeqDims& d)
 // row each, coalesced across the channels, and the 16 group sums are added in order).  Second
 // pass: the slice sums are added in order.
 __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* slice_sums, int B,
-                                                                      int H, int NC, int dk, const int* vl)
+                                                                      int H, int NC, int used, int dk, const int* vl)
 {
     __shared__ float part[kRedGroups][64];
     const int h = blockIdx.x / (dk / 64), a = 64 * (blockIdx.x % (dk / 64)) + (threadIdx.x & 63);
@@ -1077,8 +1091,9 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
     float s = 0.0f;
     for (int b = 0; b < B; ++b) {
         // partial rows of (batch, head): kBwdWaves per chunk, the chunks of a sequence and head together
+        // (of which the first `used` hold rows: one per chunk, or one per run of a reverse walk)
         size_t first = (size_t)(b * H + h) * NC;
-        int nc = NC;
+        int nc = used;
         if (vl) {
             nc = (vl[B + 1 + b] + kChunk - 1) / kChunk;
             first = (size_t)vl[2 * (B + 1) + b] * H + (size_t)h * nc;
@@ -1108,14 +1123,14 @@ __global__ void reduce_beta_slices_kernel(const float* slice_sums, float* grad_b
     grad_beta[c] = t;
 }
 
-hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream)
+hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream, int runs)
 {
     if (d.H * d.dk == 0) return hipSuccess;
     const int B = d.BH / d.H, n = d.H * d.dk;
     if (d.total_chunks() == 0) return launch_zero_floats(grad_beta, (size_t)n, stream);      // nothing contributes
     float* slice_sums = beta_partials + d.total_chunks() * kBwdWaves * d.dk;
     hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64), kRedSlices), dim3(64 * kRedGroups), 0, stream,
-                       beta_partials, slice_sums, B, d.H, d.NC, d.dk, d.lay.vl);
+                       beta_partials, slice_sums, B, d.H, d.NC, runs > 0 ? runs : d.NC, d.dk, d.lay.vl);
     hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n);
     return hipGetLastError();
 }

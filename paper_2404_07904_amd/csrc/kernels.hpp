@@ -159,7 +159,7 @@ hipError_t launch_fwd_fused(const SeqDims& d, const void* q, const void* f, cons
 
 // Per-chunk gradients dq, df, dv from the two state sweeps.
 // With d.beta set, grad_f receives the gradient w.r.t. the pre-activation z, and every wave of
-// every chunk leaves its partial sum of the gradient w.r.t. beta in `beta_partials`
+// every chunk (launch_bwd_fused: of every run) leaves its partial sum of the gradient w.r.t. beta in `beta_partials`
 // ([B*H*NC][8][dk] fp32, followed by room for the sums of the reduction's first pass:
 // beta_partials_bytes() in all), which reduce_beta_partials() adds up in a fixed order.
 hipError_t launch_bwd_grad(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
@@ -188,7 +188,9 @@ hipError_t launch_bwd_fused_grouped(const SeqDims& d, const void* q, const void*
                                     const void* ws_state, const float* grad_hT, float* grad_h0, void* grad_q,
                                     void* grad_f, void* grad_v, float* beta_partials, hipStream_t stream);
 size_t beta_partials_bytes(const SeqDims& d);
-hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream);
+// runs > 0: the partial sums come from launch_bwd_fused with a plan of that many runs, which leaves one
+// row per wave and RUN (in the first `runs` chunk slots of every sequence) instead of one per chunk.
+hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* grad_beta, hipStream_t stream, int runs = 0);
 
 // Lower bounds of all layers from Gamma [L][d] (paper Section 2): cumulative softmax over the
 // layer axis minus its first row.
