@@ -680,14 +680,21 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         for (int v = 0; v < 16; ++v) { aV[v] = 0.0f; aV2[v] = 0.0f; }
 #pragma unroll
         for (int ks = 0; ks < 2 * NRT; ++ks)
-            M::mma(aV2, M::load(Pt + (32 * rt_b + r32) * PC + 16 * ks + 8 * g), M::load_kmajor(dOm, PV, 16 * ks, 32 * bt, lane));
+            M::mma(aV2, M::load_kmajor(dOm, PV, 16 * ks, 32 * bt, lane), M::load(Pt + (32 * rt_b + r32) * PC + 16 * ks + 8 * g));
 #pragma unroll
         for (int ks = 0; ks < DK / 16; ++ks)
-            M::mma(aV, M::load(Km + (32 * rt_b + r32) * PK + 16 * ks + 8 * g), M::load_kmajor(dSm, PV, 16 * ks, 32 * bt, lane));
-        const int colv = 32 * bt + ((r32 & 0x13) | ((r32 & 4) << 1) | ((r32 & 8) >> 1));
+            M::mma(aV, M::load_kmajor(dSm, PV, 16 * ks, 32 * bt, lane), M::load(Km + (32 * rt_b + r32) * PK + 16 * ks + 8 * g));
+        // The tile is held transposed (accumulator row = dv position 8 c + 4 g + jj, column = token), so
+        // that four registers are four neighbouring dv columns of one token: position -> column swaps
+        // bits 2 and 3, which sends them to columns 16 (c / 2) + 8 g + 4 (c % 2) + jj.
+        T* dst = dVs + (size_t)(32 * rt_b + r32) * PVR + 32 * bt + 8 * g;
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            dVs[(size_t)(32 * rt_b + acc_row(v, lane)) * PVR + colv] = (T)(aV[v] + aV2[v]);
+        for (int c = 0; c < 4; ++c) {
+            tx4 pk;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pk[jj] = (T)(aV[4 * c + jj] + aV2[4 * c + jj]);
+            *reinterpret_cast<tx4*>(dst + 16 * (c >> 1) + 4 * (c & 1)) = pk;
+        }
     }
     // tile (rt_a, at), transposed (channel = accumulator row):
     //   X^T = K~^T dP^T + (G_m S_n) dO^T,   Y1^T = Q~^T dP,   Ks^T = (H_m dS) V^T
