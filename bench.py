@@ -452,13 +452,25 @@ def main():
                 binding.hgrn2_fwd(q, f, v, None, o=o, hT=hT, workspace=wsf, chunk=ck)
                 binding.hgrn2_bwd(q, f, v, dO, None, None, workspace=wsf, grad_q=gq, grad_f=gf, grad_v=gv, chunk=ck)
 
+            savedf = torch.empty(binding.hgrn2_saved_states_bytes(shf), dtype=torch.uint8, device=dev)
+
+            def fine_pair(i):         # the training pair in the same mode
+                q, f, v, dO = sets[i % 2]
+                binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=savedf, workspace=wsf, chunk=ck)
+                binding.hgrn2_bwd_saved(q, f, v, savedf, dO, None, workspace=wsf, grad_q=gq, grad_f=gf, grad_v=gv, chunk=ck)
+
             for i in range(4):
-                fine_step(i)
+                fine_step(i); fine_pair(i)
             dtf = timed(fine_step, reps=20)
+            dtp = timed(fine_pair, reps=20)
             fine["chunk_%d" % ck] = {"ms_per_step": round(dtf * 1e3, 4), "tokens_per_s": round(tokens / dtf, 1),
-                                     "workspace_MB": round(wsf.numel() / 1e6, 1)}
-            del wsf
-        fine["workload"] = "the main shape and gates; every 32 (16) tokens spread into a chunk of their own"
+                                     "training_pair_ms_per_step": round(dtp * 1e3, 4),
+                                     "training_pair_tokens_per_s": round(tokens / dtp, 1),
+                                     "workspace_MB": round(wsf.numel() / 1e6, 1),
+                                     "saved_states_MB": round(savedf.numel() / 1e6, 1)}
+            del wsf, savedf
+        fine["workload"] = ("the main shape and gates with a reference row every 32 (16) tokens: chunks that hold 32 (16) "
+                            "tokens in their middle rows")
         result["small_gate_modes"] = fine
 
     # ---- long sequences in a small batch: twice the tokens of the main shape in 32 sequences ----

@@ -39,9 +39,12 @@
  *     Small-gate modes: with chunk = 32 or 16, hgrn2_fwd, hgrn2_bwd and their _gated and
  *     _varlen forms place their reference rows every 32 or 16 tokens instead of every 64, and
  *     the bound applies to the product of 16 or 8 consecutive gates (guaranteed for
- *     f >= 0.014, f >= 1.8e-4).  The passes then run on sequences spread to twice or four
- *     times their length: about three or six times the time, and a workspace that also holds
- *     the spread tensors.  hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     f >= 0.014, f >= 1.8e-4).  A chunk of the kernels then holds 32 or 16 tokens in its middle
+ *     rows and nothing in the others: twice or four times the chunks (about 2.4 or 4.8 times
+ *     the time, and workspaces and saved states for as many chunks; the training pair
+ *     hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  Packed batches (_varlen) are
+ *     copied into spread ones for it (their workspace also holds those copies).
+ *     hgrn2_min_gate_product tells which mode a set of gates needs.
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
@@ -170,7 +173,7 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
  *   workspace      hgrn2_fwd_workspace_bytes(shape) for the forward call,
  *                  hgrn2_bwd_saved_workspace_bytes(shape, gated) for the backward call
  *   grad_beta      required when beta is given, ignored otherwise
- * BF16 storage, chunk = 0 or 64, equal-length batches in either layout; other arguments, results
+ * BF16 storage (fp32 for heads of 64 x 64), equal-length batches in either layout; other arguments, results
  * (those of the stateless calls up to the rounding of the states), status codes and stream
  * semantics as above.
  */

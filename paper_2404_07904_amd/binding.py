@@ -300,10 +300,10 @@ def hgrn2_bwd_saved_workspace_bytes(shape: hgrn2_shape, gated: bool) -> int:
 
 
 def hgrn2_fwd_saving(q, f, v, h0=None, *, beta=None, want_hT=True, o=None, hT=None, saved_states=None, workspace=None,
-                     layout=HGRN2_LAYOUT_BHND, domain_flag=None):
+                     layout=HGRN2_LAYOUT_BHND, domain_flag=None, chunk=0):
     """hgrn2_fwd (or hgrn2_fwd_gated when beta is given) that also keeps the per-chunk states for
     hgrn2_bwd_saved.  Returns o, hT, saved_states (a uint8 device buffer)."""
-    shape = _flagged(make_shape(q, v, f, 0, layout), domain_flag)
+    shape = _flagged(make_shape(q, v, f, chunk, layout), domain_flag)
     if o is None:
         o = torch.empty_like(v)
     if hT is None and want_hT:
@@ -319,10 +319,11 @@ def hgrn2_fwd_saving(q, f, v, h0=None, *, beta=None, want_hT=True, o=None, hT=No
 
 
 def hgrn2_bwd_saved(q, f, v, saved_states, grad_o, grad_hT=None, *, beta=None, want_grad_h0=False, workspace=None,
-                    grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND, domain_flag=None):
+                    grad_q=None, grad_f=None, grad_v=None, grad_h0=None, layout=HGRN2_LAYOUT_BHND, domain_flag=None,
+                    chunk=0):
     """hgrn2_bwd (hgrn2_bwd_gated when beta is given) from the states hgrn2_fwd_saving kept.  Returns
     grad_q, grad_f, grad_v, grad_h0 and, with beta, grad_beta as a fifth value."""
-    shape = _flagged(make_shape(q, v, f, 0, layout), domain_flag)
+    shape = _flagged(make_shape(q, v, f, chunk, layout), domain_flag)
     grad_q = torch.empty_like(q) if grad_q is None else grad_q
     grad_f = torch.empty_like(q) if grad_f is None else grad_f
     grad_v = torch.empty_like(v) if grad_v is None else grad_v

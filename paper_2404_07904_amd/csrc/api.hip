@@ -12,8 +12,9 @@ namespace {
 bool dtype_ok(int32_t t) { return t == HGRN2_F32 || t == HGRN2_BF16; }
 bool dim_ok(int32_t d) { return d == 64 || d == 128; }
 
-// Validates a shape; on success fills `d`.  `fine_ok`: the entry point also takes chunk = 16, the
-// small-gate mode, in which it runs on sequences spread to four times their length.
+// Validates a shape; on success fills `d`.  `fine_ok`: the entry point also takes chunk = 16 or 32,
+// the small-gate modes: an equal-length batch is then walked in chunks that hold only that many
+// tokens (TokenLayout::sub), a packed batch is spread into one whose chunks do (spread.hip).
 int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = false, bool fine_ok = false)
 {
     if (!s) return HGRN2_ERR_NULL;
@@ -22,14 +23,13 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     if (s->layout != HGRN2_LAYOUT_BHND && s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;
     const long long bh = (long long)s->B * s->H;
     if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
-    const long long nc = ((long long)s->N + kChunk - 1) / kChunk;
+    const bool fine = s->chunk == kFineChunk || s->chunk == 2 * kFineChunk;
+    const int sub = (fine && !packed) ? s->chunk : kChunk;                  // tokens per chunk
+    const long long nc = ((long long)s->N + sub - 1) / sub;
     if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
     if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
-    if ((s->chunk == kFineChunk || s->chunk == 2 * kFineChunk) && fine_ok) {
-        if (s->N > INT_MAX / 8 || bh * (nc * 4 + 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;      // the spread sequences must pass this check too
-    } else if (s->chunk != 0 && s->chunk != kChunk) {
-        return HGRN2_ERR_UNSUPPORTED;
-    }
+    if (fine ? !fine_ok : (s->chunk != 0 && s->chunk != kChunk)) return HGRN2_ERR_UNSUPPORTED;
+    if (s->N > INT_MAX / 8) return HGRN2_ERR_SHAPE;                         // row numbers around the sequence stay ints
     // fp32 storage in the backward pass: heads of 64 x 64 only (the fp32 tiles of wider heads exceed
     // the LDS), equal-length batches only
     if (backward && s->io_dtype != HGRN2_BF16 && (packed || s->dk != 64 || s->dv != 64)) return HGRN2_ERR_UNSUPPORTED;
@@ -45,6 +45,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     d->domain_flag = s->gate_domain_flag;
     const long long H = s->H, N = s->N, dk = s->dk, dv = s->dv;
     d->lay.H = d->H;
+    d->lay.sub = sub;
     if (s->layout == HGRN2_LAYOUT_BNHD) {
         if (H * dk > INT_MAX / 8 || H * dv > INT_MAX / 8) return HGRN2_ERR_SHAPE;      // token stride is kept in an int
         d->lay.sb_k = N * H * dk; d->lay.sh_k = dk; d->lay.sn_k = H * dk;
@@ -106,7 +107,7 @@ SeqDims as_runs(const SeqDims& d, int seg, int run_chunks)
 {
     if (seg <= 1) return d;               // one run: the sequence itself, with its own length
     SeqDims r = d;
-    r.BH = d.BH * seg; r.NC = run_chunks; r.N = run_chunks * kChunk;
+    r.BH = d.BH * seg; r.NC = run_chunks; r.N = run_chunks * d.lay.sub;
     r.lay.seg = seg; r.lay.n_tokens = d.N;
     return r;
 }
@@ -247,23 +248,8 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     return e;
 }
 
-// ---- small-gate mode: the same passes on spread sequences (spread.hip) -------------------------
+// ---- small-gate modes -----------------------------------------------------------------------------
 bool fine_mode(const hgrn2_shape* s) { return s && (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk); }
-
-hgrn2_shape spread_shape(const hgrn2_shape& s)
-{
-    hgrn2_shape e = s;
-    e.N = spread_tokens(s.N, s.chunk);
-    e.chunk = 0;
-    e.layout = HGRN2_LAYOUT_BHND;
-    return e;
-}
-
-// bytes of one spread tensor of `width` channels
-size_t spread_bytes(const hgrn2_shape& e, int width, bool bf16)
-{
-    return round256((size_t)e.B * e.H * e.N * width * (bf16 ? 2 : 4));
-}
 
 // packed batches: N counts the tokens of all sequences
 hgrn2_shape spread_shape_packed(const hgrn2_shape& s)
@@ -293,12 +279,6 @@ size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, false, &d, false, true) != HGRN2_OK) return 0;
-    if (fine_mode(shape)) {
-        // spread q, f, v, o, then what the forward needs on the spread shape
-        const hgrn2_shape e = spread_shape(*shape);
-        return spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) + 2 * spread_bytes(e, d.dv, d.io_bf16) +
-               hgrn2_fwd_workspace_bytes(&e);
-    }
     return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
 }
 
@@ -306,12 +286,6 @@ size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    if (fine_mode(shape)) {
-        // spread q, grad_q, grad_f; f; v, grad_o, grad_v; then what the backward needs on the spread shape
-        const hgrn2_shape e = spread_shape(*shape);
-        return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
-               3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_workspace_bytes(&e);
-    }
     return bwd_layout(d, false).total();
 }
 
@@ -323,86 +297,13 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                     size_t workspace_bytes, void* hip_stream, const void* saved_states = nullptr);
 
-// Small-gate mode of the forward pass: spread the inputs, run the pass on the spread shape, gather o.
-static int fwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated, const void* v,
-                    const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes, void* hip_stream)
-{
-    SeqDims d;
-    const int rc = check_shape(shape, false, &d, false, true);
-    if (rc != HGRN2_OK) return rc;
-    const bool has_tokens = (size_t)d.BH * d.N > 0;
-    if (has_tokens && (!q || !f || !v || !o || (gated && !beta))) return HGRN2_ERR_NULL;
-    const size_t need = hgrn2_fwd_workspace_bytes(shape);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hgrn2_shape e = spread_shape(*shape);
-    char* at = static_cast<char*>(workspace);
-    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
-    void* qs = take(spread_bytes(e, d.dk, d.io_bf16));
-    void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
-    void* vs = take(spread_bytes(e, d.dv, d.io_bf16));
-    void* os = take(spread_bytes(e, d.dv, d.io_bf16));
-    if (launch_spread(d, shape->chunk, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
-        launch_spread(d, shape->chunk, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
-        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    const int inner = fwd_impl(&e, qs, fs, beta, gated, vs, h0, os, hT, at, workspace_bytes - (size_t)(at - static_cast<char*>(workspace)),
-                               hip_stream);
-    if (inner != HGRN2_OK) return inner;
-    return launch_gather(d, shape->chunk, false, d.io_bf16, os, o, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
-}
-
-// Small-gate mode of the backward pass.
-static int bwd_fine(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated, const void* v,
-                    const float* h0, const void* grad_o, const float* grad_hT, void* grad_q, void* grad_f,
-                    float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
-                    void* hip_stream)
-{
-    SeqDims d;
-    const int rc = check_shape(shape, true, &d, false, true);
-    if (rc != HGRN2_OK) return rc;
-    const bool has_tokens = (size_t)d.BH * d.N > 0;
-    if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
-    if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
-    const size_t need = gated ? hgrn2_bwd_gated_workspace_bytes(shape) : hgrn2_bwd_workspace_bytes(shape);
-    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const hgrn2_shape e = spread_shape(*shape);
-    char* at = static_cast<char*>(workspace);
-    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
-    const size_t ek = spread_bytes(e, d.dk, d.io_bf16), ev = spread_bytes(e, d.dv, d.io_bf16);
-    void* qs = take(ek);
-    void* gqs = take(ek);
-    void* gfs = take(ek);
-    void* fs = take(spread_bytes(e, d.dk, d.gate_bf16));
-    void* vs = take(ev);
-    void* gos = take(ev);
-    void* gvs = take(ev);
-    if (launch_spread(d, shape->chunk, true, d.io_bf16, kFillZero, q, qs, stream) != hipSuccess ||
-        launch_spread(d, shape->chunk, true, d.gate_bf16, gated ? kFillPlusInf : kFillOne, f, fs, stream) != hipSuccess ||
-        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, v, vs, stream) != hipSuccess ||
-        launch_spread(d, shape->chunk, false, d.io_bf16, kFillZero, grad_o, gos, stream) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    // the filler rows add nothing to grad_beta: their gate is exactly 1, and its share carries the factor 1 - f
-    const int inner = bwd_impl(&e, qs, fs, beta, gated, vs, h0, gos, grad_hT, gqs, gfs, grad_beta, gvs, grad_h0, at,
-                               workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
-    if (inner != HGRN2_OK) return inner;
-    if (launch_gather(d, shape->chunk, true, d.io_bf16, gqs, grad_q, stream) != hipSuccess ||
-        launch_gather(d, shape->chunk, true, d.io_bf16, gfs, grad_f, stream) != hipSuccess ||
-        launch_gather(d, shape->chunk, false, d.io_bf16, gvs, grad_v, stream) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    return HGRN2_OK;
-}
-
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream, void* save_states)
 {
-    if (fine_mode(shape) && save_states) return HGRN2_ERR_UNSUPPORTED;
-    if (fine_mode(shape)) return fwd_fine(shape, q, f, beta, gated, v, h0, o, hT, workspace, workspace_bytes, hip_stream);
     SeqDims d;
-    const int rc = check_shape(shape, false, &d);
+    const int rc = check_shape(shape, false, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
     if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
@@ -460,11 +361,6 @@ size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    if (fine_mode(shape)) {
-        const hgrn2_shape e = spread_shape(*shape);
-        return 3 * spread_bytes(e, d.dk, d.io_bf16) + spread_bytes(e, d.dk, d.gate_bf16) +
-               3 * spread_bytes(e, d.dv, d.io_bf16) + hgrn2_bwd_gated_workspace_bytes(&e);
-    }
     return bwd_layout(d, true).total();
 }
 
@@ -474,12 +370,8 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                     size_t workspace_bytes, void* hip_stream, const void* saved_states)
 {
-    if (fine_mode(shape) && saved_states) return HGRN2_ERR_UNSUPPORTED;
-    if (fine_mode(shape))
-        return bwd_fine(shape, q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
-                        workspace, workspace_bytes, hip_stream);
     SeqDims d;
-    const int rc = check_shape(shape, true, &d);
+    const int rc = check_shape(shape, true, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     const bool has_tokens = (size_t)d.BH * d.N > 0;
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
@@ -524,7 +416,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
         if (pl.R > 1 && !pl.light) {
             SeqDims t = d;
             t.window = true;
-            const long long skip = (long long)pl.rc * kChunk;             // tokens of run 0
+            const long long skip = (long long)pl.rc * d.lay.sub;          // tokens of run 0
             t.N = d.N - (int)skip;
             t.NC = d.NC - pl.rc;
             const SeqDims r = as_runs(t, pl.seg_tail, pl.sub_chunks);
@@ -616,14 +508,14 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 size_t hgrn2_saved_states_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
     return round256(state_ws_bytes(d));
 }
 
 size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated)
 {
     SeqDims d;
-    if (check_shape(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
     return bwd_layout(d, gated != 0, true).total();
 }
 
@@ -632,7 +524,7 @@ int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, con
                      void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, true, &d);           // the shapes the backward pass takes
+    const int rc = check_shape(shape, true, &d, false, true);      // the shapes the backward pass takes
     if (rc != HGRN2_OK) return rc;
     const size_t need = round256(state_ws_bytes(d));
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
@@ -646,9 +538,8 @@ int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, cons
                     size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, true, &d);
+    const int rc = check_shape(shape, true, &d, false, true);
     if (rc != HGRN2_OK) return rc;
-    if (fine_mode(shape)) return HGRN2_ERR_UNSUPPORTED;
     const size_t need = round256(state_ws_bytes(d));
     if (need == 0)      // no chunks: nothing was saved, the ordinary pass handles what is left (grad_h0, grad_beta)
         return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,

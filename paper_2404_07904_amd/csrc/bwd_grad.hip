@@ -216,15 +216,20 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         c.sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, c.bh);
         return c;
     };
+    // the token whose V / dO row this thread copies into row vd_row of the tiles (a row that stands for
+    // no token re-reads a neighbouring one: what it holds drops out of every stored result)
+    auto tile_token = [&](const ChunkAt& c) {
+        return min(max(chunk_rows(p.lay.sub, c.n, c.sv.N).tok0 + vd_row, 0), c.sv.N - 1);
+    };
     auto load_fq_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, const ChunkAt& c, int lane) {
         const int col_k = (2 * lane < DK) ? 2 * lane : 0;
-        const int r0 = c.n * C + RW * w;
+        const int r0 = chunk_rows(p.lay.sub, c.n, c.sv.N).tok0 + RW * w;
         load_rows_clamped<RW, GATE_BF16>(cf, static_cast<const char*>(p.f) + c.sv.off_k * GES, r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
         load_rows_clamped<RW, io_bf16>(cq, reinterpret_cast<const char*>(qg + c.sv.off_k), r0, c.sv.N - 1, DENSE ? DK : (int)p.lay.sn_k, col_k);
     };
     auto load_chunk_rows = [&](RawRows<RW>& cf, RawRows<RW>& cq, Raw16<T>& cv, Raw16<T>& cd, const ChunkAt& c, int lane) {
         load_fq_rows(cf, cq, c, lane);
-        const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+        const size_t vo = c.sv.off_v + (size_t)tile_token(c) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
         cv.load(vg + vo);
         cd.load(dog + vo);
     };
@@ -385,7 +390,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
             // the accumulators.  Three barriers per chunk; the Q~ and dO tiles and the block totals are reused.
             auto load_light = [&](RawRows<RW>& cf, RawRows<RW>& cq, Raw16<T>& cd, const ChunkAt& c, int lane) {
                 load_fq_rows(cf, cq, c, lane);
-                const size_t vo = c.sv.off_v + (size_t)min(c.n * C + vd_row, c.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+                const size_t vo = c.sv.off_v + (size_t)tile_token(c) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
                 cd.load(dog + vo);
             };
             load_light(raw_f, raw_q, raw_d, cur, tid & 63);
@@ -395,11 +400,12 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 const int lane = lane_opaque, r32 = lane & 31;
                 const bool k_act = 2 * lane < DK;
                 if (vd_act) raw_d.store_swapped(dOm + (size_t)vd_row * PV + 16 * vd_grp);
-                const int row0 = cur.n * C + RW * w;
+                const ChunkRows lr = chunk_rows(p.lay.sub, cur.n, cur.sv.N);
+                const int row0 = lr.tok0 + RW * w;
                 f32x2 rf[RW], rq[RW];
-                convert_rows<RW>(rf, raw_f, row0, cur.sv.N, k_act, gate_bf16, 1.0f);
-                if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(cur.bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cur.sv.N);
-                convert_rows<RW>(rq, raw_q, row0, cur.sv.N, k_act, io_bf16, 0.0f);
+                convert_rows<RW>(rf, raw_f, row0, lr.end, k_act, gate_bf16, 1.0f, lr.first);
+                if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(cur.bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, lr.end, lr.first);
+                convert_rows<RW>(rq, raw_q, row0, lr.end, k_act, io_bf16, 0.0f, lr.first);
                 float a0[RW], a1[RW], t0 = 1.0f, t1 = 1.0f;
 #pragma unroll
                 for (int i = 0; i < RW; ++i) { t0 *= rf[i].x; t1 *= rf[i].y; a0[i] = t0; a1[i] = t1; }
@@ -450,7 +456,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
                 __syncthreads();          // the tiles and totals are free for the next chunk
             }
             // what the full pass over the run's last chunk needs on top: its V rows
-            const size_t vo = cur.sv.off_v + (size_t)min(cur.n * C + vd_row, cur.sv.N - 1) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
+            const size_t vo = cur.sv.off_v + (size_t)tile_token(cur) * (DENSE ? (size_t)DV : (size_t)p.lay.sn_v) + 16 * vd_grp;
             raw_v.load(vg + vo);
             rows_loaded = true;
         }
@@ -489,11 +495,12 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         raw_d.store_swapped(dOm + (size_t)vd_row * PV + 16 * vd_grp);
     }
     // rf is re-derived from the raw rows in the epilogue (the raw bf16 pairs cost half the registers)
-    const int row0 = n * C + RW * w;
+    const ChunkRows cr = chunk_rows(p.lay.sub, n, N);     // which tokens the chunk's rows stand for
+    const int row0 = cr.tok0 + RW * w;
     f32x2 rf[RW], rq[RW];
-    convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
-    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, N);
-    convert_rows<RW>(rq, raw_q, row0, N, k_act, io_bf16, 0.0f);
+    convert_rows<RW>(rf, raw_f, row0, cr.end, k_act, gate_bf16, 1.0f, cr.first);
+    if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, k_act ? 2 * lane : 0, k_act, row0, cr.end, cr.first);
+    convert_rows<RW>(rq, raw_q, row0, cr.end, k_act, io_bf16, 0.0f, cr.first);
 
     // ---------------- gate products; scaled operand tiles ----------------
     // With a = inclusive gate product from the start of this wave's 8-row block, z = exclusive
@@ -777,7 +784,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     T* dqg = static_cast<T*>(p.dq);
     T* dfg = static_cast<T*>(p.df);
     // (gates formed from pre-activations are kept instead: a second round of exponentials and reciprocals costs more than 16 registers)
-    if (!p.beta) convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
+    if (!p.beta) convert_rows<RW>(rf, raw_f, row0, cr.end, k_act, gate_bf16, 1.0f, cr.first);
     if constexpr (FUSED) {
         // the gate products again (32 multiplications) rather than 32 registers kept through the contractions
         asm volatile("" : "+v"(rf[0].x), "+v"(rf[0].y));
@@ -791,14 +798,14 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     // rows of this wave's block to global memory: one address and constant offsets when the
     // whole block lies inside the sequence, row by row otherwise
     auto store_block = [&](T* dst, const float (&x0)[RW], const float (&x1)[RW]) {
-        T* bp = dst + seq_k + (size_t)row0 * ld_k + 2 * lane;
-        if (row0 + RW <= N) {
+        T* bp = dst + seq_k + (ptrdiff_t)row0 * (ptrdiff_t)ld_k + 2 * lane;
+        if (row0 >= cr.first && row0 + RW <= cr.end) {
 #pragma unroll
             for (int i = 0; i < RW; ++i) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         } else {
 #pragma unroll
             for (int i = 0; i < RW; ++i)
-                if (row0 + i < N) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
+                if (cr.holds(RW * w + i)) store_pair_t<T>(bp, (size_t)i * ld_k, x0[i], x1[i]);
         }
     };
     if (k_act) {
@@ -831,8 +838,8 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         T* dvg = static_cast<T*>(p.dv);
         for (int idx = tid; idx < C * VPR; idx += kBwdThreads) {
             const int row = idx / VPR, cv = idx % VPR;
-            const int grow = n * C + row;
-            if (grow < N)
+            const int grow = cr.tok0 + row;
+            if (cr.holds(row))
                 *reinterpret_cast<u32x4*>(dvg + seq_v + (size_t)grow * ld_v + cv * VEC) =
                     *reinterpret_cast<const u32x4*>(dVs + (size_t)row * PVR + cv * VEC);
         }

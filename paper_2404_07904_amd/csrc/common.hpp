@@ -56,6 +56,26 @@ struct SeqView {
     int N, NC;
 };
 
+// Which tokens the C rows of chunk n of a sequence of N tokens stand for.  Ordinarily row r is token
+// n C + r.  In the small-gate modes (TokenLayout::sub = 16 or 32) a chunk holds only `sub` tokens,
+// n sub .. (n + 1) sub - 1, in its middle rows (C - sub) / 2 .. (C + sub) / 2 - 1: the mid-chunk
+// reference row then has at most sub / 2 tokens on either side, which is all a quotient of gate
+// products ever spans.  The other rows stand for no token and behave like the rows past the end of a
+// sequence (f = 1, q = 0, whatever finite values for v and grad_o; nothing stored), which leaves
+// Eq. 3 unchanged.  Row r stands for token tok0 + r iff first <= tok0 + r < end.
+struct ChunkRows {
+    int tok0, first, end;
+    __device__ __forceinline__ bool holds(int row) const { return tok0 + row >= first && tok0 + row < end; }
+};
+__device__ __forceinline__ ChunkRows chunk_rows(int sub, int n, int N)
+{
+    ChunkRows c;
+    c.tok0 = n * sub - (kChunk - sub) / 2;
+    c.first = max(n * sub, 0);
+    c.end = min(N, (n + 1) * sub);
+    return c;
+}
+
 // RUNS: the caller is one of the kernels that walk a sequence and may be handed the runs of
 // segmented sequences (TokenLayout::seg); the per-chunk kernels never are.
 template <bool DENSE, int DK, int DV, bool RUNS = false>
@@ -65,7 +85,7 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
     if (RUNS && lay.seg > 1) {
         // run r of sequence bh / seg: N tokens (NC chunks) unless it is the last, shorter one
         const int whole = bh / lay.seg, r = bh - whole * lay.seg;
-        const int nc_all = (lay.n_tokens + kChunk - 1) / kChunk;
+        const int nc_all = (lay.n_tokens + lay.sub - 1) / lay.sub;
         s.N = min(N, lay.n_tokens - r * N);
         s.NC = min(NC, nc_all - r * NC);
         s.chunk0 = (size_t)whole * nc_all + (size_t)r * NC;
@@ -199,7 +219,8 @@ template <> __device__ __forceinline__ void store_pair_t<float>(float* base, siz
 // that all loads of a batch are issued back to back and converted only when first used.  Row
 // indices are clamped into [0, n_rows) and the column is the caller's (already valid) one, so
 // every address is in bounds and no load sits behind a branch; out-of-range rows are replaced
-// by `fill` at conversion time.
+// by `fill` at conversion time.  (`row0` may be negative or past the end: the first rows of a chunk
+// of a small-gate mode stand for no token, see ChunkRows.)
 template <int RW> struct RawRows { f32x2 r[RW]; };
 
 template <int RW>
@@ -208,7 +229,7 @@ __device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, si
 {
     // A block that lies fully inside the sequence (every block but possibly the last) needs one
     // address; its rows are compile-time offsets from it.  Only a ragged block clamps per row.
-    const bool full = row0 + RW <= n_rows;
+    const bool full = row0 >= 0 && row0 + RW <= n_rows;
     if (is_bf16) {
         const char* b = static_cast<const char*>(base) + (seq_off + col) * 2;
         if (full) {
@@ -219,7 +240,7 @@ __device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, si
         } else {
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
-                const int rc = min(row0 + i, n_rows - 1);
+                const int rc = min(max(row0 + i, 0), n_rows - 1);
                 out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(b + (size_t)rc * row_stride * 2));
             }
         }
@@ -232,7 +253,7 @@ __device__ __forceinline__ void load_rows(RawRows<RW>& out, const void* base, si
         } else {
 #pragma unroll
             for (int i = 0; i < RW; ++i) {
-                const int rc = min(row0 + i, n_rows - 1);
+                const int rc = min(max(row0 + i, 0), n_rows - 1);
                 out.r[i] = *reinterpret_cast<const f32x2*>(b + (size_t)rc * row_stride * 4);
             }
         }
@@ -249,7 +270,7 @@ __device__ __forceinline__ void load_rows_clamped(RawRows<RW>& out, const char* 
                                                   int row_elems, int lane_col)
 {
     constexpr int ES = IS_BF16 ? 2 : 4;
-    if (row0 + RW - 1 <= last_row) {      // whole block inside the sequence: one address, constant offsets
+    if (row0 >= 0 && row0 + RW - 1 <= last_row) {      // whole block inside the sequence: one address, constant offsets
         const char* rp = seq_base + (size_t)row0 * (row_elems * ES) + lane_col * ES;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
@@ -259,18 +280,19 @@ __device__ __forceinline__ void load_rows_clamped(RawRows<RW>& out, const char* 
     } else {
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
-            const char* rp = seq_base + (size_t)min(row0 + i, last_row) * (row_elems * ES);
+            const char* rp = seq_base + (size_t)min(max(row0 + i, 0), last_row) * (row_elems * ES);
             if (IS_BF16) out.r[i].x = __uint_as_float(*reinterpret_cast<const uint32_t*>(rp + lane_col * ES));
             else out.r[i] = *reinterpret_cast<const f32x2*>(rp + lane_col * ES);
         }
     }
 }
 
+// Rows row0 + i outside [first_row, n_rows) are replaced by `fill`.
 template <int RW>
 __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>& raw, int row0, int n_rows,
-                                             bool lane_active, bool is_bf16, float fill)
+                                             bool lane_active, bool is_bf16, float fill, int first_row = 0)
 {
-    const bool all_rows = row0 + RW <= n_rows;      // wave-uniform: only the last chunk can be ragged
+    const bool all_rows = row0 >= first_row && row0 + RW <= n_rows;      // wave-uniform
 #pragma unroll
     for (int i = 0; i < RW; ++i) {
         f32x2 x = raw.r[i];
@@ -284,7 +306,7 @@ __device__ __forceinline__ void convert_rows(f32x2 (&dst)[RW], const RawRows<RW>
     if (!all_rows || !lane_active) {
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
-            const bool ok = lane_active && (row0 + i < n_rows);
+            const bool ok = lane_active && (row0 + i >= first_row) && (row0 + i < n_rows);
             dst[i].x = ok ? dst[i].x : fill;
             dst[i].y = ok ? dst[i].y : fill;
         }
@@ -306,12 +328,12 @@ __device__ __forceinline__ float lower_bounded_gate(float z, float beta)
 
 template <int RW>
 __device__ __forceinline__ void gate_rows(f32x2 (&rf)[RW], const float* beta_head, int col, bool lane_active,
-                                          int row0, int n_rows)
+                                          int row0, int n_rows, int first_row = 0)
 {
     const f32x2 b = *reinterpret_cast<const f32x2*>(beta_head + col);
 #pragma unroll
     for (int i = 0; i < RW; ++i) {
-        const bool ok = lane_active && (row0 + i < n_rows);
+        const bool ok = lane_active && (row0 + i >= first_row) && (row0 + i < n_rows);
         rf[i].x = ok ? lower_bounded_gate(rf[i].x, b.x) : 1.0f;
         rf[i].y = ok ? lower_bounded_gate(rf[i].y, b.y) : 1.0f;
     }

@@ -87,8 +87,11 @@ template <int NSPLIT> struct FwdFusedLds {
 // One chunk of the walk: tokens row0 .. row0 + C - 1 of a sequence of N tokens whose first token is
 // token tok0 of the packed tensors (grouped walks; 0 otherwise).  N = 0: a pass past the end.
 // `slot` is the chunk's place in an array with one entry per chunk of the batch (the kept states).
+// Row r of the chunk stands for token row0 + r of the sequence where lo <= row0 + r < hi and for no
+// token elsewhere (past the end of the sequence; in the small-gate modes, outside the chunk's middle
+// rows: ChunkRows).
 struct FusedChunk {
-    int tok0, row0, N, bh, first, last, slot;
+    int tok0, row0, N, bh, first, last, slot, lo, hi;
 };
 
 template <bool GATE_BF16, int NSPLIT, bool DENSE, bool GROUPED>
@@ -206,20 +209,23 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             } else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; cur_slot = 0; }          // past the end, for good
             cur_n = 0;
         }
-        c.tok0 = cur_tok; c.row0 = cur_n * C; c.N = cur_N; c.bh = cur_e * p.lay.H + head;
+        c.tok0 = cur_tok; c.row0 = cur_n * C; c.N = cur_N; c.bh = cur_e * p.lay.H + head; c.lo = c.row0; c.hi = cur_N;
         c.first = cur_n == 0; c.last = cur_N > 0 && cur_n == cur_nc - 1; c.slot = cur_slot + cur_n;
         return c;
     };
     const int N_one = sv.N;
     auto chunk_at = [&](int c) {             // one sequence per workgroup: chunk c of it (any c >= -1)
         FusedChunk k;
-        k.tok0 = 0; k.row0 = c * C; k.N = N_one; k.bh = bh; k.first = c == 0; k.last = c == NC - 1; k.slot = sv.chunk0 + c;
+        const ChunkRows cr = chunk_rows(p.lay.sub, c, N_one);
+        k.tok0 = 0; k.row0 = cr.tok0; k.lo = cr.first; k.hi = cr.end;
+        k.N = N_one; k.bh = bh; k.first = c == 0; k.last = c == NC - 1; k.slot = sv.chunk0 + c;
         return k;
     };
     // window of the pass: ck[j] = chunk n - 1 + j of pass n (grouped walks only)
     FusedChunk ck[5];
     if constexpr (GROUPED) {
         ck[0].tok0 = 0; ck[0].row0 = 0; ck[0].N = 0; ck[0].bh = bh; ck[0].first = 1; ck[0].last = 0; ck[0].slot = 0;
+        ck[0].lo = 0; ck[0].hi = 0;
 #pragma unroll
         for (int j = 1; j < 5; ++j) ck[j] = next_chunk();
     }
@@ -303,7 +309,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
         const char* vb = vbase + (size_t)c.tok0 * ((size_t)ld_v * 2);
 #pragma unroll
         for (int j = 0; j < NVV; ++j) {
-            const int rc = min(row0 + lane / VPR + VRS * j, last_row);
+            const int rc = min(max(row0 + lane / VPR + VRS * j, 0), last_row);
             d[j] = *reinterpret_cast<const u32x4*>(vb + (size_t)rc * ((size_t)ld_v * 2) + 2 * vcol);
         }
     };
@@ -329,9 +335,9 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     float below_floor = 1.0f;            // smallest product a reciprocal was taken of (reported once, at the end)
     auto prep_gates = [&](const RawRows<RW>& rf_raw, const RawRows<RW>& rq_raw, const FusedChunk& c) {
         f32x2 rf[RW];
-        convert_rows<RW>(rf, rf_raw, c.row0 + RW * w, c.N, true, GATE_BF16, 1.0f);
+        convert_rows<RW>(rf, rf_raw, c.row0 + RW * w, c.hi, true, GATE_BF16, 1.0f, c.lo);
         if (p.beta)
-            gate_rows<RW>(rf, p.beta + (size_t)(GROUPED ? head : bh / p.lay.seg % p.H) * DK, 2 * lane, true, c.row0 + RW * w, c.N);
+            gate_rows<RW>(rf, p.beta + (size_t)(GROUPED ? head : bh / p.lay.seg % p.H) * DK, 2 * lane, true, c.row0 + RW * w, c.hi, c.lo);
         float run0 = 1.0f, run1 = 1.0f;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
@@ -408,7 +414,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             const int row = idx / VPR, cv = idx % VPR;
             const int grow = c.row0 + row;
             obuf[k] = *reinterpret_cast<const u32x4*>(Ost + (size_t)row * PO + cv * 8);
-            if ((unsigned)grow < (unsigned)c.N)    // also false for the chunk "-1" of the first pass
+            if (grow >= c.lo && grow < c.hi)       // also false for the chunk "-1" of the first pass
                 *reinterpret_cast<u32x4*>(og + seq_v + ((size_t)c.tok0 + grow) * ld_v + dv0 + cv * 8) = obuf[k];
         }
     };

@@ -69,6 +69,7 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
     const SeqView sv = seq_view<DENSE, DK, DV>(p.lay, p.N, p.NC, bh);
     const size_t seq_k = sv.off_k, seq_v = sv.off_v;
     const int N = sv.N;
+    const ChunkRows cr = chunk_rows(p.lay.sub, n, N);        // which tokens the chunk's rows stand for
     const int ld_k = DENSE ? DK : (int)p.lay.sn_k, ld_v = DENSE ? DV : (int)p.lay.sn_v;   // token stride, elements
     const bool gate_bf16 = p.gate_bf16 != 0;
     const T* qg = static_cast<const T*>(p.q);
@@ -87,15 +88,15 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
     f32x2 rf[RW], rq[RW], rv[RW];
     {
         RawRows<RW> raw_f, raw_q, raw_v;
-        const int row0 = n * C + RW * w;
+        const int row0 = cr.tok0 + RW * w;
         const int col_k = k_act ? 2 * lane : 0, col_v = v_act ? 2 * lane : 0;
         load_rows<RW>(raw_f, p.f, seq_k, ld_k, col_k, row0, N, gate_bf16);
         load_rows<RW>(raw_q, qg, seq_k, ld_k, col_k, row0, N, is_bf16_type<T>());
         load_rows<RW>(raw_v, vg, seq_v, ld_v, col_v, row0, N, is_bf16_type<T>());
-        convert_rows<RW>(rf, raw_f, row0, N, k_act, gate_bf16, 1.0f);
-        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, N);
-        convert_rows<RW>(rq, raw_q, row0, N, k_act, is_bf16_type<T>(), 0.0f);
-        convert_rows<RW>(rv, raw_v, row0, N, v_act, is_bf16_type<T>(), 0.0f);
+        convert_rows<RW>(rf, raw_f, row0, cr.end, k_act, gate_bf16, 1.0f, cr.first);
+        if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh % p.H) * DK, col_k, k_act, row0, cr.end, cr.first);
+        convert_rows<RW>(rq, raw_q, row0, cr.end, k_act, is_bf16_type<T>(), 0.0f, cr.first);
+        convert_rows<RW>(rv, raw_v, row0, cr.end, v_act, is_bf16_type<T>(), 0.0f, cr.first);
     }
 
     // ---------------- gate products and scaled operands ----------------
@@ -213,8 +214,8 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
         T* og = static_cast<T*>(p.o);
         for (int idx = tid; idx < C * VPR; idx += kThreads) {
             const int row = idx / VPR, cv = idx % VPR;
-            const int grow = n * C + row;
-            if (grow < N) {
+            const int grow = cr.tok0 + row;
+            if (cr.holds(row)) {
                 const uint4 val = *reinterpret_cast<const uint4*>(Ost + (size_t)row * PO + cv * VEC);
                 *reinterpret_cast<uint4*>(og + seq_v + (size_t)grow * ld_v + cv * VEC) = val;
             }

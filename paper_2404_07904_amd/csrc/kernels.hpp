@@ -10,7 +10,7 @@ namespace hgrn2 {
 
 // Compile-time chunk length of the chunkwise kernels.
 constexpr int kChunk = 64;
-constexpr int kFineChunk = 16;     // closest spacing of the reference rows in the small-gate modes (spread.hip); 32 is the other
+constexpr int kFineChunk = 16;     // closest spacing of the reference rows in the small-gate modes; 32 is the other
 
 // Where token (b, h, n) of q / f (channel count dk) and of v / o (dv) starts, in elements:
 // b * sb + h * sh + n * sn.  [B][H][N][d] has sb = H N d, sh = N d, sn = d; [B][N][H][d] (what a
@@ -51,6 +51,9 @@ struct TokenLayout {
     // the length of the uncut sequence, whose last run may be shorter.
     int seg = 1;
     int n_tokens = 0;
+    // Tokens per chunk: kChunk, or 16 / 32 in the small-gate modes of equal-length batches, where a
+    // chunk's other rows stand for no token (ChunkRows in common.hpp).  NC counts chunks of `sub` tokens.
+    int sub = kChunk;
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
     __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
 };
@@ -227,22 +230,13 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
-// Small-gate modes (spread.hip): every block of `block` (16 or 32) tokens becomes a chunk of its own,
-// padded with tokens that change nothing.  spread_tokens(N, block) is the length of the spread sequence;
-// launch_spread copies a caller's tensor (q, f: key_side; v, o, gradients alike) into a dense
-// [BH][spread_tokens(N, block)][d] one with the given filler; launch_gather copies the
-// real tokens of such a tensor back into a caller's tensor.  `d` describes the caller's tensors.
-int spread_tokens(int N, int block);
+// Small-gate modes of packed batches (spread.hip): every sequence is spread, block of `block` (16 or
+// 32) tokens by block, into the middle rows of chunks of its own, the other rows padded with tokens
+// that change nothing.  spread_tokens_packed() bounds the rows of the spread batch,
+// launch_spread_offsets writes the first spread row of every sequence (B + 1 ints, the spread batch's
+// cumulative sequence lengths) from the batch's sequence table, and launch_spread_packed copies
+// [T][row] tensors to spread ones (to_spread) or back.
 enum SpreadFill { kFillZero, kFillOne, kFillPlusInf };      // q, v, gradients; gates f; gate pre-activations z
-hipError_t launch_spread(const SeqDims& d, int block, bool key_side, bool bf16, SpreadFill fill, const void* src, void* dst,
-                         hipStream_t stream);
-hipError_t launch_gather(const SeqDims& d, int block, bool key_side, bool bf16, const void* src, void* dst,
-                         hipStream_t stream);
-
-// The same for a packed batch, whose sequences are spread one by one: spread_tokens_packed() bounds
-// the rows of the spread batch, launch_spread_offsets writes the first spread row of every sequence
-// (B + 1 ints, the spread batch's cumulative sequence lengths) from the batch's sequence table, and
-// launch_spread_packed copies [T][row] tensors to spread ones (to_spread) or back.
 int spread_tokens_packed(int T, int B, int block);
 hipError_t launch_spread_offsets(const int* seq_table, int B, int block, int* cu_spread, hipStream_t stream);
 hipError_t launch_spread_packed(int T, int B, int block, int row_bytes, SpreadFill fill, bool bf16, const int* seq_table,

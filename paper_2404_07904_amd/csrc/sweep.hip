@@ -105,7 +105,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     RawRows<RW> raw_f, raw_q, raw_b;
     const int col_a = a_act ? 2 * lane : 0, col_b = col0 + (b_act ? 2 * lane : 0);
     auto load_chunk = [&](const SeqView& s, int n) {
-        const int row0 = n * C + RW * w;
+        const int row0 = chunk_rows(p.lay.sub, n, s.N).tok0 + RW * w;
         load_rows<RW>(raw_f, p.f, s.off_k, ld_k, col_a, row0, s.N, gate_bf16);
         if (MODE == kSweepGrad) load_rows<RW>(raw_q, qsrc, s.off_k, ld_k, col_a, row0, s.N, is_bf16_type<T>());
         load_rows<RW>(raw_b, bsrc, s.off_v, ld_v, col_b, row0, s.N, is_bf16_type<T>());
@@ -175,11 +175,12 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
         T* ws = static_cast<T*>(p.ws) + sv.chunk0 * DK * DV;
         f32x2 rf[RW], rq[RW], rb[RW];
         {
-            const int row0 = n * C + RW * w;
-            convert_rows<RW>(rf, raw_f, row0, N, a_act, gate_bf16, 1.0f);
-            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh / p.lay.seg % p.H) * DK, col_a, a_act, row0, N);
-            if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, N, a_act, is_bf16_type<T>(), 0.0f);
-            convert_rows<RW>(rb, raw_b, row0, N, b_act, is_bf16_type<T>(), 0.0f);
+            const ChunkRows cr = chunk_rows(p.lay.sub, n, N);
+            const int row0 = cr.tok0 + RW * w;
+            convert_rows<RW>(rf, raw_f, row0, cr.end, a_act, gate_bf16, 1.0f, cr.first);
+            if (p.beta) gate_rows<RW>(rf, p.beta + (size_t)(bh / p.lay.seg % p.H) * DK, col_a, a_act, row0, cr.end, cr.first);
+            if (MODE == kSweepGrad) convert_rows<RW>(rq, raw_q, row0, cr.end, a_act, is_bf16_type<T>(), 0.0f, cr.first);
+            convert_rows<RW>(rb, raw_b, row0, cr.end, b_act, is_bf16_type<T>(), 0.0f, cr.first);
         }
 
         // ---- gate products of this thread's RW tokens, channel pair (2*lane, 2*lane+1) ----

@@ -66,17 +66,17 @@ def test_workspace_sizes():
 
 
 def test_small_gate_mode_workspace_and_support():
-    """chunk = 16: four (seven) spread tensors, then the workspace of the pass on the spread shape."""
+    """chunk = 16 / 32, equal lengths: chunks of that many tokens, so the workspace of a sequence of
+    64 / chunk times as many tokens and nothing else; packed batches: spread tensors and the inner call."""
     s = shape(B=2, H=3, N=200, dk=64, dv=128, chunk=16)
-    spread = 2 * 3 * (13 * 64)                                  # 13 blocks of 16 tokens, a chunk each
-    inner = shape(B=2, H=3, N=13 * 64, dk=64, dv=128)
-    assert binding.hgrn2_fwd_workspace_bytes(s) == spread * (64 + 64 + 128 + 128) * 2 + binding.hgrn2_fwd_workspace_bytes(inner)
-    assert binding.hgrn2_bwd_workspace_bytes(s) == spread * (4 * 64 + 3 * 128) * 2 + binding.hgrn2_bwd_workspace_bytes(inner)
+    inner = shape(B=2, H=3, N=13 * 64, dk=64, dv=128)           # 13 blocks of 16 tokens, a chunk each
+    assert binding.hgrn2_fwd_workspace_bytes(s) == binding.hgrn2_fwd_workspace_bytes(inner) == 2 * 3 * 13 * 64 * 128 * 2
+    assert binding.hgrn2_bwd_workspace_bytes(s) == binding.hgrn2_bwd_workspace_bytes(inner)
+    assert binding.hgrn2_saved_states_bytes(s) == 2 * 3 * 13 * 64 * 128 * 2
     lib = binding.lib()
     sp = ctypes.byref(s)
     big = 1 << 40
-    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == (spread * (4 * 64 + 3 * 128) * 2
-                                                          + binding.hgrn2_bwd_gated_workspace_bytes(inner))
+    assert binding.hgrn2_bwd_gated_workspace_bytes(s) == binding.hgrn2_bwd_gated_workspace_bytes(inner)
     assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL      # beta missing
     # packed batches: sequence table, spread offsets, the spread tensors of (200 // 16 + 2) chunks, the inner call
     sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=16)
@@ -90,8 +90,7 @@ def test_small_gate_mode_workspace_and_support():
     assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=48)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
     # reference rows every 32 tokens: 7 blocks of 32 tokens, a chunk each
     s32 = shape(B=2, H=3, N=200, dk=64, dv=128, chunk=32)
-    assert binding.hgrn2_fwd_workspace_bytes(s32) == (2 * 3 * 7 * 64 * (64 + 64 + 128 + 128) * 2
-                                                      + binding.hgrn2_fwd_workspace_bytes(shape(B=2, H=3, N=7 * 64, dk=64, dv=128)))
+    assert binding.hgrn2_fwd_workspace_bytes(s32) == binding.hgrn2_fwd_workspace_bytes(shape(B=2, H=3, N=7 * 64, dk=64, dv=128))
 
 
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):

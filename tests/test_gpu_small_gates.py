@@ -1,6 +1,7 @@
 """Small gates.  With a reference row every 64 tokens the chunkwise kernels are exact while the gate
 product of every half chunk stays above 2^-100; chunk = 16 (32) in the shape asks for reference rows
-every 16 (32) tokens (the passes then run on sequences spread to four times (twice) their length),
+every 16 (32) tokens (a chunk of the kernels then holds only that many tokens, in its middle rows;
+packed batches are copied into spread ones),
 which moves that bound to products of 8 (16) gates.  The cases here lie outside the first domain and inside the
 second and are compared with the fp64 oracle, which has no such limit; the probe must say so for
 both spacings.  Tolerance: max|x-y|/max|y| <= 2e-2 per tensor (bf16), 1e-4 (fp32 forward)."""
@@ -64,6 +65,39 @@ def test_small_gates_fwd_bwd(kind, B, H, N, dk, dv, layout, chunk):
     check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
     check("dh0", host(gh0), rh, tol)
     print("    for comparison, o with reference rows every 64 tokens: error %.3e" % rel_err(get(o64), ro), flush=True)
+
+
+@pytest.mark.parametrize("kind,B,H,N,dk,dv,layout,chunk,io", [
+    ("loguniform", 8, 16, 200, 128, 128, 0, 16, "bf16"),      # single-pass forward hands its states over; two light runs backward
+    ("loguniform32", 2, 2, 1500, 128, 128, 1, 32, "bf16"),    # 47 chunks of 32 tokens: runs forward, boundary sweeps backward
+    ("resets", 1, 3, 130, 64, 128, 0, 16, "bf16"),
+    ("loguniform32", 2, 2, 150, 64, 64, 0, 16, "f32"),        # fp32 storage: the chunkwise algebra of the mode at 1e-4 (gates
+                                                               # >= 0.02: grad_f divides by f, which multiplies fp32 rounding by 1/f)
+])
+def test_small_gates_training_pair(kind, B, H, N, dk, dv, layout, chunk, io):
+    """hgrn2_fwd_saving / hgrn2_bwd_saved with reference rows every 16 / 32 tokens: the kept states are those
+    of the shorter chunks."""
+    print("\n[small gates, training pair] %s B=%d H=%d N=%d dk=%d dv=%d layout=%d chunk=%d %s"
+          % (kind, B, H, N, dk, dv, layout, chunk, io), flush=True)
+    w = small_gate_workload(7750 + N, B, H, N, dk, dv, kind, io_dtype=io)
+    put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
+    get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
+    q, f, v, dO = put(dev(w.q, io)), put(dev(w.f, io)), put(dev(w.v, io)), put(dev(w.dO, io))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    fine = float(binding.hgrn2_min_gate_product(f, layout=layout, chunk=chunk).item())
+    assert LIMIT < fine
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o, hT, saved = binding.hgrn2_fwd_saving(q, f, v, h0, layout=layout, chunk=chunk, domain_flag=flag)
+    gq, gf, gv, gh0 = binding.hgrn2_bwd_saved(q, f, v, saved, dO, dhT, want_grad_h0=True, layout=layout, chunk=chunk,
+                                             domain_flag=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    tol = TOL[io]
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    rq, rf, rv, rh = oracle.bwd(w.q, w.f, w.v, w.dO, w.h0, w.dhT)
+    check("o", get(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
+    check("dh0", host(gh0), rh, tol)
 
 
 def test_small_gates_fp32_forward():
