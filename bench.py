@@ -469,6 +469,25 @@ def main():
                                      "workspace_MB": round(wsf.numel() / 1e6, 1),
                                      "saved_states_MB": round(savedf.numel() / 1e6, 1)}
             del wsf, savedf
+        # chunk length chosen on the device (HGRN2_CHUNK_AUTO): the headline's training pair with ordinary
+        # gates, for which the passes for 32 and 16 tokens per chunk are enqueued and return at once
+        sha = binding.make_shape(sets[0][0], sets[0][2], sets[0][1], -1)
+        wsa = torch.empty(binding.hgrn2_bwd_workspace_bytes(sha), dtype=torch.uint8, device=dev)
+        saveda = torch.empty(binding.hgrn2_saved_states_bytes(sha), dtype=torch.uint8, device=dev)
+
+        def auto_pair(i):
+            q, f, v, dO = sets[i % 2]
+            binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=saveda, workspace=wsa, chunk=-1)
+            binding.hgrn2_bwd_saved(q, f, v, saveda, dO, None, workspace=wsa, grad_q=gq, grad_f=gf, grad_v=gv, chunk=-1)
+
+        for i in range(10):
+            auto_pair(i)
+        dta = timed(auto_pair, reps=40)
+        fine["chunk_chosen_on_device"] = {"training_pair_ms_per_step": round(dta * 1e3, 4),
+                                          "training_pair_tokens_per_s": round(tokens / dta, 1),
+                                          "workspace_MB": round(wsa.numel() / 1e6, 1),
+                                          "saved_states_MB": round(saveda.numel() / 1e6, 1)}
+        del wsa, saveda
         fine["workload"] = ("the main shape and gates with a reference row every 32 (16) tokens: chunks that hold 32 (16) "
                             "tokens in their middle rows")
         result["small_gate_modes"] = fine

@@ -45,6 +45,14 @@
  *     hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  Packed batches (_varlen) are
  *     copied into spread ones for it (their workspace also holds those copies).
  *     hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     chunk = HGRN2_CHUNK_AUTO (equal-length batches: hgrn2_fwd, hgrn2_bwd, their _gated, _saving /
+ *     _saved and _noalloc forms) needs no probe: the pass is enqueued for 64, then 32, then 16 tokens
+ *     per chunk; the kernels of the first raise a flag inside the workspace when a product falls
+ *     below the floor, those of the next run only if it is set (they return at once otherwise) and
+ *     overwrite every result, and so on.  The results are those of the longest chunk the gates
+ *     allow; shape->gate_domain_flag is raised only when even 16 tokens per chunk are too many.
+ *     Ordinary gates pay two launches that do nothing (a few microseconds per pass); the
+ *     workspaces and saved states are sized for 16 tokens per chunk.
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
@@ -73,6 +81,8 @@ typedef enum {
 } hgrn2_status;
 
 typedef enum { HGRN2_F32 = 0, HGRN2_BF16 = 1 } hgrn2_dtype;
+/* hgrn2_shape::chunk value that lets the device choose the chunk length (see "Gate domain" above) */
+#define HGRN2_CHUNK_AUTO (-1)
 
 /* Memory order of the sequence tensors.  The d channels of one token of one head are always
  * contiguous; HGRN2_LAYOUT_BNHD is what a projection of a [B][N][model width] activation writes

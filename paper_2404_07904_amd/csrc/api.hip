@@ -251,6 +251,46 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
 // ---- small-gate modes -----------------------------------------------------------------------------
 bool fine_mode(const hgrn2_shape* s) { return s && (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk); }
 
+// chunk = HGRN2_CHUNK_AUTO (equal-length batches): the pass is enqueued for 64, then 32, then 16
+// tokens per chunk.  The kernels of the first raise a flag when a gate product falls below the floor
+// of their reciprocals; those of the second run only if it is set (the others return at once) and
+// raise a second flag, on which the third depends: the results are those of the longest chunk the
+// gates allow, at the cost of two launches that do nothing when the gates are ordinary.
+bool auto_mode(const hgrn2_shape* s) { return s && s->chunk == HGRN2_CHUNK_AUTO; }
+constexpr size_t kAutoHead = 256;         // the flags, at the head of the workspace (ints: flag of 64, flag of 32)
+constexpr int kAlternatives = 3;
+
+// the shapes the pass is run on: the caller's, or its three alternatives
+int alternatives(const hgrn2_shape* shape, hgrn2_shape (&alt)[kAlternatives])
+{
+    alt[0] = *shape;
+    if (!auto_mode(shape)) return 1;
+    static const int32_t chunks[kAlternatives] = {0, 2 * kFineChunk, kFineChunk};
+    for (int i = 0; i < kAlternatives; ++i) { alt[i] = *shape; alt[i].chunk = chunks[i]; }
+    return kAlternatives;
+}
+
+// largest value of a size over the alternatives (0 as soon as one of them is 0 for a shape with tokens: invalid)
+template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F bytes_of, bool head)
+{
+    if (!shape) return 0;
+    hgrn2_shape alt[kAlternatives];
+    const int n = alternatives(shape, alt);
+    size_t m = 0;
+    for (int i = 0; i < n; ++i) { const size_t b = bytes_of(&alt[i]); if (b > m) m = b; }
+    return m + ((n > 1 && head) ? kAutoHead : 0);
+}
+
+// How one alternative is enqueued: which device int its kernels compare with `path` before doing
+// anything (null: they always run), and which device int they raise when a gate product falls below
+// the floor (instead of the shape's own).
+struct Alternative {
+    const int* choice = nullptr;
+    int path = 0;
+    int* flag = nullptr;
+    bool validate_only = false;           // stop after the argument checks
+};
+
 // packed batches: N counts the tokens of all sequences
 hgrn2_shape spread_shape_packed(const hgrn2_shape& s)
 {
@@ -277,30 +317,82 @@ extern "C" {
 
 size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
 {
-    SeqDims d;
-    if (check_shape(shape, false, &d, false, true) != HGRN2_OK) return 0;
-    return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
+    return max_over_alternatives(shape, [](const hgrn2_shape* s) -> size_t {
+        SeqDims d;
+        if (check_shape(s, false, &d, false, true) != HGRN2_OK) return 0;
+        return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
+    }, true);
 }
 
 size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
 {
-    SeqDims d;
-    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    return bwd_layout(d, false).total();
+    return max_over_alternatives(shape, [](const hgrn2_shape* s) -> size_t {
+        SeqDims d;
+        if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
+        return bwd_layout(d, false).total();
+    }, true);
 }
 
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream, void* save_states = nullptr);
+static int fwd_one(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                   const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                   void* hip_stream, void* save_states, const Alternative* alt);
+static int bwd_one(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                   const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                   void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                   size_t workspace_bytes, void* hip_stream, const void* saved_states, const Alternative* alt);
 static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                     size_t workspace_bytes, void* hip_stream, const void* saved_states = nullptr);
 
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
+// With chunk = HGRN2_CHUNK_AUTO: its three alternatives.  `save_states` then ends in kAutoHead bytes
+// whose first int names the alternative that ran (0, 1, 2), for the backward pass of the pair.
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream, void* save_states)
+{
+    if (!auto_mode(shape)) return fwd_one(shape, q, f, beta, gated, v, h0, o, hT, workspace, workspace_bytes, hip_stream, save_states, nullptr);
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    const size_t need = hgrn2_fwd_workspace_bytes(shape);
+    if (need == 0) {                      // an invalid shape: the first alternative names the error
+        SeqDims d;
+        const int rc = check_shape(&alt[0], false, &d, false, true);
+        return rc != HGRN2_OK ? rc : HGRN2_ERR_SHAPE;
+    }
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    char* rest = static_cast<char*>(workspace) + kAutoHead;
+    Alternative a;
+    a.validate_only = true;
+    for (int i = 0; i < kAlternatives; ++i) {
+        const int rc = fwd_one(&alt[i], q, f, beta, gated, v, h0, o, hT, rest, workspace_bytes - kAutoHead, hip_stream, save_states, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* flags = static_cast<int*>(workspace);
+    if (launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    a.validate_only = false;
+    for (int i = 0; i < kAlternatives; ++i) {
+        a.choice = i == 0 ? nullptr : flags + (i - 1);
+        a.path = 1;
+        a.flag = i + 1 < kAlternatives ? flags + i : shape->gate_domain_flag;
+        const int rc = fwd_one(&alt[i], q, f, beta, gated, v, h0, o, hT, rest, workspace_bytes - kAutoHead, hip_stream, save_states, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    if (save_states) {
+        int* which = reinterpret_cast<int*>(static_cast<char*>(save_states) + hgrn2_saved_states_bytes(shape) - kAutoHead);
+        if (launch_sum_ints(flags, 2, which, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    }
+    return HGRN2_OK;
+}
+
+static int fwd_one(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                   const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
+                   void* hip_stream, void* save_states, const Alternative* alt)
 {
     SeqDims d;
     const int rc = check_shape(shape, false, &d, false, true);
@@ -309,9 +401,11 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
     if (gated && has_tokens && !beta) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
+    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.domain_flag = alt->flag; }
     const size_t one = round256(state_ws_bytes(d));
     const size_t need = one + run_state_bytes(d, false) + run_decay_bytes(d, false);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    if (alt && alt->validate_only) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (d.BH == 0) return HGRN2_OK;
     if (!has_tokens && !hT) return HGRN2_OK;
@@ -328,7 +422,7 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
         float* run_state = reinterpret_cast<float*>(static_cast<char*>(workspace) + one);
         float* run_decay = reinterpret_cast<float*>(reinterpret_cast<char*>(run_state) + run_state_bytes(d, false));
         if (launch_sweep(r, kSweepStateFwd, q, f, v, nullptr, run_state, nullptr, run_decay, stream) != hipSuccess ||
-            launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_state, run_decay, hT, false, stream) != hipSuccess)
+            launch_run_carry(d.BH, seg, d.dk, d.dv, h0, run_state, run_decay, hT, false, stream, d.lay.choice, d.lay.path) != hipSuccess)
             return HGRN2_ERR_HIP;
         if (fwd_fused_supported(r))
             return launch_fwd_fused(r, q, f, v, run_state, o, nullptr, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
@@ -359,16 +453,70 @@ int hgrn2_fwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 
 size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
 {
-    SeqDims d;
-    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    return bwd_layout(d, true).total();
+    return max_over_alternatives(shape, [](const hgrn2_shape* s) -> size_t {
+        SeqDims d;
+        if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
+        return bwd_layout(d, true).total();
+    }, true);
 }
 
 // Backward pass; `gated`: `f` holds pre-activations, grad_f receives dL/dz and grad_beta dL/dbeta.
+// With chunk = HGRN2_CHUNK_AUTO: its three alternatives, chosen as in the forward pass, or (with the
+// states a forward pass kept) by the int that pass left behind them.
 static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
                     void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                     size_t workspace_bytes, void* hip_stream, const void* saved_states)
+{
+    if (!auto_mode(shape))
+        return bwd_one(shape, q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0, workspace,
+                       workspace_bytes, hip_stream, saved_states, nullptr);
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    const size_t head = saved_states ? 0 : kAutoHead;
+    const size_t need = saved_states ? hgrn2_bwd_saved_workspace_bytes(shape, gated ? 1 : 0)
+                                     : (gated ? hgrn2_bwd_gated_workspace_bytes(shape) : hgrn2_bwd_workspace_bytes(shape));
+    {
+        SeqDims d;
+        const int rc = check_shape(&alt[0], true, &d, false, true);
+        if (rc != HGRN2_OK) return rc;
+    }
+    if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    char* rest = static_cast<char*>(workspace) + head;
+    const size_t rest_bytes = workspace_bytes - (workspace ? head : 0);
+    Alternative a;
+    a.validate_only = true;
+    for (int i = 0; i < kAlternatives; ++i) {
+        const int rc = bwd_one(&alt[i], q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                               rest, rest_bytes, hip_stream, saved_states, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* flags = static_cast<int*>(workspace);
+    const int* which = saved_states ? reinterpret_cast<const int*>(static_cast<const char*>(saved_states) +
+                                                                   hgrn2_saved_states_bytes(shape) - kAutoHead)
+                                    : nullptr;
+    if (!saved_states && launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    a.validate_only = false;
+    for (int i = 0; i < kAlternatives; ++i) {
+        if (saved_states) {
+            a.choice = which; a.path = i;
+            a.flag = i + 1 < kAlternatives ? nullptr : shape->gate_domain_flag;
+        } else {
+            a.choice = i == 0 ? nullptr : flags + (i - 1); a.path = 1;
+            a.flag = i + 1 < kAlternatives ? flags + i : shape->gate_domain_flag;
+        }
+        const int rc = bwd_one(&alt[i], q, f, beta, gated, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                               rest, rest_bytes, hip_stream, saved_states, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    return HGRN2_OK;
+}
+
+static int bwd_one(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
+                   const void* v, const float* h0, const void* grad_o, const float* grad_hT, void* grad_q,
+                   void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                   size_t workspace_bytes, void* hip_stream, const void* saved_states, const Alternative* alt)
 {
     SeqDims d;
     const int rc = check_shape(shape, true, &d, false, true);
@@ -377,9 +525,11 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
     if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
+    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.domain_flag = alt->flag; }
     const BwdLayout l = bwd_layout(d, gated, saved_states != nullptr);
     const size_t need = l.total();
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
+    if (alt && alt->validate_only) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* at = static_cast<char*>(workspace);
     auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
@@ -404,7 +554,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
         } else if (seg > 1) {
             const SeqDims r = as_runs(d, seg, run_chunks);
             if (launch_sweep(r, kSweepStateBwd, nullptr, f, v, nullptr, fwd_run_state, nullptr, fwd_run_decay, stream) != hipSuccess ||
-                launch_run_carry(d.BH, seg, d.dk, d.dv, h0, fwd_run_state, fwd_run_decay, nullptr, false, stream) != hipSuccess ||
+                launch_run_carry(d.BH, seg, d.dk, d.dv, h0, fwd_run_state, fwd_run_decay, nullptr, false, stream, d.lay.choice, d.lay.path) != hipSuccess ||
                 launch_sweep(r, kSweepStateBwd, nullptr, f, v, fwd_run_state, nullptr, ws_out, nullptr, stream) != hipSuccess)
                 return HGRN2_ERR_HIP;
         } else if (launch_sweep(d, kSweepStateBwd, nullptr, f, v, h0, nullptr, ws_out, nullptr, stream) != hipSuccess) {
@@ -425,7 +575,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
             const char* f_t = static_cast<const char*>(f) + (size_t)skip * d.lay.sn_k * ge;
             const char* g_t = static_cast<const char*>(grad_o) + (size_t)skip * d.lay.sn_v * io;
             if (launch_sweep(r, kSweepGrad, q_t, f_t, g_t, nullptr, tail_state, nullptr, tail_decay, stream) != hipSuccess ||
-                launch_run_carry(d.BH, pl.seg_tail, d.dk, d.dv, grad_hT, tail_state, tail_decay, bound0, true, stream) != hipSuccess)
+                launch_run_carry(d.BH, pl.seg_tail, d.dk, d.dv, grad_hT, tail_state, tail_decay, bound0, true, stream, d.lay.choice, d.lay.path) != hipSuccess)
                 return HGRN2_ERR_HIP;
         }
         // 3. the reverse walk: dq, df, dv of every chunk, grad_h0
@@ -486,7 +636,10 @@ int hgrn2_bwd_noalloc(const hgrn2_shape* shape, const void* q, const void* f, co
                       float* grad_h0, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, true, &d, false, true);
+    hgrn2_shape alt[kAlternatives];
+    if (!shape) return HGRN2_ERR_NULL;
+    alternatives(shape, alt);
+    const int rc = check_shape(&alt[0], true, &d, false, true);
     if (rc != HGRN2_OK) return rc;
     if (hgrn2_bwd_workspace_bytes(shape) > kScratchBytes) return HGRN2_ERR_WORKSPACE;
     void* ws = nullptr;
@@ -507,16 +660,22 @@ int hgrn2_bwd_gated(const hgrn2_shape* shape, const void* q, const void* z, cons
 
 size_t hgrn2_saved_states_bytes(const hgrn2_shape* shape)
 {
-    SeqDims d;
-    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    return round256(state_ws_bytes(d));
+    // (chunk = HGRN2_CHUNK_AUTO: room for the alternative with most chunks, then the int that names the one that ran)
+    return max_over_alternatives(shape, [](const hgrn2_shape* s) -> size_t {
+        SeqDims d;
+        if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
+        return round256(state_ws_bytes(d));
+    }, true);
 }
 
 size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated)
 {
-    SeqDims d;
-    if (check_shape(shape, true, &d, false, true) != HGRN2_OK) return 0;
-    return bwd_layout(d, gated != 0, true).total();
+    const bool g = gated != 0;
+    return max_over_alternatives(shape, [g](const hgrn2_shape* s) -> size_t {
+        SeqDims d;
+        if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
+        return bwd_layout(d, g, true).total();
+    }, false);
 }
 
 int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,
@@ -524,9 +683,12 @@ int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, con
                      void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, true, &d, false, true);      // the shapes the backward pass takes
+    hgrn2_shape alt[kAlternatives];
+    if (!shape) return HGRN2_ERR_NULL;
+    alternatives(shape, alt);
+    const int rc = check_shape(&alt[0], true, &d, false, true);      // the shapes the backward pass takes
     if (rc != HGRN2_OK) return rc;
-    const size_t need = round256(state_ws_bytes(d));
+    const size_t need = state_ws_bytes(d) > 0 ? hgrn2_saved_states_bytes(shape) : 0;
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
     return fwd_impl(shape, q, f, beta, beta != nullptr, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
                     need > 0 ? saved_states : nullptr);
@@ -538,9 +700,12 @@ int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, cons
                     size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape(shape, true, &d, false, true);
+    hgrn2_shape alt[kAlternatives];
+    if (!shape) return HGRN2_ERR_NULL;
+    alternatives(shape, alt);
+    const int rc = check_shape(&alt[0], true, &d, false, true);
     if (rc != HGRN2_OK) return rc;
-    const size_t need = round256(state_ws_bytes(d));
+    const size_t need = state_ws_bytes(d) > 0 ? hgrn2_saved_states_bytes(shape) : 0;
     if (need == 0)      // no chunks: nothing was saved, the ordinary pass handles what is left (grad_h0, grad_beta)
         return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
                         grad_h0, workspace, workspace_bytes, hip_stream);

@@ -173,10 +173,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
     float* ones = reinterpret_cast<float*>(smem + L::one);
     float* zeros = reinterpret_cast<float*>(smem + L::zero);
 
-    if constexpr (!DENSE) {
-        // a packed batch whose table chose the other backward pass: nothing to do here
-        if (p.lay.choice && table_read(p.lay.choice, 0) != p.lay.path) return;
-    }
+    if (not_chosen(p.lay)) return;       // (a packed batch whose table chose the other backward pass; a chunk length not called for)
     const int tid = threadIdx.x;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave index, in a scalar register
     constexpr bool gate_bf16 = GATE_BF16;
@@ -1097,8 +1094,10 @@ size_t beta_partials_bytes(const SeqDims& d)
 // row each, coalesced across the channels, and the 16 group sums are added in order).  Second
 // pass: the slice sums are added in order.
 __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* slice_sums, int B,
-                                                                      int H, int NC, int used, int dk, const int* vl)
+                                                                      int H, int NC, int used, int dk, const int* vl,
+                                                                      const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
     __shared__ float part[kRedGroups][64];
     const int h = blockIdx.x / (dk / 64), a = 64 * (blockIdx.x % (dk / 64)) + (threadIdx.x & 63);
     const int grp = threadIdx.x >> 6, slice = blockIdx.y;
@@ -1127,8 +1126,9 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
     }
 }
 
-__global__ void reduce_beta_slices_kernel(const float* slice_sums, float* grad_beta, int n)
+__global__ void reduce_beta_slices_kernel(const float* slice_sums, float* grad_beta, int n, const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= n) return;
     float t = 0.0f;
@@ -1144,8 +1144,10 @@ hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* g
     if (d.total_chunks() == 0) return launch_zero_floats(grad_beta, (size_t)n, stream);      // nothing contributes
     float* slice_sums = beta_partials + d.total_chunks() * kBwdWaves * d.dk;
     hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64), kRedSlices), dim3(64 * kRedGroups), 0, stream,
-                       beta_partials, slice_sums, B, d.H, d.NC, runs > 0 ? runs : d.NC, d.dk, d.lay.vl);
-    hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n);
+                       beta_partials, slice_sums, B, d.H, d.NC, runs > 0 ? runs : d.NC, d.dk, d.lay.vl,
+                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path);
+    hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n,
+                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path);
     return hipGetLastError();
 }
 

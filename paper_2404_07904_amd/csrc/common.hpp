@@ -48,6 +48,13 @@ __device__ __forceinline__ int table_read(const int* table, int i)
     return ((const_ptr)table)[i];
 }
 
+// A launch may be one of several alternatives, of which an int that an earlier kernel wrote picks
+// one (TokenLayout::choice, ::path): the workgroups of the others return at once.
+__device__ __forceinline__ bool not_chosen(const TokenLayout& lay)
+{
+    return lay.choice && table_read(lay.choice, 0) != lay.path;
+}
+
 // ---- which tokens a sequence (b, h) owns --------------------------------------------------------
 // N tokens, NC chunks, element offsets of its first token in q / f (off_k) and v / o (off_v), and
 // the index of its first chunk in the per-chunk workspaces.  `bh` must be uniform over the wave.

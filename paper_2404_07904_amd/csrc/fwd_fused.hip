@@ -132,6 +132,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
     float* cA = reinterpret_cast<float*>(smem + L::ca);
     float* cH = reinterpret_cast<float*>(smem + L::ch);
 
+    if (not_chosen(p.lay)) return;       // one of several chunk lengths, and not the one called for
     // workgroup -> (sequence, dv half): ids 8 apart land on the same XCD (ids are dealt to the 8
     // XCDs round-robin), so the two halves of a sequence share an L2 for the q, f rows both read
     int bh, split;

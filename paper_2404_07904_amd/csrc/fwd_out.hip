@@ -62,6 +62,7 @@ __device__ __forceinline__ void fwd_out_body(const FwdOutParams& p)
     float* tot = reinterpret_cast<float*>(smem + L::tot);
     T* Ost = reinterpret_cast<T*>(smem + L::ost);   // output staging aliases K~ once P has been formed
 
+    if (not_chosen(p.lay)) return;       // one of several chunk lengths, and not the one called for
     int n, bh;
     if (!locate_chunk<DENSE>(p.lay, p.BH, p.NC, blockIdx.x, bh, n)) return;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, r32 = lane & 31, g = lane >> 5;

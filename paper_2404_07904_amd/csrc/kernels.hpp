@@ -36,6 +36,9 @@ struct TokenLayout {
     // gradient kernel), made from the sizes of the groups; it is the int behind the group array.  The
     // kernels of both passes are enqueued, each with `path` set to the choice it belongs to, and
     // those of the other one return at once.  Null: no choice to make.
+    // Equal-length batches use the same pair for the chunk length chosen on the device
+    // (hgrn2_shape::chunk = HGRN2_CHUNK_AUTO): the passes for 64, 32 and 16 tokens per chunk are
+    // enqueued one after the other and those not called for return at once.
     const int* choice = nullptr;
     int path = -1;
     // The fused reverse walk of a packed batch cuts the chunks of a head -- sequence after sequence,
@@ -140,8 +143,10 @@ hipError_t launch_sweep_pair(const SeqDims& d, const void* q, const void* f, con
 // state entering each run, from which the ordinary sweeps then start run by run.
 hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f, const void* v, const void* grad_o,
                                   float* run_state, float* run_dstate, float* run_decay, hipStream_t stream);
+// (choice, path: as TokenLayout's; the kernel returns at once when *choice != path)
 hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* carried_in, float* run_state,
-                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream);
+                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream,
+                            const int* choice = nullptr, int path = 0);
 // The same for a packed batch cut by launch_varlen_run_table: sequence b of head h owns the runs
 // first_run[b] .. first_run[b + 1] - 1, whose states sit at [run * H + h].
 hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, int dv, const float* carried_in,
@@ -255,6 +260,8 @@ size_t varlen_groups_bytes(int G);
 hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
+// *out = src[0] + ... + src[n - 1], on the device
+hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream);
 // (groups != null: the group array over the table's G groups, launch_varlen_groups(), in the same launch)
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G = 0,
                                int* groups = nullptr);

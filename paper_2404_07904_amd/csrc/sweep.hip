@@ -72,10 +72,7 @@ __device__ __forceinline__ void sweep_body(const SweepParams& p, int block_id)
     // slab to its own final one), with the first rows of the next sequence already in flight during
     // the last chunk of the current one: a batch of many short sequences then costs a workgroup's
     // start-up and a trip to memory once per group, not once per sequence.
-    if constexpr (!DENSE) {
-        // a packed batch whose table chose the other backward pass: nothing to do here
-        if (p.lay.choice && table_read(p.lay.choice, 0) != p.lay.path) return;
-    }
+    if (not_chosen(p.lay)) return;       // (a packed batch whose table chose the other backward pass; a chunk length not called for)
     int id, tile;
     xcd_map(block_id, p.n_tile, id, tile);
     int bh_first, bh_end, bh_step;
@@ -481,8 +478,9 @@ hipError_t launch_sweep_pair_ends(const SeqDims& d, const void* q, const void* f
 // entering each run, which replaces add_r in place, and the state leaving the sequence.
 __global__ __launch_bounds__(256) void run_carry_kernel(const float* carried_in, float* run_state, const float* run_decay,
                                                         float* carried_out, int seg, const int* first_run, int H,
-                                                        int dk, int dv, int reverse)
+                                                        int dk, int dv, int reverse, const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
     const size_t per = (size_t)dk * dv;
     const size_t e4 = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (e4 >= per) return;
@@ -510,12 +508,13 @@ __global__ __launch_bounds__(256) void run_carry_kernel(const float* carried_in,
 }
 
 hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* carried_in, float* run_state,
-                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream)
+                            const float* run_decay, float* carried_out, bool reverse, hipStream_t stream,
+                            const int* choice, int path)
 {
     if (n_seq == 0) return hipSuccess;
     const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
     hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, n_seq), dim3(256), 0, stream, carried_in, run_state, run_decay,
-                       carried_out, seg, static_cast<const int*>(nullptr), 1, dk, dv, reverse ? 1 : 0);
+                       carried_out, seg, static_cast<const int*>(nullptr), 1, dk, dv, reverse ? 1 : 0, choice, path);
     return hipGetLastError();
 }
 
@@ -526,7 +525,7 @@ hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, i
     if (B * H == 0) return hipSuccess;
     const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
     hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, B * H), dim3(256), 0, stream, carried_in, run_state, run_decay,
-                       carried_out, 0, first_run, H, dk, dv, reverse ? 1 : 0);
+                       carried_out, 0, first_run, H, dk, dv, reverse ? 1 : 0, static_cast<const int*>(nullptr), 0);
     return hipGetLastError();
 }
 

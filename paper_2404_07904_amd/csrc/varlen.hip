@@ -231,6 +231,20 @@ hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream)
     return hipGetLastError();
 }
 
+// *out = src[0] + ... + src[n - 1] (a few ints)
+__global__ void sum_ints_kernel(const int* src, int n, int* out)
+{
+    int t = 0;
+    for (int i = 0; i < n; ++i) t += src[i];
+    *out = t;
+}
+
+hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sum_ints_kernel, dim3(1), dim3(1), 0, stream, src, n, out);
+    return hipGetLastError();
+}
+
 size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups)

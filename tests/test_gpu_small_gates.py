@@ -100,6 +100,96 @@ def test_small_gates_training_pair(kind, B, H, N, dk, dv, layout, chunk, io):
     check("dh0", host(gh0), rh, tol)
 
 
+@pytest.mark.parametrize("kind,expect,B,H,N,dk,dv,layout", [
+    ("ordinary", 0, 2, 3, 300, 128, 128, 0),
+    ("loguniform32", 32, 8, 16, 200, 128, 128, 0),     # single-pass forward, light runs backward
+    ("loguniform32", 32, 2, 2, 1500, 64, 128, 1),      # runs forward and backward
+    ("loguniform", 16, 2, 3, 333, 128, 64, 1),
+    ("resets", None, 1, 2, 200, 64, 64, 0),           # (whichever spacing these gates turn out to need)
+])
+def test_chunk_length_chosen_on_the_device(kind, expect, B, H, N, dk, dv, layout):
+    """chunk = HGRN2_CHUNK_AUTO: the passes for 64, 32 and 16 tokens per chunk are enqueued and the flags
+    the kernels raise decide which of them run.  The results must be those of the chunk length the
+    gates need, bit for bit, for the stateless calls and for the training pair, and agree with the oracle."""
+    AUTO = -1
+    print("\n[chunk chosen on the device] %s (expect %s) B=%d H=%d N=%d dk=%d dv=%d layout=%d" % (kind, expect, B, H, N, dk, dv, layout), flush=True)
+    if kind == "ordinary":
+        w = synth.make_sequence(7600 + N, B, H, N, dk, dv, io_dtype="bf16", lb=0.0, with_h0=True, with_dO=True, with_dhT=True)
+    else:
+        w = small_gate_workload(7600 + N, B, H, N, dk, dv, kind)
+    put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
+    get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
+    q, f, v, dO = put(dev(w.q, "bf16")), put(dev(w.f, "bf16")), put(dev(w.v, "bf16")), put(dev(w.dO, "bf16"))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    # which spacing the gates need, by the probe
+    need = 0
+    for ck in (0, 32, 16):
+        if float(binding.hgrn2_min_gate_product(f, layout=layout, chunk=ck).item()) > LIMIT:
+            need = ck
+            break
+    else:
+        raise AssertionError("gates outside every domain")
+    print("    the probe says: chunk = %d" % need, flush=True)
+    assert expect is None or need == expect
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o_a, hT_a = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=AUTO, domain_flag=flag)
+    g_a = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=AUTO, domain_flag=flag)
+    o_r, hT_r = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=need)
+    g_r = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=need)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    assert torch.equal(o_a, o_r) and torch.equal(hT_a, hT_r)
+    for x, y in zip(g_a, g_r):
+        assert torch.equal(x, y)
+    # the training pair
+    o_p, hT_p, saved = binding.hgrn2_fwd_saving(q, f, v, h0, layout=layout, chunk=AUTO, domain_flag=flag)
+    g_p = binding.hgrn2_bwd_saved(q, f, v, saved, dO, dhT, want_grad_h0=True, layout=layout, chunk=AUTO, domain_flag=flag)
+    o_s, hT_s, saved_r = binding.hgrn2_fwd_saving(q, f, v, h0, layout=layout, chunk=need)
+    g_s = binding.hgrn2_bwd_saved(q, f, v, saved_r, dO, dhT, want_grad_h0=True, layout=layout, chunk=need)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    assert torch.equal(o_p, o_s) and torch.equal(hT_p, hT_s)
+    for x, y in zip(g_p, g_s):
+        assert torch.equal(x, y)
+    tol = TOL["bf16"]
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    rq, rf, rv, rh = oracle.bwd(w.q, w.f, w.v, w.dO, w.h0, w.dhT)
+    check("o", get(o_a), ro, tol); check("hT", host(hT_a), rhT, tol)
+    check("dq", get(g_p[0]), rq, tol); check("df", get(g_p[1]), rf, tol); check("dv", get(g_p[2]), rv, tol)
+    check("dh0", host(g_p[3]), rh, tol)
+
+
+def test_chunk_length_chosen_on_the_device_gated_and_out_of_every_domain():
+    """The same with the gate formed in the kernels (grad_beta is reduced by the alternative that ran), and
+    gates that even 16 tokens per chunk cannot take: only then is the caller's flag raised."""
+    AUTO = -1
+    B, H, N, dk, dv = 2, 2, 170, 128, 64
+    rng = np.random.default_rng(8051)
+    w = synth.make_sequence(8050, B, H, N, dk, dv, io_dtype="bf16", with_h0=True, with_dO=True, with_dhT=True)
+    z = synth.bf16_round((-5.0 + 1.5 * rng.standard_normal((B, H, N, dk))).astype(np.float32))
+    beta = rng.uniform(0.0, 1e-3, size=(H, dk)).astype(np.float32)
+    q, zd, v, dO = dev(w.q, "bf16"), dev(z, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+    bd = torch.from_numpy(beta).cuda()
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o, hT = binding.hgrn2_fwd_gated(q, zd, bd, v, h0, chunk=AUTO, domain_flag=flag)
+    got = binding.hgrn2_bwd_gated(q, zd, bd, v, dO, h0, dhT, want_grad_h0=True, chunk=AUTO, domain_flag=flag)
+    want = binding.hgrn2_bwd_gated(q, zd, bd, v, dO, h0, dhT, want_grad_h0=True, chunk=16)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    for x, y in zip(got, want):
+        assert torch.equal(x, y)
+    ro, rhT = oracle.fwd_gated(w.q, z, beta, w.v, w.h0)
+    check("o", host(o), ro, TOL["bf16"]); check("hT", host(hT), rhT, TOL["bf16"])
+    rb = oracle.bwd_gated(w.q, z, beta, w.v, w.dO, w.h0, w.dhT)[2]
+    check("dbeta", host(got[2]), rb, TOL["bf16"])
+    # gates of 1e-6 throughout: 8 of them multiply to 1e-48 < 2^-100
+    tiny = torch.full((B, H, N, dk), 1e-6, device="cuda").to(torch.bfloat16)
+    binding.hgrn2_fwd(q, tiny, v, h0, chunk=AUTO, domain_flag=flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 1
+
+
 def test_small_gates_fp32_forward():
     B, H, N, dk, dv = 1, 2, 150, 64, 64
     print("\n[small gates fp32] B=%d H=%d N=%d" % (B, H, N), flush=True)
