@@ -121,13 +121,18 @@ def main():
     hT = torch.empty((B, H, D, D), dtype=torch.float32, device=dev)
     gq, gf, gv = (torch.empty_like(sets[0][0]) for _ in range(3))
 
+    # the kernels raise this device int when a gate product leaves the domain of the 64-token chunks
+    # (it costs nothing in the timed region; read once, at the end)
+    domain_flag = torch.zeros(1, dtype=torch.int32, device=dev)
+
     def train_fwd(i):
         q, f, v, _ = sets[i % 2]
-        binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=saved[i % 2], workspace=ws)
+        binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=saved[i % 2], workspace=ws, domain_flag=domain_flag)
 
     def train_bwd(i):
         q, f, v, dO = sets[i % 2]
-        binding.hgrn2_bwd_saved(q, f, v, saved[i % 2], dO, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv)
+        binding.hgrn2_bwd_saved(q, f, v, saved[i % 2], dO, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv,
+                                domain_flag=domain_flag)
 
     def step(i):
         train_fwd(i)
@@ -782,6 +787,8 @@ def main():
                                   "sample": "the full benchmark workload (B=8,H=16,N=2048,d=128), fwd+bwd in fp64, "
                                             "%d repetition(s), %.1f s" % (reps, t_cpu)}
         result["parity_vs_oracle_full_size"] = errs
+    torch.cuda.synchronize()
+    result["gate_domain_flag"] = int(domain_flag.item())       # 0: every step of the headline ran inside the gate domain
     print(json.dumps(result), flush=True)
 
 
