@@ -55,6 +55,59 @@ def test_captured_forward_backward_replays(B, H, N, d):
             assert torch.equal(a, b), "replay %d: %s differs from the eager result" % (k, name)
 
 
+def test_captured_training_pair_chooses_the_chunk_length_at_every_replay():
+    """chunk = HGRN2_CHUNK_AUTO in a captured training pair: the graph holds the passes for all three chunk
+    lengths, and the gates of each replay decide on the device which of them run -- ordinary gates, gates
+    that need 32 tokens per chunk, gates that need 16, ordinary ones again -- with no new capture.  Every
+    replay must give exactly what the eager call with that chunk length gives."""
+    B, H, N, d = 2, 3, 300, 128
+    AUTO = -1
+    print("\n[graph] chunk length chosen on the device, B=%d H=%d N=%d d=%d" % (B, H, N, d), flush=True)
+    static = fresh(8700, B, H, N, d)
+    q, f, v, dO, h0, dhT = static
+    shape = binding.make_shape(q, v, f, AUTO)
+    ws = torch.empty(binding.hgrn2_bwd_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    saved = torch.empty(binding.hgrn2_saved_states_bytes(shape), dtype=torch.uint8, device="cuda")
+    o, hT = torch.empty_like(v), torch.empty((B, H, d, d), device="cuda")
+    gq, gf, gv, gh0 = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty_like(hT)
+    outs = (o, hT, gq, gf, gv, gh0)
+
+    def step(chunk):
+        binding.hgrn2_fwd_saving(q, f, v, h0, o=o, hT=hT, saved_states=saved, workspace=ws, chunk=chunk)
+        binding.hgrn2_bwd_saved(q, f, v, saved, dO, dhT, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv, grad_h0=gh0, chunk=chunk)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for c in (AUTO, 0, 32, 16):
+            step(c)                              # warm-up outside the capture (first-launch set-up)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(AUTO)
+    rng = np.random.default_rng(8701)
+    for k, (lo, need) in enumerate(((None, 0), (0.02, 32), (1e-3, 16), (None, 0), (0.02, 32))):
+        new = fresh(8702 + k, B, H, N, d)
+        if lo is not None:       # gates log-uniform in [lo, 1]
+            g = 10.0 ** rng.uniform(np.log10(lo), 0.0, size=(B, H, N, d))
+            new[1] = dev(synth.bf16_round(g.astype(np.float32)), "bf16")
+        for dst, src in zip(static, new):
+            dst.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()                            # eager work between the replays
+        limit = 2.0 ** -100
+        ok = [float(binding.hgrn2_min_gate_product(f, chunk=c).item()) > limit for c in (0, 32, 16)]
+        assert (0, 32, 16)[ok.index(True)] == need
+        step(need)
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "hT", "dq", "df", "dv", "dh0"), got, outs):
+            assert torch.equal(a, b), "replay %d (chunk %d): %s differs from the eager result" % (k, need, name)
+
+
 def test_captured_decode_steps_replay():
     B, H, d, T = 4, 3, 64, 6
     print("\n[graph] decode B=%d H=%d d=%d, %d steps per replay" % (B, H, d, T), flush=True)
