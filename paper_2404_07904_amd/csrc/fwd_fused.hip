@@ -489,7 +489,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src));
             const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src + 8 * 8));   // dv column + 8: lane + 8
             const frag out = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            *reinterpret_cast<frag*>(dst + state_frag_offset(ta, dv0 / 32 + tb, DV / 32, half, lane)) = out;
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, out), reinterpret_cast<u32x4*>(dst + state_frag_offset(ta, dv0 / 32 + tb, DV / 32, half, lane)));
         }
     };
 
