@@ -189,3 +189,29 @@ def test_steps_equal_fwd():
             for t in range(70)]
     check("o", host(torch.stack(outs, 2)), host(o), 2e-2)
     check("hT", host(st), host(hT), 1e-2)
+
+
+@pytest.mark.parametrize("B,H,dk,dv,io", [(2, 3, 64, 64, 0), (2, 3, 128, 64, 1), (9, 8, 128, 128, 1)])
+def test_empty_sequences_with_no_workspace_at_all(B, H, dk, dv, io):
+    """N = 0 needs no workspace, so NULL is a legal one: the final state is the initial one and the gradient
+    of the final state passes through, on the paths with separate sweeps and on the single-pass one."""
+    import ctypes
+    print("\n[fwd/bwd] N=0, workspace NULL, B=%d H=%d dk=%d dv=%d io=%d" % (B, H, dk, dv, io), flush=True)
+    L = binding.lib()
+    shape = binding.hgrn2_shape(B, H, 0, dk, dv, 0, io, io, 0)
+    assert binding.hgrn2_fwd_workspace_bytes(shape) == 0 and binding.hgrn2_bwd_workspace_bytes(shape) == 0
+    g = torch.Generator(device="cuda").manual_seed(5)
+    h0 = torch.randn((B, H, dk, dv), generator=g, device="cuda")
+    dhT = torch.randn((B, H, dk, dv), generator=g, device="cuda")
+    hT, dh0 = torch.full_like(h0, 7.0), torch.full_like(h0, 7.0)
+    P = lambda t: ctypes.c_void_p(t.data_ptr())
+    s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.hgrn2_fwd(ctypes.byref(shape), None, None, None, P(h0), None, P(hT), None, ctypes.c_size_t(0), s) == 0
+    assert L.hgrn2_bwd(ctypes.byref(shape), None, None, None, P(h0), None, P(dhT), None, None, None, P(dh0), None,
+                       ctypes.c_size_t(0), s) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(hT, h0) and torch.equal(dh0, dhT)
+    # no initial state: the final state of an empty sequence is zero
+    assert L.hgrn2_fwd(ctypes.byref(shape), None, None, None, None, None, P(hT), None, ctypes.c_size_t(0), s) == 0
+    torch.cuda.synchronize()
+    assert float(hT.abs().max()) == 0.0
