@@ -40,11 +40,12 @@
  *     _varlen forms place their reference rows every 32 or 16 tokens instead of every 64, and
  *     the bound applies to the product of 16 or 8 consecutive gates (guaranteed for
  *     f >= 0.014, f >= 1.8e-4).  A chunk of the kernels then holds 32 or 16 tokens in its middle
- *     rows and nothing in the others: twice or four times the chunks (about 2.4 or 4.8 times
- *     the time, and workspaces and saved states for as many chunks; the training pair
- *     hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  Packed batches (_varlen) are
- *     copied into spread ones for it (their workspace also holds those copies).
- *     hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     rows and nothing in the others: twice or four times the chunks (1.8 or 3.6 times the time
+ *     of the training pair, and workspaces and saved states for as many chunks; the training
+ *     pair hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  Equal-length batches
+ *     also take chunk = 8 (products of 4 gates: f >= 3e-8, eight times the chunks).  Packed
+ *     batches (_varlen) are copied into spread ones for chunk = 32 or 16 (their workspace also
+ *     holds those copies).  hgrn2_min_gate_product tells which mode a set of gates needs.
  *     chunk = HGRN2_CHUNK_AUTO (equal-length batches: hgrn2_fwd, hgrn2_bwd, their _gated, _saving /
  *     _saved and _noalloc forms) needs no probe: the pass is enqueued for 64, then 32, then 16 tokens
  *     per chunk; the kernels of the first raise a flag inside the workspace when a product falls
@@ -53,7 +54,7 @@
  *     allow; shape->gate_domain_flag is raised only when even 16 tokens per chunk are too many.
  *     Ordinary gates pay two launches that do nothing (a few microseconds per pass); the
  *     workspaces and saved states are sized for 16 tokens per chunk.
- *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16 where stated;
+ *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16, 8, HGRN2_CHUNK_AUTO where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.
  *     io_dtype F32 is supported by hgrn2_fwd, hgrn2_step and, for heads of dk = dv = 64, by hgrn2_bwd

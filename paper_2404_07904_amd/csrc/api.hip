@@ -23,7 +23,7 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     if (s->layout != HGRN2_LAYOUT_BHND && s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;
     const long long bh = (long long)s->B * s->H;
     if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
-    const bool fine = s->chunk == kFineChunk || s->chunk == 2 * kFineChunk;
+    const bool fine = s->chunk == kFineChunk || s->chunk == 2 * kFineChunk || (s->chunk == kFineChunk / 2 && !packed);   // (8: equal-length batches only)
     const int sub = (fine && !packed) ? s->chunk : kChunk;                  // tokens per chunk
     const long long nc = ((long long)s->N + sub - 1) / sub;
     if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
@@ -249,7 +249,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
 }
 
 // ---- small-gate modes -----------------------------------------------------------------------------
-bool fine_mode(const hgrn2_shape* s) { return s && (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk); }
+bool fine_mode(const hgrn2_shape* s) { return s && (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk || s->chunk == kFineChunk / 2); }
 
 // chunk = HGRN2_CHUNK_AUTO (equal-length batches): the pass is enqueued for 64, then 32, then 16
 // tokens per chunk.  The kernels of the first raise a flag when a gate product falls below the floor

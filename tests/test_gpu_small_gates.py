@@ -25,6 +25,8 @@ def small_gate_workload(seed, B, H, N, dk, dv, kind, io_dtype="bf16"):
     rng = np.random.default_rng(seed + 1)
     if kind == "loguniform":
         f = 10.0 ** rng.uniform(-3.0, 0.0, size=w.f.shape)
+    elif kind == "loguniform8":           # for reference rows every 8 tokens: 4 gates multiply to 1e-20 at worst, 8 gates to 1e-40
+        f = 10.0 ** rng.uniform(-5.0, 0.0, size=w.f.shape)
     elif kind == "loguniform32":          # for reference rows every 32 tokens: 16 gates multiply to 6e-28 at worst
         f = 10.0 ** rng.uniform(np.log10(0.02), 0.0, size=w.f.shape)
     else:
@@ -40,6 +42,8 @@ def small_gate_workload(seed, B, H, N, dk, dv, kind, io_dtype="bf16"):
     ("resets", 1, 2, 1100, 64, 128, 0, 16),          # spread to 69 chunks: walked in runs
     ("loguniform32", 2, 2, 300, 128, 64, 1, 32),
     ("loguniform32", 1, 3, 700, 64, 64, 0, 32),
+    ("loguniform8", 2, 2, 150, 128, 128, 0, 8),      # a chunk holds 8 tokens, in rows 28 .. 35: half a row block of two waves each
+    ("loguniform8", 1, 3, 100, 64, 128, 1, 8),
 ])
 def test_small_gates_fwd_bwd(kind, B, H, N, dk, dv, layout, chunk):
     print("\n[small gates] %s B=%d H=%d N=%d dk=%d dv=%d layout=%d chunk=%d" % (kind, B, H, N, dk, dv, layout, chunk), flush=True)
