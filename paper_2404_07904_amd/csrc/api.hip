@@ -270,12 +270,14 @@ int alternatives(const hgrn2_shape* shape, hgrn2_shape (&alt)[kAlternatives])
     return kAlternatives;
 }
 
-// largest value of a size over the alternatives (0 as soon as one of them is 0 for a shape with tokens: invalid)
-template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F bytes_of, bool head)
+// largest value of a size over the alternatives (plus, with `head`, the flags' place when there are several)
+template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F bytes_of, bool head, bool backward)
 {
     if (!shape) return 0;
     hgrn2_shape alt[kAlternatives];
     const int n = alternatives(shape, alt);
+    SeqDims d;
+    if (check_shape(&alt[0], backward, &d, false, true) != HGRN2_OK) return 0;      // an invalid shape needs nothing
     size_t m = 0;
     for (int i = 0; i < n; ++i) { const size_t b = bytes_of(&alt[i]); if (b > m) m = b; }
     return m + ((n > 1 && head) ? kAutoHead : 0);
@@ -321,7 +323,7 @@ size_t hgrn2_fwd_workspace_bytes(const hgrn2_shape* shape)
         SeqDims d;
         if (check_shape(s, false, &d, false, true) != HGRN2_OK) return 0;
         return round256(state_ws_bytes(d)) + run_state_bytes(d, false) + run_decay_bytes(d, false);
-    }, true);
+    }, true, false);
 }
 
 size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
@@ -330,7 +332,7 @@ size_t hgrn2_bwd_workspace_bytes(const hgrn2_shape* shape)
         SeqDims d;
         if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
         return bwd_layout(d, false).total();
-    }, true);
+    }, true, true);
 }
 
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
@@ -457,7 +459,7 @@ size_t hgrn2_bwd_gated_workspace_bytes(const hgrn2_shape* shape)
         SeqDims d;
         if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
         return bwd_layout(d, true).total();
-    }, true);
+    }, true, true);
 }
 
 // Backward pass; `gated`: `f` holds pre-activations, grad_f receives dL/dz and grad_beta dL/dbeta.
@@ -665,7 +667,7 @@ size_t hgrn2_saved_states_bytes(const hgrn2_shape* shape)
         SeqDims d;
         if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
         return round256(state_ws_bytes(d));
-    }, true);
+    }, true, true);
 }
 
 size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated)
@@ -675,7 +677,7 @@ size_t hgrn2_bwd_saved_workspace_bytes(const hgrn2_shape* shape, int32_t gated)
         SeqDims d;
         if (check_shape(s, true, &d, false, true) != HGRN2_OK) return 0;
         return bwd_layout(d, g, true).total();
-    }, false);
+    }, false, true);
 }
 
 int hgrn2_fwd_saving(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, const void* v,

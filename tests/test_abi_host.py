@@ -93,6 +93,38 @@ def test_small_gate_mode_workspace_and_support():
     assert binding.hgrn2_fwd_workspace_bytes(s32) == binding.hgrn2_fwd_workspace_bytes(shape(B=2, H=3, N=7 * 64, dk=64, dv=128))
 
 
+def test_chunk_length_chosen_on_the_device_sizes_and_support():
+    """chunk = HGRN2_CHUNK_AUTO: workspaces and kept states are those of the alternative with most chunks (16
+    tokens per chunk) plus 256 bytes for the flags; equal-length entry points only; chunk = 8 likewise."""
+    AUTO = -1
+    a, s16, s8 = (shape(B=2, H=3, N=200, dk=64, dv=128, chunk=c) for c in (AUTO, 16, 8))
+    assert binding.hgrn2_fwd_workspace_bytes(a) == 256 + binding.hgrn2_fwd_workspace_bytes(s16)
+    assert binding.hgrn2_bwd_workspace_bytes(a) == 256 + binding.hgrn2_bwd_workspace_bytes(s16)
+    assert binding.hgrn2_bwd_gated_workspace_bytes(a) == 256 + binding.hgrn2_bwd_gated_workspace_bytes(s16)
+    assert binding.hgrn2_saved_states_bytes(a) == 256 + binding.hgrn2_saved_states_bytes(s16)
+    assert binding.hgrn2_bwd_saved_workspace_bytes(a, False) == binding.hgrn2_bwd_saved_workspace_bytes(s16, False)
+    assert binding.hgrn2_saved_states_bytes(s8) == 2 * 3 * 25 * 64 * 128 * 2          # 25 chunks of 8 tokens
+    lib = binding.lib()
+    big = 1 << 40
+    ap = ctypes.byref(a)
+    assert lib.hgrn2_fwd(ap, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, binding.hgrn2_fwd_workspace_bytes(s16), None) == E_WS
+    assert lib.hgrn2_fwd(ap, None, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL
+    assert lib.hgrn2_bwd(ap, FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL
+    assert lib.hgrn2_bwd(ap, FAKE, FAKE, FAKE, None, FAKE, None, FAKE, FAKE, FAKE, None, FAKE_WS, 1024, None) == E_WS
+    assert lib.hgrn2_fwd_saving(ap, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, binding.hgrn2_saved_states_bytes(s16),
+                                FAKE_WS, big, None) == E_WS
+    bad = shape(B=2, H=3, N=200, dk=96, dv=128, chunk=AUTO)
+    assert binding.hgrn2_fwd_workspace_bytes(bad) == 0
+    assert lib.hgrn2_fwd(ctypes.byref(bad), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
+    assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=-2)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_SHAPE
+    # not offered: the stage calls, packed batches
+    assert lib.hgrn2_state_sweep(ap, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_SHAPE
+    for c, code in ((AUTO, E_SHAPE), (8, E_UNSUP)):
+        sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=c)
+        assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == 0
+        assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == code
+
+
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):
     return binding.lib().hgrn2_fwd(ctypes.byref(s) if s is not None else None, q, f, v, h0, o, hT, ws, ws_bytes, None)
 
