@@ -52,7 +52,7 @@
  *     below the floor, those of the next run only if it is set (they return at once otherwise) and
  *     overwrite every result, and so on.  The results are those of the longest chunk the gates
  *     allow; shape->gate_domain_flag is raised only when even 16 tokens per chunk are too many.
- *     Ordinary gates pay two launches that do nothing (a few microseconds per pass); the
+ *     Ordinary gates pay the launches that do nothing (about ten microseconds per pass); the
  *     workspaces and saved states are sized for 16 tokens per chunk.
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16, 8, HGRN2_CHUNK_AUTO where stated;
  *     any B, H, N >= 0.
