@@ -50,6 +50,43 @@ def test_config2_full_size(layer):
     run_fwd_bwd_bench_configuration(synth.config2(layer))
 
 
+def test_config2_full_size_training_pair_with_the_chunk_length_chosen_on_the_device():
+    """The benchmark's step (hgrn2_fwd_saving + hgrn2_bwd_saved at B=8, H=16, N=2048, d=128) with
+    chunk = HGRN2_CHUNK_AUTO, once on the gates of layer 12 (the 64-token chunks run, the others return
+    at once) and once on gates outside their domain (log-uniform in [0.02, 1]: the kernels fall back to
+    32 tokens per chunk), every output element against the oracle both times."""
+    AUTO = -1
+    for kind in ("layer 12", "log-uniform gates in [0.02, 1]"):
+        print("\n[full] config2 training pair, chunk chosen on the device, %s" % kind, flush=True)
+        w = synth.config2(12)
+        if kind != "layer 12":
+            rng = np.random.default_rng(20240499)
+            w.f = synth.bf16_round((10.0 ** rng.uniform(np.log10(0.02), 0.0, size=w.f.shape)).astype(np.float32))
+        q, f, v, dO = dev(w.q, "bf16"), dev(w.f, "bf16"), dev(w.v, "bf16"), dev(w.dO, "bf16")
+        shape = binding.make_shape(q, v, f, AUTO)
+        ws = torch.empty(binding.hgrn2_bwd_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+        saved = torch.empty(binding.hgrn2_saved_states_bytes(shape), dtype=torch.uint8, device="cuda")
+        o, gq, gf, gv = torch.empty_like(v), torch.empty_like(q), torch.empty_like(q), torch.empty_like(v)
+        hT = torch.empty((shape.B, shape.H, shape.dk, shape.dv), dtype=torch.float32, device="cuda")
+        flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            binding.hgrn2_fwd_saving(q, f, v, None, o=o, hT=hT, saved_states=saved, workspace=ws, chunk=AUTO, domain_flag=flag)
+            binding.hgrn2_bwd_saved(q, f, v, saved, dO, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv, chunk=AUTO,
+                                    domain_flag=flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        need = [c for c in (0, 32, 16) if float(binding.hgrn2_min_gate_product(f, chunk=c).item()) > 2.0 ** -100][0]
+        print("    the probe says: chunk = %d" % need, flush=True)
+        assert need == (0 if kind == "layer 12" else 32)
+        tol = TOL["bf16"]
+        ro, rhT = oracle.fwd(w.q, w.f, w.v, None)
+        check("o", host(o), ro, tol); check("hT", host(hT), rhT, tol)
+        del ro, rhT
+        rq, rf, rv, _ = oracle.bwd(w.q, w.f, w.v, w.dO, None, None, want_dh0=False)
+        check("dq", host(gq), rq, tol); check("dv", host(gv), rv, tol); check("df", host(gf), rf, tol)
+        del q, f, v, dO, ws, saved, o, gq, gf, gv
+
+
 @pytest.mark.parametrize("gate_dtype", ["bf16", "f32"])
 def test_config3_full_size(gate_dtype):
     """B=2, H=16, N=16384, dk=dv=128, gates in [0.99, 1]: 256 chunks of carried state."""
