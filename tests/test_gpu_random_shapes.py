@@ -51,6 +51,38 @@ def test_random_equal_length(seed):
     check("dh0", host(gh0), rh, tol)
 
 
+@pytest.mark.parametrize("seed", range(9050, 9062))
+def test_random_equal_length_shorter_chunks(seed):
+    """The same with 32, 16 or 8 tokens per chunk, or the chunk length chosen on the device, as the stateless
+    calls or as the training pair: on gates every mode can take, all of them must agree with the oracle."""
+    rng, B, H, N, dk, dv = draw(seed)
+    N = int(N * rng.choice([1, 1, 4]))                     # some long enough for runs of the shorter chunks
+    layout = int(rng.integers(0, 2))
+    chunk = int(rng.choice([32, 16, 8, -1]))
+    pair = bool(rng.integers(0, 2))
+    with_state = bool(rng.integers(0, 2))
+    print("\n[random] seed=%d B=%d H=%d N=%d dk=%d dv=%d layout=%d chunk=%d pair=%s states=%s"
+          % (seed, B, H, N, dk, dv, layout, chunk, pair, with_state), flush=True)
+    w = synth.make_sequence(seed, B, H, N, dk, dv, io_dtype="bf16", lb=0.3, with_h0=with_state, with_dO=True, with_dhT=with_state)
+    put = (lambda t: t.permute(0, 2, 1, 3).contiguous()) if layout == BNHD else (lambda t: t)
+    get = (lambda t: host(t.permute(0, 2, 1, 3))) if layout == BNHD else host
+    q, f, v, dO = put(dev(w.q, "bf16")), put(dev(w.f, "bf16")), put(dev(w.v, "bf16")), put(dev(w.dO, "bf16"))
+    h0, dhT = dev(w.h0), dev(w.dhT)
+    if pair:
+        o, hT, saved = binding.hgrn2_fwd_saving(q, f, v, h0, layout=layout, chunk=chunk)
+        gq, gf, gv, gh0 = binding.hgrn2_bwd_saved(q, f, v, saved, dO, dhT, want_grad_h0=True, layout=layout, chunk=chunk)
+    else:
+        o, hT = binding.hgrn2_fwd(q, f, v, h0, layout=layout, chunk=chunk)
+        gq, gf, gv, gh0 = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=chunk)
+    torch.cuda.synchronize()
+    tol = TOL["bf16"]
+    ro, rhT = oracle.fwd(w.q, w.f, w.v, w.h0)
+    rq, rf, rv, rh = oracle.bwd(w.q, w.f, w.v, w.dO, w.h0, w.dhT)
+    check("o", get(o), ro, tol); check("hT", host(hT), rhT, tol)
+    check("dq", get(gq), rq, tol); check("df", get(gf), rf, tol); check("dv", get(gv), rv, tol)
+    check("dh0", host(gh0), rh, tol)
+
+
 @pytest.mark.parametrize("seed", range(9100, 9108))
 def test_random_packed_sequences(seed):
     rng, B, H, _, dk, dv = draw(seed)
