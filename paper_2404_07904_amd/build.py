@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhgrn2.so")
-SOURCES = ["api.hip", "sweep.hip", "fwd_out.hip", "fwd_fused.hip", "bwd_grad.hip", "step.hip", "hgrn1.hip", "varlen.hip", "domain.hip", "spread.hip", "probe.hip", "proj.hip"]
+SOURCES = ["api.hip", "sweep.hip", "fwd_out.hip", "fwd_fused.hip", "bwd_grad.hip", "step.hip", "hgrn1.hip", "varlen.hip", "domain.hip", "probe.hip", "proj.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep the compiler from forming packed-fp32 VALU instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -13,8 +13,8 @@ bool dtype_ok(int32_t t) { return t == HGRN2_F32 || t == HGRN2_BF16; }
 bool dim_ok(int32_t d) { return d == 64 || d == 128; }
 
 // Validates a shape; on success fills `d`.  `fine_ok`: the entry point also takes chunk = 16 or 32,
-// the small-gate modes: an equal-length batch is then walked in chunks that hold only that many
-// tokens (TokenLayout::sub), a packed batch is spread into one whose chunks do (spread.hip).
+// the small-gate modes: the batch is then walked in chunks that hold only that many tokens
+// (TokenLayout::sub).
 int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = false, bool fine_ok = false)
 {
     if (!s) return HGRN2_ERR_NULL;
@@ -23,8 +23,8 @@ int check_shape(const hgrn2_shape* s, bool backward, SeqDims* d, bool packed = f
     if (s->layout != HGRN2_LAYOUT_BHND && s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;
     const long long bh = (long long)s->B * s->H;
     if (bh > INT_MAX / 16) return HGRN2_ERR_SHAPE;
-    const bool fine = s->chunk == kFineChunk || s->chunk == 2 * kFineChunk || (s->chunk == kFineChunk / 2 && !packed);   // (8: equal-length batches only)
-    const int sub = (fine && !packed) ? s->chunk : kChunk;                  // tokens per chunk
+    const bool fine = s->chunk == kFineChunk || s->chunk == 2 * kFineChunk || s->chunk == kFineChunk / 2;
+    const int sub = fine ? s->chunk : kChunk;                               // tokens per chunk
     const long long nc = ((long long)s->N + sub - 1) / sub;
     if (!packed && bh * nc > INT_MAX / 2) return HGRN2_ERR_SHAPE;          // one workgroup per chunk (packed sequences: checked by the caller)
     if (!dim_ok(s->dk) || !dim_ok(s->dv)) return HGRN2_ERR_UNSUPPORTED;
@@ -65,12 +65,7 @@ int check_shape_varlen(const hgrn2_shape* s, bool backward, SeqDims* d, bool fin
     const int rc = check_shape(s, backward, d, true, fine_ok);
     if (rc != HGRN2_OK) return rc;
     if (s->layout != HGRN2_LAYOUT_BNHD) return HGRN2_ERR_SHAPE;          // packed tokens are token-major
-    if (s->chunk == kFineChunk || s->chunk == 2 * kFineChunk) {
-        // small-gate mode: the spread batch must pass this check too
-        const long long spread = ((long long)s->N / s->chunk + s->B) * kChunk;
-        if (spread > INT_MAX / 8 || (spread / kChunk + s->B) * (s->H > 0 ? s->H : 1) > INT_MAX / 2) return HGRN2_ERR_SHAPE;
-    }
-    const long long bound = (long long)s->N / kChunk + s->B;
+    const long long bound = (long long)s->N / d->lay.sub + s->B;
     if (bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2 || s->B > INT_MAX / 8) return HGRN2_ERR_SHAPE;
     d->NC = (int)bound;
     d->packed = true;
@@ -191,10 +186,10 @@ PackedRuns plan_packed_runs(const hgrn2_shape* s, const SeqDims& d, bool backwar
     };
     SeqDims mean = d;
     mean.packed = false;
-    mean.NC = (int)(((long long)d.N / kChunk + s->B - 1) / s->B);
+    mean.NC = (int)(((long long)d.N / d.lay.sub + s->B - 1) / s->B);
     int rc;
     const long long bound = plan_runs(mean, backward, &rc) <= 1 ? 0
-                          : s->B + ((long long)d.N / kChunk + s->B) / rc + 1;       // >= sum_b ceil(NC_b / rc)
+                          : s->B + ((long long)d.N / d.lay.sub + s->B) / rc + 1;    // >= sum_b ceil(NC_b / rc)
     if (bound == 0 || bound * (s->H > 0 ? s->H : 1) > INT_MAX / 2) {
         with_groups(p);
         return p;
@@ -223,12 +218,12 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     d->lay.vl = seq_table;
     // (a batch that is not cut gets its group array, over the sequence table, in the same launch)
     int* groups_here = (p.G > 0 && p.run_chunks == 0) ? reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at) : nullptr;
-    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream, p.G, groups_here) : hipSuccess;
+    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream, p.G, groups_here, d->lay.sub) : hipSuccess;
     if (e != hipSuccess) return e;
     if (p.run_chunks != 0) {
         int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
         int* fr = run_table + 4 * ((size_t)p.R + 1);
-        e = launch ? launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream) : hipSuccess;
+        e = launch ? launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream, d->lay.sub) : hipSuccess;
         if (e != hipSuccess) return e;
         d->lay.vl = run_table;
         d->lay.B = p.R;
@@ -292,26 +287,6 @@ struct Alternative {
     int* flag = nullptr;
     bool validate_only = false;           // stop after the argument checks
 };
-
-// packed batches: N counts the tokens of all sequences
-hgrn2_shape spread_shape_packed(const hgrn2_shape& s)
-{
-    hgrn2_shape e = s;
-    e.N = spread_tokens_packed(s.N, s.B, s.chunk);
-    e.chunk = 0;
-    return e;
-}
-
-size_t packed_spread_bytes(const hgrn2_shape& e, int width, bool bf16)
-{
-    return round256((size_t)e.N * e.H * width * (bf16 ? 2 : 4));
-}
-
-// the batch's sequence table and the spread batch's cumulative lengths, at the head of the workspace
-size_t packed_fine_head_bytes(const hgrn2_shape& s)
-{
-    return round256(varlen_table_bytes(s.B)) + round256(((size_t)s.B + 1) * sizeof(int));
-}
 
 }   // namespace
 
@@ -716,84 +691,10 @@ int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, cons
                     grad_h0, workspace, workspace_bytes, hip_stream, saved_states);
 }
 
-// Small-gate modes of the packed entry points, forward (backward = false: o, hT) and backward: every
-// sequence is spread on its own, the spread batch goes through the packed entry point, and the
-// real tokens' rows are gathered back.
-static int varlen_fine(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                       const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
-                       void* o, float* hT, void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0,
-                       bool backward, void* workspace, size_t workspace_bytes, void* hip_stream)
-{
-    SeqDims d;
-    const int rc = check_shape_varlen(shape, backward, &d, true);
-    if (rc != HGRN2_OK) return rc;
-    const bool has_tokens = d.N > 0;
-    if (backward) {
-        if (beta && !grad_beta && (size_t)shape->H * d.dk > 0) return HGRN2_ERR_NULL;
-        if (d.BH > 0 && (!cu_seqlens || (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v))))
-            return HGRN2_ERR_NULL;
-    } else {
-        if (d.BH == 0) return HGRN2_OK;
-        if (!cu_seqlens || (has_tokens && (!q || !f || !v || !o))) return HGRN2_ERR_NULL;
-    }
-    const hgrn2_shape e = spread_shape_packed(*shape);
-    const size_t need = backward ? hgrn2_bwd_varlen_workspace_bytes(shape) : hgrn2_fwd_varlen_workspace_bytes(shape);
-    if (d.BH > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
-    if (d.BH == 0)       // no sequences: the packed entry point itself knows what that means for grad_beta
-        return hgrn2_bwd_varlen(&e, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
-                                grad_h0, workspace, workspace_bytes, hip_stream);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int T = d.N, B = shape->B, block = shape->chunk;
-    char* at = static_cast<char*>(workspace);
-    auto take = [&](size_t bytes) { char* r = at; at += bytes; return r; };
-    int* seq_table = reinterpret_cast<int*>(take(round256(varlen_table_bytes(B))));
-    int* cu_spread = reinterpret_cast<int*>(take(round256(((size_t)B + 1) * sizeof(int))));
-    const int io = d.io_bf16 ? 2 : 4, ge = d.gate_bf16 ? 2 : 4;
-    const int row_k = shape->H * d.dk * io, row_g = shape->H * d.dk * ge, row_v = shape->H * d.dv * io;
-    const size_t ek = packed_spread_bytes(e, d.dk, d.io_bf16), eg = packed_spread_bytes(e, d.dk, d.gate_bf16),
-                 ev = packed_spread_bytes(e, d.dv, d.io_bf16);
-    if (launch_varlen_table(cu_seqlens, B, T, seq_table, stream) != hipSuccess ||
-        launch_spread_offsets(seq_table, B, block, cu_spread, stream) != hipSuccess)
-        return HGRN2_ERR_HIP;
-    auto spread = [&](const void* src, void* dst, int row_bytes, SpreadFill fill, bool bf16) {
-        return launch_spread_packed(T, B, block, row_bytes, fill, bf16, seq_table, cu_spread, src, dst, true, stream) == hipSuccess;
-    };
-    auto gather = [&](const void* src, void* dst, int row_bytes) {
-        return launch_spread_packed(T, B, block, row_bytes, kFillZero, true, seq_table, cu_spread, src, dst, false, stream) == hipSuccess;
-    };
-    void* qs = take(ek);
-    void* fs = take(eg);
-    void* vs = take(ev);
-    if (!spread(q, qs, row_k, kFillZero, d.io_bf16) || !spread(f, fs, row_g, beta ? kFillPlusInf : kFillOne, d.gate_bf16) ||
-        !spread(v, vs, row_v, kFillZero, d.io_bf16))
-        return HGRN2_ERR_HIP;
-    if (!backward) {
-        void* os = take(ev);
-        const int inner = hgrn2_fwd_varlen(&e, cu_spread, qs, fs, beta, vs, h0, os, hT, at,
-                                           workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
-        if (inner != HGRN2_OK) return inner;
-        return gather(os, o, row_v) ? HGRN2_OK : HGRN2_ERR_HIP;
-    }
-    void* gos = take(ev);
-    void* gqs = take(ek);
-    void* gfs = take(ek);
-    void* gvs = take(ev);
-    if (!spread(grad_o, gos, row_v, kFillZero, d.io_bf16)) return HGRN2_ERR_HIP;
-    const int inner = hgrn2_bwd_varlen(&e, cu_spread, qs, fs, beta, vs, h0, gos, grad_hT, gqs, gfs, grad_beta, gvs, grad_h0, at,
-                                       workspace_bytes - (size_t)(at - static_cast<char*>(workspace)), hip_stream);
-    if (inner != HGRN2_OK) return inner;
-    return gather(gqs, grad_q, row_k) && gather(gfs, grad_f, row_k) && gather(gvs, grad_v, row_v) ? HGRN2_OK : HGRN2_ERR_HIP;
-}
-
 size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, false, &d, true) != HGRN2_OK) return 0;
-    if (fine_mode(shape)) {
-        const hgrn2_shape e = spread_shape_packed(*shape);
-        return packed_fine_head_bytes(*shape) + packed_spread_bytes(e, d.dk, d.io_bf16) + packed_spread_bytes(e, d.dk, d.gate_bf16) +
-               2 * packed_spread_bytes(e, d.dv, d.io_bf16) + hgrn2_fwd_varlen_workspace_bytes(&e);
-    }
     const PackedRuns p = plan_packed_runs(shape, d, false);
     return p.table_bytes + round256(state_ws_bytes(d)) + p.state_bytes + p.decay_bytes;
 }
@@ -802,12 +703,6 @@ size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
-    if (fine_mode(shape)) {
-        const hgrn2_shape e = spread_shape_packed(*shape);
-        return packed_fine_head_bytes(*shape) + 3 * packed_spread_bytes(e, d.dk, d.io_bf16) +
-               packed_spread_bytes(e, d.dk, d.gate_bf16) + 3 * packed_spread_bytes(e, d.dv, d.io_bf16) +
-               hgrn2_bwd_varlen_workspace_bytes(&e);
-    }
     const PackedRuns p = plan_packed_runs(shape, d, true);
     return p.table_bytes + 2 * (round256(state_ws_bytes(d)) + p.state_bytes) + p.decay_bytes +
            round256(beta_partials_bytes(d));
@@ -826,12 +721,8 @@ static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                            const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
                            size_t workspace_bytes, void* hip_stream, void* save_states)
 {
-    if (fine_mode(shape) && save_states) return HGRN2_ERR_UNSUPPORTED;
-    if (fine_mode(shape))
-        return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, nullptr, nullptr, o, hT, nullptr, nullptr, nullptr,
-                           nullptr, nullptr, false, workspace, workspace_bytes, hip_stream);
     SeqDims d;
-    const int rc = check_shape_varlen(shape, false, &d);
+    const int rc = check_shape_varlen(shape, false, &d, true);
     if (rc != HGRN2_OK) return rc;
     d.beta = beta;
     if (d.BH == 0) return HGRN2_OK;
@@ -897,7 +788,7 @@ static size_t packed_saved_bytes(const hgrn2_shape* shape, const SeqDims& d)
 size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape)
 {
     SeqDims d;
-    if (check_shape_varlen(shape, true, &d) != HGRN2_OK) return 0;
+    if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
     return packed_saved_bytes(shape, d);
 }
 
@@ -906,7 +797,7 @@ int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens,
                             size_t saved_states_bytes, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape_varlen(shape, true, &d);      // the shapes the backward pass takes
+    const int rc = check_shape_varlen(shape, true, &d, true);      // the shapes the backward pass takes
     if (rc != HGRN2_OK) return rc;
     const size_t need = packed_saved_bytes(shape, d);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
@@ -919,12 +810,8 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                            void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
                            size_t workspace_bytes, void* hip_stream, const void* saved_states)
 {
-    if (fine_mode(shape) && saved_states) return HGRN2_ERR_UNSUPPORTED;
-    if (fine_mode(shape))
-        return varlen_fine(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, nullptr, nullptr, grad_q, grad_f,
-                           grad_beta, grad_v, grad_h0, true, workspace, workspace_bytes, hip_stream);
     SeqDims d;
-    const int rc = check_shape_varlen(shape, true, &d);
+    const int rc = check_shape_varlen(shape, true, &d, true);
     if (rc != HGRN2_OK) return rc;
     d.beta = beta;
     if (beta && !grad_beta && (size_t)shape->H * d.dk > 0) return HGRN2_ERR_NULL;
@@ -1029,9 +916,8 @@ int hgrn2_bwd_varlen_saved(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                            void* hip_stream)
 {
     SeqDims d;
-    const int rc = check_shape_varlen(shape, true, &d);
+    const int rc = check_shape_varlen(shape, true, &d, true);
     if (rc != HGRN2_OK) return rc;
-    if (fine_mode(shape)) return HGRN2_ERR_UNSUPPORTED;
     const size_t need = packed_saved_bytes(shape, d);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
     return bwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
@@ -1072,6 +958,9 @@ int hgrn2_min_gate_product_varlen(const hgrn2_shape* shape, const int32_t* cu_se
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     d.beta = beta;
+    // the probe's windows lie in a table of 64-token chunks whatever chunk length it is asked about
+    d.lay.sub = kChunk;
+    d.NC = (int)((long long)d.N / kChunk + shape->B);
     if (d.BH == 0) d.NC = 0;                  // no sequences: the probe writes 1
     else {
         int* table = static_cast<int*>(workspace);

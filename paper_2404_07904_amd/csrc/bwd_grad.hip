@@ -260,7 +260,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         if (c.n > 0) { ChunkAt r = c; r.n = c.n - 1; return r; }
         for (int e = c.bh / p.lay.H - 1; e >= 0; --e) {
             const int len = table_read(p.lay.vl, p.lay.B + 1 + e);
-            if (len > 0) return chunk_en(e, (len + C - 1) / C - 1);
+            if (len > 0) return chunk_en(e, (len + p.lay.sub - 1) / p.lay.sub - 1);
         }
         return c;
     };
@@ -1095,7 +1095,7 @@ size_t beta_partials_bytes(const SeqDims& d)
 // pass: the slice sums are added in order.
 __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const float* partials, float* slice_sums, int B,
                                                                       int H, int NC, int used, int dk, const int* vl,
-                                                                      const int* choice, int path)
+                                                                      const int* choice, int path, int sub)
 {
     if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
     __shared__ float part[kRedGroups][64];
@@ -1108,7 +1108,7 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
         size_t first = (size_t)(b * H + h) * NC;
         int nc = used;
         if (vl) {
-            nc = (vl[B + 1 + b] + kChunk - 1) / kChunk;
+            nc = (vl[B + 1 + b] + sub - 1) / sub;
             first = (size_t)vl[2 * (B + 1) + b] * H + (size_t)h * nc;
         }
         const int rows = nc * kBwdWaves;
@@ -1145,7 +1145,7 @@ hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* g
     float* slice_sums = beta_partials + d.total_chunks() * kBwdWaves * d.dk;
     hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64), kRedSlices), dim3(64 * kRedGroups), 0, stream,
                        beta_partials, slice_sums, B, d.H, d.NC, runs > 0 ? runs : d.NC, d.dk, d.lay.vl,
-                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path);
+                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path, d.lay.sub);
     hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n,
                        d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path);
     return hipGetLastError();

@@ -204,13 +204,14 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             int e = cur_e + 1, len = 0;
             while (e < e1 && (len = table_read(t_len, e)) == 0) ++e;
             if (e < e1) {
-                cur_e = e; cur_N = len; cur_nc = (len + C - 1) / C; cur_tok = table_read(t_start, e);
+                cur_e = e; cur_N = len; cur_nc = (len + p.lay.sub - 1) / p.lay.sub; cur_tok = table_read(t_start, e);
                 // the chunks of (sequence, head) lie together, the heads of a sequence one after the other
                 cur_slot = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e) * p.lay.H + head * cur_nc;
             } else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; cur_slot = 0; }          // past the end, for good
             cur_n = 0;
         }
-        c.tok0 = cur_tok; c.row0 = cur_n * C; c.N = cur_N; c.bh = cur_e * p.lay.H + head; c.lo = c.row0; c.hi = cur_N;
+        const ChunkRows cr = chunk_rows(p.lay.sub, cur_n, cur_N);
+        c.tok0 = cur_tok; c.row0 = cr.tok0; c.lo = cr.first; c.hi = cr.end; c.N = cur_N; c.bh = cur_e * p.lay.H + head;
         c.first = cur_n == 0; c.last = cur_N > 0 && cur_n == cur_nc - 1; c.slot = cur_slot + cur_n;
         return c;
     };

@@ -54,8 +54,8 @@ struct TokenLayout {
     // the length of the uncut sequence, whose last run may be shorter.
     int seg = 1;
     int n_tokens = 0;
-    // Tokens per chunk: kChunk, or 16 / 32 in the small-gate modes of equal-length batches, where a
-    // chunk's other rows stand for no token (ChunkRows in common.hpp).  NC counts chunks of `sub` tokens.
+    // Tokens per chunk: kChunk, or fewer in the small-gate modes, where a chunk's other rows stand for
+    // no token (ChunkRows in common.hpp).  NC and the chunk counts of the tables count chunks of `sub` tokens.
     int sub = kChunk;
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
     __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
@@ -235,22 +235,11 @@ size_t state_ws_bytes(const SeqDims& d);
 // to [0, T] and made non-decreasing, so that whatever the array holds, the sequences the kernels
 // see are disjoint pieces of the T tokens.
 size_t varlen_table_bytes(int B);
-// Small-gate modes of packed batches (spread.hip): every sequence is spread, block of `block` (16 or
-// 32) tokens by block, into the middle rows of chunks of its own, the other rows padded with tokens
-// that change nothing.  spread_tokens_packed() bounds the rows of the spread batch,
-// launch_spread_offsets writes the first spread row of every sequence (B + 1 ints, the spread batch's
-// cumulative sequence lengths) from the batch's sequence table, and launch_spread_packed copies
-// [T][row] tensors to spread ones (to_spread) or back.
-enum SpreadFill { kFillZero, kFillOne, kFillPlusInf };      // q, v, gradients; gates f; gate pre-activations z
-int spread_tokens_packed(int T, int B, int block);
-hipError_t launch_spread_offsets(const int* seq_table, int B, int block, int* cu_spread, hipStream_t stream);
-hipError_t launch_spread_packed(int T, int B, int block, int row_bytes, SpreadFill fill, bool bf16, const int* seq_table,
-                                const int* cu_spread, const void* src, void* dst, bool to_spread, hipStream_t stream);
-
 // Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
 size_t varlen_run_table_bytes(int B, int R);
+// (sub: tokens per chunk, TokenLayout::sub)
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
-                                   int* first_run, hipStream_t stream);
+                                   int* first_run, hipStream_t stream, int sub = kChunk);
 // Groups of a table's sequences (sequence or run table with n_entries entries): G + 1 ints, group g
 // = entries [groups[g], groups[g + 1]), cut where the chunk count reaches g / G of the total, so that
 // groups hold about equally many chunks (a group is never finer than one entry); and one more int,
@@ -264,6 +253,6 @@ hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream);
 // (groups != null: the group array over the table's G groups, launch_varlen_groups(), in the same launch)
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G = 0,
-                               int* groups = nullptr);
+                               int* groups = nullptr, int sub = kChunk);
 
 }   // namespace hgrn2

@@ -104,7 +104,7 @@ __device__ __forceinline__ int block_prefix(int v, int* wave_tot)
 }
 
 // With `groups` (null: none) the group array of the table is built in the same launch.
-__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab, int G, int* groups)
+__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab, int G, int* groups, int sub)
 {
     __shared__ int wave_tot[kTabThreads / 64];
     const int n = B + 1, tid = threadIdx.x;
@@ -124,12 +124,12 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     for (int i = lo; i < hi; ++i) {
         const int len = i < B ? tab[i + 1] - tab[i] : 0;
         tab[n + i] = len;
-        c += (len + kChunk - 1) / kChunk;
+        c += (len + sub - 1) / sub;
     }
     run = block_prefix<false>(c, wave_tot);
     for (int i = lo; i < hi; ++i) {
         tab[2 * n + i] = run;
-        run += (tab[n + i] + kChunk - 1) / kChunk;
+        run += (tab[n + i] + sub - 1) / sub;
     }
     __syncthreads();                                              // all lengths are visible
 
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
 // (B + 1 entries).  Runs are whole chunks, so the chunk counts of the run table add up as those of
 // the sequence table do.  The runs keep their order (no sorting by length: none is long).
 __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int* seq_tab, int B, int T, int run_chunks,
-                                                                       int R, int* run_tab, int* first_run)
+                                                                       int R, int* run_tab, int* first_run, int sub)
 {
     __shared__ int part[kTabThreads];
     const int n = B + 1, tid = threadIdx.x;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int
     const int* len = seq_tab + n;
     const int* before = seq_tab + 2 * n;
     auto runs_of = [&](int b) {
-        const int nc = b < B ? (len[b] + kChunk - 1) / kChunk : 0;
+        const int nc = b < B ? (len[b] + sub - 1) / sub : 0;
         return (nc + run_chunks - 1) / run_chunks;
     };
     int c = 0;
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int
     __syncthreads();
     int first = 0;
     for (int j = 0; j < tid; ++j) first += part[j];
-    const int m = R + 1, run_tokens = run_chunks * kChunk;
+    const int m = R + 1, run_tokens = run_chunks * sub;
     for (int b = lo; b < hi; ++b) {
         first_run[b] = first;
         const int nr = runs_of(b);
@@ -247,9 +247,9 @@ hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream)
 
 size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
-hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups)
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups, int sub)
 {
-    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table, G, groups);
+    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table, G, groups, sub);
     return hipGetLastError();
 }
 
@@ -264,10 +264,10 @@ hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* gro
 size_t varlen_run_table_bytes(int B, int R) { return varlen_table_bytes(R) + ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
-                                   int* first_run, hipStream_t stream)
+                                   int* first_run, hipStream_t stream, int sub)
 {
     hipLaunchKernelGGL(varlen_run_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, seq_table, B, T, run_chunks, R,
-                       run_table, first_run);
+                       run_table, first_run, sub);
     return hipGetLastError();
 }
 

@@ -78,11 +78,10 @@ def test_small_gate_mode_workspace_and_support():
     big = 1 << 40
     assert binding.hgrn2_bwd_gated_workspace_bytes(s) == binding.hgrn2_bwd_gated_workspace_bytes(inner)
     assert lib.hgrn2_fwd_gated(sp, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL      # beta missing
-    # packed batches: sequence table, spread offsets, the spread tensors of (200 // 16 + 2) chunks, the inner call
+    # packed batches: the tables and the states of at most 200 // 16 + 2 chunks of 16 tokens per head
     sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=16)
-    inner_v = shape(B=2, H=3, N=14 * 64, dk=64, dv=128, layout=1)
-    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == (256 + 256 + 14 * 64 * 3 * (64 + 64 + 128 + 128) * 2
-                                                            + binding.hgrn2_fwd_varlen_workspace_bytes(inner_v))
+    tables = binding.hgrn2_fwd_varlen_workspace_bytes(shape(B=2, H=3, N=200, dk=64, dv=128, layout=1)) - 5 * 3 * 64 * 128 * 2
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == tables + 14 * 3 * 64 * 128 * 2
     # not offered for the stage calls
     assert lib.hgrn2_state_sweep(sp, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_UNSUP
     assert lib.hgrn2_fwd(sp, FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, 1024, None) == E_WS
@@ -119,10 +118,9 @@ def test_chunk_length_chosen_on_the_device_sizes_and_support():
     assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=-2)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_SHAPE
     # not offered: the stage calls, packed batches
     assert lib.hgrn2_state_sweep(ap, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_SHAPE
-    for c, code in ((AUTO, E_SHAPE), (8, E_UNSUP)):
-        sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=c)
-        assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == 0
-        assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == code
+    sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=AUTO)
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == 0
+    assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_SHAPE
 
 
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):
@@ -332,7 +330,7 @@ def test_varlen_workspace_and_error_codes():
     for call in (fwd_s, bwd_s):
         assert call(shape(layout=0)) == E_SHAPE
         assert call(shape(layout=1, io=0, gate=0)) == E_UNSUP        # the shapes the backward pass takes
-        assert call(shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1, chunk=16)) == E_UNSUP
+        assert call(shape(B=6, H=3, N=1000, dk=64, dv=64, layout=1, chunk=48)) == E_UNSUP
         assert call(s, sv=None) == E_WS
         assert call(s, sn=states + table - 1) == E_WS
         assert call(s, cu=None) == E_NULL

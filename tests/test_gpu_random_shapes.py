@@ -89,7 +89,8 @@ def test_random_packed_sequences(seed):
     lens = [int(x) for x in rng.integers(0, 150, size=B)]
     T = int(sum(lens))
     gated = bool(rng.integers(0, 2))
-    print("\n[random packed] seed=%d H=%d dk=%d dv=%d gated=%s lens=%s" % (seed, H, dk, dv, gated, lens), flush=True)
+    chunk = (0, 32, 16, 8)[seed % 4]                      # tokens per chunk (0: 64); these gates allow any
+    print("\n[random packed] seed=%d H=%d dk=%d dv=%d gated=%s chunk=%d lens=%s" % (seed, H, dk, dv, gated, chunk, lens), flush=True)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     w = synth.make_sequence(seed, 1, H, max(T, 1), dk, dv, io_dtype="bf16", lb=0.3, with_dO=True)
     z = synth.bf16_round((1.5 * rng.standard_normal((1, H, max(T, 1), dk), dtype=np.float32)).astype(np.float32))
@@ -103,8 +104,8 @@ def test_random_packed_sequences(seed):
     q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
     cud = torch.from_numpy(cu).cuda()
     bd = torch.from_numpy(beta).cuda() if gated else None
-    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd)
-    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk)
     torch.cuda.synchronize()
     ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
     rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))
@@ -212,7 +213,8 @@ def test_random_packed_long_documents(seed):
     lens[int(rng.integers(0, B))] = int(rng.integers(B * 2100, B * 2100 + 1500))      # the mean length is past the cut
     T = int(sum(lens))
     gated = bool(rng.integers(0, 2))
-    print("\n[random packed long] seed=%d H=%d dk=%d dv=%d gated=%s lens=%s" % (seed, H, dk, dv, gated, lens), flush=True)
+    chunk = (0, 0, 32, 16, 0)[seed % 5]                   # tokens per chunk (0: 64); these gates allow any
+    print("\n[random packed long] seed=%d H=%d dk=%d dv=%d gated=%s chunk=%d lens=%s" % (seed, H, dk, dv, gated, chunk, lens), flush=True)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     w = synth.make_sequence(seed, 1, H, T, dk, dv, io_dtype="bf16", lb=0.8, with_dO=True)
     z = synth.bf16_round((1.0 + 1.5 * rng.standard_normal((1, H, T, dk), dtype=np.float32)).astype(np.float32))
@@ -225,8 +227,8 @@ def test_random_packed_long_documents(seed):
     q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
     cud = torch.from_numpy(cu).cuda()
     bd = torch.from_numpy(beta).cuda() if gated else None
-    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd)
-    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True)
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk)
     torch.cuda.synchronize()
     ro, rq, rg, rv = (np.zeros((H, T, d)) for d in (dv, dk, dk, dv))
     rhT, rh0, rb = np.zeros((B, H, dk, dv)), np.zeros((B, H, dk, dv)), np.zeros((H, dk))

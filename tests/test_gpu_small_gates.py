@@ -247,16 +247,21 @@ def test_small_gates_with_the_gate_formed_in_the_kernels():
     check("dv", host(gv), rv, tol); check("dh0", host(gh0), rh, tol)
 
 
-@pytest.mark.parametrize("lens,H,dk,dv,gated,chunk", [
-    ([150, 0, 37, 260], 2, 64, 64, False, 16),
-    ([90, 300], 3, 128, 64, True, 16),
-    ([200, 1, 333], 2, 128, 128, False, 32),
+@pytest.mark.parametrize("lens,H,dk,dv,gated,chunk,pair", [
+    ([150, 0, 37, 260], 2, 64, 64, False, 16, False),
+    ([90, 300], 3, 128, 64, True, 16, False),
+    ([200, 1, 333], 2, 128, 128, False, 32, False),
+    ([150, 0, 37, 260], 2, 64, 64, False, 16, True),
+    ([70, 45, 0, 33, 90, 17, 64, 1, 80, 5, 120, 31, 66, 48, 12, 100] * 3, 16, 128, 128, False, 32, True),  # groups of sequences per workgroup
+    ([1300, 900], 2, 128, 128, False, 16, True),       # documents walked in runs of the shorter chunks
+    ([60, 9, 100], 3, 64, 128, False, 8, False),
 ])
-def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk):
-    """Every sequence of a packed batch is spread on its own (ragged last blocks, an empty and a
-    one-token sequence), with the gates given or formed in the kernels."""
+def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk, pair):
+    """Packed batches take the shorter chunks like equal-length ones (the tables count chunks of 32, 16 or 8
+    tokens): ragged last chunks, empty and one-token sequences, groups of sequences per workgroup,
+    documents cut into runs, the gates given or formed in the kernels, stateless or as the training pair."""
     B, T = len(lens), int(sum(lens))
-    print("\n[small gates packed] H=%d dk=%d dv=%d gated=%s chunk=%d lens=%s" % (H, dk, dv, gated, chunk, lens), flush=True)
+    print("\n[small gates packed] H=%d dk=%d dv=%d gated=%s chunk=%d pair=%s lens=%s" % (H, dk, dv, gated, chunk, pair, lens), flush=True)
     rng = np.random.default_rng(8100 + T)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     w = small_gate_workload(8100 + B, 1, H, T, dk, dv, "loguniform" if chunk == 16 else "loguniform32")
@@ -270,8 +275,13 @@ def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk):
     q, g, v, dO = pk(w.q), pk(gate_in), pk(w.v), pk(w.dO)
     cud = torch.from_numpy(cu).cuda()
     bd = torch.from_numpy(beta).cuda() if gated else None
-    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk)
-    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk)
+    saved = None
+    if pair:
+        saved = torch.empty(max(binding.hgrn2_saved_states_varlen_bytes(binding.make_shape_varlen(q, v, g, B, chunk)), 256),
+                            dtype=torch.uint8, device="cuda")
+    o, hT = binding.hgrn2_fwd_varlen(q, g, v, cud, dev(h0), beta=bd, chunk=chunk, saved_states=saved)
+    res = binding.hgrn2_bwd_varlen(q, g, v, dO, cud, dev(h0), dev(dhT), beta=bd, want_grad_h0=True, chunk=chunk,
+                                   saved_states=saved)
     # the probe on the packed batch: windows restart with every sequence
     gates = oracle.gate(z, beta) if gated else w.f
     for ck in (0, chunk):
