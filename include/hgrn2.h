@@ -42,10 +42,10 @@
  *     f >= 0.014, f >= 1.8e-4).  A chunk of the kernels then holds 32 or 16 tokens in its middle
  *     rows and nothing in the others: twice or four times the chunks (1.8 or 3.6 times the time
  *     of the training pair, and workspaces and saved states for as many chunks; the training
- *     pair hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  Equal-length batches
- *     also take chunk = 8 (products of 4 gates: f >= 3e-8, eight times the chunks).  Packed
- *     batches (_varlen) are copied into spread ones for chunk = 32 or 16 (their workspace also
- *     holds those copies).  hgrn2_min_gate_product tells which mode a set of gates needs.
+ *     pair hgrn2_fwd_saving / hgrn2_bwd_saved takes the modes as well).  chunk = 8 goes one
+ *     step further (products of 4 gates: f >= 3e-8, eight times the chunks).  Packed batches
+ *     (_varlen, with their training pair) take the three modes the same way.
+ *     hgrn2_min_gate_product tells which mode a set of gates needs.
  *     chunk = HGRN2_CHUNK_AUTO (equal-length batches: hgrn2_fwd, hgrn2_bwd, their _gated, _saving /
  *     _saved and _noalloc forms) needs no probe: the pass is enqueued for 64, then 32, then 16 tokens
  *     per chunk; the kernels of the first raise a flag inside the workspace when a product falls

@@ -67,7 +67,7 @@ def test_workspace_sizes():
 
 def test_small_gate_mode_workspace_and_support():
     """chunk = 16 / 32, equal lengths: chunks of that many tokens, so the workspace of a sequence of
-    64 / chunk times as many tokens and nothing else; packed batches: spread tensors and the inner call."""
+    64 / chunk times as many tokens and nothing else; packed batches alike."""
     s = shape(B=2, H=3, N=200, dk=64, dv=128, chunk=16)
     inner = shape(B=2, H=3, N=13 * 64, dk=64, dv=128)           # 13 blocks of 16 tokens, a chunk each
     assert binding.hgrn2_fwd_workspace_bytes(s) == binding.hgrn2_fwd_workspace_bytes(inner) == 2 * 3 * 13 * 64 * 128 * 2

@@ -1,7 +1,6 @@
 """Small gates.  With a reference row every 64 tokens the chunkwise kernels are exact while the gate
 product of every half chunk stays above 2^-100; chunk = 16 (32) in the shape asks for reference rows
-every 16 (32) tokens (a chunk of the kernels then holds only that many tokens, in its middle rows;
-packed batches are copied into spread ones),
+every 16 (32) tokens (a chunk of the kernels then holds only that many tokens, in its middle rows),
 which moves that bound to products of 8 (16) gates.  The cases here lie outside the first domain and inside the
 second and are compared with the fp64 oracle, which has no such limit; the probe must say so for
 both spacings.  Tolerance: max|x-y|/max|y| <= 2e-2 per tensor (bf16), 1e-4 (fp32 forward)."""
@@ -39,7 +38,7 @@ def small_gate_workload(seed, B, H, N, dk, dv, kind, io_dtype="bf16"):
     ("loguniform", 2, 3, 200, 64, 64, 0, 16),
     ("resets", 1, 2, 333, 128, 128, 1, 16),
     ("loguniform", 9, 8, 130, 128, 128, 0, 16),      # enough sequences for the single-pass forward
-    ("resets", 1, 2, 1100, 64, 128, 0, 16),          # spread to 69 chunks: walked in runs
+    ("resets", 1, 2, 1100, 64, 128, 0, 16),          # 69 chunks of 16 tokens: walked in runs
     ("loguniform32", 2, 2, 300, 128, 64, 1, 32),
     ("loguniform32", 1, 3, 700, 64, 64, 0, 32),
     ("loguniform8", 2, 2, 150, 128, 128, 0, 8),      # a chunk holds 8 tokens, in rows 28 .. 35: half a row block of two waves each
@@ -214,7 +213,7 @@ def test_fine_and_coarse_reference_rows_agree_on_ordinary_gates():
     torch.cuda.synchronize()
     for name, x, y in zip(("dq", "df", "dv", "dh0"), a, b):
         check(name, host(y), host(x), 1e-2)
-    # empty sequences pass through the spreading as well
+    # empty sequences pass in this mode as well
     e = torch.empty((B, H, 0, d), dtype=torch.bfloat16, device="cuda")
     o, hT = binding.hgrn2_fwd(e, e, e, dev(w.h0), chunk=16)
     torch.cuda.synchronize()
