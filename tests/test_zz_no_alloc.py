@@ -13,18 +13,21 @@ from gpu_util import TOL, dev, host, check
 pytestmark = pytest.mark.gpu
 
 
-def run_pair(seed, B, H, N, dk, dv, layout=binding.HGRN2_LAYOUT_BHND):
+def run_pair(seed, B, H, N, dk, dv, layout=binding.HGRN2_LAYOUT_BHND, chunk=0, small_gates=False):
     w = synth.make_sequence(seed, B, H, N, dk, dv, io_dtype="bf16", lb=0.2, with_h0=True, with_dO=True,
                             with_dhT=True)
+    if small_gates:      # log-uniform in [0.02, 1]: outside the domain of 64-token chunks, inside that of 32-token ones
+        rng = np.random.default_rng(seed)
+        w.f = synth.bf16_round((10.0 ** rng.uniform(np.log10(0.02), 0.0, size=w.f.shape)).astype(np.float32))
     q, f, v, dO = (dev(x, "bf16") for x in (w.q, w.f, w.v, w.dO))
     if layout == binding.HGRN2_LAYOUT_BNHD:
         q, f, v, dO = (t.permute(0, 2, 1, 3).contiguous() for t in (q, f, v, dO))
     h0, dhT = dev(w.h0), dev(w.dhT)
-    ref = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout)
+    ref = binding.hgrn2_bwd(q, f, v, dO, h0, dhT, want_grad_h0=True, layout=layout, chunk=chunk)
     # outputs pre-filled with a pattern: the call has to write every element
     outs = [torch.full_like(q, 7.0), torch.full_like(q, 7.0), torch.full_like(v, 7.0),
             torch.full((B, H, dk, dv), 7.0, dtype=torch.float32, device=q.device)]
-    got = binding.hgrn2_bwd_noalloc(q, f, v, dO, h0, dhT, *outs, layout=layout)
+    got = binding.hgrn2_bwd_noalloc(q, f, v, dO, h0, dhT, *outs, layout=layout, chunk=chunk)
     torch.cuda.synchronize()
     for name, x, r in zip(("dq", "df", "dv", "dh0"), got, ref):
         check(name, host(x), host(r), TOL["bf16"])
@@ -39,6 +42,15 @@ def test_two_calls_second_smaller():
     run_pair(902, 1, 2, 70, 64, 64)
     print("  third call, token-major: B=2 H=2 N=130 dk=128 dv=128", flush=True)
     run_pair(903, 2, 2, 130, 128, 128, layout=binding.HGRN2_LAYOUT_BNHD)
+
+
+def test_chunk_length_chosen_on_the_device_in_the_built_in_workspace():
+    """chunk = HGRN2_CHUNK_AUTO keeps its flags in the built-in array too: ordinary gates, then gates that make
+    the kernels fall back to 32 tokens per chunk, then ordinary ones again (what the calls before left in the
+    array, flags included, must not matter)."""
+    for k, small in enumerate((False, True, False)):
+        print("\n  call %d, chunk chosen on the device, small gates: %s" % (k, small), flush=True)
+        run_pair(910 + k, 2, 3, 200 - 30 * k, 128, 128, chunk=-1, small_gates=small)
 
 
 def test_limit_is_enforced_before_any_launch():
