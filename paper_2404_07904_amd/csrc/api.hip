@@ -684,7 +684,7 @@ int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, cons
     if (rc != HGRN2_OK) return rc;
     const size_t need = state_ws_bytes(d) > 0 ? hgrn2_saved_states_bytes(shape) : 0;
     if (need == 0)      // no chunks: nothing was saved, the ordinary pass handles what is left (grad_h0, grad_beta)
-        return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+        return bwd_impl(&alt[0], q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
                         grad_h0, workspace, workspace_bytes, hip_stream);
     if (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255)) return HGRN2_ERR_WORKSPACE;
     return bwd_impl(shape, q, f, beta, beta != nullptr, v, nullptr, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,

@@ -193,6 +193,23 @@ def test_chunk_length_chosen_on_the_device_gated_and_out_of_every_domain():
     assert int(flag.item()) == 1
 
 
+def test_chunk_length_chosen_on_the_device_without_tokens():
+    """N = 0 in every form of the call: the final state is the initial one, the state gradient passes through."""
+    AUTO = -1
+    B, H, d = 2, 3, 64
+    e = torch.empty((B, H, 0, d), dtype=torch.bfloat16, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(3)
+    h0 = torch.randn((B, H, d, d), generator=g, device="cuda")
+    dhT = torch.randn((B, H, d, d), generator=g, device="cuda")
+    o, hT = binding.hgrn2_fwd(e, e, e, h0, chunk=AUTO)
+    res = binding.hgrn2_bwd(e, e, e, e, h0, dhT, want_grad_h0=True, chunk=AUTO)
+    o2, hT2, saved = binding.hgrn2_fwd_saving(e, e, e, h0, chunk=AUTO)
+    res2 = binding.hgrn2_bwd_saved(e, e, e, saved, e, dhT, want_grad_h0=True, chunk=AUTO)
+    torch.cuda.synchronize()
+    assert torch.equal(hT, h0) and torch.equal(hT2, h0)
+    assert torch.equal(res[3], dhT) and torch.equal(res2[3], dhT)
+
+
 def test_small_gates_fp32_forward():
     B, H, N, dk, dv = 1, 2, 150, 64, 64
     print("\n[small gates fp32] B=%d H=%d N=%d" % (B, H, N), flush=True)
