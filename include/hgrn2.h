@@ -46,14 +46,15 @@
  *     step further (products of 4 gates: f >= 3e-8, eight times the chunks).  Packed batches
  *     (_varlen, with their training pair) take the three modes the same way.
  *     hgrn2_min_gate_product tells which mode a set of gates needs.
- *     chunk = HGRN2_CHUNK_AUTO (equal-length batches: hgrn2_fwd, hgrn2_bwd, their _gated, _saving /
- *     _saved and _noalloc forms) needs no probe: the pass is enqueued for 64, then 32, then 16 tokens
+ *     chunk = HGRN2_CHUNK_AUTO (hgrn2_fwd, hgrn2_bwd, their _gated, _saving / _saved, _noalloc and
+ *     _varlen forms) needs no probe: the pass is enqueued for 64, then 32, then 16 tokens
  *     per chunk; the kernels of the first raise a flag inside the workspace when a product falls
  *     below the floor, those of the next run only if it is set (they return at once otherwise) and
  *     overwrite every result, and so on.  The results are those of the longest chunk the gates
  *     allow; shape->gate_domain_flag is raised only when even 16 tokens per chunk are too many.
  *     Ordinary gates pay the launches that do nothing (about ten microseconds per pass); the
- *     workspaces and saved states are sized for 16 tokens per chunk.
+ *     workspaces and saved states are sized for 16 tokens per chunk (the saved states of a packed
+ *     batch: for all three chunk lengths, one after the other).
  *   - Supported shapes: dk, dv in {64, 128}; chunk in {0 (= 64), 64}, and 32, 16, 8, HGRN2_CHUNK_AUTO where stated;
  *     any B, H, N >= 0.
  *     A sequence length that is not a multiple of the chunk is handled inside the kernels.

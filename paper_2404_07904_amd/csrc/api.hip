@@ -218,12 +218,14 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     d->lay.vl = seq_table;
     // (a batch that is not cut gets its group array, over the sequence table, in the same launch)
     int* groups_here = (p.G > 0 && p.run_chunks == 0) ? reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at) : nullptr;
-    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream, p.G, groups_here, d->lay.sub) : hipSuccess;
+    hipError_t e = launch ? launch_varlen_table(cu_seqlens, s->B, d->N, seq_table, stream, p.G, groups_here, d->lay.sub,
+                                                d->lay.alt, d->lay.alt_path) : hipSuccess;
     if (e != hipSuccess) return e;
     if (p.run_chunks != 0) {
         int* run_table = reinterpret_cast<int*>(static_cast<char*>(workspace) + round256(varlen_table_bytes(s->B)));
         int* fr = run_table + 4 * ((size_t)p.R + 1);
-        e = launch ? launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream, d->lay.sub) : hipSuccess;
+        e = launch ? launch_varlen_run_table(seq_table, s->B, d->N, p.run_chunks, p.R, run_table, fr, stream, d->lay.sub,
+                                             d->lay.alt, d->lay.alt_path) : hipSuccess;
         if (e != hipSuccess) return e;
         d->lay.vl = run_table;
         d->lay.B = p.R;
@@ -232,7 +234,7 @@ hipError_t build_packed_tables(const hgrn2_shape* s, const PackedRuns& p, const 
     }
     if (p.G > 0) {
         int* groups = reinterpret_cast<int*>(static_cast<char*>(workspace) + p.groups_at);
-        if (launch && !groups_here) e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream);
+        if (launch && !groups_here) e = launch_varlen_groups(d->lay.vl, d->lay.B, p.G, groups, stream, d->lay.alt, d->lay.alt_path);
         if (p.by_groups) {
             d->lay.groups = groups;
             d->lay.G = p.G;
@@ -266,15 +268,17 @@ int alternatives(const hgrn2_shape* shape, hgrn2_shape (&alt)[kAlternatives])
 }
 
 // largest value of a size over the alternatives (plus, with `head`, the flags' place when there are several)
-template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F bytes_of, bool head, bool backward)
+// (`sum`: the total instead -- every alternative keeps a place of its own)
+template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F bytes_of, bool head, bool backward,
+                                                   bool packed = false, bool sum = false)
 {
     if (!shape) return 0;
     hgrn2_shape alt[kAlternatives];
     const int n = alternatives(shape, alt);
     SeqDims d;
-    if (check_shape(&alt[0], backward, &d, false, true) != HGRN2_OK) return 0;      // an invalid shape needs nothing
+    if (check_shape(&alt[0], backward, &d, packed, true) != HGRN2_OK) return 0;      // an invalid shape needs nothing
     size_t m = 0;
-    for (int i = 0; i < n; ++i) { const size_t b = bytes_of(&alt[i]); if (b > m) m = b; }
+    for (int i = 0; i < n; ++i) { const size_t b = bytes_of(&alt[i]); m = sum ? m + b : (b > m ? b : m); }
     return m + ((n > 1 && head) ? kAutoHead : 0);
 }
 
@@ -691,7 +695,7 @@ int hgrn2_bwd_saved(const hgrn2_shape* shape, const void* q, const void* f, cons
                     grad_h0, workspace, workspace_bytes, hip_stream, saved_states);
 }
 
-size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+static size_t fwd_varlen_ws_one(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, false, &d, true) != HGRN2_OK) return 0;
@@ -699,13 +703,23 @@ size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
     return p.table_bytes + round256(state_ws_bytes(d)) + p.state_bytes + p.decay_bytes;
 }
 
-size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+static size_t bwd_varlen_ws_one(const hgrn2_shape* shape)
 {
     SeqDims d;
     if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
     const PackedRuns p = plan_packed_runs(shape, d, true);
     return p.table_bytes + 2 * (round256(state_ws_bytes(d)) + p.state_bytes) + p.decay_bytes +
            round256(beta_partials_bytes(d));
+}
+
+size_t hgrn2_fwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+{
+    return max_over_alternatives(shape, fwd_varlen_ws_one, true, false, true);
+}
+
+size_t hgrn2_bwd_varlen_workspace_bytes(const hgrn2_shape* shape)
+{
+    return max_over_alternatives(shape, bwd_varlen_ws_one, true, true, true);
 }
 
 // A packed batch's forward pass can hand its per-chunk states to the backward pass only when both
@@ -717,19 +731,21 @@ static bool packed_states_kept(const hgrn2_shape* shape, const SeqDims& d)
     return plan_packed_runs(shape, d, false).run_chunks == plan_packed_runs(shape, d, true).run_chunks;
 }
 
-static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                           const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
-                           size_t workspace_bytes, void* hip_stream, void* save_states)
+static int fwd_varlen_one(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                          const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
+                          size_t workspace_bytes, void* hip_stream, void* save_states, const Alternative* alt)
 {
     SeqDims d;
     const int rc = check_shape_varlen(shape, false, &d, true);
     if (rc != HGRN2_OK) return rc;
     d.beta = beta;
+    if (alt) { d.lay.alt = alt->choice; d.lay.alt_path = alt->path; d.domain_flag = alt->flag; }
     if (d.BH == 0) return HGRN2_OK;
     const bool has_tokens = d.N > 0;
     if (!cu_seqlens || (has_tokens && (!q || !f || !v || !o))) return HGRN2_ERR_NULL;
-    const size_t need = hgrn2_fwd_varlen_workspace_bytes(shape);
+    const size_t need = fwd_varlen_ws_one(shape);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    if (alt && alt->validate_only) return HGRN2_OK;
     if (!has_tokens && !hT) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const PackedRuns pr = plan_packed_runs(shape, d, false);
@@ -749,7 +765,7 @@ static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
         float* run_decay = reinterpret_cast<float*>(static_cast<char*>(ws_s) + one + pr.state_bytes);
         if (launch_sweep(d, kSweepStateFwd, q, f, v, nullptr, run_state, nullptr, run_decay, stream) != hipSuccess ||
             launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_state, run_decay, hT, false,
-                                    stream) != hipSuccess)
+                                    stream, d.lay.alt, d.lay.alt_path) != hipSuccess)
             return HGRN2_ERR_HIP;
         if (fwd_fused_supported(d))
             return launch_fwd_fused(d, q, f, v, run_state, o, nullptr, save_states, stream) == hipSuccess ? HGRN2_OK : HGRN2_ERR_HIP;
@@ -772,6 +788,87 @@ static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     return HGRN2_OK;
 }
 
+// what the forward pass of a packed training pair leaves: the chunk states, then the tables
+static size_t packed_saved_bytes(const hgrn2_shape* shape, const SeqDims& d)
+{
+    return round256(state_ws_bytes(d)) + plan_packed_runs(shape, d, true).table_bytes;
+}
+
+static size_t packed_saved_one(const hgrn2_shape* shape)
+{
+    SeqDims d;
+    if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
+    return packed_saved_bytes(shape, d);
+}
+
+// (chunk = HGRN2_CHUNK_AUTO: every alternative keeps its states and tables in a place of its own, one
+// after the other, and the int that names the alternative that ran follows them)
+size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape)
+{
+    return max_over_alternatives(shape, packed_saved_one, true, true, true, true);
+}
+
+// where alternative i of `shape` keeps its states inside `saved` (null stays null), or null when that
+// alternative's pair keeps none (see packed_states_kept)
+static void* packed_saved_place(const hgrn2_shape* shape, int i, const void* saved)
+{
+    if (!saved) return nullptr;
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    size_t off = 0;
+    for (int j = 0; j < i; ++j) off += packed_saved_one(&alt[j]);
+    SeqDims d;
+    if (check_shape_varlen(&alt[i], true, &d, true) != HGRN2_OK) return nullptr;
+    if (state_ws_bytes(d) == 0 || !packed_states_kept(&alt[i], d)) return nullptr;
+    return const_cast<char*>(static_cast<const char*>(saved)) + off;
+}
+
+// Forward pass of a packed batch, or (chunk = HGRN2_CHUNK_AUTO) its three alternatives, as fwd_impl.
+static int fwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, void* save_states)
+{
+    if (!shape) return HGRN2_ERR_NULL;
+    if (!auto_mode(shape))
+        return fwd_varlen_one(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
+                              packed_saved_place(shape, 0, save_states), nullptr);
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    {
+        SeqDims d;
+        const int rc = check_shape_varlen(&alt[0], false, &d, true);
+        if (rc != HGRN2_OK) return rc;
+        if (d.BH == 0) return HGRN2_OK;
+    }
+    const size_t need = hgrn2_fwd_varlen_workspace_bytes(shape);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    char* rest = static_cast<char*>(workspace) + kAutoHead;
+    Alternative a;
+    a.validate_only = true;
+    for (int i = 0; i < kAlternatives; ++i) {
+        const int rc = fwd_varlen_one(&alt[i], cu_seqlens, q, f, beta, v, h0, o, hT, rest, workspace_bytes - kAutoHead, hip_stream,
+                                      nullptr, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* flags = static_cast<int*>(workspace);
+    if (launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    a.validate_only = false;
+    for (int i = 0; i < kAlternatives; ++i) {
+        a.choice = i == 0 ? nullptr : flags + (i - 1);
+        a.path = 1;
+        a.flag = i + 1 < kAlternatives ? flags + i : shape->gate_domain_flag;
+        const int rc = fwd_varlen_one(&alt[i], cu_seqlens, q, f, beta, v, h0, o, hT, rest, workspace_bytes - kAutoHead, hip_stream,
+                                      packed_saved_place(shape, i, save_states), &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    if (save_states) {
+        int* which = reinterpret_cast<int*>(static_cast<char*>(save_states) + hgrn2_saved_states_varlen_bytes(shape) - kAutoHead);
+        if (launch_sum_ints(flags, 2, which, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    }
+    return HGRN2_OK;
+}
+
 int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
                      const float* beta, const void* v, const float* h0, void* o, float* hT, void* workspace,
                      size_t workspace_bytes, void* hip_stream)
@@ -779,43 +876,34 @@ int hgrn2_fwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const 
     return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream, nullptr);
 }
 
-// what the forward pass of a packed training pair leaves: the chunk states, then the tables
-static size_t packed_saved_bytes(const hgrn2_shape* shape, const SeqDims& d)
-{
-    return round256(state_ws_bytes(d)) + plan_packed_runs(shape, d, true).table_bytes;
-}
-
-size_t hgrn2_saved_states_varlen_bytes(const hgrn2_shape* shape)
-{
-    SeqDims d;
-    if (check_shape_varlen(shape, true, &d, true) != HGRN2_OK) return 0;
-    return packed_saved_bytes(shape, d);
-}
-
 int hgrn2_fwd_varlen_saving(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
                             const float* beta, const void* v, const float* h0, void* o, float* hT, void* saved_states,
                             size_t saved_states_bytes, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
+    if (!shape) return HGRN2_ERR_NULL;
     SeqDims d;
-    const int rc = check_shape_varlen(shape, true, &d, true);      // the shapes the backward pass takes
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    const int rc = check_shape_varlen(&alt[0], true, &d, true);      // the shapes the backward pass takes
     if (rc != HGRN2_OK) return rc;
-    const size_t need = packed_saved_bytes(shape, d);
+    const size_t need = hgrn2_saved_states_varlen_bytes(shape);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
-    return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream,
-                           state_ws_bytes(d) > 0 && packed_states_kept(shape, d) ? saved_states : nullptr);
+    return fwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, o, hT, workspace, workspace_bytes, hip_stream, saved_states);
 }
 
-static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
-                           const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
-                           void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
-                           size_t workspace_bytes, void* hip_stream, const void* saved_states)
+static int bwd_varlen_one(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                          const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                          void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                          size_t workspace_bytes, void* hip_stream, const void* saved_states, const Alternative* alt)
 {
     SeqDims d;
     const int rc = check_shape_varlen(shape, true, &d, true);
     if (rc != HGRN2_OK) return rc;
     d.beta = beta;
+    if (alt) { d.lay.alt = alt->choice; d.lay.alt_path = alt->path; d.domain_flag = alt->flag; }
     if (beta && !grad_beta && (size_t)shape->H * d.dk > 0) return HGRN2_ERR_NULL;
     if (d.BH == 0) {
+        if (alt && alt->validate_only) return HGRN2_OK;
         // no sequences: nothing contributes to the gradient of beta
         if (beta && (size_t)shape->H * d.dk > 0 &&
             launch_zero_floats(grad_beta, (size_t)shape->H * d.dk, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
@@ -825,14 +913,15 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     const bool has_tokens = d.N > 0;
     if (!cu_seqlens || (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)))
         return HGRN2_ERR_NULL;
-    const size_t need = hgrn2_bwd_varlen_workspace_bytes(shape);
+    const size_t need = bwd_varlen_ws_one(shape);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    if (alt && alt->validate_only) return HGRN2_OK;
     if (!has_tokens && !grad_h0 && !beta) return HGRN2_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const PackedRuns pr = plan_packed_runs(shape, d, true);
     const size_t one = round256(state_ws_bytes(d));
     char* base = static_cast<char*>(workspace) + pr.table_bytes;
-    if (saved_states && (!has_tokens || !packed_states_kept(shape, d))) saved_states = nullptr;   // none were kept
+    if (!has_tokens) saved_states = nullptr;          // none were kept
     // with states left by the forward pass, only the sweep of the state gradient remains to be run
     void* ws_s = saved_states ? const_cast<void*>(saved_states) : base;
     void* ws_ds = base + one;
@@ -856,12 +945,12 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                 return HGRN2_ERR_HIP;
         } else if (launch_sweep_pair_ends(d, q, f, v, grad_o, run_s, run_ds, run_decay, stream) != hipSuccess ||
                    launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, h0, run_s, run_decay, nullptr, false,
-                                           stream) != hipSuccess ||
+                                           stream, d.lay.alt, d.lay.alt_path) != hipSuccess ||
                    launch_sweep(d, kSweepStateBwd, nullptr, f, v, run_s, nullptr, ws_s, nullptr, stream) != hipSuccess) {
             return HGRN2_ERR_HIP;
         }
         if (launch_run_carry_packed(shape->B, shape->H, first_run, d.dk, d.dv, grad_hT, run_ds, run_decay, grad_h0, true,
-                                    stream) != hipSuccess ||
+                                    stream, d.lay.alt, d.lay.alt_path) != hipSuccess ||
             launch_bwd_fused_grouped(d, q, f, v, grad_o, ws_s, run_ds, nullptr, grad_q, grad_f, grad_v, ws_part,
                                      stream) != hipSuccess)
             return HGRN2_ERR_HIP;
@@ -900,6 +989,61 @@ static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
     return HGRN2_OK;
 }
 
+// Backward pass of a packed batch, or (chunk = HGRN2_CHUNK_AUTO) its three alternatives, as bwd_impl.
+static int bwd_varlen_impl(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
+                           const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
+                           void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
+                           size_t workspace_bytes, void* hip_stream, const void* saved_states)
+{
+    if (!shape) return HGRN2_ERR_NULL;
+    if (!auto_mode(shape))
+        return bwd_varlen_one(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                              workspace, workspace_bytes, hip_stream, packed_saved_place(shape, 0, saved_states), nullptr);
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    bool no_sequences = false;
+    {
+        SeqDims d;
+        const int rc = check_shape_varlen(&alt[0], true, &d, true);
+        if (rc != HGRN2_OK) return rc;
+        no_sequences = d.BH == 0;
+    }
+    if (no_sequences)       // (grad_beta = 0: any alternative does that, and none needs a workspace)
+        return bwd_varlen_one(&alt[0], cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
+                              workspace, workspace_bytes, hip_stream, nullptr, nullptr);
+    const size_t need = hgrn2_bwd_varlen_workspace_bytes(shape);
+    if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255)) return HGRN2_ERR_WORKSPACE;
+    char* rest = static_cast<char*>(workspace) + kAutoHead;
+    Alternative a;
+    a.validate_only = true;
+    for (int i = 0; i < kAlternatives; ++i) {
+        const int rc = bwd_varlen_one(&alt[i], cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+                                      grad_h0, rest, workspace_bytes - kAutoHead, hip_stream, nullptr, &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int* flags = static_cast<int*>(workspace);
+    const int* which = saved_states ? reinterpret_cast<const int*>(static_cast<const char*>(saved_states) +
+                                                                   hgrn2_saved_states_varlen_bytes(shape) - kAutoHead)
+                                    : nullptr;
+    if (!saved_states && launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
+    a.validate_only = false;
+    for (int i = 0; i < kAlternatives; ++i) {
+        if (saved_states) {
+            a.choice = which; a.path = i;
+            a.flag = i + 1 < kAlternatives ? nullptr : shape->gate_domain_flag;
+        } else {
+            a.choice = i == 0 ? nullptr : flags + (i - 1); a.path = 1;
+            a.flag = i + 1 < kAlternatives ? flags + i : shape->gate_domain_flag;
+        }
+        const int rc = bwd_varlen_one(&alt[i], cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v,
+                                      grad_h0, rest, workspace_bytes - kAutoHead, hip_stream,
+                                      packed_saved_place(shape, i, saved_states), &a);
+        if (rc != HGRN2_OK) return rc;
+    }
+    return HGRN2_OK;
+}
+
 int hgrn2_bwd_varlen(const hgrn2_shape* shape, const int32_t* cu_seqlens, const void* q, const void* f,
                      const float* beta, const void* v, const float* h0, const void* grad_o, const float* grad_hT,
                      void* grad_q, void* grad_f, float* grad_beta, void* grad_v, float* grad_h0, void* workspace,
@@ -915,13 +1059,16 @@ int hgrn2_bwd_varlen_saved(const hgrn2_shape* shape, const int32_t* cu_seqlens, 
                            float* grad_beta, void* grad_v, float* grad_h0, void* workspace, size_t workspace_bytes,
                            void* hip_stream)
 {
+    if (!shape) return HGRN2_ERR_NULL;
     SeqDims d;
-    const int rc = check_shape_varlen(shape, true, &d, true);
+    hgrn2_shape alt[kAlternatives];
+    alternatives(shape, alt);
+    const int rc = check_shape_varlen(&alt[0], true, &d, true);
     if (rc != HGRN2_OK) return rc;
-    const size_t need = packed_saved_bytes(shape, d);
+    const size_t need = hgrn2_saved_states_varlen_bytes(shape);
     if (need > 0 && (!saved_states || saved_states_bytes < need || ((uintptr_t)saved_states & 255))) return HGRN2_ERR_WORKSPACE;
     return bwd_varlen_impl(shape, cu_seqlens, q, f, beta, v, h0, grad_o, grad_hT, grad_q, grad_f, grad_beta, grad_v, grad_h0,
-                           workspace, workspace_bytes, hip_stream, state_ws_bytes(d) > 0 ? saved_states : nullptr);
+                           workspace, workspace_bytes, hip_stream, saved_states);
 }
 
 int hgrn2_min_gate_product(const hgrn2_shape* shape, const void* f, const float* beta, float* min_product,

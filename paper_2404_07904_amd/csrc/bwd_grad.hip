@@ -1145,9 +1145,9 @@ hipError_t reduce_beta_partials(const SeqDims& d, float* beta_partials, float* g
     float* slice_sums = beta_partials + d.total_chunks() * kBwdWaves * d.dk;
     hipLaunchKernelGGL(reduce_beta_kernel, dim3(d.H * (d.dk / 64), kRedSlices), dim3(64 * kRedGroups), 0, stream,
                        beta_partials, slice_sums, B, d.H, d.NC, runs > 0 ? runs : d.NC, d.dk, d.lay.vl,
-                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path, d.lay.sub);
+                       d.packed ? d.lay.alt : d.lay.choice, d.packed ? d.lay.alt_path : d.lay.path, d.lay.sub);
     hipLaunchKernelGGL(reduce_beta_slices_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, slice_sums, grad_beta, n,
-                       d.packed ? static_cast<const int*>(nullptr) : d.lay.choice, d.lay.path);
+                       d.packed ? d.lay.alt : d.lay.choice, d.packed ? d.lay.alt_path : d.lay.path);
     return hipGetLastError();
 }
 

@@ -52,7 +52,7 @@ __device__ __forceinline__ int table_read(const int* table, int i)
 // one (TokenLayout::choice, ::path): the workgroups of the others return at once.
 __device__ __forceinline__ bool not_chosen(const TokenLayout& lay)
 {
-    return lay.choice && table_read(lay.choice, 0) != lay.path;
+    return (lay.choice && table_read(lay.choice, 0) != lay.path) || (lay.alt && table_read(lay.alt, 0) != lay.alt_path);
 }
 
 // ---- which tokens a sequence (b, h) owns --------------------------------------------------------

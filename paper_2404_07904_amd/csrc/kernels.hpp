@@ -41,6 +41,9 @@ struct TokenLayout {
     // enqueued one after the other and those not called for return at once.
     const int* choice = nullptr;
     int path = -1;
+    // A second such pair, for packed batches (whose first one is taken by the choice of backward pass).
+    const int* alt = nullptr;
+    int alt_path = 0;
     // The fused reverse walk of a packed batch cuts the chunks of a head -- sequence after sequence,
     // `total` of them -- into `spans` equal pieces, span s = chunks [s total / spans, (s + 1) total /
     // spans), a workgroup each; a span may start and end inside a sequence.  0: no such walk.
@@ -151,7 +154,7 @@ hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* car
 // first_run[b] .. first_run[b + 1] - 1, whose states sit at [run * H + h].
 hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, int dv, const float* carried_in,
                                    float* run_state, const float* run_decay, float* carried_out, bool reverse,
-                                   hipStream_t stream);
+                                   hipStream_t stream, const int* choice = nullptr, int path = 0);
 
 // Per-chunk forward read-out  O = tril(Q~ K~^T) V + (Q G) S_n.
 hipError_t launch_fwd_out(const SeqDims& d, const void* q, const void* f, const void* v, const void* ws_state,
@@ -238,21 +241,23 @@ size_t varlen_table_bytes(int B);
 // Run table of a packed batch (see varlen.hip): R entries and, behind them, first_run[B + 1].
 size_t varlen_run_table_bytes(int B, int R);
 // (sub: tokens per chunk, TokenLayout::sub)
+// (choice, path: the kernel returns at once when *choice != path)
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
-                                   int* first_run, hipStream_t stream, int sub = kChunk);
+                                   int* first_run, hipStream_t stream, int sub = kChunk, const int* choice = nullptr, int path = 0);
 // Groups of a table's sequences (sequence or run table with n_entries entries): G + 1 ints, group g
 // = entries [groups[g], groups[g + 1]), cut where the chunk count reaches g / G of the total, so that
 // groups hold about equally many chunks (a group is never finer than one entry); and one more int,
 // the choice of backward pass (TokenLayout::path): the reverse walk over groups takes as long as its
 // largest group, the per-chunk pass as long as all chunks shared among the compute units.
 size_t varlen_groups_bytes(int G);
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream);
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream,
+                                const int* choice = nullptr, int path = 0);
 // dst[0 .. n) = 0, as a kernel (safe under graph capture)
 hipError_t launch_zero_floats(float* dst, size_t n, hipStream_t stream);
 // *out = src[0] + ... + src[n - 1], on the device
 hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream);
 // (groups != null: the group array over the table's G groups, launch_varlen_groups(), in the same launch)
 hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G = 0,
-                               int* groups = nullptr, int sub = kChunk);
+                               int* groups = nullptr, int sub = kChunk, const int* choice = nullptr, int path = 0);
 
 }   // namespace hgrn2

@@ -520,12 +520,12 @@ hipError_t launch_run_carry(int n_seq, int seg, int dk, int dv, const float* car
 
 hipError_t launch_run_carry_packed(int B, int H, const int* first_run, int dk, int dv, const float* carried_in,
                                    float* run_state, const float* run_decay, float* carried_out, bool reverse,
-                                   hipStream_t stream)
+                                   hipStream_t stream, const int* choice, int path)
 {
     if (B * H == 0) return hipSuccess;
     const unsigned blocks = (unsigned)(((size_t)dk * dv / 4 + 255) / 256);
     hipLaunchKernelGGL(run_carry_kernel, dim3(blocks, B * H), dim3(256), 0, stream, carried_in, run_state, run_decay,
-                       carried_out, 0, first_run, H, dk, dv, reverse ? 1 : 0, static_cast<const int*>(nullptr), 0);
+                       carried_out, 0, first_run, H, dk, dv, reverse ? 1 : 0, choice, path);
     return hipGetLastError();
 }
 

@@ -76,8 +76,10 @@ __device__ __forceinline__ void build_groups(const int* tab, int n_entries, int 
     }
 }
 
-__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups)
+__global__ __launch_bounds__(kTabThreads) void varlen_groups_kernel(const int* tab, int n_entries, int G, int* groups,
+                                                                    const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
     build_groups(tab, n_entries, G, groups);
 }
 
@@ -104,8 +106,10 @@ __device__ __forceinline__ int block_prefix(int v, int* wave_tot)
 }
 
 // With `groups` (null: none) the group array of the table is built in the same launch.
-__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab, int G, int* groups, int sub)
+__global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu, int B, int T, int* tab, int G, int* groups, int sub,
+                                                                   const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
     __shared__ int wave_tot[kTabThreads / 64];
     const int n = B + 1, tid = threadIdx.x;
     const int per = (n + kTabThreads - 1) / kTabThreads;
@@ -174,8 +178,10 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
 // (B + 1 entries).  Runs are whole chunks, so the chunk counts of the run table add up as those of
 // the sequence table do.  The runs keep their order (no sorting by length: none is long).
 __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int* seq_tab, int B, int T, int run_chunks,
-                                                                       int R, int* run_tab, int* first_run, int sub)
+                                                                       int R, int* run_tab, int* first_run, int sub,
+                                                                       const int* choice, int path)
 {
+    if (choice && table_read(choice, 0) != path) return;
     __shared__ int part[kTabThreads];
     const int n = B + 1, tid = threadIdx.x;
     const int per = (n + kTabThreads - 1) / kTabThreads;
@@ -247,27 +253,28 @@ hipError_t launch_sum_ints(const int* src, int n, int* out, hipStream_t stream)
 
 size_t varlen_table_bytes(int B) { return 4 * ((size_t)B + 1) * sizeof(int); }
 
-hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups, int sub)
+hipError_t launch_varlen_table(const int* cu_seqlens, int B, int T, int* table, hipStream_t stream, int G, int* groups, int sub,
+                               const int* choice, int path)
 {
-    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table, G, groups, sub);
+    hipLaunchKernelGGL(varlen_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, cu_seqlens, B, T, table, G, groups, sub, choice, path);
     return hipGetLastError();
 }
 
 size_t varlen_groups_bytes(int G) { return (2 * (size_t)G + 2) * sizeof(int); }
 
-hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream)
+hipError_t launch_varlen_groups(const int* table, int n_entries, int G, int* groups, hipStream_t stream, const int* choice, int path)
 {
-    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, groups);
+    hipLaunchKernelGGL(varlen_groups_kernel, dim3(1), dim3(kTabThreads), 0, stream, table, n_entries, G, groups, choice, path);
     return hipGetLastError();
 }
 
 size_t varlen_run_table_bytes(int B, int R) { return varlen_table_bytes(R) + ((size_t)B + 1) * sizeof(int); }
 
 hipError_t launch_varlen_run_table(const int* seq_table, int B, int T, int run_chunks, int R, int* run_table,
-                                   int* first_run, hipStream_t stream, int sub)
+                                   int* first_run, hipStream_t stream, int sub, const int* choice, int path)
 {
     hipLaunchKernelGGL(varlen_run_table_kernel, dim3(1), dim3(kTabThreads), 0, stream, seq_table, B, T, run_chunks, R,
-                       run_table, first_run, sub);
+                       run_table, first_run, sub, choice, path);
     return hipGetLastError();
 }
 

@@ -116,11 +116,17 @@ def test_chunk_length_chosen_on_the_device_sizes_and_support():
     assert binding.hgrn2_fwd_workspace_bytes(bad) == 0
     assert lib.hgrn2_fwd(ctypes.byref(bad), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_UNSUP
     assert lib.hgrn2_fwd(ctypes.byref(shape(chunk=-2)), FAKE, FAKE, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_SHAPE
-    # not offered: the stage calls, packed batches
+    # not offered: the stage calls
     assert lib.hgrn2_state_sweep(ap, 0, None, FAKE, FAKE, None, None, FAKE_WS, big, None) == E_SHAPE
-    sv = shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=AUTO)
-    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == 0
-    assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_SHAPE
+    # packed batches: the workspace of the alternative with most chunks plus the flags; every alternative keeps its
+    # states and tables in a place of its own
+    sv, sv64, sv32, sv16 = (shape(B=2, H=3, N=200, dk=64, dv=128, layout=1, chunk=c) for c in (AUTO, 0, 32, 16))
+    assert binding.hgrn2_fwd_varlen_workspace_bytes(sv) == 256 + binding.hgrn2_fwd_varlen_workspace_bytes(sv16)
+    assert binding.hgrn2_bwd_varlen_workspace_bytes(sv) == 256 + binding.hgrn2_bwd_varlen_workspace_bytes(sv16)
+    assert binding.hgrn2_saved_states_varlen_bytes(sv) == 256 + sum(binding.hgrn2_saved_states_varlen_bytes(x) for x in (sv64, sv32, sv16))
+    assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, FAKE, FAKE, None, FAKE, None, FAKE, None, FAKE_WS,
+                                binding.hgrn2_fwd_varlen_workspace_bytes(sv16), None) == E_WS
+    assert lib.hgrn2_fwd_varlen(ctypes.byref(sv), FAKE, None, FAKE, None, FAKE, None, FAKE, None, FAKE_WS, big, None) == E_NULL
 
 
 def call_fwd(s, q=FAKE, f=FAKE, v=FAKE, h0=None, o=FAKE, hT=None, ws=FAKE_WS, ws_bytes=1 << 40):

@@ -328,6 +328,52 @@ def test_small_gates_in_a_packed_batch(lens, H, dk, dv, gated, chunk, pair):
         check("dbeta", host(res[4]), rb, tol)
 
 
+@pytest.mark.parametrize("kind,lens,H,dk,dv,pair", [
+    ("ordinary", [150, 0, 37, 260], 2, 64, 64, False),
+    ("loguniform32", [200, 1, 333], 2, 128, 128, True),
+    ("loguniform", [90, 300, 45], 3, 128, 64, True),
+    ("loguniform32", [70, 45, 0, 33, 90, 17, 64, 1, 80, 5, 120, 31, 66, 48, 12, 100] * 3, 16, 128, 128, True),   # groups of sequences
+    ("loguniform", [1300, 900], 2, 128, 128, False),      # documents walked in runs
+])
+def test_chunk_length_chosen_on_the_device_in_a_packed_batch(kind, lens, H, dk, dv, pair):
+    """chunk = HGRN2_CHUNK_AUTO for packed batches: the three passes build their own tables and those not called
+    for return at once, table kernels included.  The results must be those of the chunk length the probe
+    names, bit for bit, stateless or as the training pair (whose kept states lie in a place per alternative)."""
+    AUTO = -1
+    B, T = len(lens), int(sum(lens))
+    print("\n[chunk chosen on the device, packed] %s H=%d dk=%d dv=%d pair=%s lens=%s" % (kind, H, dk, dv, pair, lens), flush=True)
+    rng = np.random.default_rng(8300 + T)
+    cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+    if kind == "ordinary":
+        w = synth.make_sequence(8300 + B, 1, H, T, dk, dv, io_dtype="bf16", lb=0.0, with_dO=True)
+    else:
+        w = small_gate_workload(8300 + B, 1, H, T, dk, dv, kind)
+    pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
+    q, f, v, dO = pk(w.q), pk(w.f), pk(w.v), pk(w.dO)
+    h0 = dev((0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32))
+    dhT = dev((0.1 * rng.standard_normal((B, H, dk, dv))).astype(np.float32))
+    need = [c for c in (0, 32, 16) if float(binding.hgrn2_min_gate_product_varlen(f, cu, chunk=c).item()) > LIMIT][0]
+    print("    the probe says: chunk = %d" % need, flush=True)
+    assert need == {"ordinary": 0, "loguniform32": 32, "loguniform": 16}[kind]
+
+    def run(chunk, flag):
+        saved = None
+        if pair:
+            saved = torch.empty(max(binding.hgrn2_saved_states_varlen_bytes(binding.make_shape_varlen(q, v, f, B, chunk)), 256),
+                                dtype=torch.uint8, device="cuda")
+        o, hT = binding.hgrn2_fwd_varlen(q, f, v, cu, h0, chunk=chunk, saved_states=saved, domain_flag=flag)
+        return (o, hT) + tuple(binding.hgrn2_bwd_varlen(q, f, v, dO, cu, h0, dhT, want_grad_h0=True, chunk=chunk,
+                                                        saved_states=saved, domain_flag=flag))
+
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    got = run(AUTO, flag)
+    want = run(need, None)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    for name, x, y in zip(("o", "hT", "dq", "df", "dv", "dh0"), got, want):
+        assert torch.equal(x, y), "%s differs from the call with chunk = %d" % (name, need)
+
+
 @pytest.mark.parametrize("dk,dv,B,H", [(64, 64, 2, 3), (128, 128, 8, 8), (128, 64, 1, 2)])
 def test_gate_domain_flag(dk, dv, B, H):
     """shape->gate_domain_flag: set by the forward and by the backward kernels exactly when a product of
