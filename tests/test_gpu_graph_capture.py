@@ -169,17 +169,21 @@ def test_two_streams_with_their_own_workspaces():
                 assert torch.equal(x, y)
 
 
-@pytest.mark.parametrize("H,d,n_docs", [(16, 128, 24), (4, 64, 5)])
-def test_captured_packed_training_pair_replays(H, d, n_docs):
+@pytest.mark.parametrize("H,d,n_docs,chunk", [(16, 128, 24, 0), (4, 64, 5, 0), (4, 128, 7, -1)])
+def test_captured_packed_training_pair_replays(H, d, n_docs, chunk):
     """The packed entry points read cu_seqlens on the device only (their tables are built by a
     kernel of the call), so a captured step serves batches cut differently: every replay gets new
-    tokens AND new document boundaries (same token count, same number of documents)."""
+    tokens AND new document boundaries (same token count, same number of documents).  With the chunk length
+    chosen on the device (chunk = -1) every other replay also gets gates outside the domain of 64-token
+    chunks, so that the replays take different chunk lengths."""
     T = 3000
-    print("\n[graph] packed pair T=%d H=%d d=%d, %d documents" % (T, H, d, n_docs), flush=True)
+    print("\n[graph] packed pair T=%d H=%d d=%d, %d documents, chunk=%d" % (T, H, d, n_docs, chunk), flush=True)
     rng = np.random.default_rng(8700 + H)
 
     def fresh_packed(seed):
         w = synth.make_sequence(seed, 1, H, T, d, d, io_dtype="bf16", lb=0.3, with_dO=True)
+        if chunk == -1 and seed % 2 == 1:          # log-uniform gates in [0.02, 1]: 32 tokens per chunk
+            w.f = synth.bf16_round((10.0 ** rng.uniform(np.log10(0.02), 0.0, size=w.f.shape)).astype(np.float32))
         pk = lambda x: dev(x, "bf16")[0].permute(1, 0, 2).contiguous()
         cuts = np.sort(rng.integers(0, T + 1, size=n_docs - 1))
         cu = torch.from_numpy(np.concatenate([[0], cuts, [T]]).astype(np.int32)).cuda()
@@ -187,16 +191,16 @@ def test_captured_packed_training_pair_replays(H, d, n_docs):
 
     static = fresh_packed(8700)
     q, f, v, dO, cu = static
-    shape = binding.make_shape_varlen(q, v, f, n_docs)
+    shape = binding.make_shape_varlen(q, v, f, n_docs, chunk)
     ws = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
     kept = torch.empty(binding.hgrn2_saved_states_varlen_bytes(shape), dtype=torch.uint8, device="cuda")
     o, hT = torch.empty_like(v), torch.empty((n_docs, H, d, d), device="cuda")
     gq, gf, gv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(v)
 
     def step():
-        binding.hgrn2_fwd_varlen(q, f, v, cu, None, o=o, hT=hT, workspace=ws, saved_states=kept)
+        binding.hgrn2_fwd_varlen(q, f, v, cu, None, o=o, hT=hT, workspace=ws, saved_states=kept, chunk=chunk)
         binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=ws, grad_q=gq, grad_f=gf, grad_v=gv,
-                                 saved_states=kept)
+                                 saved_states=kept, chunk=chunk)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
