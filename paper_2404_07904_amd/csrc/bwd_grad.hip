@@ -260,7 +260,7 @@ __device__ __forceinline__ void bwd_grad_body(const BwdGradParams& p)
         if (c.n > 0) { ChunkAt r = c; r.n = c.n - 1; return r; }
         for (int e = c.bh / p.lay.H - 1; e >= 0; --e) {
             const int len = table_read(p.lay.vl, p.lay.B + 1 + e);
-            if (len > 0) return chunk_en(e, (len + p.lay.sub - 1) / p.lay.sub - 1);
+            if (len > 0) return chunk_en(e, p.lay.chunks_of(len) - 1);
         }
         return c;
     };
@@ -1108,7 +1108,7 @@ __global__ __launch_bounds__(64 * kRedGroups) void reduce_beta_kernel(const floa
         size_t first = (size_t)(b * H + h) * NC;
         int nc = used;
         if (vl) {
-            nc = (vl[B + 1 + b] + sub - 1) / sub;
+            nc = (vl[B + 1 + b] + sub - 1) >> (31 - __builtin_clz((unsigned)sub));
             first = (size_t)vl[2 * (B + 1) + b] * H + (size_t)h * nc;
         }
         const int rows = nc * kBwdWaves;

@@ -92,7 +92,7 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
     if (RUNS && lay.seg > 1) {
         // run r of sequence bh / seg: N tokens (NC chunks) unless it is the last, shorter one
         const int whole = bh / lay.seg, r = bh - whole * lay.seg;
-        const int nc_all = (lay.n_tokens + lay.sub - 1) / lay.sub;
+        const int nc_all = lay.chunks_of(lay.n_tokens);
         s.N = min(N, lay.n_tokens - r * N);
         s.NC = min(NC, nc_all - r * NC);
         s.chunk0 = (size_t)whole * nc_all + (size_t)r * NC;
@@ -114,7 +114,7 @@ __device__ __forceinline__ SeqView seq_view(const TokenLayout& lay, int N, int N
             const int b = bh / lay.H, h = bh - b * lay.H;
             const int start = table_read(lay.vl, b);
             s.N = table_read(lay.vl, lay.B + 1 + b);
-            s.NC = (s.N + lay.sub - 1) / lay.sub;
+            s.NC = lay.chunks_of(s.N);
             s.off_k = (size_t)start * lay.sn_k + (size_t)h * lay.sh_k;
             s.off_v = (size_t)start * lay.sn_v + (size_t)h * lay.sh_v;
             s.chunk0 = (size_t)table_read(lay.vl, 2 * (lay.B + 1) + b) * lay.H + (size_t)h * s.NC;
@@ -168,7 +168,7 @@ __device__ __forceinline__ bool locate_chunk(const TokenLayout& lay, int BH, int
                     if (cb[mid] * lay.H <= chunk) lo = mid; else hi = mid;
                 }
             }
-            const int nc = (lay.vl[lay.B + 1 + lo] + lay.sub - 1) / lay.sub;    // > 0: the range is not empty
+            const int nc = lay.chunks_of(lay.vl[lay.B + 1 + lo]);               // > 0: the range is not empty
             const int rem = chunk - cb[lo] * lay.H;
             const int h = rem / nc;
             bh = lo * lay.H + h;

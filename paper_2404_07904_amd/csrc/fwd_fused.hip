@@ -204,7 +204,7 @@ __device__ __forceinline__ void fwd_fused_body(const FwdFusedParams& p)
             int e = cur_e + 1, len = 0;
             while (e < e1 && (len = table_read(t_len, e)) == 0) ++e;
             if (e < e1) {
-                cur_e = e; cur_N = len; cur_nc = (len + p.lay.sub - 1) / p.lay.sub; cur_tok = table_read(t_start, e);
+                cur_e = e; cur_N = len; cur_nc = p.lay.chunks_of(len); cur_tok = table_read(t_start, e);
                 // the chunks of (sequence, head) lie together, the heads of a sequence one after the other
                 cur_slot = table_read(p.lay.vl, 2 * (p.lay.B + 1) + e) * p.lay.H + head * cur_nc;
             } else { cur_e = e1; cur_N = 0; cur_nc = 0; cur_tok = 0; cur_slot = 0; }          // past the end, for good

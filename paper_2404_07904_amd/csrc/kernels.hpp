@@ -60,6 +60,8 @@ struct TokenLayout {
     // Tokens per chunk: kChunk, or fewer in the small-gate modes, where a chunk's other rows stand for
     // no token (ChunkRows in common.hpp).  NC and the chunk counts of the tables count chunks of `sub` tokens.
     int sub = kChunk;
+    // (a power of two: the chunks of `len` tokens are counted with a shift, not a division)
+    __host__ __device__ int chunks_of(int len) const { return (len + sub - 1) >> (31 - __builtin_clz((unsigned)sub)); }
     __host__ __device__ size_t off_k(int bh) const { return (size_t)(bh / H) * sb_k + (size_t)(bh % H) * sh_k; }
     __host__ __device__ size_t off_v(int bh) const { return (size_t)(bh / H) * sb_v + (size_t)(bh % H) * sh_v; }
 };

@@ -110,6 +110,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
                                                                    const int* choice, int path)
 {
     if (choice && table_read(choice, 0) != path) return;        // one of several alternatives, and not the one called for
+    const int shift = 31 - __builtin_clz((unsigned)sub);         // sub is a power of two
     __shared__ int wave_tot[kTabThreads / 64];
     const int n = B + 1, tid = threadIdx.x;
     const int per = (n + kTabThreads - 1) / kTabThreads;
@@ -128,12 +129,12 @@ __global__ __launch_bounds__(kTabThreads) void varlen_table_kernel(const int* cu
     for (int i = lo; i < hi; ++i) {
         const int len = i < B ? tab[i + 1] - tab[i] : 0;
         tab[n + i] = len;
-        c += (len + sub - 1) / sub;
+        c += (len + sub - 1) >> shift;
     }
     run = block_prefix<false>(c, wave_tot);
     for (int i = lo; i < hi; ++i) {
         tab[2 * n + i] = run;
-        run += (tab[n + i] + sub - 1) / sub;
+        run += (tab[n + i] + sub - 1) >> shift;
     }
     __syncthreads();                                              // all lengths are visible
 
@@ -182,6 +183,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int
                                                                        const int* choice, int path)
 {
     if (choice && table_read(choice, 0) != path) return;
+    const int shift = 31 - __builtin_clz((unsigned)sub);         // sub is a power of two
     __shared__ int part[kTabThreads];
     const int n = B + 1, tid = threadIdx.x;
     const int per = (n + kTabThreads - 1) / kTabThreads;
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kTabThreads) void varlen_run_table_kernel(const int
     const int* len = seq_tab + n;
     const int* before = seq_tab + 2 * n;
     auto runs_of = [&](int b) {
-        const int nc = b < B ? (len[b] + sub - 1) / sub : 0;
+        const int nc = b < B ? (len[b] + sub - 1) >> shift : 0;
         return (nc + run_chunks - 1) / run_chunks;
     };
     int c = 0;
