@@ -654,20 +654,20 @@ def main():
         pack = lambda t: t.permute(0, 2, 1, 3).reshape(T, H, D).contiguous()          # [B][H][N][d] -> [B N][H][d]
         vsets = [tuple(pack(t) for t in st_) for st_ in sets]
 
-        def run_varlen(cu_list, pair=False):
+        def run_varlen(cu_list, pair=False, chunk=0):
             # pair: the forward pass keeps the chunk states for the backward pass (hgrn2_fwd_varlen_saving /
             # hgrn2_bwd_varlen_saved) instead of the backward pass recomputing them
             cu = torch.tensor(cu_list, dtype=torch.int32, device=dev)
-            shp = binding.make_shape_varlen(vsets[0][0], vsets[0][2], vsets[0][1], len(cu_list) - 1)
+            shp = binding.make_shape_varlen(vsets[0][0], vsets[0][2], vsets[0][1], len(cu_list) - 1, chunk)
             wsv = torch.empty(binding.hgrn2_bwd_varlen_workspace_bytes(shp), dtype=torch.uint8, device=dev)
             kept = torch.empty(binding.hgrn2_saved_states_varlen_bytes(shp), dtype=torch.uint8, device=dev) if pair else None
             ov, gqv, gfv, gvv = (torch.empty_like(vsets[0][0]) for _ in range(4))
 
             def fn(i):
                 q, f, v, dO = vsets[i % 2]
-                binding.hgrn2_fwd_varlen(q, f, v, cu, None, want_hT=False, o=ov, workspace=wsv, saved_states=kept)
+                binding.hgrn2_fwd_varlen(q, f, v, cu, None, want_hT=False, o=ov, workspace=wsv, saved_states=kept, chunk=chunk)
                 binding.hgrn2_bwd_varlen(q, f, v, dO, cu, None, None, workspace=wsv, grad_q=gqv, grad_f=gfv, grad_v=gvv,
-                                         saved_states=kept)
+                                         saved_states=kept, chunk=chunk)
             for i in range(6):
                 fn(i)
             return timed(fn, reps=30)
@@ -678,6 +678,9 @@ def main():
         t_short = {L: run_varlen(list(range(0, T + 1, L))) for L in (1024, 256, 64)}
         t_pair = {"document_mix": run_varlen(cu_mix, True), "8_equal_sequences": run_varlen([N * b for b in range(B + 1)], True)}
         t_pair.update({str(L): run_varlen(list(range(0, T + 1, L)), True) for L in (1024, 256, 64)})
+        # the document mix as a training pair with 32 tokens per chunk, and with the chunk length chosen on the device
+        t_pair["document_mix_chunk_32"] = run_varlen(cu_mix, True, 32)
+        t_pair["document_mix_chunk_chosen_on_device"] = run_varlen(cu_mix, True, -1)
 
         def fixed_bnhd(i):          # the same packing seen as an equal-length [B][N][H][d] batch
             q, f, v, dO = (t.view(B, N, H, D) for t in vsets[i % 2])
