@@ -94,7 +94,8 @@ typedef enum { HGRN2_LAYOUT_BHND = 0, HGRN2_LAYOUT_BNHD = 1 } hgrn2_layout;
 
 typedef struct {
     int32_t B, H, N, dk, dv;
-    int32_t chunk;      /* chunk length of the chunkwise algorithm; 0 selects the default (64) */
+    int32_t chunk;      /* tokens per chunk of the chunkwise algorithm: 0 selects the default (64); 32, 16, 8 and
+                           HGRN2_CHUNK_AUTO where stated (see "Gate domain" above) */
     int32_t io_dtype;   /* hgrn2_dtype of q, v, o and of every grad_* sequence tensor */
     int32_t gate_dtype; /* hgrn2_dtype of f (grad_f follows io_dtype) */
     int32_t layout;     /* hgrn2_layout of every sequence tensor (q, f, v, o, grad_*); 0 = [B][H][N][d] */
