@@ -288,6 +288,8 @@ template <typename F> size_t max_over_alternatives(const hgrn2_shape* shape, F b
 struct Alternative {
     const int* choice = nullptr;
     int path = 0;
+    const int* choice2 = nullptr;         // a second condition of the same kind (equal-length batches)
+    int path2 = 0;
     int* flag = nullptr;
     bool validate_only = false;           // stop after the argument checks
 };
@@ -331,7 +333,7 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
 
 // Forward pass; `beta` null: `f` holds the gates; else `f` holds their pre-activations (Eq. 2).
 // With chunk = HGRN2_CHUNK_AUTO: its three alternatives.  `save_states` then ends in kAutoHead bytes
-// whose first int names the alternative that ran (0, 1, 2), for the backward pass of the pair.
+// that hold the two flags, for the backward pass of the pair.
 static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, const float* beta, bool gated,
                     const void* v, const float* h0, void* o, float* hT, void* workspace, size_t workspace_bytes,
                     void* hip_stream, void* save_states)
@@ -354,7 +356,9 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
         if (rc != HGRN2_OK) return rc;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    int* flags = static_cast<int*>(workspace);
+    // (a training pair keeps the two flags behind the states: the backward pass reads them there)
+    int* flags = save_states ? reinterpret_cast<int*>(static_cast<char*>(save_states) + hgrn2_saved_states_bytes(shape) - kAutoHead)
+                             : static_cast<int*>(workspace);
     if (launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
     a.validate_only = false;
     for (int i = 0; i < kAlternatives; ++i) {
@@ -363,10 +367,6 @@ static int fwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
         a.flag = i + 1 < kAlternatives ? flags + i : shape->gate_domain_flag;
         const int rc = fwd_one(&alt[i], q, f, beta, gated, v, h0, o, hT, rest, workspace_bytes - kAutoHead, hip_stream, save_states, &a);
         if (rc != HGRN2_OK) return rc;
-    }
-    if (save_states) {
-        int* which = reinterpret_cast<int*>(static_cast<char*>(save_states) + hgrn2_saved_states_bytes(shape) - kAutoHead);
-        if (launch_sum_ints(flags, 2, which, stream) != hipSuccess) return HGRN2_ERR_HIP;
     }
     return HGRN2_OK;
 }
@@ -382,7 +382,7 @@ static int fwd_one(const hgrn2_shape* shape, const void* q, const void* f, const
     if (has_tokens && (!q || !f || !v || !o)) return HGRN2_ERR_NULL;
     if (gated && has_tokens && !beta) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
-    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.domain_flag = alt->flag; }
+    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.lay.alt = alt->choice2; d.lay.alt_path = alt->path2; d.domain_flag = alt->flag; }
     const size_t one = round256(state_ws_bytes(d));
     const size_t need = one + run_state_bytes(d, false) + run_decay_bytes(d, false);
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
@@ -474,14 +474,18 @@ static int bwd_impl(const hgrn2_shape* shape, const void* q, const void* f, cons
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     int* flags = static_cast<int*>(workspace);
-    const int* which = saved_states ? reinterpret_cast<const int*>(static_cast<const char*>(saved_states) +
-                                                                   hgrn2_saved_states_bytes(shape) - kAutoHead)
-                                    : nullptr;
+    // the flags the forward pass of the pair left behind the states: 64 tokens per chunk ran alone if the
+    // first is clear, 16 if the second is set, 32 otherwise
+    const int* kept = saved_states ? reinterpret_cast<const int*>(static_cast<const char*>(saved_states) +
+                                                                  hgrn2_saved_states_bytes(shape) - kAutoHead)
+                                   : nullptr;
     if (!saved_states && launch_zero_floats(reinterpret_cast<float*>(flags), 4, stream) != hipSuccess) return HGRN2_ERR_HIP;
     a.validate_only = false;
     for (int i = 0; i < kAlternatives; ++i) {
+        a.choice2 = nullptr; a.path2 = 0;
         if (saved_states) {
-            a.choice = which; a.path = i;
+            a.choice = i == 2 ? kept + 1 : kept; a.path = i == 0 ? 0 : 1;
+            if (i == 1) a.choice2 = kept + 1;
             a.flag = i + 1 < kAlternatives ? nullptr : shape->gate_domain_flag;
         } else {
             a.choice = i == 0 ? nullptr : flags + (i - 1); a.path = 1;
@@ -506,7 +510,7 @@ static int bwd_one(const hgrn2_shape* shape, const void* q, const void* f, const
     if (has_tokens && (!q || !f || !v || !grad_o || !grad_q || !grad_f || !grad_v)) return HGRN2_ERR_NULL;
     if (gated && (size_t)shape->H * d.dk > 0 && (!grad_beta || (has_tokens && !beta))) return HGRN2_ERR_NULL;
     d.beta = gated ? beta : nullptr;
-    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.domain_flag = alt->flag; }
+    if (alt) { d.lay.choice = alt->choice; d.lay.path = alt->path; d.lay.alt = alt->choice2; d.lay.alt_path = alt->path2; d.domain_flag = alt->flag; }
     const BwdLayout l = bwd_layout(d, gated, saved_states != nullptr);
     const size_t need = l.total();
     if (need > 0 && (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255))) return HGRN2_ERR_WORKSPACE;
