@@ -980,9 +980,12 @@ BwdFusedPlan plan_bwd_fused(const SeqDims& d)
     if (R < 1) R = 1;
     if (R >= 2 && R <= kMaxLightRuns) {
         // Few runs: each workgroup walks the chunks after its run itself, at `rho` of a chunk's full
-        // cost (measured), and the cuts are placed so that all runs take the same time T:
+        // cost, and the cuts are placed so that all runs take the same time T:
         // len_r = T - rho (NC - end_r), from the last run (len = T) backwards; T by bisection.
-        const double rho = 0.16;
+        // rho is set by the balance that measures best (128 sequences of 32 chunks in two runs: 14 + 18
+        // chunks 180 us, 15 + 17 185 us, 13 + 19 187 us; a light chunk alone costs 0.16 of a full one,
+        // but the light walks run while the memory system is busiest).
+        const double rho = 0.24;
         double lo = 0.0, hi = (double)d.NC;
         for (int iter = 0; iter < 50; ++iter) {
             const double T = 0.5 * (lo + hi);
